@@ -1,0 +1,193 @@
+/*
+ * vt_oracle.c -- plain CPU oracle (test infrastructure only; see vt_oracle.h).
+ *
+ * Build: gcc -O2 -ffp-contract=off -fno-fast-math -shared -fPIC vt_oracle.c -lm
+ * Every floating-point step below is exact or a single IEEE operation; nothing here is
+ * blocked, fused or reordered beyond what the paper's algorithms state.
+ */
+#include "vt_oracle.h"
+
+#include <math.h>
+#include <string.h>
+
+static uint64_t f64_bits(double x) { uint64_t b; memcpy(&b, &x, 8); return b; }
+static uint32_t f32_bits(float x)  { uint32_t b; memcpy(&b, &x, 4); return b; }
+static float    f32_from(uint32_t b) { float x; memcpy(&x, &b, 4); return x; }
+
+#define TWO28 268435456.0 /* 2^28 */
+
+/* Method, primitive 1 with b_r = 32: "round to the nearest FP32".  The C conversion from
+ * double to float under the default rounding mode IS the IEEE convertFormat operation with
+ * roundTiesToEven, so the definition is the cast itself. */
+static float rnd32(double x) { return (float)x; }
+
+uint32_t vto_rnd32_bits(double x)
+{
+    if (isnan(x)) return 0x7FC00000u;
+    return f32_bits(rnd32(x));
+}
+
+uint32_t vto_thr_from_tau(double tau_ulp)
+{
+    if (!(tau_ulp >= 0.0 && tau_ulp <= 0.5)) return 0xFFFFFFFFu;
+    return (uint32_t)ceil(ldexp(tau_ulp, 29)); /* power-of-two scaling is exact */
+}
+
+/* Algorithm "log", steps 1-2: exp = exponent scale of x, then |x - rnd(x)| relative to it.
+ * Returned in units of 2^-29 ulp32(x), where every quantity involved is exact in binary64:
+ *  - FP32-normal and larger magnitudes: the test does not depend on the binade, so x is
+ *    scaled by a power of two into [1,2), where ulp32 = 2^-23 and the unit is 2^-52.
+ *  - magnitudes below 2^-126: FP32 spacing is fixed at 2^-149, unit 2^-178. */
+double vto_scaled_round_error(double x)
+{
+    if (isnan(x) || isinf(x)) return -1.0;
+    if (x == 0.0) return 0.0;
+    int E = ilogb(x);
+    if (E >= -126) {
+        double xs = scalbn(x, -E);                 /* exact, |xs| in [1,2) */
+        double d  = fabs(xs - (double)rnd32(xs));  /* exact: both are multiples of 2^-52 */
+        return ldexp(d, 52);
+    } else {
+        double d = fabs(x - (double)rnd32(x));     /* exact: |d| <= 2^-150 on x's own grid */
+        return ldexp(d, 178);
+    }
+}
+
+uint32_t vto_boundary_distance(double x)
+{
+    double q = vto_scaled_round_error(x);
+    if (q < 0.0) return 1u << 28;
+    return (uint32_t)(TWO28 - ceil(q)); /* floor(2^28 - q) without rounding the subtraction */
+}
+
+/* Algorithm "log": three-way decision.  exp*tau of the paper equals
+ * (0.5 - thr 2^-29) ulp32(x); in the scaled unit that is 2^28 - thr. */
+int vto_ternary_code(double x, uint32_t thr)
+{
+    double q = vto_scaled_round_error(x);
+    if (q < 0.0) return 1;                              /* NaN, +-Inf: ignore */
+    double y = (double)rnd32(x);                        /* may be +-Inf on overflow */
+    if (q > TWO28 - (double)thr && x < y) return 2;     /* far from rnd(x), rounded up */
+    if (q > TWO28 - (double)thr && x > y) return 0;     /* far from rnd(x), rounded down */
+    return 1;
+}
+
+int vto_round_log(const double *x, uint64_t n, double tau_ulp, float *y,
+                  uint32_t *idx, uint32_t *dir, uint64_t cap, uint64_t *count)
+{
+    uint32_t thr = vto_thr_from_tau(tau_ulp);
+    if (thr == 0xFFFFFFFFu || n >= (1ull << 32) || !count) return VTO_ERR_INVALID_ARG;
+    if (n && (!x || !y)) return VTO_ERR_INVALID_ARG;
+    if (cap && (!idx || !dir)) return VTO_ERR_INVALID_ARG;
+    for (uint64_t w = 0; w < (cap + 31) / 32; ++w) dir[w] = 0;
+    uint64_t c = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        int code = vto_ternary_code(x[i], thr);         /* log(output, ...) first ... */
+        y[i] = f32_from(vto_rnd32_bits(x[i]));          /* ... then output = rnd(output) */
+        if (code != 1) {
+            if (c < cap) {
+                idx[c] = (uint32_t)i;
+                if (code == 2) dir[c >> 5] |= 1u << (c & 31);
+            }
+            ++c;
+        }
+    }
+    *count = c;
+    return VTO_OK;
+}
+
+/* Primitive "rev" as the paper words it: round to nearest, then, if the trainer went the
+ * other way, take the neighbouring FP32 value on the trainer's side of x. */
+static float rev(double x, int code)
+{
+    if (isnan(x)) return f32_from(0x7FC00000u);
+    float y = rnd32(x);
+    if (code == 0 && x < (double)y) return nextafterf(y, -INFINITY); /* float below x */
+    if (code == 2 && x > (double)y) return nextafterf(y, INFINITY);  /* float above x */
+    return y;
+}
+
+int vto_round_replay(const double *x, uint64_t n, const uint32_t *idx, const uint32_t *dir,
+                     uint64_t count, float *y)
+{
+    if (n >= (1ull << 32)) return VTO_ERR_INVALID_ARG;
+    if (n && (!x || !y)) return VTO_ERR_INVALID_ARG;
+    if (count && (!idx || !dir)) return VTO_ERR_INVALID_ARG;
+    uint64_t p = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        int code = 1;                                    /* c = read(F) for element i */
+        while (p < count && idx[p] < i) ++p;             /* tolerate stray entries */
+        if (p < count && idx[p] == i) {
+            code = ((dir[p >> 5] >> (p & 31)) & 1u) ? 2 : 0;
+            ++p;
+        }
+        y[i] = rev(x[i], code);
+    }
+    return VTO_OK;
+}
+
+int vto_gemm_f64(int transA, int transB, int64_t M, int64_t N, int64_t K, double alpha,
+                 const double *A, int64_t lda, const double *B, int64_t ldb,
+                 const double *bias, double *C, int64_t ldc, int order)
+{
+    if (M < 0 || N < 0 || K < 0 || order < 0 || order > 2) return VTO_ERR_INVALID_ARG;
+    for (int64_t i = 0; i < M; ++i) {
+        for (int64_t j = 0; j < N; ++j) {
+            double c;
+            if (order == 2) {
+                long double acc = 0.0L;
+                for (int64_t k = 0; k < K; ++k) {
+                    double a = transA ? A[k * lda + i] : A[i * lda + k];
+                    double b = transB ? B[j * ldb + k] : B[k * ldb + j];
+                    acc += (long double)a * (long double)b;
+                }
+                long double r = (long double)alpha * acc;
+                if (bias) r += (long double)bias[j];
+                c = (double)r;
+            } else {
+                double acc = 0.0;
+                for (int64_t s = 0; s < K; ++s) {
+                    int64_t k = order == 0 ? s : K - 1 - s;
+                    double a = transA ? A[k * lda + i] : A[i * lda + k];
+                    double b = transB ? B[j * ldb + k] : B[k * ldb + j];
+                    double p = a * b;
+                    acc = acc + p;
+                }
+                c = alpha * acc;
+                if (bias) c = c + bias[j];
+            }
+            C[i * ldc + j] = c;
+        }
+    }
+    return VTO_OK;
+}
+
+/* Monotone integer image of a binary64 pattern: sign-magnitude -> two's complement. */
+static int64_t ord64(double y)
+{
+    uint64_t b = f64_bits(y);
+    uint64_t mag = b & 0x7FFFFFFFFFFFFFFFull;
+    return (b >> 63) ? -(int64_t)mag : (int64_t)mag;
+}
+
+int vto_threshold_stats(const double *y1, const double *y2, uint64_t n, uint64_t out[68])
+{
+    if (!out || (n && (!y1 || !y2))) return VTO_ERR_INVALID_ARG;
+    for (int b = 0; b < 68; ++b) out[b] = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        int64_t o1 = ord64(y1[i]), o2 = ord64(y2[i]);
+        uint64_t diff = o1 > o2 ? (uint64_t)o1 - (uint64_t)o2 : (uint64_t)o2 - (uint64_t)o1;
+        int bin = 0;
+        for (uint64_t d = diff; d; d >>= 1) ++bin;      /* 0, else 1 + floor(log2 diff) */
+        out[3 + bin] += 1;
+        if (diff > out[2]) out[2] = diff;
+        if (vto_rnd32_bits(y1[i]) != vto_rnd32_bits(y2[i])) {   /* rnd(y1) != rnd(y2) */
+            uint32_t d1 = vto_boundary_distance(y1[i]);
+            uint32_t d2 = vto_boundary_distance(y2[i]);
+            uint64_t need = 1 + (uint64_t)(d1 > d2 ? d1 : d2);
+            out[0] += 1;
+            if (need > out[1]) out[1] = need;
+        }
+    }
+    return VTO_OK;
+}

@@ -1,0 +1,89 @@
+/*
+ * vt_oracle.h -- plain CPU oracle for the verifiable-training round/log/replay path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This code is the slow, scalar, obviously-correct statement of
+ * what the method computes, written from the paper (Method section: primitives rnd, log,
+ * rev, threshold; Appendix algorithms "log", "audit", "threshold").  It shares no code with
+ * the HIP library and must never be called from the product path; only the tests, the smoke
+ * check and the bench's cpu_baseline leg use it.
+ *
+ * Conventions (the paper's quantities restated exactly):
+ *   ulp32(x)  spacing of FP32 numbers at x: 2^(max(E,-126)-23), E = floor(log2|x|).
+ *   tau_ulp   threshold measured from the rounding boundary (FP32 midpoint) in units of
+ *             ulp32(x).  The paper's tau (distance from the rounded value, written c*2^-23)
+ *             maps to tau_ulp = 0.5 - c.
+ *   thr       integer threshold ceil(tau_ulp * 2^29) in [0, 2^28]; one unit is the FP64
+ *             spacing inside an FP32-normal binade.
+ *   logged    |x - rnd(x)| > (0.5 - thr*2^-29) * ulp32(x)          (Algorithm "log")
+ *   dir       1 when rnd(x) > x (rounded toward +inf, the paper's code 2), else 0 (code 0)
+ *   log       ascending element indices of logged elements + one direction bit each,
+ *             bit (p & 31) of word dir[p >> 5] for entry p.
+ *
+ * Parity status: every function here is pinned by tests/test_oracle_*.py against exact
+ * rational arithmetic, library routines, closed forms and brute force -- except the NaN
+ * payload convention (canonical 0x7FC00000), which is a convention of this build
+ * ("parity unpinned").
+ */
+#ifndef VT_ORACLE_H
+#define VT_ORACLE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VTO_OK 0
+#define VTO_ERR_INVALID_ARG 1
+
+/* rnd_32: IEEE binary64 -> binary32 conversion, round to nearest, ties to even.
+ * Returns the FP32 bit pattern; NaN inputs give 0x7FC00000. (Method, primitive 1.) */
+uint32_t vto_rnd32_bits(double x);
+
+/* ceil(tau_ulp * 2^29); returns 0xFFFFFFFF when tau_ulp is outside [0, 0.5] or NaN. */
+uint32_t vto_thr_from_tau(double tau_ulp);
+
+/* Scaled distance to the rounded value, q = |x - rnd(x)| / (2^-29 ulp32(x)), a real in
+ * [0, 2^28].  For |x| >= 2^-126 the test is exponent-invariant, so x is first scaled into
+ * [1,2); this extends the FP32 grid past FLT_MAX for values that overflow to infinity.
+ * Returns -1 for NaN and +-Inf (never logged). (Algorithm "log", first two steps.) */
+double vto_scaled_round_error(double x);
+
+/* floor(2^28 - q): the boundary distance in threshold units; 2^28 for NaN/Inf. */
+uint32_t vto_boundary_distance(double x);
+
+/* Paper's ternary code for one element: 2 = logged, rounded up; 0 = logged, rounded down;
+ * 1 = ignore. (Algorithm "log".) */
+int vto_ternary_code(double x, uint32_t thr);
+
+/* Trainer side: y[i] = rnd_32(x[i]); logged elements appended to idx/dir in ascending i.
+ * *count receives the number of logged elements even when it exceeds cap (then only the
+ * first cap entries are stored).  n must be < 2^32. */
+int vto_round_log(const double *x, uint64_t n, double tau_ulp, float *y,
+                  uint32_t *idx, uint32_t *dir, uint64_t cap, uint64_t *count);
+
+/* Auditor side (primitive "rev", Algorithm "audit"): unlogged i -> rnd_32(x[i]); logged i
+ * -> rnd_32(x[i]) stepped one FP32 value toward the logged direction when it lies on the
+ * other side of x[i]. */
+int vto_round_replay(const double *x, uint64_t n, const uint32_t *idx, const uint32_t *dir,
+                     uint64_t count, float *y);
+
+/* Scalar FP64 GEMM, C[i,j] = alpha * sum_k opA(i,k) opB(k,j) (+ bias[j]), no contraction.
+ * order 0: k ascending; 1: k descending; 2: long double accumulation ("truth").
+ * Row-major storage; transX != 0 means the operand is stored transposed. */
+int vto_gemm_f64(int transA, int transB, int64_t M, int64_t N, int64_t K, double alpha,
+                 const double *A, int64_t lda, const double *B, int64_t ldb,
+                 const double *bias, double *C, int64_t ldc, int order);
+
+/* Threshold statistics over two results of the same operation (Algorithm "threshold",
+ * collection loop): out[0] = number of elements whose FP32 roundings differ (bit patterns),
+ * out[1] = 1 + max over those of max(D(y1), D(y2)) (0 when there are none),
+ * out[2] = max |ord(y1) - ord(y2)| in FP64 steps, out[3+b] = histogram: b = 0 for equal,
+ * else 1 + floor(log2(steps)). */
+int vto_threshold_stats(const double *y1, const double *y2, uint64_t n, uint64_t out[68]);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,150 @@
+"""ctypes access to the plain C oracle (oracle/vt_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, the smoke check and the bench's cpu_baseline
+leg.  The product package never imports this module.  No arithmetic of the method lives in
+this file: it compiles the C source with gcc, loads it, and marshals numpy arrays.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "vt_oracle.c")
+_LIB = os.path.join(_HERE, "libvt_oracle.so")
+_lib = None
+
+CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-fno-unsafe-math-optimizations",
+          "-shared", "-fPIC", "-std=c11", "-Wall", "-Wextra"]
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (scalar, no contraction, no fast-math)."""
+    hdr = os.path.join(_HERE, "vt_oracle.h")
+    if (not force and os.path.exists(_LIB)
+            and os.path.getmtime(_LIB) >= max(os.path.getmtime(_SRC), os.path.getmtime(hdr))):
+        return _LIB
+    subprocess.check_call(["gcc", *CFLAGS, "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(_LIB)
+        dp, fp = C.POINTER(C.c_double), C.POINTER(C.c_float)
+        u32p, u64p = C.POINTER(C.c_uint32), C.POINTER(C.c_uint64)
+        L.vto_rnd32_bits.restype = C.c_uint32
+        L.vto_rnd32_bits.argtypes = [C.c_double]
+        L.vto_thr_from_tau.restype = C.c_uint32
+        L.vto_thr_from_tau.argtypes = [C.c_double]
+        L.vto_scaled_round_error.restype = C.c_double
+        L.vto_scaled_round_error.argtypes = [C.c_double]
+        L.vto_boundary_distance.restype = C.c_uint32
+        L.vto_boundary_distance.argtypes = [C.c_double]
+        L.vto_ternary_code.restype = C.c_int
+        L.vto_ternary_code.argtypes = [C.c_double, C.c_uint32]
+        L.vto_round_log.restype = C.c_int
+        L.vto_round_log.argtypes = [dp, C.c_uint64, C.c_double, fp, u32p, u32p, C.c_uint64, u64p]
+        L.vto_round_replay.restype = C.c_int
+        L.vto_round_replay.argtypes = [dp, C.c_uint64, u32p, u32p, C.c_uint64, fp]
+        L.vto_gemm_f64.restype = C.c_int
+        L.vto_gemm_f64.argtypes = [C.c_int, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_double,
+                                   dp, C.c_int64, dp, C.c_int64, dp, dp, C.c_int64, C.c_int]
+        L.vto_threshold_stats.restype = C.c_int
+        L.vto_threshold_stats.argtypes = [dp, dp, C.c_uint64, u64p]
+        _lib = L
+    return _lib
+
+
+def _p(a, ct):
+    return a.ctypes.data_as(C.POINTER(ct)) if a is not None else None
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def rnd32_bits(x: float) -> int:
+    return int(lib().vto_rnd32_bits(float(x)))
+
+
+def thr_from_tau(tau_ulp: float) -> int:
+    return int(lib().vto_thr_from_tau(float(tau_ulp)))
+
+
+def scaled_round_error(x: float) -> float:
+    return float(lib().vto_scaled_round_error(float(x)))
+
+
+def boundary_distance(x: float) -> int:
+    return int(lib().vto_boundary_distance(float(x)))
+
+
+def ternary_code(x: float, thr: int) -> int:
+    return int(lib().vto_ternary_code(float(x), int(thr)))
+
+
+def round_log(x, tau_ulp: float, cap: int | None = None):
+    """Returns (y float32[n], idx uint32[min(count,cap)], dir words uint32[ceil(cap/32)], count)."""
+    x = _f64(x).ravel()
+    n = x.size
+    cap = n if cap is None else int(cap)
+    y = np.empty(n, np.float32)
+    idx = np.zeros(max(cap, 1), np.uint32)
+    dirw = np.zeros(max((cap + 31) // 32, 1), np.uint32)
+    cnt = C.c_uint64(0)
+    rc = lib().vto_round_log(_p(x, C.c_double), n, float(tau_ulp), _p(y, C.c_float),
+                             _p(idx, C.c_uint32), _p(dirw, C.c_uint32), cap, C.byref(cnt))
+    if rc != 0:
+        raise ValueError(f"vto_round_log: error {rc}")
+    c = int(cnt.value)
+    k = min(c, cap)
+    return y, idx[:k].copy(), dirw[:(k + 31) // 32].copy(), c
+
+
+def round_replay(x, idx, dirw, count: int | None = None):
+    x = _f64(x).ravel()
+    idx = np.ascontiguousarray(idx, dtype=np.uint32)
+    dirw = np.ascontiguousarray(dirw, dtype=np.uint32)
+    count = idx.size if count is None else int(count)
+    assert dirw.size * 32 >= count and idx.size >= count
+    y = np.empty(x.size, np.float32)
+    rc = lib().vto_round_replay(_p(x, C.c_double), x.size, _p(idx, C.c_uint32),
+                                _p(dirw, C.c_uint32), count, _p(y, C.c_float))
+    if rc != 0:
+        raise ValueError(f"vto_round_replay: error {rc}")
+    return y
+
+
+def gemm_f64(A, B, *, transA=False, transB=False, alpha=1.0, bias=None, order=0):
+    """A, B are 2-D row-major arrays as stored; transX says the stored array is op(X)^T."""
+    A, B = _f64(A), _f64(B)
+    M, K = (A.shape[1], A.shape[0]) if transA else A.shape
+    K2, N = (B.shape[1], B.shape[0]) if transB else B.shape
+    assert K == K2
+    if bias is not None:
+        bias = _f64(bias)
+        assert bias.size == N
+    Cm = np.empty((M, N), np.float64)
+    rc = lib().vto_gemm_f64(int(transA), int(transB), M, N, K, float(alpha),
+                            _p(A, C.c_double), A.shape[1], _p(B, C.c_double), B.shape[1],
+                            _p(bias, C.c_double), _p(Cm, C.c_double), N, int(order))
+    if rc != 0:
+        raise ValueError(f"vto_gemm_f64: error {rc}")
+    return Cm
+
+
+def threshold_stats(y1, y2):
+    y1, y2 = _f64(y1).ravel(), _f64(y2).ravel()
+    assert y1.size == y2.size
+    out = np.zeros(68, np.uint64)
+    rc = lib().vto_threshold_stats(_p(y1, C.c_double), _p(y2, C.c_double), y1.size,
+                                   _p(out, C.c_uint64))
+    if rc != 0:
+        raise ValueError(f"vto_threshold_stats: error {rc}")
+    return {"n_flip": int(out[0]), "thr_flip": int(out[1]), "max_ulp64_diff": int(out[2]),
+            "hist": out[3:].astype(np.uint64).copy()}
