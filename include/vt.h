@@ -1,0 +1,161 @@
+/*
+ * vt.h -- C ABI of the verifiable-training hot path on MI355X (gfx950).
+ *
+ * The library implements the per-layer hook of "Optimistic Verifiable Training by Controlling
+ * Hardware Nondeterminism": a layer is computed in FP64, every output is rounded to FP32, and
+ * the rounding direction of every output that lies close to an FP32 rounding boundary is
+ * recorded in a log; an auditor who recomputed the layer with a different accumulation order
+ * replays that log and ends with bit-identical FP32 values (paper: Method section, primitives
+ * rnd / log / rev / threshold; Appendix algorithms "train", "audit", "log", "threshold").
+ *
+ * General conventions
+ *   - Every pointer named in a "device" role is DEVICE memory owned by the caller (for example
+ *     a PyTorch tensor's data_ptr()).  The library never allocates, frees or retains device
+ *     memory; scratch space is passed in as `ws` and sized with vt_workspace_bytes().
+ *   - `hip_stream` is a hipStream_t (NULL = the default stream).  Calls enqueue work on it and
+ *     return without synchronising; outputs are valid once the stream has been synchronised.
+ *   - The return value is a host-side status (VT_OK or a VT_ERR_* code); argument errors are
+ *     detected before anything is enqueued.  vt_strerror() names a code.
+ *   - Same inputs (and same `variant`) give bit-identical outputs on every run: no kernel uses
+ *     floating-point atomics or a timing-dependent summation order.
+ *
+ * Threshold
+ *   `tau_ulp` is the logging threshold measured from the rounding boundary (the midpoint
+ *   between two neighbouring FP32 values) in units of ulp32(x), the FP32 spacing at x.  The
+ *   paper states its threshold tau as a distance from the *rounded value*, tau = c * 2^-23
+ *   with c in [0.25, 0.5] (Method, "Reducing storage cost"; Algorithm "log" logs when
+ *   |x - rnd(x)| > exp * tau); the two describe the same set with tau_ulp = 0.5 - c.
+ *   The library quantises once on the host: thr = ceil(tau_ulp * 2^29), so one unit of thr is
+ *   one FP64 step inside an FP32-normal binade, and an element is logged iff its boundary
+ *   distance D(x) < thr.  tau_ulp must lie in [0, 0.5].  thr = 1 logs exact ties only.
+ *
+ * The log (one segment per call; the caller sequences segments, Algorithm "audit" reads them
+ * in the same order)
+ *   idx[p]   linear index of the p-th logged output, ascending in p
+ *   dir      one bit per entry: bit (p & 31) of word dir[p >> 5]; 1 = rnd(x) > x (the paper's
+ *            code 2, "up", toward +infinity also for negative x), 0 = rnd(x) < x (code 0)
+ *   count    number of logged outputs.  If it exceeds `cap`, only the first `cap` entries (in
+ *            canonical order) are stored; all other outputs of the call are still complete,
+ *            and the caller may re-run with a larger log.
+ *   Unlogged outputs are the paper's code 1 ("ignore").
+ */
+#ifndef VT_H
+#define VT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VT_OK 0
+#define VT_ERR_INVALID_ARG 1   /* null / negative / misaligned argument, tau_ulp outside [0,0.5], size limit */
+#define VT_ERR_WORKSPACE 2     /* ws is NULL or smaller than vt_workspace_bytes() */
+#define VT_ERR_HIP 3           /* a HIP call or kernel launch failed */
+#define VT_ERR_UNSUPPORTED 4   /* valid request this build has no kernel for */
+
+/* Operation selector for vt_workspace_bytes(). */
+#define VT_OP_ROUND_LOG 0      /* element count n = M * N * batch, K ignored */
+#define VT_OP_ROUND_REPLAY 1   /* needs no workspace (returns 0) */
+#define VT_OP_GEMM_ROUND_LOG 2
+#define VT_OP_THRESHOLD_STATS 3 /* needs no workspace (returns 0) */
+
+/* Caller-owned log buffers (all four pointers are device pointers). */
+typedef struct vt_log {
+    uint32_t *idx;    /* [cap]            ascending linear indices of logged outputs      */
+    uint32_t *dir;    /* [ceil(cap / 32)] packed direction bits, see above                */
+    uint64_t  cap;    /* capacity in entries                                              */
+    uint64_t *count;  /* device scalar: number of logged outputs (may exceed cap)         */
+} vt_log;
+
+/*
+ * Trainer side on a flat FP64 array (Algorithm "train", forward and backward loops:
+ * log(output, b_r, tau, F) followed by output <- rnd_{b_r}(output), with b_r = 32;
+ * Algorithm "log" for the decision).
+ *   x        device, n FP64 values (8-byte aligned)
+ *   y        device, n FP32 values: y[i] = rnd_32(x[i]), IEEE round-to-nearest-even; NaN inputs
+ *            give the canonical quiet NaN 0x7FC00000; overflow gives +-infinity
+ *   log      host struct of device pointers; must not be NULL; log->count must not be NULL;
+ *            idx/dir may be NULL only if cap == 0
+ *   ws       device scratch of at least vt_workspace_bytes(VT_OP_ROUND_LOG, 1, n, 0, 1) bytes,
+ *            256-byte aligned; contents are overwritten
+ *   n        0 <= n < 2^32 (indices are 32-bit)
+ */
+int vt_round_log(const double *x, uint64_t n, double tau_ulp, float *y, const vt_log *log,
+                 void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Auditor side (primitive "rev"; Algorithm "audit": c <- read(F); output_i <- rev(output_i, b_r, c)).
+ *   x            device, the auditor's own n FP64 results
+ *   idx, dir     device, the trainer's log segment for this tensor (count entries, idx ascending)
+ *   count        host value: entries in the segment
+ *   y            device, n FP32 values: unlogged i -> rnd_32(x[i]); logged i -> x[i] rounded toward
+ *                the logged direction (the FP32 neighbour of x[i] on the trainer's side), which is
+ *                what "rev" produces from rnd_32(x[i]) and one nextafter step.
+ *   Entries whose index is >= n are ignored.  If idx is not ascending the result is unspecified
+ *   (but every access stays in bounds).  No workspace is used (ws may be NULL).
+ */
+int vt_round_replay(const double *x, uint64_t n, const uint32_t *idx, const uint32_t *dir,
+                    uint64_t count, float *y, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * The layer itself, fused with the trainer hook (Algorithm "train": output <- l(input) in
+ * b_tr = 64, then log and rnd; the Nondeterminism Challenge section names the tiling of
+ * GEMMs as the source of divergence this controls).
+ *
+ *   C64[b,i,j] = alpha * sum_k opA[b,i,k] * opB[b,k,j]  (+ bias[j])        in FP64 (MFMA)
+ *   C32[b,i,j] = rnd_32(C64[b,i,j]);  decisions logged with linear index (b*M + i)*N + j.
+ *
+ *   transA/transB  0: operand stored row-major as op(X) (A: M x K, B: K x N);
+ *                  1: stored transposed (A: K x M, B: N x K), still row-major
+ *   lda, ldb, ldc  row pitches in elements; strideA/B/C: element offsets between batches
+ *                  (strideA or strideB may be 0 to share an operand)
+ *   bias           device, N FP64 values added after the alpha scaling, or NULL
+ *   C32            device, FP32 output, row pitch ldc >= N
+ *   C64_debug      device or NULL: when given, receives the FP64 values before rounding
+ *                  (dense, pitch N, batch stride M*N) -- for tests and threshold statistics
+ *   variant        accumulation order: 0 = k ascending in one chain per output;
+ *                  1 = k tiles visited in descending order.  Different variants give FP64
+ *                  results that differ in their low bits, as two GPU types would.
+ *   M*N*batch must be < 2^32.  A, B 8-byte aligned.
+ *   ws             at least vt_workspace_bytes(VT_OP_GEMM_ROUND_LOG, M, N, K, batch) bytes.
+ */
+int vt_gemm_f64_round_log(int transA, int transB, int64_t M, int64_t N, int64_t K, double alpha,
+                          const double *A, int64_t lda, int64_t strideA,
+                          const double *B, int64_t ldb, int64_t strideB,
+                          const double *bias, int64_t batch,
+                          float *C32, int64_t ldc, int64_t strideC,
+                          double *C64_debug, int variant,
+                          double tau_ulp, const vt_log *log,
+                          void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Statistics from which a per-layer threshold follows (Algorithm "threshold": the collection
+ * loop over outputs y1, y2 of one layer computed on two devices; here two accumulation orders).
+ *   y1, y2   device, n FP64 values each
+ *   out      device, 68 x uint64:
+ *            out[0]     n_flip   = #{ i : bits(rnd_32(y1[i])) != bits(rnd_32(y2[i])) }
+ *            out[1]     thr_flip = 1 + max over those i of max(D(y1[i]), D(y2[i])), 0 if none:
+ *                       the smallest thr that logs every observed flip, which is the value the
+ *                       algorithm's binary search brackets (tau = (0.5 - (thr_flip-1) 2^-29) 2^-23)
+ *            out[2]     max over i of |ord(y1[i]) - ord(y2[i])|, the distance in FP64 steps
+ *            out[3+b]   histogram of that distance: b = 0 for equal, else 1 + floor(log2(distance))
+ *   The call zeroes `out` itself.  Integer reductions only, so the result is order-independent.
+ */
+int vt_threshold_stats(const double *y1, const double *y2, uint64_t n, uint64_t *out,
+                       void *hip_stream);
+
+/* Scratch bytes needed by an operation of the given shape (0 if none). */
+size_t vt_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int64_t batch);
+
+/* ceil(tau_ulp * 2^29), or 0xFFFFFFFF if tau_ulp is not in [0, 0.5]. Host-only helper. */
+uint32_t vt_thr_from_tau(double tau_ulp);
+
+/* Static string for a status code. */
+const char *vt_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VT_H */

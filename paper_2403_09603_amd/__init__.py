@@ -1,0 +1,12 @@
+"""MI355X-native round/log/replay hot path of optimistic verifiable training.
+
+Thin Python access to the C-ABI library (include/vt.h).  Every step of the path runs in the
+HIP kernels of libvt_hip.so; this package only marshals PyTorch device pointers and streams.
+There is no CPU fallback: calling any entry point without the built library raises.
+"""
+from .binding import (  # noqa: F401
+    VT_OP_GEMM_ROUND_LOG, VT_OP_ROUND_LOG, VT_OP_ROUND_REPLAY, VT_OP_THRESHOLD_STATS,
+    VtError, Log, alloc_log, alloc_workspace, library_path, load_library,
+    vt_gemm_f64_round_log, vt_round_log, vt_round_replay, vt_strerror, vt_thr_from_tau,
+    vt_threshold_stats, vt_workspace_bytes,
+)

@@ -1,0 +1,175 @@
+"""ctypes binding of libvt_hip.so -- argument marshalling only.
+
+Function names and argument meaning follow include/vt.h one to one.  Tensors must live on the
+GPU and be contiguous; PyTorch supplies device memory and the current HIP stream, nothing else.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libvt_hip.so")
+_lib = None
+
+VT_OP_ROUND_LOG, VT_OP_ROUND_REPLAY, VT_OP_GEMM_ROUND_LOG, VT_OP_THRESHOLD_STATS = 0, 1, 2, 3
+
+
+class VtError(RuntimeError):
+    pass
+
+
+class _VtLog(C.Structure):
+    _fields_ = [("idx", C.c_void_p), ("dir", C.c_void_p), ("cap", C.c_uint64), ("count", C.c_void_p)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load the HIP library; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise VtError(f"{_LIB_PATH} is missing: build it with `python -m paper_2403_09603_amd.build` "
+                      "(or __graft_entry__.build()); there is no CPU fallback")
+    L = C.CDLL(_LIB_PATH)
+    vp, i64, u64, dbl, cint = C.c_void_p, C.c_int64, C.c_uint64, C.c_double, C.c_int
+    L.vt_round_log.restype = cint
+    L.vt_round_log.argtypes = [vp, u64, dbl, vp, C.POINTER(_VtLog), vp, C.c_size_t, vp]
+    L.vt_round_replay.restype = cint
+    L.vt_round_replay.argtypes = [vp, u64, vp, vp, u64, vp, vp, C.c_size_t, vp]
+    L.vt_gemm_f64_round_log.restype = cint
+    L.vt_gemm_f64_round_log.argtypes = [cint, cint, i64, i64, i64, dbl, vp, i64, i64, vp, i64, i64, vp, i64,
+                                        vp, i64, i64, vp, cint, dbl, C.POINTER(_VtLog), vp, C.c_size_t, vp]
+    L.vt_threshold_stats.restype = cint
+    L.vt_threshold_stats.argtypes = [vp, vp, u64, vp, vp]
+    L.vt_workspace_bytes.restype = C.c_size_t
+    L.vt_workspace_bytes.argtypes = [cint, i64, i64, i64, i64]
+    L.vt_thr_from_tau.restype = C.c_uint32
+    L.vt_thr_from_tau.argtypes = [dbl]
+    L.vt_strerror.restype = C.c_char_p
+    L.vt_strerror.argtypes = [cint]
+    _lib = L
+    return L
+
+
+def vt_strerror(code: int) -> str:
+    return load_library().vt_strerror(int(code)).decode()
+
+
+def _check(code: int, what: str):
+    if code != 0:
+        raise VtError(f"{what}: {vt_strerror(code)} (status {code})")
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise VtError("tensor must be on the GPU")
+    if not t.is_contiguous():
+        raise VtError("tensor must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise VtError(f"expected {dtype}, got {t.dtype}")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+@dataclass
+class Log:
+    """Caller-owned device buffers of one log segment (the vt_log struct of include/vt.h)."""
+    idx: torch.Tensor      # int32 [cap]  (bit pattern of uint32 indices)
+    dir: torch.Tensor      # int32 [ceil(cap/32)]
+    count: torch.Tensor    # int64 [1]
+    cap: int
+
+    def _c(self) -> _VtLog:
+        return _VtLog(self.idx.data_ptr() if self.cap else None, self.dir.data_ptr() if self.cap else None,
+                      self.cap, self.count.data_ptr())
+
+
+def alloc_log(cap: int, device="cuda") -> Log:
+    cap = int(cap)
+    return Log(torch.empty(max(cap, 1), dtype=torch.int32, device=device),
+               torch.empty(max((cap + 31) // 32, 1), dtype=torch.int32, device=device),
+               torch.zeros(1, dtype=torch.int64, device=device), cap)
+
+
+def vt_workspace_bytes(op: int, M: int, N: int, K: int = 0, batch: int = 1) -> int:
+    return int(load_library().vt_workspace_bytes(int(op), int(M), int(N), int(K), int(batch)))
+
+
+def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def vt_thr_from_tau(tau_ulp: float) -> int:
+    return int(load_library().vt_thr_from_tau(float(tau_ulp)))
+
+
+def vt_round_log(x: torch.Tensor, tau_ulp: float, y: torch.Tensor, log: Log, ws: torch.Tensor, stream=None):
+    n = x.numel()
+    if y.numel() != n:
+        raise VtError("y must have as many elements as x")
+    clog = log._c()
+    _check(load_library().vt_round_log(_ptr(x, torch.float64), n, float(tau_ulp), _ptr(y, torch.float32),
+                                       C.byref(clog), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)),
+           "vt_round_log")
+
+
+def vt_round_replay(x: torch.Tensor, idx: torch.Tensor, dir: torch.Tensor, count: int, y: torch.Tensor,
+                    stream=None):
+    n = x.numel()
+    if y.numel() != n:
+        raise VtError("y must have as many elements as x")
+    count = int(count)
+    if count > idx.numel() or (count + 31) // 32 > dir.numel():
+        raise VtError("count exceeds the log buffers")
+    _check(load_library().vt_round_replay(_ptr(x, torch.float64), n, _ptr(idx, torch.int32), _ptr(dir, torch.int32),
+                                          count, _ptr(y, torch.float32), None, 0, _stream(stream)),
+           "vt_round_replay")
+
+
+def vt_gemm_f64_round_log(transA: bool, transB: bool, M: int, N: int, K: int, alpha: float,
+                          A: torch.Tensor, lda: int, strideA: int, B: torch.Tensor, ldb: int, strideB: int,
+                          bias, batch: int, C32: torch.Tensor, ldc: int, strideC: int, C64_debug,
+                          variant: int, tau_ulp: float, log: Log, ws: torch.Tensor, stream=None):
+    # extent checks: the kernels trust lda/ldb/ldc/strides, so make sure the tensors cover them
+    def need(rows, cols, ld, stride):
+        return 0 if rows == 0 or cols == 0 or batch == 0 else (batch - 1) * stride + (rows - 1) * ld + cols
+    if A.numel() < need(K if transA else M, M if transA else K, lda, strideA):
+        raise VtError("A is smaller than M, K, lda, strideA, batch imply")
+    if B.numel() < need(N if transB else K, K if transB else N, ldb, strideB):
+        raise VtError("B is smaller than K, N, ldb, strideB, batch imply")
+    if C32.numel() < need(M, N, ldc, strideC):
+        raise VtError("C32 is smaller than M, N, ldc, strideC, batch imply")
+    if bias is not None and bias.numel() < N:
+        raise VtError("bias is shorter than N")
+    if C64_debug is not None and C64_debug.numel() < M * N * batch:
+        raise VtError("C64_debug is smaller than M*N*batch")
+    clog = log._c()
+    _check(load_library().vt_gemm_f64_round_log(
+        int(bool(transA)), int(bool(transB)), int(M), int(N), int(K), float(alpha),
+        _ptr(A, torch.float64), int(lda), int(strideA), _ptr(B, torch.float64), int(ldb), int(strideB),
+        _ptr(bias, torch.float64), int(batch), _ptr(C32, torch.float32), int(ldc), int(strideC),
+        _ptr(C64_debug, torch.float64), int(variant), float(tau_ulp), C.byref(clog),
+        _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "vt_gemm_f64_round_log")
+
+
+def vt_threshold_stats(y1: torch.Tensor, y2: torch.Tensor, out: torch.Tensor, stream=None):
+    if y1.numel() != y2.numel():
+        raise VtError("y1 and y2 differ in size")
+    if out.numel() < 68 or out.dtype != torch.int64:
+        raise VtError("out must be an int64 tensor of 68 elements")
+    _check(load_library().vt_threshold_stats(_ptr(y1, torch.float64), _ptr(y2, torch.float64), y1.numel(),
+                                             _ptr(out), _stream(stream)), "vt_threshold_stats")

@@ -1,0 +1,137 @@
+// vt_api.hip -- the C ABI declared in include/vt.h: argument checks and kernel sequencing.
+#include "../../include/vt.h"
+#include "vt_kernels.h"
+
+#include <cmath>
+
+namespace {
+
+inline bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? VT_OK : VT_ERR_HIP; }
+
+inline bool log_ok(const vt_log *log)
+{
+    if (!log || !log->count || !aligned(log->count, 8)) return false;
+    if (log->cap && (!log->idx || !log->dir || !aligned(log->idx, 4) || !aligned(log->dir, 4))) return false;
+    return true;
+}
+
+// planes already hold the decisions: count per segment (unless the producer did), scan, compact
+int finish_log(const vt::Planes &pl, const vt_log *log, bool counted, hipStream_t s)
+{
+    const vt::LogOut lo{log->idx, log->dir, log->cap, log->count};
+    hipError_t e = hipSuccess;
+    if (!counted) e = vt::launch_seg_count(pl, s);
+    if (e == hipSuccess) e = vt::launch_seg_scan(pl, lo, s);
+    if (e == hipSuccess) e = vt::launch_compact(pl, lo, s);
+    return hip_status(e);
+}
+
+}  // namespace
+
+extern "C" {
+
+uint32_t vt_thr_from_tau(double tau_ulp)
+{
+    if (!(tau_ulp >= 0.0 && tau_ulp <= 0.5)) return 0xFFFFFFFFu;
+    return (uint32_t)std::ceil(std::ldexp(tau_ulp, 29));
+}
+
+const char *vt_strerror(int code)
+{
+    switch (code) {
+    case VT_OK: return "ok";
+    case VT_ERR_INVALID_ARG: return "invalid argument";
+    case VT_ERR_WORKSPACE: return "workspace missing or too small";
+    case VT_ERR_HIP: return "HIP call or kernel launch failed";
+    case VT_ERR_UNSUPPORTED: return "unsupported request";
+    default: return "unknown status";
+    }
+}
+
+size_t vt_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int64_t batch)
+{
+    (void)K;
+    if (M < 0 || N < 0 || batch < 0) return 0;
+    switch (op) {
+    case VT_OP_ROUND_LOG: return vt::planes_bytes(1, (uint64_t)M * (uint64_t)N * (uint64_t)batch);
+    case VT_OP_GEMM_ROUND_LOG: return vt::planes_bytes((uint64_t)M * (uint64_t)batch, (uint64_t)N);
+    default: return 0;
+    }
+}
+
+int vt_round_log(const double *x, uint64_t n, double tau_ulp, float *y, const vt_log *log,
+                 void *ws, size_t ws_bytes, void *hip_stream)
+{
+    const uint32_t thr = vt_thr_from_tau(tau_ulp);
+    if (thr == 0xFFFFFFFFu || n >= (1ull << 32) || !log_ok(log)) return VT_ERR_INVALID_ARG;
+    if (n && (!x || !y || !aligned(x, 8) || !aligned(y, 4))) return VT_ERR_INVALID_ARG;
+    const size_t need = vt::planes_bytes(1, n);
+    if (need && (!ws || ws_bytes < need || !aligned(ws, 256))) return VT_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const vt::Planes pl = vt::planes_carve(ws, 1, n);
+    hipError_t e = vt::launch_round_planes(x, n, thr, y, pl, s);
+    if (e != hipSuccess) return VT_ERR_HIP;
+    return finish_log(pl, log, /*counted=*/true, s);
+}
+
+int vt_round_replay(const double *x, uint64_t n, const uint32_t *idx, const uint32_t *dir,
+                    uint64_t count, float *y, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    (void)ws; (void)ws_bytes;
+    if (n >= (1ull << 32) || count >= (1ull << 32)) return VT_ERR_INVALID_ARG;
+    if (n && (!x || !y || !aligned(x, 8) || !aligned(y, 4))) return VT_ERR_INVALID_ARG;
+    if (count && (!idx || !dir || !aligned(idx, 4) || !aligned(dir, 4))) return VT_ERR_INVALID_ARG;
+    return hip_status(vt::launch_replay(x, n, idx, dir, count, y, (hipStream_t)hip_stream));
+}
+
+int vt_gemm_f64_round_log(int transA, int transB, int64_t M, int64_t N, int64_t K, double alpha,
+                          const double *A, int64_t lda, int64_t strideA,
+                          const double *B, int64_t ldb, int64_t strideB,
+                          const double *bias, int64_t batch,
+                          float *C32, int64_t ldc, int64_t strideC,
+                          double *C64_debug, int variant,
+                          double tau_ulp, const vt_log *log,
+                          void *ws, size_t ws_bytes, void *hip_stream)
+{
+    const uint32_t thr = vt_thr_from_tau(tau_ulp);
+    if (thr == 0xFFFFFFFFu || !log_ok(log)) return VT_ERR_INVALID_ARG;
+    if (M < 0 || N < 0 || K < 0 || batch < 0 || variant < 0 || variant > 1) return VT_ERR_INVALID_ARG;
+    if ((transA != 0 && transA != 1) || (transB != 0 && transB != 1)) return VT_ERR_INVALID_ARG;
+    if ((unsigned __int128)M * (unsigned __int128)N * (unsigned __int128)batch >= ((unsigned __int128)1 << 32))
+        return VT_ERR_INVALID_ARG;          // log indices are 32-bit
+    const uint64_t total = (uint64_t)M * (uint64_t)N * (uint64_t)batch;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (total == 0) {                       // nothing to compute; the log is empty
+        const vt::Planes pl = vt::planes_carve(ws, 0, 0);
+        const vt::LogOut lo{log->idx, log->dir, log->cap, log->count};
+        return hip_status(vt::launch_seg_scan(pl, lo, s));
+    }
+    if (!C32 || !aligned(C32, 4) || ldc < N || (batch > 1 && strideC < 0)) return VT_ERR_INVALID_ARG;
+    if (K > 0) {
+        if (!A || !B || !aligned(A, 8) || !aligned(B, 8)) return VT_ERR_INVALID_ARG;
+        if (lda < (transA ? M : K) || ldb < (transB ? K : N) || strideA < 0 || strideB < 0) return VT_ERR_INVALID_ARG;
+    }
+    if (C64_debug && !aligned(C64_debug, 8)) return VT_ERR_INVALID_ARG;
+    const size_t need = vt::planes_bytes((uint64_t)M * (uint64_t)batch, (uint64_t)N);
+    if (!ws || ws_bytes < need || !aligned(ws, 256)) return VT_ERR_WORKSPACE;
+    const vt::Planes pl = vt::planes_carve(ws, (uint64_t)M * (uint64_t)batch, (uint64_t)N);
+    vt::GemmArgs g;
+    g.transA = transA; g.transB = transB; g.M = M; g.N = N; g.K = K; g.alpha = alpha;
+    g.A = A; g.lda = lda; g.strideA = strideA; g.B = B; g.ldb = ldb; g.strideB = strideB;
+    g.bias = bias; g.batch = batch; g.C32 = C32; g.ldc = ldc; g.strideC = strideC;
+    g.C64 = C64_debug; g.variant = variant; g.thr = thr;
+    hipError_t e = vt::launch_gemm_round_planes(g, pl, s);
+    if (e != hipSuccess) return VT_ERR_HIP;
+    return finish_log(pl, log, /*counted=*/false, s);
+}
+
+int vt_threshold_stats(const double *y1, const double *y2, uint64_t n, uint64_t *out, void *hip_stream)
+{
+    if (!out || !aligned(out, 8)) return VT_ERR_INVALID_ARG;
+    if (n && (!y1 || !y2 || !aligned(y1, 8) || !aligned(y2, 8))) return VT_ERR_INVALID_ARG;
+    return hip_status(vt::launch_stats(y1, y2, n, out, (hipStream_t)hip_stream));
+}
+
+}  // extern "C"

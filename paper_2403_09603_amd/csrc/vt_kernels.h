@@ -1,0 +1,67 @@
+// vt_kernels.h -- host-callable launchers of the gfx950 kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace vt {
+
+// A "segment" is 64 consecutive 64-bit words of a decision bit-plane (4096 outputs); one
+// wavefront owns one segment in the plane-producing and plane-compacting kernels.
+constexpr uint32_t kSegWords = 64;
+constexpr uint32_t kSegElems = 64 * kSegWords;
+
+// Decision bit-planes and per-segment bookkeeping inside the caller's workspace.
+struct Planes {
+    uint64_t *logged;    // [segs * 64] bit = 1: output is logged
+    uint64_t *dir;       // [segs * 64] bit = 1: rounded toward +inf
+    uint32_t *seg_cnt;   // [segs] logged outputs per segment
+    uint32_t *seg_off;   // [segs] exclusive prefix of seg_cnt
+    uint64_t words;      // words in use (rows * words_per_row)
+    uint32_t segs;       // ceil(words / 64)
+    // bit -> linear index mapping: word w covers row w / wpr, columns 64 * (w % wpr) ...
+    uint32_t wpr;        // words per row
+    uint32_t ncols;      // row length N (linear index = row * N + col)
+};
+
+size_t planes_bytes(uint64_t rows, uint64_t ncols);
+Planes planes_carve(void *ws, uint64_t rows, uint64_t ncols);
+
+struct LogOut {
+    uint32_t *idx;
+    uint32_t *dir;
+    uint64_t cap;
+    uint64_t *count;
+};
+
+// round + decide on a flat array: y, both bit-planes and seg_cnt (standalone trainer hook)
+hipError_t launch_round_planes(const double *x, uint64_t n, uint32_t thr, float *y, const Planes &pl,
+                               hipStream_t s);
+// seg_cnt from an already written `logged` plane (GEMM epilogue output)
+hipError_t launch_seg_count(const Planes &pl, hipStream_t s);
+// seg_off = exclusive scan(seg_cnt); *count = total; clears the dir words compaction will OR into
+hipError_t launch_seg_scan(const Planes &pl, const LogOut &log, hipStream_t s);
+// ordered stream compaction: planes -> ascending idx[] + packed direction bits
+hipError_t launch_compact(const Planes &pl, const LogOut &log, hipStream_t s);
+
+hipError_t launch_replay(const double *x, uint64_t n, const uint32_t *idx, const uint32_t *dir,
+                         uint64_t count, float *y, hipStream_t s);
+
+hipError_t launch_stats(const double *y1, const double *y2, uint64_t n, uint64_t *out, hipStream_t s);
+
+struct GemmArgs {
+    int transA, transB;
+    int64_t M, N, K;
+    double alpha;
+    const double *A; int64_t lda, strideA;
+    const double *B; int64_t ldb, strideB;
+    const double *bias;
+    int64_t batch;
+    float *C32; int64_t ldc, strideC;
+    double *C64;          // optional dense FP64 copy (pitch N)
+    int variant;
+    uint32_t thr;
+};
+hipError_t launch_gemm_round_planes(const GemmArgs &g, const Planes &pl, hipStream_t s);
+
+}  // namespace vt

@@ -1,0 +1,83 @@
+"""numpy-in / numpy-out wrappers around the HIP library for the GPU parity tests.
+Everything computed here goes through the C ABI (paper_2403_09603_amd.binding)."""
+import numpy as np
+import torch
+
+import paper_2403_09603_amd as vt
+
+DEV = "cuda"
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+def gpu_round_log(x, tau, cap=None):
+    x = np.ascontiguousarray(x, np.float64).ravel()
+    n = x.size
+    cap = n if cap is None else cap
+    xd = dev(x) if n else torch.empty(0, dtype=torch.float64, device=DEV)
+    y = torch.empty(n, dtype=torch.float32, device=DEV)
+    log = vt.alloc_log(cap)
+    ws = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_ROUND_LOG, 1, n))
+    vt.vt_round_log(xd, tau, y, log, ws)
+    torch.cuda.synchronize()
+    count = int(log.count.item())
+    k = min(count, cap)
+    return (y.cpu().numpy(), u32(log.idx)[:k].copy(), u32(log.dir)[:(k + 31) // 32].copy(), count)
+
+
+def gpu_round_replay(x, idx, dirw, count=None):
+    x = np.ascontiguousarray(x, np.float64).ravel()
+    count = len(idx) if count is None else count
+    xd = dev(x)
+    y = torch.empty(x.size, dtype=torch.float32, device=DEV)
+    idx_d = dev(np.ascontiguousarray(idx, np.uint32).view(np.int32)) if len(idx) else torch.zeros(1, dtype=torch.int32, device=DEV)
+    dir_d = dev(np.ascontiguousarray(dirw, np.uint32).view(np.int32)) if len(dirw) else torch.zeros(1, dtype=torch.int32, device=DEV)
+    vt.vt_round_replay(xd, idx_d, dir_d, count, y)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+def gpu_stats(y1, y2):
+    out = torch.full((68,), -1, dtype=torch.int64, device=DEV)
+    vt.vt_threshold_stats(dev(np.ascontiguousarray(y1, np.float64).ravel()),
+                          dev(np.ascontiguousarray(y2, np.float64).ravel()), out)
+    torch.cuda.synchronize()
+    o = out.cpu().numpy().view(np.uint64)
+    return {"n_flip": int(o[0]), "thr_flip": int(o[1]), "max_ulp64_diff": int(o[2]), "hist": o[3:].copy()}
+
+
+def gpu_gemm(A, B, *, transA=False, transB=False, alpha=1.0, bias=None, tau=0.0, variant=0, cap=None,
+             want_c64=True, ldc=None):
+    """A, B: numpy arrays as stored, 2-D (or 3-D with a leading batch dimension)."""
+    A = np.ascontiguousarray(A, np.float64)
+    B = np.ascontiguousarray(B, np.float64)
+    batch = A.shape[0] if A.ndim == 3 else 1
+    a2, b2 = A.shape[-2:], B.shape[-2:]
+    M, K = (a2[1], a2[0]) if transA else a2
+    K2, N = (b2[1], b2[0]) if transB else b2
+    assert K == K2
+    strideA = a2[0] * a2[1] if A.ndim == 3 else 0
+    strideB = b2[0] * b2[1] if B.ndim == 3 else 0
+    ldc = N if ldc is None else ldc
+    total = batch * M * N
+    cap = total if cap is None else cap
+    Ad, Bd = dev(A), dev(B)
+    C32 = torch.full((batch, M, ldc), float("nan"), dtype=torch.float32, device=DEV)
+    C64 = torch.empty((batch, M, N), dtype=torch.float64, device=DEV) if want_c64 else None
+    log = vt.alloc_log(cap)
+    ws = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG, M, N, K, batch))
+    bias_d = dev(np.ascontiguousarray(bias, np.float64)) if bias is not None else None
+    vt.vt_gemm_f64_round_log(transA, transB, M, N, K, alpha, Ad, a2[1], strideA, Bd, b2[1], strideB, bias_d, batch,
+                             C32, ldc, M * ldc, C64, variant, tau, log, ws)
+    torch.cuda.synchronize()
+    count = int(log.count.item())
+    k = min(count, cap)
+    return {"C32": C32.cpu().numpy()[:, :, :N].reshape(batch, M, N), "C32_full": C32.cpu().numpy(),
+            "C64": C64.cpu().numpy() if want_c64 else None,
+            "idx": u32(log.idx)[:k].copy(), "dir": u32(log.dir)[:(k + 31) // 32].copy(), "count": count}

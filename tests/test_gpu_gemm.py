@@ -1,0 +1,158 @@
+"""GPU parity: fused FP64 GEMM + round + log against the CPU oracle through the C ABI.
+
+FP64 values: within 1e-12 * |alpha| * ||A_i|| ||B_j|| (+ |bias|) of the oracle's extended-precision
+result.  Everything after the FP64 value -- FP32 outputs, logged index list, direction bits,
+count -- must be bit-exact against the oracle's round/log applied to the kernel's own FP64 values.
+"""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import vt_oracle as vo
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    import gpu_util
+    return gpu_util
+
+
+def _bits(y):
+    return np.ascontiguousarray(y, np.float32).view(np.uint32)
+
+
+def _dir_bits(dirw, count):
+    return np.unpackbits(np.ascontiguousarray(dirw, np.uint32).view(np.uint8), bitorder="little")[:count]
+
+
+def _check(G, A, B, *, transA=False, transB=False, alpha=1.0, bias=None, tau=2.0 ** -6, variant=0, ldc=None):
+    r = G.gpu_gemm(A, B, transA=transA, transB=transB, alpha=alpha, bias=bias, tau=tau, variant=variant, ldc=ldc)
+    A3 = A if A.ndim == 3 else A[None]
+    B3 = B if B.ndim == 3 else B[None]
+    batch = max(A3.shape[0], B3.shape[0])
+    for b in range(batch):
+        Ab, Bb = A3[b % A3.shape[0]], B3[b % B3.shape[0]]
+        truth = vo.gemm_f64(Ab, Bb, transA=transA, transB=transB, alpha=alpha, bias=bias, order=2)
+        opA = Ab.T if transA else Ab
+        opB = Bb.T if transB else Bb
+        bound = 1e-12 * (abs(alpha) * np.linalg.norm(opA, axis=1)[:, None] * np.linalg.norm(opB, axis=0)[None, :]
+                         + (np.abs(bias)[None, :] if bias is not None else 0.0)) + 1e-300
+        assert np.all(np.abs(r["C64"][b] - truth) <= bound), float(np.max(np.abs(r["C64"][b] - truth) / bound))
+    yo, io, do, co = vo.round_log(r["C64"].ravel(), tau)
+    assert r["count"] == co
+    assert np.array_equal(_bits(r["C32"].ravel()), _bits(yo))
+    assert np.array_equal(r["idx"], io)
+    assert np.array_equal(_dir_bits(r["dir"], len(io)), _dir_bits(do, len(io)))
+    return r
+
+
+def test_config1_tiny_gemm_and_auditor_replay(G):
+    """Config 1: 256^3, N(0,1).  Trainer = GPU; auditor = CPU oracle with reversed k summation;
+    threshold from the statistics of the pair; the oracle replays the GPU's log: 0 mismatches."""
+    A, B = si.tiny_gemm()
+    r0 = _check(G, A, B, tau=0.0)
+    aud = vo.gemm_f64(A, B, order=1)
+    st = G.gpu_stats(r0["C64"], aud)
+    so = vo.threshold_stats(r0["C64"], aud)
+    assert st["n_flip"] == so["n_flip"] and st["thr_flip"] == so["thr_flip"] and np.array_equal(st["hist"], so["hist"])
+    need = max(st["thr_flip"], st["max_ulp64_diff"] + 1, 1)
+    thr = 1 << int(np.ceil(np.log2(need)))
+    assert thr <= 1 << 27
+    r = _check(G, A, B, tau=thr * 2.0 ** -29)
+    y_aud = vo.round_replay(aud.ravel(), r["idx"], r["dir"])
+    assert np.array_equal(_bits(y_aud), _bits(r["C32"].ravel()))
+    y_gpu_aud = G.gpu_round_replay(aud.ravel(), r["idx"], r["dir"])
+    assert np.array_equal(_bits(y_gpu_aud), _bits(r["C32"].ravel()))
+
+
+def test_variants_differ_in_low_bits_and_are_deterministic(G):
+    A, B = si.tiny_gemm()
+    r0 = G.gpu_gemm(A, B, variant=0, tau=0.25)
+    r1 = G.gpu_gemm(A, B, variant=1, tau=0.25)
+    r0b = G.gpu_gemm(A, B, variant=0, tau=0.25)
+    assert np.array_equal(r0["C64"], r0b["C64"]) and np.array_equal(r0["idx"], r0b["idx"])
+    assert np.array_equal(r0["dir"], r0b["dir"])
+    assert (r0["C64"] != r1["C64"]).mean() > 0.3
+    assert np.max(np.abs(r0["C64"] - r1["C64"])) < 1e-12
+    _check(G, A, B, variant=1)
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1), (130, 70, 37), (128, 128, 16), (129, 257, 17), (64, 200, 100),
+                                   (300, 64, 5), (17, 1000, 64), (256, 192, 0)])
+def test_ragged_shapes(G, shape):
+    M, N, K = shape
+    g = si.rng(si.seed_for(1, 11) + M + 7 * N + 13 * K)
+    A, B = g.standard_normal((M, K)), g.standard_normal((K, N))
+    bias = g.standard_normal(N)
+    _check(G, A, B, alpha=0.5, bias=bias, tau=2.0 ** -3)
+
+
+@pytest.mark.parametrize("transA,transB", [(False, True), (True, False), (True, True)])
+def test_transposed_operands(G, transA, transB):
+    g = si.rng(si.seed_for(1, 12))
+    M, N, K = 150, 90, 75
+    A = g.standard_normal((K, M) if transA else (M, K))
+    B = g.standard_normal((N, K) if transB else (K, N))
+    _check(G, A, B, transA=transA, transB=transB, alpha=0.125, tau=2.0 ** -5)
+
+
+def test_batched_scores_shape(G):
+    """Attention scores: per (batch, head) Q K^T / 8 with B stored transposed, alpha = 1/8."""
+    g = si.rng(si.seed_for(3, 0))
+    Q = g.standard_normal((3, 200, 64)).astype(np.float32).astype(np.float64)
+    Kh = g.standard_normal((3, 136, 64)).astype(np.float32).astype(np.float64)
+    _check(G, Q, Kh, transB=True, alpha=0.125, tau=2.0 ** -4)
+    _check(G, Q, Kh[0], transB=True, alpha=0.125, tau=2.0 ** -4)       # shared B (stride 0)
+
+
+def test_padded_output_pitch(G):
+    g = si.rng(si.seed_for(1, 13))
+    A, B = g.standard_normal((70, 33)), g.standard_normal((33, 50))
+    r = _check(G, A, B, ldc=64)
+    assert np.isnan(r["C32_full"][:, :, 50:]).all()          # padding untouched
+
+
+def test_small_integer_matrices_are_exact(G):
+    g = si.rng(si.seed_for(1, 14))
+    A = g.integers(-50, 51, (140, 77)).astype(np.float64)
+    B = g.integers(-50, 51, (77, 130)).astype(np.float64)
+    want = (A.astype(np.int64) @ B.astype(np.int64)).astype(np.float64)
+    for variant in (0, 1):
+        r = G.gpu_gemm(A, B, variant=variant, tau=0.5)
+        assert np.array_equal(r["C64"][0], want)
+        assert r["count"] == 0                               # integers are FP32 values: nothing to log
+
+
+def test_planted_midpoint_gemm_flips_and_replay(G):
+    """Outputs sit on or next to FP32 midpoints, so two accumulation orders round differently
+    for many outputs; the log must bring the auditor back: 0 mismatches."""
+    A, B = si.planted_midpoint_gemm(192, 160, 64, si.seed_for(1, 15))
+    r = _check(G, A, B, tau=0.0)
+    aud = vo.gemm_f64(A, B, order=1)
+    st = G.gpu_stats(r["C64"], aud)
+    assert st["n_flip"] > 1000                               # the test is not vacuous
+    need = max(st["thr_flip"], st["max_ulp64_diff"] + 1)
+    thr = 1 << int(np.ceil(np.log2(need)))
+    assert thr <= 1 << 27
+    r = _check(G, A, B, tau=thr * 2.0 ** -29)
+    plain = vo.round_replay(aud.ravel(), r["idx"][:0], np.zeros(1, np.uint32), count=0)
+    assert (_bits(plain) != _bits(r["C32"].ravel())).sum() == st["n_flip"]
+    for replay in (vo.round_replay, G.gpu_round_replay):
+        assert np.array_equal(_bits(replay(aud.ravel(), r["idx"], r["dir"])), _bits(r["C32"].ravel()))
+    # GPU variant 1 as the auditor
+    r1 = G.gpu_gemm(A, B, variant=1)
+    st1 = G.gpu_stats(r["C64"], r1["C64"])
+    if max(st1["thr_flip"], st1["max_ulp64_diff"] + 1) <= thr:
+        assert np.array_equal(_bits(G.gpu_round_replay(r1["C64"].ravel(), r["idx"], r["dir"])), _bits(r["C32"].ravel()))
+
+
+def test_log_capacity_overflow(G):
+    A, B = si.tiny_gemm()
+    full = G.gpu_gemm(A, B, tau=0.25)
+    cut = G.gpu_gemm(A, B, tau=0.25, cap=1000)
+    assert cut["count"] == full["count"] > 1000
+    assert np.array_equal(cut["idx"], full["idx"][:1000])
+    assert np.array_equal(_dir_bits(cut["dir"], 1000), _dir_bits(full["dir"], 1000))
+    assert np.array_equal(_bits(cut["C32"]), _bits(full["C32"]))

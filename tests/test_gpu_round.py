@@ -1,0 +1,119 @@
+"""GPU parity: standalone round/log, replay and threshold statistics against the CPU oracle,
+element by element through the C ABI.  Bar: bit-exact FP32 outputs, index lists, direction
+bits, counts and integer statistics."""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import vt_oracle as vo
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    import gpu_util
+    return gpu_util
+
+
+def _bits(y):
+    return np.ascontiguousarray(y, np.float32).view(np.uint32)
+
+
+def _dir_bits(dirw, count):
+    return np.unpackbits(np.ascontiguousarray(dirw, np.uint32).view(np.uint8), bitorder="little")[:count]
+
+
+def _same_log(g, o):
+    yg, ig, dg, cg = g
+    yo, io, do, co = o
+    assert cg == co
+    assert np.array_equal(_bits(yg), _bits(yo))
+    assert np.array_equal(ig, io)
+    assert np.array_equal(_dir_bits(dg, len(ig)), _dir_bits(do, len(io)))
+
+
+TAUS = [0.0, 2.0 ** -40, 2.0 ** -24, 2.0 ** -4, 0.25, 0.5]
+
+
+@pytest.mark.parametrize("tau", TAUS)
+def test_round_log_edge_values(G, tau):
+    x = si.edge_values()
+    _same_log(G.gpu_round_log(x, tau), vo.round_log(x, tau))
+
+
+@pytest.mark.parametrize("n", [0, 1, 63, 64, 65, 4095, 4096, 4097, 3 * 4096 + 17, 16 * 4096, 100003])
+def test_round_log_ragged_sizes(G, n):
+    x, _ = si.planted_vector(n, si.seed_for(1, 4) + n, thr=32, planted_frac=0.2) if n else (np.zeros(0), None)
+    for tau in (2.0 ** -24, 0.25):
+        _same_log(G.gpu_round_log(x, tau), vo.round_log(x, tau))
+
+
+@pytest.mark.parametrize("tau", [2.0 ** -30, 2.0 ** -4, 0.25])
+def test_round_log_config1_vector(G, tau):
+    """Config 1: 2^20 values ~ N(0,1); at tau = 2^-30 (thr = 1) random data logs nothing, so the
+    same vector is also run with 1 % planted exact ties."""
+    x = si.normal(1 << 20, si.seed_for(1, 2))
+    _same_log(G.gpu_round_log(x, tau), vo.round_log(x, tau))
+    xp, kind = si.planted_vector(1 << 20, si.seed_for(1, 3), thr=1, planted_frac=0.01)
+    g = G.gpu_round_log(xp, tau)
+    _same_log(g, vo.round_log(xp, tau))
+    if tau == 2.0 ** -30:
+        assert g[3] == int((kind == 1).sum()) > 0
+
+
+def test_round_log_is_deterministic_and_cap_overflow(G):
+    x, _ = si.planted_vector(50000, si.seed_for(1, 5), thr=1 << 20, planted_frac=0.3)
+    tau = 2.0 ** -9
+    a = G.gpu_round_log(x, tau)
+    b = G.gpu_round_log(x, tau)
+    assert a[3] == b[3] and all(np.array_equal(p, q) for p, q in zip(a[:3], b[:3]))
+    full = vo.round_log(x, tau)
+    for cap in (0, 1, 31, 32, 33, 1000, full[3] - 1, full[3]):
+        g = G.gpu_round_log(x, tau, cap=cap)
+        o = vo.round_log(x, tau, cap=cap)
+        _same_log(g, o)
+        assert g[3] == full[3] and len(g[1]) == min(cap, full[3])
+
+
+@pytest.mark.parametrize("thr,tau", [(1, 2.0 ** -40), (32, 2.0 ** -24), (1 << 20, 2.0 ** -9), (1 << 27, 0.25)])
+def test_replay_matches_oracle_and_trainer(G, thr, tau):
+    n = 3 * 4096 + 123
+    x, _ = si.planted_vector(n, si.seed_for(5, 4), thr=thr, planted_frac=0.25)
+    xa = si.perturb_steps(x, si.seed_for(5, 5), thr)
+    yT, idx, dirw, count = G.gpu_round_log(x, tau)
+    yA = G.gpu_round_replay(xa, idx, dirw)
+    assert np.array_equal(_bits(yA), _bits(vo.round_replay(xa, idx, dirw)))   # GPU replay == oracle replay
+    assert np.array_equal(_bits(yA), _bits(yT))                                # auditor == trainer: 0 mismatches
+    # CPU auditor replaying the GPU trainer's log
+    assert np.array_equal(_bits(vo.round_replay(xa, idx, dirw)), _bits(yT))
+
+
+def test_replay_edge_values_all_logged_and_empty(G):
+    x = si.edge_values()
+    n = x.size
+    idx = np.arange(n, dtype=np.uint32)
+    for word in (0, 0xFFFFFFFF, 0xA5A5A5A5):
+        dirw = np.full((n + 31) // 32, word, np.uint32)
+        assert np.array_equal(_bits(G.gpu_round_replay(x, idx, dirw)), _bits(vo.round_replay(x, idx, dirw)))
+    empty = G.gpu_round_replay(x, idx[:0], np.zeros(0, np.uint32), count=0)
+    assert np.array_equal(_bits(empty), _bits(vo.round_replay(x, idx[:0], np.zeros(1, np.uint32), count=0)))
+    # sparse log with entries at tile borders and stray indices >= n (ignored)
+    idx2 = np.array([0, 4095, 4096, 8191, n - 1, n, n + 7], np.uint32)
+    dir2 = np.array([0b1010101], np.uint32)
+    assert np.array_equal(_bits(G.gpu_round_replay(x, idx2, dir2)), _bits(vo.round_replay(x, idx2, dir2)))
+
+
+@pytest.mark.parametrize("n", [1, 64, 4097, 70001])
+def test_threshold_stats(G, n):
+    thr = 4096
+    x, _ = si.planted_vector(n, si.seed_for(6, 8) + n, thr=thr, planted_frac=0.3)
+    y2 = si.perturb_steps(x, si.seed_for(6, 9), thr)
+    if n > 8:
+        x[:4] = [0.0, -0.0, 1.0, np.inf]
+        y2[:4] = [-0.0, 0.0, -1.0, np.inf]
+    g, o = G.gpu_stats(x, y2), vo.threshold_stats(x, y2)
+    assert g["n_flip"] == o["n_flip"] and g["thr_flip"] == o["thr_flip"]
+    assert g["max_ulp64_diff"] == o["max_ulp64_diff"]
+    assert np.array_equal(g["hist"], o["hist"])
+    assert G.gpu_stats(x, x)["n_flip"] == 0
