@@ -152,6 +152,16 @@ size_t vt_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int64_t batch
 /* ceil(tau_ulp * 2^29), or 0xFFFFFFFF if tau_ulp is not in [0, 0.5]. Host-only helper. */
 uint32_t vt_thr_from_tau(double tau_ulp);
 
+/*
+ * Optional instrumentation for benchmarks (no counterpart in the paper).  While two hipEvent_t
+ * handles are registered, vt_gemm_f64_round_log, vt_round_log and vt_round_replay record
+ * ev_begin immediately before and ev_end immediately after their MAIN kernel (the GEMM, the
+ * round/decide sweep, the replay sweep) on the call's stream, so a caller can time that kernel
+ * alone, without the small log-compaction kernels that follow it.  Pass NULL, NULL to clear.
+ * Process-wide, not thread-safe; the events stay owned by the caller.
+ */
+int vt_set_kernel_events(void *ev_begin, void *ev_end);
+
 /* Static string for a status code. */
 const char *vt_strerror(int code);
 

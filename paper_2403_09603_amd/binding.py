@@ -53,6 +53,8 @@ def load_library():
     L.vt_workspace_bytes.argtypes = [cint, i64, i64, i64, i64]
     L.vt_thr_from_tau.restype = C.c_uint32
     L.vt_thr_from_tau.argtypes = [dbl]
+    L.vt_set_kernel_events.restype = cint
+    L.vt_set_kernel_events.argtypes = [vp, vp]
     L.vt_strerror.restype = C.c_char_p
     L.vt_strerror.argtypes = [cint]
     _lib = L
@@ -164,6 +166,12 @@ def vt_gemm_f64_round_log(transA: bool, transB: bool, M: int, N: int, K: int, al
         _ptr(bias, torch.float64), int(batch), _ptr(C32, torch.float32), int(ldc), int(strideC),
         _ptr(C64_debug, torch.float64), int(variant), float(tau_ulp), C.byref(clog),
         _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "vt_gemm_f64_round_log")
+
+
+def vt_set_kernel_events(ev_begin, ev_end):
+    """ev_begin / ev_end: raw hipEvent_t handles (ints) or None to clear."""
+    _check(load_library().vt_set_kernel_events(C.c_void_p(ev_begin) if ev_begin else None,
+                                               C.c_void_p(ev_end) if ev_end else None), "vt_set_kernel_events")
 
 
 def vt_threshold_stats(y1: torch.Tensor, y2: torch.Tensor, out: torch.Tensor, stream=None):

@@ -6,6 +6,11 @@
 
 namespace {
 
+// Optional instrumentation (vt_set_kernel_events): events recorded around the main kernel.
+hipEvent_t g_ev_begin = nullptr, g_ev_end = nullptr;
+inline void mark_begin(hipStream_t s) { if (g_ev_begin) (void)hipEventRecord(g_ev_begin, s); }
+inline void mark_end(hipStream_t s) { if (g_ev_end) (void)hipEventRecord(g_ev_end, s); }
+
 inline bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? VT_OK : VT_ERR_HIP; }
@@ -71,7 +76,9 @@ int vt_round_log(const double *x, uint64_t n, double tau_ulp, float *y, const vt
     if (need && (!ws || ws_bytes < need || !aligned(ws, 256))) return VT_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)hip_stream;
     const vt::Planes pl = vt::planes_carve(ws, 1, n);
+    mark_begin(s);
     hipError_t e = vt::launch_round_planes(x, n, thr, y, pl, s);
+    mark_end(s);
     if (e != hipSuccess) return VT_ERR_HIP;
     return finish_log(pl, log, /*counted=*/true, s);
 }
@@ -83,7 +90,11 @@ int vt_round_replay(const double *x, uint64_t n, const uint32_t *idx, const uint
     if (n >= (1ull << 32) || count >= (1ull << 32)) return VT_ERR_INVALID_ARG;
     if (n && (!x || !y || !aligned(x, 8) || !aligned(y, 4))) return VT_ERR_INVALID_ARG;
     if (count && (!idx || !dir || !aligned(idx, 4) || !aligned(dir, 4))) return VT_ERR_INVALID_ARG;
-    return hip_status(vt::launch_replay(x, n, idx, dir, count, y, (hipStream_t)hip_stream));
+    hipStream_t s = (hipStream_t)hip_stream;
+    mark_begin(s);
+    const hipError_t e = vt::launch_replay(x, n, idx, dir, count, y, s);
+    mark_end(s);
+    return hip_status(e);
 }
 
 int vt_gemm_f64_round_log(int transA, int transB, int64_t M, int64_t N, int64_t K, double alpha,
@@ -122,7 +133,9 @@ int vt_gemm_f64_round_log(int transA, int transB, int64_t M, int64_t N, int64_t 
     g.A = A; g.lda = lda; g.strideA = strideA; g.B = B; g.ldb = ldb; g.strideB = strideB;
     g.bias = bias; g.batch = batch; g.C32 = C32; g.ldc = ldc; g.strideC = strideC;
     g.C64 = C64_debug; g.variant = variant; g.thr = thr;
+    mark_begin(s);
     hipError_t e = vt::launch_gemm_round_planes(g, pl, s);
+    mark_end(s);
     if (e != hipSuccess) return VT_ERR_HIP;
     return finish_log(pl, log, /*counted=*/false, s);
 }
@@ -132,6 +145,14 @@ int vt_threshold_stats(const double *y1, const double *y2, uint64_t n, uint64_t 
     if (!out || !aligned(out, 8)) return VT_ERR_INVALID_ARG;
     if (n && (!y1 || !y2 || !aligned(y1, 8) || !aligned(y2, 8))) return VT_ERR_INVALID_ARG;
     return hip_status(vt::launch_stats(y1, y2, n, out, (hipStream_t)hip_stream));
+}
+
+int vt_set_kernel_events(void *ev_begin, void *ev_end)
+{
+    if ((ev_begin == nullptr) != (ev_end == nullptr)) return VT_ERR_INVALID_ARG;
+    g_ev_begin = (hipEvent_t)ev_begin;
+    g_ev_end = (hipEvent_t)ev_end;
+    return VT_OK;
 }
 
 }  // extern "C"
