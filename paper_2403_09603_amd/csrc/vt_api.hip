@@ -60,7 +60,11 @@ size_t vt_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int64_t batch
     (void)K;
     if (M < 0 || N < 0 || batch < 0) return 0;
     switch (op) {
-    case VT_OP_ROUND_LOG: return vt::planes_bytes(1, (uint64_t)M * (uint64_t)N * (uint64_t)batch);
+    case VT_OP_ROUND_LOG: {
+        const uint64_t n = (uint64_t)M * (uint64_t)N * (uint64_t)batch;
+        const size_t a = vt::planes_bytes(1, n), b = vt::onepass_bytes(n);
+        return a > b ? a : b;
+    }
     case VT_OP_GEMM_ROUND_LOG: return vt::planes_bytes((uint64_t)M * (uint64_t)batch, (uint64_t)N);
     default: return 0;
     }
@@ -72,9 +76,16 @@ int vt_round_log(const double *x, uint64_t n, double tau_ulp, float *y, const vt
     const uint32_t thr = vt_thr_from_tau(tau_ulp);
     if (thr == 0xFFFFFFFFu || n >= (1ull << 32) || !log_ok(log)) return VT_ERR_INVALID_ARG;
     if (n && (!x || !y || !aligned(x, 8) || !aligned(y, 4))) return VT_ERR_INVALID_ARG;
-    const size_t need = vt::planes_bytes(1, n);
-    if (need && (!ws || ws_bytes < need || !aligned(ws, 256))) return VT_ERR_WORKSPACE;
+    const size_t need = vt_workspace_bytes(VT_OP_ROUND_LOG, 1, (int64_t)n, 0, 1);
+    if (!ws || ws_bytes < need || !aligned(ws, 256)) return VT_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)hip_stream;
+    if (vt::onepass_usable(x, y)) {         // one streaming pass; otherwise bit-planes + compaction
+        const vt::LogOut lo{log->idx, log->dir, log->cap, log->count};
+        mark_begin(s);
+        const hipError_t e1 = vt::launch_round_log_onepass(x, n, thr, y, ws, lo, s);
+        mark_end(s);
+        return hip_status(e1);
+    }
     const vt::Planes pl = vt::planes_carve(ws, 1, n);
     mark_begin(s);
     hipError_t e = vt::launch_round_planes(x, n, thr, y, pl, s);

@@ -80,6 +80,34 @@ static __host__ __device__ __forceinline__ Decision decide(uint64_t bits)
     return decide_slow(bits);
 }
 
+// Branch-free form of decide() for the streaming kernels, valid when `slow` comes back false,
+// i.e. for finite x with 2^-126 <= |x| < 2^128.  There the FP32 result is a normal number (or
+// overflows to infinity from the top binade), so the hardware conversion under the default
+// round-to-nearest-even mode gives rnd_32(x) without touching denormal handling; the dropped
+// bits still decide D and the direction: the magnitude grows iff r + (kept LSB) > 2^28.
+// Lanes with slow == true must be redone with decide() (NaN, Inf, zero, tiny, |x| >= 2^128).
+struct FastDecision {
+    float y;
+    uint32_t D;
+    bool grow;      // magnitude rounded up
+    bool neg;       // sign bit of x
+    bool slow;
+};
+
+__device__ __forceinline__ FastDecision decide_fast(double x)
+{
+    const uint64_t bits = (uint64_t)__double_as_longlong(x);
+    const uint32_t hi = (uint32_t)(bits >> 32), lo = (uint32_t)bits;
+    FastDecision o;
+    o.slow = ((hi & 0x7FFFFFFFu) - (897u << 20)) >= ((1151u - 897u) << 20);
+    const uint32_t r = lo & kMask29;
+    o.D = __usad(r, kHalf, 0u);                     // |r - 2^28|
+    o.grow = r + ((lo >> 29) & 1u) > kHalf;
+    o.neg = (int32_t)hi < 0;
+    o.y = (float)x;
+    return o;
+}
+
 // Replay of one logged element (primitive "rev"): the FP32 neighbour of x on the logged side,
 // i.e. x rounded toward +inf (dir = 1) or toward -inf (dir = 0).
 static __host__ __device__ __forceinline__ uint32_t directed_slow(uint64_t bits, uint32_t dir)
@@ -132,5 +160,32 @@ __device__ __forceinline__ uint32_t rank_below(uint64_t m)
 {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
 }
+
+__device__ __forceinline__ uint64_t ballot(bool p) { return __ballot(p); }
+
+__device__ __forceinline__ uint64_t readlane64(uint64_t v, uint32_t l)
+{
+    const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)v, (int)l);
+    const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), (int)l);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// LDS written by some lanes of a wave and read by others of the same wave: LDS operations of
+// one wave complete in issue order, so only the compiler has to be kept from reordering.
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+constexpr uint64_t kOneBits = 0x3FF0000000000000ull;   // 1.0: padding value, never logged
 
 }  // namespace vt

@@ -44,6 +44,12 @@ hipError_t launch_seg_scan(const Planes &pl, const LogOut &log, hipStream_t s);
 // ordered stream compaction: planes -> ascending idx[] + packed direction bits
 hipError_t launch_compact(const Planes &pl, const LogOut &log, hipStream_t s);
 
+// single-pass standalone trainer hook (chained scan); needs x 16-byte and y 8-byte aligned
+size_t onepass_bytes(uint64_t n);
+bool onepass_usable(const double *x, const float *y);
+hipError_t launch_round_log_onepass(const double *x, uint64_t n, uint32_t thr, float *y, void *ws,
+                                    const LogOut &log, hipStream_t s);
+
 hipError_t launch_replay(const double *x, uint64_t n, const uint32_t *idx, const uint32_t *dir,
                          uint64_t count, float *y, hipStream_t s);
 

@@ -10,33 +10,6 @@ namespace vt {
 
 namespace {
 
-constexpr uint64_t kOneBits = 0x3FF0000000000000ull;   // 1.0: padding value, never logged
-
-__device__ __forceinline__ uint64_t ballot(bool p) { return __ballot(p); }
-
-__device__ __forceinline__ uint64_t readlane64(uint64_t v, uint32_t l)
-{
-    const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)v, (int)l);
-    const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), (int)l);
-    return ((uint64_t)hi << 32) | lo;
-}
-
-__device__ __forceinline__ uint32_t wave_sum(uint32_t v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
-}
-
-// LDS written by some lanes of a wave and read by others of the same wave: LDS operations of
-// one wave complete in issue order, so only the compiler has to be kept from reordering.
-__device__ __forceinline__ void wave_lds_fence()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 // --------------------------------------------------------------------------------------------
 // round_planes: one wave per segment of 4096 outputs, one output per lane per step, so that a
 // wave ballot IS the 64-bit plane word.  Loads are issued eight deep.

@@ -1,0 +1,303 @@
+// vt_round_onepass.hip -- the standalone trainer hook as ONE streaming pass (gfx950, wave64).
+//
+// Each tile workgroup rounds 8192 FP64 values (16-byte loads, eight in flight per lane,
+// non-temporal both ways), decides which outputs are logged and compacts their entries in LDS.
+// The input is read once and nothing but the outputs is written, so the kernel moves exactly
+// the algorithmic bytes: 8 B + 4 B per element plus 4.125 B per logged entry.
+//
+// Position in the globally ordered log, without a second pass over the data: workgroup 0 is a
+// scanner.  A tile publishes its count in its status word and waits (one wave only; the other
+// seven retire at once) until the scanner has replaced it by the tile's offset.  The scanner
+// polls up to 1024 consecutive status words per round, takes the prefix of them that is
+// already published, scans it in LDS and writes the offsets back, so the log position of a
+// tile costs two memory round trips however many tiles are in flight, each status line has
+// one polling reader, and the scan advances by up to 1024 tiles per round trip.  (Measured
+// alternatives on 2^28 values, which stream in 0.50 ms: tile-to-tile decoupled look-back
+// 0.71 ms -- its frontier moves slower than HBM retires tiles; per-bucket atomic totals read
+// by every tile 2.7 ms -- polling of shared lines serialises at the memory side.)
+// Integer sums in a fixed order: the result does not depend on timing.
+//
+// Progress: the scanner is workgroup 0, dispatched first, and depends only on tiles publishing
+// their counts, which no tile waits for anything to do; tiles depend only on the scanner.
+// Every wait is bounded all the same: after kSpinLimit polls without progress the waiter sets
+// the error word and goes on, so the grid always drains; the host-visible result is then
+// *count = UINT64_MAX.
+#include "vt_device.h"
+#include "vt_kernels.h"
+
+namespace vt {
+
+namespace {
+
+typedef double d2 __attribute__((ext_vector_type(2)));
+typedef float f2 __attribute__((ext_vector_type(2)));
+
+constexpr int kThreads = 512;        // 8 waves
+constexpr int kWaves = kThreads / 64;
+constexpr int kWaveChunk = 1024;     // contiguous outputs per wave: 8 rows of 128
+constexpr int kRows = 8;
+constexpr int kTile = kWaves * kWaveChunk;   // outputs per workgroup
+constexpr int kScanThreads = 256, kScanPer = 4;      // scanner: 1024 status words per round
+constexpr uint32_t kSpinLimit = 1u << 18;
+
+constexpr uint64_t kCountFlag = 1ull << 62, kOffsetFlag = 2ull << 62, kValMask = (1ull << 62) - 1;
+
+__device__ __forceinline__ uint64_t st_load(const uint64_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_store(uint64_t *p, uint64_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__global__ __launch_bounds__(256) void onepass_init_kernel(uint64_t *__restrict__ st, uint32_t tiles,
+                                                           uint32_t *__restrict__ err, uint32_t *__restrict__ dir,
+                                                           uint64_t dir_words, uint64_t *__restrict__ count)
+{
+    const uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+    const uint64_t stride = (uint64_t)gridDim.x * 256u;
+    for (uint64_t k = i; k < tiles; k += stride) st[k] = 0;
+    for (uint64_t k = i; k < dir_words; k += stride) dir[k] = 0;
+    if (i == 0) { *err = 0; if (tiles == 0) *count = 0; }
+}
+
+// Workgroup 0: turns published counts into offsets, in tile order.
+__device__ __forceinline__ void scanner(uint64_t *__restrict__ st, uint32_t tiles, uint32_t *__restrict__ err,
+                                        uint64_t *__restrict__ count, uint32_t *s_u32)
+{
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wv = tid >> 6;
+    uint32_t *s_min = s_u32;          // [4] first unpublished position per wave
+    uint32_t *s_sum = s_u32 + 4;      // [4] count total per wave
+    uint64_t run = 0;
+    uint32_t base = 0, idle = 0;
+    bool force = false;
+    while (base < tiles) {
+        uint64_t v[kScanPer];
+        uint32_t first = kScanPer;                        // first unpublished among my four
+#pragma unroll
+        for (int j = kScanPer - 1; j >= 0; --j) {
+            const uint64_t t = (uint64_t)base + tid * kScanPer + j;
+            v[j] = t < tiles ? st_load(st + t) : kCountFlag;   // past the end: published, count 0
+            if (force && (v[j] >> 62) == 0) v[j] = kCountFlag;
+            if ((v[j] >> 62) == 0) first = j;
+        }
+        uint32_t pos = first < kScanPer ? tid * kScanPer + first : kScanThreads * kScanPer;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const uint32_t other = __shfl_xor(pos, o, 64);
+            pos = other < pos ? other : pos;
+        }
+        if (lane == 0) s_min[wv] = pos;
+        __syncthreads();
+        uint32_t R = s_min[0];
+#pragma unroll
+        for (int w = 1; w < kScanThreads / 64; ++w) R = s_min[w] < R ? s_min[w] : R;
+        if (R > tiles - base) R = tiles - base;
+        if (R == 0) {                                      // nothing new yet
+            __syncthreads();
+            if (++idle > kSpinLimit) {                     // never expected: stop waiting, drain
+                if (tid == 0) atomicOr(err, 1u);
+                force = true;
+            }
+            __builtin_amdgcn_s_sleep(2);
+            continue;
+        }
+        idle = 0;
+        // exclusive scan of the counts of tiles base .. base + R - 1
+        uint32_t c[kScanPer], mine = 0;
+#pragma unroll
+        for (int j = 0; j < kScanPer; ++j) {
+            c[j] = tid * kScanPer + j < R ? (uint32_t)(v[j] & kValMask) : 0u;
+            mine += c[j];
+        }
+        uint32_t incl = mine;                              // inclusive scan across the wave
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t up = __shfl_up(incl, o, 64);
+            if (lane >= (uint32_t)o) incl += up;
+        }
+        if (lane == 63) s_sum[wv] = incl;
+        __syncthreads();
+        uint32_t before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < kScanThreads / 64; ++w) {
+            if ((uint32_t)w < wv) before += s_sum[w];
+            total += s_sum[w];
+        }
+        uint64_t off = run + before + (incl - mine);
+#pragma unroll
+        for (int j = 0; j < kScanPer; ++j) {
+            const uint32_t q = tid * kScanPer + j;
+            if (q < R) st_store(st + base + q, kOffsetFlag | off);
+            off += c[j];
+        }
+        run += total;
+        base += R;
+        __syncthreads();                                   // s_min / s_sum are reused next round
+    }
+    if (tid == 0) *count = __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ? ~0ull : run;
+}
+
+// One wave's share of a tile: 1024 contiguous values as 8 rows of 128 (two per lane).  FULL:
+// the whole tile lies inside the array, so no access is guarded.  Returns the wave's count;
+// entries go to `ent` in element order.
+template <bool FULL>
+__device__ __forceinline__ uint32_t round_rows(const double *__restrict__ x, uint64_t n, uint32_t thr,
+                                               float *__restrict__ y, uint64_t wbase, uint32_t lane,
+                                               uint16_t *__restrict__ ent)
+{
+    d2 v[kRows];
+#pragma unroll
+    for (int u = 0; u < kRows; ++u) {
+        const uint64_t e = wbase + (uint64_t)u * 128u + 2u * lane;
+        if (FULL || e + 1 < n) v[u] = __builtin_nontemporal_load((const d2 *)(x + e));
+        else {
+            v[u].x = e < n ? x[e] : 1.0;                              // 1.0 is never logged
+            v[u].y = 1.0;
+        }
+    }
+    uint32_t wcount = 0;
+#pragma unroll
+    for (int u = 0; u < kRows; ++u) {
+        const uint64_t e = wbase + (uint64_t)u * 128u + 2u * lane;
+        const FastDecision a = decide_fast(v[u].x), b = decide_fast(v[u].y);
+        uint32_t ya = __float_as_uint(a.y), yb = __float_as_uint(b.y);
+        bool la = a.D < thr, lb = b.D < thr;
+        bool da = a.grow != a.neg, db = b.grow != b.neg;
+        if (__builtin_expect(ballot(a.slow || b.slow) != 0, 0)) {      // rare values: redo those lanes
+            if (a.slow) {
+                const Decision d = decide((uint64_t)__double_as_longlong(v[u].x));
+                ya = d.ybits; la = d.D < thr; da = d.dir != 0;
+            }
+            if (b.slow) {
+                const Decision d = decide((uint64_t)__double_as_longlong(v[u].y));
+                yb = d.ybits; lb = d.D < thr; db = d.dir != 0;
+            }
+        }
+        if (FULL || e + 1 < n) {
+            f2 o;
+            o.x = __uint_as_float(ya);
+            o.y = __uint_as_float(yb);
+            __builtin_nontemporal_store(o, (f2 *)(y + e));
+        } else if (e < n) {
+            y[e] = __uint_as_float(ya);
+        }
+        if (!FULL) { la = la && e < n; lb = lb && e + 1 < n; }
+        const uint64_t m0 = ballot(la), m1 = ballot(lb);
+        if (m0 | m1) {
+            const uint32_t r0 = wcount + rank_below(m0) + rank_below(m1);
+            const uint32_t pos = (uint32_t)u * 128u + 2u * lane;
+            if (la) ent[r0] = (uint16_t)(pos | (da ? 0x8000u : 0u));
+            if (lb) ent[r0 + (la ? 1u : 0u)] = (uint16_t)((pos + 1u) | (db ? 0x8000u : 0u));
+            wcount += popc64(m0) + popc64(m1);
+        }
+    }
+    return wcount;
+}
+
+__global__ __launch_bounds__(kThreads) void round_log_onepass_kernel(const double *__restrict__ x, uint64_t n,
+                                                                uint32_t thr, float *__restrict__ y,
+                                                                uint64_t *__restrict__ st, uint32_t tiles,
+                                                                uint32_t *__restrict__ err,
+                                                                uint32_t *__restrict__ idx, uint32_t *__restrict__ dir,
+                                                                uint64_t cap, uint64_t *__restrict__ count)
+{
+    __shared__ uint16_t ent[kWaves][kWaveChunk];  // per wave: position in its chunk | direction << 15
+    __shared__ uint32_t s_wc[kWaves];             // logged outputs per wave (scanner: scratch)
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wv = tid >> 6;
+    if (blockIdx.x == 0) {
+        if (tid < kScanThreads) scanner(st, tiles, err, count, s_wc);
+        return;
+    }
+    const uint32_t tile = blockIdx.x - 1;
+    const uint64_t wbase = (uint64_t)tile * kTile + (uint64_t)wv * kWaveChunk;
+    const uint32_t wcount = ((uint64_t)(tile + 1) * kTile <= n)
+                                ? round_rows<true>(x, n, thr, y, wbase, lane, ent[wv])
+                                : round_rows<false>(x, n, thr, y, wbase, lane, ent[wv]);
+    if (lane == 0) s_wc[wv] = wcount;
+    __syncthreads();
+    // Only wave 0 goes on: it alone waits for the tile's place in the log, so the other seven
+    // waves free their slots for the next tiles' loads meanwhile.
+    if (wv != 0) return;
+    uint32_t pre[kWaves + 1];                     // exclusive prefix of the waves' counts
+    pre[0] = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) pre[w + 1] = pre[w] + s_wc[w];
+    const uint32_t c = pre[kWaves];
+    if (lane == 0) st_store(st + tile, kCountFlag | c);
+    if (c == 0) return;                           // nothing to place: no need to wait
+    uint64_t sv = 0;
+    for (uint32_t spins = 0;; ++spins) {
+        __builtin_amdgcn_s_sleep(8);
+        sv = st_load(st + tile);
+        if ((sv >> 62) == 2) break;
+        if (spins > kSpinLimit) {                 // never expected: give up, do not hang
+            if (lane == 0) atomicOr(err, 1u);
+            sv = 0;
+            break;
+        }
+    }
+    const uint64_t off = sv & kValMask;
+    const uint64_t end = off + c < cap ? off + c : cap;
+    // entries leave in groups of 64 aligned in log position: contiguous index stores, and one
+    // ballot gives two whole direction words
+    for (uint64_t G = off & ~63ull; G < end; G += 64) {
+        const uint64_t p = G + lane;
+        const bool valid = p >= off && p < end;
+        uint32_t e = 0;
+        if (valid) {
+            const uint32_t q = (uint32_t)(p - off);
+            uint32_t chunk = 0, start = 0;
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w)
+                if (q >= pre[w]) { chunk = w; start = pre[w]; }
+            e = ent[chunk][q - start];
+            idx[p] = (uint32_t)((uint64_t)tile * kTile + chunk * kWaveChunk + (e & 0x3FFu));
+        }
+        const uint64_t dm = ballot(valid && (e >> 15));
+        const uint64_t vm = ballot(valid);
+        if (lane < 2) {
+            const uint32_t vh = lane ? (uint32_t)(vm >> 32) : (uint32_t)vm;
+            const uint32_t dh = lane ? (uint32_t)(dm >> 32) : (uint32_t)dm;
+            uint32_t *wp = dir + (G >> 5) + lane;
+            if (vh == 0xFFFFFFFFu) *wp = dh;
+            else if (vh && dh) atomicOr(wp, dh);
+        }
+    }
+}
+
+}  // namespace
+
+size_t onepass_bytes(uint64_t n)
+{
+    const uint64_t tiles = (n + kTile - 1) / kTile;
+    return (size_t)((tiles * 8 + 255) / 256 * 256 + 256);
+}
+
+bool onepass_usable(const double *x, const float *y)
+{
+    return ((uintptr_t)x % 16 == 0) && ((uintptr_t)y % 8 == 0);
+}
+
+hipError_t launch_round_log_onepass(const double *x, uint64_t n, uint32_t thr, float *y, void *ws,
+                                    const LogOut &log, hipStream_t s)
+{
+    const uint32_t tiles = (uint32_t)((n + kTile - 1) / kTile);
+    uint64_t *st = (uint64_t *)ws;
+    uint32_t *err = (uint32_t *)((char *)ws + ((uint64_t)tiles * 8 + 255) / 256 * 256);
+    const uint64_t stored = log.cap < n ? log.cap : n;
+    const uint64_t dir_words = (stored + 31) / 32;
+    const uint64_t work = tiles > dir_words ? tiles : dir_words;
+    uint32_t blocks = (uint32_t)((work + 1023) / 1024);
+    if (blocks < 1) blocks = 1;
+    if (blocks > 4096) blocks = 4096;
+    onepass_init_kernel<<<blocks, 256, 0, s>>>(st, tiles, err, log.dir, dir_words, log.count);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || tiles == 0) return e;
+    round_log_onepass_kernel<<<tiles + 1, kThreads, 0, s>>>(x, n, thr, y, st, tiles, err, log.idx, log.dir, log.cap,
+                                                            log.count);
+    return hipGetLastError();
+}
+
+}  // namespace vt

@@ -16,11 +16,20 @@ def u32(t):
     return t.cpu().numpy().view(np.uint32)
 
 
-def gpu_round_log(x, tau, cap=None):
+def gpu_round_log(x, tau, cap=None, misalign=False):
+    """misalign=True places x on an 8-byte (not 16-byte) boundary, which makes the library take
+    its bit-plane + compaction path instead of the single-pass kernel."""
     x = np.ascontiguousarray(x, np.float64).ravel()
     n = x.size
     cap = n if cap is None else cap
-    xd = dev(x) if n else torch.empty(0, dtype=torch.float64, device=DEV)
+    if misalign:
+        buf = torch.empty(n + 1, dtype=torch.float64, device=DEV)
+        xd = buf[1:]
+        if n:
+            xd.copy_(torch.from_numpy(x))
+        assert n == 0 or xd.data_ptr() % 16 == 8
+    else:
+        xd = dev(x) if n else torch.empty(0, dtype=torch.float64, device=DEV)
     y = torch.empty(n, dtype=torch.float32, device=DEV)
     log = vt.alloc_log(cap)
     ws = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_ROUND_LOG, 1, n))

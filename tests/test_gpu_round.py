@@ -36,17 +36,34 @@ def _same_log(g, o):
 TAUS = [0.0, 2.0 ** -40, 2.0 ** -24, 2.0 ** -4, 0.25, 0.5]
 
 
+# misalign=False: single-pass kernel; misalign=True: bit-plane + compaction path
+@pytest.mark.parametrize("misalign", [False, True])
 @pytest.mark.parametrize("tau", TAUS)
-def test_round_log_edge_values(G, tau):
+def test_round_log_edge_values(G, tau, misalign):
     x = si.edge_values()
-    _same_log(G.gpu_round_log(x, tau), vo.round_log(x, tau))
+    _same_log(G.gpu_round_log(x, tau, misalign=misalign), vo.round_log(x, tau))
 
 
-@pytest.mark.parametrize("n", [0, 1, 63, 64, 65, 4095, 4096, 4097, 3 * 4096 + 17, 16 * 4096, 100003])
-def test_round_log_ragged_sizes(G, n):
+@pytest.mark.parametrize("misalign", [False, True])
+@pytest.mark.parametrize("n", [0, 1, 2, 63, 64, 65, 127, 129, 1023, 1025, 4095, 4096, 4097, 3 * 4096 + 17,
+                               16 * 4096, 100003, 70 * 4096 + 5])
+def test_round_log_ragged_sizes(G, n, misalign):
     x, _ = si.planted_vector(n, si.seed_for(1, 4) + n, thr=32, planted_frac=0.2) if n else (np.zeros(0), None)
     for tau in (2.0 ** -24, 0.25):
-        _same_log(G.gpu_round_log(x, tau), vo.round_log(x, tau))
+        _same_log(G.gpu_round_log(x, tau, misalign=misalign), vo.round_log(x, tau))
+
+
+def test_round_log_paths_agree_on_many_tiles(G):
+    """600 tiles of 8192 (more than two buckets of 256 tiles) with very uneven density: a dense
+    planted stretch, a long run that logs nothing, then dense again."""
+    n = 600 * 8192 + 77
+    x, _ = si.planted_vector(n, si.seed_for(1, 6), thr=64, planted_frac=0.9)
+    x[40 * 8192:430 * 8192] = 1.5                      # FP32 values: never logged
+    tau = 64 * 2.0 ** -29
+    o = vo.round_log(x, tau)
+    for misalign in (False, True):
+        for _ in range(2):
+            _same_log(G.gpu_round_log(x, tau, misalign=misalign), o)
 
 
 @pytest.mark.parametrize("tau", [2.0 ** -30, 2.0 ** -4, 0.25])
@@ -69,8 +86,8 @@ def test_round_log_is_deterministic_and_cap_overflow(G):
     b = G.gpu_round_log(x, tau)
     assert a[3] == b[3] and all(np.array_equal(p, q) for p, q in zip(a[:3], b[:3]))
     full = vo.round_log(x, tau)
-    for cap in (0, 1, 31, 32, 33, 1000, full[3] - 1, full[3]):
-        g = G.gpu_round_log(x, tau, cap=cap)
+    for cap, misalign in [(c, m) for c in (0, 1, 31, 32, 33, 1000, full[3] - 1, full[3]) for m in (False, True)]:
+        g = G.gpu_round_log(x, tau, cap=cap, misalign=misalign)
         o = vo.round_log(x, tau, cap=cap)
         _same_log(g, o)
         assert g[3] == full[3] and len(g[1]) == min(cap, full[3])
