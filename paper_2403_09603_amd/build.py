@@ -12,7 +12,7 @@ SOURCES = ["vt_api.hip", "vt_round_kernels.hip", "vt_round_onepass.hip", "vt_gem
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option"]
+         "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option"] + os.environ.get("VT_EXTRA_FLAGS", "").split()
 
 
 def build_lib(verbose: bool = False) -> str:

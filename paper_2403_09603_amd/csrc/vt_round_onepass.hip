@@ -19,9 +19,9 @@
 //
 // Progress: the scanner is workgroup 0, dispatched first, and depends only on tiles publishing
 // their counts, which no tile waits for anything to do; tiles depend only on the scanner.
-// Every wait is bounded all the same: after kSpinLimit polls without progress the waiter sets
-// the error word and goes on, so the grid always drains; the host-visible result is then
-// *count = UINT64_MAX.
+// Every wait is bounded all the same: after kSpinLimit polls without progress (seconds) a
+// waiter sets the error word, which releases every other waiter too, so the grid always
+// drains; the host-visible result is then *count = UINT64_MAX.
 #include "vt_device.h"
 #include "vt_kernels.h"
 
@@ -38,7 +38,7 @@ constexpr int kWaveChunk = 1024;     // contiguous outputs per wave: 8 rows of 1
 constexpr int kRows = 8;
 constexpr int kTile = kWaves * kWaveChunk;   // outputs per workgroup
 constexpr int kScanThreads = 256, kScanPer = 4;      // scanner: 1024 status words per round
-constexpr uint32_t kSpinLimit = 1u << 18;
+constexpr uint32_t kSpinLimit = 1u << 21;   // polls (each a few microseconds) before a waiter gives up
 
 constexpr uint64_t kCountFlag = 1ull << 62, kOffsetFlag = 2ull << 62, kValMask = (1ull << 62) - 1;
 
@@ -70,7 +70,7 @@ __device__ __forceinline__ void scanner(uint64_t *__restrict__ st, uint32_t tile
     uint32_t *s_min = s_u32;          // [4] first unpublished position per wave
     uint32_t *s_sum = s_u32 + 4;      // [4] count total per wave
     uint64_t run = 0;
-    uint32_t base = 0, idle = 0;
+    uint32_t base = 0, idle = 0, rounds = 0, idle_rounds = 0;
     bool force = false;
     while (base < tiles) {
         uint64_t v[kScanPer];
@@ -94,7 +94,9 @@ __device__ __forceinline__ void scanner(uint64_t *__restrict__ st, uint32_t tile
 #pragma unroll
         for (int w = 1; w < kScanThreads / 64; ++w) R = s_min[w] < R ? s_min[w] : R;
         if (R > tiles - base) R = tiles - base;
+        ++rounds;
         if (R == 0) {                                      // nothing new yet
+            ++idle_rounds;
             __syncthreads();
             if (++idle > kSpinLimit) {                     // never expected: stop waiting, drain
                 if (tid == 0) atomicOr(err, 1u);
@@ -136,7 +138,11 @@ __device__ __forceinline__ void scanner(uint64_t *__restrict__ st, uint32_t tile
         base += R;
         __syncthreads();                                   // s_min / s_sum are reused next round
     }
-    if (tid == 0) *count = __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ? ~0ull : run;
+    if (tid == 0) {
+        *count = __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ? ~0ull : run;
+        err[1] = rounds;                                   // diagnostics: scan rounds, of which idle
+        err[2] = idle_rounds;
+    }
 }
 
 // One wave's share of a tile: 1024 contiguous values as 8 rows of 128 (two per lane).  FULL:
@@ -229,10 +235,13 @@ __global__ __launch_bounds__(kThreads) void round_log_onepass_kernel(const doubl
     if (c == 0) return;                           // nothing to place: no need to wait
     uint64_t sv = 0;
     for (uint32_t spins = 0;; ++spins) {
-        __builtin_amdgcn_s_sleep(8);
+        // polls are round trips to memory and compete with the stream: a scan round takes a
+        // few microseconds, so poll about that often (s_sleep 127 = 8128 cycles)
+        __builtin_amdgcn_s_sleep(127);
         sv = st_load(st + tile);
         if ((sv >> 62) == 2) break;
-        if (spins > kSpinLimit) {                 // never expected: give up, do not hang
+        const bool failed = __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
+        if (failed || spins > kSpinLimit) {       // never expected: give up, do not hang
             if (lane == 0) atomicOr(err, 1u);
             sv = 0;
             break;
@@ -253,7 +262,7 @@ __global__ __launch_bounds__(kThreads) void round_log_onepass_kernel(const doubl
             for (int w = 1; w < kWaves; ++w)
                 if (q >= pre[w]) { chunk = w; start = pre[w]; }
             e = ent[chunk][q - start];
-            idx[p] = (uint32_t)((uint64_t)tile * kTile + chunk * kWaveChunk + (e & 0x3FFu));
+            __builtin_nontemporal_store((uint32_t)((uint64_t)tile * kTile + chunk * kWaveChunk + (e & 0x3FFu)), idx + p);
         }
         const uint64_t dm = ballot(valid && (e >> 15));
         const uint64_t vm = ballot(valid);
