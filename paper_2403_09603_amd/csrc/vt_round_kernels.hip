@@ -167,8 +167,10 @@ __global__ __launch_bounds__(256) void compact_kernel(const uint64_t *__restrict
 }
 
 // --------------------------------------------------------------------------------------------
-// replay: one block per 4096 outputs.  The block's slice of the sorted log is found with two
-// 64-ary searches (one wave each), scattered into LDS bit arrays, then the outputs are streamed.
+// replay: one workgroup per 4096 outputs, each wave a contiguous 1024 (16-byte loads, eight in
+// flight).  The first log entry of the tile is found with one 64-ary search of the sorted index
+// list; the tile's entries are then read in order and dropped into a byte array in LDS (index
+// values are distinct, so plain stores suffice), from which every output picks its own flag.
 // --------------------------------------------------------------------------------------------
 __device__ __forceinline__ uint64_t wave_lower_bound(const uint32_t *__restrict__ idx, uint64_t count,
                                                      uint64_t target, uint32_t lane)
@@ -187,50 +189,93 @@ __device__ __forceinline__ uint64_t wave_lower_bound(const uint32_t *__restrict_
     return a;
 }
 
-constexpr int kReplayTile = 4096;
-constexpr int kReplayPer = kReplayTile / 256;
+typedef double d2 __attribute__((ext_vector_type(2)));
+typedef float f2 __attribute__((ext_vector_type(2)));
 
-__global__ __launch_bounds__(256) void replay_kernel(const uint64_t *__restrict__ x, uint64_t n,
+constexpr int kReplayTile = 4096;
+constexpr int kReplayChunk = 1024;       // per wave: 8 rows of 128
+constexpr int kReplayRows = 8;
+
+template <bool FULL, bool VEC>
+__device__ __forceinline__ void replay_load(const double *__restrict__ x, uint64_t n, uint64_t wbase, uint32_t lane,
+                                            d2 (&v)[kReplayRows])
+{
+#pragma unroll
+    for (int u = 0; u < kReplayRows; ++u) {
+        const uint64_t e = wbase + (uint64_t)u * 128u + 2u * lane;
+        if (VEC && (FULL || e + 1 < n)) v[u] = __builtin_nontemporal_load((const d2 *)(x + e));
+        else {
+            v[u].x = e < n ? x[e] : 1.0;
+            v[u].y = e + 1 < n ? x[e + 1] : 1.0;
+        }
+    }
+}
+
+template <bool FULL, bool VEC>
+__device__ __forceinline__ void replay_store(const d2 (&v)[kReplayRows], const uint8_t *__restrict__ flags,
+                                             uint32_t wv, float *__restrict__ y, uint64_t n, uint64_t wbase,
+                                             uint32_t lane)
+{
+#pragma unroll
+    for (int u = 0; u < kReplayRows; ++u) {
+        const uint32_t pos = wv * kReplayChunk + (uint32_t)u * 128u + 2u * lane;
+        const uint64_t e = wbase + (uint64_t)u * 128u + 2u * lane;
+        const uint32_t f = *(const uint16_t *)(flags + pos);          // flags of both outputs
+        const FastDecision a = decide_fast(v[u].x), b = decide_fast(v[u].y);
+        uint32_t ya = __float_as_uint(a.y), yb = __float_as_uint(b.y);
+        if (__builtin_expect(ballot(a.slow || b.slow || f != 0) != 0, 0)) {
+            const uint64_t xa = (uint64_t)__double_as_longlong(v[u].x), xb = (uint64_t)__double_as_longlong(v[u].y);
+            if (f & 1u) ya = directed(xa, (f >> 1) & 1u);
+            else if (a.slow) ya = decide(xa).ybits;
+            if (f & 0x100u) yb = directed(xb, (f >> 9) & 1u);
+            else if (b.slow) yb = decide(xb).ybits;
+        }
+        if (VEC && (FULL || e + 1 < n)) {
+            f2 o;
+            o.x = __uint_as_float(ya);
+            o.y = __uint_as_float(yb);
+            __builtin_nontemporal_store(o, (f2 *)(y + e));
+        } else {
+            if (e < n) y[e] = __uint_as_float(ya);
+            if (e + 1 < n) y[e + 1] = __uint_as_float(yb);
+        }
+    }
+}
+
+template <bool VEC>
+__global__ __launch_bounds__(256) void replay_kernel(const double *__restrict__ x, uint64_t n,
                                                      const uint32_t *__restrict__ idx,
                                                      const uint32_t *__restrict__ dir, uint64_t count,
-                                                     uint32_t *__restrict__ y)
+                                                     float *__restrict__ y)
 {
-    __shared__ uint32_t s_lg[kReplayTile / 32], s_dr[kReplayTile / 32];
-    __shared__ uint64_t s_range[2];
+    __shared__ __attribute__((aligned(16))) uint8_t flags[kReplayTile];   // bit 0: logged, bit 1: direction
+    __shared__ uint64_t s_lo;
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wv = tid >> 6;
     const uint64_t start = (uint64_t)blockIdx.x * kReplayTile;
     const uint64_t stop = start + kReplayTile < n ? start + kReplayTile : n;
-    uint64_t v[kReplayPer];
-#pragma unroll
-    for (int u = 0; u < kReplayPer; ++u) {
-        const uint64_t e = start + (uint64_t)u * 256u + tid;
-        v[u] = e < stop ? __builtin_nontemporal_load(x + e) : kOneBits;
-    }
-    if (tid < kReplayTile / 32) { s_lg[tid] = 0; s_dr[tid] = 0; }
-    if (wv < 2) {
-        const uint64_t r = wave_lower_bound(idx, count, wv ? stop : start, lane);
-        if (lane == 0) s_range[wv] = r;
-    }
-    __syncthreads();
-    const uint64_t lo = s_range[0], hi = s_range[1];
-    for (uint64_t p = lo + tid; p < hi; p += 256) {
-        const uint64_t i = idx[p];
-        if (i >= start && i < stop) {
-            const uint32_t o = (uint32_t)(i - start);
-            atomicOr(&s_lg[o >> 5], 1u << (o & 31u));
-            if ((dir[p >> 5] >> (p & 31u)) & 1u) atomicOr(&s_dr[o >> 5], 1u << (o & 31u));
-        }
+    const uint64_t wbase = start + (uint64_t)wv * kReplayChunk;
+    const bool full = start + kReplayTile <= n;
+    d2 v[kReplayRows];
+    if (full) replay_load<true, VEC>(x, n, wbase, lane, v);
+    else replay_load<false, VEC>(x, n, wbase, lane, v);
+    ((uint4 *)flags)[tid] = make_uint4(0, 0, 0, 0);
+    if (wv == 0) {
+        const uint64_t r = wave_lower_bound(idx, count, start, lane);
+        if (lane == 0) s_lo = r;
     }
     __syncthreads();
-#pragma unroll
-    for (int u = 0; u < kReplayPer; ++u) {
-        const uint32_t o = (uint32_t)u * 256u + tid;
-        const uint64_t e = start + o;
-        const uint32_t lg = (s_lg[o >> 5] >> (o & 31u)) & 1u;
-        const uint32_t dr = (s_dr[o >> 5] >> (o & 31u)) & 1u;
-        const uint32_t yb = lg ? directed(v[u], dr) : decide(v[u]).ybits;
-        if (e < stop) __builtin_nontemporal_store(yb, y + e);
+    const uint64_t lo = s_lo;
+    // at most 4096 entries belong to the tile: 64 rounds of 64, plus one for a ragged start
+    for (uint32_t r = wv; r <= kReplayTile / 64; r += 4) {
+        const uint64_t p = lo + (uint64_t)r * 64u + lane;
+        const uint64_t i = p < count ? (uint64_t)idx[p] : ~0ull;
+        if (i >= start && i < stop)
+            flags[i - start] = (uint8_t)(1u | (((dir[p >> 5] >> (p & 31u)) & 1u) << 1));
+        if (ballot(i < stop) == 0) break;                    // sorted list: nothing further belongs here
     }
+    __syncthreads();
+    if (full) replay_store<true, VEC>(v, flags, wv, y, n, wbase, lane);
+    else replay_store<false, VEC>(v, flags, wv, y, n, wbase, lane);
 }
 
 // --------------------------------------------------------------------------------------------
@@ -243,53 +288,85 @@ __global__ void fill_u64_kernel(uint64_t *p, uint32_t nwords, uint64_t v)
     if (i < nwords) p[i] = v;
 }
 
-__global__ __launch_bounds__(256) void stats_kernel(const uint64_t *__restrict__ y1, const uint64_t *__restrict__ y2,
+// Persistent grid (few workgroups, so few global atomics at the end), 16-byte loads, eight in
+// flight per lane.  The histogram lives in LDS in 16 copies selected by lane, which keeps
+// same-address collisions of the LDS atomics short; identical pairs (bin 0) are only counted.
+constexpr int kStatsU = 4;                      // 16-byte loads per array, lane and iteration
+constexpr int kStatsTile = 256 * 2 * kStatsU;   // elements per workgroup and iteration
+
+struct StatsAcc {
+    uint32_t flips, thrmax, equal;
+    uint64_t dmax;
+};
+
+__device__ __forceinline__ void stats_one(uint64_t a, uint64_t b, double xa, double xb, bool valid, uint32_t copy,
+                                          uint32_t (*hist)[66], StatsAcc &acc)
+{
+    if (!valid) return;
+    if (a == b) { ++acc.equal; return; }
+    const int64_t oa = ord64(a), ob = ord64(b);
+    const uint64_t diff = oa > ob ? (uint64_t)oa - (uint64_t)ob : (uint64_t)ob - (uint64_t)oa;
+    if (diff == 0) ++acc.equal;                                   // +0 / -0
+    else {
+        atomicAdd(&hist[copy][64u - (uint32_t)__clzll((long long)diff)], 1u);
+        acc.dmax = diff > acc.dmax ? diff : acc.dmax;
+    }
+    const FastDecision fa = decide_fast(xa), fb = decide_fast(xb);
+    uint32_t ya = __float_as_uint(fa.y), yb = __float_as_uint(fb.y), Da = fa.D, Db = fb.D;
+    if (fa.slow) { const Decision d = decide(a); ya = d.ybits; Da = d.D; }
+    if (fb.slow) { const Decision d = decide(b); yb = d.ybits; Db = d.D; }
+    if (ya != yb) {
+        ++acc.flips;
+        const uint32_t need = 1u + (Da > Db ? Da : Db);
+        acc.thrmax = need > acc.thrmax ? need : acc.thrmax;
+    }
+}
+
+template <bool VEC>
+__global__ __launch_bounds__(256) void stats_kernel(const double *__restrict__ y1, const double *__restrict__ y2,
                                                     uint64_t n, uint64_t *__restrict__ out)
 {
-    __shared__ uint32_t s_hist[65];
-    __shared__ unsigned long long s_flip, s_thr, s_max;
-    const uint32_t tid = threadIdx.x, lane = tid & 63u;
-    if (tid < 65) s_hist[tid] = 0;
-    if (tid == 0) { s_flip = 0; s_thr = 0; s_max = 0; }
+    __shared__ uint32_t hist[16][66];
+    __shared__ unsigned long long s_flip, s_thr, s_max, s_eq;
+    const uint32_t tid = threadIdx.x, copy = tid & 15u;
+    for (uint32_t k = tid; k < 16 * 66; k += 256) (&hist[0][0])[k] = 0;
+    if (tid == 0) { s_flip = 0; s_thr = 0; s_max = 0; s_eq = 0; }
     __syncthreads();
-    uint32_t flips = 0, thrmax = 0;
-    uint64_t dmax = 0;
-    const uint64_t stride = (uint64_t)gridDim.x * 256u;
-    const uint64_t rounds = (n + stride - 1) / stride;      // uniform trip count: ballots need whole waves
-    for (uint64_t rd = 0; rd < rounds; ++rd) {
-        const uint64_t i = rd * stride + (uint64_t)blockIdx.x * 256u + tid;
-        const bool in = i < n;
-        const uint64_t a = in ? __builtin_nontemporal_load(y1 + i) : 0;
-        const uint64_t b = in ? __builtin_nontemporal_load(y2 + i) : 0;
-        const int64_t oa = ord64(a), ob = ord64(b);
-        const uint64_t diff = oa > ob ? (uint64_t)oa - (uint64_t)ob : (uint64_t)ob - (uint64_t)oa;
-        uint32_t bin = diff ? 64u - (uint32_t)__clzll((long long)diff) : 0u;
-        if (in) {
-            dmax = diff > dmax ? diff : dmax;
-            if (a != b) {                                   // identical patterns cannot flip (+0 / -0 can)
-                const Decision da = decide(a), db = decide(b);
-                if (da.ybits != db.ybits) {
-                    ++flips;
-                    const uint32_t need = 1u + (da.D > db.D ? da.D : db.D);
-                    thrmax = need > thrmax ? need : thrmax;
-                }
+    StatsAcc acc = {0, 0, 0, 0};
+    for (uint64_t base = (uint64_t)blockIdx.x * kStatsTile; base < n; base += (uint64_t)gridDim.x * kStatsTile) {
+        d2 a[kStatsU], b[kStatsU];
+        const bool full = base + kStatsTile <= n;
+#pragma unroll
+        for (int u = 0; u < kStatsU; ++u) {
+            const uint64_t e = base + (uint64_t)u * 512u + 2u * tid;
+            if (VEC && (full || e + 1 < n)) {
+                a[u] = __builtin_nontemporal_load((const d2 *)(y1 + e));
+                b[u] = __builtin_nontemporal_load((const d2 *)(y2 + e));
+            } else {
+                a[u].x = e < n ? y1[e] : 0.0;      a[u].y = e + 1 < n ? y1[e + 1] : 0.0;
+                b[u].x = e < n ? y2[e] : 0.0;      b[u].y = e + 1 < n ? y2[e + 1] : 0.0;
             }
         }
-        // histogram: one LDS atomic per distinct bin per wave
-        uint64_t todo = ballot(in);
-        while (todo) {
-            const uint32_t leader = (uint32_t)__builtin_ctzll(todo);
-            const uint32_t lb = (uint32_t)__builtin_amdgcn_readlane((int)bin, (int)leader);
-            const uint64_t same = ballot(in && bin == lb) & todo;
-            if (lane == leader) atomicAdd(&s_hist[lb], popc64(same));
-            todo &= ~same;
+#pragma unroll
+        for (int u = 0; u < kStatsU; ++u) {
+            const uint64_t e = base + (uint64_t)u * 512u + 2u * tid;
+            stats_one((uint64_t)__double_as_longlong(a[u].x), (uint64_t)__double_as_longlong(b[u].x), a[u].x, b[u].x,
+                      full || e < n, copy, hist, acc);
+            stats_one((uint64_t)__double_as_longlong(a[u].y), (uint64_t)__double_as_longlong(b[u].y), a[u].y, b[u].y,
+                      full || e + 1 < n, copy, hist, acc);
         }
     }
-    atomicAdd(&s_flip, (unsigned long long)flips);
-    atomicMax(&s_thr, (unsigned long long)thrmax);
-    atomicMax(&s_max, (unsigned long long)dmax);
+    atomicAdd(&s_flip, (unsigned long long)acc.flips);
+    atomicAdd(&s_eq, (unsigned long long)acc.equal);
+    atomicMax(&s_thr, (unsigned long long)acc.thrmax);
+    atomicMax(&s_max, (unsigned long long)acc.dmax);
     __syncthreads();
-    if (tid < 65 && s_hist[tid]) atomicAdd((unsigned long long *)&out[3 + tid], (unsigned long long)s_hist[tid]);
+    if (tid < 65) {
+        unsigned long long h = tid == 0 ? s_eq : 0ull;
+#pragma unroll
+        for (int c = 0; c < 16; ++c) h += hist[c][tid];
+        if (h) atomicAdd((unsigned long long *)&out[3 + tid], h);
+    }
     if (tid == 0) {
         if (s_flip) atomicAdd((unsigned long long *)&out[0], s_flip);
         if (s_thr) atomicMax((unsigned long long *)&out[1], s_thr);
@@ -363,7 +440,10 @@ hipError_t launch_replay(const double *x, uint64_t n, const uint32_t *idx, const
 {
     if (n == 0) return hipSuccess;
     const uint64_t blocks = (n + kReplayTile - 1) / kReplayTile;
-    replay_kernel<<<(uint32_t)blocks, 256, 0, s>>>((const uint64_t *)x, n, idx, dir, count, (uint32_t *)y);
+    if (((uintptr_t)x % 16 == 0) && ((uintptr_t)y % 8 == 0))
+        replay_kernel<true><<<(uint32_t)blocks, 256, 0, s>>>(x, n, idx, dir, count, y);
+    else
+        replay_kernel<false><<<(uint32_t)blocks, 256, 0, s>>>(x, n, idx, dir, count, y);
     return hipGetLastError();
 }
 
@@ -372,9 +452,12 @@ hipError_t launch_stats(const double *y1, const double *y2, uint64_t n, uint64_t
     fill_u64_kernel<<<1, 128, 0, s>>>(out, 68, 0);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || n == 0) return e;
-    uint64_t blocks = (n + 256 * 8 - 1) / (256 * 8);
-    if (blocks > 16384) blocks = 16384;
-    stats_kernel<<<(uint32_t)blocks, 256, 0, s>>>((const uint64_t *)y1, (const uint64_t *)y2, n, out);
+    uint64_t blocks = (n + kStatsTile - 1) / kStatsTile;
+    if (blocks > 2048) blocks = 2048;                       // 8 workgroups per CU
+    if (((uintptr_t)y1 % 16 == 0) && ((uintptr_t)y2 % 16 == 0))
+        stats_kernel<true><<<(uint32_t)blocks, 256, 0, s>>>(y1, y2, n, out);
+    else
+        stats_kernel<false><<<(uint32_t)blocks, 256, 0, s>>>(y1, y2, n, out);
     return hipGetLastError();
 }
 

@@ -40,10 +40,15 @@ def gpu_round_log(x, tau, cap=None, misalign=False):
     return (y.cpu().numpy(), u32(log.idx)[:k].copy(), u32(log.dir)[:(k + 31) // 32].copy(), count)
 
 
-def gpu_round_replay(x, idx, dirw, count=None):
+def gpu_round_replay(x, idx, dirw, count=None, misalign=False):
     x = np.ascontiguousarray(x, np.float64).ravel()
     count = len(idx) if count is None else count
-    xd = dev(x)
+    if misalign:
+        buf = torch.empty(x.size + 1, dtype=torch.float64, device=DEV)
+        xd = buf[1:]
+        xd.copy_(torch.from_numpy(x))
+    else:
+        xd = dev(x)
     y = torch.empty(x.size, dtype=torch.float32, device=DEV)
     idx_d = dev(np.ascontiguousarray(idx, np.uint32).view(np.int32)) if len(idx) else torch.zeros(1, dtype=torch.int32, device=DEV)
     dir_d = dev(np.ascontiguousarray(dirw, np.uint32).view(np.int32)) if len(dirw) else torch.zeros(1, dtype=torch.int32, device=DEV)

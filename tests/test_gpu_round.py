@@ -101,6 +101,7 @@ def test_replay_matches_oracle_and_trainer(G, thr, tau):
     yT, idx, dirw, count = G.gpu_round_log(x, tau)
     yA = G.gpu_round_replay(xa, idx, dirw)
     assert np.array_equal(_bits(yA), _bits(vo.round_replay(xa, idx, dirw)))   # GPU replay == oracle replay
+    assert np.array_equal(_bits(G.gpu_round_replay(xa, idx, dirw, misalign=True)), _bits(yA))
     assert np.array_equal(_bits(yA), _bits(yT))                                # auditor == trainer: 0 mismatches
     # CPU auditor replaying the GPU trainer's log
     assert np.array_equal(_bits(vo.round_replay(xa, idx, dirw)), _bits(yT))
@@ -112,7 +113,9 @@ def test_replay_edge_values_all_logged_and_empty(G):
     idx = np.arange(n, dtype=np.uint32)
     for word in (0, 0xFFFFFFFF, 0xA5A5A5A5):
         dirw = np.full((n + 31) // 32, word, np.uint32)
-        assert np.array_equal(_bits(G.gpu_round_replay(x, idx, dirw)), _bits(vo.round_replay(x, idx, dirw)))
+        want = _bits(vo.round_replay(x, idx, dirw))
+        assert np.array_equal(_bits(G.gpu_round_replay(x, idx, dirw)), want)
+        assert np.array_equal(_bits(G.gpu_round_replay(x, idx, dirw, misalign=True)), want)
     empty = G.gpu_round_replay(x, idx[:0], np.zeros(0, np.uint32), count=0)
     assert np.array_equal(_bits(empty), _bits(vo.round_replay(x, idx[:0], np.zeros(1, np.uint32), count=0)))
     # sparse log with entries at tile borders and stray indices >= n (ignored)
