@@ -68,6 +68,20 @@ __device__ __forceinline__ void load_tile(const double *__restrict__ base, int64
     }
 }
 
+// Same tile when it lies wholly inside the operand and 16-byte loads are legal: eight straight
+// vector loads, no guards.
+template <bool KC>
+__device__ __forceinline__ void load_tile_fast(const double *__restrict__ base, int64_t ld, int64_t mn0, int64_t k0,
+                                               d2 (&regs)[4])
+{
+    const int t = threadIdx.x;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (KC) regs[j] = *(const d2 *)(base + (mn0 + (t >> 3) + 32 * j) * ld + k0 + (t & 7) * 2);
+        else    regs[j] = *(const d2 *)(base + (k0 + (t >> 6) + 4 * j) * ld + mn0 + (t & 63) * 2);
+    }
+}
+
 template <bool KC>
 __device__ __forceinline__ void store_tile(double *__restrict__ S, const d2 (&regs)[4])
 {
@@ -120,11 +134,18 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
         for (int j = 0; j < 4; ++j) acc[i][j] = (d4){0.0, 0.0, 0.0, 0.0};
 
     const int nkt = (int)((p.K + BK - 1) / BK);
+    // whole-tile operands take the unguarded loader (a uniform choice per k step)
+    const bool fastA = p.vecA && bm + BM <= p.M, fastB = p.vecB && bn + BN <= p.N;
     d2 ra[4], rb[4];
+    auto fetch = [&](int64_t k0) {
+        const bool kfull = k0 + BK <= p.K;
+        if (fastA && kfull) load_tile_fast<KCA>(A, p.lda, bm, k0, ra);
+        else load_tile<KCA>(A, p.lda, bm, k0, p.M, p.K, p.vecA, ra);
+        if (fastB && kfull) load_tile_fast<KCB>(B, p.ldb, bn, k0, rb);
+        else load_tile<KCB>(B, p.ldb, bn, k0, p.N, p.K, p.vecB, rb);
+    };
     if (nkt > 0) {
-        const int64_t k0 = (int64_t)(p.variant ? nkt - 1 : 0) * BK;
-        load_tile<KCA>(A, p.lda, bm, k0, p.M, p.K, p.vecA, ra);
-        load_tile<KCB>(B, p.ldb, bn, k0, p.N, p.K, p.vecB, rb);
+        fetch((int64_t)(p.variant ? nkt - 1 : 0) * BK);
         store_tile<KCA>(lds, ra);
         store_tile<KCB>(lds + 2 * kTileDoubles, rb);
     }
@@ -132,11 +153,7 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
     int cur = 0;
     for (int it = 0; it < nkt; ++it) {
         const bool more = it + 1 < nkt;
-        if (more) {
-            const int64_t k0 = (int64_t)(p.variant ? nkt - 2 - it : it + 1) * BK;
-            load_tile<KCA>(A, p.lda, bm, k0, p.M, p.K, p.vecA, ra);
-            load_tile<KCB>(B, p.ldb, bn, k0, p.N, p.K, p.vecB, rb);
-        }
+        if (more) fetch((int64_t)(p.variant ? nkt - 2 - it : it + 1) * BK);
         const double *As = lds + cur * kTileDoubles + wm * 64 + (lane & 15);
         const double *Bs = lds + (2 + cur) * kTileDoubles + wn * 64 + (lane & 15);
 #pragma unroll
@@ -184,13 +201,21 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
                 const bool in = row < p.M && col < p.N;
                 double c = p.alpha * acc[i][j][r];
                 if (p.bias) c = c + bias_v[j];
-                const Decision d = decide((uint64_t)__double_as_longlong(c));
+                const FastDecision f = decide_fast(c);
+                uint32_t yb = __float_as_uint(f.y);
+                bool logged = f.D < p.thr, up = f.grow != f.neg;
+                if (__builtin_expect(__ballot(f.slow) != 0, 0)) {     // NaN, Inf, zero, tiny or huge values
+                    if (f.slow) {
+                        const Decision d = decide((uint64_t)__double_as_longlong(c));
+                        yb = d.ybits; logged = d.D < p.thr; up = d.dir != 0;
+                    }
+                }
                 if (in) {
-                    C32[row * p.ldc + col] = __uint_as_float(d.ybits);
+                    C32[row * p.ldc + col] = __uint_as_float(yb);
                     if (C64) C64[row * p.N + col] = c;
                 }
-                const uint64_t lg = __ballot(in && d.D < p.thr);
-                const uint64_t dr = __ballot(d.dir != 0) & lg;
+                const uint64_t lg = __ballot(in && logged);
+                const uint64_t dr = __ballot(up) & lg;
                 lgw |= ((lg >> (16 * g)) & 0xFFFFull) << (16 * j);
                 drw |= ((dr >> (16 * g)) & 0xFFFFull) << (16 * j);
             }
