@@ -63,7 +63,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-stream", action="store_true", help="skip the 2^28-element standalone sweep")
-    ap.add_argument("--cpu-rows", type=int, default=384, help="rows of X the CPU oracle is timed on")
+    ap.add_argument("--cpu-rows", type=int, default=1024, help="rows of X the CPU oracle is timed on")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain elementwise kernel over 1 GiB in / 1 GiB out (torch.neg), so that "
+                         "HBM byte counters can be scaled against a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -81,6 +84,14 @@ def main():
     torch.cuda.set_device(0)
     lib = vt.load_library()
     ev = HipEvents(lib)
+
+    if args.calib_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.neg(src, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---------------------------------------------------------------- workload (config 2)
     M, K, N = 8192, 768, 3072

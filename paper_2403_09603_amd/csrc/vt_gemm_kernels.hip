@@ -68,18 +68,22 @@ __device__ __forceinline__ void load_tile(const double *__restrict__ base, int64
     }
 }
 
-// Same tile when it lies wholly inside the operand and 16-byte loads are legal: eight straight
-// vector loads, no guards.
+// Same tile when it lies wholly inside the operand and 16-byte loads are legal: four straight
+// vector loads from a per-thread pointer to the tile's k = 0 position, no guards.
 template <bool KC>
-__device__ __forceinline__ void load_tile_fast(const double *__restrict__ base, int64_t ld, int64_t mn0, int64_t k0,
-                                               d2 (&regs)[4])
+__device__ __forceinline__ const double *tile_origin(const double *__restrict__ base, int64_t ld, int64_t mn0)
 {
     const int t = threadIdx.x;
+    return KC ? base + (mn0 + (t >> 3)) * ld + (t & 7) * 2 : base + (int64_t)(t >> 6) * ld + mn0 + (t & 63) * 2;
+}
+
+template <bool KC>
+__device__ __forceinline__ void load_tile_fast(const double *__restrict__ origin, int64_t ld, int64_t k0, d2 (&regs)[4])
+{
+    const double *p = KC ? origin + k0 : origin + k0 * ld;
+    const int64_t step = KC ? 32 * ld : 4 * ld;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        if (KC) regs[j] = *(const d2 *)(base + (mn0 + (t >> 3) + 32 * j) * ld + k0 + (t & 7) * 2);
-        else    regs[j] = *(const d2 *)(base + (k0 + (t >> 6) + 4 * j) * ld + mn0 + (t & 63) * 2);
-    }
+    for (int j = 0; j < 4; ++j) regs[j] = *(const d2 *)(p + j * step);
 }
 
 template <bool KC>
@@ -136,12 +140,13 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
     const int nkt = (int)((p.K + BK - 1) / BK);
     // whole-tile operands take the unguarded loader (a uniform choice per k step)
     const bool fastA = p.vecA && bm + BM <= p.M, fastB = p.vecB && bn + BN <= p.N;
+    const double *oa = tile_origin<KCA>(A, p.lda, bm), *ob = tile_origin<KCB>(B, p.ldb, bn);
     d2 ra[4], rb[4];
     auto fetch = [&](int64_t k0) {
         const bool kfull = k0 + BK <= p.K;
-        if (fastA && kfull) load_tile_fast<KCA>(A, p.lda, bm, k0, ra);
+        if (fastA && kfull) load_tile_fast<KCA>(oa, p.lda, k0, ra);
         else load_tile<KCA>(A, p.lda, bm, k0, p.M, p.K, p.vecA, ra);
-        if (fastB && kfull) load_tile_fast<KCB>(B, p.ldb, bn, k0, rb);
+        if (fastB && kfull) load_tile_fast<KCB>(ob, p.ldb, k0, rb);
         else load_tile<KCB>(B, p.ldb, bn, k0, p.N, p.K, p.vecB, rb);
     };
     if (nkt > 0) {
@@ -156,21 +161,28 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
         if (more) fetch((int64_t)(p.variant ? nkt - 2 - it : it + 1) * BK);
         const double *As = lds + cur * kTileDoubles + wm * 64 + (lane & 15);
         const double *Bs = lds + (2 + cur) * kTileDoubles + wn * 64 + (lane & 15);
+        double a[4], bb[4];
 #pragma unroll
         for (int kk = 0; kk < BK / 4; ++kk) {
             const int krow = (kk * 4 + (lane >> 4)) * LDS_S;
-            double a[4], bb[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) { a[i] = As[krow + i * 16]; bb[i] = Bs[krow + i * 16]; }
+            if (kk == BK / 4 - 1) {
+                // The next tile goes to the other LDS buffer in the shadow of the last 16 MFMAs
+                // of this one (its fragments are already requested: LDS completes in order), so
+                // a wave's MFMA stream has no gap before the barrier.
+                __builtin_amdgcn_sched_barrier(0);
+                if (more) {
+                    store_tile<KCA>(lds + (cur ^ 1) * kTileDoubles, ra);
+                    store_tile<KCB>(lds + (2 + (cur ^ 1)) * kTileDoubles, rb);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], bb[j], acc[i][j], 0, 0, 0);
-        }
-        if (more) {
-            store_tile<KCA>(lds + (cur ^ 1) * kTileDoubles, ra);
-            store_tile<KCB>(lds + (2 + (cur ^ 1)) * kTileDoubles, rb);
         }
         __syncthreads();
         cur ^= 1;
