@@ -115,9 +115,9 @@ int vt_round_replay(const double *x, uint64_t n, const uint32_t *idx, const uint
  *   C32            device, FP32 output, row pitch ldc >= N
  *   C64_debug      device or NULL: when given, receives the FP64 values before rounding
  *                  (dense, pitch N, batch stride M*N) -- for tests and threshold statistics
- *   variant        accumulation order: 0 = k ascending in one chain per output;
- *                  1 = k tiles visited in descending order.  Different variants give FP64
- *                  results that differ in their low bits, as two GPU types would.
+ *   variant        accumulation order: 0 = k steps (and split-K slices) in ascending order;
+ *                  1 = in descending order.  Different variants give FP64 results that differ
+ *                  in their low bits, as two GPU types would.
  *   M*N*batch must be < 2^32.  A, B 8-byte aligned.
  *   ws             at least vt_workspace_bytes(VT_OP_GEMM_ROUND_LOG, M, N, K, batch) bytes.
  */
@@ -151,6 +151,16 @@ size_t vt_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int64_t batch
 
 /* ceil(tau_ulp * 2^29), or 0xFFFFFFFF if tau_ulp is not in [0, 0.5]. Host-only helper. */
 uint32_t vt_thr_from_tau(double tau_ulp);
+
+/*
+ * Introspection (host only, no counterpart in the paper): the workgroup tile and the split-K
+ * factor vt_gemm_f64_round_log uses for a problem of this shape.  The choice is a pure function
+ * of these arguments, so a given call always accumulates in the same order.  splits > 1 (only
+ * for dense outputs: ldc == N and strideC == M*N) means the K range is cut into that many
+ * slices whose FP64 partial sums are added in a fixed order before the single rounding.
+ */
+int vt_gemm_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int64_t ldc, int64_t strideC,
+                 int *tile_m, int *tile_n, int *splits);
 
 /*
  * Optional instrumentation for benchmarks (no counterpart in the paper).  While two hipEvent_t

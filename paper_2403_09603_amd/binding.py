@@ -53,6 +53,8 @@ def load_library():
     L.vt_workspace_bytes.argtypes = [cint, i64, i64, i64, i64]
     L.vt_thr_from_tau.restype = C.c_uint32
     L.vt_thr_from_tau.argtypes = [dbl]
+    L.vt_gemm_plan.restype = cint
+    L.vt_gemm_plan.argtypes = [i64, i64, i64, i64, i64, i64, C.POINTER(cint), C.POINTER(cint), C.POINTER(cint)]
     L.vt_set_kernel_events.restype = cint
     L.vt_set_kernel_events.argtypes = [vp, vp]
     L.vt_strerror.restype = C.c_char_p
@@ -166,6 +168,15 @@ def vt_gemm_f64_round_log(transA: bool, transB: bool, M: int, N: int, K: int, al
         _ptr(bias, torch.float64), int(batch), _ptr(C32, torch.float32), int(ldc), int(strideC),
         _ptr(C64_debug, torch.float64), int(variant), float(tau_ulp), C.byref(clog),
         _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "vt_gemm_f64_round_log")
+
+
+def vt_gemm_plan(M: int, N: int, K: int, batch: int = 1, ldc: int | None = None, strideC: int | None = None):
+    """(tile_m, tile_n, splits) the GEMM entry point uses for this shape."""
+    tm, tn, sp = C.c_int(), C.c_int(), C.c_int()
+    _check(load_library().vt_gemm_plan(int(M), int(N), int(K), int(batch), int(N if ldc is None else ldc),
+                                       int(M * N if strideC is None else strideC), C.byref(tm), C.byref(tn),
+                                       C.byref(sp)), "vt_gemm_plan")
+    return tm.value, tn.value, sp.value
 
 
 def vt_set_kernel_events(ev_begin, ev_end):

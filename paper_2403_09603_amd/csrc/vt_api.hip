@@ -22,6 +22,37 @@ inline bool log_ok(const vt_log *log)
     return true;
 }
 
+inline size_t round_log_bytes(uint64_t n)
+{
+    const size_t a = vt::planes_bytes(1, n), b = vt::onepass_bytes(n);
+    return a > b ? a : b;
+}
+
+inline bool split_allowed(int64_t M, int64_t N, int64_t batch, int64_t ldc, int64_t strideC)
+{
+    return ldc == N && (batch <= 1 || strideC == M * N);    // the round/log pass sees one flat tensor
+}
+
+// round + log of a flat FP64 tensor that already lives in device memory (trainer hook)
+int round_log_flat(const double *x, uint64_t n, uint32_t thr, float *y, const vt_log *log, void *ws, hipStream_t s,
+                   bool mark)
+{
+    const vt::LogOut lo{log->idx, log->dir, log->cap, log->count};
+    if (vt::onepass_usable(x, y)) {         // one streaming pass; otherwise bit-planes + compaction
+        if (mark) mark_begin(s);
+        const hipError_t e1 = vt::launch_round_log_onepass(x, n, thr, y, ws, lo, s);
+        if (mark) mark_end(s);
+        return hip_status(e1);
+    }
+    const vt::Planes pl = vt::planes_carve(ws, 1, n);
+    if (mark) mark_begin(s);
+    hipError_t e = vt::launch_round_planes(x, n, thr, y, pl, s);
+    if (mark) mark_end(s);
+    if (e == hipSuccess) e = vt::launch_seg_scan(pl, lo, s);
+    if (e == hipSuccess) e = vt::launch_compact(pl, lo, s);
+    return hip_status(e);
+}
+
 // planes already hold the decisions: count per segment (unless the producer did), scan, compact
 int finish_log(const vt::Planes &pl, const vt_log *log, bool counted, hipStream_t s)
 {
@@ -60,12 +91,16 @@ size_t vt_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int64_t batch
     (void)K;
     if (M < 0 || N < 0 || batch < 0) return 0;
     switch (op) {
-    case VT_OP_ROUND_LOG: {
-        const uint64_t n = (uint64_t)M * (uint64_t)N * (uint64_t)batch;
-        const size_t a = vt::planes_bytes(1, n), b = vt::onepass_bytes(n);
-        return a > b ? a : b;
+    case VT_OP_ROUND_LOG: return round_log_bytes((uint64_t)M * (uint64_t)N * (uint64_t)batch);
+    case VT_OP_GEMM_ROUND_LOG: {
+        // sized for the split-K path too (taken for dense outputs when few tiles meet a long K)
+        size_t bytes = vt::planes_bytes((uint64_t)M * (uint64_t)batch, (uint64_t)N);
+        const vt::GemmPlan plan = vt::plan_gemm(M, N, K < 0 ? 0 : K, batch, true);
+        if (plan.splits > 1)
+            bytes += vt::gemm_split_bytes(M, N, batch, plan.splits) +
+                     round_log_bytes((uint64_t)M * (uint64_t)N * (uint64_t)batch);
+        return bytes;
     }
-    case VT_OP_GEMM_ROUND_LOG: return vt::planes_bytes((uint64_t)M * (uint64_t)batch, (uint64_t)N);
     default: return 0;
     }
 }
@@ -76,22 +111,9 @@ int vt_round_log(const double *x, uint64_t n, double tau_ulp, float *y, const vt
     const uint32_t thr = vt_thr_from_tau(tau_ulp);
     if (thr == 0xFFFFFFFFu || n >= (1ull << 32) || !log_ok(log)) return VT_ERR_INVALID_ARG;
     if (n && (!x || !y || !aligned(x, 8) || !aligned(y, 4))) return VT_ERR_INVALID_ARG;
-    const size_t need = vt_workspace_bytes(VT_OP_ROUND_LOG, 1, (int64_t)n, 0, 1);
+    const size_t need = round_log_bytes(n);
     if (!ws || ws_bytes < need || !aligned(ws, 256)) return VT_ERR_WORKSPACE;
-    hipStream_t s = (hipStream_t)hip_stream;
-    if (vt::onepass_usable(x, y)) {         // one streaming pass; otherwise bit-planes + compaction
-        const vt::LogOut lo{log->idx, log->dir, log->cap, log->count};
-        mark_begin(s);
-        const hipError_t e1 = vt::launch_round_log_onepass(x, n, thr, y, ws, lo, s);
-        mark_end(s);
-        return hip_status(e1);
-    }
-    const vt::Planes pl = vt::planes_carve(ws, 1, n);
-    mark_begin(s);
-    hipError_t e = vt::launch_round_planes(x, n, thr, y, pl, s);
-    mark_end(s);
-    if (e != hipSuccess) return VT_ERR_HIP;
-    return finish_log(pl, log, /*counted=*/true, s);
+    return round_log_flat(x, n, thr, y, log, ws, (hipStream_t)hip_stream, /*mark=*/true);
 }
 
 int vt_round_replay(const double *x, uint64_t n, const uint32_t *idx, const uint32_t *dir,
@@ -136,16 +158,29 @@ int vt_gemm_f64_round_log(int transA, int transB, int64_t M, int64_t N, int64_t 
         if (lda < (transA ? M : K) || ldb < (transB ? K : N) || strideA < 0 || strideB < 0) return VT_ERR_INVALID_ARG;
     }
     if (C64_debug && !aligned(C64_debug, 8)) return VT_ERR_INVALID_ARG;
-    const size_t need = vt::planes_bytes((uint64_t)M * (uint64_t)batch, (uint64_t)N);
+    const size_t need = vt_workspace_bytes(VT_OP_GEMM_ROUND_LOG, M, N, K, batch);
     if (!ws || ws_bytes < need || !aligned(ws, 256)) return VT_ERR_WORKSPACE;
     const vt::Planes pl = vt::planes_carve(ws, (uint64_t)M * (uint64_t)batch, (uint64_t)N);
+    const size_t planes = vt::planes_bytes((uint64_t)M * (uint64_t)batch, (uint64_t)N);
+    const vt::GemmPlan plan = vt::plan_gemm(M, N, K, batch, split_allowed(M, N, batch, ldc, strideC));
     vt::GemmArgs g;
     g.transA = transA; g.transB = transB; g.M = M; g.N = N; g.K = K; g.alpha = alpha;
     g.A = A; g.lda = lda; g.strideA = strideA; g.B = B; g.ldb = ldb; g.strideB = strideB;
     g.bias = bias; g.batch = batch; g.C32 = C32; g.ldc = ldc; g.strideC = strideC;
     g.C64 = C64_debug; g.variant = variant; g.thr = thr;
+    if (plan.splits > 1) {
+        // slabs -> fixed-order sum (alpha, bias) -> standalone round/log over the flat result
+        double *partial = (double *)((char *)ws + planes);
+        double *reduced = partial + (uint64_t)plan.splits * total;
+        void *ws_rl = (char *)partial + vt::gemm_split_bytes(M, N, batch, plan.splits);
+        mark_begin(s);
+        const hipError_t e2 = vt::launch_gemm_round_planes(g, plan, pl, partial, reduced, s);
+        mark_end(s);
+        if (e2 != hipSuccess) return VT_ERR_HIP;
+        return round_log_flat(reduced, total, thr, C32, log, ws_rl, s, /*mark=*/false);
+    }
     mark_begin(s);
-    hipError_t e = vt::launch_gemm_round_planes(g, pl, s);
+    hipError_t e = vt::launch_gemm_round_planes(g, plan, pl, nullptr, nullptr, s);
     mark_end(s);
     if (e != hipSuccess) return VT_ERR_HIP;
     return finish_log(pl, log, /*counted=*/false, s);
@@ -156,6 +191,18 @@ int vt_threshold_stats(const double *y1, const double *y2, uint64_t n, uint64_t 
     if (!out || !aligned(out, 8)) return VT_ERR_INVALID_ARG;
     if (n && (!y1 || !y2 || !aligned(y1, 8) || !aligned(y2, 8))) return VT_ERR_INVALID_ARG;
     return hip_status(vt::launch_stats(y1, y2, n, out, (hipStream_t)hip_stream));
+}
+
+int vt_gemm_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int64_t ldc, int64_t strideC,
+                 int *tile_m, int *tile_n, int *splits)
+{
+    if (M < 0 || N < 0 || K < 0 || batch < 0 || !tile_m || !tile_n || !splits) return VT_ERR_INVALID_ARG;
+    const vt::GemmPlan plan = vt::plan_gemm(M, N, K, batch, split_allowed(M, N, batch, ldc, strideC));
+    static const int bm[4] = {128, 64, 128, 64}, bn[4] = {128, 128, 64, 64};
+    *tile_m = bm[plan.shape];
+    *tile_n = bn[plan.shape];
+    *splits = plan.splits;
+    return VT_OK;
 }
 
 int vt_set_kernel_events(void *ev_begin, void *ev_end)

@@ -5,15 +5,29 @@
 // decision written as one bit of two row-major bit-planes, all from registers: the FP64
 // result never goes to memory (unless the caller asks for the debug copy).
 //
-// Tiling: workgroup 256 threads = 2 x 2 waves, workgroup tile 128 x 128, wave tile 64 x 64 =
-// 4 x 4 MFMA tiles (128 accumulator registers per lane), K step 16, operands staged through
-// LDS in k-major order ([k][m], [k][n]) and double-buffered against the global loads.
+// Tiling: a workgroup is 256 threads = 4 waves arranged WM x WN (2 x 2 or 4 x 1); a wave owns
+// TM x 4 MFMA tiles of 16 x 16, i.e. 16 TM rows by 64 columns, so that one wave always produces
+// whole 64-bit words of the decision planes.  Workgroup tiles: 128 x 128 (2x2, TM 4: the large
+// shape, 128 accumulator registers per lane), 64 x 128 (2x2, TM 2), 128 x 64 (4x1, TM 2) and
+// 64 x 64 (4x1, TM 1) for narrow outputs and for problems with too few tiles to fill 256 CUs.
+// K step 16; operands are staged through LDS in k-major order ([k][m], [k][n]), double-buffered
+// against the global loads, and the next tile is written to LDS in the shadow of the last MFMA
+// group of the current one.
+//
+// Split-K (weight-gradient shapes: tiny outputs, very long K): the K range is cut into `splits`
+// contiguous slices, every slice writes its raw FP64 accumulators to its own workspace slab, and
+// a second kernel adds the slabs in a fixed order before the single rounding -- the order of
+// additions never depends on timing.
 //
 // Lane layout of v_mfma_f64_16x16x4_f64 (measured on gfx950):
 //   A operand: lane l holds A[i = l % 16][k = l / 16];  B operand: lane l holds B[k = l / 16][j = l % 16]
 //   D: register r of lane l holds D[i = 4 r + l / 16][j = l % 16].
 #include "vt_device.h"
 #include "vt_kernels.h"
+
+#include <cmath>
+#include <cstdlib>
+#include <type_traits>
 
 namespace vt {
 
@@ -22,34 +36,40 @@ namespace {
 typedef double d4 __attribute__((ext_vector_type(4)));
 typedef double d2 __attribute__((ext_vector_type(2)));
 
-constexpr int BM = 128, BN = 128, BK = 16;
-constexpr int LDS_S = 128 + 16;                 // row pitch in doubles: k rows 32 banks apart
-constexpr int kTileDoubles = BK * LDS_S;
+constexpr int BK = 16;
+// LDS row pitch = tile width + 18 doubles.  A k-contiguous operand is transposed on its way into
+// LDS: the 32 lanes of a write pass hold 8 k rows x 4 columns, and with a pitch of 18 mod 32
+// doubles those land on 32 different bank pairs (a pitch of 16 mod 32 put all 8 k rows on one
+// pair: 8-way conflicts that kept the LDS pipe busy for about as long as the MFMAs).  Fragment
+// reads (2 k rows x 16 columns per pass) then overlap in 2 of 32 bank pairs only.
+constexpr int kPad = 18;
 
 struct GemmParams {
     const double *A, *B, *bias;
     float *C32;
-    double *C64;
+    double *C64;                                // optional dense FP64 copy (fused path only)
+    double *partial;                            // split-K slabs [split][batch][M][N]
     uint64_t *pl_logged, *pl_dir;
-    int64_t M, N, K, lda, ldb, ldc, strideA, strideB, strideC;
+    int64_t M, N, K, lda, ldb, ldc, strideA, strideB, strideC, batch;
     double alpha;
-    uint32_t thr, wpr, tilesM, tilesN, total_tiles;
-    int variant, vecA, vecB;
+    uint32_t thr, wpr, tilesM, tilesN, tiles_per_split, total_blocks;
+    int variant, vecA, vecB, splits, kt_per_split;
 };
 
-// Global -> registers for one 128 x 16 operand tile.  KC = the operand is contiguous along k
-// (element (mn, k) at base[mn * ld + k]); otherwise contiguous along m/n (base[k * ld + mn]).
+// Global -> registers for one R x 16 operand tile (R = 64 or 128 rows/columns of the output).
+// KC = the operand is contiguous along k (element (mn, k) at base[mn * ld + k]); otherwise
+// contiguous along m/n (base[k * ld + mn]).  Each thread moves R / 32 pairs of doubles.
 // Out-of-range elements read as 0, so partial tiles add exact zeros.
-template <bool KC>
+template <bool KC, int R>
 __device__ __forceinline__ void load_tile(const double *__restrict__ base, int64_t ld, int64_t mn0, int64_t k0,
-                                          int64_t MN, int64_t K, int vec, d2 (&regs)[4])
+                                          int64_t MN, int64_t K, int vec, d2 (&regs)[R / 32])
 {
     const int t = threadIdx.x;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < R / 32; ++j) {
         int64_t mn, k;
         if (KC) { mn = mn0 + (t >> 3) + 32 * j; k = k0 + (t & 7) * 2; }
-        else    { k = k0 + (t >> 6) + 4 * j;    mn = mn0 + (t & 63) * 2; }
+        else    { k = k0 + t / (R / 2) + (512 / R) * j; mn = mn0 + (t % (R / 2)) * 2; }
         d2 v = {0.0, 0.0};
         if (KC) {
             if (mn < MN) {
@@ -68,56 +88,69 @@ __device__ __forceinline__ void load_tile(const double *__restrict__ base, int64
     }
 }
 
-// Same tile when it lies wholly inside the operand and 16-byte loads are legal: four straight
-// vector loads from a per-thread pointer to the tile's k = 0 position, no guards.
-template <bool KC>
-__device__ __forceinline__ const double *tile_origin(const double *__restrict__ base, int64_t ld, int64_t mn0)
-{
-    const int t = threadIdx.x;
-    return KC ? base + (mn0 + (t >> 3)) * ld + (t & 7) * 2 : base + (int64_t)(t >> 6) * ld + mn0 + (t & 63) * 2;
-}
-
-template <bool KC>
-__device__ __forceinline__ void load_tile_fast(const double *__restrict__ origin, int64_t ld, int64_t k0, d2 (&regs)[4])
-{
-    const double *p = KC ? origin + k0 : origin + k0 * ld;
-    const int64_t step = KC ? 32 * ld : 4 * ld;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) regs[j] = *(const d2 *)(p + j * step);
-}
-
-template <bool KC>
-__device__ __forceinline__ void store_tile(double *__restrict__ S, const d2 (&regs)[4])
+// Same tile when it lies wholly inside the operand and 16-byte loads are legal: straight vector
+// loads, no guards.  Addresses are a workgroup-uniform base (scalar registers, advanced per k
+// step) plus a per-thread 32-bit byte offset that never changes, so the loop spends no vector
+// instructions -- and no load-destination registers -- on address arithmetic.
+template <bool KC, int R>
+__device__ __forceinline__ void tile_offsets(int64_t ld, uint32_t (&off)[R / 32])
 {
     const int t = threadIdx.x;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < R / 32; ++j)
+        off[j] = KC ? (uint32_t)((((t >> 3) + 32 * j) * ld + (t & 7) * 2) * 8)
+                    : (uint32_t)(((t / (R / 2) + (512 / R) * j) * ld + (t % (R / 2)) * 2) * 8);
+}
+
+template <bool KC, int R>
+__device__ __forceinline__ void load_tile_fast(const char *__restrict__ base, int64_t ld, int64_t k0,
+                                               const uint32_t (&off)[R / 32], d2 (&regs)[R / 32])
+{
+    const char *p = base + (KC ? k0 : k0 * ld) * 8;      // uniform
+#pragma unroll
+    for (int j = 0; j < R / 32; ++j) regs[j] = *(const d2 *)(p + off[j]);
+}
+
+template <bool KC, int R>
+__device__ __forceinline__ void store_tile(double *__restrict__ S, const d2 (&regs)[R / 32])
+{
+    const int t = threadIdx.x;
+    constexpr int pitch = R + kPad;
+#pragma unroll
+    for (int j = 0; j < R / 32; ++j) {
         if (KC) {
             const int mn = (t >> 3) + 32 * j, k = (t & 7) * 2;
-            S[k * LDS_S + mn] = regs[j].x;
-            S[(k + 1) * LDS_S + mn] = regs[j].y;
+            S[k * pitch + mn] = regs[j].x;
+            S[(k + 1) * pitch + mn] = regs[j].y;
         } else {
-            const int k = (t >> 6) + 4 * j, mn = (t & 63) * 2;
-            *(d2 *)&S[k * LDS_S + mn] = regs[j];
+            const int k = t / (R / 2) + (512 / R) * j, mn = (t % (R / 2)) * 2;
+            *(d2 *)&S[k * pitch + mn] = regs[j];
         }
     }
 }
 
-template <bool KCA, bool KCB>
+template <bool KCA, bool KCB, int WM, int TM>
 __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmParams p)
 {
-    __shared__ double lds[4 * kTileDoubles];     // A0 A1 B0 B1
+    constexpr int WN = 4 / WM;
+    constexpr int BM = WM * 16 * TM, BN = WN * 64;
+    constexpr int PA = BM + kPad, PB = BN + kPad;          // LDS pitches
+    constexpr int SA = BK * PA, SB = BK * PB;              // doubles per stage
+    __shared__ double lds[2 * SA + 2 * SB];                // A0 A1 B0 B1
+    double *const ldsA = lds, *const ldsB = lds + 2 * SA;
     const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
-    const int wm = wv >> 1, wn = wv & 1;
+    const int wm = wv / WN, wn = wv % WN;
 
-    // Workgroup -> tile.  Consecutive workgroup ids land on different XCDs (8 of them, each
-    // with its own L2), so ids are first regrouped per XCD, then walked in bands of 8 row
+    // Workgroup -> (split, tile).  Consecutive workgroup ids land on different XCDs (8 of them,
+    // each with its own L2), so ids are first regrouped per XCD, then walked in bands of 8 row
     // tiles so that neighbours in time share A and B panels in that L2.
     uint32_t pid;
     {
-        const uint32_t i = blockIdx.x, q = p.total_tiles / 8u, r = p.total_tiles % 8u, xcd = i % 8u;
+        const uint32_t i = blockIdx.x, q = p.total_blocks / 8u, r = p.total_blocks % 8u, xcd = i % 8u;
         pid = xcd * q + (xcd < r ? xcd : r) + i / 8u;
     }
+    const uint32_t split = pid / p.tiles_per_split;
+    pid -= split * p.tiles_per_split;
     const uint32_t per_batch = p.tilesM * p.tilesN;
     const uint32_t b = pid / per_batch;
     const uint32_t pin = pid - b * per_batch;
@@ -131,66 +164,117 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
     const double *A = p.A + (int64_t)b * p.strideA;
     const double *B = p.B + (int64_t)b * p.strideB;
 
-    d4 acc[4][4];
+    d4 acc[TM][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = (d4){0.0, 0.0, 0.0, 0.0};
 
-    const int nkt = (int)((p.K + BK - 1) / BK);
+    // this workgroup's k tiles: [kt0, kt1)
+    const int nkt_all = (int)((p.K + BK - 1) / BK);
+    const int kt0 = (int)split * p.kt_per_split;
+    const int kt1 = kt0 + p.kt_per_split < nkt_all ? kt0 + p.kt_per_split : nkt_all;
+    const int nkt = kt1 > kt0 ? kt1 - kt0 : 0;
     // whole-tile operands take the unguarded loader (a uniform choice per k step)
-    const bool fastA = p.vecA && bm + BM <= p.M, fastB = p.vecB && bn + BN <= p.N;
-    const double *oa = tile_origin<KCA>(A, p.lda, bm), *ob = tile_origin<KCB>(B, p.ldb, bn);
-    d2 ra[4], rb[4];
-    auto fetch = [&](int64_t k0) {
-        const bool kfull = k0 + BK <= p.K;
-        if (fastA && kfull) load_tile_fast<KCA>(oa, p.lda, k0, ra);
-        else load_tile<KCA>(A, p.lda, bm, k0, p.M, p.K, p.vecA, ra);
-        if (fastB && kfull) load_tile_fast<KCB>(ob, p.ldb, k0, rb);
-        else load_tile<KCB>(B, p.ldb, bn, k0, p.N, p.K, p.vecB, rb);
-    };
-    if (nkt > 0) {
-        fetch((int64_t)(p.variant ? nkt - 1 : 0) * BK);
-        store_tile<KCA>(lds, ra);
-        store_tile<KCB>(lds + 2 * kTileDoubles, rb);
-    }
-    __syncthreads();
-    int cur = 0;
-    for (int it = 0; it < nkt; ++it) {
-        const bool more = it + 1 < nkt;
-        if (more) fetch((int64_t)(p.variant ? nkt - 2 - it : it + 1) * BK);
-        const double *As = lds + cur * kTileDoubles + wm * 64 + (lane & 15);
-        const double *Bs = lds + (2 + cur) * kTileDoubles + wn * 64 + (lane & 15);
-        double a[4], bb[4];
-#pragma unroll
-        for (int kk = 0; kk < BK / 4; ++kk) {
-            const int krow = (kk * 4 + (lane >> 4)) * LDS_S;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) { a[i] = As[krow + i * 16]; bb[i] = Bs[krow + i * 16]; }
-            if (kk == BK / 4 - 1) {
-                // The next tile goes to the other LDS buffer in the shadow of the last 16 MFMAs
-                // of this one (its fragments are already requested: LDS completes in order), so
-                // a wave's MFMA stream has no gap before the barrier.
-                __builtin_amdgcn_sched_barrier(0);
-                if (more) {
-                    store_tile<KCA>(lds + (cur ^ 1) * kTileDoubles, ra);
-                    store_tile<KCB>(lds + (2 + (cur ^ 1)) * kTileDoubles, rb);
-                }
-                __builtin_amdgcn_sched_barrier(0);
+    // (the per-thread offsets of the unguarded loader are 32-bit: pitches up to 2^31 / 8 / 128)
+    const bool fastA = p.vecA && bm + BM <= p.M && p.lda < (1 << 21);
+    const bool fastB = p.vecB && bn + BN <= p.N && p.ldb < (1 << 21);
+    const char *baseA = (const char *)(A + (KCA ? bm * p.lda : bm));
+    const char *baseB = (const char *)(B + (KCB ? bn * p.ldb : bn));
+    uint32_t offA[BM / 32], offB[BN / 32];
+    tile_offsets<KCA, BM>(p.lda, offA);
+    tile_offsets<KCB, BN>(p.ldb, offB);
+    // Two register sets: tile it+2 is in flight from memory while tile it+1 (fetched one step
+    // earlier) goes to LDS and tile it is multiplied, so a fetch has two full steps to land.
+    // The loop exists twice: with unguarded loads only (every tile of this workgroup lies inside
+    // the operands; straight-line code, so the load counter waits are exact and the newest
+    // fetch stays in flight across the LDS stores), and with the guarded loader for edges.
+    d2 ra0[BM / 32], rb0[BN / 32], ra1[BM / 32], rb1[BN / 32];
+    auto main_loop = [&](auto fast_tag) {
+        constexpr bool FAST = decltype(fast_tag)::value;
+        auto fetch = [&](int it, d2 (&ra)[BM / 32], d2 (&rb)[BN / 32]) {   // `it`-th step in this variant's order
+            const int64_t k0 = (int64_t)(p.variant ? kt1 - 1 - it : kt0 + it) * BK;
+            if constexpr (FAST) {
+                load_tile_fast<KCA, BM>(baseA, p.lda, k0, offA, ra);
+                load_tile_fast<KCB, BN>(baseB, p.ldb, k0, offB, rb);
+            } else {
+                load_tile<KCA, BM>(A, p.lda, bm, k0, p.M, p.K, p.vecA, ra);
+                load_tile<KCB, BN>(B, p.ldb, bn, k0, p.N, p.K, p.vecB, rb);
             }
+        };
+        // one k step: multiply the tile in LDS stage `cur`; start the fetch of tile it+2 into (la, lb);
+        // move tile it+1 from (sa, sb) to the other stage in the shadow of the last MFMA group
+        auto step = [&](int it, int cur, d2 (&la)[BM / 32], d2 (&lb)[BN / 32], d2 (&sa)[BM / 32], d2 (&sb)[BN / 32]) {
+            // In the unguarded loop the fetch and the LDS store are unconditional (past the end
+            // they repeat the last tile and fill a stage nobody reads): with no branch around
+            // them the compiler's load-counter waits are exact.
+            if (FAST) fetch(it + 2 < nkt ? it + 2 : nkt - 1, la, lb);
+            else if (it + 2 < nkt) fetch(it + 2, la, lb);
+            const bool more = FAST || it + 1 < nkt;
+            const double *As = ldsA + cur * SA + wm * (16 * TM) + (lane & 15);
+            const double *Bs = ldsB + cur * SB + wn * 64 + (lane & 15);
+            double a[TM], bb[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int kk = 0; kk < BK / 4; ++kk) {
+                const int krow = kk * 4 + (lane >> 4);
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], bb[j], acc[i][j], 0, 0, 0);
+                for (int i = 0; i < TM; ++i) a[i] = As[krow * PA + i * 16];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) bb[j] = Bs[krow * PB + j * 16];
+                if (kk == BK / 4 - 1) {
+                    // (the last group's fragments are already requested: LDS completes in order,
+                    // so the wave's MFMA stream has no gap before the barrier)
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (more) {
+                        store_tile<KCA, BM>(ldsA + (cur ^ 1) * SA, sa);
+                        store_tile<KCB, BN>(ldsB + (cur ^ 1) * SB, sb);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], bb[j], acc[i][j], 0, 0, 0);
+            }
+            __syncthreads();
+        };
+        if (nkt > 0) {
+            fetch(0, ra0, rb0);
+            store_tile<KCA, BM>(ldsA, ra0);
+            store_tile<KCB, BN>(ldsB, rb0);
+            if (nkt > 1) fetch(1, ra0, rb0);
         }
         __syncthreads();
-        cur ^= 1;
+        for (int it = 0; it < nkt; it += 2) {
+            step(it, 0, ra1, rb1, ra0, rb0);                // tile it+1 sits in set 0, it+2 goes to set 1
+            if (it + 1 < nkt) step(it + 1, 1, ra0, rb0, ra1, rb1);
+        }
+    };
+    if (fastA && fastB && (int64_t)kt1 * BK <= p.K) main_loop(std::true_type{});
+    else main_loop(std::false_type{});
+
+    const int g = lane >> 4, c16 = lane & 15;
+    const int64_t row0 = bm + wm * (16 * TM), col0 = bn + wn * 64;
+
+    if (p.splits > 1) {
+        // ---- split-K: raw accumulators to this slice's slab; alpha, bias, rounding come later
+        double *P = p.partial + ((int64_t)split * p.batch + (int64_t)b) * p.M * p.N;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int64_t row = row0 + i * 16 + 4 * r + g;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int64_t col = col0 + j * 16 + c16;
+                    if (row < p.M && col < p.N) P[row * p.N + col] = acc[i][j][r];
+                }
+            }
+        return;
     }
 
     // ---- epilogue: alpha, bias, round, decide, store, bit-planes -------------------------
-    const int g = lane >> 4, c16 = lane & 15;
-    const int64_t row0 = bm + wm * 64, col0 = bn + wn * 64;
     const uint64_t colword = (uint64_t)col0 >> 6;
     const bool word_exists = colword < p.wpr;
     float *C32 = p.C32 + (int64_t)b * p.strideC;
@@ -202,7 +286,7 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
         bias_v[j] = (p.bias && col < p.N) ? p.bias[col] : 0.0;
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < TM; ++i) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int64_t row = row0 + i * 16 + 4 * r + g;
@@ -240,30 +324,105 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
     }
 }
 
+// Split-K second stage: out[e] = alpha * (P[0][e] + P[1][e] + ...) (+ bias[col]), slabs added in
+// ascending order (variant 0) or descending order (variant 1).  One thread per output.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const double *__restrict__ P, uint64_t slab, int splits,
+                                                            int variant, double alpha, const double *__restrict__ bias,
+                                                            uint32_t N, double *__restrict__ out,
+                                                            double *__restrict__ out2)
+{
+    const uint64_t e = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+    if (e >= slab) return;
+    double s = 0.0;
+    for (int k = 0; k < splits; ++k) s = s + P[(uint64_t)(variant ? splits - 1 - k : k) * slab + e];
+    double c = alpha * s;
+    if (bias) c = c + bias[e % N];
+    out[e] = c;
+    if (out2) out2[e] = c;
+}
+
+struct TileShape { int wm, tm, bm, bn; double eff; };
+constexpr TileShape kShapes[4] = {{2, 4, 128, 128, 1.00}, {2, 2, 64, 128, 0.88}, {4, 2, 128, 64, 0.88}, {4, 1, 64, 64, 0.75}};
+
+template <int WM, int TM>
+hipError_t launch_shape(const GemmParams &p, bool kca, bool kcb, hipStream_t s)
+{
+    const dim3 grid(p.total_blocks), block(256);
+    if (kca && kcb) gemm_round_planes_kernel<true, true, WM, TM><<<grid, block, 0, s>>>(p);
+    else if (kca && !kcb) gemm_round_planes_kernel<true, false, WM, TM><<<grid, block, 0, s>>>(p);
+    else if (!kca && kcb) gemm_round_planes_kernel<false, true, WM, TM><<<grid, block, 0, s>>>(p);
+    else gemm_round_planes_kernel<false, false, WM, TM><<<grid, block, 0, s>>>(p);
+    return hipGetLastError();
+}
+
 }  // namespace
 
-hipError_t launch_gemm_round_planes(const GemmArgs &g, const Planes &pl, hipStream_t s)
+// Tile shape and split count for a problem: minimise (rounds of 256 workgroups) x (work per
+// workgroup) / (efficiency of the shape), plus the cost of writing and re-reading the slabs.
+// Pure host arithmetic on the shape, so the choice (and with it the accumulation order) is a
+// function of the arguments alone.
+GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split)
 {
+    GemmPlan best{0, 1, 0};
+    double best_cost = 1e300;
+    const int64_t nkt = (K + BK - 1) / BK;
+    for (int sh = 0; sh < 4; ++sh) {
+        const TileShape &t = kShapes[sh];
+        const double tiles = (double)((M + t.bm - 1) / t.bm) * (double)((N + t.bn - 1) / t.bn) * (double)batch;
+        for (int sp = 1; sp <= 64; sp *= 2) {
+            if (sp > 1 && (!allow_split || nkt / sp < 8)) break;        // keep >= 8 k steps per slice
+            const double rounds = std::ceil(tiles * sp / 256.0);
+            // MFMA time of one workgroup per k step ~ bm*bn/ (128 flop/clk/CU) * 2*16; +3 steps of ramp/epilogue
+            double cost = rounds * (double)t.bm * t.bn * ((double)(nkt + sp - 1) / sp + 3.0) / t.eff;
+            if (sp > 1) cost += 40.0 * (double)M * N * batch * (sp + 2) / 256.0;   // slab write + read, reduced tensor
+            if (cost < best_cost) { best_cost = cost; best = GemmPlan{sh, sp, 0}; }
+        }
+    }
+    best.kt_per_split = (int)((nkt + best.splits - 1) / best.splits);
+    if (best.kt_per_split < 1) best.kt_per_split = 1;
+    return best;
+}
+
+size_t gemm_split_bytes(int64_t M, int64_t N, int64_t batch, int splits)
+{
+    if (splits <= 1) return 0;
+    const uint64_t slab = (uint64_t)M * N * batch * 8;
+    return (size_t)((slab + 255) / 256 * 256 * (uint64_t)(splits + 1));   // slabs + the reduced tensor
+}
+
+hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, const Planes &pl, double *partial,
+                                    double *reduced, hipStream_t s)
+{
+    const TileShape &t = kShapes[plan.shape];
     GemmParams p;
-    p.A = g.A; p.B = g.B; p.bias = g.bias; p.C32 = g.C32; p.C64 = g.C64;
+    p.A = g.A; p.B = g.B; p.bias = g.bias; p.C32 = g.C32; p.C64 = g.C64; p.partial = partial;
     p.pl_logged = pl.logged; p.pl_dir = pl.dir;
     p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc;
-    p.strideA = g.strideA; p.strideB = g.strideB; p.strideC = g.strideC;
+    p.strideA = g.strideA; p.strideB = g.strideB; p.strideC = g.strideC; p.batch = g.batch;
     p.alpha = g.alpha; p.thr = g.thr; p.wpr = pl.wpr; p.variant = g.variant;
-    p.tilesM = (uint32_t)((g.M + BM - 1) / BM);
-    p.tilesN = (uint32_t)((g.N + BN - 1) / BN);
-    const uint64_t total = (uint64_t)p.tilesM * p.tilesN * (uint64_t)g.batch;
+    p.splits = plan.splits; p.kt_per_split = plan.kt_per_split;
+    p.tilesM = (uint32_t)((g.M + t.bm - 1) / t.bm);
+    p.tilesN = (uint32_t)((g.N + t.bn - 1) / t.bn);
+    const uint64_t per_split = (uint64_t)p.tilesM * p.tilesN * (uint64_t)g.batch;
+    const uint64_t total = per_split * (uint64_t)plan.splits;
     if (total == 0) return hipSuccess;
     if (total > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    p.total_tiles = (uint32_t)total;
+    p.tiles_per_split = (uint32_t)per_split;
+    p.total_blocks = (uint32_t)total;
     p.vecA = ((uintptr_t)g.A % 16 == 0) && (g.lda % 2 == 0) && (g.strideA % 2 == 0);
     p.vecB = ((uintptr_t)g.B % 16 == 0) && (g.ldb % 2 == 0) && (g.strideB % 2 == 0);
     const bool kca = !g.transA, kcb = g.transB != 0;
-    const dim3 grid(p.total_tiles), block(256);
-    if (kca && kcb) gemm_round_planes_kernel<true, true><<<grid, block, 0, s>>>(p);
-    else if (kca && !kcb) gemm_round_planes_kernel<true, false><<<grid, block, 0, s>>>(p);
-    else if (!kca && kcb) gemm_round_planes_kernel<false, true><<<grid, block, 0, s>>>(p);
-    else gemm_round_planes_kernel<false, false><<<grid, block, 0, s>>>(p);
+    hipError_t e;
+    switch (plan.shape) {
+    case 0: e = launch_shape<2, 4>(p, kca, kcb, s); break;
+    case 1: e = launch_shape<2, 2>(p, kca, kcb, s); break;
+    case 2: e = launch_shape<4, 2>(p, kca, kcb, s); break;
+    default: e = launch_shape<4, 1>(p, kca, kcb, s); break;
+    }
+    if (e != hipSuccess || plan.splits <= 1) return e;
+    const uint64_t slab = (uint64_t)g.M * g.N * g.batch;
+    splitk_reduce_kernel<<<(uint32_t)((slab + 255) / 256), 256, 0, s>>>(partial, slab, plan.splits, g.variant, g.alpha,
+                                                                      g.bias, (uint32_t)g.N, reduced, g.C64);
     return hipGetLastError();
 }
 

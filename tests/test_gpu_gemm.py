@@ -89,6 +89,51 @@ def test_ragged_shapes(G, shape):
     _check(G, A, B, alpha=0.5, bias=bias, tau=2.0 ** -3)
 
 
+def test_every_tile_shape_and_split_factor_is_exercised(G):
+    """The entry point picks a workgroup tile (128x128, 64x128, 128x64, 64x64) and a split-K factor
+    from the shape alone; run problems that land on each and check all of them like any other."""
+    import paper_2403_09603_amd as vt
+    g = si.rng(si.seed_for(1, 16))
+    seen = set()
+    cases = [(4100, 4100, 8, 1, False, False),      # more than a thousand 128x128 tiles
+             (100000, 64, 8, 1, False, False),      # narrow N, many rows
+             (700, 1500, 40, 1, False, False),
+             (1000, 768, 24, 1, False, False),
+             (2100, 64, 50, 1, False, False),       # narrow N
+             (300, 50, 33, 1, False, False),
+             (260, 250, 20, 1, False, False),
+             (64, 147, 5003, 1, True, False),       # weight-gradient shape: tiny output, long K
+             (130, 200, 2600, 1, True, False),
+             (96, 64, 1100, 3, False, True)]
+    for M, N, K, batch, tA, tB in cases:
+        plan = vt.vt_gemm_plan(M, N, K, batch)
+        seen.add(plan[:2])
+        seen.add(("split", plan[2] > 1))
+        shapeA = (K, M) if tA else (M, K)
+        shapeB = (N, K) if tB else (K, N)
+        A = g.standard_normal((batch,) + shapeA if batch > 1 else shapeA)
+        B = g.standard_normal((batch,) + shapeB if batch > 1 else shapeB) * 0.1
+        bias = g.standard_normal(N)
+        for variant in (0, 1):
+            _check(G, A, B, transA=tA, transB=tB, alpha=0.75, bias=bias, tau=2.0 ** -4, variant=variant)
+    assert {(128, 128), (64, 128), (128, 64), (64, 64), ("split", True), ("split", False)} <= seen, seen
+
+
+def test_split_k_is_deterministic_and_variants_differ(G):
+    g = si.rng(si.seed_for(1, 17))
+    A, B = g.standard_normal((6000, 64)), g.standard_normal((6000, 147))
+    import paper_2403_09603_amd as vt
+    assert vt.vt_gemm_plan(64, 147, 6000, 1)[2] > 1
+    r0 = G.gpu_gemm(A, B, transA=True, tau=0.25)
+    r0b = G.gpu_gemm(A, B, transA=True, tau=0.25)
+    r1 = G.gpu_gemm(A, B, transA=True, tau=0.25, variant=1)
+    assert np.array_equal(r0["C64"], r0b["C64"]) and np.array_equal(r0["idx"], r0b["idx"])
+    assert np.array_equal(r0["dir"], r0b["dir"]) and np.array_equal(_bits(r0["C32"]), _bits(r0b["C32"]))
+    assert (r0["C64"] != r1["C64"]).mean() > 0.3
+    # padded output pitch switches split-K off (the round/log pass needs a dense tensor): still correct
+    _check(G, A, B, transA=True, tau=0.25, ldc=160)
+
+
 @pytest.mark.parametrize("transA,transB", [(False, True), (True, False), (True, True)])
 def test_transposed_operands(G, transA, transB):
     g = si.rng(si.seed_for(1, 12))
