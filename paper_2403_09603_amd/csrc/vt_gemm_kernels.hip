@@ -334,15 +334,25 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const double *__rest
     const uint64_t e = (uint64_t)blockIdx.x * 256u + threadIdx.x;
     if (e >= slab) return;
     double s = 0.0;
-    for (int k = 0; k < splits; ++k) s = s + P[(uint64_t)(variant ? splits - 1 - k : k) * slab + e];
+    int k = 0;
+    for (; k + 8 <= splits; k += 8) {                      // eight loads in flight, additions still in order
+        double v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = P[(uint64_t)(variant ? splits - 1 - (k + u) : k + u) * slab + e];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s = s + v[u];
+    }
+    for (; k < splits; ++k) s = s + P[(uint64_t)(variant ? splits - 1 - k : k) * slab + e];
     double c = alpha * s;
     if (bias) c = c + bias[e % N];
     out[e] = c;
     if (out2) out2[e] = c;
 }
 
-struct TileShape { int wm, tm, bm, bn; double eff; };
-constexpr TileShape kShapes[4] = {{2, 4, 128, 128, 1.00}, {2, 2, 64, 128, 0.88}, {4, 2, 128, 64, 0.88}, {4, 1, 64, 64, 0.75}};
+// bm x bn, measured MFMA efficiency with a full CU, workgroups that fit on one CU (LDS-bound)
+struct TileShape { int wm, tm, bm, bn; double eff; int conc; };
+constexpr TileShape kShapes[4] = {{2, 4, 128, 128, 0.85, 2}, {2, 2, 64, 128, 0.78, 2}, {4, 2, 128, 64, 0.74, 2},
+                                  {4, 1, 64, 64, 0.62, 3}};
 
 template <int WM, int TM>
 hipError_t launch_shape(const GemmParams &p, bool kca, bool kcb, hipStream_t s)
@@ -357,10 +367,11 @@ hipError_t launch_shape(const GemmParams &p, bool kca, bool kcb, hipStream_t s)
 
 }  // namespace
 
-// Tile shape and split count for a problem: minimise (rounds of 256 workgroups) x (work per
-// workgroup) / (efficiency of the shape), plus the cost of writing and re-reading the slabs.
-// Pure host arithmetic on the shape, so the choice (and with it the accumulation order) is a
-// function of the arguments alone.
+// Tile shape and split count for a problem, from a small cost model calibrated on the box (unit:
+// a quarter MFMA-pipe cycle per CU): rounds of 256 workgroups x work per workgroup / efficiency
+// of the shape (lower when a CU holds a single workgroup, which cannot hide its own stalls), plus
+// for split-K the two extra kernels and the slab traffic.  Pure host arithmetic on the shape, so
+// the choice (and with it the accumulation order) is a function of the arguments alone.
 GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split)
 {
     GemmPlan best{0, 1, 0};
@@ -369,12 +380,13 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_sp
     for (int sh = 0; sh < 4; ++sh) {
         const TileShape &t = kShapes[sh];
         const double tiles = (double)((M + t.bm - 1) / t.bm) * (double)((N + t.bn - 1) / t.bn) * (double)batch;
-        for (int sp = 1; sp <= 64; sp *= 2) {
+        for (int sp = 1; sp <= 256; sp *= 2) {
             if (sp > 1 && (!allow_split || nkt / sp < 8)) break;        // keep >= 8 k steps per slice
-            const double rounds = std::ceil(tiles * sp / 256.0);
-            // MFMA time of one workgroup per k step ~ bm*bn/ (128 flop/clk/CU) * 2*16; +3 steps of ramp/epilogue
-            double cost = rounds * (double)t.bm * t.bn * ((double)(nkt + sp - 1) / sp + 3.0) / t.eff;
-            if (sp > 1) cost += 40.0 * (double)M * N * batch * (sp + 2) / 256.0;   // slab write + read, reduced tensor
+            const double blocks = tiles * sp;
+            const double rounds = std::ceil(blocks / 256.0);
+            const double eff = t.eff * (rounds >= 2.0 ? 1.0 : 0.72);
+            double cost = rounds * (double)t.bm * t.bn * ((double)((nkt + sp - 1) / sp) + 10.0) / eff;
+            if (sp > 1) cost += 144000.0 + 0.03 * (double)M * N * batch * (sp + 2);
             if (cost < best_cost) { best_cost = cost; best = GemmPlan{sh, sp, 0}; }
         }
     }
