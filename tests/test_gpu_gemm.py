@@ -95,7 +95,7 @@ def test_every_tile_shape_and_split_factor_is_exercised(G):
     import paper_2403_09603_amd as vt
     g = si.rng(si.seed_for(1, 16))
     seen = set()
-    cases = [(4100, 4100, 8, 1, False, False),      # more than a thousand 128x128 tiles
+    cases = [(4096, 3072, 8, 1, False, False),      # whole rounds of 128x128 tiles
              (100000, 64, 8, 1, False, False),      # narrow N, many rows
              (700, 1500, 40, 1, False, False),
              (1000, 768, 24, 1, False, False),
