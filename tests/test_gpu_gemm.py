@@ -98,6 +98,7 @@ def test_every_tile_shape_and_split_factor_is_exercised(G):
     cases = [(4096, 3072, 8, 1, False, False),      # whole rounds of 128x128 tiles
              (100000, 64, 8, 1, False, False),      # narrow N, many rows
              (700, 1500, 40, 1, False, False),
+             (1500, 2304, 24, 1, False, False),
              (1000, 768, 24, 1, False, False),
              (2100, 64, 50, 1, False, False),       # narrow N
              (300, 50, 33, 1, False, False),
