@@ -52,6 +52,19 @@ class HipEvents:
         return float(ms.value)
 
 
+def measured_traffic():
+    """HBM-side bytes per trainer-GEMM launch from the committed rocprofv3 counter summary
+    (FETCH_SIZE and WRITE_SIZE passes of this same command, scaled against a plain copy), or None."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "gemm_round_planes_gpt2_mlp_up_counters.md")) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return int(line.split()[1])
+    except (OSError, ValueError, IndexError):
+        pass
+    return None
+
+
 def next_pow2(v: int) -> int:
     return 1 << max(int(v) - 1, 0).bit_length()
 
@@ -179,7 +192,8 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "gemm_round_planes_kernel (trainer, variant 0)",
                      "achieved": round(achieved, 3), "peak": FP64_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / FP64_MFMA_PEAK_TFLOPS, 4), "kernel_ms": round(gemm_ms, 4),
-                     "traffic": None},
+                     "algorithmic_bytes": 8 * (M * K + K * N + N) + 4 * M * N + 2 * (M * ((N + 63) // 64) * 8),
+                     "traffic": measured_traffic()},
     }
 
     # ------------------------------------------------ standalone HBM-bound sweep (2^28 elements)
