@@ -162,6 +162,80 @@ int vto_gemm_f64(int transA, int transB, int64_t M, int64_t N, int64_t K, double
     return VTO_OK;
 }
 
+int vto_conv2d_out_size(const vto_conv2d *d, int64_t *Ho, int64_t *Wo)
+{
+    if (!d || d->N < 0 || d->H < 0 || d->W < 0 || d->C < 0 || d->KH < 1 || d->KW < 1 || d->stride_h < 1 ||
+        d->stride_w < 1 || d->pad_h < 0 || d->pad_w < 0 || d->dil_h < 1 || d->dil_w < 1)
+        return VTO_ERR_INVALID_ARG;
+    int64_t eh = d->H + 2 * d->pad_h - d->dil_h * (d->KH - 1) - 1;
+    int64_t ew = d->W + 2 * d->pad_w - d->dil_w * (d->KW - 1) - 1;
+    *Ho = eh < 0 ? 0 : eh / d->stride_h + 1;
+    *Wo = ew < 0 ? 0 : ew / d->stride_w + 1;
+    return VTO_OK;
+}
+
+/* X[n,h,w,ci] with zero padding outside the image */
+static double conv_x(const vto_conv2d *d, const double *X, int64_t n, int64_t h, int64_t w, int64_t ci)
+{
+    if (h < 0 || h >= d->H || w < 0 || w >= d->W) return 0.0;
+    return X[((n * d->H + h) * d->W + w) * d->C + ci];
+}
+
+int vto_conv2d_fwd_f64(const vto_conv2d *d, int64_t Cout, const double *X, const double *Wt,
+                       const double *bias, double *Y, int order)
+{
+    int64_t Ho, Wo;
+    if (vto_conv2d_out_size(d, &Ho, &Wo) != VTO_OK || Cout < 0 || order < 0 || order > 2) return VTO_ERR_INVALID_ARG;
+    const int64_t taps = d->KH * d->KW * d->C;
+    for (int64_t n = 0; n < d->N; ++n)
+        for (int64_t ho = 0; ho < Ho; ++ho)
+            for (int64_t wo = 0; wo < Wo; ++wo)
+                for (int64_t co = 0; co < Cout; ++co) {
+                    double acc = 0.0;
+                    long double accl = 0.0L;
+                    for (int64_t s = 0; s < taps; ++s) {
+                        int64_t t = order == 1 ? taps - 1 - s : s;
+                        int64_t ci = t % d->C, kw = (t / d->C) % d->KW, kh = t / (d->C * d->KW);
+                        double x = conv_x(d, X, n, ho * d->stride_h - d->pad_h + kh * d->dil_h,
+                                          wo * d->stride_w - d->pad_w + kw * d->dil_w, ci);
+                        double w = Wt[((kh * d->KW + kw) * d->C + ci) * Cout + co];
+                        if (order == 2) accl += (long double)x * (long double)w;
+                        else { double p = x * w; acc = acc + p; }
+                    }
+                    double y;
+                    if (order == 2) { if (bias) accl += (long double)bias[co]; y = (double)accl; }
+                    else { y = acc; if (bias) y = y + bias[co]; }
+                    Y[((n * Ho + ho) * Wo + wo) * Cout + co] = y;
+                }
+    return VTO_OK;
+}
+
+int vto_conv2d_wgrad_f64(const vto_conv2d *d, int64_t Cout, const double *X, const double *dY,
+                         double *dW, int order)
+{
+    int64_t Ho, Wo;
+    if (vto_conv2d_out_size(d, &Ho, &Wo) != VTO_OK || Cout < 0 || order < 0 || order > 2) return VTO_ERR_INVALID_ARG;
+    const int64_t pos = d->N * Ho * Wo;
+    for (int64_t kh = 0; kh < d->KH; ++kh)
+        for (int64_t kw = 0; kw < d->KW; ++kw)
+            for (int64_t ci = 0; ci < d->C; ++ci)
+                for (int64_t co = 0; co < Cout; ++co) {
+                    double acc = 0.0;
+                    long double accl = 0.0L;
+                    for (int64_t s = 0; s < pos; ++s) {
+                        int64_t m = order == 1 ? pos - 1 - s : s;
+                        int64_t wo = m % Wo, ho = (m / Wo) % Ho, n = m / (Wo * Ho);
+                        double x = conv_x(d, X, n, ho * d->stride_h - d->pad_h + kh * d->dil_h,
+                                          wo * d->stride_w - d->pad_w + kw * d->dil_w, ci);
+                        double g = dY[m * Cout + co];
+                        if (order == 2) accl += (long double)x * (long double)g;
+                        else { double p = x * g; acc = acc + p; }
+                    }
+                    dW[((kh * d->KW + kw) * d->C + ci) * Cout + co] = order == 2 ? (double)accl : acc;
+                }
+    return VTO_OK;
+}
+
 /* Monotone integer image of a binary64 pattern: sign-magnitude -> two's complement. */
 static int64_t ord64(double y)
 {

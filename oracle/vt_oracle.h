@@ -76,6 +76,30 @@ int vto_gemm_f64(int transA, int transB, int64_t M, int64_t N, int64_t K, double
                  const double *A, int64_t lda, const double *B, int64_t ldb,
                  const double *bias, double *C, int64_t ldc, int order);
 
+/* A 2-D convolution layer, the other "intermediate computation" the method rounds after
+ * (Method, "rounding after intermediate computations, e.g. a convolution"; Experiments,
+ * ResNet-50; Algorithm "train" rounds forward outputs and gradients alike).  Cross-correlation
+ * with zero padding, as deep-learning layers define it; channels-last storage:
+ *   X [N][H][W][C],  Wt [KH][KW][C][Cout],  Y, dY [N][Ho][Wo][Cout],
+ *   Ho = (H + 2 pad_h - dil_h (KH-1) - 1) / stride_h + 1  (floor), Wo alike. */
+typedef struct vto_conv2d {
+    int64_t N, H, W, C, KH, KW, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+} vto_conv2d;
+
+int vto_conv2d_out_size(const vto_conv2d *d, int64_t *Ho, int64_t *Wo);
+
+/* Y[n,ho,wo,co] = sum_{kh,kw,ci} X[n, ho s - p + kh dil, wo s - p + kw dil, ci] Wt[kh,kw,ci,co]
+ * (+ bias[co]); taps that fall into the padding contribute nothing.
+ * order 0: taps in ascending (kh,kw,ci); 1: descending; 2: long double accumulation. */
+int vto_conv2d_fwd_f64(const vto_conv2d *d, int64_t Cout, const double *X, const double *Wt,
+                       const double *bias, double *Y, int order);
+
+/* Gradient of sum(Y * dY) with respect to the weights:
+ * dW[kh,kw,ci,co] = sum_{n,ho,wo} X[n, ho s - p + kh dil, wo s - p + kw dil, ci] dY[n,ho,wo,co].
+ * order 0: output positions in ascending (n,ho,wo); 1: descending; 2: long double. */
+int vto_conv2d_wgrad_f64(const vto_conv2d *d, int64_t Cout, const double *X, const double *dY,
+                         double *dW, int order);
+
 /* Threshold statistics over two results of the same operation (Algorithm "threshold",
  * collection loop): out[0] = number of elements whose FP32 roundings differ (bit patterns),
  * out[1] = 1 + max over those of max(D(y1), D(y2)) (0 when there are none),

@@ -20,6 +20,12 @@ CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-fno-unsafe-math-optimi
           "-shared", "-fPIC", "-std=c11", "-Wall", "-Wextra"]
 
 
+class Conv2d(C.Structure):
+    """vto_conv2d: geometry of a channels-last 2-D convolution."""
+    _fields_ = [(k, C.c_int64) for k in ("N", "H", "W", "C", "KH", "KW", "stride_h", "stride_w", "pad_h", "pad_w",
+                                         "dil_h", "dil_w")]
+
+
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (scalar, no contraction, no fast-math)."""
     hdr = os.path.join(_HERE, "vt_oracle.h")
@@ -54,6 +60,12 @@ def lib():
         L.vto_gemm_f64.restype = C.c_int
         L.vto_gemm_f64.argtypes = [C.c_int, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_double,
                                    dp, C.c_int64, dp, C.c_int64, dp, dp, C.c_int64, C.c_int]
+        L.vto_conv2d_out_size.restype = C.c_int
+        L.vto_conv2d_out_size.argtypes = [C.POINTER(Conv2d), C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+        L.vto_conv2d_fwd_f64.restype = C.c_int
+        L.vto_conv2d_fwd_f64.argtypes = [C.POINTER(Conv2d), C.c_int64, dp, dp, dp, dp, C.c_int]
+        L.vto_conv2d_wgrad_f64.restype = C.c_int
+        L.vto_conv2d_wgrad_f64.argtypes = [C.POINTER(Conv2d), C.c_int64, dp, dp, dp, C.c_int]
         L.vto_threshold_stats.restype = C.c_int
         L.vto_threshold_stats.argtypes = [dp, dp, C.c_uint64, u64p]
         _lib = L
@@ -136,6 +148,49 @@ def gemm_f64(A, B, *, transA=False, transB=False, alpha=1.0, bias=None, order=0)
     if rc != 0:
         raise ValueError(f"vto_gemm_f64: error {rc}")
     return Cm
+
+
+def conv2d_geometry(xshape, KH, KW, stride=1, pad=0, dil=1):
+    """(Conv2d, Ho, Wo) for an input of shape (N, H, W, C); stride/pad/dil: int or (h, w) pair."""
+    pair = lambda v: (int(v), int(v)) if np.isscalar(v) else (int(v[0]), int(v[1]))
+    (sh, sw), (ph, pw), (dh, dw) = pair(stride), pair(pad), pair(dil)
+    N, H, W, Cin = (int(v) for v in xshape)
+    d = Conv2d(N, H, W, Cin, int(KH), int(KW), sh, sw, ph, pw, dh, dw)
+    ho, wo = C.c_int64(), C.c_int64()
+    if lib().vto_conv2d_out_size(C.byref(d), C.byref(ho), C.byref(wo)) != 0:
+        raise ValueError("vto_conv2d_out_size: invalid geometry")
+    return d, ho.value, wo.value
+
+
+def conv2d_fwd(X, Wt, *, stride=1, pad=0, dil=1, bias=None, order=0):
+    """X (N,H,W,C), Wt (KH,KW,C,Cout) -> Y (N,Ho,Wo,Cout)."""
+    X, Wt = _f64(X), _f64(Wt)
+    assert X.ndim == 4 and Wt.ndim == 4 and Wt.shape[2] == X.shape[3]
+    d, Ho, Wo = conv2d_geometry(X.shape, Wt.shape[0], Wt.shape[1], stride, pad, dil)
+    Cout = Wt.shape[3]
+    if bias is not None:
+        bias = _f64(bias)
+        assert bias.size == Cout
+    Y = np.empty((X.shape[0], Ho, Wo, Cout), np.float64)
+    rc = lib().vto_conv2d_fwd_f64(C.byref(d), Cout, _p(X, C.c_double), _p(Wt, C.c_double), _p(bias, C.c_double),
+                                  _p(Y, C.c_double), int(order))
+    if rc != 0:
+        raise ValueError(f"vto_conv2d_fwd_f64: error {rc}")
+    return Y
+
+
+def conv2d_wgrad(X, dY, KH, KW, *, stride=1, pad=0, dil=1, order=0):
+    """X (N,H,W,C), dY (N,Ho,Wo,Cout) -> dW (KH,KW,C,Cout)."""
+    X, dY = _f64(X), _f64(dY)
+    d, Ho, Wo = conv2d_geometry(X.shape, KH, KW, stride, pad, dil)
+    assert dY.shape[:3] == (X.shape[0], Ho, Wo)
+    Cout = dY.shape[3]
+    dW = np.empty((KH, KW, X.shape[3], Cout), np.float64)
+    rc = lib().vto_conv2d_wgrad_f64(C.byref(d), Cout, _p(X, C.c_double), _p(dY, C.c_double), _p(dW, C.c_double),
+                                    int(order))
+    if rc != 0:
+        raise ValueError(f"vto_conv2d_wgrad_f64: error {rc}")
+    return dW
 
 
 def threshold_stats(y1, y2):
