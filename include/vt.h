@@ -131,6 +131,46 @@ int vt_gemm_f64_round_log(int transA, int transB, int64_t M, int64_t N, int64_t 
                           void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * A convolution layer fused with the trainer hook (the paper's other example of an
+ * "intermediate computation": Method, rounding after e.g. a convolution; Experiments, ResNet-50;
+ * Algorithm "train" rounds and logs forward outputs and gradients alike).  The layer is the GEMM
+ * above over the im2col matrix of the image, which is never materialised: the kernel forms the
+ * addresses while it loads.  Cross-correlation with zero padding, channels last:
+ *
+ *   VT_CONV_FORWARD      Y[n,ho,wo,co]   = sum_{kh,kw,ci} X[n, ho s - p + kh d, wo s - p + kw d, ci] Wt[kh,kw,ci,co] (+ bias[co])
+ *                        B = Wt [KH][KW][C][Cout];  C32 = Y [N][Ho][Wo][Cout]
+ *   VT_CONV_WEIGHT_GRAD  dW[kh,kw,ci,co] = sum_{n,ho,wo} X[n, ho s - p + kh d, wo s - p + kw d, ci] dY[n,ho,wo,co]
+ *                        B = dY [N][Ho][Wo][Cout];  C32 = dW [KH][KW][C][Cout];  bias must be NULL
+ *   Ho = floor((H + 2 pad_h - dil_h (KH - 1) - 1) / stride_h) + 1, Wo alike.
+ *
+ *   X            device, the image batch [N][H][W][C], dense, 8-byte aligned (16-byte alignment and
+ *                an even C let the kernel use 16-byte loads)
+ *   C32, C64_debug, variant, tau_ulp, log: as for vt_gemm_f64_round_log; outputs are dense; the
+ *                log index of an output is its linear index in C32.  variant 0 accumulates taps
+ *                (forward) or output positions (weight gradient) in ascending order, 1 descending.
+ *   ws           at least vt_workspace_bytes(VT_OP_GEMM_ROUND_LOG, M, N, K, 1) bytes for the
+ *                (M, N, K) that vt_conv2d_gemm_shape reports.
+ *   Limits: every field of the geometry below 2^24; N H W C, N Ho Wo and KH KW C below 2^31;
+ *   outputs below 2^32.
+ */
+typedef struct vt_conv2d {
+    int64_t N, H, W, C;                       /* image batch, channels last */
+    int64_t KH, KW;                           /* filter size */
+    int64_t stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+} vt_conv2d;
+
+#define VT_CONV_FORWARD 0
+#define VT_CONV_WEIGHT_GRAD 1
+
+int vt_conv2d_f64_round_log(int mode, const vt_conv2d *d, int64_t Cout, const double *X, const double *B,
+                            const double *bias, float *C32, double *C64_debug, int variant,
+                            double tau_ulp, const vt_log *log, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* The GEMM the convolution runs as: forward M = N Ho Wo, N = Cout, K = KH KW C; weight gradient
+ * M = KH KW C, N = Cout, K = N Ho Wo.  Host only. */
+int vt_conv2d_gemm_shape(const vt_conv2d *d, int64_t Cout, int mode, int64_t *M, int64_t *N, int64_t *K);
+
+/*
  * Statistics from which a per-layer threshold follows (Algorithm "threshold": the collection
  * loop over outputs y1, y2 of one layer computed on two devices; here two accumulation orders).
  *   y1, y2   device, n FP64 values each

@@ -16,6 +16,7 @@ _LIB_PATH = os.path.join(_HERE, "libvt_hip.so")
 _lib = None
 
 VT_OP_ROUND_LOG, VT_OP_ROUND_REPLAY, VT_OP_GEMM_ROUND_LOG, VT_OP_THRESHOLD_STATS = 0, 1, 2, 3
+VT_CONV_FORWARD, VT_CONV_WEIGHT_GRAD = 0, 1
 
 
 class VtError(RuntimeError):
@@ -24,6 +25,12 @@ class VtError(RuntimeError):
 
 class _VtLog(C.Structure):
     _fields_ = [("idx", C.c_void_p), ("dir", C.c_void_p), ("cap", C.c_uint64), ("count", C.c_void_p)]
+
+
+class Conv2d(C.Structure):
+    """vt_conv2d of include/vt.h: geometry of a channels-last 2-D convolution."""
+    _fields_ = [(k, C.c_int64) for k in ("N", "H", "W", "C", "KH", "KW", "stride_h", "stride_w", "pad_h", "pad_w",
+                                         "dil_h", "dil_w")]
 
 
 def library_path() -> str:
@@ -47,6 +54,11 @@ def load_library():
     L.vt_gemm_f64_round_log.restype = cint
     L.vt_gemm_f64_round_log.argtypes = [cint, cint, i64, i64, i64, dbl, vp, i64, i64, vp, i64, i64, vp, i64,
                                         vp, i64, i64, vp, cint, dbl, C.POINTER(_VtLog), vp, C.c_size_t, vp]
+    L.vt_conv2d_f64_round_log.restype = cint
+    L.vt_conv2d_f64_round_log.argtypes = [cint, C.POINTER(Conv2d), i64, vp, vp, vp, vp, vp, cint, dbl,
+                                          C.POINTER(_VtLog), vp, C.c_size_t, vp]
+    L.vt_conv2d_gemm_shape.restype = cint
+    L.vt_conv2d_gemm_shape.argtypes = [C.POINTER(Conv2d), i64, cint, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
     L.vt_threshold_stats.restype = cint
     L.vt_threshold_stats.argtypes = [vp, vp, u64, vp, vp]
     L.vt_workspace_bytes.restype = C.c_size_t
@@ -168,6 +180,33 @@ def vt_gemm_f64_round_log(transA: bool, transB: bool, M: int, N: int, K: int, al
         _ptr(bias, torch.float64), int(batch), _ptr(C32, torch.float32), int(ldc), int(strideC),
         _ptr(C64_debug, torch.float64), int(variant), float(tau_ulp), C.byref(clog),
         _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "vt_gemm_f64_round_log")
+
+
+def vt_conv2d_gemm_shape(d: Conv2d, Cout: int, mode: int):
+    """(M, N, K) of the GEMM the convolution runs as (sizes the workspace and the outputs)."""
+    M, N, K = C.c_int64(), C.c_int64(), C.c_int64()
+    _check(load_library().vt_conv2d_gemm_shape(C.byref(d), int(Cout), int(mode), C.byref(M), C.byref(N), C.byref(K)),
+           "vt_conv2d_gemm_shape")
+    return M.value, N.value, K.value
+
+
+def vt_conv2d_f64_round_log(mode: int, d: Conv2d, Cout: int, X: torch.Tensor, B: torch.Tensor, bias,
+                            C32: torch.Tensor, C64_debug, variant: int, tau_ulp: float, log: Log,
+                            ws: torch.Tensor, stream=None):
+    M, N, K = vt_conv2d_gemm_shape(d, Cout, mode)
+    if X.numel() < d.N * d.H * d.W * d.C:
+        raise VtError("X is smaller than N*H*W*C")
+    if B.numel() < K * N:
+        raise VtError("B is smaller than the geometry implies")
+    if C32.numel() < M * N or (C64_debug is not None and C64_debug.numel() < M * N):
+        raise VtError("output is smaller than the geometry implies")
+    if bias is not None and bias.numel() < N:
+        raise VtError("bias is shorter than Cout")
+    clog = log._c()
+    _check(load_library().vt_conv2d_f64_round_log(
+        int(mode), C.byref(d), int(Cout), _ptr(X, torch.float64), _ptr(B, torch.float64), _ptr(bias, torch.float64),
+        _ptr(C32, torch.float32), _ptr(C64_debug, torch.float64), int(variant), float(tau_ulp), C.byref(clog),
+        _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "vt_conv2d_f64_round_log")
 
 
 def vt_gemm_plan(M: int, N: int, K: int, batch: int = 1, ldc: int | None = None, strideC: int | None = None):

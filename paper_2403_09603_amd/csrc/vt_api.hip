@@ -64,6 +64,61 @@ int finish_log(const vt::Planes &pl, const vt_log *log, bool counted, hipStream_
     return hip_status(e);
 }
 
+// workspace check, plan, launch and log compaction shared by the GEMM and convolution entry points
+int run_gemm(vt::GemmArgs &g, const vt_log *log, void *ws, size_t ws_bytes, hipStream_t s)
+{
+    const int64_t M = g.M, N = g.N, K = g.K, batch = g.batch;
+    const uint64_t total = (uint64_t)M * (uint64_t)N * (uint64_t)batch;
+    const size_t need = vt_workspace_bytes(VT_OP_GEMM_ROUND_LOG, M, N, K, batch);
+    if (!ws || ws_bytes < need || !aligned(ws, 256)) return VT_ERR_WORKSPACE;
+    const vt::Planes pl = vt::planes_carve(ws, (uint64_t)M * (uint64_t)batch, (uint64_t)N);
+    const size_t planes = vt::planes_bytes((uint64_t)M * (uint64_t)batch, (uint64_t)N);
+    const vt::GemmPlan plan = vt::plan_gemm(M, N, K, batch, split_allowed(M, N, batch, g.ldc, g.strideC));
+    if (plan.splits > 1) {
+        // slabs -> fixed-order sum (alpha, bias) -> standalone round/log over the flat result
+        double *partial = (double *)((char *)ws + planes);
+        double *reduced = partial + (uint64_t)plan.splits * total;
+        void *ws_rl = (char *)partial + vt::gemm_split_bytes(M, N, batch, plan.splits);
+        mark_begin(s);
+        const hipError_t e2 = vt::launch_gemm_round_planes(g, plan, pl, partial, reduced, s);
+        mark_end(s);
+        if (e2 != hipSuccess) return VT_ERR_HIP;
+        return round_log_flat(reduced, total, g.thr, g.C32, log, ws_rl, s, /*mark=*/false);
+    }
+    mark_begin(s);
+    hipError_t e = vt::launch_gemm_round_planes(g, plan, pl, nullptr, nullptr, s);
+    mark_end(s);
+    if (e != hipSuccess) return VT_ERR_HIP;
+    return finish_log(pl, log, /*counted=*/false, s);
+}
+
+// Validates a convolution geometry and fills the internal descriptor (with the output size).
+// Limits keep every index the kernel forms inside 32 bits.
+bool conv_desc(const vt_conv2d *d, int64_t Cout, int mode, vt::ConvDesc *c)
+{
+    if (!d || Cout < 0 || (mode != VT_CONV_FORWARD && mode != VT_CONV_WEIGHT_GRAD)) return false;
+    const int64_t lim = (int64_t)1 << 24;
+    if (d->N < 0 || d->H < 0 || d->W < 0 || d->C < 0 || d->KH < 1 || d->KW < 1 || d->stride_h < 1 || d->stride_w < 1 ||
+        d->pad_h < 0 || d->pad_w < 0 || d->dil_h < 1 || d->dil_w < 1)
+        return false;
+    if (d->N >= lim || d->H >= lim || d->W >= lim || d->C >= lim || d->KH >= lim || d->KW >= lim || d->stride_h >= lim ||
+        d->stride_w >= lim || d->pad_h >= lim || d->pad_w >= lim || d->dil_h >= lim || d->dil_w >= lim || Cout >= lim)
+        return false;
+    if (d->dil_h * (d->KH - 1) >= lim || d->dil_w * (d->KW - 1) >= lim) return false;
+    const int64_t eh = d->H + 2 * d->pad_h - d->dil_h * (d->KH - 1) - 1;
+    const int64_t ew = d->W + 2 * d->pad_w - d->dil_w * (d->KW - 1) - 1;
+    c->N = d->N; c->H = d->H; c->W = d->W; c->C = d->C; c->KH = d->KH; c->KW = d->KW;
+    c->stride_h = d->stride_h; c->stride_w = d->stride_w; c->pad_h = d->pad_h; c->pad_w = d->pad_w;
+    c->dil_h = d->dil_h; c->dil_w = d->dil_w;
+    c->Ho = eh < 0 ? 0 : eh / d->stride_h + 1;
+    c->Wo = ew < 0 ? 0 : ew / d->stride_w + 1;
+    const unsigned __int128 two31 = (unsigned __int128)1 << 31;
+    if ((unsigned __int128)d->N * d->H * d->W * d->C >= two31) return false;          // image elements
+    if ((unsigned __int128)d->N * c->Ho * c->Wo >= two31) return false;               // im2col rows
+    if ((unsigned __int128)d->KH * d->KW * d->C >= two31) return false;               // taps
+    return true;
+}
+
 }  // namespace
 
 extern "C" {
@@ -158,32 +213,52 @@ int vt_gemm_f64_round_log(int transA, int transB, int64_t M, int64_t N, int64_t 
         if (lda < (transA ? M : K) || ldb < (transB ? K : N) || strideA < 0 || strideB < 0) return VT_ERR_INVALID_ARG;
     }
     if (C64_debug && !aligned(C64_debug, 8)) return VT_ERR_INVALID_ARG;
-    const size_t need = vt_workspace_bytes(VT_OP_GEMM_ROUND_LOG, M, N, K, batch);
-    if (!ws || ws_bytes < need || !aligned(ws, 256)) return VT_ERR_WORKSPACE;
-    const vt::Planes pl = vt::planes_carve(ws, (uint64_t)M * (uint64_t)batch, (uint64_t)N);
-    const size_t planes = vt::planes_bytes((uint64_t)M * (uint64_t)batch, (uint64_t)N);
-    const vt::GemmPlan plan = vt::plan_gemm(M, N, K, batch, split_allowed(M, N, batch, ldc, strideC));
     vt::GemmArgs g;
     g.transA = transA; g.transB = transB; g.M = M; g.N = N; g.K = K; g.alpha = alpha;
     g.A = A; g.lda = lda; g.strideA = strideA; g.B = B; g.ldb = ldb; g.strideB = strideB;
     g.bias = bias; g.batch = batch; g.C32 = C32; g.ldc = ldc; g.strideC = strideC;
     g.C64 = C64_debug; g.variant = variant; g.thr = thr;
-    if (plan.splits > 1) {
-        // slabs -> fixed-order sum (alpha, bias) -> standalone round/log over the flat result
-        double *partial = (double *)((char *)ws + planes);
-        double *reduced = partial + (uint64_t)plan.splits * total;
-        void *ws_rl = (char *)partial + vt::gemm_split_bytes(M, N, batch, plan.splits);
-        mark_begin(s);
-        const hipError_t e2 = vt::launch_gemm_round_planes(g, plan, pl, partial, reduced, s);
-        mark_end(s);
-        if (e2 != hipSuccess) return VT_ERR_HIP;
-        return round_log_flat(reduced, total, thr, C32, log, ws_rl, s, /*mark=*/false);
+    return run_gemm(g, log, ws, ws_bytes, s);
+}
+
+int vt_conv2d_gemm_shape(const vt_conv2d *d, int64_t Cout, int mode, int64_t *M, int64_t *N, int64_t *K)
+{
+    vt::ConvDesc c;
+    if (!M || !N || !K || !conv_desc(d, Cout, mode, &c)) return VT_ERR_INVALID_ARG;
+    const int64_t rows = c.N * c.Ho * c.Wo, taps = c.KH * c.KW * c.C;
+    *M = mode == VT_CONV_FORWARD ? rows : taps;
+    *N = Cout;
+    *K = mode == VT_CONV_FORWARD ? taps : rows;
+    return VT_OK;
+}
+
+int vt_conv2d_f64_round_log(int mode, const vt_conv2d *d, int64_t Cout, const double *X, const double *B,
+                            const double *bias, float *C32, double *C64_debug, int variant,
+                            double tau_ulp, const vt_log *log, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    const uint32_t thr = vt_thr_from_tau(tau_ulp);
+    vt::ConvDesc c;
+    if (thr == 0xFFFFFFFFu || !log_ok(log) || variant < 0 || variant > 1) return VT_ERR_INVALID_ARG;
+    if (!conv_desc(d, Cout, mode, &c)) return VT_ERR_INVALID_ARG;
+    if (mode == VT_CONV_WEIGHT_GRAD && bias) return VT_ERR_INVALID_ARG;
+    const int64_t rows = c.N * c.Ho * c.Wo, taps = c.KH * c.KW * c.C;
+    const int64_t M = mode == VT_CONV_FORWARD ? rows : taps, K = mode == VT_CONV_FORWARD ? taps : rows;
+    if ((unsigned __int128)M * (unsigned __int128)Cout >= ((unsigned __int128)1 << 32)) return VT_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (M * Cout == 0) {
+        const vt::Planes pl = vt::planes_carve(ws, 0, 0);
+        const vt::LogOut lo{log->idx, log->dir, log->cap, log->count};
+        return hip_status(vt::launch_seg_scan(pl, lo, s));
     }
-    mark_begin(s);
-    hipError_t e = vt::launch_gemm_round_planes(g, plan, pl, nullptr, nullptr, s);
-    mark_end(s);
-    if (e != hipSuccess) return VT_ERR_HIP;
-    return finish_log(pl, log, /*counted=*/false, s);
+    if (!C32 || !aligned(C32, 4) || (C64_debug && !aligned(C64_debug, 8))) return VT_ERR_INVALID_ARG;
+    if (K > 0 && (!X || !B || !aligned(X, 8) || !aligned(B, 8))) return VT_ERR_INVALID_ARG;
+    vt::GemmArgs g;
+    g.conv = &c; g.conv_wgrad = mode == VT_CONV_WEIGHT_GRAD;
+    g.transA = g.conv_wgrad ? 1 : 0; g.transB = 0; g.M = M; g.N = Cout; g.K = K; g.alpha = 1.0;
+    g.A = X; g.lda = 0; g.strideA = 0; g.B = B; g.ldb = Cout; g.strideB = 0;
+    g.bias = bias; g.batch = 1; g.C32 = C32; g.ldc = Cout; g.strideC = 0;
+    g.C64 = C64_debug; g.variant = variant; g.thr = thr;
+    return run_gemm(g, log, ws, ws_bytes, s);
 }
 
 int vt_threshold_stats(const double *y1, const double *y2, uint64_t n, uint64_t *out, void *hip_stream)

@@ -188,4 +188,84 @@ __device__ __forceinline__ void wave_lds_fence()
 
 constexpr uint64_t kOneBits = 0x3FF0000000000000ull;   // 1.0: padding value, never logged
 
+// ---- implicit im2col index arithmetic (convolution as GEMM) --------------------------------
+
+// Implicit im2col view of a channels-last image X[N][H][W][C] (A operand modes 2 and 3): the
+// matrix element (row m = (n, ho, wo), tap kc = (kh, kw, ci)) is X[n, ho s - p + kh d, wo s - p + kw d, ci],
+// zero in the padding.  Indices are split with a reciprocal multiply and one correction step.
+struct ConvGeom {
+    int32_t H, W, C, Wo, HoWo, KWC;
+    int32_t sh, sw, ph, pw, dh, dw;
+    int32_t vec;                     // taps (kc, kc + 1), kc even, are one aligned 16-byte load (C even)
+    uint32_t rows, taps;             // N Ho Wo and KH KW C
+    double inv_HoWo, inv_Wo, inv_KWC, inv_C;
+};
+
+constexpr int32_t kNowhere = -(1 << 30);        // row / tap coordinate that fails every bounds test
+
+// q = x / d, r = x % d for d >= 1: the double product is within one of the quotient.
+static __host__ __device__ __forceinline__ void divmod_u32(uint32_t x, uint32_t d, double inv, uint32_t &q, uint32_t &r)
+{
+    q = (uint32_t)((double)x * inv);
+    int32_t rem = (int32_t)(x - q * d);
+    if (rem < 0) { --q; rem += (int32_t)d; }
+    else if ((uint32_t)rem >= d) { ++q; rem -= (int32_t)d; }
+    r = (uint32_t)rem;
+}
+
+struct RowPos { int32_t base, h0, w0; };        // element offset of X[n, h0, w0, 0]; top-left tap position
+struct TapPos { int32_t off, hh, ww; };         // (hh W + ww) C + ci with hh = kh dil_h, ww = kw dil_w
+
+static __host__ __device__ __forceinline__ RowPos conv_row(const ConvGeom &c, uint32_t m)
+{
+    uint32_t n, rem, ho, wo;
+    divmod_u32(m, (uint32_t)c.HoWo, c.inv_HoWo, n, rem);
+    divmod_u32(rem, (uint32_t)c.Wo, c.inv_Wo, ho, wo);
+    RowPos r;
+    r.h0 = (int32_t)ho * c.sh - c.ph;
+    r.w0 = (int32_t)wo * c.sw - c.pw;
+    r.base = (int32_t)(((n * (uint32_t)c.H + (uint32_t)r.h0) * (uint32_t)c.W + (uint32_t)r.w0) * (uint32_t)c.C);
+    if (m >= c.rows) r.h0 = kNowhere;
+    return r;
+}
+
+static __host__ __device__ __forceinline__ TapPos conv_tap(const ConvGeom &c, uint32_t kc)
+{
+    uint32_t kh, rem, kw, ci;
+    divmod_u32(kc, (uint32_t)c.KWC, c.inv_KWC, kh, rem);
+    divmod_u32(rem, (uint32_t)c.C, c.inv_C, kw, ci);
+    TapPos t;
+    t.hh = (int32_t)kh * c.dh;
+    t.ww = (int32_t)kw * c.dw;
+    t.off = (int32_t)(((uint32_t)t.hh * (uint32_t)c.W + (uint32_t)t.ww) * (uint32_t)c.C + ci);
+    if (kc >= c.taps) t.hh = kNowhere;
+    return t;
+}
+
+
+static inline ConvGeom conv_geom(int64_t N, int64_t H, int64_t W, int64_t C, int64_t KH, int64_t KW, int64_t sh,
+                                 int64_t sw, int64_t ph, int64_t pw, int64_t dh, int64_t dw, int64_t Ho, int64_t Wo,
+                                 bool vec)
+{
+    ConvGeom c;
+    c.H = (int32_t)H; c.W = (int32_t)W; c.C = (int32_t)C; c.Wo = (int32_t)Wo;
+    c.HoWo = (int32_t)(Ho * Wo); c.KWC = (int32_t)(KW * C);
+    c.sh = (int32_t)sh; c.sw = (int32_t)sw; c.ph = (int32_t)ph; c.pw = (int32_t)pw; c.dh = (int32_t)dh; c.dw = (int32_t)dw;
+    c.vec = vec ? 1 : 0;
+    c.rows = (uint32_t)(N * Ho * Wo); c.taps = (uint32_t)(KH * KW * C);
+    c.inv_HoWo = 1.0 / (double)(c.HoWo > 0 ? c.HoWo : 1); c.inv_Wo = 1.0 / (double)(c.Wo > 0 ? c.Wo : 1);
+    c.inv_KWC = 1.0 / (double)(c.KWC > 0 ? c.KWC : 1); c.inv_C = 1.0 / (double)(c.C > 0 ? c.C : 1);
+    return c;
+}
+
+// Element offset of the im2col matrix entry (row m, tap kc) in the image, or -1 when it is a
+// padding zero or lies outside the matrix: what conv_gather loads, as one function.
+static __host__ __device__ __forceinline__ int64_t conv_element(const ConvGeom &c, uint32_t m, uint32_t kc)
+{
+    const RowPos r = conv_row(c, m);
+    const TapPos t = conv_tap(c, kc);
+    const bool ok = (uint32_t)(r.h0 + t.hh) < (uint32_t)c.H && (uint32_t)(r.w0 + t.ww) < (uint32_t)c.W;
+    return ok ? (int64_t)(r.base + t.off) : -1;
+}
+
 }  // namespace vt

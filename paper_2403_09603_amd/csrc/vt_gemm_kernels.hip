@@ -45,6 +45,7 @@ constexpr int BK = 16;
 constexpr int kPad = 18;
 
 struct GemmParams {
+    ConvGeom conv;
     const double *A, *B, *bias;
     float *C32;
     double *C64;                                // optional dense FP64 copy (fused path only)
@@ -55,6 +56,28 @@ struct GemmParams {
     uint32_t thr, wpr, tilesM, tilesN, tiles_per_split, total_blocks;
     int variant, vecA, vecB, splits, kt_per_split;
 };
+
+// Two neighbouring taps of one row.  The load is unconditional (from X[0] when the element lies
+// in the padding or outside the matrix) and the value is selected afterwards, so the loop body
+// stays free of branches.
+template <bool VEC>
+__device__ __forceinline__ d2 conv_gather(const double *__restrict__ X, const ConvGeom &c, const RowPos &r,
+                                          const TapPos &t0, const TapPos &t1)
+{
+    const bool ok0 = (uint32_t)(r.h0 + t0.hh) < (uint32_t)c.H && (uint32_t)(r.w0 + t0.ww) < (uint32_t)c.W;
+    d2 v;
+    if (VEC) {
+        const d2 x = *(const d2 *)(X + (ok0 ? r.base + t0.off : 0));
+        v.x = ok0 ? x.x : 0.0;
+        v.y = ok0 ? x.y : 0.0;
+    } else {
+        const bool ok1 = (uint32_t)(r.h0 + t1.hh) < (uint32_t)c.H && (uint32_t)(r.w0 + t1.ww) < (uint32_t)c.W;
+        const double a = X[ok0 ? r.base + t0.off : 0], b = X[ok1 ? r.base + t1.off : 0];
+        v.x = ok0 ? a : 0.0;
+        v.y = ok1 ? b : 0.0;
+    }
+    return v;
+}
 
 // Global -> registers for one R x 16 operand tile (R = 64 or 128 rows/columns of the output).
 // KC = the operand is contiguous along k (element (mn, k) at base[mn * ld + k]); otherwise
@@ -129,9 +152,14 @@ __device__ __forceinline__ void store_tile(double *__restrict__ S, const d2 (&re
     }
 }
 
-template <bool KCA, bool KCB, int WM, int TM>
+// AM, the A operand: 0 = stored transposed (contiguous along m), 1 = row-major (contiguous along
+// k), 2 = implicit im2col of an image, rows x taps (convolution forward), 3 = its transpose,
+// taps x rows (convolution weight gradient).  KCB: B is stored transposed (contiguous along k).
+template <int AM, bool KCB, int WM, int TM>
 __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmParams p)
 {
+    constexpr bool KCA = AM == 1 || AM == 2;
+    constexpr bool GA = AM >= 2;
     constexpr int WN = 4 / WM;
     constexpr int BM = WM * 16 * TM, BN = WN * 64;
     constexpr int PA = BM + kPad, PB = BN + kPad;          // LDS pitches
@@ -177,7 +205,7 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
     const int nkt = kt1 > kt0 ? kt1 - kt0 : 0;
     // whole-tile operands take the unguarded loader (a uniform choice per k step)
     // (the per-thread offsets of the unguarded loader are 32-bit: pitches up to 2^31 / 8 / 128)
-    const bool fastA = p.vecA && bm + BM <= p.M && p.lda < (1 << 21);
+    const bool fastA = GA ? p.conv.vec != 0 : p.vecA && bm + BM <= p.M && p.lda < (1 << 21);
     const bool fastB = p.vecB && bn + BN <= p.N && p.ldb < (1 << 21);
     const char *baseA = (const char *)(A + (KCA ? bm * p.lda : bm));
     const char *baseB = (const char *)(B + (KCB ? bn * p.ldb : bn));
@@ -190,17 +218,50 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
     // the operands; straight-line code, so the load counter waits are exact and the newest
     // fetch stays in flight across the LDS stores), and with the guarded loader for edges.
     d2 ra0[BM / 32], rb0[BN / 32], ra1[BM / 32], rb1[BN / 32];
+    // Implicit im2col: the part of the address that belongs to this thread for the whole loop --
+    // its rows of the image matrix (forward) or its pair of taps (weight gradient).
+    RowPos rowp[AM == 2 ? BM / 32 : 1];
+    TapPos tap0{0, 0, 0}, tap1{0, 0, 0};
+    if constexpr (AM == 2) {
+#pragma unroll
+        for (int j = 0; j < BM / 32; ++j) rowp[j] = conv_row(p.conv, (uint32_t)bm + (t >> 3) + 32 * j);
+    }
+    if constexpr (AM == 3) {
+        const uint32_t kc = (uint32_t)bm + (t % (BM / 2)) * 2;
+        tap0 = conv_tap(p.conv, kc);
+        tap1 = conv_tap(p.conv, kc + 1);
+    }
+    auto gather_tile = [&](auto vec_tag, int64_t k0, d2 (&ra)[BM / 32]) {
+        constexpr bool VEC = decltype(vec_tag)::value;
+        if constexpr (AM == 2) {
+            const uint32_t kc = (uint32_t)k0 + (t & 7) * 2;
+            const TapPos t0 = conv_tap(p.conv, kc);
+            const TapPos t1 = VEC ? t0 : conv_tap(p.conv, kc + 1);
+#pragma unroll
+            for (int j = 0; j < BM / 32; ++j) ra[j] = conv_gather<VEC>(p.A, p.conv, rowp[j], t0, t1);
+        } else if constexpr (AM == 3) {
+#pragma unroll
+            for (int j = 0; j < BM / 32; ++j) {
+                const RowPos r = conv_row(p.conv, (uint32_t)k0 + t / (BM / 2) + (512 / BM) * j);
+                ra[j] = conv_gather<VEC>(p.A, p.conv, r, tap0, tap1);
+            }
+        }
+    };
     auto main_loop = [&](auto fast_tag) {
         constexpr bool FAST = decltype(fast_tag)::value;
         auto fetch = [&](int it, d2 (&ra)[BM / 32], d2 (&rb)[BN / 32]) {   // `it`-th step in this variant's order
             const int64_t k0 = (int64_t)(p.variant ? kt1 - 1 - it : kt0 + it) * BK;
-            if constexpr (FAST) {
+            if constexpr (GA) {
+                if constexpr (FAST) gather_tile(std::true_type{}, k0, ra);
+                else if (p.conv.vec) gather_tile(std::true_type{}, k0, ra);
+                else gather_tile(std::false_type{}, k0, ra);
+            } else if constexpr (FAST) {
                 load_tile_fast<KCA, BM>(baseA, p.lda, k0, offA, ra);
-                load_tile_fast<KCB, BN>(baseB, p.ldb, k0, offB, rb);
             } else {
                 load_tile<KCA, BM>(A, p.lda, bm, k0, p.M, p.K, p.vecA, ra);
-                load_tile<KCB, BN>(B, p.ldb, bn, k0, p.N, p.K, p.vecB, rb);
             }
+            if constexpr (FAST) load_tile_fast<KCB, BN>(baseB, p.ldb, k0, offB, rb);
+            else load_tile<KCB, BN>(B, p.ldb, bn, k0, p.N, p.K, p.vecB, rb);
         };
         // one k step: multiply the tile in LDS stage `cur`; start the fetch of tile it+2 into (la, lb);
         // move tile it+1 from (sa, sb) to the other stage in the shadow of the last MFMA group
@@ -355,13 +416,16 @@ constexpr TileShape kShapes[4] = {{2, 4, 128, 128, 0.85, 2}, {2, 2, 64, 128, 0.7
                                   {4, 1, 64, 64, 0.62, 3}};
 
 template <int WM, int TM>
-hipError_t launch_shape(const GemmParams &p, bool kca, bool kcb, hipStream_t s)
+hipError_t launch_shape(const GemmParams &p, int am, bool kcb, hipStream_t s)
 {
     const dim3 grid(p.total_blocks), block(256);
-    if (kca && kcb) gemm_round_planes_kernel<true, true, WM, TM><<<grid, block, 0, s>>>(p);
-    else if (kca && !kcb) gemm_round_planes_kernel<true, false, WM, TM><<<grid, block, 0, s>>>(p);
-    else if (!kca && kcb) gemm_round_planes_kernel<false, true, WM, TM><<<grid, block, 0, s>>>(p);
-    else gemm_round_planes_kernel<false, false, WM, TM><<<grid, block, 0, s>>>(p);
+    if (am == 2 && !kcb) gemm_round_planes_kernel<2, false, WM, TM><<<grid, block, 0, s>>>(p);
+    else if (am == 3 && !kcb) gemm_round_planes_kernel<3, false, WM, TM><<<grid, block, 0, s>>>(p);
+    else if (am == 1 && kcb) gemm_round_planes_kernel<1, true, WM, TM><<<grid, block, 0, s>>>(p);
+    else if (am == 1 && !kcb) gemm_round_planes_kernel<1, false, WM, TM><<<grid, block, 0, s>>>(p);
+    else if (am == 0 && kcb) gemm_round_planes_kernel<0, true, WM, TM><<<grid, block, 0, s>>>(p);
+    else if (am == 0 && !kcb) gemm_round_planes_kernel<0, false, WM, TM><<<grid, block, 0, s>>>(p);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
@@ -423,13 +487,24 @@ hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, con
     p.total_blocks = (uint32_t)total;
     p.vecA = ((uintptr_t)g.A % 16 == 0) && (g.lda % 2 == 0) && (g.strideA % 2 == 0);
     p.vecB = ((uintptr_t)g.B % 16 == 0) && (g.ldb % 2 == 0) && (g.strideB % 2 == 0);
-    const bool kca = !g.transA, kcb = g.transB != 0;
+    const bool kcb = g.transB != 0;
+    int am = g.transA ? 0 : 1;
+    p.conv = ConvGeom{};
+    if (g.conv) {
+        // A is the image; the matrix the kernel multiplies is its im2col view (transposed for the
+        // weight gradient).  The caller has checked the geometry (sizes below 2^31).
+        const ConvDesc &d = *g.conv;
+        p.conv = conv_geom(d.N, d.H, d.W, d.C, d.KH, d.KW, d.stride_h, d.stride_w, d.pad_h, d.pad_w, d.dil_h, d.dil_w,
+                           d.Ho, d.Wo, (d.C % 2 == 0) && ((uintptr_t)g.A % 16 == 0));
+        am = g.conv_wgrad ? 3 : 2;
+        p.vecA = p.conv.vec;
+    }
     hipError_t e;
     switch (plan.shape) {
-    case 0: e = launch_shape<2, 4>(p, kca, kcb, s); break;
-    case 1: e = launch_shape<2, 2>(p, kca, kcb, s); break;
-    case 2: e = launch_shape<4, 2>(p, kca, kcb, s); break;
-    default: e = launch_shape<4, 1>(p, kca, kcb, s); break;
+    case 0: e = launch_shape<2, 4>(p, am, kcb, s); break;
+    case 1: e = launch_shape<2, 2>(p, am, kcb, s); break;
+    case 2: e = launch_shape<4, 2>(p, am, kcb, s); break;
+    default: e = launch_shape<4, 1>(p, am, kcb, s); break;
     }
     if (e != hipSuccess || plan.splits <= 1) return e;
     const uint64_t slab = (uint64_t)g.M * g.N * g.batch;

@@ -55,7 +55,15 @@ hipError_t launch_replay(const double *x, uint64_t n, const uint32_t *idx, const
 
 hipError_t launch_stats(const double *y1, const double *y2, uint64_t n, uint64_t *out, hipStream_t s);
 
+// Geometry of a channels-last convolution whose image the GEMM kernel reads through an implicit
+// im2col view (all sizes already validated by the caller).
+struct ConvDesc {
+    int64_t N, H, W, C, KH, KW, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, Ho, Wo;
+};
+
 struct GemmArgs {
+    const ConvDesc *conv = nullptr;   // non-null: A is an image X[N][H][W][C]; M, K describe its im2col matrix
+    bool conv_wgrad = false;          // the matrix is used transposed (taps x rows): weight gradient
     int transA, transB;
     int64_t M, N, K;
     double alpha;

@@ -95,3 +95,35 @@ def gpu_gemm(A, B, *, transA=False, transB=False, alpha=1.0, bias=None, tau=0.0,
     return {"C32": C32.cpu().numpy()[:, :, :N].reshape(batch, M, N), "C32_full": C32.cpu().numpy(),
             "C64": C64.cpu().numpy() if want_c64 else None,
             "idx": u32(log.idx)[:k].copy(), "dir": u32(log.dir)[:(k + 31) // 32].copy(), "count": count}
+
+
+def gpu_conv(mode, X, B, KH, KW, *, stride=1, pad=0, dil=1, bias=None, tau=0.0, variant=0, misalign=False):
+    """mode 0: forward, B = weights (KH,KW,C,Cout); mode 1: weight gradient, B = dY (N,Ho,Wo,Cout).
+    X is (N,H,W,C).  misalign=True puts X on an 8-byte (not 16-byte) boundary."""
+    pair = lambda v: (int(v), int(v)) if np.isscalar(v) else (int(v[0]), int(v[1]))
+    (sh, sw), (ph, pw), (dh, dw) = pair(stride), pair(pad), pair(dil)
+    X = np.ascontiguousarray(X, np.float64)
+    B = np.ascontiguousarray(B, np.float64)
+    N, H, W, Cin = X.shape
+    Cout = B.shape[-1]
+    d = vt.Conv2d(N, H, W, Cin, KH, KW, sh, sw, ph, pw, dh, dw)
+    M, Nn, K = vt.vt_conv2d_gemm_shape(d, Cout, mode)
+    if misalign:
+        buf = torch.empty(X.size + 1, dtype=torch.float64, device=DEV)
+        Xd = buf[1:]
+        Xd.copy_(torch.from_numpy(X.ravel()))
+        assert Xd.data_ptr() % 16 == 8
+    else:
+        Xd = dev(X.ravel())
+    Bd = dev(B.ravel())
+    C32 = torch.full((max(M * Nn, 1),), float("nan"), dtype=torch.float32, device=DEV)
+    C64 = torch.empty(max(M * Nn, 1), dtype=torch.float64, device=DEV)
+    log = vt.alloc_log(M * Nn)
+    ws = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG, M, Nn, K, 1))
+    bias_d = dev(np.ascontiguousarray(bias, np.float64)) if bias is not None else None
+    vt.vt_conv2d_f64_round_log(mode, d, Cout, Xd, Bd, bias_d, C32, C64, variant, tau, log, ws)
+    torch.cuda.synchronize()
+    count = int(log.count.item())
+    return {"C32": C32.cpu().numpy()[:M * Nn].reshape(M, Nn), "C64": C64.cpu().numpy()[:M * Nn].reshape(M, Nn),
+            "idx": u32(log.idx)[:count].copy(), "dir": u32(log.dir)[:(count + 31) // 32].copy(), "count": count,
+            "shape": (M, Nn, K)}

@@ -12,3 +12,13 @@ extern "C" void h_directed(const uint64_t *bits, uint64_t n, uint32_t dir, uint3
 {
     for (uint64_t i = 0; i < n; ++i) y[i] = vt::directed(bits[i], dir);
 }
+
+// im2col index arithmetic of the convolution loader: offsets[m * taps + kc] = image element or -1
+extern "C" void h_im2col_offsets(const int64_t *g /* N H W C KH KW sh sw ph pw dh dw Ho Wo */, uint32_t row0, uint32_t rows_to_do,
+                                 uint32_t tap0, uint32_t taps_to_do, int64_t *offsets)
+{
+    const vt::ConvGeom c = vt::conv_geom(g[0], g[1], g[2], g[3], g[4], g[5], g[6], g[7], g[8], g[9], g[10], g[11], g[12],
+                                         g[13], false);
+    for (uint32_t m = 0; m < rows_to_do; ++m)
+        for (uint32_t k = 0; k < taps_to_do; ++k) offsets[(uint64_t)m * taps_to_do + k] = vt::conv_element(c, row0 + m, tap0 + k);
+}

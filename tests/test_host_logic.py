@@ -85,6 +85,60 @@ def test_argument_validation_happens_on_the_host(hiplib):
     assert hiplib.vt_strerror(INVALID).decode() == "invalid argument"
 
 
+def test_conv_geometry_and_validation_on_the_host(hiplib):
+    import paper_2403_09603_amd.binding as b
+    cnt = (C.c_uint64 * 1)()
+    log = b._VtLog(None, None, 0, C.addressof(cnt))
+    fake = C.c_void_p(0x1000)
+    INVALID, WORKSPACE = 1, 2
+    # GEMM shapes of the ResNet-50 geometry at batch 64 against the oracle's output size
+    for (H, Cin, K, s, p, Cout) in [(224, 3, 7, 2, 3, 64), (56, 64, 3, 1, 1, 64), (56, 256, 1, 2, 0, 512),
+                                    (14, 256, 3, 1, 1, 256), (7, 512, 3, 1, 1, 512)]:
+        d = b.Conv2d(64, H, H, Cin, K, K, s, s, p, p, 1, 1)
+        _, Ho, Wo = vo.conv2d_geometry((64, H, H, Cin), K, K, s, p, 1)
+        assert b.vt_conv2d_gemm_shape(d, Cout, b.VT_CONV_FORWARD) == (64 * Ho * Wo, Cout, K * K * Cin)
+        assert b.vt_conv2d_gemm_shape(d, Cout, b.VT_CONV_WEIGHT_GRAD) == (K * K * Cin, Cout, 64 * Ho * Wo)
+    f = hiplib.vt_conv2d_f64_round_log
+    good = b.Conv2d(2, 8, 8, 4, 3, 3, 1, 1, 1, 1, 1, 1)
+    def call(d=good, mode=0, Cout=8, X=fake, bias=None, variant=0, tau=0.1, ws=fake, wsb=1 << 20):
+        return f(mode, C.byref(d), Cout, X, fake, bias, fake, None, variant, tau, C.byref(log), ws, wsb, None)
+    assert call(mode=2) == INVALID and call(variant=3) == INVALID and call(tau=0.6) == INVALID
+    assert call(X=None) == INVALID and call(mode=1, bias=fake) == INVALID and call(Cout=-1) == INVALID
+    for field, val in (("KH", 0), ("stride_w", 0), ("dil_h", 0), ("pad_w", -1), ("N", -1), ("H", 1 << 24)):
+        bad = b.Conv2d(2, 8, 8, 4, 3, 3, 1, 1, 1, 1, 1, 1)
+        setattr(bad, field, val)
+        assert call(d=bad) == INVALID, field
+    assert call(d=b.Conv2d(1 << 12, 1 << 10, 1 << 10, 4, 3, 3, 1, 1, 1, 1, 1, 1)) == INVALID   # image >= 2^31 elements
+    assert call(ws=None, wsb=0) == WORKSPACE and call(wsb=16) == WORKSPACE
+
+
+def test_im2col_index_arithmetic_on_host(harith):
+    """The loader's row/tap decomposition (reciprocal multiply + correction) against plain integer
+    arithmetic, including rows and taps past the end of the matrix and geometries near the limits."""
+    geoms = [(2, 9, 11, 3, 3, 3, 1, 1, 1, 1, 1, 1), (1, 12, 10, 2, 7, 7, 2, 2, 3, 3, 1, 1), (3, 8, 7, 4, 1, 1, 2, 2, 0, 0, 1, 1),
+             (1, 10, 13, 3, 3, 2, 2, 1, 1, 0, 1, 2), (1, 9, 9, 2, 3, 3, 1, 1, 2, 2, 2, 2), (64, 224, 224, 3, 7, 7, 2, 2, 3, 3, 1, 1),
+             (5, 1 << 12, 1 << 12, 25, 3, 3, 1, 1, 1, 1, 1, 1)]
+    for geo in geoms:
+        N, H, W, Cin, KH, KW, sh, sw, ph, pw, dh, dw = geo
+        Ho = (H + 2 * ph - dh * (KH - 1) - 1) // sh + 1
+        Wo = (W + 2 * pw - dw * (KW - 1) - 1) // sw + 1
+        rows, taps = N * Ho * Wo, KH * KW * Cin
+        arr = np.array(list(geo) + [Ho, Wo], np.int64)
+        # the first rows/taps and the last ones (plus some past the end of the matrix)
+        for row0, tap0 in ((0, 0), (max(rows - 300, 0), max(taps - 150, 0))):
+            nr, nt = min(rows - row0 + 40, 400), min(taps - tap0 + 20, 200)
+            out = np.empty((nr, nt), np.int64)
+            harith.h_im2col_offsets(arr.ctypes.data_as(C.POINTER(C.c_int64)), C.c_uint32(row0), C.c_uint32(nr),
+                                    C.c_uint32(tap0), C.c_uint32(nt), out.ctypes.data_as(C.POINTER(C.c_int64)))
+            m, k = np.meshgrid(row0 + np.arange(nr), tap0 + np.arange(nt), indexing="ij")
+            n_, ho, wo = m // (Ho * Wo), (m // Wo) % Ho, m % Wo
+            kh, kw, ci = k // (KW * Cin), (k // Cin) % KW, k % Cin
+            h, w = ho * sh - ph + kh * dh, wo * sw - pw + kw * dw
+            ok = (m < rows) & (k < taps) & (h >= 0) & (h < H) & (w >= 0) & (w < W)
+            want = np.where(ok, ((n_ * H + h) * W + w) * Cin + ci, -1)
+            assert np.array_equal(out, want), (geo, row0, tap0)
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     import paper_2403_09603_amd.binding as b
     monkeypatch.setattr(b, "_lib", None)
