@@ -152,6 +152,20 @@ __device__ __forceinline__ void store_tile(double *__restrict__ S, const d2 (&re
     }
 }
 
+// Bits [16 q, 16 q + 16) of two wave-uniform 64-bit masks, side by side: a's in the low half.
+__device__ __forceinline__ uint32_t pack16(uint64_t a, uint64_t b, int q)
+{
+    const uint32_t x = (uint32_t)(a >> (32 * (q >> 1))), y = (uint32_t)(b >> (32 * (q >> 1)));
+    return (q & 1) ? (x >> 16) | (y & 0xFFFF0000u) : (x & 0xFFFFu) | (y << 16);
+}
+
+// v with lane `ln` (a compile-time constant) replaced by the wave-uniform value s.
+__device__ __forceinline__ int write_lane(uint32_t s, int ln, int v)
+{
+    asm("v_writelane_b32 %0, %1, %2" : "+v"(v) : "s"(s), "n"(ln));
+    return v;
+}
+
 // AM, the A operand: 0 = stored transposed (contiguous along m), 1 = row-major (contiguous along
 // k), 2 = implicit im2col of an image, rows x taps (convolution forward), 3 = its transpose,
 // taps x rows (convolution weight gradient).  KCB: B is stored transposed (contiguous along k).
@@ -166,7 +180,8 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
     constexpr int SA = BK * PA, SB = BK * PB;              // doubles per stage
     __shared__ double lds[2 * SA + 2 * SB];                // A0 A1 B0 B1
     double *const ldsA = lds, *const ldsB = lds + 2 * SA;
-    const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
+    const int t = threadIdx.x, lane = t & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(t >> 6);      // wave-uniform: keeps tile addresses in scalar registers
     const int wm = wv / WN, wn = wv % WN;
 
     // Workgroup -> (split, tile).  Consecutive workgroup ids land on different XCDs (8 of them,
@@ -337,6 +352,84 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
 
     // ---- epilogue: alpha, bias, round, decide, store, bit-planes -------------------------
     const uint64_t colword = (uint64_t)col0 >> 6;
+    // Whole tile inside the matrix (and pitches that fit 32-bit lane offsets): no guards, every
+    // address is a wave-uniform base plus a lane offset that never changes, the four ballots of
+    // a row group are transposed into plane words with scalar pack operations, and the rare
+    // values that need the integer rounding path are handled once per group of four.
+    if (bm + BM <= p.M && bn + BN <= p.N && p.ldc < (1 << 26) && p.N < (1 << 25)) {
+        auto full = [&](auto has64_tag) {
+            constexpr bool HAS64 = decltype(has64_tag)::value;
+            char *c32_row = (char *)(p.C32 + (int64_t)b * p.strideC + row0 * p.ldc + col0);      // uniform, row 4 r of block i
+            char *c64_row = HAS64 ? (char *)(p.C64 + ((int64_t)b * p.M + row0) * p.N + col0) : nullptr;
+            const uint32_t step32 = (uint32_t)p.ldc * 16u, step64 = (uint32_t)p.N * 32u;         // four rows further
+            const uint32_t off32 = ((uint32_t)g * (uint32_t)p.ldc + (uint32_t)c16) * 4u;
+            const uint32_t off64 = ((uint32_t)g * (uint32_t)p.N + (uint32_t)c16) * 8u;
+            char *wl_blk = (char *)(p.pl_logged + ((uint64_t)b * (uint64_t)p.M + (uint64_t)row0) * p.wpr + colword);
+            char *wd_blk = (char *)(p.pl_dir + ((uint64_t)b * (uint64_t)p.M + (uint64_t)row0) * p.wpr + colword);
+            const uint32_t offw = (uint32_t)(lane & 15) * p.wpr * 8u;                            // lane = row of the block
+            double bias_f[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bias_f[j] = p.bias ? p.bias[col0 + j * 16 + c16] : -0.0;   // x + (-0) = x
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                int wl_lo = 0, wl_hi = 0, wd_lo = 0, wd_hi = 0;       // lane q: plane words of row q of this block
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    double c[4];
+                    uint32_t yb[4];
+                    uint64_t lg[4], dr[4], slow[4], any_slow = 0;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        c[j] = p.alpha * acc[i][j][r] + bias_f[j];
+                        const FastDecision f = decide_fast(c[j]);
+                        yb[j] = __float_as_uint(f.y);
+                        lg[j] = __ballot(f.D < p.thr);
+                        dr[j] = __ballot(f.grow != f.neg) & lg[j];
+                        slow[j] = __ballot(f.slow);
+                        any_slow |= slow[j];
+                    }
+                    if (__builtin_expect(any_slow != 0, 0)) {          // NaN, Inf, zero, tiny or huge values
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const Decision d = decide((uint64_t)__double_as_longlong(c[j]));
+                            const bool sl = (slow[j] >> lane) & 1;
+                            if (sl) yb[j] = d.ybits;
+                            const uint64_t lgs = __ballot(d.D < p.thr), drs = __ballot(d.dir != 0) & lgs;
+                            lg[j] = (lg[j] & ~slow[j]) | (lgs & slow[j]);
+                            dr[j] = (dr[j] & ~slow[j]) | (drs & slow[j]);
+                        }
+                    }
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        *(float *)(c32_row + off32 + j * 64) = __uint_as_float(yb[j]);
+                        if (HAS64) *(double *)(c64_row + off64 + j * 128) = c[j];
+                    }
+                    c32_row += step32;
+                    if (HAS64) c64_row += step64;
+                    // 16-bit group q of the four ballots -> plane word of row 4 r + q (scalar packs),
+                    // parked in lane 4 r + q until the block's sixteen rows are complete
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int ln = 4 * r + q;
+                        wl_lo = write_lane(pack16(lg[0], lg[1], q), ln, wl_lo);
+                        wl_hi = write_lane(pack16(lg[2], lg[3], q), ln, wl_hi);
+                        wd_lo = write_lane(pack16(dr[0], dr[1], q), ln, wd_lo);
+                        wd_hi = write_lane(pack16(dr[2], dr[3], q), ln, wd_hi);
+                    }
+                }
+                if (lane < 16) {
+                    *(uint64_t *)(wl_blk + offw) = ((uint64_t)(uint32_t)wl_hi << 32) | (uint32_t)wl_lo;
+                    *(uint64_t *)(wd_blk + offw) = ((uint64_t)(uint32_t)wd_hi << 32) | (uint32_t)wd_lo;
+                }
+                wl_blk += (uint64_t)p.wpr * 128u;
+                wd_blk += (uint64_t)p.wpr * 128u;
+            }
+        };
+        if (p.C64) full(std::true_type{});
+        else full(std::false_type{});
+        return;
+    }
+    // edge tiles: every access guarded
     const bool word_exists = colword < p.wpr;
     float *C32 = p.C32 + (int64_t)b * p.strideC;
     double *C64 = p.C64 ? p.C64 + (int64_t)b * p.M * p.N : nullptr;
