@@ -4,11 +4,13 @@ from __future__ import annotations
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvt_hip.so")
-SOURCES = ["vt_api.hip", "vt_round_kernels.hip", "vt_round_onepass.hip", "vt_gemm_kernels.hip"]
+SOURCES = ["vt_gemm_shape_128x128.hip", "vt_gemm_shape_64x128.hip", "vt_gemm_shape_128x64.hip", "vt_gemm_shape_64x64.hip",
+           "vt_api.hip", "vt_round_kernels.hip", "vt_round_onepass.hip", "vt_gemm_kernels.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -17,8 +19,7 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-ffp-contract=o
 
 def build_lib(verbose: bool = False) -> str:
     """Compile every source for gfx950 and link the shared library. Always recompiles."""
-    objs = []
-    for src in SOURCES:
+    def compile_one(src):
         obj = os.path.join(CSRC, src.replace(".hip", ".o"))
         cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
@@ -29,7 +30,11 @@ def build_lib(verbose: bool = False) -> str:
             raise RuntimeError(f"hipcc failed on {src}:\n{err}")
         if verbose and err.strip():
             print(err, file=sys.stderr)
-        objs.append(obj)
+        return obj
+
+    # the translation units are independent: compile them side by side (the GEMM tile shapes dominate)
+    with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1, 8)) as pool:
+        objs = list(pool.map(compile_one, SOURCES))
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
     return LIB
 

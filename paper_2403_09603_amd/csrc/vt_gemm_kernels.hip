@@ -22,461 +22,16 @@
 // Lane layout of v_mfma_f64_16x16x4_f64 (measured on gfx950):
 //   A operand: lane l holds A[i = l % 16][k = l / 16];  B operand: lane l holds B[k = l / 16][j = l % 16]
 //   D: register r of lane l holds D[i = 4 r + l / 16][j = l % 16].
-#include "vt_device.h"
-#include "vt_kernels.h"
+// This file: the tile-shape and split-K plan, the split-K reduction and the launcher; the kernel
+// template lives in vt_gemm_tile.h.
+#include "vt_gemm_tile.h"
 
 #include <cmath>
 #include <cstdlib>
-#include <type_traits>
 
 namespace vt {
 
 namespace {
-
-typedef double d4 __attribute__((ext_vector_type(4)));
-typedef double d2 __attribute__((ext_vector_type(2)));
-
-constexpr int BK = 16;
-// LDS row pitch = tile width + 18 doubles.  A k-contiguous operand is transposed on its way into
-// LDS: the 32 lanes of a write pass hold 8 k rows x 4 columns, and with a pitch of 18 mod 32
-// doubles those land on 32 different bank pairs (a pitch of 16 mod 32 put all 8 k rows on one
-// pair: 8-way conflicts that kept the LDS pipe busy for about as long as the MFMAs).  Fragment
-// reads (2 k rows x 16 columns per pass) then overlap in 2 of 32 bank pairs only.
-constexpr int kPad = 18;
-
-struct GemmParams {
-    ConvGeom conv;
-    const double *A, *B, *bias;
-    float *C32;
-    double *C64;                                // optional dense FP64 copy (fused path only)
-    double *partial;                            // split-K slabs [split][batch][M][N]
-    uint64_t *pl_logged, *pl_dir;
-    int64_t M, N, K, lda, ldb, ldc, strideA, strideB, strideC, batch;
-    double alpha;
-    uint32_t thr, wpr, tilesM, tilesN, tiles_per_split, total_blocks;
-    int variant, vecA, vecB, splits, kt_per_split;
-};
-
-// Two neighbouring taps of one row.  The load is unconditional (from X[0] when the element lies
-// in the padding or outside the matrix) and the value is selected afterwards, so the loop body
-// stays free of branches.
-template <bool VEC>
-__device__ __forceinline__ d2 conv_gather(const double *__restrict__ X, const ConvGeom &c, const RowPos &r,
-                                          const TapPos &t0, const TapPos &t1)
-{
-    const bool ok0 = (uint32_t)(r.h0 + t0.hh) < (uint32_t)c.H && (uint32_t)(r.w0 + t0.ww) < (uint32_t)c.W;
-    d2 v;
-    if (VEC) {
-        const d2 x = *(const d2 *)(X + (ok0 ? r.base + t0.off : 0));
-        v.x = ok0 ? x.x : 0.0;
-        v.y = ok0 ? x.y : 0.0;
-    } else {
-        const bool ok1 = (uint32_t)(r.h0 + t1.hh) < (uint32_t)c.H && (uint32_t)(r.w0 + t1.ww) < (uint32_t)c.W;
-        const double a = X[ok0 ? r.base + t0.off : 0], b = X[ok1 ? r.base + t1.off : 0];
-        v.x = ok0 ? a : 0.0;
-        v.y = ok1 ? b : 0.0;
-    }
-    return v;
-}
-
-// Global -> registers for one R x 16 operand tile (R = 64 or 128 rows/columns of the output).
-// KC = the operand is contiguous along k (element (mn, k) at base[mn * ld + k]); otherwise
-// contiguous along m/n (base[k * ld + mn]).  Each thread moves R / 32 pairs of doubles.
-// Out-of-range elements read as 0, so partial tiles add exact zeros.
-template <bool KC, int R>
-__device__ __forceinline__ void load_tile(const double *__restrict__ base, int64_t ld, int64_t mn0, int64_t k0,
-                                          int64_t MN, int64_t K, int vec, d2 (&regs)[R / 32])
-{
-    const int t = threadIdx.x;
-#pragma unroll
-    for (int j = 0; j < R / 32; ++j) {
-        int64_t mn, k;
-        if (KC) { mn = mn0 + (t >> 3) + 32 * j; k = k0 + (t & 7) * 2; }
-        else    { k = k0 + t / (R / 2) + (512 / R) * j; mn = mn0 + (t % (R / 2)) * 2; }
-        d2 v = {0.0, 0.0};
-        if (KC) {
-            if (mn < MN) {
-                const double *p = base + mn * ld + k;
-                if (vec && k + 1 < K) v = *(const d2 *)p;
-                else { if (k < K) v.x = p[0]; if (k + 1 < K) v.y = p[1]; }
-            }
-        } else {
-            if (k < K) {
-                const double *p = base + k * ld + mn;
-                if (vec && mn + 1 < MN) v = *(const d2 *)p;
-                else { if (mn < MN) v.x = p[0]; if (mn + 1 < MN) v.y = p[1]; }
-            }
-        }
-        regs[j] = v;
-    }
-}
-
-// Same tile when it lies wholly inside the operand and 16-byte loads are legal: straight vector
-// loads, no guards.  Addresses are a workgroup-uniform base (scalar registers, advanced per k
-// step) plus a per-thread 32-bit byte offset that never changes, so the loop spends no vector
-// instructions -- and no load-destination registers -- on address arithmetic.
-template <bool KC, int R>
-__device__ __forceinline__ void tile_offsets(int64_t ld, uint32_t (&off)[R / 32])
-{
-    const int t = threadIdx.x;
-#pragma unroll
-    for (int j = 0; j < R / 32; ++j)
-        off[j] = KC ? (uint32_t)((((t >> 3) + 32 * j) * ld + (t & 7) * 2) * 8)
-                    : (uint32_t)(((t / (R / 2) + (512 / R) * j) * ld + (t % (R / 2)) * 2) * 8);
-}
-
-template <bool KC, int R>
-__device__ __forceinline__ void load_tile_fast(const char *__restrict__ base, int64_t ld, int64_t k0,
-                                               const uint32_t (&off)[R / 32], d2 (&regs)[R / 32])
-{
-    const char *p = base + (KC ? k0 : k0 * ld) * 8;      // uniform
-#pragma unroll
-    for (int j = 0; j < R / 32; ++j) regs[j] = *(const d2 *)(p + off[j]);
-}
-
-template <bool KC, int R>
-__device__ __forceinline__ void store_tile(double *__restrict__ S, const d2 (&regs)[R / 32])
-{
-    const int t = threadIdx.x;
-    constexpr int pitch = R + kPad;
-#pragma unroll
-    for (int j = 0; j < R / 32; ++j) {
-        if (KC) {
-            const int mn = (t >> 3) + 32 * j, k = (t & 7) * 2;
-            S[k * pitch + mn] = regs[j].x;
-            S[(k + 1) * pitch + mn] = regs[j].y;
-        } else {
-            const int k = t / (R / 2) + (512 / R) * j, mn = (t % (R / 2)) * 2;
-            *(d2 *)&S[k * pitch + mn] = regs[j];
-        }
-    }
-}
-
-// Bits [16 q, 16 q + 16) of two wave-uniform 64-bit masks, side by side: a's in the low half.
-__device__ __forceinline__ uint32_t pack16(uint64_t a, uint64_t b, int q)
-{
-    const uint32_t x = (uint32_t)(a >> (32 * (q >> 1))), y = (uint32_t)(b >> (32 * (q >> 1)));
-    return (q & 1) ? (x >> 16) | (y & 0xFFFF0000u) : (x & 0xFFFFu) | (y << 16);
-}
-
-// v with lane `ln` (a compile-time constant) replaced by the wave-uniform value s.
-__device__ __forceinline__ int write_lane(uint32_t s, int ln, int v)
-{
-    asm("v_writelane_b32 %0, %1, %2" : "+v"(v) : "s"(s), "n"(ln));
-    return v;
-}
-
-// AM, the A operand: 0 = stored transposed (contiguous along m), 1 = row-major (contiguous along
-// k), 2 = implicit im2col of an image, rows x taps (convolution forward), 3 = its transpose,
-// taps x rows (convolution weight gradient).  KCB: B is stored transposed (contiguous along k).
-template <int AM, bool KCB, int WM, int TM>
-__global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmParams p)
-{
-    constexpr bool KCA = AM == 1 || AM == 2;
-    constexpr bool GA = AM >= 2;
-    constexpr int WN = 4 / WM;
-    constexpr int BM = WM * 16 * TM, BN = WN * 64;
-    constexpr int PA = BM + kPad, PB = BN + kPad;          // LDS pitches
-    constexpr int SA = BK * PA, SB = BK * PB;              // doubles per stage
-    __shared__ double lds[2 * SA + 2 * SB];                // A0 A1 B0 B1
-    double *const ldsA = lds, *const ldsB = lds + 2 * SA;
-    const int t = threadIdx.x, lane = t & 63;
-    const int wv = __builtin_amdgcn_readfirstlane(t >> 6);      // wave-uniform: keeps tile addresses in scalar registers
-    const int wm = wv / WN, wn = wv % WN;
-
-    // Workgroup -> (split, tile).  Consecutive workgroup ids land on different XCDs (8 of them,
-    // each with its own L2), so ids are first regrouped per XCD, then walked in bands of 8 row
-    // tiles so that neighbours in time share A and B panels in that L2.
-    uint32_t pid;
-    {
-        const uint32_t i = blockIdx.x, q = p.total_blocks / 8u, r = p.total_blocks % 8u, xcd = i % 8u;
-        pid = xcd * q + (xcd < r ? xcd : r) + i / 8u;
-    }
-    const uint32_t split = pid / p.tiles_per_split;
-    pid -= split * p.tiles_per_split;
-    const uint32_t per_batch = p.tilesM * p.tilesN;
-    const uint32_t b = pid / per_batch;
-    const uint32_t pin = pid - b * per_batch;
-    const uint32_t GM = 8, width = GM * p.tilesN;
-    const uint32_t first_m = (pin / width) * GM;
-    const uint32_t gsz = p.tilesM - first_m < GM ? p.tilesM - first_m : GM;
-    const uint32_t tm_ = first_m + (pin % width) % gsz;
-    const uint32_t tn_ = (pin % width) / gsz;
-    const int64_t bm = (int64_t)tm_ * BM, bn = (int64_t)tn_ * BN;
-
-    const double *A = p.A + (int64_t)b * p.strideA;
-    const double *B = p.B + (int64_t)b * p.strideB;
-
-    d4 acc[TM][4];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = (d4){0.0, 0.0, 0.0, 0.0};
-
-    // this workgroup's k tiles: [kt0, kt1)
-    const int nkt_all = (int)((p.K + BK - 1) / BK);
-    const int kt0 = (int)split * p.kt_per_split;
-    const int kt1 = kt0 + p.kt_per_split < nkt_all ? kt0 + p.kt_per_split : nkt_all;
-    const int nkt = kt1 > kt0 ? kt1 - kt0 : 0;
-    // whole-tile operands take the unguarded loader (a uniform choice per k step)
-    // (the per-thread offsets of the unguarded loader are 32-bit: pitches up to 2^31 / 8 / 128)
-    const bool fastA = GA ? p.conv.vec != 0 : p.vecA && bm + BM <= p.M && p.lda < (1 << 21);
-    const bool fastB = p.vecB && bn + BN <= p.N && p.ldb < (1 << 21);
-    const char *baseA = (const char *)(A + (KCA ? bm * p.lda : bm));
-    const char *baseB = (const char *)(B + (KCB ? bn * p.ldb : bn));
-    uint32_t offA[BM / 32], offB[BN / 32];
-    tile_offsets<KCA, BM>(p.lda, offA);
-    tile_offsets<KCB, BN>(p.ldb, offB);
-    // Two register sets: tile it+2 is in flight from memory while tile it+1 (fetched one step
-    // earlier) goes to LDS and tile it is multiplied, so a fetch has two full steps to land.
-    // The loop exists twice: with unguarded loads only (every tile of this workgroup lies inside
-    // the operands; straight-line code, so the load counter waits are exact and the newest
-    // fetch stays in flight across the LDS stores), and with the guarded loader for edges.
-    d2 ra0[BM / 32], rb0[BN / 32], ra1[BM / 32], rb1[BN / 32];
-    // Implicit im2col: the part of the address that belongs to this thread for the whole loop --
-    // its rows of the image matrix (forward) or its pair of taps (weight gradient).
-    RowPos rowp[AM == 2 ? BM / 32 : 1];
-    TapPos tap0{0, 0, 0}, tap1{0, 0, 0};
-    if constexpr (AM == 2) {
-#pragma unroll
-        for (int j = 0; j < BM / 32; ++j) rowp[j] = conv_row(p.conv, (uint32_t)bm + (t >> 3) + 32 * j);
-    }
-    if constexpr (AM == 3) {
-        const uint32_t kc = (uint32_t)bm + (t % (BM / 2)) * 2;
-        tap0 = conv_tap(p.conv, kc);
-        tap1 = conv_tap(p.conv, kc + 1);
-    }
-    auto gather_tile = [&](auto vec_tag, int64_t k0, d2 (&ra)[BM / 32]) {
-        constexpr bool VEC = decltype(vec_tag)::value;
-        if constexpr (AM == 2) {
-            const uint32_t kc = (uint32_t)k0 + (t & 7) * 2;
-            const TapPos t0 = conv_tap(p.conv, kc);
-            const TapPos t1 = VEC ? t0 : conv_tap(p.conv, kc + 1);
-#pragma unroll
-            for (int j = 0; j < BM / 32; ++j) ra[j] = conv_gather<VEC>(p.A, p.conv, rowp[j], t0, t1);
-        } else if constexpr (AM == 3) {
-#pragma unroll
-            for (int j = 0; j < BM / 32; ++j) {
-                const RowPos r = conv_row(p.conv, (uint32_t)k0 + t / (BM / 2) + (512 / BM) * j);
-                ra[j] = conv_gather<VEC>(p.A, p.conv, r, tap0, tap1);
-            }
-        }
-    };
-    auto main_loop = [&](auto fast_tag) {
-        constexpr bool FAST = decltype(fast_tag)::value;
-        auto fetch = [&](int it, d2 (&ra)[BM / 32], d2 (&rb)[BN / 32]) {   // `it`-th step in this variant's order
-            const int64_t k0 = (int64_t)(p.variant ? kt1 - 1 - it : kt0 + it) * BK;
-            if constexpr (GA) {
-                if constexpr (FAST) gather_tile(std::true_type{}, k0, ra);
-                else if (p.conv.vec) gather_tile(std::true_type{}, k0, ra);
-                else gather_tile(std::false_type{}, k0, ra);
-            } else if constexpr (FAST) {
-                load_tile_fast<KCA, BM>(baseA, p.lda, k0, offA, ra);
-            } else {
-                load_tile<KCA, BM>(A, p.lda, bm, k0, p.M, p.K, p.vecA, ra);
-            }
-            if constexpr (FAST) load_tile_fast<KCB, BN>(baseB, p.ldb, k0, offB, rb);
-            else load_tile<KCB, BN>(B, p.ldb, bn, k0, p.N, p.K, p.vecB, rb);
-        };
-        // one k step: multiply the tile in LDS stage `cur`; start the fetch of tile it+2 into (la, lb);
-        // move tile it+1 from (sa, sb) to the other stage in the shadow of the last MFMA group
-        auto step = [&](int it, int cur, d2 (&la)[BM / 32], d2 (&lb)[BN / 32], d2 (&sa)[BM / 32], d2 (&sb)[BN / 32]) {
-            // In the unguarded loop the fetch and the LDS store are unconditional (past the end
-            // they repeat the last tile and fill a stage nobody reads): with no branch around
-            // them the compiler's load-counter waits are exact.
-            if (FAST) fetch(it + 2 < nkt ? it + 2 : nkt - 1, la, lb);
-            else if (it + 2 < nkt) fetch(it + 2, la, lb);
-            const bool more = FAST || it + 1 < nkt;
-            const double *As = ldsA + cur * SA + wm * (16 * TM) + (lane & 15);
-            const double *Bs = ldsB + cur * SB + wn * 64 + (lane & 15);
-            double a[TM], bb[4];
-#pragma unroll
-            for (int kk = 0; kk < BK / 4; ++kk) {
-                const int krow = kk * 4 + (lane >> 4);
-#pragma unroll
-                for (int i = 0; i < TM; ++i) a[i] = As[krow * PA + i * 16];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) bb[j] = Bs[krow * PB + j * 16];
-                if (kk == BK / 4 - 1) {
-                    // (the last group's fragments are already requested: LDS completes in order,
-                    // so the wave's MFMA stream has no gap before the barrier)
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (more) {
-                        store_tile<KCA, BM>(ldsA + (cur ^ 1) * SA, sa);
-                        store_tile<KCB, BN>(ldsB + (cur ^ 1) * SB, sb);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], bb[j], acc[i][j], 0, 0, 0);
-            }
-            __syncthreads();
-        };
-        if (nkt > 0) {
-            fetch(0, ra0, rb0);
-            store_tile<KCA, BM>(ldsA, ra0);
-            store_tile<KCB, BN>(ldsB, rb0);
-            if (nkt > 1) fetch(1, ra0, rb0);
-        }
-        __syncthreads();
-        for (int it = 0; it < nkt; it += 2) {
-            step(it, 0, ra1, rb1, ra0, rb0);                // tile it+1 sits in set 0, it+2 goes to set 1
-            if (it + 1 < nkt) step(it + 1, 1, ra0, rb0, ra1, rb1);
-        }
-    };
-    if (fastA && fastB && (int64_t)kt1 * BK <= p.K) main_loop(std::true_type{});
-    else main_loop(std::false_type{});
-
-    const int g = lane >> 4, c16 = lane & 15;
-    const int64_t row0 = bm + wm * (16 * TM), col0 = bn + wn * 64;
-
-    if (p.splits > 1) {
-        // ---- split-K: raw accumulators to this slice's slab; alpha, bias, rounding come later
-        double *P = p.partial + ((int64_t)split * p.batch + (int64_t)b) * p.M * p.N;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int64_t row = row0 + i * 16 + 4 * r + g;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int64_t col = col0 + j * 16 + c16;
-                    if (row < p.M && col < p.N) P[row * p.N + col] = acc[i][j][r];
-                }
-            }
-        return;
-    }
-
-    // ---- epilogue: alpha, bias, round, decide, store, bit-planes -------------------------
-    const uint64_t colword = (uint64_t)col0 >> 6;
-    // Whole tile inside the matrix (and pitches that fit 32-bit lane offsets): no guards, every
-    // address is a wave-uniform base plus a lane offset that never changes, the four ballots of
-    // a row group are transposed into plane words with scalar pack operations, and the rare
-    // values that need the integer rounding path are handled once per group of four.
-    if (bm + BM <= p.M && bn + BN <= p.N && p.ldc < (1 << 26) && p.N < (1 << 25)) {
-        auto full = [&](auto has64_tag) {
-            constexpr bool HAS64 = decltype(has64_tag)::value;
-            char *c32_row = (char *)(p.C32 + (int64_t)b * p.strideC + row0 * p.ldc + col0);      // uniform, row 4 r of block i
-            char *c64_row = HAS64 ? (char *)(p.C64 + ((int64_t)b * p.M + row0) * p.N + col0) : nullptr;
-            const uint32_t step32 = (uint32_t)p.ldc * 16u, step64 = (uint32_t)p.N * 32u;         // four rows further
-            const uint32_t off32 = ((uint32_t)g * (uint32_t)p.ldc + (uint32_t)c16) * 4u;
-            const uint32_t off64 = ((uint32_t)g * (uint32_t)p.N + (uint32_t)c16) * 8u;
-            char *wl_blk = (char *)(p.pl_logged + ((uint64_t)b * (uint64_t)p.M + (uint64_t)row0) * p.wpr + colword);
-            char *wd_blk = (char *)(p.pl_dir + ((uint64_t)b * (uint64_t)p.M + (uint64_t)row0) * p.wpr + colword);
-            const uint32_t offw = (uint32_t)(lane & 15) * p.wpr * 8u;                            // lane = row of the block
-            double bias_f[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) bias_f[j] = p.bias ? p.bias[col0 + j * 16 + c16] : -0.0;   // x + (-0) = x
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                int wl_lo = 0, wl_hi = 0, wd_lo = 0, wd_hi = 0;       // lane q: plane words of row q of this block
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    double c[4];
-                    uint32_t yb[4];
-                    uint64_t lg[4], dr[4], slow[4], any_slow = 0;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        c[j] = p.alpha * acc[i][j][r] + bias_f[j];
-                        const FastDecision f = decide_fast(c[j]);
-                        yb[j] = __float_as_uint(f.y);
-                        lg[j] = __ballot(f.D < p.thr);
-                        dr[j] = __ballot(f.grow != f.neg) & lg[j];
-                        slow[j] = __ballot(f.slow);
-                        any_slow |= slow[j];
-                    }
-                    if (__builtin_expect(any_slow != 0, 0)) {          // NaN, Inf, zero, tiny or huge values
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const Decision d = decide((uint64_t)__double_as_longlong(c[j]));
-                            const bool sl = (slow[j] >> lane) & 1;
-                            if (sl) yb[j] = d.ybits;
-                            const uint64_t lgs = __ballot(d.D < p.thr), drs = __ballot(d.dir != 0) & lgs;
-                            lg[j] = (lg[j] & ~slow[j]) | (lgs & slow[j]);
-                            dr[j] = (dr[j] & ~slow[j]) | (drs & slow[j]);
-                        }
-                    }
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        *(float *)(c32_row + off32 + j * 64) = __uint_as_float(yb[j]);
-                        if (HAS64) *(double *)(c64_row + off64 + j * 128) = c[j];
-                    }
-                    c32_row += step32;
-                    if (HAS64) c64_row += step64;
-                    // 16-bit group q of the four ballots -> plane word of row 4 r + q (scalar packs),
-                    // parked in lane 4 r + q until the block's sixteen rows are complete
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int ln = 4 * r + q;
-                        wl_lo = write_lane(pack16(lg[0], lg[1], q), ln, wl_lo);
-                        wl_hi = write_lane(pack16(lg[2], lg[3], q), ln, wl_hi);
-                        wd_lo = write_lane(pack16(dr[0], dr[1], q), ln, wd_lo);
-                        wd_hi = write_lane(pack16(dr[2], dr[3], q), ln, wd_hi);
-                    }
-                }
-                if (lane < 16) {
-                    *(uint64_t *)(wl_blk + offw) = ((uint64_t)(uint32_t)wl_hi << 32) | (uint32_t)wl_lo;
-                    *(uint64_t *)(wd_blk + offw) = ((uint64_t)(uint32_t)wd_hi << 32) | (uint32_t)wd_lo;
-                }
-                wl_blk += (uint64_t)p.wpr * 128u;
-                wd_blk += (uint64_t)p.wpr * 128u;
-            }
-        };
-        if (p.C64) full(std::true_type{});
-        else full(std::false_type{});
-        return;
-    }
-    // edge tiles: every access guarded
-    const bool word_exists = colword < p.wpr;
-    float *C32 = p.C32 + (int64_t)b * p.strideC;
-    double *C64 = p.C64 ? p.C64 + (int64_t)b * p.M * p.N : nullptr;
-    double bias_v[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int64_t col = col0 + j * 16 + c16;
-        bias_v[j] = (p.bias && col < p.N) ? p.bias[col] : 0.0;
-    }
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int64_t row = row0 + i * 16 + 4 * r + g;
-            uint64_t lgw = 0, drw = 0;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int64_t col = col0 + j * 16 + c16;
-                const bool in = row < p.M && col < p.N;
-                double c = p.alpha * acc[i][j][r];
-                if (p.bias) c = c + bias_v[j];
-                const FastDecision f = decide_fast(c);
-                uint32_t yb = __float_as_uint(f.y);
-                bool logged = f.D < p.thr, up = f.grow != f.neg;
-                if (__builtin_expect(__ballot(f.slow) != 0, 0)) {     // NaN, Inf, zero, tiny or huge values
-                    if (f.slow) {
-                        const Decision d = decide((uint64_t)__double_as_longlong(c));
-                        yb = d.ybits; logged = d.D < p.thr; up = d.dir != 0;
-                    }
-                }
-                if (in) {
-                    C32[row * p.ldc + col] = __uint_as_float(yb);
-                    if (C64) C64[row * p.N + col] = c;
-                }
-                const uint64_t lg = __ballot(in && logged);
-                const uint64_t dr = __ballot(up) & lg;
-                lgw |= ((lg >> (16 * g)) & 0xFFFFull) << (16 * j);
-                drw |= ((dr >> (16 * g)) & 0xFFFFull) << (16 * j);
-            }
-            if (c16 == 0 && row < p.M && word_exists) {
-                const uint64_t w = ((uint64_t)b * (uint64_t)p.M + (uint64_t)row) * p.wpr + colword;
-                p.pl_logged[w] = lgw;
-                p.pl_dir[w] = drw;
-            }
-        }
-    }
-}
 
 // Split-K second stage: out[e] = alpha * (P[0][e] + P[1][e] + ...) (+ bias[col]), slabs added in
 // ascending order (variant 0) or descending order (variant 1).  One thread per output.
@@ -507,20 +62,6 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const double *__rest
 struct TileShape { int wm, tm, bm, bn; double eff; int conc; };
 constexpr TileShape kShapes[4] = {{2, 4, 128, 128, 0.85, 2}, {2, 2, 64, 128, 0.78, 2}, {4, 2, 128, 64, 0.74, 2},
                                   {4, 1, 64, 64, 0.62, 3}};
-
-template <int WM, int TM>
-hipError_t launch_shape(const GemmParams &p, int am, bool kcb, hipStream_t s)
-{
-    const dim3 grid(p.total_blocks), block(256);
-    if (am == 2 && !kcb) gemm_round_planes_kernel<2, false, WM, TM><<<grid, block, 0, s>>>(p);
-    else if (am == 3 && !kcb) gemm_round_planes_kernel<3, false, WM, TM><<<grid, block, 0, s>>>(p);
-    else if (am == 1 && kcb) gemm_round_planes_kernel<1, true, WM, TM><<<grid, block, 0, s>>>(p);
-    else if (am == 1 && !kcb) gemm_round_planes_kernel<1, false, WM, TM><<<grid, block, 0, s>>>(p);
-    else if (am == 0 && kcb) gemm_round_planes_kernel<0, true, WM, TM><<<grid, block, 0, s>>>(p);
-    else if (am == 0 && !kcb) gemm_round_planes_kernel<0, false, WM, TM><<<grid, block, 0, s>>>(p);
-    else return hipErrorInvalidValue;
-    return hipGetLastError();
-}
 
 }  // namespace
 
@@ -594,10 +135,10 @@ hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, con
     }
     hipError_t e;
     switch (plan.shape) {
-    case 0: e = launch_shape<2, 4>(p, am, kcb, s); break;
-    case 1: e = launch_shape<2, 2>(p, am, kcb, s); break;
-    case 2: e = launch_shape<4, 2>(p, am, kcb, s); break;
-    default: e = launch_shape<4, 1>(p, am, kcb, s); break;
+    case 0: e = launch_gemm_128x128(p, am, kcb, s); break;
+    case 1: e = launch_gemm_64x128(p, am, kcb, s); break;
+    case 2: e = launch_gemm_128x64(p, am, kcb, s); break;
+    default: e = launch_gemm_64x64(p, am, kcb, s); break;
     }
     if (e != hipSuccess || plan.splits <= 1) return e;
     const uint64_t slab = (uint64_t)g.M * g.N * g.batch;
