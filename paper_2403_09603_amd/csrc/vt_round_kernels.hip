@@ -172,11 +172,27 @@ __global__ __launch_bounds__(256) void compact_kernel(const uint64_t *__restrict
 // list; the tile's entries are then read in order and dropped into a byte array in LDS (index
 // values are distinct, so plain stores suffice), from which every output picks its own flag.
 // --------------------------------------------------------------------------------------------
+// A position a with a <= lower_bound(idx, target) <= a + 3, found by one wavefront.  `guess` is
+// where the bound would be if the entries were spread evenly; a first round probes 64 positions,
+// 256 apart, around it, and when they bracket the bound (the usual case) one more round ends the
+// search; otherwise the 64-ary search runs on whatever range remains.  Every read is in bounds.
+constexpr uint64_t kProbeGap = 256, kProbeWindow = 64 * kProbeGap;
+
 __device__ __forceinline__ uint64_t wave_lower_bound(const uint32_t *__restrict__ idx, uint64_t count,
-                                                     uint64_t target, uint32_t lane)
+                                                     uint64_t target, uint64_t guess, uint32_t lane)
 {
     uint64_t a = 0, b = count;                              // answer in [a, b]
-    while (b > a) {
+    if (count > kProbeWindow) {
+        uint64_t a0 = guess > kProbeWindow / 2 ? guess - kProbeWindow / 2 : 0;
+        if (a0 + kProbeWindow > count) a0 = count - kProbeWindow;
+        const uint32_t c = popc64(ballot((uint64_t)idx[a0 + (uint64_t)lane * kProbeGap] < target));
+        if (c == 0) b = a0;
+        else {
+            a = a0 + (uint64_t)(c - 1) * kProbeGap + 1;
+            if (c < 64) b = a0 + (uint64_t)c * kProbeGap;
+        }
+    }
+    while (b - a > 3) {
         const uint64_t step = (b - a + 63) >> 6;
         const uint64_t q = a + (uint64_t)lane * step;
         const bool pred = q < b && (uint64_t)idx[q] < target;
@@ -251,7 +267,15 @@ __global__ __launch_bounds__(256) void replay_kernel(const double *__restrict__ 
     __shared__ __attribute__((aligned(16))) uint8_t flags[kReplayTile];   // bit 0: logged, bit 1: direction
     __shared__ uint64_t s_lo;
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wv = tid >> 6;
-    const uint64_t start = (uint64_t)blockIdx.x * kReplayTile;
+    // Consecutive workgroup ids run on different XCDs (8, each with its own L2).  Every XCD takes
+    // one contiguous eighth of the tiles, so the index-list lines that the searches of
+    // neighbouring tiles share are fetched into one L2 instead of eight.
+    uint32_t tile;
+    {
+        const uint32_t i = blockIdx.x, q = gridDim.x / 8u, r = gridDim.x % 8u, xcd = i % 8u;
+        tile = xcd * q + (xcd < r ? xcd : r) + i / 8u;
+    }
+    const uint64_t start = (uint64_t)tile * kReplayTile;
     const uint64_t stop = start + kReplayTile < n ? start + kReplayTile : n;
     const uint64_t wbase = start + (uint64_t)wv * kReplayChunk;
     const bool full = start + kReplayTile <= n;
@@ -260,12 +284,14 @@ __global__ __launch_bounds__(256) void replay_kernel(const double *__restrict__ 
     else replay_load<false, VEC>(x, n, wbase, lane, v);
     ((uint4 *)flags)[tid] = make_uint4(0, 0, 0, 0);
     if (wv == 0) {
-        const uint64_t r = wave_lower_bound(idx, count, start, lane);
+        const double even = (double)start * ((double)count / (double)n);
+        const uint64_t r = wave_lower_bound(idx, count, start, even < (double)count ? (uint64_t)even : count, lane);
         if (lane == 0) s_lo = r;
     }
     __syncthreads();
     const uint64_t lo = s_lo;
-    // at most 4096 entries belong to the tile: 64 rounds of 64, plus one for a ragged start
+    // lo is at most 3 before the tile's first entry, and at most 4096 entries belong to the tile:
+    // 64 rounds of 64 plus one for the ragged start
     for (uint32_t r = wv; r <= kReplayTile / 64; r += 4) {
         const uint64_t p = lo + (uint64_t)r * 64u + lane;
         const uint64_t i = p < count ? (uint64_t)idx[p] : ~0ull;
@@ -311,13 +337,22 @@ __device__ __forceinline__ void stats_one(uint64_t a, uint64_t b, double xa, dou
         atomicAdd(&hist[copy][64u - (uint32_t)__clzll((long long)diff)], 1u);
         acc.dmax = diff > acc.dmax ? diff : acc.dmax;
     }
-    const FastDecision fa = decide_fast(xa), fb = decide_fast(xb);
-    uint32_t ya = __float_as_uint(fa.y), yb = __float_as_uint(fb.y), Da = fa.D, Db = fb.D;
-    if (fa.slow) { const Decision d = decide(a); ya = d.ybits; Da = d.D; }
-    if (fb.slow) { const Decision d = decide(b); yb = d.ybits; Db = d.D; }
-    if (ya != yb) {
+    // FP32 roundings: hardware conversion when both values are ordinary (the conversion cannot
+    // differ from the integer definition there); distances only for the rare pairs that flip
+    const uint32_t ha = (uint32_t)(a >> 32) & 0x7FFFFFFFu, hb = (uint32_t)(b >> 32) & 0x7FFFFFFFu;
+    const bool ordinary = (ha - (897u << 20)) < ((1151u - 897u) << 20) && (hb - (897u << 20)) < ((1151u - 897u) << 20);
+    if (ordinary) {
+        if (__float_as_uint((float)xa) == __float_as_uint((float)xb)) return;
+        const uint32_t Da = __usad((uint32_t)a & kMask29, kHalf, 0u), Db = __usad((uint32_t)b & kMask29, kHalf, 0u);
         ++acc.flips;
         const uint32_t need = 1u + (Da > Db ? Da : Db);
+        acc.thrmax = need > acc.thrmax ? need : acc.thrmax;
+        return;
+    }
+    const Decision da = decide(a), db = decide(b);
+    if (da.ybits != db.ybits) {
+        ++acc.flips;
+        const uint32_t need = 1u + (da.D > db.D ? da.D : db.D);
         acc.thrmax = need > acc.thrmax ? need : acc.thrmax;
     }
 }

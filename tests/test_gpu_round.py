@@ -107,6 +107,27 @@ def test_replay_matches_oracle_and_trainer(G, thr, tau):
     assert np.array_equal(_bits(vo.round_replay(xa, idx, dirw)), _bits(yT))
 
 
+@pytest.mark.parametrize("layout", ["even", "front", "back", "middle", "short"])
+def test_replay_with_uneven_log_density(G, layout):
+    """The replay kernel guesses where a tile's entries start from the average density and falls
+    back to a full search when the guess is off: logs that are dense at one end, in the middle, or
+    shorter than the probe window must all give the oracle's result."""
+    n = 1 << 20
+    g = si.rng(si.seed_for(5, 6))
+    x = g.standard_normal(n)
+    u = g.random(n)
+    pos = np.arange(n)
+    dense = {"even": np.ones(n, bool), "front": pos < n // 16, "back": pos >= n - n // 16,
+             "middle": (pos > n // 2) & (pos < n // 2 + n // 32), "short": pos < 0}[layout]
+    logged = (u < np.where(dense, 0.6, 0.0005)) if layout != "even" else (u < 0.1)
+    idx = np.flatnonzero(logged).astype(np.uint32)
+    assert (idx.size > 20000) == (layout != "short")
+    dirw = g.integers(0, 1 << 32, (idx.size + 31) // 32 + 1, dtype=np.uint64).astype(np.uint32)
+    want = _bits(vo.round_replay(x, idx, dirw, count=idx.size))
+    assert np.array_equal(_bits(G.gpu_round_replay(x, idx, dirw, count=idx.size)), want)
+    assert np.array_equal(_bits(G.gpu_round_replay(x, idx, dirw, count=idx.size, misalign=True)), want)
+
+
 def test_replay_edge_values_all_logged_and_empty(G):
     x = si.edge_values()
     n = x.size
