@@ -126,6 +126,53 @@ int vto_round_replay(const double *x, uint64_t n, const uint32_t *idx, const uin
     return VTO_OK;
 }
 
+uint8_t vto_ternary_pack5(const uint8_t codes[5])
+{
+    unsigned v = 0, w = 1;
+    for (int j = 0; j < 5; ++j) { v += codes[j] * w; w *= 3; }
+    return (uint8_t)v;
+}
+
+void vto_ternary_unpack5(uint8_t byte, uint8_t codes[5])
+{
+    unsigned v = byte;
+    for (int j = 0; j < 5; ++j) { codes[j] = (uint8_t)(v % 3); v /= 3; }
+}
+
+int vto_round_log_dense(const double *x, uint64_t n, double tau_ulp, float *y, uint8_t *tlog,
+                        uint64_t *n_logged)
+{
+    uint32_t thr = vto_thr_from_tau(tau_ulp);
+    if (thr == 0xFFFFFFFFu || (n && (!x || !y || !tlog))) return VTO_ERR_INVALID_ARG;
+    uint64_t logged = 0;
+    for (uint64_t k = 0; k * 5 < n; ++k) {
+        uint8_t codes[5];
+        for (int j = 0; j < 5; ++j) {
+            uint64_t i = k * 5 + (uint64_t)j;
+            codes[j] = 1;                                    /* past the end: ignore */
+            if (i < n) {
+                codes[j] = (uint8_t)vto_ternary_code(x[i], thr);
+                y[i] = f32_from(vto_rnd32_bits(x[i]));
+                if (codes[j] != 1) ++logged;
+            }
+        }
+        tlog[k] = vto_ternary_pack5(codes);
+    }
+    if (n_logged) *n_logged = logged;
+    return VTO_OK;
+}
+
+int vto_round_replay_dense(const double *x, uint64_t n, const uint8_t *tlog, float *y)
+{
+    if (n && (!x || !y || !tlog)) return VTO_ERR_INVALID_ARG;
+    for (uint64_t i = 0; i < n; ++i) {
+        uint8_t codes[5];
+        vto_ternary_unpack5(tlog[i / 5], codes);             /* c = read(F) for element i */
+        y[i] = rev(x[i], codes[i % 5]);
+    }
+    return VTO_OK;
+}
+
 int vto_gemm_f64(int transA, int transB, int64_t M, int64_t N, int64_t K, double alpha,
                  const double *A, int64_t lda, const double *B, int64_t ldb,
                  const double *bias, double *C, int64_t ldc, int order)

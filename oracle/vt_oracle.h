@@ -69,6 +69,22 @@ int vto_round_log(const double *x, uint64_t n, double tau_ulp, float *y,
 int vto_round_replay(const double *x, uint64_t n, const uint32_t *idx, const uint32_t *dir,
                      uint64_t count, float *y);
 
+/* The log as the paper stores it (Method, "Reducing storage cost"): one ternary entry per
+ * output -- 2 rounded up, 0 rounded down, 1 ignore -- in element order, five entries per byte by
+ * radix-3 to radix-2 conversion (3^5 = 243 <= 256, 1.6 bits per entry).  Reading taken here:
+ * byte k holds elements 5k .. 5k+4, element 5k+j as the digit of weight 3^j; positions past the
+ * end of the tensor hold 1.  The log of n outputs is ceil(n/5) bytes. */
+uint8_t vto_ternary_pack5(const uint8_t codes[5]);
+void vto_ternary_unpack5(uint8_t byte, uint8_t codes[5]);   /* digit j = (byte / 3^j) % 3 for any byte */
+
+/* Trainer side with the packed ternary log: y[i] = rnd_32(x[i]), tlog = ceil(n/5) bytes;
+ * *n_logged (optional) receives the number of entries that are not 1. */
+int vto_round_log_dense(const double *x, uint64_t n, double tau_ulp, float *y, uint8_t *tlog,
+                        uint64_t *n_logged);
+
+/* Auditor side: entry i of the packed log applied to x[i] with "rev". */
+int vto_round_replay_dense(const double *x, uint64_t n, const uint8_t *tlog, float *y);
+
 /* Scalar FP64 GEMM, C[i,j] = alpha * sum_k opA(i,k) opB(k,j) (+ bias[j]), no contraction.
  * order 0: k ascending; 1: k descending; 2: long double accumulation ("truth").
  * Row-major storage; transX != 0 means the operand is stored transposed. */

@@ -60,6 +60,15 @@ def lib():
         L.vto_gemm_f64.restype = C.c_int
         L.vto_gemm_f64.argtypes = [C.c_int, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_double,
                                    dp, C.c_int64, dp, C.c_int64, dp, dp, C.c_int64, C.c_int]
+        u8p = C.POINTER(C.c_uint8)
+        L.vto_ternary_pack5.restype = C.c_uint8
+        L.vto_ternary_pack5.argtypes = [u8p]
+        L.vto_ternary_unpack5.restype = None
+        L.vto_ternary_unpack5.argtypes = [C.c_uint8, u8p]
+        L.vto_round_log_dense.restype = C.c_int
+        L.vto_round_log_dense.argtypes = [dp, C.c_uint64, C.c_double, fp, u8p, u64p]
+        L.vto_round_replay_dense.restype = C.c_int
+        L.vto_round_replay_dense.argtypes = [dp, C.c_uint64, u8p, fp]
         L.vto_conv2d_out_size.restype = C.c_int
         L.vto_conv2d_out_size.argtypes = [C.POINTER(Conv2d), C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
         L.vto_conv2d_fwd_f64.restype = C.c_int
@@ -129,6 +138,46 @@ def round_replay(x, idx, dirw, count: int | None = None):
                                 _p(dirw, C.c_uint32), count, _p(y, C.c_float))
     if rc != 0:
         raise ValueError(f"vto_round_replay: error {rc}")
+    return y
+
+
+def ternary_pack5(codes) -> int:
+    c = np.ascontiguousarray(codes, np.uint8)
+    assert c.size == 5
+    return int(lib().vto_ternary_pack5(_p(c, C.c_uint8)))
+
+
+def ternary_unpack5(byte: int):
+    c = np.zeros(5, np.uint8)
+    lib().vto_ternary_unpack5(int(byte), _p(c, C.c_uint8))
+    return c
+
+
+def round_log_dense(x, tau_ulp: float):
+    """Returns (y float32[n], tlog uint8[ceil(n/5)], n_logged)."""
+    x = _f64(x).ravel()
+    n = x.size
+    y = np.empty(n, np.float32)
+    tlog = np.zeros(max((n + 4) // 5, 1), np.uint8)
+    cnt = C.c_uint64(0)
+    rc = lib().vto_round_log_dense(_p(x, C.c_double), n, float(tau_ulp), _p(y, C.c_float), _p(tlog, C.c_uint8),
+                                   C.byref(cnt))
+    if rc != 0:
+        raise ValueError(f"vto_round_log_dense: error {rc}")
+    return y, tlog[:(n + 4) // 5].copy(), int(cnt.value)
+
+
+def round_replay_dense(x, tlog):
+    x = _f64(x).ravel()
+    n = x.size
+    t = np.ascontiguousarray(tlog, np.uint8)
+    assert t.size >= (n + 4) // 5
+    if t.size == 0:
+        t = np.zeros(1, np.uint8)
+    y = np.empty(n, np.float32)
+    rc = lib().vto_round_replay_dense(_p(x, C.c_double), n, _p(t, C.c_uint8), _p(y, C.c_float))
+    if rc != 0:
+        raise ValueError(f"vto_round_replay_dense: error {rc}")
     return y
 
 
