@@ -230,6 +230,13 @@ def main():
         rp_call, rp_kern = timed(lambda: vt.vt_round_replay(xad, logs.idx, logs.dir, cnt, y2))
         st_call, _ = timed(lambda: vt.vt_threshold_stats(xd, xad, stats))
         mism_s = int((y1.view(torch.int32) != y2.view(torch.int32)).sum().item())
+        # the same tensor with the log in the paper's packed ternary form (five entries per byte)
+        dlog = vt.alloc_dense_log(n)
+        rd_call, rd_kern = timed(lambda: vt.vt_round_log(xd, tau_s, y1, dlog, wss))
+        pd_call, pd_kern = timed(lambda: vt.vt_round_replay_dense(xad, dlog.dense, y2))
+        mism_d = int((y1.view(torch.int32) != y2.view(torch.int32)).sum().item())
+        cnt_d = int(dlog.count.item())
+        bytes_d = n * (8 + 4 + 0.2)
         rho = cnt / n
         bytes_rl = n * (8 + 4 + rho * 4.125)
         out["standalone"] = {
@@ -242,8 +249,16 @@ def main():
             "replay_frac_hbm": round(bytes_rl / rp_call * 1e-6 / HBM_PEAK_GBS, 4),
             "stats_ms": round(st_call, 4), "stats_GBs": round(n * 16 / st_call * 1e-6, 1),
             "replay_mismatches": mism_s,
+            "packed_ternary_log": {
+                "log_bytes_per_element": 0.2, "logged": cnt_d,
+                "round_log_ms": round(rd_call, 4), "round_log_GBs": round(bytes_d / rd_call * 1e-6, 1),
+                "round_log_frac_hbm": round(bytes_d / rd_call * 1e-6 / HBM_PEAK_GBS, 4),
+                "round_log_main_kernel_ms": round(rd_kern, 4),
+                "replay_ms": round(pd_call, 4), "replay_GBs": round(bytes_d / pd_call * 1e-6, 1),
+                "replay_frac_hbm": round(bytes_d / pd_call * 1e-6 / HBM_PEAK_GBS, 4),
+                "replay_mismatches": mism_d},
         }
-        del xd, xad, y1, y2, logs, wss
+        del xd, xad, y1, y2, logs, wss, dlog
 
     # ------------------------------------------------ CPU oracle baseline (bounded sample)
     if not args.no_cpu:

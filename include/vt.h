@@ -38,6 +38,15 @@
  *            canonical order) are stored; all other outputs of the call are still complete,
  *            and the caller may re-run with a larger log.
  *   Unlogged outputs are the paper's code 1 ("ignore").
+ *
+ * The same decisions in the paper's own storage format (Method, "Reducing storage cost"): when
+ * `dense` is not NULL the call writes one ternary entry per output instead -- 2 rounded up,
+ * 0 rounded down, 1 ignore -- in output order, five entries per byte by radix-3 to radix-2
+ * conversion: byte k holds outputs 5k .. 5k+4, output 5k+j with weight 3^j, and the tail of the
+ * last byte holds 1.  The buffer is ceil(total / 5) bytes, 4-byte aligned; `cap` must then be 0
+ * (idx and dir are not used) and `count` still receives the number of entries that are not 1.
+ * 1.6 bits per output whatever the density: smaller than the index list once more than about
+ * 5 % of the outputs are logged.
  */
 #ifndef VT_H
 #define VT_H
@@ -67,6 +76,7 @@ typedef struct vt_log {
     uint32_t *dir;    /* [ceil(cap / 32)] packed direction bits, see above                */
     uint64_t  cap;    /* capacity in entries                                              */
     uint64_t *count;  /* device scalar: number of logged outputs (may exceed cap)         */
+    uint8_t  *dense;  /* NULL, or [ceil(total / 5)] packed ternary log (then cap must be 0) */
 } vt_log;
 
 /*
@@ -98,6 +108,14 @@ int vt_round_log(const double *x, uint64_t n, double tau_ulp, float *y, const vt
  */
 int vt_round_replay(const double *x, uint64_t n, const uint32_t *idx, const uint32_t *dir,
                     uint64_t count, float *y, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Auditor side from the packed ternary log (same primitive "rev"; the log is positional, so entry
+ * i is read for output i as Algorithm "audit" does).
+ *   tlog     device, ceil(n / 5) bytes as written through vt_log.dense, 4-byte aligned.  Bytes
+ *            above 242 (never written by the trainer) decode digit by digit, the sixth dropped.
+ */
+int vt_round_replay_dense(const double *x, uint64_t n, const uint8_t *tlog, float *y, void *hip_stream);
 
 /*
  * The layer itself, fused with the trainer hook (Algorithm "train": output <- l(input) in

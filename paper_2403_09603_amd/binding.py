@@ -24,7 +24,8 @@ class VtError(RuntimeError):
 
 
 class _VtLog(C.Structure):
-    _fields_ = [("idx", C.c_void_p), ("dir", C.c_void_p), ("cap", C.c_uint64), ("count", C.c_void_p)]
+    _fields_ = [("idx", C.c_void_p), ("dir", C.c_void_p), ("cap", C.c_uint64), ("count", C.c_void_p),
+                ("dense", C.c_void_p)]
 
 
 class Conv2d(C.Structure):
@@ -51,6 +52,8 @@ def load_library():
     L.vt_round_log.argtypes = [vp, u64, dbl, vp, C.POINTER(_VtLog), vp, C.c_size_t, vp]
     L.vt_round_replay.restype = cint
     L.vt_round_replay.argtypes = [vp, u64, vp, vp, u64, vp, vp, C.c_size_t, vp]
+    L.vt_round_replay_dense.restype = cint
+    L.vt_round_replay_dense.argtypes = [vp, u64, vp, vp, vp]
     L.vt_gemm_f64_round_log.restype = cint
     L.vt_gemm_f64_round_log.argtypes = [cint, cint, i64, i64, i64, dbl, vp, i64, i64, vp, i64, i64, vp, i64,
                                         vp, i64, i64, vp, cint, dbl, C.POINTER(_VtLog), vp, C.c_size_t, vp]
@@ -108,10 +111,13 @@ class Log:
     dir: torch.Tensor      # int32 [ceil(cap/32)]
     count: torch.Tensor    # int64 [1]
     cap: int
+    dense: torch.Tensor | None = None   # uint8 [ceil(total/5)]: packed ternary log (then cap is 0)
 
     def _c(self) -> _VtLog:
+        if self.dense is not None and (not self.dense.is_cuda or self.dense.dtype != torch.uint8):
+            raise VtError("dense log must be a uint8 tensor on the GPU")
         return _VtLog(self.idx.data_ptr() if self.cap else None, self.dir.data_ptr() if self.cap else None,
-                      self.cap, self.count.data_ptr())
+                      self.cap, self.count.data_ptr(), self.dense.data_ptr() if self.dense is not None else None)
 
 
 def alloc_log(cap: int, device="cuda") -> Log:
@@ -119,6 +125,14 @@ def alloc_log(cap: int, device="cuda") -> Log:
     return Log(torch.empty(max(cap, 1), dtype=torch.int32, device=device),
                torch.empty(max((cap + 31) // 32, 1), dtype=torch.int32, device=device),
                torch.zeros(1, dtype=torch.int64, device=device), cap)
+
+
+def alloc_dense_log(total: int, device="cuda") -> Log:
+    """Buffers for the packed ternary form of the log of `total` outputs (five entries per byte)."""
+    total = int(total)
+    return Log(torch.empty(1, dtype=torch.int32, device=device), torch.empty(1, dtype=torch.int32, device=device),
+               torch.zeros(1, dtype=torch.int64, device=device), 0,
+               torch.empty(max((total + 4) // 5, 4), dtype=torch.uint8, device=device))
 
 
 def vt_workspace_bytes(op: int, M: int, N: int, K: int = 0, batch: int = 1) -> int:
@@ -137,6 +151,8 @@ def vt_round_log(x: torch.Tensor, tau_ulp: float, y: torch.Tensor, log: Log, ws:
     n = x.numel()
     if y.numel() != n:
         raise VtError("y must have as many elements as x")
+    if log.dense is not None and log.dense.numel() < (n + 4) // 5:
+        raise VtError("dense log is smaller than ceil(n/5) bytes")
     clog = log._c()
     _check(load_library().vt_round_log(_ptr(x, torch.float64), n, float(tau_ulp), _ptr(y, torch.float32),
                                        C.byref(clog), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)),
@@ -156,6 +172,16 @@ def vt_round_replay(x: torch.Tensor, idx: torch.Tensor, dir: torch.Tensor, count
            "vt_round_replay")
 
 
+def vt_round_replay_dense(x: torch.Tensor, tlog: torch.Tensor, y: torch.Tensor, stream=None):
+    n = x.numel()
+    if y.numel() != n:
+        raise VtError("y must have as many elements as x")
+    if tlog.dtype != torch.uint8 or tlog.numel() < (n + 4) // 5:
+        raise VtError("tlog must be a uint8 tensor of ceil(n/5) bytes")
+    _check(load_library().vt_round_replay_dense(_ptr(x, torch.float64), n, _ptr(tlog), _ptr(y, torch.float32),
+                                                _stream(stream)), "vt_round_replay_dense")
+
+
 def vt_gemm_f64_round_log(transA: bool, transB: bool, M: int, N: int, K: int, alpha: float,
                           A: torch.Tensor, lda: int, strideA: int, B: torch.Tensor, ldb: int, strideB: int,
                           bias, batch: int, C32: torch.Tensor, ldc: int, strideC: int, C64_debug,
@@ -173,6 +199,8 @@ def vt_gemm_f64_round_log(transA: bool, transB: bool, M: int, N: int, K: int, al
         raise VtError("bias is shorter than N")
     if C64_debug is not None and C64_debug.numel() < M * N * batch:
         raise VtError("C64_debug is smaller than M*N*batch")
+    if log.dense is not None and log.dense.numel() < (M * N * batch + 4) // 5:
+        raise VtError("dense log is smaller than ceil(M*N*batch/5) bytes")
     clog = log._c()
     _check(load_library().vt_gemm_f64_round_log(
         int(bool(transA)), int(bool(transB)), int(M), int(N), int(K), float(alpha),
@@ -202,6 +230,8 @@ def vt_conv2d_f64_round_log(mode: int, d: Conv2d, Cout: int, X: torch.Tensor, B:
         raise VtError("output is smaller than the geometry implies")
     if bias is not None and bias.numel() < N:
         raise VtError("bias is shorter than Cout")
+    if log.dense is not None and log.dense.numel() < (M * N + 4) // 5:
+        raise VtError("dense log is smaller than ceil(outputs/5) bytes")
     clog = log._c()
     _check(load_library().vt_conv2d_f64_round_log(
         int(mode), C.byref(d), int(Cout), _ptr(X, torch.float64), _ptr(B, torch.float64), _ptr(bias, torch.float64),

@@ -19,13 +19,14 @@ inline bool log_ok(const vt_log *log)
 {
     if (!log || !log->count || !aligned(log->count, 8)) return false;
     if (log->cap && (!log->idx || !log->dir || !aligned(log->idx, 4) || !aligned(log->dir, 4))) return false;
+    if (log->dense && (log->cap || !aligned(log->dense, 4))) return false;      // one format per call
     return true;
 }
 
 inline size_t round_log_bytes(uint64_t n)
 {
-    const size_t a = vt::planes_bytes(1, n), b = vt::onepass_bytes(n);
-    return a > b ? a : b;
+    const size_t a = vt::planes_bytes(1, n), b = vt::onepass_bytes(n), c = vt::dense_count_bytes();
+    return a > b ? (a > c ? a : c) : (b > c ? b : c);
 }
 
 inline bool split_allowed(int64_t M, int64_t N, int64_t batch, int64_t ldc, int64_t strideC)
@@ -37,6 +38,12 @@ inline bool split_allowed(int64_t M, int64_t N, int64_t batch, int64_t ldc, int6
 int round_log_flat(const double *x, uint64_t n, uint32_t thr, float *y, const vt_log *log, void *ws, hipStream_t s,
                    bool mark)
 {
+    if (log->dense) {                       // packed ternary log: positional, a plain stream
+        if (mark) mark_begin(s);
+        const hipError_t e0 = vt::launch_round_log_dense(x, n, thr, y, log->dense, log->count, (uint64_t *)ws, s);
+        if (mark) mark_end(s);
+        return hip_status(e0);
+    }
     const vt::LogOut lo{log->idx, log->dir, log->cap, log->count};
     if (vt::onepass_usable(x, y)) {         // one streaming pass; otherwise bit-planes + compaction
         if (mark) mark_begin(s);
@@ -54,13 +61,13 @@ int round_log_flat(const double *x, uint64_t n, uint32_t thr, float *y, const vt
 }
 
 // planes already hold the decisions: count per segment (unless the producer did), scan, compact
-int finish_log(const vt::Planes &pl, const vt_log *log, bool counted, hipStream_t s)
+int finish_log(const vt::Planes &pl, uint64_t rows, const vt_log *log, bool counted, hipStream_t s)
 {
     const vt::LogOut lo{log->idx, log->dir, log->cap, log->count};
     hipError_t e = hipSuccess;
     if (!counted) e = vt::launch_seg_count(pl, s);
-    if (e == hipSuccess) e = vt::launch_seg_scan(pl, lo, s);
-    if (e == hipSuccess) e = vt::launch_compact(pl, lo, s);
+    if (e == hipSuccess) e = vt::launch_seg_scan(pl, lo, s);                 // also writes *count
+    if (e == hipSuccess) e = log->dense ? vt::launch_planes_to_dense(pl, rows, log->dense, s) : vt::launch_compact(pl, lo, s);
     return hip_status(e);
 }
 
@@ -89,7 +96,7 @@ int run_gemm(vt::GemmArgs &g, const vt_log *log, void *ws, size_t ws_bytes, hipS
     hipError_t e = vt::launch_gemm_round_planes(g, plan, pl, nullptr, nullptr, s);
     mark_end(s);
     if (e != hipSuccess) return VT_ERR_HIP;
-    return finish_log(pl, log, /*counted=*/false, s);
+    return finish_log(pl, (uint64_t)M * (uint64_t)batch, log, /*counted=*/false, s);
 }
 
 // Validates a convolution geometry and fills the internal descriptor (with the output size).
@@ -181,6 +188,16 @@ int vt_round_replay(const double *x, uint64_t n, const uint32_t *idx, const uint
     hipStream_t s = (hipStream_t)hip_stream;
     mark_begin(s);
     const hipError_t e = vt::launch_replay(x, n, idx, dir, count, y, s);
+    mark_end(s);
+    return hip_status(e);
+}
+
+int vt_round_replay_dense(const double *x, uint64_t n, const uint8_t *tlog, float *y, void *hip_stream)
+{
+    if (n && (!x || !y || !tlog || !aligned(x, 8) || !aligned(y, 4) || !aligned(tlog, 4))) return VT_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)hip_stream;
+    mark_begin(s);
+    const hipError_t e = vt::launch_replay_dense(x, n, tlog, y, s);
     mark_end(s);
     return hip_status(e);
 }

@@ -53,6 +53,13 @@ hipError_t launch_round_log_onepass(const double *x, uint64_t n, uint32_t thr, f
 hipError_t launch_replay(const double *x, uint64_t n, const uint32_t *idx, const uint32_t *dir,
                          uint64_t count, float *y, hipStream_t s);
 
+// the paper's packed ternary log (five entries per byte): trainer, auditor, and from bit-planes
+size_t dense_count_bytes();   // scratch for the logged-output count of the call below
+hipError_t launch_round_log_dense(const double *x, uint64_t n, uint32_t thr, float *y, uint8_t *tlog,
+                                  uint64_t *n_logged, uint64_t *slots, hipStream_t s);
+hipError_t launch_replay_dense(const double *x, uint64_t n, const uint8_t *tlog, float *y, hipStream_t s);
+hipError_t launch_planes_to_dense(const Planes &pl, uint64_t rows, uint8_t *tlog, hipStream_t s);
+
 hipError_t launch_stats(const double *y1, const double *y2, uint64_t n, uint64_t *out, hipStream_t s);
 
 // Geometry of a channels-last convolution whose image the GEMM kernel reads through an implicit

@@ -1,0 +1,295 @@
+// vt_round_dense.hip -- the log in the paper's own storage format (gfx950, wave64).
+//
+// One ternary entry per output (2 rounded up, 0 rounded down, 1 ignore), five entries per byte
+// by radix-3 to radix-2 conversion: byte k holds elements 5k .. 5k+4, element 5k+j with weight
+// 3^j; the tail of the last byte holds 1.  The format is positional, so neither side needs a
+// scan or a search: both kernels are plain streams, 8 B in and 4.2 B out per element (trainer),
+// 8.2 B in and 4 B out (auditor).
+//
+// A wavefront works on 1280 consecutive elements: ten rows of 128, each lane loading two
+// neighbouring values per row (16-byte, coalesced), all ten loads in flight at once; one
+// workgroup of four waves per 5120 elements, as the plain convert-copy that reaches the highest
+// bandwidth on this part is shaped.  Five consecutive elements live in different lanes, so the
+// codes cross the wave through LDS: written by (row, lane), read back twenty at a time by the
+// lane that packs (or unpacks) four bytes of the log.
+//
+// The number of logged outputs is summed into 256 counters spread over as many cache lines (one
+// atomic per wave; atomics on a single address would serialise at about 11 ns each, longer than
+// the whole stream) and folded by a one-workgroup kernel afterwards.
+#include "vt_device.h"
+#include "vt_kernels.h"
+
+namespace vt {
+
+namespace {
+
+typedef double d2 __attribute__((ext_vector_type(2)));
+typedef float f2 __attribute__((ext_vector_type(2)));
+
+constexpr int kRows = 10;                     // rows of 128 per wave: 1280 elements, 256 log bytes
+constexpr uint32_t kChunk = 128u * kRows;
+constexpr int kWaves = 4;                     // 256 threads
+constexpr uint32_t kTile = kChunk * kWaves;   // 5120 elements, 1024 log bytes per workgroup
+constexpr uint32_t kSlots = 256, kSlotStride = 8;   // counters, one per 64-byte line (in uint64 units)
+
+__global__ __launch_bounds__(256) void zero_slots_kernel(uint64_t *slots) { slots[threadIdx.x * kSlotStride] = 0; }
+
+__global__ __launch_bounds__(256) void sum_slots_kernel(const uint64_t *__restrict__ slots, uint64_t *__restrict__ out)
+{
+    __shared__ unsigned long long total;
+    if (threadIdx.x == 0) total = 0;
+    __syncthreads();
+    atomicAdd(&total, (unsigned long long)slots[threadIdx.x * kSlotStride]);     // integer sum: order-free
+    __syncthreads();
+    if (threadIdx.x == 0) *out = total;
+}
+
+__global__ void zero_u64_kernel(uint64_t *p) { *p = 0; }
+
+// ternary code and FP32 bits of one value
+__device__ __forceinline__ uint32_t code_of(double x, uint32_t thr, uint32_t &ybits)
+{
+    const FastDecision f = decide_fast(x);
+    ybits = __float_as_uint(f.y);
+    bool logged = f.D < thr, up = f.grow != f.neg;
+    if (__builtin_expect(f.slow, 0)) {
+        const Decision d = decide((uint64_t)__double_as_longlong(x));
+        ybits = d.ybits; logged = d.D < thr; up = d.dir != 0;
+    }
+    return logged ? (up ? 2u : 0u) : 1u;
+}
+
+template <bool FULL, bool VEC>
+__device__ __forceinline__ void load_rows(const double *__restrict__ x, uint64_t n, uint64_t base, uint32_t lane,
+                                          d2 (&v)[kRows])
+{
+#pragma unroll
+    for (int u = 0; u < kRows; ++u) {
+        const uint64_t e = base + (uint64_t)u * 128u + 2u * lane;
+        if (VEC && (FULL || e + 1 < n)) v[u] = __builtin_nontemporal_load((const d2 *)(x + e));
+        else {
+            v[u].x = e < n ? x[e] : 1.0;                          // 1.0 is never logged: code 1 in the tail
+            v[u].y = e + 1 < n ? x[e + 1] : 1.0;
+        }
+    }
+}
+
+template <bool FULL, bool VEC>
+__device__ __forceinline__ void store_pair(float *__restrict__ y, uint64_t n, uint64_t e, uint32_t ya, uint32_t yb)
+{
+    if (VEC && (FULL || e + 1 < n)) {
+        f2 o;
+        o.x = __uint_as_float(ya);
+        o.y = __uint_as_float(yb);
+        __builtin_nontemporal_store(o, (f2 *)(y + e));
+    } else {
+        if (e < n) y[e] = __uint_as_float(ya);
+        if (e + 1 < n) y[e + 1] = __uint_as_float(yb);
+    }
+}
+
+// Trainer: y = rnd_32(x), tlog = packed codes.  One workgroup per 5120 elements.
+template <bool FULL, bool VEC>
+__device__ __forceinline__ void round_log_dense_chunk(const double *__restrict__ x, uint64_t n, uint32_t thr,
+                                                      float *__restrict__ y, uint8_t *__restrict__ tlog,
+                                                      uint64_t base, uint32_t lane, uint8_t *__restrict__ mine,
+                                                      uint64_t *__restrict__ slots)
+{
+    d2 v[kRows];
+    load_rows<FULL, VEC>(x, n, base, lane, v);
+    uint32_t logged = 0;
+#pragma unroll
+    for (int u = 0; u < kRows; ++u) {
+        uint32_t ya, yb;
+        const uint32_t ca = code_of(v[u].x, thr, ya), cb = code_of(v[u].y, thr, yb);
+        store_pair<FULL, VEC>(y, n, base + (uint64_t)u * 128u + 2u * lane, ya, yb);
+        logged += (ca != 1u) + (cb != 1u);
+        *(uint16_t *)(mine + u * 128 + 2 * lane) = (uint16_t)(ca | (cb << 8));
+    }
+    wave_lds_fence();
+    // this lane packs elements 20 lane .. 20 lane + 19 of the chunk: four bytes of the log
+    uint32_t w[5];
+#pragma unroll
+    for (int k = 0; k < 5; ++k) w[k] = *(const uint32_t *)(mine + 20 * lane + 4 * k);
+    uint32_t packed = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {                                 // byte q: codes 5 q .. 5 q + 4
+        uint32_t byte = 0, weight = 1;
+#pragma unroll
+        for (int j = 0; j < 5; ++j) {
+            const int c = 5 * q + j;
+            byte += ((w[c >> 2] >> (8 * (c & 3))) & 0xFFu) * weight;
+            weight *= 3u;
+        }
+        packed |= byte << (8 * q);
+    }
+    const uint64_t byte0 = base / 5u + 4u * lane;                 // base is a multiple of 1280
+    if (FULL) *(uint32_t *)(tlog + byte0) = packed;
+    else {
+        const uint64_t nbytes = (n + 4) / 5;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (byte0 + q < nbytes) tlog[byte0 + q] = (uint8_t)(packed >> (8 * q));
+    }
+    if (slots) {
+        logged = wave_sum(logged);
+        if (lane == 0 && logged)
+            atomicAdd((unsigned long long *)(slots + ((blockIdx.x * kWaves + (threadIdx.x >> 6)) % kSlots) * kSlotStride),
+                      (unsigned long long)logged);
+    }
+}
+
+template <bool VEC>
+__global__ __launch_bounds__(256) void round_log_dense_kernel(const double *__restrict__ x, uint64_t n, uint32_t thr,
+                                                              float *__restrict__ y, uint8_t *__restrict__ tlog,
+                                                              uint64_t *__restrict__ slots)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t codes[kWaves][kChunk];
+    const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
+    const uint64_t base = (uint64_t)blockIdx.x * kTile + (uint64_t)wv * kChunk;
+    if (base >= n) return;
+    if (base + kChunk <= n) round_log_dense_chunk<true, VEC>(x, n, thr, y, tlog, base, lane, codes[wv], slots);
+    else round_log_dense_chunk<false, VEC>(x, n, thr, y, tlog, base, lane, codes[wv], slots);
+}
+
+// Auditor: entry i of the packed log applied to x[i].
+template <bool FULL, bool VEC>
+__device__ __forceinline__ void replay_dense_chunk(const double *__restrict__ x, uint64_t n,
+                                                   const uint8_t *__restrict__ tlog, float *__restrict__ y,
+                                                   uint64_t base, uint32_t lane, uint8_t *__restrict__ mine)
+{
+    d2 v[kRows];
+    load_rows<FULL, VEC>(x, n, base, lane, v);
+    // four bytes of the log -> twenty codes, written where their elements' lanes will look
+    const uint64_t byte0 = base / 5u + 4u * lane;
+    uint32_t packed = 0x79797979u;                                // 0x79 = 121 = five times "ignore"
+    if (FULL) packed = *(const uint32_t *)(tlog + byte0);
+    else {
+        const uint64_t nbytes = (n + 4) / 5;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (byte0 + q < nbytes) packed = (packed & ~(0xFFu << (8 * q))) | ((uint32_t)tlog[byte0 + q] << (8 * q));
+    }
+    uint32_t w[5] = {0, 0, 0, 0, 0};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        uint32_t byte = (packed >> (8 * q)) & 0xFFu;
+#pragma unroll
+        for (int j = 0; j < 5; ++j) {
+            const int c = 5 * q + j;
+            w[c >> 2] |= (byte % 3u) << (8 * (c & 3));
+            byte /= 3u;
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 5; ++k) *(uint32_t *)(mine + 20 * lane + 4 * k) = w[k];
+    wave_lds_fence();
+#pragma unroll
+    for (int u = 0; u < kRows; ++u) {
+        const uint32_t cw = *(const uint16_t *)(mine + u * 128 + 2 * lane);
+        const uint32_t ca = cw & 0xFFu, cb = cw >> 8;
+        const uint64_t ba = (uint64_t)__double_as_longlong(v[u].x), bb = (uint64_t)__double_as_longlong(v[u].y);
+        // unlogged: nearest (hardware conversion where it cannot differ from the definition);
+        // logged: toward the recorded side
+        const FastDecision fa = decide_fast(v[u].x), fb = decide_fast(v[u].y);
+        uint32_t ya = __float_as_uint(fa.y), yb = __float_as_uint(fb.y);
+        if (__builtin_expect(fa.slow, 0)) ya = decide(ba).ybits;
+        if (__builtin_expect(fb.slow, 0)) yb = decide(bb).ybits;
+        if (ca != 1u) ya = directed(ba, ca >> 1);
+        if (cb != 1u) yb = directed(bb, cb >> 1);
+        store_pair<FULL, VEC>(y, n, base + (uint64_t)u * 128u + 2u * lane, ya, yb);
+    }
+}
+
+template <bool VEC>
+__global__ __launch_bounds__(256) void replay_dense_kernel(const double *__restrict__ x, uint64_t n,
+                                                           const uint8_t *__restrict__ tlog, float *__restrict__ y)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t codes[kWaves][kChunk];
+    const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
+    const uint64_t base = (uint64_t)blockIdx.x * kTile + (uint64_t)wv * kChunk;
+    if (base >= n) return;
+    if (base + kChunk <= n) replay_dense_chunk<true, VEC>(x, n, tlog, y, base, lane, codes[wv]);
+    else replay_dense_chunk<false, VEC>(x, n, tlog, y, base, lane, codes[wv]);
+}
+
+// Decision bit-planes of a dense (rows x ncols) output -> packed ternary log; one thread per byte.
+__global__ __launch_bounds__(256) void planes_to_dense_kernel(const uint64_t *__restrict__ logged,
+                                                              const uint64_t *__restrict__ dir, uint32_t wpr,
+                                                              uint32_t ncols, uint64_t total, uint8_t *__restrict__ tlog)
+{
+    const uint64_t k = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+    if (k * 5 >= total) return;
+    uint32_t byte = 0, weight = 1;
+    uint32_t row = (uint32_t)((k * 5) / ncols), col = (uint32_t)((k * 5) % ncols);
+#pragma unroll
+    for (int j = 0; j < 5; ++j) {
+        uint32_t code = 1;
+        if (k * 5 + (uint64_t)j < total) {
+            const uint64_t w = (uint64_t)row * wpr + (col >> 6);
+            const uint32_t lg = (uint32_t)(logged[w] >> (col & 63u)) & 1u, up = (uint32_t)(dir[w] >> (col & 63u)) & 1u;
+            code = lg ? 2u * up : 1u;
+        }
+        byte += code * weight;
+        weight *= 3u;
+        if (++col == ncols) { col = 0; ++row; }
+    }
+    tlog[k] = (uint8_t)byte;
+}
+
+}  // namespace
+
+size_t dense_count_bytes() { return (size_t)kSlots * kSlotStride * 8; }
+
+// `slots`: dense_count_bytes() of scratch, needed when n_logged is wanted
+hipError_t launch_round_log_dense(const double *x, uint64_t n, uint32_t thr, float *y, uint8_t *tlog,
+                                  uint64_t *n_logged, uint64_t *slots, hipStream_t s)
+{
+    if (n == 0 || !n_logged || !slots) {
+        if (n_logged) {
+            zero_u64_kernel<<<1, 1, 0, s>>>(n_logged);
+            const hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+        if (n == 0) return hipSuccess;
+        slots = nullptr;
+    } else {
+        zero_slots_kernel<<<1, kSlots, 0, s>>>(slots);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    const uint64_t blocks = (n + kTile - 1) / kTile;
+    if (((uintptr_t)x % 16 == 0) && ((uintptr_t)y % 8 == 0))
+        round_log_dense_kernel<true><<<(uint32_t)blocks, 256, 0, s>>>(x, n, thr, y, tlog, slots);
+    else
+        round_log_dense_kernel<false><<<(uint32_t)blocks, 256, 0, s>>>(x, n, thr, y, tlog, slots);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && slots) {
+        sum_slots_kernel<<<1, kSlots, 0, s>>>(slots, n_logged);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+hipError_t launch_replay_dense(const double *x, uint64_t n, const uint8_t *tlog, float *y, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    const uint64_t blocks = (n + kTile - 1) / kTile;
+    if (((uintptr_t)x % 16 == 0) && ((uintptr_t)y % 8 == 0))
+        replay_dense_kernel<true><<<(uint32_t)blocks, 256, 0, s>>>(x, n, tlog, y);
+    else
+        replay_dense_kernel<false><<<(uint32_t)blocks, 256, 0, s>>>(x, n, tlog, y);
+    return hipGetLastError();
+}
+
+hipError_t launch_planes_to_dense(const Planes &pl, uint64_t rows, uint8_t *tlog, hipStream_t s)
+{
+    const uint64_t total = rows * (uint64_t)pl.ncols;
+    if (total == 0) return hipSuccess;
+    const uint64_t bytes = (total + 4) / 5;
+    planes_to_dense_kernel<<<(uint32_t)((bytes + 255) / 256), 256, 0, s>>>(pl.logged, pl.dir, pl.wpr, pl.ncols, total,
+                                                                         tlog);
+    return hipGetLastError();
+}
+
+}  // namespace vt

@@ -127,3 +127,70 @@ def gpu_conv(mode, X, B, KH, KW, *, stride=1, pad=0, dil=1, bias=None, tau=0.0, 
     return {"C32": C32.cpu().numpy()[:M * Nn].reshape(M, Nn), "C64": C64.cpu().numpy()[:M * Nn].reshape(M, Nn),
             "idx": u32(log.idx)[:count].copy(), "dir": u32(log.dir)[:(count + 31) // 32].copy(), "count": count,
             "shape": (M, Nn, K)}
+
+
+def gpu_round_log_dense(x, tau, misalign=False):
+    """Standalone trainer hook writing the packed ternary log: (y, tlog bytes, n_logged)."""
+    x = np.ascontiguousarray(x, np.float64).ravel()
+    n = x.size
+    if misalign:
+        buf = torch.empty(n + 1, dtype=torch.float64, device=DEV)
+        xd = buf[1:]
+        if n:
+            xd.copy_(torch.from_numpy(x))
+    else:
+        xd = dev(x) if n else torch.empty(0, dtype=torch.float64, device=DEV)
+    y = torch.empty(n, dtype=torch.float32, device=DEV)
+    log = vt.alloc_dense_log(n)
+    log.dense.fill_(0xEE)
+    log.count.fill_(-1)
+    ws = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_ROUND_LOG, 1, n))
+    vt.vt_round_log(xd, tau, y, log, ws)
+    torch.cuda.synchronize()
+    full = log.dense.cpu().numpy()
+    assert (full[(n + 4) // 5:] == 0xEE).all()               # nothing written past the log
+    return y.cpu().numpy(), full[:(n + 4) // 5].copy(), int(log.count.item())
+
+
+def gpu_round_replay_dense(x, tlog, misalign=False):
+    x = np.ascontiguousarray(x, np.float64).ravel()
+    if misalign:
+        buf = torch.empty(x.size + 1, dtype=torch.float64, device=DEV)
+        xd = buf[1:]
+        xd.copy_(torch.from_numpy(x))
+    else:
+        xd = dev(x) if x.size else torch.empty(0, dtype=torch.float64, device=DEV)
+    t = np.ascontiguousarray(tlog, np.uint8)
+    td = dev(t) if t.size else torch.zeros(4, dtype=torch.uint8, device=DEV)
+    y = torch.empty(x.size, dtype=torch.float32, device=DEV)
+    vt.vt_round_replay_dense(xd, td, y)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+def gpu_gemm_dense(A, B, *, transA=False, transB=False, alpha=1.0, bias=None, tau=0.0, variant=0, ldc=None):
+    """GEMM entry point with the packed ternary log as output format."""
+    A = np.ascontiguousarray(A, np.float64)
+    B = np.ascontiguousarray(B, np.float64)
+    batch = A.shape[0] if A.ndim == 3 else 1
+    a2, b2 = A.shape[-2:], B.shape[-2:]
+    M, K = (a2[1], a2[0]) if transA else a2
+    K2, N = (b2[1], b2[0]) if transB else b2
+    assert K == K2
+    strideA = a2[0] * a2[1] if A.ndim == 3 else 0
+    strideB = b2[0] * b2[1] if B.ndim == 3 else 0
+    ldc = N if ldc is None else ldc
+    total = batch * M * N
+    C32 = torch.full((batch, M, ldc), float("nan"), dtype=torch.float32, device=DEV)
+    C64 = torch.empty((batch, M, N), dtype=torch.float64, device=DEV)
+    log = vt.alloc_dense_log(total)
+    log.dense.fill_(0xEE)
+    ws = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG, M, N, K, batch))
+    bias_d = dev(np.ascontiguousarray(bias, np.float64)) if bias is not None else None
+    vt.vt_gemm_f64_round_log(transA, transB, M, N, K, alpha, dev(A), a2[1], strideA, dev(B), b2[1], strideB, bias_d, batch,
+                             C32, ldc, M * ldc, C64, variant, tau, log, ws)
+    torch.cuda.synchronize()
+    full = log.dense.cpu().numpy()
+    assert (full[max((total + 4) // 5, 0):] == 0xEE).all()
+    return {"C32": C32.cpu().numpy()[:, :, :N].reshape(batch, M, N), "C64": C64.cpu().numpy(),
+            "tlog": full[:(total + 4) // 5].copy(), "count": int(log.count.item())}

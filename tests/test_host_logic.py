@@ -57,7 +57,7 @@ def test_argument_validation_happens_on_the_host(hiplib):
     """None of these calls may reach a kernel launch: they run here without a GPU."""
     import paper_2403_09603_amd.binding as b
     cnt = (C.c_uint64 * 1)()
-    log = b._VtLog(None, None, 0, C.addressof(cnt))
+    log = b._VtLog(None, None, 0, C.addressof(cnt), None)
     fake = C.c_void_p(0x1000)
     INVALID, WORKSPACE = 1, 2
     assert hiplib.vt_round_log(fake, 16, 0.75, fake, C.byref(log), fake, 1 << 20, None) == INVALID   # tau
@@ -66,8 +66,14 @@ def test_argument_validation_happens_on_the_host(hiplib):
     assert hiplib.vt_round_log(fake, 16, 0.1, fake, None, fake, 1 << 20, None) == INVALID
     assert hiplib.vt_round_log(fake, 16, 0.1, fake, C.byref(log), None, 0, None) == WORKSPACE
     assert hiplib.vt_round_log(fake, 1 << 20, 0.1, fake, C.byref(log), fake, 1024, None) == WORKSPACE
-    badlog = b._VtLog(None, None, 8, C.addressof(cnt))
+    badlog = b._VtLog(None, None, 8, C.addressof(cnt), None)
     assert hiplib.vt_round_log(fake, 16, 0.1, fake, C.byref(badlog), fake, 1 << 20, None) == INVALID
+    both = b._VtLog(0x1000, 0x1000, 8, C.addressof(cnt), 0x2000)                 # two formats in one call
+    assert hiplib.vt_round_log(fake, 16, 0.1, fake, C.byref(both), fake, 1 << 20, None) == INVALID
+    odd = b._VtLog(None, None, 0, C.addressof(cnt), 0x2001)                      # misaligned packed log
+    assert hiplib.vt_round_log(fake, 16, 0.1, fake, C.byref(odd), fake, 1 << 20, None) == INVALID
+    assert hiplib.vt_round_replay_dense(fake, 16, None, fake, None) == INVALID
+    assert hiplib.vt_round_replay_dense(fake, 16, C.c_void_p(0x2002), fake, None) == INVALID
     assert hiplib.vt_round_replay(fake, 1 << 32, None, None, 0, fake, None, 0, None) == INVALID
     assert hiplib.vt_round_replay(fake, 16, None, None, 4, fake, None, 0, None) == INVALID
     g = hiplib.vt_gemm_f64_round_log
@@ -88,7 +94,7 @@ def test_argument_validation_happens_on_the_host(hiplib):
 def test_conv_geometry_and_validation_on_the_host(hiplib):
     import paper_2403_09603_amd.binding as b
     cnt = (C.c_uint64 * 1)()
-    log = b._VtLog(None, None, 0, C.addressof(cnt))
+    log = b._VtLog(None, None, 0, C.addressof(cnt), None)
     fake = C.c_void_p(0x1000)
     INVALID, WORKSPACE = 1, 2
     # GEMM shapes of the ResNet-50 geometry at batch 64 against the oracle's output size
