@@ -21,6 +21,46 @@ static float    f32_from(uint32_t b) { float x; memcpy(&x, &b, 4); return x; }
  * roundTiesToEven, so the definition is the cast itself. */
 static float rnd32(double x) { return (float)x; }
 
+/* Method, primitive 1 for b_r < 32 (and the caption of the floating-point figure): the nearest
+ * 32-bit float that has zeros in the last 32 - b_r bits of its mantissa, i.e. the nearest point
+ * of the grid with b_r - 9 mantissa bits in x's binade (spacing 2^(32 - b_r) ulp32).  Written
+ * with exact binary64 steps: scale so that the grid becomes the integers, round to the nearest
+ * integer with ties to even (rint under the default mode), scale back.  Below 2^-126 the FP32
+ * spacing is fixed at 2^-149, so the grid is the multiples of 2^(-149 + 32 - b_r).  A result of
+ * 2^128 or more is infinity.  b_r = 32 is the cast above. */
+static int valid_br(int b_r) { return b_r >= 10 && b_r <= 32; }
+
+static int grid_scale_exponent(double x, int b_r)      /* grid spacing at x is 2^(-this) */
+{
+    int E = ilogb(x);
+    if (E < -126) E = -126;
+    return (b_r - 9) - E;
+}
+
+static float rnd_b(double x, int b_r)
+{
+    if (b_r == 32) return rnd32(x);
+    if (isnan(x) || isinf(x) || x == 0.0) return (float)x;
+    int sc = grid_scale_exponent(x, b_r);
+    double y = scalbn(rint(scalbn(x, sc)), -sc);        /* exact: |x| 2^sc < 2^24 has <= 53 bits */
+    return (float)y;                                    /* on the FP32 grid already; >= 2^128 -> inf */
+}
+
+/* x rounded down (toward -inf) or up (toward +inf) on the same grid: what "rev" returns. */
+static float directed_b(double x, int b_r, int up)
+{
+    if (isnan(x) || isinf(x) || x == 0.0) return (float)x;
+    int sc = grid_scale_exponent(x, b_r);
+    double t = scalbn(x, sc);
+    double y = scalbn(up ? ceil(t) : floor(t), -sc);
+    if (y == 0.0) y = copysign(0.0, x);                 /* keeps the sign of x, like IEEE directed rounding */
+    if (fabs(y) >= 0x1p128) {                           /* past the largest finite grid value */
+        double top = scalbn(ldexp(1.0, b_r - 8) - 1.0, 127 - (b_r - 9));
+        y = (up == (x > 0)) ? copysign(INFINITY, x) : copysign(top, x);
+    }
+    return (float)y;
+}
+
 uint32_t vto_rnd32_bits(double x)
 {
     if (isnan(x)) return 0x7FC00000u;
@@ -38,35 +78,49 @@ uint32_t vto_thr_from_tau(double tau_ulp)
  *  - FP32-normal and larger magnitudes: the test does not depend on the binade, so x is
  *    scaled by a power of two into [1,2), where ulp32 = 2^-23 and the unit is 2^-52.
  *  - magnitudes below 2^-126: FP32 spacing is fixed at 2^-149, unit 2^-178. */
-double vto_scaled_round_error(double x)
+/* For b_r < 32 the grid spacing is 2^(32 - b_r) ulp32(x) and the unit is 2^-29 of THAT spacing,
+ * so the result is still a real in [0, 2^28] (no longer always an integer). */
+double vto_scaled_round_error_b(double x, int b_r)
 {
     if (isnan(x) || isinf(x)) return -1.0;
     if (x == 0.0) return 0.0;
-    int E = ilogb(x);
+    int E = ilogb(x), k = 32 - b_r;
     if (E >= -126) {
-        double xs = scalbn(x, -E);                 /* exact, |xs| in [1,2) */
-        double d  = fabs(xs - (double)rnd32(xs));  /* exact: both are multiples of 2^-52 */
-        return ldexp(d, 52);
+        double xs = scalbn(x, -E);                      /* exact, |xs| in [1,2) */
+        double d  = fabs(xs - (double)rnd_b(xs, b_r));  /* exact: both are multiples of 2^-52 */
+        return ldexp(d, 52 - k);
     } else {
-        double d = fabs(x - (double)rnd32(x));     /* exact: |d| <= 2^-150 on x's own grid */
-        return ldexp(d, 178);
+        double d = fabs(x - (double)rnd_b(x, b_r));     /* exact: |d| <= 2^(-150+k) on x's own grid */
+        return ldexp(d, 178 - k);
     }
 }
 
-uint32_t vto_boundary_distance(double x)
+double vto_scaled_round_error(double x) { return vto_scaled_round_error_b(x, 32); }
+
+uint32_t vto_boundary_distance_b(double x, int b_r)
 {
-    double q = vto_scaled_round_error(x);
+    double q = vto_scaled_round_error_b(x, b_r);
     if (q < 0.0) return 1u << 28;
     return (uint32_t)(TWO28 - ceil(q)); /* floor(2^28 - q) without rounding the subtraction */
 }
 
+uint32_t vto_boundary_distance(double x) { return vto_boundary_distance_b(x, 32); }
+
+uint32_t vto_rnd_b_bits(double x, int b_r)
+{
+    if (isnan(x)) return 0x7FC00000u;
+    return f32_bits(rnd_b(x, b_r));
+}
+
 /* Algorithm "log": three-way decision.  exp*tau of the paper equals
  * (0.5 - thr 2^-29) ulp32(x); in the scaled unit that is 2^28 - thr. */
-int vto_ternary_code(double x, uint32_t thr)
+int vto_ternary_code(double x, uint32_t thr) { return vto_ternary_code_b(x, thr, 32); }
+
+int vto_ternary_code_b(double x, uint32_t thr, int b_r)
 {
-    double q = vto_scaled_round_error(x);
+    double q = vto_scaled_round_error_b(x, b_r);
     if (q < 0.0) return 1;                              /* NaN, +-Inf: ignore */
-    double y = (double)rnd32(x);                        /* may be +-Inf on overflow */
+    double y = (double)rnd_b(x, b_r);                   /* may be +-Inf on overflow */
     if (q > TWO28 - (double)thr && x < y) return 2;     /* far from rnd(x), rounded up */
     if (q > TWO28 - (double)thr && x > y) return 0;     /* far from rnd(x), rounded down */
     return 1;
@@ -75,15 +129,21 @@ int vto_ternary_code(double x, uint32_t thr)
 int vto_round_log(const double *x, uint64_t n, double tau_ulp, float *y,
                   uint32_t *idx, uint32_t *dir, uint64_t cap, uint64_t *count)
 {
+    return vto_round_log_b(x, n, tau_ulp, 32, y, idx, dir, cap, count);
+}
+
+int vto_round_log_b(const double *x, uint64_t n, double tau_ulp, int b_r, float *y,
+                    uint32_t *idx, uint32_t *dir, uint64_t cap, uint64_t *count)
+{
     uint32_t thr = vto_thr_from_tau(tau_ulp);
-    if (thr == 0xFFFFFFFFu || n >= (1ull << 32) || !count) return VTO_ERR_INVALID_ARG;
+    if (thr == 0xFFFFFFFFu || n >= (1ull << 32) || !count || !valid_br(b_r)) return VTO_ERR_INVALID_ARG;
     if (n && (!x || !y)) return VTO_ERR_INVALID_ARG;
     if (cap && (!idx || !dir)) return VTO_ERR_INVALID_ARG;
     for (uint64_t w = 0; w < (cap + 31) / 32; ++w) dir[w] = 0;
     uint64_t c = 0;
     for (uint64_t i = 0; i < n; ++i) {
-        int code = vto_ternary_code(x[i], thr);         /* log(output, ...) first ... */
-        y[i] = f32_from(vto_rnd32_bits(x[i]));          /* ... then output = rnd(output) */
+        int code = vto_ternary_code_b(x[i], thr, b_r);  /* log(output, ...) first ... */
+        y[i] = f32_from(vto_rnd_b_bits(x[i], b_r));     /* ... then output = rnd(output) */
         if (code != 1) {
             if (c < cap) {
                 idx[c] = (uint32_t)i;
@@ -98,19 +158,30 @@ int vto_round_log(const double *x, uint64_t n, double tau_ulp, float *y,
 
 /* Primitive "rev" as the paper words it: round to nearest, then, if the trainer went the
  * other way, take the neighbouring FP32 value on the trainer's side of x. */
-static float rev(double x, int code)
+static float rev(double x, int code, int b_r)
 {
     if (isnan(x)) return f32_from(0x7FC00000u);
-    float y = rnd32(x);
-    if (code == 0 && x < (double)y) return nextafterf(y, -INFINITY); /* float below x */
-    if (code == 2 && x > (double)y) return nextafterf(y, INFINITY);  /* float above x */
+    float y = rnd_b(x, b_r);
+    if (b_r == 32) {
+        if (code == 0 && x < (double)y) return nextafterf(y, -INFINITY); /* float below x */
+        if (code == 2 && x > (double)y) return nextafterf(y, INFINITY);  /* float above x */
+        return y;
+    }
+    if (code == 0 && x < (double)y) return directed_b(x, b_r, 0);    /* grid point below x */
+    if (code == 2 && x > (double)y) return directed_b(x, b_r, 1);    /* grid point above x */
     return y;
 }
 
 int vto_round_replay(const double *x, uint64_t n, const uint32_t *idx, const uint32_t *dir,
                      uint64_t count, float *y)
 {
-    if (n >= (1ull << 32)) return VTO_ERR_INVALID_ARG;
+    return vto_round_replay_b(x, n, idx, dir, count, 32, y);
+}
+
+int vto_round_replay_b(const double *x, uint64_t n, const uint32_t *idx, const uint32_t *dir,
+                       uint64_t count, int b_r, float *y)
+{
+    if (n >= (1ull << 32) || !valid_br(b_r)) return VTO_ERR_INVALID_ARG;
     if (n && (!x || !y)) return VTO_ERR_INVALID_ARG;
     if (count && (!idx || !dir)) return VTO_ERR_INVALID_ARG;
     uint64_t p = 0;
@@ -121,7 +192,7 @@ int vto_round_replay(const double *x, uint64_t n, const uint32_t *idx, const uin
             code = ((dir[p >> 5] >> (p & 31)) & 1u) ? 2 : 0;
             ++p;
         }
-        y[i] = rev(x[i], code);
+        y[i] = rev(x[i], code, b_r);
     }
     return VTO_OK;
 }
@@ -142,8 +213,14 @@ void vto_ternary_unpack5(uint8_t byte, uint8_t codes[5])
 int vto_round_log_dense(const double *x, uint64_t n, double tau_ulp, float *y, uint8_t *tlog,
                         uint64_t *n_logged)
 {
+    return vto_round_log_dense_b(x, n, tau_ulp, 32, y, tlog, n_logged);
+}
+
+int vto_round_log_dense_b(const double *x, uint64_t n, double tau_ulp, int b_r, float *y, uint8_t *tlog,
+                          uint64_t *n_logged)
+{
     uint32_t thr = vto_thr_from_tau(tau_ulp);
-    if (thr == 0xFFFFFFFFu || (n && (!x || !y || !tlog))) return VTO_ERR_INVALID_ARG;
+    if (thr == 0xFFFFFFFFu || !valid_br(b_r) || (n && (!x || !y || !tlog))) return VTO_ERR_INVALID_ARG;
     uint64_t logged = 0;
     for (uint64_t k = 0; k * 5 < n; ++k) {
         uint8_t codes[5];
@@ -151,8 +228,8 @@ int vto_round_log_dense(const double *x, uint64_t n, double tau_ulp, float *y, u
             uint64_t i = k * 5 + (uint64_t)j;
             codes[j] = 1;                                    /* past the end: ignore */
             if (i < n) {
-                codes[j] = (uint8_t)vto_ternary_code(x[i], thr);
-                y[i] = f32_from(vto_rnd32_bits(x[i]));
+                codes[j] = (uint8_t)vto_ternary_code_b(x[i], thr, b_r);
+                y[i] = f32_from(vto_rnd_b_bits(x[i], b_r));
                 if (codes[j] != 1) ++logged;
             }
         }
@@ -164,11 +241,16 @@ int vto_round_log_dense(const double *x, uint64_t n, double tau_ulp, float *y, u
 
 int vto_round_replay_dense(const double *x, uint64_t n, const uint8_t *tlog, float *y)
 {
-    if (n && (!x || !y || !tlog)) return VTO_ERR_INVALID_ARG;
+    return vto_round_replay_dense_b(x, n, tlog, 32, y);
+}
+
+int vto_round_replay_dense_b(const double *x, uint64_t n, const uint8_t *tlog, int b_r, float *y)
+{
+    if (!valid_br(b_r) || (n && (!x || !y || !tlog))) return VTO_ERR_INVALID_ARG;
     for (uint64_t i = 0; i < n; ++i) {
         uint8_t codes[5];
         vto_ternary_unpack5(tlog[i / 5], codes);             /* c = read(F) for element i */
-        y[i] = rev(x[i], codes[i % 5]);
+        y[i] = rev(x[i], codes[i % 5], b_r);
     }
     return VTO_OK;
 }
@@ -293,7 +375,12 @@ static int64_t ord64(double y)
 
 int vto_threshold_stats(const double *y1, const double *y2, uint64_t n, uint64_t out[68])
 {
-    if (!out || (n && (!y1 || !y2))) return VTO_ERR_INVALID_ARG;
+    return vto_threshold_stats_b(y1, y2, n, 32, out);
+}
+
+int vto_threshold_stats_b(const double *y1, const double *y2, uint64_t n, int b_r, uint64_t out[68])
+{
+    if (!out || !valid_br(b_r) || (n && (!y1 || !y2))) return VTO_ERR_INVALID_ARG;
     for (int b = 0; b < 68; ++b) out[b] = 0;
     for (uint64_t i = 0; i < n; ++i) {
         int64_t o1 = ord64(y1[i]), o2 = ord64(y2[i]);
@@ -302,9 +389,9 @@ int vto_threshold_stats(const double *y1, const double *y2, uint64_t n, uint64_t
         for (uint64_t d = diff; d; d >>= 1) ++bin;      /* 0, else 1 + floor(log2 diff) */
         out[3 + bin] += 1;
         if (diff > out[2]) out[2] = diff;
-        if (vto_rnd32_bits(y1[i]) != vto_rnd32_bits(y2[i])) {   /* rnd(y1) != rnd(y2) */
-            uint32_t d1 = vto_boundary_distance(y1[i]);
-            uint32_t d2 = vto_boundary_distance(y2[i]);
+        if (vto_rnd_b_bits(y1[i], b_r) != vto_rnd_b_bits(y2[i], b_r)) {   /* rnd(y1) != rnd(y2) */
+            uint32_t d1 = vto_boundary_distance_b(y1[i], b_r);
+            uint32_t d2 = vto_boundary_distance_b(y2[i], b_r);
             uint64_t need = 1 + (uint64_t)(d1 > d2 ? d1 : d2);
             out[0] += 1;
             if (need > out[1]) out[1] = need;

@@ -116,6 +116,24 @@ int vto_conv2d_fwd_f64(const vto_conv2d *d, int64_t Cout, const double *X, const
 int vto_conv2d_wgrad_f64(const vto_conv2d *d, int64_t Cout, const double *X, const double *dY,
                          double *dW, int order);
 
+/* The same primitives with a rounding amount b_r < 32 (Method, primitives rnd_{b_r}, log, rev;
+ * caption of the floating-point figure: the nearest 32-bit float with zeros in the last 32 - b_r
+ * mantissa bits).  The grid spacing is 2^(32 - b_r) ulp32(x); tau_ulp and thr are measured in
+ * units of THAT spacing (thr = ceil(tau_ulp 2^29) as before), so the threshold search range
+ * [0.25, 0.5] x spacing keeps its meaning.  10 <= b_r <= 32; b_r = 32 is the functions above. */
+uint32_t vto_rnd_b_bits(double x, int b_r);
+double vto_scaled_round_error_b(double x, int b_r);
+uint32_t vto_boundary_distance_b(double x, int b_r);
+int vto_ternary_code_b(double x, uint32_t thr, int b_r);
+int vto_round_log_b(const double *x, uint64_t n, double tau_ulp, int b_r, float *y,
+                    uint32_t *idx, uint32_t *dir, uint64_t cap, uint64_t *count);
+int vto_round_replay_b(const double *x, uint64_t n, const uint32_t *idx, const uint32_t *dir,
+                       uint64_t count, int b_r, float *y);
+int vto_round_log_dense_b(const double *x, uint64_t n, double tau_ulp, int b_r, float *y, uint8_t *tlog,
+                          uint64_t *n_logged);
+int vto_round_replay_dense_b(const double *x, uint64_t n, const uint8_t *tlog, int b_r, float *y);
+int vto_threshold_stats_b(const double *y1, const double *y2, uint64_t n, int b_r, uint64_t out[68]);
+
 /* Threshold statistics over two results of the same operation (Algorithm "threshold",
  * collection loop): out[0] = number of elements whose FP32 roundings differ (bit patterns),
  * out[1] = 1 + max over those of max(D(y1), D(y2)) (0 when there are none),

@@ -69,6 +69,24 @@ def lib():
         L.vto_round_log_dense.argtypes = [dp, C.c_uint64, C.c_double, fp, u8p, u64p]
         L.vto_round_replay_dense.restype = C.c_int
         L.vto_round_replay_dense.argtypes = [dp, C.c_uint64, u8p, fp]
+        L.vto_rnd_b_bits.restype = C.c_uint32
+        L.vto_rnd_b_bits.argtypes = [C.c_double, C.c_int]
+        L.vto_scaled_round_error_b.restype = C.c_double
+        L.vto_scaled_round_error_b.argtypes = [C.c_double, C.c_int]
+        L.vto_boundary_distance_b.restype = C.c_uint32
+        L.vto_boundary_distance_b.argtypes = [C.c_double, C.c_int]
+        L.vto_ternary_code_b.restype = C.c_int
+        L.vto_ternary_code_b.argtypes = [C.c_double, C.c_uint32, C.c_int]
+        L.vto_round_log_b.restype = C.c_int
+        L.vto_round_log_b.argtypes = [dp, C.c_uint64, C.c_double, C.c_int, fp, u32p, u32p, C.c_uint64, u64p]
+        L.vto_round_replay_b.restype = C.c_int
+        L.vto_round_replay_b.argtypes = [dp, C.c_uint64, u32p, u32p, C.c_uint64, C.c_int, fp]
+        L.vto_round_log_dense_b.restype = C.c_int
+        L.vto_round_log_dense_b.argtypes = [dp, C.c_uint64, C.c_double, C.c_int, fp, u8p, u64p]
+        L.vto_round_replay_dense_b.restype = C.c_int
+        L.vto_round_replay_dense_b.argtypes = [dp, C.c_uint64, u8p, C.c_int, fp]
+        L.vto_threshold_stats_b.restype = C.c_int
+        L.vto_threshold_stats_b.argtypes = [dp, dp, C.c_uint64, C.c_int, u64p]
         L.vto_conv2d_out_size.restype = C.c_int
         L.vto_conv2d_out_size.argtypes = [C.POINTER(Conv2d), C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
         L.vto_conv2d_fwd_f64.restype = C.c_int
@@ -97,19 +115,23 @@ def thr_from_tau(tau_ulp: float) -> int:
     return int(lib().vto_thr_from_tau(float(tau_ulp)))
 
 
-def scaled_round_error(x: float) -> float:
-    return float(lib().vto_scaled_round_error(float(x)))
+def rnd_bits(x: float, b_r: int = 32) -> int:
+    return int(lib().vto_rnd_b_bits(float(x), int(b_r)))
 
 
-def boundary_distance(x: float) -> int:
-    return int(lib().vto_boundary_distance(float(x)))
+def scaled_round_error(x: float, b_r: int = 32) -> float:
+    return float(lib().vto_scaled_round_error_b(float(x), int(b_r)))
 
 
-def ternary_code(x: float, thr: int) -> int:
-    return int(lib().vto_ternary_code(float(x), int(thr)))
+def boundary_distance(x: float, b_r: int = 32) -> int:
+    return int(lib().vto_boundary_distance_b(float(x), int(b_r)))
 
 
-def round_log(x, tau_ulp: float, cap: int | None = None):
+def ternary_code(x: float, thr: int, b_r: int = 32) -> int:
+    return int(lib().vto_ternary_code_b(float(x), int(thr), int(b_r)))
+
+
+def round_log(x, tau_ulp: float, cap: int | None = None, b_r: int = 32):
     """Returns (y float32[n], idx uint32[min(count,cap)], dir words uint32[ceil(cap/32)], count)."""
     x = _f64(x).ravel()
     n = x.size
@@ -118,8 +140,8 @@ def round_log(x, tau_ulp: float, cap: int | None = None):
     idx = np.zeros(max(cap, 1), np.uint32)
     dirw = np.zeros(max((cap + 31) // 32, 1), np.uint32)
     cnt = C.c_uint64(0)
-    rc = lib().vto_round_log(_p(x, C.c_double), n, float(tau_ulp), _p(y, C.c_float),
-                             _p(idx, C.c_uint32), _p(dirw, C.c_uint32), cap, C.byref(cnt))
+    rc = lib().vto_round_log_b(_p(x, C.c_double), n, float(tau_ulp), int(b_r), _p(y, C.c_float),
+                               _p(idx, C.c_uint32), _p(dirw, C.c_uint32), cap, C.byref(cnt))
     if rc != 0:
         raise ValueError(f"vto_round_log: error {rc}")
     c = int(cnt.value)
@@ -127,15 +149,15 @@ def round_log(x, tau_ulp: float, cap: int | None = None):
     return y, idx[:k].copy(), dirw[:(k + 31) // 32].copy(), c
 
 
-def round_replay(x, idx, dirw, count: int | None = None):
+def round_replay(x, idx, dirw, count: int | None = None, b_r: int = 32):
     x = _f64(x).ravel()
     idx = np.ascontiguousarray(idx, dtype=np.uint32)
     dirw = np.ascontiguousarray(dirw, dtype=np.uint32)
     count = idx.size if count is None else int(count)
     assert dirw.size * 32 >= count and idx.size >= count
     y = np.empty(x.size, np.float32)
-    rc = lib().vto_round_replay(_p(x, C.c_double), x.size, _p(idx, C.c_uint32),
-                                _p(dirw, C.c_uint32), count, _p(y, C.c_float))
+    rc = lib().vto_round_replay_b(_p(x, C.c_double), x.size, _p(idx, C.c_uint32),
+                                  _p(dirw, C.c_uint32), count, int(b_r), _p(y, C.c_float))
     if rc != 0:
         raise ValueError(f"vto_round_replay: error {rc}")
     return y
@@ -153,21 +175,21 @@ def ternary_unpack5(byte: int):
     return c
 
 
-def round_log_dense(x, tau_ulp: float):
+def round_log_dense(x, tau_ulp: float, b_r: int = 32):
     """Returns (y float32[n], tlog uint8[ceil(n/5)], n_logged)."""
     x = _f64(x).ravel()
     n = x.size
     y = np.empty(n, np.float32)
     tlog = np.zeros(max((n + 4) // 5, 1), np.uint8)
     cnt = C.c_uint64(0)
-    rc = lib().vto_round_log_dense(_p(x, C.c_double), n, float(tau_ulp), _p(y, C.c_float), _p(tlog, C.c_uint8),
-                                   C.byref(cnt))
+    rc = lib().vto_round_log_dense_b(_p(x, C.c_double), n, float(tau_ulp), int(b_r), _p(y, C.c_float),
+                                     _p(tlog, C.c_uint8), C.byref(cnt))
     if rc != 0:
         raise ValueError(f"vto_round_log_dense: error {rc}")
     return y, tlog[:(n + 4) // 5].copy(), int(cnt.value)
 
 
-def round_replay_dense(x, tlog):
+def round_replay_dense(x, tlog, b_r: int = 32):
     x = _f64(x).ravel()
     n = x.size
     t = np.ascontiguousarray(tlog, np.uint8)
@@ -175,7 +197,7 @@ def round_replay_dense(x, tlog):
     if t.size == 0:
         t = np.zeros(1, np.uint8)
     y = np.empty(n, np.float32)
-    rc = lib().vto_round_replay_dense(_p(x, C.c_double), n, _p(t, C.c_uint8), _p(y, C.c_float))
+    rc = lib().vto_round_replay_dense_b(_p(x, C.c_double), n, _p(t, C.c_uint8), int(b_r), _p(y, C.c_float))
     if rc != 0:
         raise ValueError(f"vto_round_replay_dense: error {rc}")
     return y
@@ -242,12 +264,12 @@ def conv2d_wgrad(X, dY, KH, KW, *, stride=1, pad=0, dil=1, order=0):
     return dW
 
 
-def threshold_stats(y1, y2):
+def threshold_stats(y1, y2, b_r: int = 32):
     y1, y2 = _f64(y1).ravel(), _f64(y2).ravel()
     assert y1.size == y2.size
     out = np.zeros(68, np.uint64)
-    rc = lib().vto_threshold_stats(_p(y1, C.c_double), _p(y2, C.c_double), y1.size,
-                                   _p(out, C.c_uint64))
+    rc = lib().vto_threshold_stats_b(_p(y1, C.c_double), _p(y2, C.c_double), y1.size, int(b_r),
+                                     _p(out, C.c_uint64))
     if rc != 0:
         raise ValueError(f"vto_threshold_stats: error {rc}")
     return {"n_flip": int(out[0]), "thr_flip": int(out[1]), "max_ulp64_diff": int(out[2]),

@@ -24,15 +24,22 @@ def floor_log2(v: Fraction) -> int:
     return e
 
 
-def ulp32(v: Fraction) -> Fraction:
+def ulp32(v: Fraction, b: int = 32) -> Fraction:
+    """Spacing at v of the 32-bit floats whose last 32 - b mantissa bits are zero (b = 32: FP32)."""
     if v == 0:
-        return TWO ** -149
-    return TWO ** (max(floor_log2(abs(v)), -126) - 23)
+        return TWO ** (-149 + 32 - b)
+    return TWO ** (max(floor_log2(abs(v)), -126) - 23 + 32 - b)
 
 
-def rnd32_unbounded(v: Fraction) -> Fraction:
-    """Nearest multiple of ulp32(v), ties to the even multiple; exponent range unbounded above."""
-    u = ulp32(v)
+def top_finite(b: int = 32) -> Fraction:
+    """Largest finite value of that grid: b - 8 significant bits, all ones, in the top binade."""
+    m = b - 9
+    return Fraction((2 ** (m + 1) - 1) * 2 ** (127 - m))
+
+
+def rnd32_unbounded(v: Fraction, b: int = 32) -> Fraction:
+    """Nearest multiple of the spacing at v, ties to the even multiple; exponent range unbounded above."""
+    u = ulp32(v, b)
     q = v / u
     lo = math.floor(q)
     frac = q - lo
@@ -51,48 +58,49 @@ def f32_bits_of_value(v: Fraction, negative_zero: bool = False) -> int:
     return struct.unpack("<I", b)[0]
 
 
-def rnd32_bits(x: float) -> int:
-    """IEEE binary64 -> binary32, roundTiesToEven, as a bit pattern."""
+def rnd32_bits(x: float, b: int = 32) -> int:
+    """IEEE binary64 -> binary32, roundTiesToEven, as a bit pattern (b < 32: onto the coarser grid)."""
     if math.isnan(x):
         return 0x7FC00000
     if math.isinf(x):
         return 0x7F800000 if x > 0 else 0xFF800000
     v = Fraction(x)
-    r = rnd32_unbounded(v)
+    r = rnd32_unbounded(v, b)
     neg = math.copysign(1.0, x) < 0
     if abs(r) > FLT_MAX:
         return 0xFF800000 if neg else 0x7F800000
     return f32_bits_of_value(r, negative_zero=neg)
 
 
-def round_directed_bits(x: float, up: bool) -> int:
+def round_directed_bits(x: float, up: bool, b: int = 32) -> int:
     """roundTowardPositive (up) / roundTowardNegative (not up) of a binary64 value to FP32."""
     if math.isnan(x):
         return 0x7FC00000
     if math.isinf(x):
         return 0x7F800000 if x > 0 else 0xFF800000
     v = Fraction(x)
-    u = ulp32(v)
+    u = ulp32(v, b)
     q = v / u
     k = math.ceil(q) if up else math.floor(q)
     r = k * u
     neg = math.copysign(1.0, x) < 0
-    if r > FLT_MAX:
-        return 0x7F800000 if up else f32_bits_of_value(FLT_MAX)
-    if r < -FLT_MAX:
-        return f32_bits_of_value(-FLT_MAX) if up else 0xFF800000
+    top = top_finite(b)
+    if r > top:
+        return 0x7F800000 if up else f32_bits_of_value(top)
+    if r < -top:
+        return f32_bits_of_value(-top) if up else 0xFF800000
     return f32_bits_of_value(r, negative_zero=neg)
 
 
-def ternary_code(x: float, thr: int) -> int:
+def ternary_code(x: float, thr: int, b: int = 32) -> int:
     """Algorithm "log" with tau = (1/2 - thr 2^-29) 2^-23: 2 = logged/up, 0 = logged/down,
     1 = ignore.  rnd is taken on the unbounded grid, so values that overflow FP32 are judged
     against the grid continued past FLT_MAX (the direction is still by value: rnd = +-inf)."""
     if math.isnan(x) or math.isinf(x):
         return 1
     v = Fraction(x)
-    r = rnd32_unbounded(v)
-    tau_scaled = (Fraction(1, 2) - Fraction(thr, 2 ** 29)) * ulp32(v)   # exp * tau
+    r = rnd32_unbounded(v, b)
+    tau_scaled = (Fraction(1, 2) - Fraction(thr, 2 ** 29)) * ulp32(v, b)   # exp * tau
     far = abs(v - r) > tau_scaled
     if abs(r) > FLT_MAX:                       # the value actually produced is +-inf
         return 1 if not far else (2 if v > 0 else 0)
@@ -103,23 +111,23 @@ def ternary_code(x: float, thr: int) -> int:
     return 1
 
 
-def boundary_distance(x: float) -> int:
+def boundary_distance(x: float, b: int = 32) -> int:
     """floor of (ulp32/2 - |x - rnd(x)|) in units of 2^-29 ulp32; 2^28 for NaN/Inf."""
     if math.isnan(x) or math.isinf(x):
         return 1 << 28
     v = Fraction(x)
-    r = rnd32_unbounded(v)
-    u = ulp32(v)
+    r = rnd32_unbounded(v, b)
+    u = ulp32(v, b)
     return math.floor((u / 2 - abs(v - r)) / (u / 2 ** 29))
 
 
-def replay_bits(x: float, code: int) -> int:
+def replay_bits(x: float, code: int, b: int = 32) -> int:
     """Primitive "rev": code 0 -> the FP32 value below x when rnd(x) went above it, code 2 ->
     the one above x when rnd(x) went below; otherwise rnd(x).  Since rnd(x) is one of the two
     FP32 neighbours of x this is roundTowardNegative / roundTowardPositive."""
     if code == 1:
-        return rnd32_bits(x)
-    return round_directed_bits(x, up=(code == 2))
+        return rnd32_bits(x, b)
+    return round_directed_bits(x, up=(code == 2), b=b)
 
 
 def exact_dot(a, b) -> Fraction:
