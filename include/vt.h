@@ -47,6 +47,13 @@
  * (idx and dir are not used) and `count` still receives the number of entries that are not 1.
  * 1.6 bits per output whatever the density: smaller than the index list once more than about
  * 5 % of the outputs are logged.
+ *
+ * Rounding amount (Method, primitives rnd_{b_r}, log, rev; caption of the floating-point figure):
+ * `b_r` = 32 (or 0) rounds to FP32.  10 <= b_r < 32 rounds to the nearest 32-bit float whose last
+ * 32 - b_r mantissa bits are zero (b_r - 9 mantissa bits; 16 is bfloat16's grid); outputs are
+ * still stored as FP32.  The grid spacing is then 2^(32 - b_r) ulp32(x), and tau_ulp, thr and
+ * the statistics are measured relative to THAT spacing, so [0, 0.5] keeps its meaning.  The
+ * auditor passes the same b_r to the *_br replay and statistics calls.
  */
 #ifndef VT_H
 #define VT_H
@@ -69,6 +76,7 @@ extern "C" {
 #define VT_OP_ROUND_REPLAY 1   /* needs no workspace (returns 0) */
 #define VT_OP_GEMM_ROUND_LOG 2
 #define VT_OP_THRESHOLD_STATS 3 /* needs no workspace (returns 0) */
+#define VT_OP_GEMM_ROUND_LOG_BR 4 /* GEMM / convolution with log->b_r below 32 (rounds in a second pass) */
 
 /* Caller-owned log buffers (all four pointers are device pointers). */
 typedef struct vt_log {
@@ -77,6 +85,7 @@ typedef struct vt_log {
     uint64_t  cap;    /* capacity in entries                                              */
     uint64_t *count;  /* device scalar: number of logged outputs (may exceed cap)         */
     uint8_t  *dense;  /* NULL, or [ceil(total / 5)] packed ternary log (then cap must be 0) */
+    int32_t   b_r;    /* rounding amount: 0 or 32 = FP32, else 10 .. 31                    */
 } vt_log;
 
 /*
@@ -117,6 +126,11 @@ int vt_round_replay(const double *x, uint64_t n, const uint32_t *idx, const uint
  */
 int vt_round_replay_dense(const double *x, uint64_t n, const uint8_t *tlog, float *y, void *hip_stream);
 
+/* The two auditor calls above for a log that was written with rounding amount b_r (10 .. 32). */
+int vt_round_replay_br(const double *x, uint64_t n, const uint32_t *idx, const uint32_t *dir,
+                       uint64_t count, int b_r, float *y, void *hip_stream);
+int vt_round_replay_dense_br(const double *x, uint64_t n, const uint8_t *tlog, int b_r, float *y, void *hip_stream);
+
 /*
  * The layer itself, fused with the trainer hook (Algorithm "train": output <- l(input) in
  * b_tr = 64, then log and rnd; the Nondeterminism Challenge section names the tiling of
@@ -138,6 +152,10 @@ int vt_round_replay_dense(const double *x, uint64_t n, const uint8_t *tlog, floa
  *                  in their low bits, as two GPU types would.
  *   M*N*batch must be < 2^32.  A, B 8-byte aligned.
  *   ws             at least vt_workspace_bytes(VT_OP_GEMM_ROUND_LOG, M, N, K, batch) bytes.
+ *   With log->b_r below 32 the FP64 result goes through memory once and is rounded by the
+ *   standalone hook (the fused epilogue uses the hardware's FP32 conversion): C32 must then be
+ *   dense (ldc == N, strideC == M*N; VT_ERR_UNSUPPORTED otherwise) and ws is sized with
+ *   VT_OP_GEMM_ROUND_LOG_BR.
  */
 int vt_gemm_f64_round_log(int transA, int transB, int64_t M, int64_t N, int64_t K, double alpha,
                           const double *A, int64_t lda, int64_t strideA,
@@ -203,6 +221,10 @@ int vt_conv2d_gemm_shape(const vt_conv2d *d, int64_t Cout, int mode, int64_t *M,
  */
 int vt_threshold_stats(const double *y1, const double *y2, uint64_t n, uint64_t *out,
                        void *hip_stream);
+/* The same for rounding amount b_r (Algorithm "threshold" takes b_r as an input): rnd and D on the
+ * b_r grid, thr_flip in units of 2^-29 of its spacing. */
+int vt_threshold_stats_br(const double *y1, const double *y2, uint64_t n, int b_r, uint64_t *out,
+                          void *hip_stream);
 
 /* Scratch bytes needed by an operation of the given shape (0 if none). */
 size_t vt_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int64_t batch);

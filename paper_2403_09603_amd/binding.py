@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libvt_hip.so")
 _lib = None
 
-VT_OP_ROUND_LOG, VT_OP_ROUND_REPLAY, VT_OP_GEMM_ROUND_LOG, VT_OP_THRESHOLD_STATS = 0, 1, 2, 3
+VT_OP_ROUND_LOG, VT_OP_ROUND_REPLAY, VT_OP_GEMM_ROUND_LOG, VT_OP_THRESHOLD_STATS, VT_OP_GEMM_ROUND_LOG_BR = 0, 1, 2, 3, 4
 VT_CONV_FORWARD, VT_CONV_WEIGHT_GRAD = 0, 1
 
 
@@ -25,7 +25,7 @@ class VtError(RuntimeError):
 
 class _VtLog(C.Structure):
     _fields_ = [("idx", C.c_void_p), ("dir", C.c_void_p), ("cap", C.c_uint64), ("count", C.c_void_p),
-                ("dense", C.c_void_p)]
+                ("dense", C.c_void_p), ("b_r", C.c_int32)]
 
 
 class Conv2d(C.Structure):
@@ -54,6 +54,12 @@ def load_library():
     L.vt_round_replay.argtypes = [vp, u64, vp, vp, u64, vp, vp, C.c_size_t, vp]
     L.vt_round_replay_dense.restype = cint
     L.vt_round_replay_dense.argtypes = [vp, u64, vp, vp, vp]
+    L.vt_round_replay_br.restype = cint
+    L.vt_round_replay_br.argtypes = [vp, u64, vp, vp, u64, cint, vp, vp]
+    L.vt_round_replay_dense_br.restype = cint
+    L.vt_round_replay_dense_br.argtypes = [vp, u64, vp, cint, vp, vp]
+    L.vt_threshold_stats_br.restype = cint
+    L.vt_threshold_stats_br.argtypes = [vp, vp, u64, cint, vp, vp]
     L.vt_gemm_f64_round_log.restype = cint
     L.vt_gemm_f64_round_log.argtypes = [cint, cint, i64, i64, i64, dbl, vp, i64, i64, vp, i64, i64, vp, i64,
                                         vp, i64, i64, vp, cint, dbl, C.POINTER(_VtLog), vp, C.c_size_t, vp]
@@ -112,12 +118,14 @@ class Log:
     count: torch.Tensor    # int64 [1]
     cap: int
     dense: torch.Tensor | None = None   # uint8 [ceil(total/5)]: packed ternary log (then cap is 0)
+    b_r: int = 32          # rounding amount the trainer call uses (10 .. 32)
 
     def _c(self) -> _VtLog:
         if self.dense is not None and (not self.dense.is_cuda or self.dense.dtype != torch.uint8):
             raise VtError("dense log must be a uint8 tensor on the GPU")
         return _VtLog(self.idx.data_ptr() if self.cap else None, self.dir.data_ptr() if self.cap else None,
-                      self.cap, self.count.data_ptr(), self.dense.data_ptr() if self.dense is not None else None)
+                      self.cap, self.count.data_ptr(), self.dense.data_ptr() if self.dense is not None else None,
+                      int(self.b_r))
 
 
 def alloc_log(cap: int, device="cuda") -> Log:
@@ -160,26 +168,36 @@ def vt_round_log(x: torch.Tensor, tau_ulp: float, y: torch.Tensor, log: Log, ws:
 
 
 def vt_round_replay(x: torch.Tensor, idx: torch.Tensor, dir: torch.Tensor, count: int, y: torch.Tensor,
-                    stream=None):
+                    stream=None, b_r: int = 32):
     n = x.numel()
     if y.numel() != n:
         raise VtError("y must have as many elements as x")
     count = int(count)
     if count > idx.numel() or (count + 31) // 32 > dir.numel():
         raise VtError("count exceeds the log buffers")
-    _check(load_library().vt_round_replay(_ptr(x, torch.float64), n, _ptr(idx, torch.int32), _ptr(dir, torch.int32),
-                                          count, _ptr(y, torch.float32), None, 0, _stream(stream)),
-           "vt_round_replay")
+    if b_r == 32:
+        _check(load_library().vt_round_replay(_ptr(x, torch.float64), n, _ptr(idx, torch.int32),
+                                              _ptr(dir, torch.int32), count, _ptr(y, torch.float32), None, 0,
+                                              _stream(stream)), "vt_round_replay")
+    else:
+        _check(load_library().vt_round_replay_br(_ptr(x, torch.float64), n, _ptr(idx, torch.int32),
+                                                 _ptr(dir, torch.int32), count, int(b_r), _ptr(y, torch.float32),
+                                                 _stream(stream)), "vt_round_replay_br")
 
 
-def vt_round_replay_dense(x: torch.Tensor, tlog: torch.Tensor, y: torch.Tensor, stream=None):
+def vt_round_replay_dense(x: torch.Tensor, tlog: torch.Tensor, y: torch.Tensor, stream=None, b_r: int = 32):
     n = x.numel()
     if y.numel() != n:
         raise VtError("y must have as many elements as x")
     if tlog.dtype != torch.uint8 or tlog.numel() < (n + 4) // 5:
         raise VtError("tlog must be a uint8 tensor of ceil(n/5) bytes")
-    _check(load_library().vt_round_replay_dense(_ptr(x, torch.float64), n, _ptr(tlog), _ptr(y, torch.float32),
-                                                _stream(stream)), "vt_round_replay_dense")
+    if b_r == 32:
+        _check(load_library().vt_round_replay_dense(_ptr(x, torch.float64), n, _ptr(tlog), _ptr(y, torch.float32),
+                                                    _stream(stream)), "vt_round_replay_dense")
+    else:
+        _check(load_library().vt_round_replay_dense_br(_ptr(x, torch.float64), n, _ptr(tlog), int(b_r),
+                                                       _ptr(y, torch.float32), _stream(stream)),
+               "vt_round_replay_dense_br")
 
 
 def vt_gemm_f64_round_log(transA: bool, transB: bool, M: int, N: int, K: int, alpha: float,
@@ -254,10 +272,14 @@ def vt_set_kernel_events(ev_begin, ev_end):
                                                C.c_void_p(ev_end) if ev_end else None), "vt_set_kernel_events")
 
 
-def vt_threshold_stats(y1: torch.Tensor, y2: torch.Tensor, out: torch.Tensor, stream=None):
+def vt_threshold_stats(y1: torch.Tensor, y2: torch.Tensor, out: torch.Tensor, stream=None, b_r: int = 32):
     if y1.numel() != y2.numel():
         raise VtError("y1 and y2 differ in size")
     if out.numel() < 68 or out.dtype != torch.int64:
         raise VtError("out must be an int64 tensor of 68 elements")
-    _check(load_library().vt_threshold_stats(_ptr(y1, torch.float64), _ptr(y2, torch.float64), y1.numel(),
-                                             _ptr(out), _stream(stream)), "vt_threshold_stats")
+    if b_r == 32:
+        _check(load_library().vt_threshold_stats(_ptr(y1, torch.float64), _ptr(y2, torch.float64), y1.numel(),
+                                                 _ptr(out), _stream(stream)), "vt_threshold_stats")
+    else:
+        _check(load_library().vt_threshold_stats_br(_ptr(y1, torch.float64), _ptr(y2, torch.float64), y1.numel(),
+                                                    int(b_r), _ptr(out), _stream(stream)), "vt_threshold_stats_br")

@@ -20,8 +20,12 @@ inline bool log_ok(const vt_log *log)
     if (!log || !log->count || !aligned(log->count, 8)) return false;
     if (log->cap && (!log->idx || !log->dir || !aligned(log->idx, 4) || !aligned(log->dir, 4))) return false;
     if (log->dense && (log->cap || !aligned(log->dense, 4))) return false;      // one format per call
+    if (log->b_r != 0 && (log->b_r < 10 || log->b_r > 32)) return false;
     return true;
 }
+
+inline bool br_ok(int b_r) { return b_r >= 10 && b_r <= 32; }
+inline uint32_t k_of(int b_r) { return b_r == 0 ? 0u : (uint32_t)(32 - b_r); }   // zeroed low mantissa bits
 
 inline size_t round_log_bytes(uint64_t n)
 {
@@ -38,22 +42,23 @@ inline bool split_allowed(int64_t M, int64_t N, int64_t batch, int64_t ldc, int6
 int round_log_flat(const double *x, uint64_t n, uint32_t thr, float *y, const vt_log *log, void *ws, hipStream_t s,
                    bool mark)
 {
+    const uint32_t k = k_of(log->b_r);
     if (log->dense) {                       // packed ternary log: positional, a plain stream
         if (mark) mark_begin(s);
-        const hipError_t e0 = vt::launch_round_log_dense(x, n, thr, y, log->dense, log->count, (uint64_t *)ws, s);
+        const hipError_t e0 = vt::launch_round_log_dense(x, n, thr, k, y, log->dense, log->count, (uint64_t *)ws, s);
         if (mark) mark_end(s);
         return hip_status(e0);
     }
     const vt::LogOut lo{log->idx, log->dir, log->cap, log->count};
     if (vt::onepass_usable(x, y)) {         // one streaming pass; otherwise bit-planes + compaction
         if (mark) mark_begin(s);
-        const hipError_t e1 = vt::launch_round_log_onepass(x, n, thr, y, ws, lo, s);
+        const hipError_t e1 = vt::launch_round_log_onepass(x, n, thr, k, y, ws, lo, s);
         if (mark) mark_end(s);
         return hip_status(e1);
     }
     const vt::Planes pl = vt::planes_carve(ws, 1, n);
     if (mark) mark_begin(s);
-    hipError_t e = vt::launch_round_planes(x, n, thr, y, pl, s);
+    hipError_t e = vt::launch_round_planes(x, n, thr, k, y, pl, s);
     if (mark) mark_end(s);
     if (e == hipSuccess) e = vt::launch_seg_scan(pl, lo, s);
     if (e == hipSuccess) e = vt::launch_compact(pl, lo, s);
@@ -76,12 +81,16 @@ int run_gemm(vt::GemmArgs &g, const vt_log *log, void *ws, size_t ws_bytes, hipS
 {
     const int64_t M = g.M, N = g.N, K = g.K, batch = g.batch;
     const uint64_t total = (uint64_t)M * (uint64_t)N * (uint64_t)batch;
-    const size_t need = vt_workspace_bytes(VT_OP_GEMM_ROUND_LOG, M, N, K, batch);
+    // a rounding amount below 32 is applied by the standalone hook to the FP64 result in memory
+    const bool two_pass = k_of(log->b_r) != 0;
+    if (two_pass && !split_allowed(M, N, batch, g.ldc, g.strideC)) return VT_ERR_UNSUPPORTED;
+    const size_t need = vt_workspace_bytes(two_pass ? VT_OP_GEMM_ROUND_LOG_BR : VT_OP_GEMM_ROUND_LOG, M, N, K, batch);
     if (!ws || ws_bytes < need || !aligned(ws, 256)) return VT_ERR_WORKSPACE;
     const vt::Planes pl = vt::planes_carve(ws, (uint64_t)M * (uint64_t)batch, (uint64_t)N);
     const size_t planes = vt::planes_bytes((uint64_t)M * (uint64_t)batch, (uint64_t)N);
     const vt::GemmPlan plan = vt::plan_gemm(M, N, K, batch, split_allowed(M, N, batch, g.ldc, g.strideC));
-    if (plan.splits > 1) {
+    g.raw = two_pass;
+    if (plan.splits > 1 || two_pass) {
         // slabs -> fixed-order sum (alpha, bias) -> standalone round/log over the flat result
         double *partial = (double *)((char *)ws + planes);
         double *reduced = partial + (uint64_t)plan.splits * total;
@@ -154,6 +163,11 @@ size_t vt_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int64_t batch
     if (M < 0 || N < 0 || batch < 0) return 0;
     switch (op) {
     case VT_OP_ROUND_LOG: return round_log_bytes((uint64_t)M * (uint64_t)N * (uint64_t)batch);
+    case VT_OP_GEMM_ROUND_LOG_BR: {
+        const vt::GemmPlan plan = vt::plan_gemm(M, N, K < 0 ? 0 : K, batch, true);
+        return vt::planes_bytes((uint64_t)M * (uint64_t)batch, (uint64_t)N) + vt::gemm_split_bytes(M, N, batch, plan.splits) +
+               round_log_bytes((uint64_t)M * (uint64_t)N * (uint64_t)batch);
+    }
     case VT_OP_GEMM_ROUND_LOG: {
         // sized for the split-K path too (taken for dense outputs when few tiles meet a long K)
         size_t bytes = vt::planes_bytes((uint64_t)M * (uint64_t)batch, (uint64_t)N);
@@ -182,22 +196,34 @@ int vt_round_replay(const double *x, uint64_t n, const uint32_t *idx, const uint
                     uint64_t count, float *y, void *ws, size_t ws_bytes, void *hip_stream)
 {
     (void)ws; (void)ws_bytes;
-    if (n >= (1ull << 32) || count >= (1ull << 32)) return VT_ERR_INVALID_ARG;
+    return vt_round_replay_br(x, n, idx, dir, count, 32, y, hip_stream);
+}
+
+int vt_round_replay_br(const double *x, uint64_t n, const uint32_t *idx, const uint32_t *dir,
+                       uint64_t count, int b_r, float *y, void *hip_stream)
+{
+    if (n >= (1ull << 32) || count >= (1ull << 32) || !br_ok(b_r)) return VT_ERR_INVALID_ARG;
     if (n && (!x || !y || !aligned(x, 8) || !aligned(y, 4))) return VT_ERR_INVALID_ARG;
     if (count && (!idx || !dir || !aligned(idx, 4) || !aligned(dir, 4))) return VT_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)hip_stream;
     mark_begin(s);
-    const hipError_t e = vt::launch_replay(x, n, idx, dir, count, y, s);
+    const hipError_t e = vt::launch_replay(x, n, idx, dir, count, k_of(b_r), y, s);
     mark_end(s);
     return hip_status(e);
 }
 
 int vt_round_replay_dense(const double *x, uint64_t n, const uint8_t *tlog, float *y, void *hip_stream)
 {
+    return vt_round_replay_dense_br(x, n, tlog, 32, y, hip_stream);
+}
+
+int vt_round_replay_dense_br(const double *x, uint64_t n, const uint8_t *tlog, int b_r, float *y, void *hip_stream)
+{
+    if (!br_ok(b_r)) return VT_ERR_INVALID_ARG;
     if (n && (!x || !y || !tlog || !aligned(x, 8) || !aligned(y, 4) || !aligned(tlog, 4))) return VT_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)hip_stream;
     mark_begin(s);
-    const hipError_t e = vt::launch_replay_dense(x, n, tlog, y, s);
+    const hipError_t e = vt::launch_replay_dense(x, n, tlog, k_of(b_r), y, s);
     mark_end(s);
     return hip_status(e);
 }
@@ -280,9 +306,14 @@ int vt_conv2d_f64_round_log(int mode, const vt_conv2d *d, int64_t Cout, const do
 
 int vt_threshold_stats(const double *y1, const double *y2, uint64_t n, uint64_t *out, void *hip_stream)
 {
-    if (!out || !aligned(out, 8)) return VT_ERR_INVALID_ARG;
+    return vt_threshold_stats_br(y1, y2, n, 32, out, hip_stream);
+}
+
+int vt_threshold_stats_br(const double *y1, const double *y2, uint64_t n, int b_r, uint64_t *out, void *hip_stream)
+{
+    if (!out || !aligned(out, 8) || !br_ok(b_r)) return VT_ERR_INVALID_ARG;
     if (n && (!y1 || !y2 || !aligned(y1, 8) || !aligned(y2, 8))) return VT_ERR_INVALID_ARG;
-    return hip_status(vt::launch_stats(y1, y2, n, out, (hipStream_t)hip_stream));
+    return hip_status(vt::launch_stats(y1, y2, n, k_of(b_r), out, (hipStream_t)hip_stream));
 }
 
 int vt_gemm_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int64_t ldc, int64_t strideC,

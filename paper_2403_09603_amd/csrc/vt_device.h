@@ -144,6 +144,117 @@ static __host__ __device__ __forceinline__ uint32_t directed(uint64_t bits, uint
     return directed_slow(bits, dir);
 }
 
+// ---- rounding amounts b_r < 32 -------------------------------------------------------------
+// The target grid is the 32-bit floats whose last k = 32 - b_r mantissa bits are zero: spacing
+// 2^k ulp32.  With T the FP32 pattern of |x| truncated (exponent and 23 mantissa bits) and r the
+// 29 bits FP64 carries beyond it, the bits dropped by the coarser grid are R = (T mod 2^k) 2^29 + r
+// (29 + k of them), the rounding boundary is R = 2^(28+k), and the kept pattern is T >> k.  The
+// distance is reported in units of 2^k FP64 steps (2^-29 of the grid spacing), so thresholds
+// keep their meaning relative to the spacing.  k = 0 gives decide() and directed().
+static __host__ __device__ __forceinline__ Decision decide_k(uint64_t bits, uint32_t k)
+{
+    const uint32_t hi = (uint32_t)(bits >> 32), lo = (uint32_t)bits;
+    const uint32_t sign = hi >> 31, ahi = hi & 0x7FFFFFFFu;
+    const uint32_t maskk = (1u << k) - 1u;
+    const uint64_t half = 1ull << (28 + k);
+    Decision o;
+    if (__builtin_expect(ahi - (897u << 20) < ((2047u - 897u) << 20), 1)) {      // finite, |x| >= 2^-126
+        const uint32_t m23 = ((hi & 0xFFFFFu) << 3) | (lo >> 29);
+        const uint64_t R = ((uint64_t)(m23 & maskk) << 29) | (lo & kMask29);
+        o.D = (uint32_t)((R > half ? R - half : half - R) >> k);
+        const uint32_t e = ahi - (896u << 20);
+        uint32_t t, up;
+        if (__builtin_expect(e >= (255u << 20), 0)) { t = kF32Inf; up = 1; }     // |x| >= 2^128: overflows
+        else {
+            const uint32_t P = ((e << 3) | (lo >> 29)) >> k;
+            up = (R > half) || (R == half && (P & 1u));
+            t = (P + up) << k;                                                   // carries reach 0x7F800000 = Inf
+        }
+        o.ybits = (sign << 31) | t;
+        o.dir = up ^ sign;
+        return o;
+    }
+    const uint64_t mag = bits & 0x7FFFFFFFFFFFFFFFull;
+    if (mag > 0x7FF0000000000000ull) { o.ybits = kF32QNaN; o.D = kHalf; o.dir = 0; return o; }
+    if (mag == 0x7FF0000000000000ull) { o.ybits = (sign << 31) | kF32Inf; o.D = kHalf; o.dir = 0; return o; }
+    const uint32_t eb = (uint32_t)(mag >> 52);                       // below 2^-126: fixed spacing 2^(-149 + k)
+    const uint64_t sig = eb ? ((mag & 0x000FFFFFFFFFFFFFull) | (1ull << 52)) : mag;
+    const uint32_t sh = eb ? 897u - eb : 896u;
+    uint64_t q = 0;
+    uint32_t sticky;
+    if (sh > 63) { sticky = sig != 0; }
+    else { q = sig >> sh; sticky = (sig & ((1ull << sh) - 1)) != 0; }
+    const uint32_t t0 = (uint32_t)(q >> 29);
+    const uint64_t R = ((uint64_t)(t0 & maskk) << 29) | ((uint32_t)q & kMask29);
+    const uint32_t P = t0 >> k;
+    const uint32_t up = (R > half) || (R == half && (sticky || (P & 1u)));
+    o.D = (uint32_t)((R >= half ? R - half : half - R - sticky) >> k);
+    o.ybits = (sign << 31) | ((P + up) << k);
+    o.dir = up ^ sign;
+    return o;
+}
+
+// x rounded toward +inf (dir = 1) or -inf (dir = 0) on the same grid
+static __host__ __device__ __forceinline__ uint32_t directed_k(uint64_t bits, uint32_t dir, uint32_t k)
+{
+    const uint32_t hi = (uint32_t)(bits >> 32), lo = (uint32_t)bits;
+    const uint32_t sign = hi >> 31, ahi = hi & 0x7FFFFFFFu;
+    const uint32_t maskk = (1u << k) - 1u;
+    const uint32_t away = dir ^ sign;                                 // rounding grows the magnitude
+    if (__builtin_expect(ahi - (897u << 20) < ((2047u - 897u) << 20), 1)) {
+        const uint32_t e = ahi - (896u << 20);
+        uint32_t t;
+        if (__builtin_expect(e >= (255u << 20), 0)) t = away ? kF32Inf : (0x7F7FFFFFu >> k) << k;
+        else {
+            const uint32_t T = (e << 3) | (lo >> 29);
+            const uint32_t inexact = ((T & maskk) | (lo & kMask29)) != 0;
+            t = ((T >> k) + (inexact & away)) << k;
+        }
+        return (sign << 31) | t;
+    }
+    const uint64_t mag = bits & 0x7FFFFFFFFFFFFFFFull;
+    if (mag > 0x7FF0000000000000ull) return kF32QNaN;
+    if (mag == 0x7FF0000000000000ull) return (sign << 31) | kF32Inf;
+    const uint32_t eb = (uint32_t)(mag >> 52);
+    const uint64_t sig = eb ? ((mag & 0x000FFFFFFFFFFFFFull) | (1ull << 52)) : mag;
+    const uint32_t sh = eb ? 897u - eb : 896u;
+    uint64_t q = 0;
+    uint32_t inexact;
+    if (sh > 63) { inexact = sig != 0; }
+    else { q = sig >> sh; inexact = (sig & ((1ull << sh) - 1)) != 0; }
+    const uint32_t t0 = (uint32_t)(q >> 29);
+    inexact |= ((t0 & maskk) | ((uint32_t)q & kMask29)) != 0;
+    return (sign << 31) | (((t0 >> k) + (inexact & away)) << k);
+}
+
+// What every streaming kernel needs of one value: rnd(x), whether it is logged, and the side.
+struct Rounded {
+    uint32_t ybits;
+    bool logged, up;
+};
+
+// K0: rounding amount 32 (the hardware conversion does the common case); otherwise k = 32 - b_r.
+template <bool K0>
+__device__ __forceinline__ Rounded round_decide(double x, uint32_t thr, uint32_t k)
+{
+    const uint64_t bits = (uint64_t)__double_as_longlong(x);
+    Rounded o;
+    if (K0) {
+        const FastDecision f = decide_fast(x);
+        o.ybits = __float_as_uint(f.y);
+        o.logged = f.D < thr;
+        o.up = f.grow != f.neg;
+        if (__builtin_expect(f.slow, 0)) {
+            const Decision d = decide(bits);
+            o.ybits = d.ybits; o.logged = d.D < thr; o.up = d.dir != 0;
+        }
+    } else {
+        const Decision d = decide_k(bits, k);
+        o.ybits = d.ybits; o.logged = d.D < thr; o.up = d.dir != 0;
+    }
+    return o;
+}
+
 // Monotone integer image of a binary64 pattern (sign-magnitude -> two's complement).
 static __host__ __device__ __forceinline__ int64_t ord64(uint64_t bits)
 {

@@ -95,7 +95,7 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_sp
 
 size_t gemm_split_bytes(int64_t M, int64_t N, int64_t batch, int splits)
 {
-    if (splits <= 1) return 0;
+    if (splits < 1) return 0;
     const uint64_t slab = (uint64_t)M * N * batch * 8;
     return (size_t)((slab + 255) / 256 * 256 * (uint64_t)(splits + 1));   // slabs + the reduced tensor
 }
@@ -110,7 +110,7 @@ hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, con
     p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc;
     p.strideA = g.strideA; p.strideB = g.strideB; p.strideC = g.strideC; p.batch = g.batch;
     p.alpha = g.alpha; p.thr = g.thr; p.wpr = pl.wpr; p.variant = g.variant;
-    p.splits = plan.splits; p.kt_per_split = plan.kt_per_split;
+    p.splits = plan.splits; p.kt_per_split = plan.kt_per_split; p.raw = g.raw ? 1 : 0;
     p.tilesM = (uint32_t)((g.M + t.bm - 1) / t.bm);
     p.tilesN = (uint32_t)((g.N + t.bn - 1) / t.bn);
     const uint64_t per_split = (uint64_t)p.tilesM * p.tilesN * (uint64_t)g.batch;
@@ -140,7 +140,7 @@ hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, con
     case 2: e = launch_gemm_128x64(p, am, kcb, s); break;
     default: e = launch_gemm_64x64(p, am, kcb, s); break;
     }
-    if (e != hipSuccess || plan.splits <= 1) return e;
+    if (e != hipSuccess || (plan.splits <= 1 && !g.raw)) return e;
     const uint64_t slab = (uint64_t)g.M * g.N * g.batch;
     splitk_reduce_kernel<<<(uint32_t)((slab + 255) / 256), 256, 0, s>>>(partial, slab, plan.splits, g.variant, g.alpha,
                                                                       g.bias, (uint32_t)g.N, reduced, g.C64);

@@ -51,7 +51,7 @@ struct GemmParams {
     int64_t M, N, K, lda, ldb, ldc, strideA, strideB, strideC, batch;
     double alpha;
     uint32_t thr, wpr, tilesM, tilesN, tiles_per_split, total_blocks;
-    int variant, vecA, vecB, splits, kt_per_split;
+    int variant, vecA, vecB, splits, kt_per_split, raw;
 };
 
 namespace {
@@ -343,8 +343,8 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
     const int g = lane >> 4, c16 = lane & 15;
     const int64_t row0 = bm + wm * (16 * TM), col0 = bn + wn * 64;
 
-    if (p.splits > 1) {
-        // ---- split-K: raw accumulators to this slice's slab; alpha, bias, rounding come later
+    if (p.splits > 1 || p.raw) {
+        // ---- split-K (or a caller that rounds in a later pass): raw accumulators to this slice's slab; alpha, bias, rounding come later
         double *P = p.partial + ((int64_t)split * p.batch + (int64_t)b) * p.M * p.N;
 #pragma unroll
         for (int i = 0; i < TM; ++i)

@@ -35,7 +35,8 @@ struct LogOut {
 };
 
 // round + decide on a flat array: y, both bit-planes and seg_cnt (standalone trainer hook)
-hipError_t launch_round_planes(const double *x, uint64_t n, uint32_t thr, float *y, const Planes &pl,
+// (k = 32 - b_r low mantissa bits of every FP32 result are zero; 0 is plain FP32, see vt_device.h)
+hipError_t launch_round_planes(const double *x, uint64_t n, uint32_t thr, uint32_t k, float *y, const Planes &pl,
                                hipStream_t s);
 // seg_cnt from an already written `logged` plane (GEMM epilogue output)
 hipError_t launch_seg_count(const Planes &pl, hipStream_t s);
@@ -47,20 +48,20 @@ hipError_t launch_compact(const Planes &pl, const LogOut &log, hipStream_t s);
 // single-pass standalone trainer hook (chained scan); needs x 16-byte and y 8-byte aligned
 size_t onepass_bytes(uint64_t n);
 bool onepass_usable(const double *x, const float *y);
-hipError_t launch_round_log_onepass(const double *x, uint64_t n, uint32_t thr, float *y, void *ws,
+hipError_t launch_round_log_onepass(const double *x, uint64_t n, uint32_t thr, uint32_t k, float *y, void *ws,
                                     const LogOut &log, hipStream_t s);
 
 hipError_t launch_replay(const double *x, uint64_t n, const uint32_t *idx, const uint32_t *dir,
-                         uint64_t count, float *y, hipStream_t s);
+                         uint64_t count, uint32_t k, float *y, hipStream_t s);
 
 // the paper's packed ternary log (five entries per byte): trainer, auditor, and from bit-planes
 size_t dense_count_bytes();   // scratch for the logged-output count of the call below
-hipError_t launch_round_log_dense(const double *x, uint64_t n, uint32_t thr, float *y, uint8_t *tlog,
+hipError_t launch_round_log_dense(const double *x, uint64_t n, uint32_t thr, uint32_t k, float *y, uint8_t *tlog,
                                   uint64_t *n_logged, uint64_t *slots, hipStream_t s);
-hipError_t launch_replay_dense(const double *x, uint64_t n, const uint8_t *tlog, float *y, hipStream_t s);
+hipError_t launch_replay_dense(const double *x, uint64_t n, const uint8_t *tlog, uint32_t k, float *y, hipStream_t s);
 hipError_t launch_planes_to_dense(const Planes &pl, uint64_t rows, uint8_t *tlog, hipStream_t s);
 
-hipError_t launch_stats(const double *y1, const double *y2, uint64_t n, uint64_t *out, hipStream_t s);
+hipError_t launch_stats(const double *y1, const double *y2, uint64_t n, uint32_t k, uint64_t *out, hipStream_t s);
 
 // Geometry of a channels-last convolution whose image the GEMM kernel reads through an implicit
 // im2col view (all sizes already validated by the caller).
@@ -82,6 +83,7 @@ struct GemmArgs {
     double *C64;          // optional dense FP64 copy (pitch N)
     int variant;
     uint32_t thr;
+    bool raw = false;     // leave alpha, bias and the rounding to a later pass even without split-K
 };
 // Tile shape (index into the kernel's shape table) and split-K factor chosen for a problem.
 struct GemmPlan {
@@ -91,8 +93,9 @@ struct GemmPlan {
 };
 GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split);
 size_t gemm_split_bytes(int64_t M, int64_t N, int64_t batch, int splits);
-// splits == 1: C32 / C64 / planes written by the epilogue.  splits > 1: `partial` receives the
-// slabs, `reduced` (and g.C64 if set) the FP64 result alpha * sum + bias; nothing else is written.
+// splits == 1 and not g.raw: C32 / C64 / planes written by the epilogue.  Otherwise `partial`
+// receives the slabs, `reduced` (and g.C64 if set) the FP64 result alpha * sum + bias; nothing
+// else is written.
 hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, const Planes &pl, double *partial,
                                     double *reduced, hipStream_t s);
 

@@ -47,16 +47,12 @@ __global__ __launch_bounds__(256) void sum_slots_kernel(const uint64_t *__restri
 __global__ void zero_u64_kernel(uint64_t *p) { *p = 0; }
 
 // ternary code and FP32 bits of one value
-__device__ __forceinline__ uint32_t code_of(double x, uint32_t thr, uint32_t &ybits)
+template <bool K0>
+__device__ __forceinline__ uint32_t code_of(double x, uint32_t thr, uint32_t k, uint32_t &ybits)
 {
-    const FastDecision f = decide_fast(x);
-    ybits = __float_as_uint(f.y);
-    bool logged = f.D < thr, up = f.grow != f.neg;
-    if (__builtin_expect(f.slow, 0)) {
-        const Decision d = decide((uint64_t)__double_as_longlong(x));
-        ybits = d.ybits; logged = d.D < thr; up = d.dir != 0;
-    }
-    return logged ? (up ? 2u : 0u) : 1u;
+    const Rounded r = round_decide<K0>(x, thr, k);
+    ybits = r.ybits;
+    return r.logged ? (r.up ? 2u : 0u) : 1u;
 }
 
 template <bool FULL, bool VEC>
@@ -89,8 +85,8 @@ __device__ __forceinline__ void store_pair(float *__restrict__ y, uint64_t n, ui
 }
 
 // Trainer: y = rnd_32(x), tlog = packed codes.  One workgroup per 5120 elements.
-template <bool FULL, bool VEC>
-__device__ __forceinline__ void round_log_dense_chunk(const double *__restrict__ x, uint64_t n, uint32_t thr,
+template <bool FULL, bool VEC, bool K0>
+__device__ __forceinline__ void round_log_dense_chunk(const double *__restrict__ x, uint64_t n, uint32_t thr, uint32_t k,
                                                       float *__restrict__ y, uint8_t *__restrict__ tlog,
                                                       uint64_t base, uint32_t lane, uint8_t *__restrict__ mine,
                                                       uint64_t *__restrict__ slots)
@@ -101,7 +97,7 @@ __device__ __forceinline__ void round_log_dense_chunk(const double *__restrict__
 #pragma unroll
     for (int u = 0; u < kRows; ++u) {
         uint32_t ya, yb;
-        const uint32_t ca = code_of(v[u].x, thr, ya), cb = code_of(v[u].y, thr, yb);
+        const uint32_t ca = code_of<K0>(v[u].x, thr, k, ya), cb = code_of<K0>(v[u].y, thr, k, yb);
         store_pair<FULL, VEC>(y, n, base + (uint64_t)u * 128u + 2u * lane, ya, yb);
         logged += (ca != 1u) + (cb != 1u);
         *(uint16_t *)(mine + u * 128 + 2 * lane) = (uint16_t)(ca | (cb << 8));
@@ -139,24 +135,24 @@ __device__ __forceinline__ void round_log_dense_chunk(const double *__restrict__
     }
 }
 
-template <bool VEC>
+template <bool VEC, bool K0>
 __global__ __launch_bounds__(256) void round_log_dense_kernel(const double *__restrict__ x, uint64_t n, uint32_t thr,
-                                                              float *__restrict__ y, uint8_t *__restrict__ tlog,
-                                                              uint64_t *__restrict__ slots)
+                                                              uint32_t k, float *__restrict__ y,
+                                                              uint8_t *__restrict__ tlog, uint64_t *__restrict__ slots)
 {
     __shared__ __attribute__((aligned(16))) uint8_t codes[kWaves][kChunk];
     const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
     const uint64_t base = (uint64_t)blockIdx.x * kTile + (uint64_t)wv * kChunk;
     if (base >= n) return;
-    if (base + kChunk <= n) round_log_dense_chunk<true, VEC>(x, n, thr, y, tlog, base, lane, codes[wv], slots);
-    else round_log_dense_chunk<false, VEC>(x, n, thr, y, tlog, base, lane, codes[wv], slots);
+    if (base + kChunk <= n) round_log_dense_chunk<true, VEC, K0>(x, n, thr, k, y, tlog, base, lane, codes[wv], slots);
+    else round_log_dense_chunk<false, VEC, K0>(x, n, thr, k, y, tlog, base, lane, codes[wv], slots);
 }
 
 // Auditor: entry i of the packed log applied to x[i].
-template <bool FULL, bool VEC>
+template <bool FULL, bool VEC, bool K0>
 __device__ __forceinline__ void replay_dense_chunk(const double *__restrict__ x, uint64_t n,
                                                    const uint8_t *__restrict__ tlog, float *__restrict__ y,
-                                                   uint64_t base, uint32_t lane, uint8_t *__restrict__ mine)
+                                                   uint64_t base, uint32_t lane, uint8_t *__restrict__ mine, uint32_t k)
 {
     d2 v[kRows];
     load_rows<FULL, VEC>(x, n, base, lane, v);
@@ -191,26 +187,34 @@ __device__ __forceinline__ void replay_dense_chunk(const double *__restrict__ x,
         const uint64_t ba = (uint64_t)__double_as_longlong(v[u].x), bb = (uint64_t)__double_as_longlong(v[u].y);
         // unlogged: nearest (hardware conversion where it cannot differ from the definition);
         // logged: toward the recorded side
-        const FastDecision fa = decide_fast(v[u].x), fb = decide_fast(v[u].y);
-        uint32_t ya = __float_as_uint(fa.y), yb = __float_as_uint(fb.y);
-        if (__builtin_expect(fa.slow, 0)) ya = decide(ba).ybits;
-        if (__builtin_expect(fb.slow, 0)) yb = decide(bb).ybits;
-        if (ca != 1u) ya = directed(ba, ca >> 1);
-        if (cb != 1u) yb = directed(bb, cb >> 1);
+        uint32_t ya, yb;
+        if (K0) {
+            const FastDecision fa = decide_fast(v[u].x), fb = decide_fast(v[u].y);
+            ya = __float_as_uint(fa.y);
+            yb = __float_as_uint(fb.y);
+            if (__builtin_expect(fa.slow, 0)) ya = decide(ba).ybits;
+            if (__builtin_expect(fb.slow, 0)) yb = decide(bb).ybits;
+            if (ca != 1u) ya = directed(ba, ca >> 1);
+            if (cb != 1u) yb = directed(bb, cb >> 1);
+        } else {
+            ya = ca != 1u ? directed_k(ba, ca >> 1, k) : decide_k(ba, k).ybits;
+            yb = cb != 1u ? directed_k(bb, cb >> 1, k) : decide_k(bb, k).ybits;
+        }
         store_pair<FULL, VEC>(y, n, base + (uint64_t)u * 128u + 2u * lane, ya, yb);
     }
 }
 
-template <bool VEC>
+template <bool VEC, bool K0>
 __global__ __launch_bounds__(256) void replay_dense_kernel(const double *__restrict__ x, uint64_t n,
-                                                           const uint8_t *__restrict__ tlog, float *__restrict__ y)
+                                                           const uint8_t *__restrict__ tlog, float *__restrict__ y,
+                                                           uint32_t k)
 {
     __shared__ __attribute__((aligned(16))) uint8_t codes[kWaves][kChunk];
     const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
     const uint64_t base = (uint64_t)blockIdx.x * kTile + (uint64_t)wv * kChunk;
     if (base >= n) return;
-    if (base + kChunk <= n) replay_dense_chunk<true, VEC>(x, n, tlog, y, base, lane, codes[wv]);
-    else replay_dense_chunk<false, VEC>(x, n, tlog, y, base, lane, codes[wv]);
+    if (base + kChunk <= n) replay_dense_chunk<true, VEC, K0>(x, n, tlog, y, base, lane, codes[wv], k);
+    else replay_dense_chunk<false, VEC, K0>(x, n, tlog, y, base, lane, codes[wv], k);
 }
 
 // Decision bit-planes of a dense (rows x ncols) output -> packed ternary log; one thread per byte.
@@ -242,7 +246,7 @@ __global__ __launch_bounds__(256) void planes_to_dense_kernel(const uint64_t *__
 size_t dense_count_bytes() { return (size_t)kSlots * kSlotStride * 8; }
 
 // `slots`: dense_count_bytes() of scratch, needed when n_logged is wanted
-hipError_t launch_round_log_dense(const double *x, uint64_t n, uint32_t thr, float *y, uint8_t *tlog,
+hipError_t launch_round_log_dense(const double *x, uint64_t n, uint32_t thr, uint32_t k, float *y, uint8_t *tlog,
                                   uint64_t *n_logged, uint64_t *slots, hipStream_t s)
 {
     if (n == 0 || !n_logged || !slots) {
@@ -259,10 +263,12 @@ hipError_t launch_round_log_dense(const double *x, uint64_t n, uint32_t thr, flo
         if (e != hipSuccess) return e;
     }
     const uint64_t blocks = (n + kTile - 1) / kTile;
-    if (((uintptr_t)x % 16 == 0) && ((uintptr_t)y % 8 == 0))
-        round_log_dense_kernel<true><<<(uint32_t)blocks, 256, 0, s>>>(x, n, thr, y, tlog, slots);
-    else
-        round_log_dense_kernel<false><<<(uint32_t)blocks, 256, 0, s>>>(x, n, thr, y, tlog, slots);
+    const bool vec = ((uintptr_t)x % 16 == 0) && ((uintptr_t)y % 8 == 0);
+    const dim3 grid((uint32_t)blocks), block(256);
+    if (vec && k == 0) round_log_dense_kernel<true, true><<<grid, block, 0, s>>>(x, n, thr, k, y, tlog, slots);
+    else if (vec) round_log_dense_kernel<true, false><<<grid, block, 0, s>>>(x, n, thr, k, y, tlog, slots);
+    else if (k == 0) round_log_dense_kernel<false, true><<<grid, block, 0, s>>>(x, n, thr, k, y, tlog, slots);
+    else round_log_dense_kernel<false, false><<<grid, block, 0, s>>>(x, n, thr, k, y, tlog, slots);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && slots) {
         sum_slots_kernel<<<1, kSlots, 0, s>>>(slots, n_logged);
@@ -271,14 +277,16 @@ hipError_t launch_round_log_dense(const double *x, uint64_t n, uint32_t thr, flo
     return e;
 }
 
-hipError_t launch_replay_dense(const double *x, uint64_t n, const uint8_t *tlog, float *y, hipStream_t s)
+hipError_t launch_replay_dense(const double *x, uint64_t n, const uint8_t *tlog, uint32_t k, float *y, hipStream_t s)
 {
     if (n == 0) return hipSuccess;
     const uint64_t blocks = (n + kTile - 1) / kTile;
-    if (((uintptr_t)x % 16 == 0) && ((uintptr_t)y % 8 == 0))
-        replay_dense_kernel<true><<<(uint32_t)blocks, 256, 0, s>>>(x, n, tlog, y);
-    else
-        replay_dense_kernel<false><<<(uint32_t)blocks, 256, 0, s>>>(x, n, tlog, y);
+    const bool vec = ((uintptr_t)x % 16 == 0) && ((uintptr_t)y % 8 == 0);
+    const dim3 grid((uint32_t)blocks), block(256);
+    if (vec && k == 0) replay_dense_kernel<true, true><<<grid, block, 0, s>>>(x, n, tlog, y, k);
+    else if (vec) replay_dense_kernel<true, false><<<grid, block, 0, s>>>(x, n, tlog, y, k);
+    else if (k == 0) replay_dense_kernel<false, true><<<grid, block, 0, s>>>(x, n, tlog, y, k);
+    else replay_dense_kernel<false, false><<<grid, block, 0, s>>>(x, n, tlog, y, k);
     return hipGetLastError();
 }
 

@@ -17,7 +17,7 @@ namespace {
 constexpr int kUnroll = 8;
 
 __global__ __launch_bounds__(256) void round_planes_kernel(const uint64_t *__restrict__ x, uint64_t n,
-                                                           uint32_t thr, uint32_t *__restrict__ y,
+                                                           uint32_t thr, uint32_t k, uint32_t *__restrict__ y,
                                                            uint64_t *__restrict__ pl_logged,
                                                            uint64_t *__restrict__ pl_dir,
                                                            uint32_t *__restrict__ seg_cnt, uint32_t segs)
@@ -37,7 +37,7 @@ __global__ __launch_bounds__(256) void round_planes_kernel(const uint64_t *__res
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const uint64_t e = base + (uint64_t)(it + u) * 64u + lane;
-            const Decision d = decide(v[u]);
+            const Decision d = decide_k(v[u], k);             // k = 0: rounding amount 32
             if (e < n) __builtin_nontemporal_store(d.ybits, y + e);
             const uint64_t lg = ballot(e < n && d.D < thr);
             const uint64_t dr = ballot(d.dir != 0) & lg;
@@ -227,24 +227,32 @@ __device__ __forceinline__ void replay_load(const double *__restrict__ x, uint64
     }
 }
 
-template <bool FULL, bool VEC>
+template <bool FULL, bool VEC, bool K0>
 __device__ __forceinline__ void replay_store(const d2 (&v)[kReplayRows], const uint8_t *__restrict__ flags,
                                              uint32_t wv, float *__restrict__ y, uint64_t n, uint64_t wbase,
-                                             uint32_t lane)
+                                             uint32_t lane, uint32_t k)
 {
 #pragma unroll
     for (int u = 0; u < kReplayRows; ++u) {
         const uint32_t pos = wv * kReplayChunk + (uint32_t)u * 128u + 2u * lane;
         const uint64_t e = wbase + (uint64_t)u * 128u + 2u * lane;
         const uint32_t f = *(const uint16_t *)(flags + pos);          // flags of both outputs
-        const FastDecision a = decide_fast(v[u].x), b = decide_fast(v[u].y);
-        uint32_t ya = __float_as_uint(a.y), yb = __float_as_uint(b.y);
-        if (__builtin_expect(ballot(a.slow || b.slow || f != 0) != 0, 0)) {
+        uint32_t ya, yb;
+        if (K0) {
+            const FastDecision a = decide_fast(v[u].x), b = decide_fast(v[u].y);
+            ya = __float_as_uint(a.y);
+            yb = __float_as_uint(b.y);
+            if (__builtin_expect(ballot(a.slow || b.slow || f != 0) != 0, 0)) {
+                const uint64_t xa = (uint64_t)__double_as_longlong(v[u].x), xb = (uint64_t)__double_as_longlong(v[u].y);
+                if (f & 1u) ya = directed(xa, (f >> 1) & 1u);
+                else if (a.slow) ya = decide(xa).ybits;
+                if (f & 0x100u) yb = directed(xb, (f >> 9) & 1u);
+                else if (b.slow) yb = decide(xb).ybits;
+            }
+        } else {                                                     // rounding amount below 32
             const uint64_t xa = (uint64_t)__double_as_longlong(v[u].x), xb = (uint64_t)__double_as_longlong(v[u].y);
-            if (f & 1u) ya = directed(xa, (f >> 1) & 1u);
-            else if (a.slow) ya = decide(xa).ybits;
-            if (f & 0x100u) yb = directed(xb, (f >> 9) & 1u);
-            else if (b.slow) yb = decide(xb).ybits;
+            ya = (f & 1u) ? directed_k(xa, (f >> 1) & 1u, k) : decide_k(xa, k).ybits;
+            yb = (f & 0x100u) ? directed_k(xb, (f >> 9) & 1u, k) : decide_k(xb, k).ybits;
         }
         if (VEC && (FULL || e + 1 < n)) {
             f2 o;
@@ -258,11 +266,11 @@ __device__ __forceinline__ void replay_store(const d2 (&v)[kReplayRows], const u
     }
 }
 
-template <bool VEC>
+template <bool VEC, bool K0>
 __global__ __launch_bounds__(256) void replay_kernel(const double *__restrict__ x, uint64_t n,
                                                      const uint32_t *__restrict__ idx,
                                                      const uint32_t *__restrict__ dir, uint64_t count,
-                                                     float *__restrict__ y)
+                                                     float *__restrict__ y, uint32_t k)
 {
     __shared__ __attribute__((aligned(16))) uint8_t flags[kReplayTile];   // bit 0: logged, bit 1: direction
     __shared__ uint64_t s_lo;
@@ -300,8 +308,8 @@ __global__ __launch_bounds__(256) void replay_kernel(const double *__restrict__ 
         if (ballot(i < stop) == 0) break;                    // sorted list: nothing further belongs here
     }
     __syncthreads();
-    if (full) replay_store<true, VEC>(v, flags, wv, y, n, wbase, lane);
-    else replay_store<false, VEC>(v, flags, wv, y, n, wbase, lane);
+    if (full) replay_store<true, VEC, K0>(v, flags, wv, y, n, wbase, lane, k);
+    else replay_store<false, VEC, K0>(v, flags, wv, y, n, wbase, lane, k);
 }
 
 // --------------------------------------------------------------------------------------------
@@ -325,8 +333,9 @@ struct StatsAcc {
     uint64_t dmax;
 };
 
+template <bool K0>
 __device__ __forceinline__ void stats_one(uint64_t a, uint64_t b, double xa, double xb, bool valid, uint32_t copy,
-                                          uint32_t (*hist)[66], StatsAcc &acc)
+                                          uint32_t (*hist)[66], StatsAcc &acc, uint32_t k)
 {
     if (!valid) return;
     if (a == b) { ++acc.equal; return; }
@@ -341,7 +350,7 @@ __device__ __forceinline__ void stats_one(uint64_t a, uint64_t b, double xa, dou
     // differ from the integer definition there); distances only for the rare pairs that flip
     const uint32_t ha = (uint32_t)(a >> 32) & 0x7FFFFFFFu, hb = (uint32_t)(b >> 32) & 0x7FFFFFFFu;
     const bool ordinary = (ha - (897u << 20)) < ((1151u - 897u) << 20) && (hb - (897u << 20)) < ((1151u - 897u) << 20);
-    if (ordinary) {
+    if (K0 && ordinary) {
         if (__float_as_uint((float)xa) == __float_as_uint((float)xb)) return;
         const uint32_t Da = __usad((uint32_t)a & kMask29, kHalf, 0u), Db = __usad((uint32_t)b & kMask29, kHalf, 0u);
         ++acc.flips;
@@ -349,7 +358,7 @@ __device__ __forceinline__ void stats_one(uint64_t a, uint64_t b, double xa, dou
         acc.thrmax = need > acc.thrmax ? need : acc.thrmax;
         return;
     }
-    const Decision da = decide(a), db = decide(b);
+    const Decision da = decide_k(a, k), db = decide_k(b, k);
     if (da.ybits != db.ybits) {
         ++acc.flips;
         const uint32_t need = 1u + (da.D > db.D ? da.D : db.D);
@@ -357,9 +366,9 @@ __device__ __forceinline__ void stats_one(uint64_t a, uint64_t b, double xa, dou
     }
 }
 
-template <bool VEC>
+template <bool VEC, bool K0>
 __global__ __launch_bounds__(256) void stats_kernel(const double *__restrict__ y1, const double *__restrict__ y2,
-                                                    uint64_t n, uint64_t *__restrict__ out)
+                                                    uint64_t n, uint64_t *__restrict__ out, uint32_t k)
 {
     __shared__ uint32_t hist[16][66];
     __shared__ unsigned long long s_flip, s_thr, s_max, s_eq;
@@ -385,10 +394,10 @@ __global__ __launch_bounds__(256) void stats_kernel(const double *__restrict__ y
 #pragma unroll
         for (int u = 0; u < kStatsU; ++u) {
             const uint64_t e = base + (uint64_t)u * 512u + 2u * tid;
-            stats_one((uint64_t)__double_as_longlong(a[u].x), (uint64_t)__double_as_longlong(b[u].x), a[u].x, b[u].x,
-                      full || e < n, copy, hist, acc);
-            stats_one((uint64_t)__double_as_longlong(a[u].y), (uint64_t)__double_as_longlong(b[u].y), a[u].y, b[u].y,
-                      full || e + 1 < n, copy, hist, acc);
+            stats_one<K0>((uint64_t)__double_as_longlong(a[u].x), (uint64_t)__double_as_longlong(b[u].x), a[u].x, b[u].x,
+                          full || e < n, copy, hist, acc, k);
+            stats_one<K0>((uint64_t)__double_as_longlong(a[u].y), (uint64_t)__double_as_longlong(b[u].y), a[u].y, b[u].y,
+                          full || e + 1 < n, copy, hist, acc, k);
         }
     }
     atomicAdd(&s_flip, (unsigned long long)acc.flips);
@@ -441,10 +450,11 @@ Planes planes_carve(void *ws, uint64_t rows, uint64_t ncols)
     return p;
 }
 
-hipError_t launch_round_planes(const double *x, uint64_t n, uint32_t thr, float *y, const Planes &pl, hipStream_t s)
+hipError_t launch_round_planes(const double *x, uint64_t n, uint32_t thr, uint32_t k, float *y, const Planes &pl,
+                               hipStream_t s)
 {
     if (pl.segs == 0) return hipSuccess;
-    round_planes_kernel<<<(pl.segs + 3) / 4, 256, 0, s>>>((const uint64_t *)x, n, thr, (uint32_t *)y, pl.logged,
+    round_planes_kernel<<<(pl.segs + 3) / 4, 256, 0, s>>>((const uint64_t *)x, n, thr, k, (uint32_t *)y, pl.logged,
                                                          pl.dir, pl.seg_cnt, pl.segs);
     return hipGetLastError();
 }
@@ -471,28 +481,32 @@ hipError_t launch_compact(const Planes &pl, const LogOut &log, hipStream_t s)
 }
 
 hipError_t launch_replay(const double *x, uint64_t n, const uint32_t *idx, const uint32_t *dir, uint64_t count,
-                         float *y, hipStream_t s)
+                         uint32_t k, float *y, hipStream_t s)
 {
     if (n == 0) return hipSuccess;
     const uint64_t blocks = (n + kReplayTile - 1) / kReplayTile;
-    if (((uintptr_t)x % 16 == 0) && ((uintptr_t)y % 8 == 0))
-        replay_kernel<true><<<(uint32_t)blocks, 256, 0, s>>>(x, n, idx, dir, count, y);
-    else
-        replay_kernel<false><<<(uint32_t)blocks, 256, 0, s>>>(x, n, idx, dir, count, y);
+    const bool vec = ((uintptr_t)x % 16 == 0) && ((uintptr_t)y % 8 == 0);
+    const dim3 grid((uint32_t)blocks), block(256);
+    if (vec && k == 0) replay_kernel<true, true><<<grid, block, 0, s>>>(x, n, idx, dir, count, y, k);
+    else if (vec) replay_kernel<true, false><<<grid, block, 0, s>>>(x, n, idx, dir, count, y, k);
+    else if (k == 0) replay_kernel<false, true><<<grid, block, 0, s>>>(x, n, idx, dir, count, y, k);
+    else replay_kernel<false, false><<<grid, block, 0, s>>>(x, n, idx, dir, count, y, k);
     return hipGetLastError();
 }
 
-hipError_t launch_stats(const double *y1, const double *y2, uint64_t n, uint64_t *out, hipStream_t s)
+hipError_t launch_stats(const double *y1, const double *y2, uint64_t n, uint32_t k, uint64_t *out, hipStream_t s)
 {
     fill_u64_kernel<<<1, 128, 0, s>>>(out, 68, 0);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || n == 0) return e;
     uint64_t blocks = (n + kStatsTile - 1) / kStatsTile;
     if (blocks > 2048) blocks = 2048;                       // 8 workgroups per CU
-    if (((uintptr_t)y1 % 16 == 0) && ((uintptr_t)y2 % 16 == 0))
-        stats_kernel<true><<<(uint32_t)blocks, 256, 0, s>>>(y1, y2, n, out);
-    else
-        stats_kernel<false><<<(uint32_t)blocks, 256, 0, s>>>(y1, y2, n, out);
+    const bool vec = ((uintptr_t)y1 % 16 == 0) && ((uintptr_t)y2 % 16 == 0);
+    const dim3 grid((uint32_t)blocks), block(256);
+    if (vec && k == 0) stats_kernel<true, true><<<grid, block, 0, s>>>(y1, y2, n, out, k);
+    else if (vec) stats_kernel<true, false><<<grid, block, 0, s>>>(y1, y2, n, out, k);
+    else if (k == 0) stats_kernel<false, true><<<grid, block, 0, s>>>(y1, y2, n, out, k);
+    else stats_kernel<false, false><<<grid, block, 0, s>>>(y1, y2, n, out, k);
     return hipGetLastError();
 }
 

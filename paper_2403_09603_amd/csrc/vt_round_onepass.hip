@@ -148,8 +148,8 @@ __device__ __forceinline__ void scanner(uint64_t *__restrict__ st, uint32_t tile
 // One wave's share of a tile: 1024 contiguous values as 8 rows of 128 (two per lane).  FULL:
 // the whole tile lies inside the array, so no access is guarded.  Returns the wave's count;
 // entries go to `ent` in element order.
-template <bool FULL>
-__device__ __forceinline__ uint32_t round_rows(const double *__restrict__ x, uint64_t n, uint32_t thr,
+template <bool FULL, bool K0>
+__device__ __forceinline__ uint32_t round_rows(const double *__restrict__ x, uint64_t n, uint32_t thr, uint32_t k,
                                                float *__restrict__ y, uint64_t wbase, uint32_t lane,
                                                uint16_t *__restrict__ ent)
 {
@@ -167,19 +167,29 @@ __device__ __forceinline__ uint32_t round_rows(const double *__restrict__ x, uin
 #pragma unroll
     for (int u = 0; u < kRows; ++u) {
         const uint64_t e = wbase + (uint64_t)u * 128u + 2u * lane;
-        const FastDecision a = decide_fast(v[u].x), b = decide_fast(v[u].y);
-        uint32_t ya = __float_as_uint(a.y), yb = __float_as_uint(b.y);
-        bool la = a.D < thr, lb = b.D < thr;
-        bool da = a.grow != a.neg, db = b.grow != b.neg;
-        if (__builtin_expect(ballot(a.slow || b.slow) != 0, 0)) {      // rare values: redo those lanes
-            if (a.slow) {
-                const Decision d = decide((uint64_t)__double_as_longlong(v[u].x));
-                ya = d.ybits; la = d.D < thr; da = d.dir != 0;
+        uint32_t ya, yb;
+        bool la, lb, da, db;
+        if (K0) {
+            const FastDecision a = decide_fast(v[u].x), b = decide_fast(v[u].y);
+            ya = __float_as_uint(a.y); yb = __float_as_uint(b.y);
+            la = a.D < thr; lb = b.D < thr;
+            da = a.grow != a.neg; db = b.grow != b.neg;
+            if (__builtin_expect(ballot(a.slow || b.slow) != 0, 0)) {      // rare values: redo those lanes
+                if (a.slow) {
+                    const Decision d = decide((uint64_t)__double_as_longlong(v[u].x));
+                    ya = d.ybits; la = d.D < thr; da = d.dir != 0;
+                }
+                if (b.slow) {
+                    const Decision d = decide((uint64_t)__double_as_longlong(v[u].y));
+                    yb = d.ybits; lb = d.D < thr; db = d.dir != 0;
+                }
             }
-            if (b.slow) {
-                const Decision d = decide((uint64_t)__double_as_longlong(v[u].y));
-                yb = d.ybits; lb = d.D < thr; db = d.dir != 0;
-            }
+        } else {                                                           // rounding amount below 32
+            const Decision a = decide_k((uint64_t)__double_as_longlong(v[u].x), k);
+            const Decision b = decide_k((uint64_t)__double_as_longlong(v[u].y), k);
+            ya = a.ybits; yb = b.ybits;
+            la = a.D < thr; lb = b.D < thr;
+            da = a.dir != 0; db = b.dir != 0;
         }
         if (FULL || e + 1 < n) {
             f2 o;
@@ -202,8 +212,9 @@ __device__ __forceinline__ uint32_t round_rows(const double *__restrict__ x, uin
     return wcount;
 }
 
+template <bool K0>
 __global__ __launch_bounds__(kThreads) void round_log_onepass_kernel(const double *__restrict__ x, uint64_t n,
-                                                                uint32_t thr, float *__restrict__ y,
+                                                                uint32_t thr, uint32_t k, float *__restrict__ y,
                                                                 uint64_t *__restrict__ st, uint32_t tiles,
                                                                 uint32_t *__restrict__ err,
                                                                 uint32_t *__restrict__ idx, uint32_t *__restrict__ dir,
@@ -219,8 +230,8 @@ __global__ __launch_bounds__(kThreads) void round_log_onepass_kernel(const doubl
     const uint32_t tile = blockIdx.x - 1;
     const uint64_t wbase = (uint64_t)tile * kTile + (uint64_t)wv * kWaveChunk;
     const uint32_t wcount = ((uint64_t)(tile + 1) * kTile <= n)
-                                ? round_rows<true>(x, n, thr, y, wbase, lane, ent[wv])
-                                : round_rows<false>(x, n, thr, y, wbase, lane, ent[wv]);
+                                ? round_rows<true, K0>(x, n, thr, k, y, wbase, lane, ent[wv])
+                                : round_rows<false, K0>(x, n, thr, k, y, wbase, lane, ent[wv]);
     if (lane == 0) s_wc[wv] = wcount;
     __syncthreads();
     // Only wave 0 goes on: it alone waits for the tile's place in the log, so the other seven
@@ -289,7 +300,7 @@ bool onepass_usable(const double *x, const float *y)
     return ((uintptr_t)x % 16 == 0) && ((uintptr_t)y % 8 == 0);
 }
 
-hipError_t launch_round_log_onepass(const double *x, uint64_t n, uint32_t thr, float *y, void *ws,
+hipError_t launch_round_log_onepass(const double *x, uint64_t n, uint32_t thr, uint32_t k, float *y, void *ws,
                                     const LogOut &log, hipStream_t s)
 {
     const uint32_t tiles = (uint32_t)((n + kTile - 1) / kTile);
@@ -304,8 +315,12 @@ hipError_t launch_round_log_onepass(const double *x, uint64_t n, uint32_t thr, f
     onepass_init_kernel<<<blocks, 256, 0, s>>>(st, tiles, err, log.dir, dir_words, log.count);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || tiles == 0) return e;
-    round_log_onepass_kernel<<<tiles + 1, kThreads, 0, s>>>(x, n, thr, y, st, tiles, err, log.idx, log.dir, log.cap,
-                                                            log.count);
+    if (k == 0)
+        round_log_onepass_kernel<true><<<tiles + 1, kThreads, 0, s>>>(x, n, thr, k, y, st, tiles, err, log.idx, log.dir,
+                                                                      log.cap, log.count);
+    else
+        round_log_onepass_kernel<false><<<tiles + 1, kThreads, 0, s>>>(x, n, thr, k, y, st, tiles, err, log.idx, log.dir,
+                                                                       log.cap, log.count);
     return hipGetLastError();
 }
 

@@ -16,7 +16,7 @@ def u32(t):
     return t.cpu().numpy().view(np.uint32)
 
 
-def gpu_round_log(x, tau, cap=None, misalign=False):
+def gpu_round_log(x, tau, cap=None, misalign=False, b_r=32):
     """misalign=True places x on an 8-byte (not 16-byte) boundary, which makes the library take
     its bit-plane + compaction path instead of the single-pass kernel."""
     x = np.ascontiguousarray(x, np.float64).ravel()
@@ -32,6 +32,7 @@ def gpu_round_log(x, tau, cap=None, misalign=False):
         xd = dev(x) if n else torch.empty(0, dtype=torch.float64, device=DEV)
     y = torch.empty(n, dtype=torch.float32, device=DEV)
     log = vt.alloc_log(cap)
+    log.b_r = b_r
     ws = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_ROUND_LOG, 1, n))
     vt.vt_round_log(xd, tau, y, log, ws)
     torch.cuda.synchronize()
@@ -40,7 +41,7 @@ def gpu_round_log(x, tau, cap=None, misalign=False):
     return (y.cpu().numpy(), u32(log.idx)[:k].copy(), u32(log.dir)[:(k + 31) // 32].copy(), count)
 
 
-def gpu_round_replay(x, idx, dirw, count=None, misalign=False):
+def gpu_round_replay(x, idx, dirw, count=None, misalign=False, b_r=32):
     x = np.ascontiguousarray(x, np.float64).ravel()
     count = len(idx) if count is None else count
     if misalign:
@@ -52,22 +53,22 @@ def gpu_round_replay(x, idx, dirw, count=None, misalign=False):
     y = torch.empty(x.size, dtype=torch.float32, device=DEV)
     idx_d = dev(np.ascontiguousarray(idx, np.uint32).view(np.int32)) if len(idx) else torch.zeros(1, dtype=torch.int32, device=DEV)
     dir_d = dev(np.ascontiguousarray(dirw, np.uint32).view(np.int32)) if len(dirw) else torch.zeros(1, dtype=torch.int32, device=DEV)
-    vt.vt_round_replay(xd, idx_d, dir_d, count, y)
+    vt.vt_round_replay(xd, idx_d, dir_d, count, y, b_r=b_r)
     torch.cuda.synchronize()
     return y.cpu().numpy()
 
 
-def gpu_stats(y1, y2):
+def gpu_stats(y1, y2, b_r=32):
     out = torch.full((68,), -1, dtype=torch.int64, device=DEV)
     vt.vt_threshold_stats(dev(np.ascontiguousarray(y1, np.float64).ravel()),
-                          dev(np.ascontiguousarray(y2, np.float64).ravel()), out)
+                          dev(np.ascontiguousarray(y2, np.float64).ravel()), out, b_r=b_r)
     torch.cuda.synchronize()
     o = out.cpu().numpy().view(np.uint64)
     return {"n_flip": int(o[0]), "thr_flip": int(o[1]), "max_ulp64_diff": int(o[2]), "hist": o[3:].copy()}
 
 
 def gpu_gemm(A, B, *, transA=False, transB=False, alpha=1.0, bias=None, tau=0.0, variant=0, cap=None,
-             want_c64=True, ldc=None):
+             want_c64=True, ldc=None, b_r=32):
     """A, B: numpy arrays as stored, 2-D (or 3-D with a leading batch dimension)."""
     A = np.ascontiguousarray(A, np.float64)
     B = np.ascontiguousarray(B, np.float64)
@@ -85,7 +86,9 @@ def gpu_gemm(A, B, *, transA=False, transB=False, alpha=1.0, bias=None, tau=0.0,
     C32 = torch.full((batch, M, ldc), float("nan"), dtype=torch.float32, device=DEV)
     C64 = torch.empty((batch, M, N), dtype=torch.float64, device=DEV) if want_c64 else None
     log = vt.alloc_log(cap)
-    ws = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG, M, N, K, batch))
+    log.b_r = b_r
+    op = vt.VT_OP_GEMM_ROUND_LOG if b_r == 32 else vt.VT_OP_GEMM_ROUND_LOG_BR
+    ws = vt.alloc_workspace(vt.vt_workspace_bytes(op, M, N, K, batch))
     bias_d = dev(np.ascontiguousarray(bias, np.float64)) if bias is not None else None
     vt.vt_gemm_f64_round_log(transA, transB, M, N, K, alpha, Ad, a2[1], strideA, Bd, b2[1], strideB, bias_d, batch,
                              C32, ldc, M * ldc, C64, variant, tau, log, ws)
@@ -97,7 +100,7 @@ def gpu_gemm(A, B, *, transA=False, transB=False, alpha=1.0, bias=None, tau=0.0,
             "idx": u32(log.idx)[:k].copy(), "dir": u32(log.dir)[:(k + 31) // 32].copy(), "count": count}
 
 
-def gpu_conv(mode, X, B, KH, KW, *, stride=1, pad=0, dil=1, bias=None, tau=0.0, variant=0, misalign=False):
+def gpu_conv(mode, X, B, KH, KW, *, stride=1, pad=0, dil=1, bias=None, tau=0.0, variant=0, misalign=False, b_r=32):
     """mode 0: forward, B = weights (KH,KW,C,Cout); mode 1: weight gradient, B = dY (N,Ho,Wo,Cout).
     X is (N,H,W,C).  misalign=True puts X on an 8-byte (not 16-byte) boundary."""
     pair = lambda v: (int(v), int(v)) if np.isscalar(v) else (int(v[0]), int(v[1]))
@@ -119,7 +122,9 @@ def gpu_conv(mode, X, B, KH, KW, *, stride=1, pad=0, dil=1, bias=None, tau=0.0, 
     C32 = torch.full((max(M * Nn, 1),), float("nan"), dtype=torch.float32, device=DEV)
     C64 = torch.empty(max(M * Nn, 1), dtype=torch.float64, device=DEV)
     log = vt.alloc_log(M * Nn)
-    ws = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG, M, Nn, K, 1))
+    log.b_r = b_r
+    ws = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG if b_r == 32 else vt.VT_OP_GEMM_ROUND_LOG_BR,
+                                                  M, Nn, K, 1))
     bias_d = dev(np.ascontiguousarray(bias, np.float64)) if bias is not None else None
     vt.vt_conv2d_f64_round_log(mode, d, Cout, Xd, Bd, bias_d, C32, C64, variant, tau, log, ws)
     torch.cuda.synchronize()
@@ -129,7 +134,7 @@ def gpu_conv(mode, X, B, KH, KW, *, stride=1, pad=0, dil=1, bias=None, tau=0.0, 
             "shape": (M, Nn, K)}
 
 
-def gpu_round_log_dense(x, tau, misalign=False):
+def gpu_round_log_dense(x, tau, misalign=False, b_r=32):
     """Standalone trainer hook writing the packed ternary log: (y, tlog bytes, n_logged)."""
     x = np.ascontiguousarray(x, np.float64).ravel()
     n = x.size
@@ -142,6 +147,7 @@ def gpu_round_log_dense(x, tau, misalign=False):
         xd = dev(x) if n else torch.empty(0, dtype=torch.float64, device=DEV)
     y = torch.empty(n, dtype=torch.float32, device=DEV)
     log = vt.alloc_dense_log(n)
+    log.b_r = b_r
     log.dense.fill_(0xEE)
     log.count.fill_(-1)
     ws = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_ROUND_LOG, 1, n))
@@ -152,7 +158,7 @@ def gpu_round_log_dense(x, tau, misalign=False):
     return y.cpu().numpy(), full[:(n + 4) // 5].copy(), int(log.count.item())
 
 
-def gpu_round_replay_dense(x, tlog, misalign=False):
+def gpu_round_replay_dense(x, tlog, misalign=False, b_r=32):
     x = np.ascontiguousarray(x, np.float64).ravel()
     if misalign:
         buf = torch.empty(x.size + 1, dtype=torch.float64, device=DEV)
@@ -163,12 +169,12 @@ def gpu_round_replay_dense(x, tlog, misalign=False):
     t = np.ascontiguousarray(tlog, np.uint8)
     td = dev(t) if t.size else torch.zeros(4, dtype=torch.uint8, device=DEV)
     y = torch.empty(x.size, dtype=torch.float32, device=DEV)
-    vt.vt_round_replay_dense(xd, td, y)
+    vt.vt_round_replay_dense(xd, td, y, b_r=b_r)
     torch.cuda.synchronize()
     return y.cpu().numpy()
 
 
-def gpu_gemm_dense(A, B, *, transA=False, transB=False, alpha=1.0, bias=None, tau=0.0, variant=0, ldc=None):
+def gpu_gemm_dense(A, B, *, transA=False, transB=False, alpha=1.0, bias=None, tau=0.0, variant=0, ldc=None, b_r=32):
     """GEMM entry point with the packed ternary log as output format."""
     A = np.ascontiguousarray(A, np.float64)
     B = np.ascontiguousarray(B, np.float64)
@@ -184,8 +190,10 @@ def gpu_gemm_dense(A, B, *, transA=False, transB=False, alpha=1.0, bias=None, ta
     C32 = torch.full((batch, M, ldc), float("nan"), dtype=torch.float32, device=DEV)
     C64 = torch.empty((batch, M, N), dtype=torch.float64, device=DEV)
     log = vt.alloc_dense_log(total)
+    log.b_r = b_r
     log.dense.fill_(0xEE)
-    ws = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG, M, N, K, batch))
+    ws = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG if b_r == 32 else vt.VT_OP_GEMM_ROUND_LOG_BR,
+                                                  M, N, K, batch))
     bias_d = dev(np.ascontiguousarray(bias, np.float64)) if bias is not None else None
     vt.vt_gemm_f64_round_log(transA, transB, M, N, K, alpha, dev(A), a2[1], strideA, dev(B), b2[1], strideB, bias_d, batch,
                              C32, ldc, M * ldc, C64, variant, tau, log, ws)

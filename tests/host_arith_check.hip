@@ -13,6 +13,18 @@ extern "C" void h_directed(const uint64_t *bits, uint64_t n, uint32_t dir, uint3
     for (uint64_t i = 0; i < n; ++i) y[i] = vt::directed(bits[i], dir);
 }
 
+extern "C" void h_decide_k(const uint64_t *bits, uint64_t n, uint32_t k, uint32_t *y, uint32_t *D, uint32_t *dir)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        vt::Decision d = vt::decide_k(bits[i], k);
+        y[i] = d.ybits; D[i] = d.D; dir[i] = d.dir;
+    }
+}
+extern "C" void h_directed_k(const uint64_t *bits, uint64_t n, uint32_t dir, uint32_t k, uint32_t *y)
+{
+    for (uint64_t i = 0; i < n; ++i) y[i] = vt::directed_k(bits[i], dir, k);
+}
+
 // im2col index arithmetic of the convolution loader: offsets[m * taps + kc] = image element or -1
 extern "C" void h_im2col_offsets(const int64_t *g /* N H W C KH KW sh sw ph pw dh dw Ho Wo */, uint32_t row0, uint32_t rows_to_do,
                                  uint32_t tap0, uint32_t taps_to_do, int64_t *offsets)

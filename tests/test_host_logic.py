@@ -57,7 +57,7 @@ def test_argument_validation_happens_on_the_host(hiplib):
     """None of these calls may reach a kernel launch: they run here without a GPU."""
     import paper_2403_09603_amd.binding as b
     cnt = (C.c_uint64 * 1)()
-    log = b._VtLog(None, None, 0, C.addressof(cnt), None)
+    log = b._VtLog(None, None, 0, C.addressof(cnt), None, 0)
     fake = C.c_void_p(0x1000)
     INVALID, WORKSPACE = 1, 2
     assert hiplib.vt_round_log(fake, 16, 0.75, fake, C.byref(log), fake, 1 << 20, None) == INVALID   # tau
@@ -66,12 +66,18 @@ def test_argument_validation_happens_on_the_host(hiplib):
     assert hiplib.vt_round_log(fake, 16, 0.1, fake, None, fake, 1 << 20, None) == INVALID
     assert hiplib.vt_round_log(fake, 16, 0.1, fake, C.byref(log), None, 0, None) == WORKSPACE
     assert hiplib.vt_round_log(fake, 1 << 20, 0.1, fake, C.byref(log), fake, 1024, None) == WORKSPACE
-    badlog = b._VtLog(None, None, 8, C.addressof(cnt), None)
+    badlog = b._VtLog(None, None, 8, C.addressof(cnt), None, 0)
     assert hiplib.vt_round_log(fake, 16, 0.1, fake, C.byref(badlog), fake, 1 << 20, None) == INVALID
-    both = b._VtLog(0x1000, 0x1000, 8, C.addressof(cnt), 0x2000)                 # two formats in one call
+    both = b._VtLog(0x1000, 0x1000, 8, C.addressof(cnt), 0x2000, 0)                 # two formats in one call
     assert hiplib.vt_round_log(fake, 16, 0.1, fake, C.byref(both), fake, 1 << 20, None) == INVALID
-    odd = b._VtLog(None, None, 0, C.addressof(cnt), 0x2001)                      # misaligned packed log
+    odd = b._VtLog(None, None, 0, C.addressof(cnt), 0x2001, 0)                      # misaligned packed log
     assert hiplib.vt_round_log(fake, 16, 0.1, fake, C.byref(odd), fake, 1 << 20, None) == INVALID
+    for bad_br in (9, 33, -1):
+        bl = b._VtLog(None, None, 0, C.addressof(cnt), None, bad_br)
+        assert hiplib.vt_round_log(fake, 16, 0.1, fake, C.byref(bl), fake, 1 << 20, None) == INVALID
+        assert hiplib.vt_round_replay_br(fake, 16, None, None, 0, bad_br, fake, None) == INVALID
+        assert hiplib.vt_round_replay_dense_br(fake, 16, fake, bad_br, fake, None) == INVALID
+        assert hiplib.vt_threshold_stats_br(fake, fake, 16, bad_br, fake, None) == INVALID
     assert hiplib.vt_round_replay_dense(fake, 16, None, fake, None) == INVALID
     assert hiplib.vt_round_replay_dense(fake, 16, C.c_void_p(0x2002), fake, None) == INVALID
     assert hiplib.vt_round_replay(fake, 1 << 32, None, None, 0, fake, None, 0, None) == INVALID
@@ -87,14 +93,48 @@ def test_argument_validation_happens_on_the_host(hiplib):
     assert call(ldc=127) == INVALID and call(variant=2) == INVALID and call(tau=-0.1) == INVALID
     assert call(tA=2) == INVALID and call(M=1 << 20, N=1 << 12, lda=64, ldc=1 << 12) == INVALID
     assert call(ws=None, wsb=0) == WORKSPACE and call(wsb=16) == WORKSPACE
+    log26 = b._VtLog(None, None, 0, C.addressof(cnt), None, 26)                  # b_r < 32 needs a dense C
+    assert g(0, 0, 128, 128, 64, 1.0, fake, 64, 0, fake, 128, 0, None, 1, fake, 160, 0, None, 0, 0.1, C.byref(log26),
+             fake, 1 << 24, None) == 4
+    assert hiplib.vt_workspace_bytes(4, 128, 128, 64, 1) > hiplib.vt_workspace_bytes(2, 128, 128, 64, 1)
     assert hiplib.vt_threshold_stats(fake, fake, 16, None, None) == INVALID
     assert hiplib.vt_strerror(INVALID).decode() == "invalid argument"
+
+
+@pytest.mark.parametrize("b", [32, 31, 29, 26, 16, 10])
+def test_kernel_arithmetic_for_other_rounding_amounts_on_host(harith, b):
+    """decide_k / directed_k (rounding amounts below 32) against the oracle, on the host."""
+    k = 32 - b
+    g = si.rng(si.seed_for(0, 20 + b))
+    rnd_bits = g.integers(0, 1 << 64, 1 << 14, dtype=np.uint64)
+    e = g.integers(1023 - 160, 1023 + 130, 1 << 14, dtype=np.uint64)
+    band = (rnd_bits & np.uint64(0x800FFFFFFFFFFFFF)) | (e << np.uint64(52))
+    base = g.standard_normal(4000).astype(np.float32).view(np.uint32) & np.uint32(~((1 << k) - 1) & 0xFFFFFFFF)
+    base = base.view(np.float32).astype(np.float64)
+    mid = (base.view(np.uint64).astype(np.int64) + (1 << (28 + k)) + g.integers(-3, 4, base.size)).astype(np.uint64)
+    x = np.concatenate([si.edge_values(), band.view(np.float64), mid.view(np.float64), base])
+    bits = np.ascontiguousarray(x).view(np.uint64)
+    n = bits.size
+    y, D, dr = (np.empty(n, np.uint32) for _ in range(3))
+    harith.h_decide_k(bits.ctypes.data_as(C.POINTER(C.c_uint64)), C.c_uint64(n), C.c_uint32(k), _u32p(y), _u32p(D), _u32p(dr))
+    yo, _, _, _ = vo.round_log(x, 0.0, b_r=b)
+    assert np.array_equal(y, yo.view(np.uint32))
+    assert np.array_equal(D, np.array([vo.boundary_distance(float(v), b) for v in x], np.uint32))
+    for thr in (1, 1 << 12, 1 << 27, 1 << 28):
+        codes = np.array([vo.ternary_code(float(v), thr, b) for v in x[::3]])
+        assert np.array_equal(np.where(D[::3] < thr, np.where(dr[::3] == 1, 2, 0), 1), codes)
+    idx = np.arange(n, dtype=np.uint32)
+    for d in (0, 1):
+        yd = np.empty(n, np.uint32)
+        harith.h_directed_k(bits.ctypes.data_as(C.POINTER(C.c_uint64)), C.c_uint64(n), C.c_uint32(d), C.c_uint32(k), _u32p(yd))
+        want = vo.round_replay(x, idx, np.full((n + 31) // 32, 0xFFFFFFFF if d else 0, np.uint32), b_r=b)
+        assert np.array_equal(yd, want.view(np.uint32))
 
 
 def test_conv_geometry_and_validation_on_the_host(hiplib):
     import paper_2403_09603_amd.binding as b
     cnt = (C.c_uint64 * 1)()
-    log = b._VtLog(None, None, 0, C.addressof(cnt), None)
+    log = b._VtLog(None, None, 0, C.addressof(cnt), None, 0)
     fake = C.c_void_p(0x1000)
     INVALID, WORKSPACE = 1, 2
     # GEMM shapes of the ResNet-50 geometry at batch 64 against the oracle's output size
