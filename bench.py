@@ -237,6 +237,13 @@ def main():
         mism_d = int((y1.view(torch.int32) != y2.view(torch.int32)).sum().item())
         cnt_d = int(dlog.count.item())
         bytes_d = n * (8 + 4 + 0.2)
+        # and with rounding amount b_r = 26 (six more mantissa bits dropped), packed log
+        dlog26 = vt.alloc_dense_log(n)
+        dlog26.b_r = 26
+        r26_call, _ = timed(lambda: vt.vt_round_log(xd, tau_s, y1, dlog26, wss), reps=5)
+        p26_call, _ = timed(lambda: vt.vt_round_replay_dense(xd, dlog26.dense, y2, b_r=26), reps=5)
+        mism_26 = int((y1.view(torch.int32) != y2.view(torch.int32)).sum().item())
+        s26_call, _ = timed(lambda: vt.vt_threshold_stats(xd, xad, stats, b_r=26), reps=5)
         rho = cnt / n
         bytes_rl = n * (8 + 4 + rho * 4.125)
         out["standalone"] = {
@@ -257,8 +264,13 @@ def main():
                 "replay_ms": round(pd_call, 4), "replay_GBs": round(bytes_d / pd_call * 1e-6, 1),
                 "replay_frac_hbm": round(bytes_d / pd_call * 1e-6 / HBM_PEAK_GBS, 4),
                 "replay_mismatches": mism_d},
+            "b_r_26_packed_log": {
+                "round_log_ms": round(r26_call, 4), "round_log_GBs": round(bytes_d / r26_call * 1e-6, 1),
+                "replay_ms": round(p26_call, 4), "replay_GBs": round(bytes_d / p26_call * 1e-6, 1),
+                "stats_ms": round(s26_call, 4), "stats_GBs": round(n * 16 / s26_call * 1e-6, 1),
+                "replay_mismatches": mism_26},
         }
-        del xd, xad, y1, y2, logs, wss, dlog
+        del xd, xad, y1, y2, logs, wss, dlog, dlog26
 
     # ------------------------------------------------ CPU oracle baseline (bounded sample)
     if not args.no_cpu:
