@@ -75,7 +75,7 @@ def load_library():
     L.vt_thr_from_tau.restype = C.c_uint32
     L.vt_thr_from_tau.argtypes = [dbl]
     L.vt_gemm_plan.restype = cint
-    L.vt_gemm_plan.argtypes = [i64, i64, i64, i64, i64, i64, C.POINTER(cint), C.POINTER(cint), C.POINTER(cint)]
+    L.vt_gemm_plan.argtypes = [cint, i64, i64, i64, i64, i64, i64, C.POINTER(cint), C.POINTER(cint), C.POINTER(cint)]
     L.vt_set_kernel_events.restype = cint
     L.vt_set_kernel_events.argtypes = [vp, vp]
     L.vt_strerror.restype = C.c_char_p
@@ -257,10 +257,11 @@ def vt_conv2d_f64_round_log(mode: int, d: Conv2d, Cout: int, X: torch.Tensor, B:
         _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "vt_conv2d_f64_round_log")
 
 
-def vt_gemm_plan(M: int, N: int, K: int, batch: int = 1, ldc: int | None = None, strideC: int | None = None):
+def vt_gemm_plan(M: int, N: int, K: int, batch: int = 1, ldc: int | None = None, strideC: int | None = None,
+                 transA: bool = False):
     """(tile_m, tile_n, splits) the GEMM entry point uses for this shape."""
     tm, tn, sp = C.c_int(), C.c_int(), C.c_int()
-    _check(load_library().vt_gemm_plan(int(M), int(N), int(K), int(batch), int(N if ldc is None else ldc),
+    _check(load_library().vt_gemm_plan(int(bool(transA)), int(M), int(N), int(K), int(batch), int(N if ldc is None else ldc),
                                        int(M * N if strideC is None else strideC), C.byref(tm), C.byref(tn),
                                        C.byref(sp)), "vt_gemm_plan")
     return tm.value, tn.value, sp.value

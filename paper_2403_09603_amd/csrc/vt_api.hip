@@ -33,6 +33,14 @@ inline size_t round_log_bytes(uint64_t n)
     return a > b ? (a > c ? a : c) : (b > c ? b : c);
 }
 
+// the larger split factor of the two operand layouts (the workspace query does not know which)
+inline int max_splits(int64_t M, int64_t N, int64_t K, int64_t batch)
+{
+    const int a = vt::plan_gemm(M, N, K < 0 ? 0 : K, batch, true, false).splits;
+    const int b = vt::plan_gemm(M, N, K < 0 ? 0 : K, batch, true, true).splits;
+    return a > b ? a : b;
+}
+
 inline bool split_allowed(int64_t M, int64_t N, int64_t batch, int64_t ldc, int64_t strideC)
 {
     return ldc == N && (batch <= 1 || strideC == M * N);    // the round/log pass sees one flat tensor
@@ -88,7 +96,7 @@ int run_gemm(vt::GemmArgs &g, const vt_log *log, void *ws, size_t ws_bytes, hipS
     if (!ws || ws_bytes < need || !aligned(ws, 256)) return VT_ERR_WORKSPACE;
     const vt::Planes pl = vt::planes_carve(ws, (uint64_t)M * (uint64_t)batch, (uint64_t)N);
     const size_t planes = vt::planes_bytes((uint64_t)M * (uint64_t)batch, (uint64_t)N);
-    const vt::GemmPlan plan = vt::plan_gemm(M, N, K, batch, split_allowed(M, N, batch, g.ldc, g.strideC));
+    const vt::GemmPlan plan = vt::plan_gemm(M, N, K, batch, split_allowed(M, N, batch, g.ldc, g.strideC), g.transA != 0);
     g.raw = two_pass;
     if (plan.splits > 1 || two_pass) {
         // slabs -> fixed-order sum (alpha, bias) -> standalone round/log over the flat result
@@ -163,18 +171,15 @@ size_t vt_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int64_t batch
     if (M < 0 || N < 0 || batch < 0) return 0;
     switch (op) {
     case VT_OP_ROUND_LOG: return round_log_bytes((uint64_t)M * (uint64_t)N * (uint64_t)batch);
-    case VT_OP_GEMM_ROUND_LOG_BR: {
-        const vt::GemmPlan plan = vt::plan_gemm(M, N, K < 0 ? 0 : K, batch, true);
-        return vt::planes_bytes((uint64_t)M * (uint64_t)batch, (uint64_t)N) + vt::gemm_split_bytes(M, N, batch, plan.splits) +
+    case VT_OP_GEMM_ROUND_LOG_BR:
+        return vt::planes_bytes((uint64_t)M * (uint64_t)batch, (uint64_t)N) + vt::gemm_split_bytes(M, N, batch, max_splits(M, N, K, batch)) +
                round_log_bytes((uint64_t)M * (uint64_t)N * (uint64_t)batch);
-    }
     case VT_OP_GEMM_ROUND_LOG: {
         // sized for the split-K path too (taken for dense outputs when few tiles meet a long K)
         size_t bytes = vt::planes_bytes((uint64_t)M * (uint64_t)batch, (uint64_t)N);
-        const vt::GemmPlan plan = vt::plan_gemm(M, N, K < 0 ? 0 : K, batch, true);
-        if (plan.splits > 1)
-            bytes += vt::gemm_split_bytes(M, N, batch, plan.splits) +
-                     round_log_bytes((uint64_t)M * (uint64_t)N * (uint64_t)batch);
+        const int splits = max_splits(M, N, K, batch);
+        if (splits > 1)
+            bytes += vt::gemm_split_bytes(M, N, batch, splits) + round_log_bytes((uint64_t)M * (uint64_t)N * (uint64_t)batch);
         return bytes;
     }
     default: return 0;
@@ -316,12 +321,12 @@ int vt_threshold_stats_br(const double *y1, const double *y2, uint64_t n, int b_
     return hip_status(vt::launch_stats(y1, y2, n, k_of(b_r), out, (hipStream_t)hip_stream));
 }
 
-int vt_gemm_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int64_t ldc, int64_t strideC,
+int vt_gemm_plan(int transA, int64_t M, int64_t N, int64_t K, int64_t batch, int64_t ldc, int64_t strideC,
                  int *tile_m, int *tile_n, int *splits)
 {
     if (M < 0 || N < 0 || K < 0 || batch < 0 || !tile_m || !tile_n || !splits) return VT_ERR_INVALID_ARG;
-    const vt::GemmPlan plan = vt::plan_gemm(M, N, K, batch, split_allowed(M, N, batch, ldc, strideC));
-    static const int bm[4] = {128, 64, 128, 64}, bn[4] = {128, 128, 64, 64};
+    const vt::GemmPlan plan = vt::plan_gemm(M, N, K, batch, split_allowed(M, N, batch, ldc, strideC), transA != 0);
+    static const int bm[3] = {128, 64, 64}, bn[3] = {128, 128, 64};
     *tile_m = bm[plan.shape];
     *tile_n = bn[plan.shape];
     *splits = plan.splits;

@@ -8,8 +8,8 @@
 // Tiling: a workgroup is 256 threads = 4 waves arranged WM x WN (2 x 2 or 4 x 1); a wave owns
 // TM x 4 MFMA tiles of 16 x 16, i.e. 16 TM rows by 64 columns, so that one wave always produces
 // whole 64-bit words of the decision planes.  Workgroup tiles: 128 x 128 (2x2, TM 4: the large
-// shape, 128 accumulator registers per lane), 64 x 128 (2x2, TM 2), 128 x 64 (4x1, TM 2) and
-// 64 x 64 (4x1, TM 1) for narrow outputs and for problems with too few tiles to fill 256 CUs.
+// shape, 128 accumulator registers per lane), 64 x 128 (2x2, TM 2) and 64 x 64 (4x1, TM 1) for
+// narrow outputs, short K and problems with too few tiles to fill 256 CUs.
 // K step 16; operands are staged through LDS in k-major order ([k][m], [k][n]), double-buffered
 // against the global loads, and the next tile is written to LDS in the shadow of the last MFMA
 // group of the current one.
@@ -58,32 +58,39 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const double *__rest
     if (out2) out2[e] = c;
 }
 
-// bm x bn, measured MFMA efficiency with a full CU, workgroups that fit on one CU (LDS-bound)
-struct TileShape { int wm, tm, bm, bn; double eff; int conc; };
-constexpr TileShape kShapes[4] = {{2, 4, 128, 128, 0.85, 2}, {2, 2, 64, 128, 0.78, 2}, {4, 2, 128, 64, 0.74, 2},
-                                  {4, 1, 64, 64, 0.62, 3}};
+// bm x bn, measured MFMA efficiency with a full CU, workgroups that fit on one CU (LDS-bound),
+// cost of a tile's start and epilogue in k steps
+struct TileShape { int wm, tm, bm, bn; double eff; int conc; double overhead; };
+constexpr int kNumShapes = 3;
+constexpr TileShape kShapes[kNumShapes] = {{2, 4, 128, 128, 0.85, 2, 6.0}, {2, 2, 64, 128, 0.80, 2, 8.0},
+                                           {4, 1, 64, 64, 0.80, 3, 8.0}};
+// the same for an A operand stored transposed (its tiles are transposed on the way into LDS
+// from the other direction; the small square tile loses more there)
+constexpr TileShape kShapesT[kNumShapes] = {{2, 4, 128, 128, 0.85, 2, 10.0}, {2, 2, 64, 128, 0.78, 2, 10.0},
+                                            {4, 1, 64, 64, 0.62, 2, 10.0}};
 
 }  // namespace
 
 // Tile shape and split count for a problem, from a small cost model calibrated on the box (unit:
 // a quarter MFMA-pipe cycle per CU): rounds of 256 workgroups x work per workgroup / efficiency
-// of the shape (lower when a CU holds a single workgroup, which cannot hide its own stalls), plus
+// of the shape (lower when the grid leaves resident slots of a CU empty, so that stalls are not
+// hidden), plus
 // for split-K the two extra kernels and the slab traffic.  Pure host arithmetic on the shape, so
 // the choice (and with it the accumulation order) is a function of the arguments alone.
-GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split)
+GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split, bool transA)
 {
     GemmPlan best{0, 1, 0};
     double best_cost = 1e300;
     const int64_t nkt = (K + BK - 1) / BK;
-    for (int sh = 0; sh < 4; ++sh) {
-        const TileShape &t = kShapes[sh];
+    for (int sh = 0; sh < kNumShapes; ++sh) {
+        const TileShape &t = transA ? kShapesT[sh] : kShapes[sh];
         const double tiles = (double)((M + t.bm - 1) / t.bm) * (double)((N + t.bn - 1) / t.bn) * (double)batch;
         for (int sp = 1; sp <= 256; sp *= 2) {
             if (sp > 1 && (!allow_split || nkt / sp < 8)) break;        // keep >= 8 k steps per slice
             const double blocks = tiles * sp;
             const double rounds = std::ceil(blocks / 256.0);
-            const double eff = t.eff * (rounds >= 2.0 ? 1.0 : 0.72);
-            double cost = rounds * (double)t.bm * t.bn * ((double)((nkt + sp - 1) / sp) + 10.0) / eff;
+            const double eff = t.eff * (rounds >= (double)t.conc ? 1.0 : 0.72);
+            double cost = rounds * (double)t.bm * t.bn * ((double)((nkt + sp - 1) / sp) + t.overhead) / eff;
             if (sp > 1) cost += 144000.0 + 0.03 * (double)M * N * batch * (sp + 2);
             if (cost < best_cost) { best_cost = cost; best = GemmPlan{sh, sp, 0}; }
         }
@@ -137,7 +144,6 @@ hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, con
     switch (plan.shape) {
     case 0: e = launch_gemm_128x128(p, am, kcb, s); break;
     case 1: e = launch_gemm_64x128(p, am, kcb, s); break;
-    case 2: e = launch_gemm_128x64(p, am, kcb, s); break;
     default: e = launch_gemm_64x64(p, am, kcb, s); break;
     }
     if (e != hipSuccess || (plan.splits <= 1 && !g.raw)) return e;

@@ -87,11 +87,11 @@ struct GemmArgs {
 };
 // Tile shape (index into the kernel's shape table) and split-K factor chosen for a problem.
 struct GemmPlan {
-    int shape;          // 0: 128x128, 1: 64x128, 2: 128x64, 3: 64x64
+    int shape;          // 0: 128x128, 1: 64x128, 2: 64x64
     int splits;         // 1 = fused epilogue; > 1 = slabs + fixed-order reduction + round/log pass
     int kt_per_split;   // k steps of 16 per slice
 };
-GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split);
+GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split, bool transA);
 size_t gemm_split_bytes(int64_t M, int64_t N, int64_t batch, int splits);
 // splits == 1 and not g.raw: C32 / C64 / planes written by the epilogue.  Otherwise `partial`
 // receives the slabs, `reduced` (and g.C64 if set) the FP64 result alpha * sum + bias; nothing

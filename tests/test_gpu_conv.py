@@ -133,7 +133,7 @@ def test_weight_gradient_with_split_k_is_deterministic(G):
     import paper_2403_09603_amd as vt
     geom = (4, 48, 48, 16, 3, 3, 32, 1, 1, 1)
     N, H, W, Cin, KH, KW, Cout, stride, pad, dil = geom
-    assert vt.vt_gemm_plan(KH * KW * Cin, Cout, N * H * W, 1)[2] > 1
+    assert vt.vt_gemm_plan(KH * KW * Cin, Cout, N * H * W, 1, transA=True)[2] > 1
     a = _check_layer(G, geom, seed=3)
     b = _check_layer(G, geom, seed=3)
     for key in a:
