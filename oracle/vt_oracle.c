@@ -365,6 +365,101 @@ int vto_conv2d_wgrad_f64(const vto_conv2d *d, int64_t Cout, const double *X, con
     return VTO_OK;
 }
 
+int vto_elementwise_f64(int op, const double *a, const double *b, uint64_t n, double *y, int exact)
+{
+    if (op < VTO_EW_ADD || op > VTO_EW_GELU_ERF || (n && (!a || !y)) || (op == VTO_EW_ADD && n && !b))
+        return VTO_ERR_INVALID_ARG;
+    for (uint64_t i = 0; i < n; ++i) {
+        double x = a[i];
+        if (op == VTO_EW_ADD) {
+            y[i] = exact ? (double)((long double)x + (long double)b[i]) : x + b[i];
+        } else if (op == VTO_EW_RELU) {
+            y[i] = isnan(x) ? x : (x > 0.0 ? x : 0.0);
+        } else if (op == VTO_EW_GELU_TANH) {
+            if (exact) {
+                long double t = (long double)x;
+                long double u = sqrtl(2.0L / 3.14159265358979323846264338327950288L) * (t + 0.044715L * t * t * t);
+                y[i] = (double)(0.5L * t * (1.0L + tanhl(u)));
+            } else {
+                double x3 = x * x * x;
+                double u = 0.7978845608028654 * (x + 0.044715 * x3);      /* sqrt(2/pi) */
+                y[i] = 0.5 * x * (1.0 + tanh(u));
+            }
+        } else {
+            if (exact) {
+                long double t = (long double)x;
+                y[i] = (double)(0.5L * t * (1.0L + erfl(t / sqrtl(2.0L))));
+            } else {
+                y[i] = 0.5 * x * (1.0 + erf(x * 0.7071067811865476));     /* 1/sqrt 2 */
+            }
+        }
+    }
+    return VTO_OK;
+}
+
+int vto_layernorm_f64(const double *x, int64_t rows, int64_t cols, const double *gamma, const double *beta,
+                      double eps, double *y, int order)
+{
+    if (rows < 0 || cols < 0 || order < 0 || order > 2 || (rows * cols && (!x || !y))) return VTO_ERR_INVALID_ARG;
+    for (int64_t r = 0; r < rows; ++r) {
+        const double *xr = x + r * cols;
+        double *yr = y + r * cols;
+        if (order == 2) {
+            long double s = 0.0L, q = 0.0L;
+            for (int64_t c = 0; c < cols; ++c) s += (long double)xr[c];
+            long double mean = s / (long double)cols;
+            for (int64_t c = 0; c < cols; ++c) { long double d = (long double)xr[c] - mean; q += d * d; }
+            long double rstd = 1.0L / sqrtl(q / (long double)cols + (long double)eps);
+            for (int64_t c = 0; c < cols; ++c) {
+                long double v = ((long double)xr[c] - mean) * rstd;
+                if (gamma) v *= (long double)gamma[c];
+                if (beta) v += (long double)beta[c];
+                yr[c] = (double)v;
+            }
+        } else {
+            double s = 0.0, q = 0.0;
+            for (int64_t t = 0; t < cols; ++t) s = s + xr[order ? cols - 1 - t : t];
+            double mean = s / (double)cols;
+            for (int64_t t = 0; t < cols; ++t) { double d = xr[order ? cols - 1 - t : t] - mean; q = q + d * d; }
+            double rstd = 1.0 / sqrt(q / (double)cols + eps);
+            for (int64_t c = 0; c < cols; ++c) {
+                double v = (xr[c] - mean) * rstd;
+                if (gamma) v = v * gamma[c];
+                if (beta) v = v + beta[c];
+                yr[c] = v;
+            }
+        }
+    }
+    return VTO_OK;
+}
+
+int vto_softmax_f64(const double *x, int64_t rows, int64_t cols, double scale, int64_t causal_period,
+                    double *y, int order)
+{
+    if (rows < 0 || cols < 0 || causal_period < 0 || order < 0 || order > 2 || (rows * cols && (!x || !y)))
+        return VTO_ERR_INVALID_ARG;
+    for (int64_t r = 0; r < rows; ++r) {
+        const double *xr = x + r * cols;
+        double *yr = y + r * cols;
+        int64_t seen = causal_period > 0 ? r % causal_period + 1 : cols;   /* columns 0 .. seen-1 are visible */
+        if (seen > cols) seen = cols;
+        double m = -INFINITY;
+        for (int64_t c = 0; c < seen; ++c) { double z = scale * xr[c]; if (z > m) m = z; }
+        if (order == 2) {
+            long double s = 0.0L;
+            for (int64_t c = 0; c < seen; ++c) s += expl((long double)scale * (long double)xr[c] - (long double)m);
+            for (int64_t c = 0; c < cols; ++c)
+                yr[c] = c < seen ? (double)(expl((long double)scale * (long double)xr[c] - (long double)m) / s) : 0.0;
+        } else {
+            double s = 0.0;
+            for (int64_t t = 0; t < seen; ++t) { int64_t c = order ? seen - 1 - t : t; s = s + exp(scale * xr[c] - m); }
+            double inv = 1.0 / s;
+            for (int64_t c = 0; c < cols; ++c) yr[c] = c < seen ? exp(scale * xr[c] - m) * inv : 0.0;
+        }
+    }
+    return VTO_OK;
+}
+
 /* Monotone integer image of a binary64 pattern: sign-magnitude -> two's complement. */
 static int64_t ord64(double y)
 {

@@ -134,6 +134,33 @@ int vto_round_log_dense_b(const double *x, uint64_t n, double tau_ulp, int b_r, 
 int vto_round_replay_dense_b(const double *x, uint64_t n, const uint8_t *tlog, int b_r, float *y);
 int vto_threshold_stats_b(const double *y1, const double *y2, uint64_t n, int b_r, uint64_t out[68]);
 
+/* The other intermediate computations of a network whose outputs the method rounds (Method:
+ * "after every intermediate computation"; Table "thresholds" lists layer norm and batch norm next to
+ * convolution and linear layers): the element-wise and row-wise layers of a transformer block, by
+ * their textbook definitions, in FP64.
+ *   VTO_EW_ADD        y = a + b                                   (residual connection)
+ *   VTO_EW_RELU       y = x if x > 0, +0 otherwise (NaN stays NaN)
+ *   VTO_EW_GELU_TANH  y = x/2 (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3)))
+ *   VTO_EW_GELU_ERF   y = x/2 (1 + erf(x / sqrt 2))
+ * exact = 0: one binary64 operation per step in the order written; exact = 1: long double. */
+#define VTO_EW_ADD 0
+#define VTO_EW_RELU 1
+#define VTO_EW_GELU_TANH 2
+#define VTO_EW_GELU_ERF 3
+int vto_elementwise_f64(int op, const double *a, const double *b, uint64_t n, double *y, int exact);
+
+/* Layer normalisation of each row: mean = sum x / cols, var = sum (x - mean)^2 / cols (biased),
+ * y = (x - mean) / sqrt(var + eps) * gamma + beta (gamma, beta optional, per column).
+ * order 0: sums over ascending columns, 1: descending, 2: long double. */
+int vto_layernorm_f64(const double *x, int64_t rows, int64_t cols, const double *gamma, const double *beta,
+                      double eps, double *y, int order);
+
+/* Softmax of each row of z = scale * x: y_c = exp(z_c - max z) / sum exp(z - max z).  With
+ * causal_period T > 0, row r sees only columns c <= r mod T (attention over a sequence of T tokens,
+ * rows stacked head after head); the other outputs are 0.  order as above. */
+int vto_softmax_f64(const double *x, int64_t rows, int64_t cols, double scale, int64_t causal_period,
+                    double *y, int order);
+
 /* Threshold statistics over two results of the same operation (Algorithm "threshold",
  * collection loop): out[0] = number of elements whose FP32 roundings differ (bit patterns),
  * out[1] = 1 + max over those of max(D(y1), D(y2)) (0 when there are none),

@@ -87,6 +87,12 @@ def lib():
         L.vto_round_replay_dense_b.argtypes = [dp, C.c_uint64, u8p, C.c_int, fp]
         L.vto_threshold_stats_b.restype = C.c_int
         L.vto_threshold_stats_b.argtypes = [dp, dp, C.c_uint64, C.c_int, u64p]
+        L.vto_elementwise_f64.restype = C.c_int
+        L.vto_elementwise_f64.argtypes = [C.c_int, dp, dp, C.c_uint64, dp, C.c_int]
+        L.vto_layernorm_f64.restype = C.c_int
+        L.vto_layernorm_f64.argtypes = [dp, C.c_int64, C.c_int64, dp, dp, C.c_double, dp, C.c_int]
+        L.vto_softmax_f64.restype = C.c_int
+        L.vto_softmax_f64.argtypes = [dp, C.c_int64, C.c_int64, C.c_double, C.c_int64, dp, C.c_int]
         L.vto_conv2d_out_size.restype = C.c_int
         L.vto_conv2d_out_size.argtypes = [C.POINTER(Conv2d), C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
         L.vto_conv2d_fwd_f64.restype = C.c_int
@@ -262,6 +268,46 @@ def conv2d_wgrad(X, dY, KH, KW, *, stride=1, pad=0, dil=1, order=0):
     if rc != 0:
         raise ValueError(f"vto_conv2d_wgrad_f64: error {rc}")
     return dW
+
+
+EW_ADD, EW_RELU, EW_GELU_TANH, EW_GELU_ERF = 0, 1, 2, 3
+
+
+def elementwise(op: int, a, b=None, exact: bool = False):
+    a = _f64(a)
+    if b is not None:
+        b = _f64(b)
+        assert b.shape == a.shape
+    y = np.empty(a.shape, np.float64)
+    rc = lib().vto_elementwise_f64(int(op), _p(a, C.c_double), _p(b, C.c_double), a.size, _p(y, C.c_double),
+                                   int(bool(exact)))
+    if rc != 0:
+        raise ValueError(f"vto_elementwise_f64: error {rc}")
+    return y
+
+
+def layernorm(x, gamma=None, beta=None, eps: float = 1e-5, order: int = 0):
+    x = _f64(x)
+    assert x.ndim == 2
+    gamma = _f64(gamma) if gamma is not None else None
+    beta = _f64(beta) if beta is not None else None
+    y = np.empty(x.shape, np.float64)
+    rc = lib().vto_layernorm_f64(_p(x, C.c_double), x.shape[0], x.shape[1], _p(gamma, C.c_double),
+                                 _p(beta, C.c_double), float(eps), _p(y, C.c_double), int(order))
+    if rc != 0:
+        raise ValueError(f"vto_layernorm_f64: error {rc}")
+    return y
+
+
+def softmax(x, scale: float = 1.0, causal_period: int = 0, order: int = 0):
+    x = _f64(x)
+    assert x.ndim == 2
+    y = np.empty(x.shape, np.float64)
+    rc = lib().vto_softmax_f64(_p(x, C.c_double), x.shape[0], x.shape[1], float(scale), int(causal_period),
+                               _p(y, C.c_double), int(order))
+    if rc != 0:
+        raise ValueError(f"vto_softmax_f64: error {rc}")
+    return y
 
 
 def threshold_stats(y1, y2, b_r: int = 32):
