@@ -244,6 +244,19 @@ def main():
         p26_call, _ = timed(lambda: vt.vt_round_replay_dense(xd, dlog26.dense, y2, b_r=26), reps=5)
         mism_26 = int((y1.view(torch.int32) != y2.view(torch.int32)).sum().item())
         s26_call, _ = timed(lambda: vt.vt_threshold_stats(xd, xad, stats, b_r=26), reps=5)
+        # fused layers (FP64 evaluation + hook in one pass, packed log): GELU, layer norm, softmax
+        # over the same 2^28 values seen as 262144 rows of 1024
+        rows_l, cols_l = n // 1024, 1024
+        wsl = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_LAYER_ROUND_LOG, rows_l, cols_l))
+        layers = {}
+        for lname, lop, kw in (("gelu_tanh", vt.VT_LAYER_GELU_TANH, {}), ("layer_norm", vt.VT_LAYER_NORM, {"eps": 1e-5}),
+                               ("softmax", vt.VT_LAYER_SOFTMAX, {"scale": 0.125})):
+            l_call, _ = timed(lambda: vt.vt_layer_f64_round_log(lop, xd, None, None, None, rows_l, cols_l, y1, None, 0,
+                                                                tau_s, dlog, wsl, **kw), reps=5)
+            # row-wise layers read the input twice (statistics, then the fused pass)
+            lbytes = n * (8 + 4 + 0.2 + (8 if lop in (vt.VT_LAYER_NORM, vt.VT_LAYER_SOFTMAX) else 0))
+            layers[lname] = {"ms": round(l_call, 4), "GBs": round(lbytes / l_call * 1e-6, 1)}
+        del wsl
         rho = cnt / n
         bytes_rl = n * (8 + 4 + rho * 4.125)
         out["standalone"] = {
@@ -264,6 +277,7 @@ def main():
                 "replay_ms": round(pd_call, 4), "replay_GBs": round(bytes_d / pd_call * 1e-6, 1),
                 "replay_frac_hbm": round(bytes_d / pd_call * 1e-6 / HBM_PEAK_GBS, 4),
                 "replay_mismatches": mism_d},
+            "fused_layers_packed_log": layers,
             "b_r_26_packed_log": {
                 "round_log_ms": round(r26_call, 4), "round_log_GBs": round(bytes_d / r26_call * 1e-6, 1),
                 "replay_ms": round(p26_call, 4), "replay_GBs": round(bytes_d / p26_call * 1e-6, 1),

@@ -77,6 +77,7 @@ extern "C" {
 #define VT_OP_GEMM_ROUND_LOG 2
 #define VT_OP_THRESHOLD_STATS 3 /* needs no workspace (returns 0) */
 #define VT_OP_GEMM_ROUND_LOG_BR 4 /* GEMM / convolution with log->b_r below 32 (rounds in a second pass) */
+#define VT_OP_LAYER_ROUND_LOG 5  /* vt_layer_f64_round_log: M = rows, N = cols */
 
 /* Caller-owned log buffers (all four pointers are device pointers). */
 typedef struct vt_log {
@@ -205,6 +206,46 @@ int vt_conv2d_f64_round_log(int mode, const vt_conv2d *d, int64_t Cout, const do
 /* The GEMM the convolution runs as: forward M = N Ho Wo, N = Cout, K = KH KW C; weight gradient
  * M = KH KW C, N = Cout, K = N Ho Wo.  Host only. */
 int vt_conv2d_gemm_shape(const vt_conv2d *d, int64_t Cout, int mode, int64_t *M, int64_t *N, int64_t *K);
+
+/*
+ * The element-wise and row-wise layers of a network, fused with the trainer hook (Method: rounding
+ * "after every intermediate computation"; Table "thresholds" lists layer norm and batch norm beside
+ * convolution and linear layers).  The layer is evaluated in FP64 from its FP64 inputs and every
+ * output is rounded and logged in the same pass; the FP64 output is never stored (unless asked for).
+ *
+ *   VT_LAYER_ADD        y = a + b                          (residual connection)
+ *   VT_LAYER_RELU       y = a if a > 0, +0 otherwise (NaN stays NaN)
+ *   VT_LAYER_GELU_TANH  y = a/2 (1 + tanh(sqrt(2/pi) (a + 0.044715 a^3)))
+ *   VT_LAYER_GELU_ERF   y = a/2 (1 + erf(a / sqrt 2))
+ *   VT_LAYER_NORM       per row: y = (a - mean) / sqrt(var + eps) * gamma + beta, biased variance;
+ *                       gamma, beta per column, either may be NULL
+ *   VT_LAYER_SOFTMAX    per row of z = scale * a: y = exp(z - max z) / sum exp(z - max z); with
+ *                       causal_period T > 0 row r sees only columns c <= r mod T, the rest are 0
+ *
+ *   a, b         device, rows x cols FP64, dense, 16-byte aligned
+ *   y            device, rows x cols FP32, 8-byte aligned; y64_debug: optional FP64 copy of the layer
+ *   variant      summation order of the row statistics (0 or 1), as two GPU types would differ
+ *   rows * cols must be < 2^32.  ws: vt_workspace_bytes(VT_OP_LAYER_ROUND_LOG, rows, cols, 0, 1).
+ */
+#define VT_LAYER_ADD 0
+#define VT_LAYER_RELU 1
+#define VT_LAYER_GELU_TANH 2
+#define VT_LAYER_GELU_ERF 3
+#define VT_LAYER_NORM 4
+#define VT_LAYER_SOFTMAX 5
+
+typedef struct vt_layer {
+    int32_t op;                      /* VT_LAYER_* */
+    const double *a, *b;             /* b: second addend of VT_LAYER_ADD, else NULL */
+    const double *gamma, *beta;      /* VT_LAYER_NORM */
+    int64_t rows, cols;
+    double eps;                      /* VT_LAYER_NORM */
+    double scale;                    /* VT_LAYER_SOFTMAX */
+    int64_t causal_period;           /* VT_LAYER_SOFTMAX, 0 = no mask */
+} vt_layer;
+
+int vt_layer_f64_round_log(const vt_layer *layer, float *y, double *y64_debug, int variant,
+                           double tau_ulp, const vt_log *log, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
  * Statistics from which a per-layer threshold follows (Algorithm "threshold": the collection

@@ -17,6 +17,8 @@ _lib = None
 
 VT_OP_ROUND_LOG, VT_OP_ROUND_REPLAY, VT_OP_GEMM_ROUND_LOG, VT_OP_THRESHOLD_STATS, VT_OP_GEMM_ROUND_LOG_BR = 0, 1, 2, 3, 4
 VT_CONV_FORWARD, VT_CONV_WEIGHT_GRAD = 0, 1
+VT_OP_LAYER_ROUND_LOG = 5
+VT_LAYER_ADD, VT_LAYER_RELU, VT_LAYER_GELU_TANH, VT_LAYER_GELU_ERF, VT_LAYER_NORM, VT_LAYER_SOFTMAX = 0, 1, 2, 3, 4, 5
 
 
 class VtError(RuntimeError):
@@ -32,6 +34,13 @@ class Conv2d(C.Structure):
     """vt_conv2d of include/vt.h: geometry of a channels-last 2-D convolution."""
     _fields_ = [(k, C.c_int64) for k in ("N", "H", "W", "C", "KH", "KW", "stride_h", "stride_w", "pad_h", "pad_w",
                                          "dil_h", "dil_w")]
+
+
+class _VtLayer(C.Structure):
+    """vt_layer of include/vt.h."""
+    _fields_ = [("op", C.c_int32), ("a", C.c_void_p), ("b", C.c_void_p), ("gamma", C.c_void_p), ("beta", C.c_void_p),
+                ("rows", C.c_int64), ("cols", C.c_int64), ("eps", C.c_double), ("scale", C.c_double),
+                ("causal_period", C.c_int64)]
 
 
 def library_path() -> str:
@@ -68,6 +77,8 @@ def load_library():
                                           C.POINTER(_VtLog), vp, C.c_size_t, vp]
     L.vt_conv2d_gemm_shape.restype = cint
     L.vt_conv2d_gemm_shape.argtypes = [C.POINTER(Conv2d), i64, cint, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
+    L.vt_layer_f64_round_log.restype = cint
+    L.vt_layer_f64_round_log.argtypes = [C.POINTER(_VtLayer), vp, vp, cint, dbl, C.POINTER(_VtLog), vp, C.c_size_t, vp]
     L.vt_threshold_stats.restype = cint
     L.vt_threshold_stats.argtypes = [vp, vp, u64, vp, vp]
     L.vt_workspace_bytes.restype = C.c_size_t
@@ -255,6 +266,31 @@ def vt_conv2d_f64_round_log(mode: int, d: Conv2d, Cout: int, X: torch.Tensor, B:
         int(mode), C.byref(d), int(Cout), _ptr(X, torch.float64), _ptr(B, torch.float64), _ptr(bias, torch.float64),
         _ptr(C32, torch.float32), _ptr(C64_debug, torch.float64), int(variant), float(tau_ulp), C.byref(clog),
         _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "vt_conv2d_f64_round_log")
+
+
+def vt_layer_f64_round_log(op: int, a: torch.Tensor, b, gamma, beta, rows: int, cols: int, y: torch.Tensor, y64_debug,
+                           variant: int, tau_ulp: float, log: Log, ws: torch.Tensor, *, eps: float = 1e-5,
+                           scale: float = 1.0, causal_period: int = 0, stream=None):
+    n = int(rows) * int(cols)
+    if a.numel() < n or y.numel() < n or (b is not None and b.numel() < n):
+        raise VtError("a, b and y must hold rows*cols elements")
+    if (gamma is not None and gamma.numel() < cols) or (beta is not None and beta.numel() < cols):
+        raise VtError("gamma and beta must hold cols elements")
+    if y64_debug is not None and y64_debug.numel() < n:
+        raise VtError("y64_debug must hold rows*cols elements")
+    if log.dense is not None and log.dense.numel() < (n + 4) // 5:
+        raise VtError("dense log is smaller than ceil(rows*cols/5) bytes")
+    layer = _VtLayer(int(op), a.data_ptr() if n else None, b.data_ptr() if b is not None and n else None,
+                     gamma.data_ptr() if gamma is not None else None, beta.data_ptr() if beta is not None else None,
+                     int(rows), int(cols), float(eps), float(scale), int(causal_period))
+    for t in (a, b, gamma, beta):
+        if t is not None:
+            _ptr(t, torch.float64)
+    clog = log._c()
+    _check(load_library().vt_layer_f64_round_log(C.byref(layer), _ptr(y, torch.float32), _ptr(y64_debug, torch.float64),
+                                                 int(variant), float(tau_ulp), C.byref(clog), _ptr(ws),
+                                                 ws.numel() * ws.element_size(), _stream(stream)),
+           "vt_layer_f64_round_log")
 
 
 def vt_gemm_plan(M: int, N: int, K: int, batch: int = 1, ldc: int | None = None, strideC: int | None = None,

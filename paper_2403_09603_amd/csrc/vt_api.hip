@@ -171,6 +171,8 @@ size_t vt_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int64_t batch
     if (M < 0 || N < 0 || batch < 0) return 0;
     switch (op) {
     case VT_OP_ROUND_LOG: return round_log_bytes((uint64_t)M * (uint64_t)N * (uint64_t)batch);
+    case VT_OP_LAYER_ROUND_LOG:
+        return round_log_bytes((uint64_t)M * (uint64_t)N * (uint64_t)batch) + vt::layer_stat_bytes((uint64_t)M * (uint64_t)batch);
     case VT_OP_GEMM_ROUND_LOG_BR:
         return vt::planes_bytes((uint64_t)M * (uint64_t)batch, (uint64_t)N) + vt::gemm_split_bytes(M, N, batch, max_splits(M, N, K, batch)) +
                round_log_bytes((uint64_t)M * (uint64_t)N * (uint64_t)batch);
@@ -307,6 +309,47 @@ int vt_conv2d_f64_round_log(int mode, const vt_conv2d *d, int64_t Cout, const do
     g.bias = bias; g.batch = 1; g.C32 = C32; g.ldc = Cout; g.strideC = 0;
     g.C64 = C64_debug; g.variant = variant; g.thr = thr;
     return run_gemm(g, log, ws, ws_bytes, s);
+}
+
+int vt_layer_f64_round_log(const vt_layer *L, float *y, double *y64_debug, int variant,
+                           double tau_ulp, const vt_log *log, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    const uint32_t thr = vt_thr_from_tau(tau_ulp);
+    if (thr == 0xFFFFFFFFu || !log_ok(log) || !L || variant < 0 || variant > 1) return VT_ERR_INVALID_ARG;
+    if (L->op < VT_LAYER_ADD || L->op > VT_LAYER_SOFTMAX || L->rows < 0 || L->cols < 0 || L->causal_period < 0)
+        return VT_ERR_INVALID_ARG;
+    if ((unsigned __int128)L->rows * (unsigned __int128)L->cols >= ((unsigned __int128)1 << 32)) return VT_ERR_INVALID_ARG;
+    if (L->causal_period >= ((int64_t)1 << 32)) return VT_ERR_INVALID_ARG;
+    const uint64_t n = (uint64_t)L->rows * (uint64_t)L->cols;
+    if (n) {
+        if (!L->a || !y || !aligned(L->a, 16) || !aligned(y, 8)) return VT_ERR_INVALID_ARG;
+        if (L->op == VT_LAYER_ADD && (!L->b || !aligned(L->b, 16))) return VT_ERR_INVALID_ARG;
+        if ((L->gamma && !aligned(L->gamma, 8)) || (L->beta && !aligned(L->beta, 8))) return VT_ERR_INVALID_ARG;
+        if (y64_debug && !aligned(y64_debug, 16)) return VT_ERR_INVALID_ARG;
+        if (L->op == VT_LAYER_NORM && !(L->eps >= 0.0)) return VT_ERR_INVALID_ARG;
+    }
+    const size_t rl = round_log_bytes(n);
+    if (!ws || ws_bytes < rl + vt::layer_stat_bytes((uint64_t)L->rows) || !aligned(ws, 256)) return VT_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    vt::LayerArgs g;
+    g.op = L->op; g.a = L->a; g.b = L->b;
+    g.gamma = L->op == VT_LAYER_NORM ? L->gamma : nullptr;
+    g.beta = L->op == VT_LAYER_NORM ? L->beta : nullptr;
+    g.stat = (const double *)((char *)ws + rl);
+    g.y64 = y64_debug;
+    g.cols = (uint32_t)(L->cols > 0 ? L->cols : 1);
+    g.inv_cols = 1.0 / (double)g.cols;
+    g.scale = L->scale;
+    g.period = L->op == VT_LAYER_SOFTMAX ? (uint32_t)L->causal_period : 0u;
+    g.inv_period = g.period ? 1.0 / (double)g.period : 0.0;
+    hipError_t e = vt::launch_layer_stats(g, (uint64_t)L->rows, L->eps, variant, s);
+    if (e != hipSuccess) return VT_ERR_HIP;
+    const uint32_t k = k_of(log->b_r);
+    mark_begin(s);
+    if (log->dense) e = vt::launch_layer_log_dense(g, n, thr, k, y, log->dense, log->count, (uint64_t *)ws, s);
+    else e = vt::launch_layer_log_onepass(g, n, thr, k, y, ws, vt::LogOut{log->idx, log->dir, log->cap, log->count}, s);
+    mark_end(s);
+    return hip_status(e);
 }
 
 int vt_threshold_stats(const double *y1, const double *y2, uint64_t n, uint64_t *out, void *hip_stream)

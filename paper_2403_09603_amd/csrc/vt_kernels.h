@@ -61,6 +61,32 @@ hipError_t launch_round_log_dense(const double *x, uint64_t n, uint32_t thr, uin
 hipError_t launch_replay_dense(const double *x, uint64_t n, const uint8_t *tlog, uint32_t k, float *y, hipStream_t s);
 hipError_t launch_planes_to_dense(const Planes &pl, uint64_t rows, uint8_t *tlog, hipStream_t s);
 
+// ---- element-wise and row-wise layers fused with the trainer hook -----------------------------
+// Layer selectors (the public VT_LAYER_* values).
+enum { kLayerAdd = 0, kLayerRelu = 1, kLayerGeluTanh = 2, kLayerGeluErf = 3, kLayerNorm = 4, kLayerSoftmax = 5 };
+
+struct LayerArgs {
+    int op;
+    const double *a, *b;          // inputs (b: second addend of the residual add)
+    const double *gamma, *beta;   // layer norm: per-column scale and shift, either may be null
+    const double *stat;           // per row: (mean, 1/std) for layer norm, (max, 1/sum) for softmax
+    double *y64;                  // optional FP64 copy of the layer's output
+    uint32_t cols;
+    double inv_cols;              // 1 / cols (index split by reciprocal multiply + correction)
+    double scale;                 // softmax: logits are scale * a
+    uint32_t period;              // softmax: causal mask period, 0 = none
+    double inv_period;
+};
+
+size_t layer_stat_bytes(uint64_t rows);
+// per-row statistics of layer norm / softmax into g.stat (no-op for the element-wise layers);
+// variant selects the summation order
+hipError_t launch_layer_stats(const LayerArgs &g, uint64_t rows, double eps, int variant, hipStream_t s);
+hipError_t launch_layer_log_onepass(const LayerArgs &g, uint64_t n, uint32_t thr, uint32_t k, float *y, void *ws,
+                                    const LogOut &log, hipStream_t s);
+hipError_t launch_layer_log_dense(const LayerArgs &g, uint64_t n, uint32_t thr, uint32_t k, float *y, uint8_t *tlog,
+                                  uint64_t *n_logged, uint64_t *slots, hipStream_t s);
+
 hipError_t launch_stats(const double *y1, const double *y2, uint64_t n, uint32_t k, uint64_t *out, hipStream_t s);
 
 // Geometry of a channels-last convolution whose image the GEMM kernel reads through an implicit

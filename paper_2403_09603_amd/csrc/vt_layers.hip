@@ -1,0 +1,110 @@
+// vt_layers.hip -- per-row statistics of the row-wise layers (layer norm, softmax) that the fused
+// layer + trainer-hook kernels read: one wavefront per row, two sweeps over the row (the second
+// one hits the cache), FP64 throughout.
+//
+// Summation order: lane l adds the columns l, l + 64, l + 128, ... of its row (variant 0: in
+// ascending order, variant 1: in descending order), then the 64 partial sums are combined by a
+// fixed butterfly (variant 0: strides 32, 16, ..., 1; variant 1: strides 1, 2, ..., 32).  Both
+// orders are fixed, so a given variant always returns the same bits; the two variants differ in
+// their low bits the way two GPU types do.
+#include "vt_device.h"
+#include "vt_kernels.h"
+
+#include <math.h>
+
+namespace vt {
+
+namespace {
+
+__device__ __forceinline__ double wave_add(double v, int variant)
+{
+    if (variant == 0) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v = v + __shfl_xor(v, o, 64);
+    } else {
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) v = v + __shfl_xor(v, o, 64);
+    }
+    return v;
+}
+
+__device__ __forceinline__ double wave_max(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const double w = __shfl_xor(v, o, 64);
+        v = w > v ? w : v;
+    }
+    return v;
+}
+
+// columns this lane visits, in the variant's order: c = lane + 64 j
+__device__ __forceinline__ uint32_t nth_col(uint32_t lane, uint32_t mine, uint32_t j, int variant)
+{
+    return lane + 64u * (variant ? mine - 1u - j : j);
+}
+
+__global__ __launch_bounds__(256) void layernorm_stats_kernel(const double *__restrict__ x, uint32_t rows, uint32_t cols,
+                                                              double eps, int variant, double *__restrict__ stat)
+{
+    const uint32_t lane = threadIdx.x & 63u, r = blockIdx.x * 4u + (threadIdx.x >> 6);
+    if (r >= rows) return;
+    const double *xr = x + (uint64_t)r * cols;
+    const uint32_t mine = cols > lane ? (cols - lane + 63u) / 64u : 0u;
+    double s = 0.0;
+    for (uint32_t j = 0; j < mine; ++j) s = s + xr[nth_col(lane, mine, j, variant)];
+    const double mean = wave_add(s, variant) / (double)cols;
+    double q = 0.0;
+    for (uint32_t j = 0; j < mine; ++j) {
+        const double d = xr[nth_col(lane, mine, j, variant)] - mean;
+        q = q + d * d;
+    }
+    const double rstd = 1.0 / sqrt(wave_add(q, variant) / (double)cols + eps);
+    if (lane == 0) {
+        stat[2 * (uint64_t)r] = mean;
+        stat[2 * (uint64_t)r + 1] = rstd;
+    }
+}
+
+__global__ __launch_bounds__(256) void softmax_stats_kernel(const double *__restrict__ x, uint32_t rows, uint32_t cols,
+                                                            double scale, uint32_t period, int variant,
+                                                            double *__restrict__ stat)
+{
+    const uint32_t lane = threadIdx.x & 63u, r = blockIdx.x * 4u + (threadIdx.x >> 6);
+    if (r >= rows) return;
+    const double *xr = x + (uint64_t)r * cols;
+    uint32_t seen = cols;                                           // columns 0 .. seen - 1 are visible
+    if (period) seen = r % period + 1u < cols ? r % period + 1u : cols;
+    const uint32_t mine = seen > lane ? (seen - lane + 63u) / 64u : 0u;
+    double m = -INFINITY;
+    for (uint32_t j = 0; j < mine; ++j) {
+        const double z = scale * xr[lane + 64u * j];
+        m = z > m ? z : m;
+    }
+    m = wave_max(m);
+    double s = 0.0;
+    for (uint32_t j = 0; j < mine; ++j) s = s + exp(scale * xr[nth_col(lane, mine, j, variant)] - m);
+    const double inv = 1.0 / wave_add(s, variant);
+    if (lane == 0) {
+        stat[2 * (uint64_t)r] = m;
+        stat[2 * (uint64_t)r + 1] = inv;
+    }
+}
+
+}  // namespace
+
+size_t layer_stat_bytes(uint64_t rows) { return (size_t)((rows * 16 + 255) / 256 * 256); }
+
+hipError_t launch_layer_stats(const LayerArgs &g, uint64_t rows, double eps, int variant, hipStream_t s)
+{
+    if (rows == 0 || g.cols == 0 || (g.op != kLayerNorm && g.op != kLayerSoftmax)) return hipSuccess;
+    const dim3 grid((uint32_t)((rows + 3) / 4)), block(256);
+    if (g.op == kLayerNorm)
+        layernorm_stats_kernel<<<grid, block, 0, s>>>(g.a, (uint32_t)rows, g.cols, eps, variant, (double *)g.stat);
+    else
+        softmax_stats_kernel<<<grid, block, 0, s>>>(g.a, (uint32_t)rows, g.cols, g.scale, g.period, variant,
+                                                    (double *)g.stat);
+    return hipGetLastError();
+}
+
+}  // namespace vt

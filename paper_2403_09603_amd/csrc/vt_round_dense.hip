@@ -18,6 +18,7 @@
 // the whole stream) and folded by a one-workgroup kernel afterwards.
 #include "vt_device.h"
 #include "vt_kernels.h"
+#include "vt_source.h"
 
 namespace vt {
 
@@ -55,19 +56,14 @@ __device__ __forceinline__ uint32_t code_of(double x, uint32_t thr, uint32_t k, 
     return r.logged ? (r.up ? 2u : 0u) : 1u;
 }
 
-template <bool FULL, bool VEC>
-__device__ __forceinline__ void load_rows(const double *__restrict__ x, uint64_t n, uint64_t base, uint32_t lane,
-                                          d2 (&v)[kRows])
+template <bool FULL, bool VEC, class Src>
+__device__ __forceinline__ void load_rows(const Src &src, uint64_t n, uint64_t base, uint32_t lane, d2 (&v)[kRows])
 {
 #pragma unroll
-    for (int u = 0; u < kRows; ++u) {
-        const uint64_t e = base + (uint64_t)u * 128u + 2u * lane;
-        if (VEC && (FULL || e + 1 < n)) v[u] = __builtin_nontemporal_load((const d2 *)(x + e));
-        else {
-            v[u].x = e < n ? x[e] : 1.0;                          // 1.0 is never logged: code 1 in the tail
-            v[u].y = e + 1 < n ? x[e + 1] : 1.0;
-        }
-    }
+    for (int u = 0; u < kRows; ++u)                               // past the end: 1.0, never logged (code 1 in the tail)
+        v[u] = src.template pair<FULL, VEC>(base + (uint64_t)u * 128u + 2u * lane, n);
+#pragma unroll
+    for (int u = 0; u < kRows; ++u) src.template keep<FULL, VEC>(base + (uint64_t)u * 128u + 2u * lane, n, v[u]);
 }
 
 template <bool FULL, bool VEC>
@@ -85,8 +81,8 @@ __device__ __forceinline__ void store_pair(float *__restrict__ y, uint64_t n, ui
 }
 
 // Trainer: y = rnd_32(x), tlog = packed codes.  One workgroup per 5120 elements.
-template <bool FULL, bool VEC, bool K0>
-__device__ __forceinline__ void round_log_dense_chunk(const double *__restrict__ x, uint64_t n, uint32_t thr, uint32_t k,
+template <bool FULL, bool VEC, bool K0, class Src>
+__device__ __forceinline__ void round_log_dense_chunk(const Src &x, uint64_t n, uint32_t thr, uint32_t k,
                                                       float *__restrict__ y, uint8_t *__restrict__ tlog,
                                                       uint64_t base, uint32_t lane, uint8_t *__restrict__ mine,
                                                       uint64_t *__restrict__ slots)
@@ -135,8 +131,8 @@ __device__ __forceinline__ void round_log_dense_chunk(const double *__restrict__
     }
 }
 
-template <bool VEC, bool K0>
-__global__ __launch_bounds__(256) void round_log_dense_kernel(const double *__restrict__ x, uint64_t n, uint32_t thr,
+template <bool VEC, bool K0, class Src>
+__global__ __launch_bounds__(256) void round_log_dense_kernel(const Src x, uint64_t n, uint32_t thr,
                                                               uint32_t k, float *__restrict__ y,
                                                               uint8_t *__restrict__ tlog, uint64_t *__restrict__ slots)
 {
@@ -155,7 +151,7 @@ __device__ __forceinline__ void replay_dense_chunk(const double *__restrict__ x,
                                                    uint64_t base, uint32_t lane, uint8_t *__restrict__ mine, uint32_t k)
 {
     d2 v[kRows];
-    load_rows<FULL, VEC>(x, n, base, lane, v);
+    load_rows<FULL, VEC>(PlainSource{x}, n, base, lane, v);
     // four bytes of the log -> twenty codes, written where their elements' lanes will look
     const uint64_t byte0 = base / 5u + 4u * lane;
     uint32_t packed = 0x79797979u;                                // 0x79 = 121 = five times "ignore"
@@ -245,9 +241,12 @@ __global__ __launch_bounds__(256) void planes_to_dense_kernel(const uint64_t *__
 
 size_t dense_count_bytes() { return (size_t)kSlots * kSlotStride * 8; }
 
+namespace {
+
 // `slots`: dense_count_bytes() of scratch, needed when n_logged is wanted
-hipError_t launch_round_log_dense(const double *x, uint64_t n, uint32_t thr, uint32_t k, float *y, uint8_t *tlog,
-                                  uint64_t *n_logged, uint64_t *slots, hipStream_t s)
+template <class Src>
+hipError_t launch_dense_from(const Src &src, bool vec, uint64_t n, uint32_t thr, uint32_t k, float *y, uint8_t *tlog,
+                             uint64_t *n_logged, uint64_t *slots, hipStream_t s)
 {
     if (n == 0 || !n_logged || !slots) {
         if (n_logged) {
@@ -263,18 +262,33 @@ hipError_t launch_round_log_dense(const double *x, uint64_t n, uint32_t thr, uin
         if (e != hipSuccess) return e;
     }
     const uint64_t blocks = (n + kTile - 1) / kTile;
-    const bool vec = ((uintptr_t)x % 16 == 0) && ((uintptr_t)y % 8 == 0);
     const dim3 grid((uint32_t)blocks), block(256);
-    if (vec && k == 0) round_log_dense_kernel<true, true><<<grid, block, 0, s>>>(x, n, thr, k, y, tlog, slots);
-    else if (vec) round_log_dense_kernel<true, false><<<grid, block, 0, s>>>(x, n, thr, k, y, tlog, slots);
-    else if (k == 0) round_log_dense_kernel<false, true><<<grid, block, 0, s>>>(x, n, thr, k, y, tlog, slots);
-    else round_log_dense_kernel<false, false><<<grid, block, 0, s>>>(x, n, thr, k, y, tlog, slots);
+    if (vec && k == 0) round_log_dense_kernel<true, true, Src><<<grid, block, 0, s>>>(src, n, thr, k, y, tlog, slots);
+    else if (vec) round_log_dense_kernel<true, false, Src><<<grid, block, 0, s>>>(src, n, thr, k, y, tlog, slots);
+    else if (k == 0) round_log_dense_kernel<false, true, Src><<<grid, block, 0, s>>>(src, n, thr, k, y, tlog, slots);
+    else round_log_dense_kernel<false, false, Src><<<grid, block, 0, s>>>(src, n, thr, k, y, tlog, slots);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && slots) {
         sum_slots_kernel<<<1, kSlots, 0, s>>>(slots, n_logged);
         e = hipGetLastError();
     }
     return e;
+}
+
+}  // namespace
+
+hipError_t launch_round_log_dense(const double *x, uint64_t n, uint32_t thr, uint32_t k, float *y, uint8_t *tlog,
+                                  uint64_t *n_logged, uint64_t *slots, hipStream_t s)
+{
+    const bool vec = ((uintptr_t)x % 16 == 0) && ((uintptr_t)y % 8 == 0);
+    return launch_dense_from(PlainSource{x}, vec, n, thr, k, y, tlog, n_logged, slots, s);
+}
+
+// the same stream with a layer evaluated on the fly as its source (inputs 16-byte aligned)
+hipError_t launch_layer_log_dense(const LayerArgs &g, uint64_t n, uint32_t thr, uint32_t k, float *y, uint8_t *tlog,
+                                  uint64_t *n_logged, uint64_t *slots, hipStream_t s)
+{
+    return launch_dense_from(LayerSource{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
 }
 
 hipError_t launch_replay_dense(const double *x, uint64_t n, const uint8_t *tlog, uint32_t k, float *y, hipStream_t s)

@@ -24,6 +24,7 @@
 // drains; the host-visible result is then *count = UINT64_MAX.
 #include "vt_device.h"
 #include "vt_kernels.h"
+#include "vt_source.h"
 
 namespace vt {
 
@@ -148,8 +149,8 @@ __device__ __forceinline__ void scanner(uint64_t *__restrict__ st, uint32_t tile
 // One wave's share of a tile: 1024 contiguous values as 8 rows of 128 (two per lane).  FULL:
 // the whole tile lies inside the array, so no access is guarded.  Returns the wave's count;
 // entries go to `ent` in element order.
-template <bool FULL, bool K0>
-__device__ __forceinline__ uint32_t round_rows(const double *__restrict__ x, uint64_t n, uint32_t thr, uint32_t k,
+template <bool FULL, bool K0, class Src>
+__device__ __forceinline__ uint32_t round_rows(const Src &x, uint64_t n, uint32_t thr, uint32_t k,
                                                float *__restrict__ y, uint64_t wbase, uint32_t lane,
                                                uint16_t *__restrict__ ent)
 {
@@ -157,12 +158,10 @@ __device__ __forceinline__ uint32_t round_rows(const double *__restrict__ x, uin
 #pragma unroll
     for (int u = 0; u < kRows; ++u) {
         const uint64_t e = wbase + (uint64_t)u * 128u + 2u * lane;
-        if (FULL || e + 1 < n) v[u] = __builtin_nontemporal_load((const d2 *)(x + e));
-        else {
-            v[u].x = e < n ? x[e] : 1.0;                              // 1.0 is never logged
-            v[u].y = 1.0;
-        }
+        v[u] = x.template pair<FULL, true>(e, n);                     // past the end: 1.0, never logged
     }
+#pragma unroll
+    for (int u = 0; u < kRows; ++u) x.template keep<FULL, true>(wbase + (uint64_t)u * 128u + 2u * lane, n, v[u]);
     uint32_t wcount = 0;
 #pragma unroll
     for (int u = 0; u < kRows; ++u) {
@@ -212,8 +211,8 @@ __device__ __forceinline__ uint32_t round_rows(const double *__restrict__ x, uin
     return wcount;
 }
 
-template <bool K0>
-__global__ __launch_bounds__(kThreads) void round_log_onepass_kernel(const double *__restrict__ x, uint64_t n,
+template <bool K0, class Src>
+__global__ __launch_bounds__(kThreads) void round_log_onepass_kernel(const Src x, uint64_t n,
                                                                 uint32_t thr, uint32_t k, float *__restrict__ y,
                                                                 uint64_t *__restrict__ st, uint32_t tiles,
                                                                 uint32_t *__restrict__ err,
@@ -300,8 +299,11 @@ bool onepass_usable(const double *x, const float *y)
     return ((uintptr_t)x % 16 == 0) && ((uintptr_t)y % 8 == 0);
 }
 
-hipError_t launch_round_log_onepass(const double *x, uint64_t n, uint32_t thr, uint32_t k, float *y, void *ws,
-                                    const LogOut &log, hipStream_t s)
+namespace {
+
+template <class Src>
+hipError_t launch_onepass_from(const Src &src, uint64_t n, uint32_t thr, uint32_t k, float *y, void *ws,
+                               const LogOut &log, hipStream_t s)
 {
     const uint32_t tiles = (uint32_t)((n + kTile - 1) / kTile);
     uint64_t *st = (uint64_t *)ws;
@@ -316,12 +318,27 @@ hipError_t launch_round_log_onepass(const double *x, uint64_t n, uint32_t thr, u
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || tiles == 0) return e;
     if (k == 0)
-        round_log_onepass_kernel<true><<<tiles + 1, kThreads, 0, s>>>(x, n, thr, k, y, st, tiles, err, log.idx, log.dir,
-                                                                      log.cap, log.count);
+        round_log_onepass_kernel<true, Src><<<tiles + 1, kThreads, 0, s>>>(src, n, thr, k, y, st, tiles, err, log.idx,
+                                                                           log.dir, log.cap, log.count);
     else
-        round_log_onepass_kernel<false><<<tiles + 1, kThreads, 0, s>>>(x, n, thr, k, y, st, tiles, err, log.idx, log.dir,
-                                                                       log.cap, log.count);
+        round_log_onepass_kernel<false, Src><<<tiles + 1, kThreads, 0, s>>>(src, n, thr, k, y, st, tiles, err, log.idx,
+                                                                            log.dir, log.cap, log.count);
     return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_round_log_onepass(const double *x, uint64_t n, uint32_t thr, uint32_t k, float *y, void *ws,
+                                    const LogOut &log, hipStream_t s)
+{
+    return launch_onepass_from(PlainSource{x}, n, thr, k, y, ws, log, s);
+}
+
+// the same pass with a layer evaluated on the fly as its source (inputs 16-byte, y 8-byte aligned)
+hipError_t launch_layer_log_onepass(const LayerArgs &g, uint64_t n, uint32_t thr, uint32_t k, float *y, void *ws,
+                                    const LogOut &log, hipStream_t s)
+{
+    return launch_onepass_from(LayerSource{g}, n, thr, k, y, ws, log, s);
 }
 
 }  // namespace vt

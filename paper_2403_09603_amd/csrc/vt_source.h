@@ -1,0 +1,98 @@
+// vt_source.h -- where the FP64 values of the streaming trainer kernels come from: a tensor in
+// memory, or an element-wise / row-wise layer evaluated on the fly so that its FP64 output never
+// goes to memory (residual add, ReLU, GELU, layer norm, softmax: the non-GEMM layers of a
+// transformer block, each an "intermediate computation" whose output the method rounds).
+#pragma once
+#include "vt_device.h"
+#include "vt_kernels.h"
+
+#include <math.h>
+
+namespace vt {
+
+typedef double src_d2 __attribute__((ext_vector_type(2)));
+
+// An FP64 tensor in memory.  pair(e) returns elements e and e + 1; past the end it returns 1.0,
+// a value that is never logged.
+struct PlainSource {
+    const double *x;
+    template <bool FULL, bool VEC>
+    __device__ __forceinline__ src_d2 pair(uint64_t e, uint64_t n) const
+    {
+        src_d2 v;
+        if (VEC && (FULL || e + 1 < n)) v = __builtin_nontemporal_load((const src_d2 *)(x + e));
+        else {
+            v.x = e < n ? x[e] : 1.0;
+            v.y = e + 1 < n ? x[e + 1] : 1.0;
+        }
+        return v;
+    }
+    template <bool FULL, bool VEC>
+    __device__ __forceinline__ void keep(uint64_t, uint64_t, src_d2) const {}
+};
+
+// One output of a layer from its input value(s); e is the output's linear index (< n).
+__device__ __forceinline__ double layer_value(const LayerArgs &g, uint32_t e, double xa, double xb)
+{
+    switch (g.op) {                                                   // wave-uniform
+    case kLayerAdd: return xa + xb;
+    case kLayerRelu: return xa > 0.0 ? xa : (xa != xa ? xa : 0.0);
+    case kLayerGeluTanh: {
+        const double x3 = xa * xa * xa;
+        const double u = 0.7978845608028654 * (xa + 0.044715 * x3);   // sqrt(2 / pi)
+        return 0.5 * xa * (1.0 + tanh(u));
+    }
+    case kLayerGeluErf: return 0.5 * xa * (1.0 + erf(xa * 0.7071067811865476));
+    case kLayerNorm: {
+        uint32_t r, c;
+        divmod_u32(e, g.cols, g.inv_cols, r, c);
+        double v = (xa - g.stat[2 * (uint64_t)r]) * g.stat[2 * (uint64_t)r + 1];
+        if (g.gamma) v = v * g.gamma[c];
+        if (g.beta) v = v + g.beta[c];
+        return v;
+    }
+    default: {                                                        // softmax
+        uint32_t r, c, seen = g.cols;
+        divmod_u32(e, g.cols, g.inv_cols, r, c);
+        if (g.period) {
+            uint32_t q, rem;
+            divmod_u32(r, g.period, g.inv_period, q, rem);
+            seen = rem + 1u < g.cols ? rem + 1u : g.cols;
+        }
+        return c < seen ? exp(g.scale * xa - g.stat[2 * (uint64_t)r]) * g.stat[2 * (uint64_t)r + 1] : 0.0;
+    }
+    }
+}
+
+struct LayerSource {
+    LayerArgs g;
+    template <bool FULL, bool VEC>
+    __device__ __forceinline__ src_d2 pair(uint64_t e, uint64_t n) const
+    {
+        const src_d2 xa = PlainSource{g.a}.template pair<FULL, VEC>(e, n);
+        src_d2 xb = {0.0, 0.0};
+        if (g.op == kLayerAdd) xb = PlainSource{g.b}.template pair<FULL, VEC>(e, n);
+        // indices past the end are clamped so that the row statistics they select exist
+        const uint32_t e0 = (uint32_t)(FULL || e < n ? e : n - 1), e1 = (uint32_t)(FULL || e + 1 < n ? e + 1 : n - 1);
+        src_d2 v;
+        v.x = layer_value(g, e0, xa.x, xb.x);
+        v.y = layer_value(g, e1, xa.y, xb.y);
+        if (!FULL) {
+            if (e >= n) v.x = 1.0;
+            if (e + 1 >= n) v.y = 1.0;
+        }
+        return v;
+    }
+    template <bool FULL, bool VEC>
+    __device__ __forceinline__ void keep(uint64_t e, uint64_t n, src_d2 v) const
+    {
+        if (!g.y64) return;
+        if (VEC && (FULL || e + 1 < n)) *(src_d2 *)(g.y64 + e) = v;
+        else {
+            if (e < n) g.y64[e] = v.x;
+            if (e + 1 < n) g.y64[e + 1] = v.y;
+        }
+    }
+};
+
+}  // namespace vt

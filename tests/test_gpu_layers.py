@@ -1,0 +1,148 @@
+"""GPU parity for the element-wise and row-wise layers fused with the trainer hook.
+
+FP64 layer outputs (debug copy) against the oracle's extended-precision evaluation within a tolerance
+derived from the arithmetic (a few FP64 roundings plus the accuracy of exp / tanh / erf, and for the
+row-wise layers the rounding of the row statistics); residual add and ReLU exactly.  FP32 outputs and
+both log formats bit-exact against the oracle's round/log of the kernel's own FP64 values.  Two
+summation orders of the row statistics stand in for two GPU types: the trainer's log replayed on the
+other order's values reproduces the trainer's FP32 outputs."""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import vt_oracle as vo
+
+pytestmark = pytest.mark.gpu
+
+ADD, RELU, GELU_TANH, GELU_ERF, NORM, SOFTMAX = range(6)
+SHAPES = [(1, 1), (7, 333), (3, 8197), (200, 768), (37, 1280)]
+
+
+@pytest.fixture(scope="module")
+def G():
+    import gpu_util
+    return gpu_util
+
+
+def _bits(y):
+    return np.ascontiguousarray(y, np.float32).view(np.uint32)
+
+
+def _dir_bits(dirw, count):
+    return np.unpackbits(np.ascontiguousarray(dirw, np.uint32).view(np.uint8), bitorder="little")[:count]
+
+
+def _hook(r, tau, b_r=32):
+    yo, io, do, co = vo.round_log(r["y64"].ravel(), tau, b_r=b_r)
+    assert r["count"] == co and np.array_equal(_bits(r["y32"].ravel()), _bits(yo))
+    if "tlog" in r:
+        assert np.array_equal(r["tlog"], vo.round_log_dense(r["y64"].ravel(), tau, b_r=b_r)[1])
+    else:
+        assert np.array_equal(r["idx"], io) and np.array_equal(_dir_bits(r["dir"], co), _dir_bits(do, co))
+
+
+def _inputs(shape, seed):
+    g = si.rng(si.seed_for(9, 100 + seed))
+    a = (g.standard_normal(shape) * 2.0).astype(np.float32).astype(np.float64)
+    b = g.standard_normal(shape).astype(np.float32).astype(np.float64)
+    if a.size > 40:
+        a.ravel()[:8] = [0.0, -0.0, 40.0, -40.0, 1e-30, -1e-30, 700.0, -700.0]
+    return a, b, g
+
+
+@pytest.mark.parametrize("dense", [False, True])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_elementwise_layers(G, shape, dense):
+    a, b, _ = _inputs(shape, shape[1])
+    tau = 2.0 ** -4
+    r = G.gpu_layer(ADD, a, b, tau=tau, dense=dense)
+    assert np.array_equal(r["y64"], vo.elementwise(vo.EW_ADD, a, b))          # one IEEE addition: exact
+    _hook(r, tau)
+    r = G.gpu_layer(RELU, a, tau=tau, dense=dense)
+    assert np.array_equal(r["y64"].view(np.uint64), vo.elementwise(vo.EW_RELU, a).view(np.uint64))
+    _hook(r, tau)
+    for op, oop in ((GELU_TANH, vo.EW_GELU_TANH), (GELU_ERF, vo.EW_GELU_ERF)):
+        r = G.gpu_layer(op, a, tau=tau, dense=dense)
+        truth = vo.elementwise(oop, a, exact=True)
+        # 0.5 x (1 + f): a handful of roundings and the function's own error, relative to |x|
+        assert np.all(np.abs(r["y64"] - truth) <= 8 * 2.0 ** -52 * np.maximum(np.abs(a), 1e-300)), op
+        _hook(r, tau)
+
+
+@pytest.mark.parametrize("dense", [False, True])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_layernorm(G, shape, dense):
+    a, _, g = _inputs(shape, 50 + shape[1])
+    a = a + 0.25
+    gamma = (g.standard_normal(shape[1]) + 1.0).astype(np.float32).astype(np.float64)
+    beta = g.standard_normal(shape[1]).astype(np.float32).astype(np.float64)
+    tau = 2.0 ** -4
+    truth = vo.layernorm(a, gamma, beta, 1e-5, order=2)
+    xhat = np.abs(vo.layernorm(a, eps=1e-5, order=2))
+    cols = shape[1]
+    # error of mean and 1/std: ~ sqrt(cols) roundings each, carried through (x - mean) rstd gamma + beta
+    bound = 2.0 ** -52 * (8 + 4 * np.sqrt(cols)) * (xhat + 1.0) * np.abs(gamma)[None, :] + 2.0 ** -52 * np.abs(truth) + 1e-300
+    res = {}
+    for variant in (0, 1):
+        r = G.gpu_layer(NORM, a, gamma=gamma, beta=beta, eps=1e-5, tau=tau, variant=variant, dense=dense)
+        assert np.all(np.abs(r["y64"] - truth) <= bound), float(np.max(np.abs(r["y64"] - truth) / bound))
+        _hook(r, tau)
+        res[variant] = r
+    again = G.gpu_layer(NORM, a, gamma=gamma, beta=beta, eps=1e-5, tau=tau, variant=0, dense=dense)
+    assert np.array_equal(again["y64"], res[0]["y64"])                         # deterministic
+    r = G.gpu_layer(NORM, a, eps=0.0, tau=tau, dense=dense)                    # no gamma, no beta
+    if cols > 1:
+        np.testing.assert_allclose(r["y64"], vo.layernorm(a, eps=0.0, order=2), rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("dense", [False, True])
+@pytest.mark.parametrize("shape,period", [((1, 1), 0), ((7, 333), 0), ((24, 200), 8), ((300, 100), 100), ((64, 1024), 0),
+                                          ((3, 8197), 0)])
+def test_softmax(G, shape, period, dense):
+    a, _, _ = _inputs(shape, 70 + shape[1])
+    a = np.clip(a, -50, 50)
+    tau, scale = 2.0 ** -4, 0.125
+    truth = vo.softmax(a, scale, period, order=2)
+    cols = shape[1]
+    bound = 2.0 ** -52 * (8 + 2 * np.sqrt(cols)) * truth + 1e-300
+    for variant in (0, 1):
+        r = G.gpu_layer(SOFTMAX, a, scale=scale, causal_period=period, tau=tau, variant=variant, dense=dense)
+        assert np.all(np.abs(r["y64"] - truth) <= bound), float(np.max(np.abs(r["y64"] - truth) / np.maximum(bound, 1e-300)))
+        assert np.all((r["y64"] == 0.0) == (truth == 0.0))                     # the mask
+        _hook(r, tau)
+
+
+def test_two_summation_orders_and_replay(G):
+    """Layer norm and softmax over long rows: the two variants differ in low bits; the threshold from
+    their statistics makes the trainer's log bring the other variant back to the trainer's outputs."""
+    g = si.rng(si.seed_for(9, 300))
+    a = g.standard_normal((512, 3072)).astype(np.float32).astype(np.float64)
+    for op, kw in ((NORM, dict(eps=1e-5)), (SOFTMAX, dict(scale=0.5))):
+        r0 = G.gpu_layer(op, a, tau=0.0, variant=0, **kw)
+        r1 = G.gpu_layer(op, a, tau=0.0, variant=1, **kw)
+        assert (r0["y64"] != r1["y64"]).mean() > 0.05
+        st = G.gpu_stats(r0["y64"], r1["y64"])
+        so = vo.threshold_stats(r0["y64"], r1["y64"])
+        assert st["n_flip"] == so["n_flip"] and st["thr_flip"] == so["thr_flip"]
+        need = max(st["thr_flip"], st["max_ulp64_diff"] + 1, 1)
+        thr = 1 << int(np.ceil(np.log2(need)))
+        assert thr <= 1 << 27
+        tau = thr * 2.0 ** -29
+        for dense in (False, True):
+            t = G.gpu_layer(op, a, tau=tau, variant=0, dense=dense, **kw)
+            if dense:
+                ya = G.gpu_round_replay_dense(r1["y64"].ravel(), t["tlog"])
+            else:
+                ya = G.gpu_round_replay(r1["y64"].ravel(), t["idx"], t["dir"])
+            assert np.array_equal(_bits(ya), _bits(t["y32"].ravel()))
+
+
+def test_rounding_amount_and_validation(G):
+    import paper_2403_09603_amd as vt
+    a, b, _ = _inputs((9, 130), 400)
+    r = G.gpu_layer(GELU_TANH, a, tau=2.0 ** -4, b_r=26)
+    _hook(r, 2.0 ** -4, b_r=26)
+    with pytest.raises(vt.VtError):
+        G.gpu_layer(ADD, a)                                                    # second addend missing
+    with pytest.raises(vt.VtError):
+        G.gpu_layer(9, a)                                                      # unknown layer
