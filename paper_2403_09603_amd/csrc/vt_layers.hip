@@ -1,12 +1,13 @@
 // vt_layers.hip -- per-row statistics of the row-wise layers (layer norm, softmax) that the fused
 // layer + trainer-hook kernels read: one wavefront per row, two sweeps over the row (the second
-// one hits the cache), FP64 throughout.
+// one hits the cache), eight loads in flight per lane, FP64 throughout.
 //
-// Summation order: lane l adds the columns l, l + 64, l + 128, ... of its row (variant 0: in
-// ascending order, variant 1: in descending order), then the 64 partial sums are combined by a
-// fixed butterfly (variant 0: strides 32, 16, ..., 1; variant 1: strides 1, 2, ..., 32).  Both
-// orders are fixed, so a given variant always returns the same bits; the two variants differ in
-// their low bits the way two GPU types do.
+// Summation order: the row is cut into chunks of 512 columns; lane l owns columns l, l + 64, ...,
+// l + 448 of each chunk and adds them to its partial sum chunk by chunk (variant 0: ascending
+// columns, variant 1: descending), then the 64 partial sums are combined by a fixed butterfly
+// (variant 0: strides 32, 16, ..., 1; variant 1: strides 1, 2, ..., 32).  Both orders are fixed, so
+// a given variant always returns the same bits; the two variants differ in their low bits the
+// way two GPU types do.
 #include "vt_device.h"
 #include "vt_kernels.h"
 
@@ -38,10 +39,28 @@ __device__ __forceinline__ double wave_max(double v)
     return v;
 }
 
-// columns this lane visits, in the variant's order: c = lane + 64 j
-__device__ __forceinline__ uint32_t nth_col(uint32_t lane, uint32_t mine, uint32_t j, int variant)
+constexpr uint32_t kInFlight = 8, kChunkCols = 64 * kInFlight;
+
+// Calls f(value) for every column c < lim of the row that belongs to this lane, in the variant's
+// order; `load` maps a column to the value to accumulate.
+template <class Load, class Fold>
+__device__ __forceinline__ void sweep(uint32_t lim, uint32_t lane, int variant, Load load, Fold fold)
 {
-    return lane + 64u * (variant ? mine - 1u - j : j);
+    const uint32_t chunks = (lim + kChunkCols - 1) / kChunkCols;
+    for (uint32_t i = 0; i < chunks; ++i) {
+        const uint32_t c0 = (variant ? chunks - 1 - i : i) * kChunkCols + lane;
+        double v[kInFlight];
+        bool in[kInFlight];
+#pragma unroll
+        for (uint32_t u = 0; u < kInFlight; ++u) {
+            const uint32_t c = c0 + 64u * (variant ? kInFlight - 1 - u : u);
+            in[u] = c < lim;
+            v[u] = in[u] ? load(c) : 0.0;
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < kInFlight; ++u)
+            if (in[u]) fold(v[u]);
+    }
 }
 
 __global__ __launch_bounds__(256) void layernorm_stats_kernel(const double *__restrict__ x, uint32_t rows, uint32_t cols,
@@ -50,15 +69,11 @@ __global__ __launch_bounds__(256) void layernorm_stats_kernel(const double *__re
     const uint32_t lane = threadIdx.x & 63u, r = blockIdx.x * 4u + (threadIdx.x >> 6);
     if (r >= rows) return;
     const double *xr = x + (uint64_t)r * cols;
-    const uint32_t mine = cols > lane ? (cols - lane + 63u) / 64u : 0u;
     double s = 0.0;
-    for (uint32_t j = 0; j < mine; ++j) s = s + xr[nth_col(lane, mine, j, variant)];
+    sweep(cols, lane, variant, [&](uint32_t c) { return xr[c]; }, [&](double v) { s = s + v; });
     const double mean = wave_add(s, variant) / (double)cols;
     double q = 0.0;
-    for (uint32_t j = 0; j < mine; ++j) {
-        const double d = xr[nth_col(lane, mine, j, variant)] - mean;
-        q = q + d * d;
-    }
+    sweep(cols, lane, variant, [&](uint32_t c) { return xr[c]; }, [&](double v) { const double d = v - mean; q = q + d * d; });
     const double rstd = 1.0 / sqrt(wave_add(q, variant) / (double)cols + eps);
     if (lane == 0) {
         stat[2 * (uint64_t)r] = mean;
@@ -75,15 +90,11 @@ __global__ __launch_bounds__(256) void softmax_stats_kernel(const double *__rest
     const double *xr = x + (uint64_t)r * cols;
     uint32_t seen = cols;                                           // columns 0 .. seen - 1 are visible
     if (period) seen = r % period + 1u < cols ? r % period + 1u : cols;
-    const uint32_t mine = seen > lane ? (seen - lane + 63u) / 64u : 0u;
     double m = -INFINITY;
-    for (uint32_t j = 0; j < mine; ++j) {
-        const double z = scale * xr[lane + 64u * j];
-        m = z > m ? z : m;
-    }
+    sweep(seen, lane, 0, [&](uint32_t c) { return scale * xr[c]; }, [&](double z) { m = z > m ? z : m; });
     m = wave_max(m);
     double s = 0.0;
-    for (uint32_t j = 0; j < mine; ++j) s = s + exp(scale * xr[nth_col(lane, mine, j, variant)] - m);
+    sweep(seen, lane, variant, [&](uint32_t c) { return xr[c]; }, [&](double v) { s = s + exp(scale * v - m); });
     const double inv = 1.0 / wave_add(s, variant);
     if (lane == 0) {
         stat[2 * (uint64_t)r] = m;

@@ -20,6 +20,8 @@
 #include "vt_kernels.h"
 #include "vt_source.h"
 
+#include <type_traits>
+
 namespace vt {
 
 namespace {
@@ -265,8 +267,10 @@ hipError_t launch_dense_from(const Src &src, bool vec, uint64_t n, uint32_t thr,
     const dim3 grid((uint32_t)blocks), block(256);
     if (vec && k == 0) round_log_dense_kernel<true, true, Src><<<grid, block, 0, s>>>(src, n, thr, k, y, tlog, slots);
     else if (vec) round_log_dense_kernel<true, false, Src><<<grid, block, 0, s>>>(src, n, thr, k, y, tlog, slots);
-    else if (k == 0) round_log_dense_kernel<false, true, Src><<<grid, block, 0, s>>>(src, n, thr, k, y, tlog, slots);
-    else round_log_dense_kernel<false, false, Src><<<grid, block, 0, s>>>(src, n, thr, k, y, tlog, slots);
+    else if constexpr (std::is_same<Src, PlainSource>::value) {     // misaligned tensors: scalar accesses
+        if (k == 0) round_log_dense_kernel<false, true, Src><<<grid, block, 0, s>>>(src, n, thr, k, y, tlog, slots);
+        else round_log_dense_kernel<false, false, Src><<<grid, block, 0, s>>>(src, n, thr, k, y, tlog, slots);
+    } else return hipErrorInvalidValue;
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && slots) {
         sum_slots_kernel<<<1, kSlots, 0, s>>>(slots, n_logged);
@@ -288,7 +292,15 @@ hipError_t launch_round_log_dense(const double *x, uint64_t n, uint32_t thr, uin
 hipError_t launch_layer_log_dense(const LayerArgs &g, uint64_t n, uint32_t thr, uint32_t k, float *y, uint8_t *tlog,
                                   uint64_t *n_logged, uint64_t *slots, hipStream_t s)
 {
-    return launch_dense_from(LayerSource{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
+    switch (g.op) {                                              // one specialised kernel per layer
+    case kLayerAdd: return launch_dense_from(LayerSource<kLayerAdd>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
+    case kLayerRelu: return launch_dense_from(LayerSource<kLayerRelu>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
+    case kLayerGeluTanh: return launch_dense_from(LayerSource<kLayerGeluTanh>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
+    case kLayerGeluErf: return launch_dense_from(LayerSource<kLayerGeluErf>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
+    case kLayerNorm: return launch_dense_from(LayerSource<kLayerNorm>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
+    case kLayerSoftmax: return launch_dense_from(LayerSource<kLayerSoftmax>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 hipError_t launch_replay_dense(const double *x, uint64_t n, const uint8_t *tlog, uint32_t k, float *y, hipStream_t s)

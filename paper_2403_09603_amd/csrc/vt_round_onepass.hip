@@ -338,7 +338,15 @@ hipError_t launch_round_log_onepass(const double *x, uint64_t n, uint32_t thr, u
 hipError_t launch_layer_log_onepass(const LayerArgs &g, uint64_t n, uint32_t thr, uint32_t k, float *y, void *ws,
                                     const LogOut &log, hipStream_t s)
 {
-    return launch_onepass_from(LayerSource{g}, n, thr, k, y, ws, log, s);
+    switch (g.op) {                                              // one specialised kernel per layer
+    case kLayerAdd: return launch_onepass_from(LayerSource<kLayerAdd>{g}, n, thr, k, y, ws, log, s);
+    case kLayerRelu: return launch_onepass_from(LayerSource<kLayerRelu>{g}, n, thr, k, y, ws, log, s);
+    case kLayerGeluTanh: return launch_onepass_from(LayerSource<kLayerGeluTanh>{g}, n, thr, k, y, ws, log, s);
+    case kLayerGeluErf: return launch_onepass_from(LayerSource<kLayerGeluErf>{g}, n, thr, k, y, ws, log, s);
+    case kLayerNorm: return launch_onepass_from(LayerSource<kLayerNorm>{g}, n, thr, k, y, ws, log, s);
+    case kLayerSoftmax: return launch_onepass_from(LayerSource<kLayerSoftmax>{g}, n, thr, k, y, ws, log, s);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace vt

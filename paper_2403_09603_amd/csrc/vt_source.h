@@ -32,15 +32,18 @@ struct PlainSource {
 };
 
 // One output of a layer from its input value(s); e is the output's linear index (< n).
+template <int OP>
 __device__ __forceinline__ double layer_value(const LayerArgs &g, uint32_t e, double xa, double xb)
 {
-    switch (g.op) {                                                   // wave-uniform
+    switch (OP) {                                                     // compile-time
     case kLayerAdd: return xa + xb;
     case kLayerRelu: return xa > 0.0 ? xa : (xa != xa ? xa : 0.0);
     case kLayerGeluTanh: {
+        // x/2 (1 + tanh u) = x / (1 + exp(-2u)): the same function with one exponential, no
+        // cancellation anywhere, and the right limits (0 for very negative x, x for large x)
         const double x3 = xa * xa * xa;
         const double u = 0.7978845608028654 * (xa + 0.044715 * x3);   // sqrt(2 / pi)
-        return 0.5 * xa * (1.0 + tanh(u));
+        return xa / (1.0 + exp(-2.0 * u));
     }
     case kLayerGeluErf: return 0.5 * xa * (1.0 + erf(xa * 0.7071067811865476));
     case kLayerNorm: {
@@ -64,19 +67,54 @@ __device__ __forceinline__ double layer_value(const LayerArgs &g, uint32_t e, do
     }
 }
 
+// One output of a row-wise layer from its row statistics st = (mean, 1/std) or (max, 1/sum).
+template <int OP>
+__device__ __forceinline__ double row_value(const LayerArgs &g, uint32_t r, uint32_t c, double xa, src_d2 st)
+{
+    if (OP == kLayerNorm) {
+        double v = (xa - st.x) * st.y;
+        if (g.gamma) v = v * g.gamma[c];
+        if (g.beta) v = v + g.beta[c];
+        return v;
+    }
+    uint32_t seen = g.cols;
+    if (g.period) {
+        uint32_t q, rem;
+        divmod_u32(r, g.period, g.inv_period, q, rem);
+        seen = rem + 1u < g.cols ? rem + 1u : g.cols;
+    }
+    return c < seen ? exp(g.scale * xa - st.x) * st.y : 0.0;
+}
+
+template <int OP>
 struct LayerSource {
     LayerArgs g;
     template <bool FULL, bool VEC>
     __device__ __forceinline__ src_d2 pair(uint64_t e, uint64_t n) const
     {
         const src_d2 xa = PlainSource{g.a}.template pair<FULL, VEC>(e, n);
+        if (FULL && OP >= kLayerNorm) {
+            // both outputs exist: split the index once, one 16-byte load of the row statistics
+            // (a second one only when the pair straddles two rows)
+            uint32_t r0, c0;
+            divmod_u32((uint32_t)e, g.cols, g.inv_cols, r0, c0);
+            const bool wrap = c0 + 1u == g.cols;
+            const uint32_t r1 = wrap ? r0 + 1u : r0, c1 = wrap ? 0u : c0 + 1u;
+            const src_d2 s0 = *(const src_d2 *)(g.stat + 2 * (uint64_t)r0);
+            src_d2 s1 = s0;
+            if (wrap) s1 = *(const src_d2 *)(g.stat + 2 * (uint64_t)r1);
+            src_d2 v;
+            v.x = row_value<OP>(g, r0, c0, xa.x, s0);
+            v.y = row_value<OP>(g, r1, c1, xa.y, s1);
+            return v;
+        }
         src_d2 xb = {0.0, 0.0};
-        if (g.op == kLayerAdd) xb = PlainSource{g.b}.template pair<FULL, VEC>(e, n);
+        if (OP == kLayerAdd) xb = PlainSource{g.b}.template pair<FULL, VEC>(e, n);
         // indices past the end are clamped so that the row statistics they select exist
         const uint32_t e0 = (uint32_t)(FULL || e < n ? e : n - 1), e1 = (uint32_t)(FULL || e + 1 < n ? e + 1 : n - 1);
         src_d2 v;
-        v.x = layer_value(g, e0, xa.x, xb.x);
-        v.y = layer_value(g, e1, xa.y, xb.y);
+        v.x = layer_value<OP>(g, e0, xa.x, xb.x);
+        v.y = layer_value<OP>(g, e1, xa.y, xb.y);
         if (!FULL) {
             if (e >= n) v.x = 1.0;
             if (e + 1 >= n) v.y = 1.0;
