@@ -143,6 +143,90 @@ def _audited_elementwise(P, name, x64, tau=2.0 ** -29):
     return y
 
 
+def _audited_layer(P, name, op, a, b, gamma, beta, rows, cols, **kw):
+    """One fused element-wise / row-wise layer for both parties (two summation orders of the row
+    statistics); FP64 values against the oracle, hook outputs bit-exact, per-layer threshold, replay."""
+    torch, vt = P.torch, P.vt
+    n = rows * cols
+
+    def run(variant, tau):
+        y = torch.empty(n, dtype=torch.float32, device="cuda")
+        y64 = torch.empty(n, dtype=torch.float64, device="cuda")
+        log = vt.alloc_log(n)
+        ws = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_LAYER_ROUND_LOG, rows, cols))
+        vt.vt_layer_f64_round_log(op, a, b, gamma, beta, rows, cols, y, y64, variant, tau, log, ws, **kw)
+        torch.cuda.synchronize()
+        return y, y64, log, int(log.count.item())
+
+    _, t64, _, _ = run(0, 0.0)
+    _, a64, _, _ = run(1, 0.0)
+    ha = a.cpu().numpy().reshape(rows, cols)
+    if op == vt.VT_LAYER_NORM:
+        truth = vo.layernorm(ha, gamma.cpu().numpy() if gamma is not None else None,
+                             beta.cpu().numpy() if beta is not None else None, kw.get("eps", 1e-5), order=2)
+    elif op == vt.VT_LAYER_SOFTMAX:
+        truth = vo.softmax(ha, kw.get("scale", 1.0), kw.get("causal_period", 0), order=2)
+    elif op == vt.VT_LAYER_ADD:
+        truth = vo.elementwise(vo.EW_ADD, ha, b.cpu().numpy().reshape(rows, cols), exact=True)
+    else:
+        truth = vo.elementwise(vo.EW_GELU_TANH, ha, exact=True)
+    tol = 2.0 ** -52 * (8 + 4 * np.sqrt(cols)) * (np.abs(truth) + (1.0 if op == vt.VT_LAYER_NORM else 0.0) + np.abs(ha) * (op == vt.VT_LAYER_GELU_TANH)) + 1e-300
+    for v64 in (t64, a64):
+        assert np.all(np.abs(v64.cpu().numpy().reshape(rows, cols) - truth) <= tol), name
+    st = P.stats(t64, a64)
+    need = max(st["thr_flip"], st["max_ulp64_diff"] + 1, 1)
+    thr = 1 << int(np.ceil(np.log2(need)))
+    assert thr <= 1 << 27, (name, need)
+    tau = thr * 2.0 ** -29
+    y, t64b, log, cnt = run(0, tau)
+    assert torch.equal(t64b, t64), name
+    yo, io, do, co = vo.round_log(t64.cpu().numpy(), tau)
+    assert cnt == co and np.array_equal(_bits(y.cpu().numpy()), _bits(yo)), name
+    assert np.array_equal(log.idx.cpu().numpy().view(np.uint32)[:cnt], io), name
+    assert np.array_equal(_bits(P.replay(a64, log, cnt).cpu().numpy()), _bits(yo)), name     # auditor == trainer
+    return y
+
+
+def test_gpt2_block_stream_through_the_library_alone():
+    """The same block with its layer norms, softmax, GELU and residual additions as fused layer +
+    hook calls: no FP64 intermediate of the block is produced outside the library."""
+    import torch
+    P = Party()
+    vt = P.vt
+    T = 136
+    g = si.rng(si.seed_for(3, 2))
+
+    def param(shape, sigma=0.02, shift=0.0):
+        return torch.from_numpy((g.standard_normal(shape) * sigma + shift).astype(np.float32).astype(np.float64)).cuda()
+
+    def f64(t32):
+        return t32.to(torch.float64)
+
+    x = param((T, D), 1.0).reshape(-1)
+    g1, be1, g2, be2 = param(D, 0.1, 1.0), param(D, 0.1), param(D, 0.1, 1.0), param(D, 0.1)
+    Wqkv, bqkv, Wo, bo = param((D, 3 * D)), param(3 * D), param((D, D)), param(D)
+    W1, b1, W2, b2 = param((D, 4 * D)), param(4 * D), param((4 * D, D)), param(D)
+    h = _audited_layer(P, "ln1", vt.VT_LAYER_NORM, x, None, g1, be1, T, D, eps=1e-5)
+    qkv32, _ = _audited_gemm(P, "qkv", f64(h), D, 0, Wqkv.reshape(-1), 3 * D, 0, bqkv, T, 3 * D, D, 1, 3 * D, 0, T * 3 * D)
+    qkv = f64(qkv32)
+    s32, _ = _audited_gemm(P, "scores", qkv, 3 * D, DH, qkv[D:], 3 * D, DH, None, T, T, DH, H, T, T * T, H * T * T,
+                           transB=True, alpha=0.125)
+    # rows are (head, token): row r attends to columns <= r mod T
+    p32 = _audited_layer(P, "softmax", vt.VT_LAYER_SOFTMAX, f64(s32), None, None, None, H * T, T, scale=1.0, causal_period=T)
+    o32, _ = _audited_gemm(P, "pv", f64(p32), T, T * T, qkv[2 * D:], 3 * D, DH, None, T, DH, T, H, D, DH, T * D)
+    a32, _ = _audited_gemm(P, "attn_out", f64(o32), D, 0, Wo.reshape(-1), D, 0, bo, T, D, D, 1, D, 0, T * D)
+    x1 = _audited_layer(P, "residual1", vt.VT_LAYER_ADD, x, f64(a32), None, None, T, D)
+    h2 = _audited_layer(P, "ln2", vt.VT_LAYER_NORM, f64(x1), None, g2, be2, T, D, eps=1e-5)
+    u32_, _ = _audited_gemm(P, "mlp_up", f64(h2), D, 0, W1.reshape(-1), 4 * D, 0, b1, T, 4 * D, D, 1, 4 * D, 0, T * 4 * D)
+    act = _audited_layer(P, "gelu", vt.VT_LAYER_GELU_TANH, f64(u32_), None, None, None, T, 4 * D)
+    d32, _ = _audited_gemm(P, "mlp_down", f64(act), 4 * D, 0, W2.reshape(-1), D, 0, b2, T, D, 4 * D, 1, D, 0, T * D)
+    out = _audited_layer(P, "residual2", vt.VT_LAYER_ADD, f64(x1), f64(d32), None, None, T, D)
+    assert torch.isfinite(out).all()
+    # the causal mask reached the probabilities: strictly upper triangle is exactly zero
+    pm = p32.reshape(H, T, T)
+    assert (pm.triu(1) == 0).all() and (pm.diagonal(dim1=1, dim2=2) > 0).all()
+
+
 @pytest.mark.parametrize("T", [200])
 def test_gpt2_block_stream(T):
     import torch
