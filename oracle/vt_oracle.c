@@ -433,6 +433,45 @@ int vto_layernorm_f64(const double *x, int64_t rows, int64_t cols, const double 
     return VTO_OK;
 }
 
+int vto_batchnorm_f64(const double *x, int64_t rows, int64_t cols, const double *gamma, const double *beta,
+                      double eps, int relu, double *y, int order)
+{
+    if (rows < 0 || cols < 0 || order < 0 || order > 2 || (rows * cols && (!x || !y))) return VTO_ERR_INVALID_ARG;
+    for (int64_t c = 0; c < cols; ++c) {
+        long double meanl = 0.0L, rstdl = 0.0L;
+        double mean = 0.0, rstd = 0.0;
+        if (order == 2) {
+            long double s = 0.0L, q = 0.0L;
+            for (int64_t r = 0; r < rows; ++r) s += (long double)x[r * cols + c];
+            meanl = s / (long double)rows;
+            for (int64_t r = 0; r < rows; ++r) { long double d = (long double)x[r * cols + c] - meanl; q += d * d; }
+            rstdl = 1.0L / sqrtl(q / (long double)rows + (long double)eps);
+        } else {
+            double s = 0.0, q = 0.0;
+            for (int64_t t = 0; t < rows; ++t) s = s + x[(order ? rows - 1 - t : t) * cols + c];
+            mean = s / (double)rows;
+            for (int64_t t = 0; t < rows; ++t) { double d = x[(order ? rows - 1 - t : t) * cols + c] - mean; q = q + d * d; }
+            rstd = 1.0 / sqrt(q / (double)rows + eps);
+        }
+        for (int64_t r = 0; r < rows; ++r) {
+            double v;
+            if (order == 2) {
+                long double w = ((long double)x[r * cols + c] - meanl) * rstdl;
+                if (gamma) w *= (long double)gamma[c];
+                if (beta) w += (long double)beta[c];
+                v = (double)w;
+            } else {
+                v = (x[r * cols + c] - mean) * rstd;
+                if (gamma) v = v * gamma[c];
+                if (beta) v = v + beta[c];
+            }
+            if (relu) v = isnan(v) ? v : (v > 0.0 ? v : 0.0);
+            y[r * cols + c] = v;
+        }
+    }
+    return VTO_OK;
+}
+
 int vto_softmax_f64(const double *x, int64_t rows, int64_t cols, double scale, int64_t causal_period,
                     double *y, int order)
 {

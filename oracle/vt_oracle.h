@@ -155,6 +155,13 @@ int vto_elementwise_f64(int op, const double *a, const double *b, uint64_t n, do
 int vto_layernorm_f64(const double *x, int64_t rows, int64_t cols, const double *gamma, const double *beta,
                       double eps, double *y, int order);
 
+/* Batch normalisation in training mode (Table "thresholds" lists it): per column (channel)
+ * mean = sum over rows / rows, var = sum (x - mean)^2 / rows (biased), y = (x - mean) /
+ * sqrt(var + eps) * gamma + beta, followed by ReLU when relu != 0.  Rows are the N*H*W positions
+ * of a channels-last activation.  order 0: sums over ascending rows, 1: descending, 2: long double. */
+int vto_batchnorm_f64(const double *x, int64_t rows, int64_t cols, const double *gamma, const double *beta,
+                      double eps, int relu, double *y, int order);
+
 /* Softmax of each row of z = scale * x: y_c = exp(z_c - max z) / sum exp(z - max z).  With
  * causal_period T > 0, row r sees only columns c <= r mod T (attention over a sequence of T tokens,
  * rows stacked head after head); the other outputs are 0.  order as above. */

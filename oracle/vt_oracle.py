@@ -91,6 +91,8 @@ def lib():
         L.vto_elementwise_f64.argtypes = [C.c_int, dp, dp, C.c_uint64, dp, C.c_int]
         L.vto_layernorm_f64.restype = C.c_int
         L.vto_layernorm_f64.argtypes = [dp, C.c_int64, C.c_int64, dp, dp, C.c_double, dp, C.c_int]
+        L.vto_batchnorm_f64.restype = C.c_int
+        L.vto_batchnorm_f64.argtypes = [dp, C.c_int64, C.c_int64, dp, dp, C.c_double, C.c_int, dp, C.c_int]
         L.vto_softmax_f64.restype = C.c_int
         L.vto_softmax_f64.argtypes = [dp, C.c_int64, C.c_int64, C.c_double, C.c_int64, dp, C.c_int]
         L.vto_conv2d_out_size.restype = C.c_int
@@ -296,6 +298,20 @@ def layernorm(x, gamma=None, beta=None, eps: float = 1e-5, order: int = 0):
                                  _p(beta, C.c_double), float(eps), _p(y, C.c_double), int(order))
     if rc != 0:
         raise ValueError(f"vto_layernorm_f64: error {rc}")
+    return y
+
+
+def batchnorm(x, gamma=None, beta=None, eps: float = 1e-5, relu: bool = False, order: int = 0):
+    """x: (rows, channels); statistics per channel over the rows (training mode)."""
+    x = _f64(x)
+    assert x.ndim == 2
+    gamma = _f64(gamma) if gamma is not None else None
+    beta = _f64(beta) if beta is not None else None
+    y = np.empty(x.shape, np.float64)
+    rc = lib().vto_batchnorm_f64(_p(x, C.c_double), x.shape[0], x.shape[1], _p(gamma, C.c_double),
+                                 _p(beta, C.c_double), float(eps), int(bool(relu)), _p(y, C.c_double), int(order))
+    if rc != 0:
+        raise ValueError(f"vto_batchnorm_f64: error {rc}")
     return y
 
 

@@ -94,6 +94,38 @@ def test_softmax_against_pytorch_and_structure(rows, cols, period):
         assert got[0] == math.exp(scale * float(x[r, 0]) - m) * (1.0 / s)
 
 
+@pytest.mark.parametrize("rows,cols", [(2, 1), (9, 3), (640, 64), (1000, 7)])
+def test_batchnorm_against_pytorch_and_summation_order(rows, cols):
+    x = _x((rows, cols), 30 + cols, 2.0) + 0.5
+    gamma, beta = _x(cols, 31) + 1.0, _x(cols, 32)
+    xt = torch.from_numpy(x.T.copy()).reshape(1, cols, rows)                      # (N, C, L): statistics over N and L
+    want = F.batch_norm(xt, None, None, torch.from_numpy(gamma), torch.from_numpy(beta), True, 0.0, 1e-5)
+    want = want.reshape(cols, rows).T.numpy()
+    for order in (0, 1, 2):
+        got = vo.batchnorm(x, gamma, beta, 1e-5, order=order)
+        np.testing.assert_allclose(got, want, rtol=0, atol=1e-12 * (np.abs(want).max() + 1.0))
+        np.testing.assert_array_equal(vo.batchnorm(x, gamma, beta, 1e-5, relu=True, order=order), np.maximum(got, 0.0))
+    plain = vo.batchnorm(x, eps=0.0, order=2)
+    if rows > 1:
+        np.testing.assert_allclose(plain.mean(axis=0), 0.0, atol=1e-13)
+        np.testing.assert_allclose((plain ** 2).mean(axis=0), 1.0, atol=1e-12)
+    for order in (0, 1):                                                          # the stated order, one channel
+        seq = list(range(rows)) if order == 0 else list(range(rows - 1, -1, -1))
+        c = cols - 1
+        s = 0.0
+        for r in seq:
+            s = s + float(x[r, c])
+        mean = s / rows
+        q = 0.0
+        for r in seq:
+            d = float(x[r, c]) - mean
+            q = q + d * d
+        rstd = 1.0 / math.sqrt(q / rows + 1e-5)
+        got = vo.batchnorm(x, gamma, beta, 1e-5, order=order)
+        for r in (0, rows // 2, rows - 1):
+            assert got[r, c] == (float(x[r, c]) - mean) * rstd * float(gamma[c]) + float(beta[c])
+
+
 def test_invalid_arguments():
     with pytest.raises(ValueError):
         vo.elementwise(7, np.ones(3))
