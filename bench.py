@@ -249,14 +249,19 @@ def main():
         rows_l, cols_l = n // 1024, 1024
         wsl = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_LAYER_ROUND_LOG, rows_l, cols_l))
         layers = {}
-        for lname, lop, kw in (("gelu_tanh", vt.VT_LAYER_GELU_TANH, {}), ("layer_norm", vt.VT_LAYER_NORM, {"eps": 1e-5}),
-                               ("softmax", vt.VT_LAYER_SOFTMAX, {"scale": 0.125})):
-            l_call, _ = timed(lambda: vt.vt_layer_f64_round_log(lop, xd, None, None, None, rows_l, cols_l, y1, None, 0,
-                                                                tau_s, dlog, wsl, **kw), reps=5)
-            # row-wise layers read the input twice (statistics, then the fused pass)
-            lbytes = n * (8 + 4 + 0.2 + (8 if lop in (vt.VT_LAYER_NORM, vt.VT_LAYER_SOFTMAX) else 0))
+        wsb = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_LAYER_ROUND_LOG, n // 64, 64))
+        for lname, lop, shape, reads, kw in (
+                ("gelu_tanh", vt.VT_LAYER_GELU_TANH, (rows_l, cols_l), 1, {}),
+                ("layer_norm", vt.VT_LAYER_NORM, (rows_l, cols_l), 2, {"eps": 1e-5}),
+                ("softmax", vt.VT_LAYER_SOFTMAX, (rows_l, cols_l), 2, {"scale": 0.125}),
+                ("batch_norm_relu_64ch", vt.VT_LAYER_BATCHNORM_RELU, (n // 64, 64), 3, {"eps": 1e-5})):
+            wsx = wsb if shape[1] == 64 else wsl
+            l_call, _ = timed(lambda: vt.vt_layer_f64_round_log(lop, xd, None, None, None, shape[0], shape[1], y1, None, 0,
+                                                                tau_s, dlog, wsx, **kw), reps=5)
+            # statistics sweeps read the input again before the fused pass does
+            lbytes = n * (8 * reads + 4 + 0.2)
             layers[lname] = {"ms": round(l_call, 4), "GBs": round(lbytes / l_call * 1e-6, 1)}
-        del wsl
+        del wsl, wsb
         rho = cnt / n
         bytes_rl = n * (8 + 4 + rho * 4.125)
         out["standalone"] = {

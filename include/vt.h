@@ -221,10 +221,13 @@ int vt_conv2d_gemm_shape(const vt_conv2d *d, int64_t Cout, int mode, int64_t *M,
  *                       gamma, beta per column, either may be NULL
  *   VT_LAYER_SOFTMAX    per row of z = scale * a: y = exp(z - max z) / sum exp(z - max z); with
  *                       causal_period T > 0 row r sees only columns c <= r mod T, the rest are 0
+ *   VT_LAYER_BATCHNORM  training mode, per column (channel) over all rows (the N H W positions of a
+ *                       channels-last activation): y = (a - mean) / sqrt(var + eps) * gamma + beta,
+ *                       biased variance; VT_LAYER_BATCHNORM_RELU applies ReLU to that
  *
  *   a, b         device, rows x cols FP64, dense, 16-byte aligned
  *   y            device, rows x cols FP32, 8-byte aligned; y64_debug: optional FP64 copy of the layer
- *   variant      summation order of the row statistics (0 or 1), as two GPU types would differ
+ *   variant      summation order of the row / column statistics (0 or 1), as two GPU types would differ
  *   rows * cols must be < 2^32.  ws: vt_workspace_bytes(VT_OP_LAYER_ROUND_LOG, rows, cols, 0, 1).
  */
 #define VT_LAYER_ADD 0
@@ -233,13 +236,15 @@ int vt_conv2d_gemm_shape(const vt_conv2d *d, int64_t Cout, int mode, int64_t *M,
 #define VT_LAYER_GELU_ERF 3
 #define VT_LAYER_NORM 4
 #define VT_LAYER_SOFTMAX 5
+#define VT_LAYER_BATCHNORM 6
+#define VT_LAYER_BATCHNORM_RELU 7
 
 typedef struct vt_layer {
     int32_t op;                      /* VT_LAYER_* */
     const double *a, *b;             /* b: second addend of VT_LAYER_ADD, else NULL */
-    const double *gamma, *beta;      /* VT_LAYER_NORM */
+    const double *gamma, *beta;      /* VT_LAYER_NORM, VT_LAYER_BATCHNORM* */
     int64_t rows, cols;
-    double eps;                      /* VT_LAYER_NORM */
+    double eps;                      /* VT_LAYER_NORM, VT_LAYER_BATCHNORM* */
     double scale;                    /* VT_LAYER_SOFTMAX */
     int64_t causal_period;           /* VT_LAYER_SOFTMAX, 0 = no mask */
 } vt_layer;

@@ -19,6 +19,7 @@ VT_OP_ROUND_LOG, VT_OP_ROUND_REPLAY, VT_OP_GEMM_ROUND_LOG, VT_OP_THRESHOLD_STATS
 VT_CONV_FORWARD, VT_CONV_WEIGHT_GRAD = 0, 1
 VT_OP_LAYER_ROUND_LOG = 5
 VT_LAYER_ADD, VT_LAYER_RELU, VT_LAYER_GELU_TANH, VT_LAYER_GELU_ERF, VT_LAYER_NORM, VT_LAYER_SOFTMAX = 0, 1, 2, 3, 4, 5
+VT_LAYER_BATCHNORM, VT_LAYER_BATCHNORM_RELU = 6, 7
 
 
 class VtError(RuntimeError):

@@ -172,7 +172,7 @@ size_t vt_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int64_t batch
     switch (op) {
     case VT_OP_ROUND_LOG: return round_log_bytes((uint64_t)M * (uint64_t)N * (uint64_t)batch);
     case VT_OP_LAYER_ROUND_LOG:
-        return round_log_bytes((uint64_t)M * (uint64_t)N * (uint64_t)batch) + vt::layer_stat_bytes((uint64_t)M * (uint64_t)batch);
+        return round_log_bytes((uint64_t)M * (uint64_t)N * (uint64_t)batch) + vt::layer_stat_bytes((uint64_t)M * (uint64_t)batch, (uint64_t)N);
     case VT_OP_GEMM_ROUND_LOG_BR:
         return vt::planes_bytes((uint64_t)M * (uint64_t)batch, (uint64_t)N) + vt::gemm_split_bytes(M, N, batch, max_splits(M, N, K, batch)) +
                round_log_bytes((uint64_t)M * (uint64_t)N * (uint64_t)batch);
@@ -316,7 +316,7 @@ int vt_layer_f64_round_log(const vt_layer *L, float *y, double *y64_debug, int v
 {
     const uint32_t thr = vt_thr_from_tau(tau_ulp);
     if (thr == 0xFFFFFFFFu || !log_ok(log) || !L || variant < 0 || variant > 1) return VT_ERR_INVALID_ARG;
-    if (L->op < VT_LAYER_ADD || L->op > VT_LAYER_SOFTMAX || L->rows < 0 || L->cols < 0 || L->causal_period < 0)
+    if (L->op < VT_LAYER_ADD || L->op > VT_LAYER_BATCHNORM_RELU || L->rows < 0 || L->cols < 0 || L->causal_period < 0)
         return VT_ERR_INVALID_ARG;
     if ((unsigned __int128)L->rows * (unsigned __int128)L->cols >= ((unsigned __int128)1 << 32)) return VT_ERR_INVALID_ARG;
     if (L->causal_period >= ((int64_t)1 << 32)) return VT_ERR_INVALID_ARG;
@@ -326,15 +326,17 @@ int vt_layer_f64_round_log(const vt_layer *L, float *y, double *y64_debug, int v
         if (L->op == VT_LAYER_ADD && (!L->b || !aligned(L->b, 16))) return VT_ERR_INVALID_ARG;
         if ((L->gamma && !aligned(L->gamma, 8)) || (L->beta && !aligned(L->beta, 8))) return VT_ERR_INVALID_ARG;
         if (y64_debug && !aligned(y64_debug, 16)) return VT_ERR_INVALID_ARG;
-        if (L->op == VT_LAYER_NORM && !(L->eps >= 0.0)) return VT_ERR_INVALID_ARG;
+        if ((L->op == VT_LAYER_NORM || L->op >= VT_LAYER_BATCHNORM) && !(L->eps >= 0.0)) return VT_ERR_INVALID_ARG;
     }
     const size_t rl = round_log_bytes(n);
-    if (!ws || ws_bytes < rl + vt::layer_stat_bytes((uint64_t)L->rows) || !aligned(ws, 256)) return VT_ERR_WORKSPACE;
+    if (!ws || ws_bytes < rl + vt::layer_stat_bytes((uint64_t)L->rows, (uint64_t)L->cols) || !aligned(ws, 256))
+        return VT_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)hip_stream;
     vt::LayerArgs g;
     g.op = L->op; g.a = L->a; g.b = L->b;
-    g.gamma = L->op == VT_LAYER_NORM ? L->gamma : nullptr;
-    g.beta = L->op == VT_LAYER_NORM ? L->beta : nullptr;
+    const bool affine = L->op == VT_LAYER_NORM || L->op >= VT_LAYER_BATCHNORM;
+    g.gamma = affine ? L->gamma : nullptr;
+    g.beta = affine ? L->beta : nullptr;
     g.stat = (const double *)((char *)ws + rl);
     g.y64 = y64_debug;
     g.cols = (uint32_t)(L->cols > 0 ? L->cols : 1);

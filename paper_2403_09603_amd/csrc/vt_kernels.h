@@ -63,13 +63,15 @@ hipError_t launch_planes_to_dense(const Planes &pl, uint64_t rows, uint8_t *tlog
 
 // ---- element-wise and row-wise layers fused with the trainer hook -----------------------------
 // Layer selectors (the public VT_LAYER_* values).
-enum { kLayerAdd = 0, kLayerRelu = 1, kLayerGeluTanh = 2, kLayerGeluErf = 3, kLayerNorm = 4, kLayerSoftmax = 5 };
+enum { kLayerAdd = 0, kLayerRelu = 1, kLayerGeluTanh = 2, kLayerGeluErf = 3, kLayerNorm = 4, kLayerSoftmax = 5,
+       kLayerBatchNorm = 6, kLayerBatchNormRelu = 7 };
 
 struct LayerArgs {
     int op;
     const double *a, *b;          // inputs (b: second addend of the residual add)
     const double *gamma, *beta;   // layer norm: per-column scale and shift, either may be null
-    const double *stat;           // per row: (mean, 1/std) for layer norm, (max, 1/sum) for softmax
+    const double *stat;           // per row: (mean, 1/std) for layer norm, (max, 1/sum) for softmax;
+                                  // per column: (mean, 1/std) for batch norm
     double *y64;                  // optional FP64 copy of the layer's output
     uint32_t cols;
     double inv_cols;              // 1 / cols (index split by reciprocal multiply + correction)
@@ -78,8 +80,9 @@ struct LayerArgs {
     double inv_period;
 };
 
-size_t layer_stat_bytes(uint64_t rows);
-// per-row statistics of layer norm / softmax into g.stat (no-op for the element-wise layers);
+size_t layer_stat_bytes(uint64_t rows, uint64_t cols);
+// per-row statistics of layer norm / softmax, per-column statistics of batch norm into g.stat
+// (no-op for the element-wise layers; batch norm also uses the scratch that follows g.stat);
 // variant selects the summation order
 hipError_t launch_layer_stats(const LayerArgs &g, uint64_t rows, double eps, int variant, hipStream_t s);
 hipError_t launch_layer_log_onepass(const LayerArgs &g, uint64_t n, uint32_t thr, uint32_t k, float *y, void *ws,

@@ -102,13 +102,96 @@ __global__ __launch_bounds__(256) void softmax_stats_kernel(const double *__rest
     }
 }
 
+// ---- batch norm: statistics per column (channel) over all rows --------------------------------
+// The rows are cut into kSlabs slabs.  A workgroup owns one slab and up to 256 columns: its 256
+// threads are cpb columns x 256 / cpb row groups; row group g adds rows g, g + groups, ... of the slab
+// for its column (variant 0: ascending, variant 1: descending), the groups are combined in a fixed
+// order, and a second kernel adds the slabs' partial sums in a fixed order.  Two sweeps: the mean,
+// then the centred squares.
+constexpr uint32_t kSlabs = 1024;
+
+template <bool CENTRED>
+__global__ __launch_bounds__(256) void column_sums_kernel(const double *__restrict__ x, uint32_t rows, uint32_t cols,
+                                                          uint32_t rows_per_slab, uint32_t cpb,
+                                                          const double *__restrict__ stat, int variant,
+                                                          double *__restrict__ partial)
+{
+    __shared__ double part[256];
+    const uint32_t t = threadIdx.x, cl = t % cpb, grp = t / cpb, groups = 256u / cpb;
+    const uint32_t c = blockIdx.y * cpb + cl;
+    const uint32_t r0 = blockIdx.x * rows_per_slab;
+    const uint32_t r1 = r0 + rows_per_slab < rows ? r0 + rows_per_slab : rows;
+    double acc = 0.0;
+    if (c < cols && r0 < rows) {
+        const double mean = CENTRED ? stat[2 * (uint64_t)c] : 0.0;
+        const uint32_t mine = r1 - r0 > grp ? (r1 - r0 - grp + groups - 1) / groups : 0u;   // rows of this group
+        for (uint32_t j0 = 0; j0 < mine; j0 += 4) {
+            double v[4];
+            bool in[4];
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u) {
+                const uint32_t j = j0 + u;
+                in[u] = j < mine;
+                const uint32_t r = r0 + grp + groups * (variant ? mine - 1 - (in[u] ? j : 0) : (in[u] ? j : 0));
+                v[u] = in[u] ? x[(uint64_t)r * cols + c] : 0.0;
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u)
+                if (in[u]) {
+                    if (CENTRED) { const double d = v[u] - mean; acc = acc + d * d; }
+                    else acc = acc + v[u];
+                }
+        }
+    }
+    part[t] = acc;
+    __syncthreads();
+    if (grp == 0 && c < cols) {
+        double s = 0.0;
+        for (uint32_t q = 0; q < groups; ++q) s = s + part[(variant ? groups - 1 - q : q) * cpb + cl];
+        partial[(uint64_t)blockIdx.x * cols + c] = s;
+    }
+}
+
+// pass 0: stat[2c] = mean; pass 1: stat[2c + 1] = 1 / sqrt(var + eps)
+__global__ __launch_bounds__(256) void column_finish_kernel(const double *__restrict__ partial, uint32_t rows, uint32_t cols,
+                                                            uint32_t slabs, double eps, int pass, int variant,
+                                                            double *__restrict__ stat)
+{
+    const uint32_t c = blockIdx.x * 256u + threadIdx.x;
+    if (c >= cols) return;
+    double s = 0.0;
+    for (uint32_t q = 0; q < slabs; ++q) s = s + partial[(uint64_t)(variant ? slabs - 1 - q : q) * cols + c];
+    if (pass == 0) stat[2 * (uint64_t)c] = s / (double)rows;
+    else stat[2 * (uint64_t)c + 1] = 1.0 / sqrt(s / (double)rows + eps);
+}
+
 }  // namespace
 
-size_t layer_stat_bytes(uint64_t rows) { return (size_t)((rows * 16 + 255) / 256 * 256); }
+// per-row statistics, or per-column statistics followed by the slabs' partial sums
+size_t layer_stat_bytes(uint64_t rows, uint64_t cols)
+{
+    const uint64_t row_wise = (rows * 16 + 255) / 256 * 256;
+    const uint64_t col_wise = (cols * 16 + 255) / 256 * 256 + ((uint64_t)kSlabs * cols * 8 + 255) / 256 * 256;
+    return (size_t)(row_wise > col_wise ? row_wise : col_wise);
+}
 
 hipError_t launch_layer_stats(const LayerArgs &g, uint64_t rows, double eps, int variant, hipStream_t s)
 {
-    if (rows == 0 || g.cols == 0 || (g.op != kLayerNorm && g.op != kLayerSoftmax)) return hipSuccess;
+    if (rows == 0 || g.cols == 0) return hipSuccess;
+    if (g.op == kLayerBatchNorm || g.op == kLayerBatchNormRelu) {
+        double *stat = (double *)g.stat;
+        double *partial = (double *)((char *)stat + ((uint64_t)g.cols * 16 + 255) / 256 * 256);
+        const uint32_t cpb = g.cols <= 64 ? 64u : g.cols <= 128 ? 128u : 256u;
+        const uint32_t per = (uint32_t)((rows + kSlabs - 1) / kSlabs);
+        const uint32_t slabs = (uint32_t)((rows + per - 1) / per);
+        const dim3 grid(slabs, (g.cols + cpb - 1) / cpb), block(256), fgrid((g.cols + 255) / 256);
+        column_sums_kernel<false><<<grid, block, 0, s>>>(g.a, (uint32_t)rows, g.cols, per, cpb, stat, variant, partial);
+        column_finish_kernel<<<fgrid, block, 0, s>>>(partial, (uint32_t)rows, g.cols, slabs, eps, 0, variant, stat);
+        column_sums_kernel<true><<<grid, block, 0, s>>>(g.a, (uint32_t)rows, g.cols, per, cpb, stat, variant, partial);
+        column_finish_kernel<<<fgrid, block, 0, s>>>(partial, (uint32_t)rows, g.cols, slabs, eps, 1, variant, stat);
+        return hipGetLastError();
+    }
+    if (g.op != kLayerNorm && g.op != kLayerSoftmax) return hipSuccess;
     const dim3 grid((uint32_t)((rows + 3) / 4)), block(256);
     if (g.op == kLayerNorm)
         layernorm_stats_kernel<<<grid, block, 0, s>>>(g.a, (uint32_t)rows, g.cols, eps, variant, (double *)g.stat);

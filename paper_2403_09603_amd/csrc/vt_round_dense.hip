@@ -299,6 +299,8 @@ hipError_t launch_layer_log_dense(const LayerArgs &g, uint64_t n, uint32_t thr, 
     case kLayerGeluErf: return launch_dense_from(LayerSource<kLayerGeluErf>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
     case kLayerNorm: return launch_dense_from(LayerSource<kLayerNorm>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
     case kLayerSoftmax: return launch_dense_from(LayerSource<kLayerSoftmax>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
+    case kLayerBatchNorm: return launch_dense_from(LayerSource<kLayerBatchNorm>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
+    case kLayerBatchNormRelu: return launch_dense_from(LayerSource<kLayerBatchNormRelu>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
     default: return hipErrorInvalidValue;
     }
 }

@@ -345,6 +345,8 @@ hipError_t launch_layer_log_onepass(const LayerArgs &g, uint64_t n, uint32_t thr
     case kLayerGeluErf: return launch_onepass_from(LayerSource<kLayerGeluErf>{g}, n, thr, k, y, ws, log, s);
     case kLayerNorm: return launch_onepass_from(LayerSource<kLayerNorm>{g}, n, thr, k, y, ws, log, s);
     case kLayerSoftmax: return launch_onepass_from(LayerSource<kLayerSoftmax>{g}, n, thr, k, y, ws, log, s);
+    case kLayerBatchNorm: return launch_onepass_from(LayerSource<kLayerBatchNorm>{g}, n, thr, k, y, ws, log, s);
+    case kLayerBatchNormRelu: return launch_onepass_from(LayerSource<kLayerBatchNormRelu>{g}, n, thr, k, y, ws, log, s);
     default: return hipErrorInvalidValue;
     }
 }

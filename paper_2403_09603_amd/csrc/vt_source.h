@@ -86,6 +86,17 @@ __device__ __forceinline__ double row_value(const LayerArgs &g, uint32_t r, uint
     return c < seen ? exp(g.scale * xa - st.x) * st.y : 0.0;
 }
 
+// One output of batch norm from its column statistics st = (mean, 1/std).
+template <int OP>
+__device__ __forceinline__ double col_value(const LayerArgs &g, uint32_t c, double xa, src_d2 st)
+{
+    double v = (xa - st.x) * st.y;
+    if (g.gamma) v = v * g.gamma[c];
+    if (g.beta) v = v + g.beta[c];
+    if (OP == kLayerBatchNormRelu) v = v > 0.0 ? v : (v != v ? v : 0.0);
+    return v;
+}
+
 template <int OP>
 struct LayerSource {
     LayerArgs g;
@@ -93,7 +104,21 @@ struct LayerSource {
     __device__ __forceinline__ src_d2 pair(uint64_t e, uint64_t n) const
     {
         const src_d2 xa = PlainSource{g.a}.template pair<FULL, VEC>(e, n);
-        if (FULL && OP >= kLayerNorm) {
+        if (OP >= kLayerBatchNorm) {
+            // statistics are per column: indices past the end are clamped, their values replaced below
+            uint32_t r0, c0;
+            divmod_u32((uint32_t)(FULL || e < n ? e : n - 1), g.cols, g.inv_cols, r0, c0);
+            const uint32_t c1 = (FULL || e + 1 < n) ? (c0 + 1u == g.cols ? 0u : c0 + 1u) : c0;
+            src_d2 v;
+            v.x = col_value<OP>(g, c0, xa.x, *(const src_d2 *)(g.stat + 2 * (uint64_t)c0));
+            v.y = col_value<OP>(g, c1, xa.y, *(const src_d2 *)(g.stat + 2 * (uint64_t)c1));
+            if (!FULL) {
+                if (e >= n) v.x = 1.0;
+                if (e + 1 >= n) v.y = 1.0;
+            }
+            return v;
+        }
+        if (FULL && (OP == kLayerNorm || OP == kLayerSoftmax)) {
             // both outputs exist: split the index once, one 16-byte load of the row statistics
             // (a second one only when the pair straddles two rows)
             uint32_t r0, c0;

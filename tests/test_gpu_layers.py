@@ -112,12 +112,35 @@ def test_softmax(G, shape, period, dense):
         _hook(r, tau)
 
 
+@pytest.mark.parametrize("dense", [False, True])
+@pytest.mark.parametrize("shape", [(2, 1), (9, 3), (700, 64), (5000, 200), (1300, 513), (40000, 64)])
+def test_batchnorm(G, shape, dense):
+    a, _, g = _inputs(shape, 90 + shape[1])
+    a = np.clip(a, -60, 60) + 0.25
+    rows, cols = shape
+    gamma = (g.standard_normal(cols) + 1.0).astype(np.float32).astype(np.float64)
+    beta = g.standard_normal(cols).astype(np.float32).astype(np.float64)
+    tau = 2.0 ** -4
+    truth = vo.batchnorm(a, gamma, beta, 1e-5, order=2)
+    xhat = np.abs(vo.batchnorm(a, eps=1e-5, order=2))
+    bound = 2.0 ** -52 * (8 + 4 * np.sqrt(rows)) * (xhat + 1.0) * np.abs(gamma)[None, :] + 2.0 ** -52 * np.abs(truth) + 1e-300
+    for variant in (0, 1):
+        r = G.gpu_layer(6, a, gamma=gamma, beta=beta, eps=1e-5, tau=tau, variant=variant, dense=dense)
+        assert np.all(np.abs(r["y64"] - truth) <= bound), float(np.max(np.abs(r["y64"] - truth) / bound))
+        _hook(r, tau)
+        rr = G.gpu_layer(7, a, gamma=gamma, beta=beta, eps=1e-5, tau=tau, variant=variant, dense=dense)
+        assert np.array_equal(rr["y64"], np.maximum(r["y64"], 0.0))              # ReLU of the same values
+        _hook(rr, tau)
+    again = G.gpu_layer(6, a, gamma=gamma, beta=beta, eps=1e-5, tau=tau, variant=1, dense=dense)
+    assert np.array_equal(again["y64"], r["y64"])                                # deterministic
+
+
 def test_two_summation_orders_and_replay(G):
     """Layer norm and softmax over long rows: the two variants differ in low bits; the threshold from
     their statistics makes the trainer's log bring the other variant back to the trainer's outputs."""
     g = si.rng(si.seed_for(9, 300))
     a = g.standard_normal((512, 3072)).astype(np.float32).astype(np.float64)
-    for op, kw in ((NORM, dict(eps=1e-5)), (SOFTMAX, dict(scale=0.5))):
+    for op, kw in ((NORM, dict(eps=1e-5)), (SOFTMAX, dict(scale=0.5)), (6, dict(eps=1e-5))):
         r0 = G.gpu_layer(op, a, tau=0.0, variant=0, **kw)
         r1 = G.gpu_layer(op, a, tau=0.0, variant=1, **kw)
         assert (r0["y64"] != r1["y64"]).mean() > 0.05
@@ -145,4 +168,4 @@ def test_rounding_amount_and_validation(G):
     with pytest.raises(vt.VtError):
         G.gpu_layer(ADD, a)                                                    # second addend missing
     with pytest.raises(vt.VtError):
-        G.gpu_layer(9, a)                                                      # unknown layer
+        G.gpu_layer(8, a)                                                      # unknown layer

@@ -167,9 +167,9 @@ def test_layer_validation_on_the_host(hiplib):
     def call(op=0, a=0x1000, bb=0x1000, rows=8, cols=16, eps=1e-5, period=0, variant=0, tau=0.1, y=0x1000, ws=0x1000, wsb=1 << 20):
         L = b._VtLayer(op, a, bb, None, None, rows, cols, eps, 1.0, period)
         return f(C.byref(L), C.c_void_p(y), None, variant, tau, C.byref(log), C.c_void_p(ws) if ws else None, wsb, None)
-    assert call(op=6) == INVALID and call(op=-1) == INVALID and call(rows=-1) == INVALID and call(variant=2) == INVALID
+    assert call(op=8) == INVALID and call(op=-1) == INVALID and call(rows=-1) == INVALID and call(variant=2) == INVALID
     assert call(a=None) == INVALID and call(a=0x1008) == INVALID and call(bb=None) == INVALID and call(y=0x1004) == INVALID
-    assert call(op=4, eps=-1.0) == INVALID and call(op=5, period=-3) == INVALID and call(tau=0.7) == INVALID
+    assert call(op=4, eps=-1.0) == INVALID and call(op=6, eps=-1.0) == INVALID and call(op=5, period=-3) == INVALID and call(tau=0.7) == INVALID
     assert call(rows=1 << 20, cols=1 << 12) == INVALID                          # 2^32 outputs
     assert call(ws=None, wsb=0) == WORKSPACE and call(wsb=64) == WORKSPACE
     assert hiplib.vt_workspace_bytes(5, 8192, 768, 0, 1) >= 8192 * 16
