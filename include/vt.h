@@ -78,6 +78,8 @@ extern "C" {
 #define VT_OP_THRESHOLD_STATS 3 /* needs no workspace (returns 0) */
 #define VT_OP_GEMM_ROUND_LOG_BR 4 /* GEMM / convolution with log->b_r below 32 (rounds in a second pass) */
 #define VT_OP_LAYER_ROUND_LOG 5  /* vt_layer_f64_round_log: M = rows, N = cols */
+#define VT_OP_SHA256_TREE 6      /* vt_sha256_tree: N = bytes, K = chunk (M, batch ignored) */
+#define VT_OP_MERKLE_ROOT 7      /* vt_merkle_root: N = leaves (M, K, batch ignored) */
 
 /* Caller-owned log buffers (all four pointers are device pointers). */
 typedef struct vt_log {
@@ -271,6 +273,39 @@ int vt_threshold_stats(const double *y1, const double *y2, uint64_t n, uint64_t 
  * b_r grid, thr_flip in units of 2^-29 of its spacing. */
 int vt_threshold_stats_br(const double *y1, const double *y2, uint64_t n, int b_r, uint64_t *out,
                           void *hip_stream);
+
+/*
+ * Hash of the model weights at a checkpoint (Method, primitive hash_sha256(theta): a SHA-256 hash of
+ * the weights in the model's precision; Algorithms "train" and "audit" append one to the Merkle
+ * leaves every k steps).  The weights are hashed where they live, as the bytes in device memory.
+ *
+ *   chunk = 0   the SHA-256 of the whole byte string.  SHA-256 is sequential over its 64-byte blocks,
+ *               so this runs on a single lane (tens of MB/s): nbytes is limited to 2^26
+ *               (VT_ERR_UNSUPPORTED above); meant for small tensors and cross-checks.
+ *   chunk > 0   (a multiple of 64) the same weights hashed as a tree, which is what the GPU hashes in
+ *               parallel: the data is cut into chunks of `chunk` bytes (the last may be shorter),
+ *               every chunk is hashed, the 32-byte digests in chunk order are the next level's data,
+ *               and so on until the data fits one chunk, whose SHA-256 is the result.  Data of at
+ *               most `chunk` bytes therefore gives the plain SHA-256.  Trainer and auditor must use
+ *               the same chunk; it is part of what "hash" means for a run.
+ *   data        device, nbytes bytes, 16-byte aligned
+ *   digest      device, 32 bytes (the digest as SHA-256 prints it, first byte first), 4-byte aligned
+ *   ws          at least vt_workspace_bytes(VT_OP_SHA256_TREE, 1, nbytes, chunk, 1) bytes, 256-byte aligned
+ */
+int vt_sha256_tree(const void *data, uint64_t nbytes, uint64_t chunk, uint8_t *digest,
+                   void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Root of the Merkle tree over the checkpoint hashes (Method, primitive tree(leaf_1 .. leaf_n);
+ * Experimental setup: every leaf is a hash of the data and every other node a hash of its children).
+ * A parent is SHA-256(left || right) over the two 32-byte children; a level's last node without a
+ * sibling moves up unchanged; one leaf is its own root.
+ *   leaves      device, n_leaves x 32 bytes, 4-byte aligned; n_leaves >= 1
+ *   root        device, 32 bytes, 4-byte aligned
+ *   ws          at least vt_workspace_bytes(VT_OP_MERKLE_ROOT, 1, n_leaves, 0, 1) bytes, 256-byte aligned
+ */
+int vt_merkle_root(const uint8_t *leaves, uint64_t n_leaves, uint8_t *root,
+                   void *ws, size_t ws_bytes, void *hip_stream);
 
 /* Scratch bytes needed by an operation of the given shape (0 if none). */
 size_t vt_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int64_t batch);

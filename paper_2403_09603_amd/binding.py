@@ -20,6 +20,7 @@ VT_CONV_FORWARD, VT_CONV_WEIGHT_GRAD = 0, 1
 VT_OP_LAYER_ROUND_LOG = 5
 VT_LAYER_ADD, VT_LAYER_RELU, VT_LAYER_GELU_TANH, VT_LAYER_GELU_ERF, VT_LAYER_NORM, VT_LAYER_SOFTMAX = 0, 1, 2, 3, 4, 5
 VT_LAYER_BATCHNORM, VT_LAYER_BATCHNORM_RELU = 6, 7
+VT_OP_SHA256_TREE, VT_OP_MERKLE_ROOT = 6, 7
 
 
 class VtError(RuntimeError):
@@ -82,6 +83,10 @@ def load_library():
     L.vt_layer_f64_round_log.argtypes = [C.POINTER(_VtLayer), vp, vp, cint, dbl, C.POINTER(_VtLog), vp, C.c_size_t, vp]
     L.vt_threshold_stats.restype = cint
     L.vt_threshold_stats.argtypes = [vp, vp, u64, vp, vp]
+    L.vt_sha256_tree.restype = cint
+    L.vt_sha256_tree.argtypes = [vp, u64, u64, vp, vp, C.c_size_t, vp]
+    L.vt_merkle_root.restype = cint
+    L.vt_merkle_root.argtypes = [vp, u64, vp, vp, C.c_size_t, vp]
     L.vt_workspace_bytes.restype = C.c_size_t
     L.vt_workspace_bytes.argtypes = [cint, i64, i64, i64, i64]
     L.vt_thr_from_tau.restype = C.c_uint32
@@ -321,3 +326,20 @@ def vt_threshold_stats(y1: torch.Tensor, y2: torch.Tensor, out: torch.Tensor, st
     else:
         _check(load_library().vt_threshold_stats_br(_ptr(y1, torch.float64), _ptr(y2, torch.float64), y1.numel(),
                                                     int(b_r), _ptr(out), _stream(stream)), "vt_threshold_stats_br")
+
+
+def vt_sha256_tree(data: torch.Tensor, chunk: int, digest: torch.Tensor, ws: torch.Tensor, stream=None):
+    """Hash the bytes of `data` (any dtype, on the GPU) into the 32-byte uint8 tensor `digest`."""
+    if digest.dtype != torch.uint8 or digest.numel() < 32:
+        raise VtError("digest must be a uint8 tensor of 32 bytes")
+    nbytes = data.numel() * data.element_size()
+    _check(load_library().vt_sha256_tree(_ptr(data) if nbytes else None, nbytes, int(chunk), _ptr(digest), _ptr(ws),
+                                         ws.numel() * ws.element_size(), _stream(stream)), "vt_sha256_tree")
+
+
+def vt_merkle_root(leaves: torch.Tensor, root: torch.Tensor, ws: torch.Tensor, stream=None):
+    """Merkle root of the 32-byte leaves (uint8 tensor of n x 32 bytes) into the 32-byte uint8 tensor `root`."""
+    if leaves.dtype != torch.uint8 or root.dtype != torch.uint8 or leaves.numel() % 32 or root.numel() < 32:
+        raise VtError("leaves must be n x 32 uint8 and root 32 uint8")
+    _check(load_library().vt_merkle_root(_ptr(leaves), leaves.numel() // 32, _ptr(root), _ptr(ws),
+                                         ws.numel() * ws.element_size(), _stream(stream)), "vt_merkle_root")

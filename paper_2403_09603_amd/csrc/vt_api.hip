@@ -184,8 +184,34 @@ size_t vt_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int64_t batch
             bytes += vt::gemm_split_bytes(M, N, batch, splits) + round_log_bytes((uint64_t)M * (uint64_t)N * (uint64_t)batch);
         return bytes;
     }
+    case VT_OP_SHA256_TREE:
+        if (K < 0 || (K % 64) != 0) return 0;
+        return vt::sha256_tree_bytes((uint64_t)N, (uint64_t)K);
+    case VT_OP_MERKLE_ROOT: return vt::merkle_root_bytes((uint64_t)N);
     default: return 0;
     }
+}
+
+int vt_sha256_tree(const void *data, uint64_t nbytes, uint64_t chunk, uint8_t *digest,
+                   void *ws, size_t ws_bytes, void *hip_stream)
+{
+    if (!digest || !aligned(digest, 4) || (chunk % 64) != 0) return VT_ERR_INVALID_ARG;
+    if (nbytes && (!data || !aligned(data, 16))) return VT_ERR_INVALID_ARG;
+    if (nbytes >= (1ull << 56)) return VT_ERR_INVALID_ARG;                       // chunk counts and bit lengths stay in range
+    if (chunk == 0 && nbytes > (1ull << 26)) return VT_ERR_UNSUPPORTED;          // the sequential form is for small inputs
+    if (chunk && nbytes / chunk >= (1ull << 36)) return VT_ERR_INVALID_ARG;      // grid limit: 2^31 workgroups of 64 chunks
+    if (!ws || ws_bytes < vt::sha256_tree_bytes(nbytes, chunk) || !aligned(ws, 256)) return VT_ERR_WORKSPACE;
+    return hip_status(vt::launch_sha256_tree((const uint8_t *)data, nbytes, chunk, (uint32_t *)digest, ws,
+                                             (hipStream_t)hip_stream));
+}
+
+int vt_merkle_root(const uint8_t *leaves, uint64_t n_leaves, uint8_t *root, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    if (!leaves || !root || n_leaves == 0 || !aligned(leaves, 4) || !aligned(root, 4)) return VT_ERR_INVALID_ARG;
+    if (n_leaves >= (1ull << 36)) return VT_ERR_INVALID_ARG;
+    if (!ws || ws_bytes < vt::merkle_root_bytes(n_leaves) || !aligned(ws, 256)) return VT_ERR_WORKSPACE;
+    return hip_status(vt::launch_merkle_root((const uint32_t *)leaves, n_leaves, (uint32_t *)root, ws,
+                                             (hipStream_t)hip_stream));
 }
 
 int vt_round_log(const double *x, uint64_t n, double tau_ulp, float *y, const vt_log *log,

@@ -90,6 +90,14 @@ hipError_t launch_layer_log_onepass(const LayerArgs &g, uint64_t n, uint32_t thr
 hipError_t launch_layer_log_dense(const LayerArgs &g, uint64_t n, uint32_t thr, uint32_t k, float *y, uint8_t *tlog,
                                   uint64_t *n_logged, uint64_t *slots, hipStream_t s);
 
+// SHA-256 of a byte string as a tree of chunks (chunk 0: the plain, sequential hash) and the
+// Merkle root over 32-byte leaves; digests are 32 bytes in device memory, 4-byte aligned
+size_t sha256_tree_bytes(uint64_t nbytes, uint64_t chunk);
+hipError_t launch_sha256_tree(const uint8_t *data, uint64_t nbytes, uint64_t chunk, uint32_t *digest, void *ws,
+                              hipStream_t s);
+size_t merkle_root_bytes(uint64_t n_leaves);
+hipError_t launch_merkle_root(const uint32_t *leaves, uint64_t n_leaves, uint32_t *root, void *ws, hipStream_t s);
+
 hipError_t launch_stats(const double *y1, const double *y2, uint64_t n, uint32_t k, uint64_t *out, hipStream_t s);
 
 // Geometry of a channels-last convolution whose image the GEMM kernel reads through an implicit

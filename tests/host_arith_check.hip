@@ -34,3 +34,30 @@ extern "C" void h_im2col_offsets(const int64_t *g /* N H W C KH KW sh sw ph pw d
     for (uint32_t m = 0; m < rows_to_do; ++m)
         for (uint32_t k = 0; k < taps_to_do; ++k) offsets[(uint64_t)m * taps_to_do + k] = vt::conv_element(c, row0 + m, tap0 + k);
 }
+
+// SHA-256 of one byte range with the library's per-lane routines (csrc/vt_sha256.h), stepping
+// through the blocks the way the chunk kernel does: whole blocks, then the ragged end or the
+// constant padding block.
+#include "../paper_2403_09603_amd/csrc/vt_sha256.h"
+extern "C" void h_sha256(const uint8_t *data, uint64_t len, uint8_t *digest)
+{
+    vt::Sha256State s;
+    vt::sha256_init(s);
+    const uint64_t blocks = len >> 6;
+    for (uint64_t b = 0; b < blocks; ++b) {
+        uint32_t w[16];
+        for (int i = 0; i < 16; ++i) {
+            uint32_t v;
+            __builtin_memcpy(&v, data + 64 * b + 4 * i, 4);
+            w[i] = vt::sha_bswap(v);
+        }
+        vt::sha256_compress(s, w);
+    }
+    const uint32_t rem = (uint32_t)(len & 63);
+    if (rem) vt::sha256_finish_ragged(s, data + 64 * blocks, rem, len);
+    else vt::sha256_pad_block(s, len);
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t v = vt::sha_bswap(s.h[i]);
+        __builtin_memcpy(digest + 4 * i, &v, 4);
+    }
+}

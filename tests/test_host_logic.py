@@ -247,3 +247,45 @@ def test_kernel_integer_arithmetic_matches_oracle_on_host(harith):
         harith.h_directed(bits.ctypes.data_as(C.POINTER(C.c_uint64)), C.c_uint64(n), C.c_uint32(d), _u32p(yd))
         want = vo.round_replay(x, idx, np.full((n + 31) // 32, 0xFFFFFFFF if d else 0, np.uint32))
         assert np.array_equal(yd, want.view(np.uint32))
+
+
+def test_sha256_lane_routines_on_host(harith):
+    """The per-lane SHA-256 the hash kernels are built from, compiled for the host: every message length
+    around the block and padding boundaries, and long random strings, against hashlib."""
+    import hashlib
+    rng = np.random.default_rng(0x2403096030F4)
+    harith.h_sha256.argtypes = [C.c_char_p, C.c_uint64, C.c_char_p]
+    lengths = list(range(0, 200)) + [255, 256, 257, 4095, 4096, 4097, 65536 + 55, 65536 + 56, 1 << 20]
+    for n in lengths:
+        data = rng.integers(0, 256, n, dtype=np.uint8).tobytes()
+        out = C.create_string_buffer(32)
+        harith.h_sha256(data, n, out)
+        assert out.raw == hashlib.sha256(data).digest(), n
+    out = C.create_string_buffer(32)
+    harith.h_sha256(b"abc", 3, out)
+    assert out.raw.hex() == "ba7816bf8f01cfea414140de5dae2223b00361a396177a9cb410ff61f20015ad"   # the standard's example
+
+
+def test_hash_entry_points_validate_on_the_host(hiplib):
+    L = hiplib
+    vp, u64 = C.c_void_p, C.c_uint64
+    L.vt_sha256_tree.restype = C.c_int
+    L.vt_sha256_tree.argtypes = [vp, u64, u64, vp, vp, C.c_size_t, vp]
+    L.vt_merkle_root.restype = C.c_int
+    L.vt_merkle_root.argtypes = [vp, u64, vp, vp, C.c_size_t, vp]
+    L.vt_workspace_bytes.restype = C.c_size_t
+    L.vt_workspace_bytes.argtypes = [C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_int64]
+    fake = 0x10000
+    assert L.vt_sha256_tree(fake, 1024, 100, fake, fake, 1 << 20, None) == 1      # chunk not a multiple of 64
+    assert L.vt_sha256_tree(fake + 8, 1024, 64, fake, fake, 1 << 20, None) == 1   # data not 16-byte aligned
+    assert L.vt_sha256_tree(fake, 1024, 64, None, fake, 1 << 20, None) == 1
+    assert L.vt_sha256_tree(fake, (1 << 26) + 1, 0, fake, fake, 1 << 20, None) == 4   # sequential form: size limit
+    assert L.vt_sha256_tree(fake, 1 << 20, 64, fake, fake, 256, None) == 2        # workspace too small
+    assert L.vt_merkle_root(fake, 0, fake, fake, 1 << 20, None) == 1
+    assert L.vt_merkle_root(fake, 1000, fake, fake, 256, None) == 2
+    # workspace: two ping-pong digest buffers, 32 bytes per chunk at the first level
+    n, chunk = 100 << 20, 4096
+    need = L.vt_workspace_bytes(6, 1, n, chunk, 1)
+    assert 32 * (n // chunk) <= need <= 32 * (n // chunk) * 1.02 + 1024
+    assert L.vt_workspace_bytes(6, 1, 100, 4096, 1) == 256
+    assert L.vt_workspace_bytes(7, 1, 1001, 0, 1) >= 2 * 32 * 501
