@@ -262,6 +262,21 @@ def main():
             lbytes = n * (8 * reads + 4 + 0.2)
             layers[lname] = {"ms": round(l_call, 4), "GBs": round(lbytes / l_call * 1e-6, 1)}
         del wsl, wsb
+        # checkpoint hash: SHA-256 chunk tree over as many bytes as GPT-2 117M has FP32 weights (here the
+        # first bytes of the resident vector), then the Merkle root over 1024 checkpoint leaves
+        hbytes = 124_439_808 * 4
+        hsrc = xd.view(torch.uint8)[:hbytes]
+        digest = torch.zeros(32, dtype=torch.uint8, device=dev)
+        hashes = {}
+        for chunk in (1024, 4096):
+            wsh = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_SHA256_TREE, 1, hbytes, chunk))
+            h_call, _ = timed(lambda: vt.vt_sha256_tree(hsrc, chunk, digest, wsh), reps=5)
+            hashes[f"sha256_tree_chunk{chunk}"] = {"ms": round(h_call, 4), "GBs": round(hbytes / h_call * 1e-6, 1)}
+        leaves = xd.view(torch.uint8)[:1024 * 32]
+        wsm = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_MERKLE_ROOT, 1, 1024))
+        m_call, _ = timed(lambda: vt.vt_merkle_root(leaves, digest, wsm), reps=5)
+        hashes["bytes"] = hbytes
+        hashes["merkle_root_1024_leaves_ms"] = round(m_call, 4)
         rho = cnt / n
         bytes_rl = n * (8 + 4 + rho * 4.125)
         out["standalone"] = {
@@ -283,6 +298,7 @@ def main():
                 "replay_frac_hbm": round(bytes_d / pd_call * 1e-6 / HBM_PEAK_GBS, 4),
                 "replay_mismatches": mism_d},
             "fused_layers_packed_log": layers,
+            "checkpoint_hash": hashes,
             "b_r_26_packed_log": {
                 "round_log_ms": round(r26_call, 4), "round_log_GBs": round(bytes_d / r26_call * 1e-6, 1),
                 "replay_ms": round(p26_call, 4), "replay_GBs": round(bytes_d / p26_call * 1e-6, 1),

@@ -26,14 +26,33 @@ static __host__ __device__ __forceinline__ void sha256_init(Sha256State &s)
 
 static __host__ __device__ __forceinline__ uint32_t sha_rotr(uint32_t x, uint32_t n) { return (x >> n) | (x << (32u - n)); }
 static __host__ __device__ __forceinline__ uint32_t sha_bswap(uint32_t x) { return __builtin_bswap32(x); }
+// a ^ b ^ c: one three-input bit operation on the GPU (truth table 0x96); the host build of this
+// header (CPU checks of the routines) takes two.
+static __host__ __device__ __forceinline__ uint32_t sha_xor3(uint32_t a, uint32_t b, uint32_t c)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+#else
+    return a ^ b ^ c;
+#endif
+}
+// Ch(e, f, g): f where e is set, g elsewhere (truth table 0xCA with inputs 0xF0, 0xCC, 0xAA).
+static __host__ __device__ __forceinline__ uint32_t sha_ch(uint32_t e, uint32_t f, uint32_t g)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_bitop3_b32(e, f, g, 0xCA);
+#else
+    return g ^ (e & (f ^ g));
+#endif
+}
 
 // One round with the working variables renamed instead of moved: the caller rotates the
 // argument order, so nothing is copied between rounds.
 #define VT_SHA_ROUND(a, b, c, d, e, f, g, h, k, w)                                              \
     do {                                                                                        \
-        const uint32_t t1 = (h) + (sha_rotr((e), 6) ^ sha_rotr((e), 11) ^ sha_rotr((e), 25)) +  \
-                            ((g) ^ ((e) & ((f) ^ (g)))) + (k) + (w);                            \
-        const uint32_t t2 = (sha_rotr((a), 2) ^ sha_rotr((a), 13) ^ sha_rotr((a), 22)) +        \
+        const uint32_t t1 = (h) + sha_xor3(sha_rotr((e), 6), sha_rotr((e), 11), sha_rotr((e), 25)) + \
+                            sha_ch((e), (f), (g)) + (k) + (w);                                  \
+        const uint32_t t2 = sha_xor3(sha_rotr((a), 2), sha_rotr((a), 13), sha_rotr((a), 22)) +  \
                             (((a) & (b)) | ((c) & ((a) | (b))));                                \
         (d) += t1;                                                                              \
         (h) = t1 + t2;                                                                          \
@@ -41,11 +60,11 @@ static __host__ __device__ __forceinline__ uint32_t sha_bswap(uint32_t x) { retu
 
 // w[i & 15] becomes W[i] for i >= 16: sigma1(W[i-2]) + W[i-7] + sigma0(W[i-15]) + W[i-16]
 #define VT_SHA_SCHED(w, i)                                                                       \
-    ((w)[(i) & 15] += (sha_rotr((w)[((i) - 2) & 15], 17) ^ sha_rotr((w)[((i) - 2) & 15], 19) ^   \
-                       ((w)[((i) - 2) & 15] >> 10)) +                                            \
+    ((w)[(i) & 15] += sha_xor3(sha_rotr((w)[((i) - 2) & 15], 17), sha_rotr((w)[((i) - 2) & 15], 19), \
+                               (w)[((i) - 2) & 15] >> 10) +                                      \
                       (w)[((i) - 7) & 15] +                                                      \
-                      (sha_rotr((w)[((i) - 15) & 15], 7) ^ sha_rotr((w)[((i) - 15) & 15], 18) ^  \
-                       ((w)[((i) - 15) & 15] >> 3)))
+                      sha_xor3(sha_rotr((w)[((i) - 15) & 15], 7), sha_rotr((w)[((i) - 15) & 15], 18), \
+                               (w)[((i) - 15) & 15] >> 3))
 
 #define VT_SHA_8ROUNDS(i, k0, k1, k2, k3, k4, k5, k6, k7)  \
     VT_SHA_ROUND(a, b, c, d, e, f, g, h, k0, w[(i) + 0]);  \
