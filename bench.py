@@ -69,6 +69,143 @@ def next_pow2(v: int) -> int:
     return 1 << max(int(v) - 1, 0).bit_length()
 
 
+def resnet50_conv_layers():
+    """The 53 convolutions of ResNet-50 at 224 x 224 (stride on the 3 x 3 of a stage's first block):
+    (kind, input height = width, Cin, filter size, Cout, stride, padding)."""
+    layers = [("7x7 first", 224, 3, 7, 64, 2, 3)]
+    h, cin = 56, 64
+    for width, blocks, stride in ((64, 3, 1), (128, 4, 2), (256, 6, 2), (512, 3, 2)):
+        for b in range(blocks):
+            s = stride if b == 0 else 1
+            layers.append(("1x1", h, cin, 1, width, 1, 0))
+            layers.append(("3x3", h, width, 3, width, s, 1))
+            layers.append(("1x1", h // s, width, 1, 4 * width, 1, 0))
+            if b == 0:
+                layers.append(("1x1 downsample", h, cin, 1, 4 * width, s, 0))
+            cin, h = 4 * width, h // s
+    assert len(layers) == 53
+    return layers
+
+
+def workload_streams(vt, torch, dev):
+    """The other two workloads the method is quoted on, as streams of fused calls on one GPU: every GEMM of
+    the GPT-2 117M layer stream (12 layers, batch 8 x 1024 tokens) and every ResNet-50 convolution at
+    batch 64 (forward and weight gradient).  tau_ulp = 1/4 (the paper's default band: half of all outputs
+    logged), decisions in the packed ternary log.  Operands are seeded synthetic tensors of the layers'
+    shapes drawn on the GPU; parity at these shapes is the tests' business, this leg only measures."""
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(0x240309603000 + 16 * 3)
+    tau = 0.25
+
+    def f32grid(t):
+        return t.float().double()
+
+    def run_stream(calls, reps=2):
+        """calls: list of (kind, flops, fn).  Runs the stream `reps` times, times the last pass as a whole
+        and per call (events on the stream the library launches on)."""
+        for _ in range(reps - 1):
+            for _, _, fn in calls:
+                fn()
+        torch.cuda.synchronize()
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)]
+        evs[0].record()
+        for i, (_, _, fn) in enumerate(calls):
+            fn()
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        total_ms = evs[0].elapsed_time(evs[-1])
+        kinds = {}
+        for i, (kind, fl, _) in enumerate(calls):
+            k = kinds.setdefault(kind, [0, 0.0, 0.0])
+            k[0] += 1; k[1] += fl; k[2] += evs[i].elapsed_time(evs[i + 1])
+        flops = sum(fl for _, fl, _ in calls)
+        return {"calls": len(calls), "TFLOP": round(flops / 1e12, 4), "ms": round(total_ms, 3),
+                "TFLOPs": round(flops / total_ms / 1e9, 2),
+                "frac_mfma_peak": round(flops / total_ms / 1e9 / FP64_MFMA_PEAK_TFLOPS, 4),
+                "by_kind": {k: {"calls": v[0], "ms": round(v[2], 3), "TFLOPs": round(v[1] / v[2] / 1e9, 2)}
+                            for k, v in kinds.items()}}
+
+    out = {}
+    # ---- GPT-2 117M: per layer QKV, scores per (batch, head), attention output, MLP up, MLP down
+    T, D, H, DH, B = 1024, 768, 12, 64, 8
+    R = B * T
+    act = f32grid(torch.randn(R, D, generator=gen, device=dev, dtype=torch.float64))
+    act4 = f32grid(torch.randn(R, 4 * D, generator=gen, device=dev, dtype=torch.float64))
+    qkv = f32grid(torch.randn(R, 3 * D, generator=gen, device=dev, dtype=torch.float64))
+    qkv_flat = qkv.view(-1)
+    wts = {n: f32grid(torch.randn(k, m, generator=gen, device=dev, dtype=torch.float64) * 0.02)
+           for n, (k, m) in {"qkv": (D, 3 * D), "attn_out": (D, D), "mlp_up": (D, 4 * D), "mlp_down": (4 * D, D)}.items()}
+    biases = {n: torch.zeros(w.shape[1], dtype=torch.float64, device=dev) for n, w in wts.items()}
+    big = R * 4 * D
+    c32 = torch.empty(max(big, B * H * T * T), dtype=torch.float32, device=dev)
+    dlog = vt.alloc_dense_log(max(big, B * H * T * T))
+    ws = vt.alloc_workspace(max(vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG, R, 4 * D, D, 1),
+                                vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG, R, D, 4 * D, 1),
+                                vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG, T, T, DH, B * H)))
+
+    def linear(name, x):
+        w = wts[name]
+        k, n = w.shape
+        return (name, 2.0 * R * n * k,
+                lambda: vt.vt_gemm_f64_round_log(False, False, R, n, k, 1.0, x, k, 0, w, n, 0, biases[name], 1, c32, n, 0,
+                                                 None, 0, tau, dlog, ws))
+
+    def scores():
+        # Q and K of (sequence b, head h) are column slices of the QKV activation: heads 64 columns apart,
+        # sequences T rows apart -- one nested-batch call covers all 96 matrices
+        return ("scores", 2.0 * B * H * T * T * DH,
+                lambda: vt.vt_gemm_f64_round_log_nested(False, True, T, T, DH, 0.125, qkv_flat, 3 * D, DH, T * 3 * D,
+                                                        qkv_flat[D:], 3 * D, DH, T * 3 * D, None, H, B,
+                                                        c32, T, T * T, None, 0, tau, dlog, ws))
+
+    calls = []
+    for _ in range(12):
+        calls.append(linear("qkv", act))
+        calls.append(scores())
+        calls.append(linear("attn_out", act))
+        calls.append(linear("mlp_up", act))
+        calls.append(linear("mlp_down", act4))
+    out["gpt2_117m_layer_stream"] = run_stream(calls)
+    out["gpt2_117m_layer_stream"]["workload"] = ("12 layers x (QKV 768->2304, scores Q K^T / 8 per head as strided slices, "
+                                                 "attention output 768->768, MLP 768->3072->768), batch 8 x 1024 tokens")
+    del act, act4, qkv, qkv_flat, wts, c32, dlog, ws, calls
+
+    # ---- ResNet-50 at batch 64: 53 forward convolutions and 53 weight gradients
+    NB = 64
+    layers = resnet50_conv_layers()
+    geo = []
+    for kind, h, cin, kf, cout, st, pad in layers:
+        ho = (h + 2 * pad - kf) // st + 1
+        geo.append((kind, vt.Conv2d(NB, h, h, cin, kf, kf, st, st, pad, pad, 1, 1), cin, kf, cout, NB * ho * ho))
+    max_x = max(NB * d.H * d.W * d.C for _, d, *_ in geo)
+    max_y = max(rows * cout for *_, cout, rows in geo)
+    max_w = max(kf * kf * cin * cout for _, _, cin, kf, cout, _ in geo)
+    gen.manual_seed(0x240309603000 + 16 * 4)
+    xbuf = f32grid(torch.randn(max_x, generator=gen, device=dev, dtype=torch.float64).clamp_(min=0.0))
+    dybuf = torch.randn(max_y, generator=gen, device=dev, dtype=torch.float64) * 1e-3
+    wbuf = f32grid(torch.randn(max_w, generator=gen, device=dev, dtype=torch.float64) * 0.05)
+    y32 = torch.empty(max(max_y, max_w), dtype=torch.float32, device=dev)
+    dlog = vt.alloc_dense_log(max(max_y, max_w))
+    need = 0
+    for _, d, cin, kf, cout, rows in geo:
+        for mode in (vt.VT_CONV_FORWARD, vt.VT_CONV_WEIGHT_GRAD):
+            m, n, k = vt.vt_conv2d_gemm_shape(d, cout, mode)
+            need = max(need, vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG, m, n, k, 1))
+    ws = vt.alloc_workspace(need)
+    fwd, wgr = [], []
+    for kind, d, cin, kf, cout, rows in geo:
+        fl = 2.0 * rows * cout * kf * kf * cin
+        fwd.append((kind, fl, lambda d=d, cout=cout: vt.vt_conv2d_f64_round_log(
+            vt.VT_CONV_FORWARD, d, cout, xbuf, wbuf, None, y32, None, 0, tau, dlog, ws)))
+        wgr.append((kind, fl, lambda d=d, cout=cout: vt.vt_conv2d_f64_round_log(
+            vt.VT_CONV_WEIGHT_GRAD, d, cout, xbuf, dybuf, None, y32, None, 0, tau, dlog, ws)))
+    out["resnet50_conv_forward"] = run_stream(fwd)
+    out["resnet50_conv_weight_grad"] = run_stream(wgr)
+    out["resnet50_conv_forward"]["workload"] = "all 53 convolutions of ResNet-50, batch 64, 224 x 224 x 3 input, implicit im2col"
+    out["resnet50_conv_weight_grad"]["workload"] = "weight gradients of the same 53 layers (deterministic split-K where the plan asks for it)"
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -76,6 +213,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-stream", action="store_true", help="skip the 2^28-element standalone sweep")
+    ap.add_argument("--no-workloads", action="store_true",
+                    help="skip the GPT-2 layer-stream and ResNet-50 convolution legs")
     ap.add_argument("--cpu-rows", type=int, default=1024, help="rows of X the CPU oracle is timed on")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain elementwise kernel over 1 GiB in / 1 GiB out (torch.neg), so that "
@@ -306,6 +445,11 @@ def main():
                 "replay_mismatches": mism_26},
         }
         del xd, xad, y1, y2, logs, wss, dlog, dlog26
+
+    # ------------------------------------------------ the other workload shapes (GPT-2 layer stream, ResNet-50 convolutions)
+    if not args.no_workloads:
+        torch.cuda.empty_cache()
+        out["workloads"] = workload_streams(vt, torch, dev)
 
     # ------------------------------------------------ CPU oracle baseline (bounded sample)
     if not args.no_cpu:

@@ -170,6 +170,25 @@ int vt_gemm_f64_round_log(int transA, int transB, int64_t M, int64_t N, int64_t 
                           void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * The same layer for operands that are batched on two levels, as the attention scores of a
+ * transformer are: Q and K of head h of sequence b are column slices of one QKV activation
+ * [sequence][token][3][head][64], so consecutive heads lie strideA apart and consecutive sequences
+ * strideA_outer apart.  Matrix (o, i), o < batch_outer, i < batch_inner, reads
+ *   A + o * strideA_outer + i * strideA   and   B + o * strideB_outer + i * strideB;
+ * its outputs are batch element b = o * batch_inner + i of C32 / C64_debug / the log, exactly as
+ * vt_gemm_f64_round_log numbers them (ws is sized with batch = batch_inner * batch_outer).  One call
+ * keeps every compute unit busy where one call per sequence would not.  Everything else as above.
+ */
+int vt_gemm_f64_round_log_nested(int transA, int transB, int64_t M, int64_t N, int64_t K, double alpha,
+                                 const double *A, int64_t lda, int64_t strideA, int64_t strideA_outer,
+                                 const double *B, int64_t ldb, int64_t strideB, int64_t strideB_outer,
+                                 const double *bias, int64_t batch_inner, int64_t batch_outer,
+                                 float *C32, int64_t ldc, int64_t strideC,
+                                 double *C64_debug, int variant,
+                                 double tau_ulp, const vt_log *log,
+                                 void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * A convolution layer fused with the trainer hook (the paper's other example of an
  * "intermediate computation": Method, rounding after e.g. a convolution; Experiments, ResNet-50;
  * Algorithm "train" rounds and logs forward outputs and gradients alike).  The layer is the GEMM

@@ -74,6 +74,10 @@ def load_library():
     L.vt_gemm_f64_round_log.restype = cint
     L.vt_gemm_f64_round_log.argtypes = [cint, cint, i64, i64, i64, dbl, vp, i64, i64, vp, i64, i64, vp, i64,
                                         vp, i64, i64, vp, cint, dbl, C.POINTER(_VtLog), vp, C.c_size_t, vp]
+    L.vt_gemm_f64_round_log_nested.restype = cint
+    L.vt_gemm_f64_round_log_nested.argtypes = [cint, cint, i64, i64, i64, dbl, vp, i64, i64, i64, vp, i64, i64, i64, vp,
+                                               i64, i64, vp, i64, i64, vp, cint, dbl, C.POINTER(_VtLog), vp,
+                                               C.c_size_t, vp]
     L.vt_conv2d_f64_round_log.restype = cint
     L.vt_conv2d_f64_round_log.argtypes = [cint, C.POINTER(Conv2d), i64, vp, vp, vp, vp, vp, cint, dbl,
                                           C.POINTER(_VtLog), vp, C.c_size_t, vp]
@@ -243,6 +247,39 @@ def vt_gemm_f64_round_log(transA: bool, transB: bool, M: int, N: int, K: int, al
         _ptr(bias, torch.float64), int(batch), _ptr(C32, torch.float32), int(ldc), int(strideC),
         _ptr(C64_debug, torch.float64), int(variant), float(tau_ulp), C.byref(clog),
         _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "vt_gemm_f64_round_log")
+
+
+def vt_gemm_f64_round_log_nested(transA: bool, transB: bool, M: int, N: int, K: int, alpha: float,
+                                 A: torch.Tensor, lda: int, strideA: int, strideA_outer: int,
+                                 B: torch.Tensor, ldb: int, strideB: int, strideB_outer: int,
+                                 bias, batch_inner: int, batch_outer: int, C32: torch.Tensor, ldc: int, strideC: int,
+                                 C64_debug, variant: int, tau_ulp: float, log: Log, ws: torch.Tensor, stream=None):
+    batch = batch_inner * batch_outer
+
+    def need(rows, cols, ld, s_in, s_out):
+        if rows == 0 or cols == 0 or batch == 0:
+            return 0
+        return (batch_outer - 1) * s_out + (batch_inner - 1) * s_in + (rows - 1) * ld + cols
+    if A.numel() < need(K if transA else M, M if transA else K, lda, strideA, strideA_outer):
+        raise VtError("A is smaller than the shape, pitches and batch strides imply")
+    if B.numel() < need(N if transB else K, K if transB else N, ldb, strideB, strideB_outer):
+        raise VtError("B is smaller than the shape, pitches and batch strides imply")
+    if batch and M and N and C32.numel() < (batch - 1) * strideC + (M - 1) * ldc + N:
+        raise VtError("C32 is smaller than M, N, ldc, strideC and the batch imply")
+    if bias is not None and bias.numel() < N:
+        raise VtError("bias is shorter than N")
+    if C64_debug is not None and C64_debug.numel() < M * N * batch:
+        raise VtError("C64_debug is smaller than M*N*batch")
+    if log.dense is not None and log.dense.numel() < (M * N * batch + 4) // 5:
+        raise VtError("dense log is smaller than ceil(M*N*batch/5) bytes")
+    clog = log._c()
+    _check(load_library().vt_gemm_f64_round_log_nested(
+        int(bool(transA)), int(bool(transB)), int(M), int(N), int(K), float(alpha),
+        _ptr(A, torch.float64), int(lda), int(strideA), int(strideA_outer),
+        _ptr(B, torch.float64), int(ldb), int(strideB), int(strideB_outer),
+        _ptr(bias, torch.float64), int(batch_inner), int(batch_outer), _ptr(C32, torch.float32), int(ldc), int(strideC),
+        _ptr(C64_debug, torch.float64), int(variant), float(tau_ulp), C.byref(clog),
+        _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "vt_gemm_f64_round_log_nested")
 
 
 def vt_conv2d_gemm_shape(d: Conv2d, Cout: int, mode: int):

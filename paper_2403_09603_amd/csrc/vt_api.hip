@@ -261,19 +261,19 @@ int vt_round_replay_dense_br(const double *x, uint64_t n, const uint8_t *tlog, i
     return hip_status(e);
 }
 
-int vt_gemm_f64_round_log(int transA, int transB, int64_t M, int64_t N, int64_t K, double alpha,
-                          const double *A, int64_t lda, int64_t strideA,
-                          const double *B, int64_t ldb, int64_t strideB,
-                          const double *bias, int64_t batch,
-                          float *C32, int64_t ldc, int64_t strideC,
-                          double *C64_debug, int variant,
-                          double tau_ulp, const vt_log *log,
-                          void *ws, size_t ws_bytes, void *hip_stream)
+// shared by the two GEMM entry points: batch_inner = 0 means one level of batching
+static int gemm_entry(int transA, int transB, int64_t M, int64_t N, int64_t K, double alpha,
+                      const double *A, int64_t lda, int64_t strideA, const double *B, int64_t ldb, int64_t strideB,
+                      const double *bias, int64_t batch, int64_t batch_inner, int64_t strideA_outer, int64_t strideB_outer,
+                      float *C32, int64_t ldc, int64_t strideC, double *C64_debug, int variant,
+                      double tau_ulp, const vt_log *log, void *ws, size_t ws_bytes, void *hip_stream)
 {
     const uint32_t thr = vt_thr_from_tau(tau_ulp);
     if (thr == 0xFFFFFFFFu || !log_ok(log)) return VT_ERR_INVALID_ARG;
     if (M < 0 || N < 0 || K < 0 || batch < 0 || variant < 0 || variant > 1) return VT_ERR_INVALID_ARG;
     if ((transA != 0 && transA != 1) || (transB != 0 && transB != 1)) return VT_ERR_INVALID_ARG;
+    if (batch_inner < 0 || strideA_outer < 0 || strideB_outer < 0) return VT_ERR_INVALID_ARG;
+    if (batch_inner > 0 && batch % batch_inner != 0) return VT_ERR_INVALID_ARG;     // whole groups only
     if ((unsigned __int128)M * (unsigned __int128)N * (unsigned __int128)batch >= ((unsigned __int128)1 << 32))
         return VT_ERR_INVALID_ARG;          // log indices are 32-bit
     const uint64_t total = (uint64_t)M * (uint64_t)N * (uint64_t)batch;
@@ -293,8 +293,39 @@ int vt_gemm_f64_round_log(int transA, int transB, int64_t M, int64_t N, int64_t 
     g.transA = transA; g.transB = transB; g.M = M; g.N = N; g.K = K; g.alpha = alpha;
     g.A = A; g.lda = lda; g.strideA = strideA; g.B = B; g.ldb = ldb; g.strideB = strideB;
     g.bias = bias; g.batch = batch; g.C32 = C32; g.ldc = ldc; g.strideC = strideC;
+    g.batch_inner = batch_inner; g.strideA2 = strideA_outer; g.strideB2 = strideB_outer;
     g.C64 = C64_debug; g.variant = variant; g.thr = thr;
     return run_gemm(g, log, ws, ws_bytes, s);
+}
+
+int vt_gemm_f64_round_log(int transA, int transB, int64_t M, int64_t N, int64_t K, double alpha,
+                          const double *A, int64_t lda, int64_t strideA,
+                          const double *B, int64_t ldb, int64_t strideB,
+                          const double *bias, int64_t batch,
+                          float *C32, int64_t ldc, int64_t strideC,
+                          double *C64_debug, int variant,
+                          double tau_ulp, const vt_log *log,
+                          void *ws, size_t ws_bytes, void *hip_stream)
+{
+    return gemm_entry(transA, transB, M, N, K, alpha, A, lda, strideA, B, ldb, strideB, bias, batch, 0, 0, 0, C32, ldc,
+                      strideC, C64_debug, variant, tau_ulp, log, ws, ws_bytes, hip_stream);
+}
+
+int vt_gemm_f64_round_log_nested(int transA, int transB, int64_t M, int64_t N, int64_t K, double alpha,
+                                 const double *A, int64_t lda, int64_t strideA, int64_t strideA_outer,
+                                 const double *B, int64_t ldb, int64_t strideB, int64_t strideB_outer,
+                                 const double *bias, int64_t batch_inner, int64_t batch_outer,
+                                 float *C32, int64_t ldc, int64_t strideC,
+                                 double *C64_debug, int variant,
+                                 double tau_ulp, const vt_log *log,
+                                 void *ws, size_t ws_bytes, void *hip_stream)
+{
+    if (batch_inner < 0 || batch_outer < 0) return VT_ERR_INVALID_ARG;
+    if ((unsigned __int128)batch_inner * (unsigned __int128)batch_outer >= ((unsigned __int128)1 << 32)) return VT_ERR_INVALID_ARG;
+    const int64_t batch = batch_inner * batch_outer;
+    return gemm_entry(transA, transB, M, N, K, alpha, A, lda, strideA, B, ldb, strideB, bias, batch, batch_inner,
+                      strideA_outer, strideB_outer, C32, ldc, strideC, C64_debug, variant, tau_ulp, log, ws, ws_bytes,
+                      hip_stream);
 }
 
 int vt_conv2d_gemm_shape(const vt_conv2d *d, int64_t Cout, int mode, int64_t *M, int64_t *N, int64_t *K)

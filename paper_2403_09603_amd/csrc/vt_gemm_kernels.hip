@@ -116,6 +116,8 @@ hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, con
     p.pl_logged = pl.logged; p.pl_dir = pl.dir;
     p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc;
     p.strideA = g.strideA; p.strideB = g.strideB; p.strideC = g.strideC; p.batch = g.batch;
+    p.batch_inner = (uint32_t)(g.batch_inner > 0 ? g.batch_inner : (g.batch > 0 ? g.batch : 1));
+    p.strideA2 = g.strideA2; p.strideB2 = g.strideB2;
     p.alpha = g.alpha; p.thr = g.thr; p.wpr = pl.wpr; p.variant = g.variant;
     p.splits = plan.splits; p.kt_per_split = plan.kt_per_split; p.raw = g.raw ? 1 : 0;
     p.tilesM = (uint32_t)((g.M + t.bm - 1) / t.bm);
@@ -126,8 +128,8 @@ hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, con
     if (total > 0x7FFFFFFFull) return hipErrorInvalidValue;
     p.tiles_per_split = (uint32_t)per_split;
     p.total_blocks = (uint32_t)total;
-    p.vecA = ((uintptr_t)g.A % 16 == 0) && (g.lda % 2 == 0) && (g.strideA % 2 == 0);
-    p.vecB = ((uintptr_t)g.B % 16 == 0) && (g.ldb % 2 == 0) && (g.strideB % 2 == 0);
+    p.vecA = ((uintptr_t)g.A % 16 == 0) && (g.lda % 2 == 0) && (g.strideA % 2 == 0) && (g.strideA2 % 2 == 0);
+    p.vecB = ((uintptr_t)g.B % 16 == 0) && (g.ldb % 2 == 0) && (g.strideB % 2 == 0) && (g.strideB2 % 2 == 0);
     const bool kcb = g.transB != 0;
     int am = g.transA ? 0 : 1;
     p.conv = ConvGeom{};

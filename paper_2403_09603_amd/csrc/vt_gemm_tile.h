@@ -48,6 +48,8 @@ struct GemmParams {
     double *partial;                            // split-K slabs [split][batch][M][N]
     uint64_t *pl_logged, *pl_dir;
     int64_t M, N, K, lda, ldb, ldc, strideA, strideB, strideC, batch;
+    int64_t strideA2, strideB2;                 // operand offsets between groups of batch_inner matrices
+    uint32_t batch_inner;                       // matrix b uses group b / batch_inner, member b % batch_inner
     double alpha;
     uint32_t thr, wpr, tilesM, tilesN, tiles_per_split, total_blocks;
     int variant, vecA, vecB, splits, kt_per_split, raw;
@@ -213,8 +215,9 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
     const uint32_t tn_ = (pin % width) / gsz;
     const int64_t bm = (int64_t)tm_ * BM, bn = (int64_t)tn_ * BN;
 
-    const double *A = p.A + (int64_t)b * p.strideA;
-    const double *B = p.B + (int64_t)b * p.strideB;
+    const uint32_t b_out = b / p.batch_inner, b_in = b - b_out * p.batch_inner;
+    const double *A = p.A + (int64_t)b_out * p.strideA2 + (int64_t)b_in * p.strideA;
+    const double *B = p.B + (int64_t)b_out * p.strideB2 + (int64_t)b_in * p.strideB;
 
     d4 acc[TM][4];
 #pragma unroll

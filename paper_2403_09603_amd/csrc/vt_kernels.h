@@ -116,6 +116,8 @@ struct GemmArgs {
     const double *B; int64_t ldb, strideB;
     const double *bias;
     int64_t batch;
+    int64_t batch_inner = 0;          // > 0: matrix b = (group b / batch_inner, member b % batch_inner); groups are
+    int64_t strideA2 = 0, strideB2 = 0;   // strideA2 / strideB2 apart, members strideA / strideB
     float *C32; int64_t ldc, strideC;
     double *C64;          // optional dense FP64 copy (pitch N)
     int variant;

@@ -215,28 +215,50 @@ __global__ __launch_bounds__(256) void replay_dense_kernel(const double *__restr
     else replay_dense_chunk<false, VEC, K0>(x, n, tlog, y, base, lane, codes[wv], k);
 }
 
-// Decision bit-planes of a dense (rows x ncols) output -> packed ternary log; one thread per byte.
+// Decision bit-planes of a dense (rows x ncols) output -> packed ternary log.  One thread per four
+// bytes (twenty outputs, one 32-bit store); the plane words of the current 64 columns stay in
+// registers and are reloaded only when the walk leaves them.
 __global__ __launch_bounds__(256) void planes_to_dense_kernel(const uint64_t *__restrict__ logged,
                                                               const uint64_t *__restrict__ dir, uint32_t wpr,
                                                               uint32_t ncols, uint64_t total, uint8_t *__restrict__ tlog)
 {
-    const uint64_t k = (uint64_t)blockIdx.x * 256u + threadIdx.x;
-    if (k * 5 >= total) return;
-    uint32_t byte = 0, weight = 1;
-    uint32_t row = (uint32_t)((k * 5) / ncols), col = (uint32_t)((k * 5) % ncols);
+    const uint64_t q = (uint64_t)blockIdx.x * 256u + threadIdx.x;       // 32-bit word of the log
+    const uint64_t e0 = q * 20u;
+    if (e0 >= total) return;
+    uint32_t row = (uint32_t)(e0 / ncols), col = (uint32_t)(e0 % ncols);
+    uint64_t wl = 0, wd = 0;
+    bool have = false;
+    uint32_t word = 0;
 #pragma unroll
-    for (int j = 0; j < 5; ++j) {
-        uint32_t code = 1;
-        if (k * 5 + (uint64_t)j < total) {
-            const uint64_t w = (uint64_t)row * wpr + (col >> 6);
-            const uint32_t lg = (uint32_t)(logged[w] >> (col & 63u)) & 1u, up = (uint32_t)(dir[w] >> (col & 63u)) & 1u;
-            code = lg ? 2u * up : 1u;
+    for (int by = 0; by < 4; ++by) {
+        uint32_t byte = 0, weight = 1;
+#pragma unroll
+        for (int j = 0; j < 5; ++j) {
+            uint32_t code = 1;
+            if (e0 + (uint64_t)(5 * by + j) < total) {
+                if (!have) {
+                    const uint64_t w = (uint64_t)row * wpr + (col >> 6);
+                    wl = logged[w];
+                    wd = dir[w];
+                    have = true;
+                }
+                const uint32_t lg = (uint32_t)(wl >> (col & 63u)) & 1u, up = (uint32_t)(wd >> (col & 63u)) & 1u;
+                code = lg ? 2u * up : 1u;
+                ++col;
+                if ((col & 63u) == 0) have = false;
+                if (col == ncols) { col = 0; ++row; have = false; }
+            }
+            byte += code * weight;
+            weight *= 3u;
         }
-        byte += code * weight;
-        weight *= 3u;
-        if (++col == ncols) { col = 0; ++row; }
+        word |= byte << (8 * by);
     }
-    tlog[k] = (uint8_t)byte;
+    const uint64_t nbytes = (total + 4) / 5;
+    if (4 * q + 4 <= nbytes) {
+        *(uint32_t *)(tlog + 4 * q) = word;
+    } else {                                          // the log ends inside this word
+        for (uint64_t i = 4 * q; i < nbytes; ++i) tlog[i] = (uint8_t)(word >> (8 * (i - 4 * q)));
+    }
 }
 
 }  // namespace
@@ -322,8 +344,8 @@ hipError_t launch_planes_to_dense(const Planes &pl, uint64_t rows, uint8_t *tlog
 {
     const uint64_t total = rows * (uint64_t)pl.ncols;
     if (total == 0) return hipSuccess;
-    const uint64_t bytes = (total + 4) / 5;
-    planes_to_dense_kernel<<<(uint32_t)((bytes + 255) / 256), 256, 0, s>>>(pl.logged, pl.dir, pl.wpr, pl.ncols, total,
+    const uint64_t words = (total + 19) / 20;
+    planes_to_dense_kernel<<<(uint32_t)((words + 255) / 256), 256, 0, s>>>(pl.logged, pl.dir, pl.wpr, pl.ncols, total,
                                                                          tlog);
     return hipGetLastError();
 }

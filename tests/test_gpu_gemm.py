@@ -202,3 +202,52 @@ def test_log_capacity_overflow(G):
     assert np.array_equal(cut["idx"], full["idx"][:1000])
     assert np.array_equal(_dir_bits(cut["dir"], 1000), _dir_bits(full["dir"], 1000))
     assert np.array_equal(_bits(cut["C32"]), _bits(full["C32"]))
+
+
+@pytest.mark.parametrize("T,variant", [(96, 0), (200, 1)])
+def test_nested_batch_attention_scores(T, variant):
+    """Two-level batching: scores Q K^T / 8 for every (sequence, head) of one QKV activation in one call.
+    FP64 values against the oracle per matrix, everything after them bit-exact, and the whole result
+    bit-identical to one call per sequence."""
+    import torch
+    import paper_2403_09603_amd as vt
+    Bo, H, DH = 3, 4, 64
+    D = H * DH
+    g = si.rng(si.seed_for(3, 7) + T)
+    qkv = g.standard_normal((Bo, T, 3 * D)).astype(np.float32).astype(np.float64)
+    tau = 2.0 ** -4
+    qd = torch.from_numpy(qkv).cuda().reshape(-1)
+    total = Bo * H * T * T
+    C32 = torch.empty(total, dtype=torch.float32, device="cuda")
+    C64 = torch.empty(total, dtype=torch.float64, device="cuda")
+    log = vt.alloc_log(total)
+    ws = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG, T, T, DH, Bo * H))
+    vt.vt_gemm_f64_round_log_nested(False, True, T, T, DH, 0.125, qd, 3 * D, DH, T * 3 * D, qd[D:], 3 * D, DH, T * 3 * D,
+                                    None, H, Bo, C32, T, T * T, C64, variant, tau, log, ws)
+    torch.cuda.synchronize()
+    c64 = C64.cpu().numpy().reshape(Bo, H, T, T)
+    for o in range(Bo):
+        for h in range(H):
+            q = np.ascontiguousarray(qkv[o, :, h * DH:(h + 1) * DH])
+            k = np.ascontiguousarray(qkv[o, :, D + h * DH: D + (h + 1) * DH])
+            truth = vo.gemm_f64(q, np.ascontiguousarray(k.T), alpha=0.125, order=2)
+            bound = 1e-12 * 0.125 * np.outer(np.linalg.norm(q, axis=1), np.linalg.norm(k, axis=1))
+            assert np.all(np.abs(c64[o, h] - truth) <= bound + 1e-300), (o, h)
+    cnt = int(log.count.item())
+    yo, io, do, co = vo.round_log(c64.ravel(), tau)
+    assert cnt == co and cnt > 0
+    assert np.array_equal(C32.cpu().numpy().view(np.uint32), yo.view(np.uint32))
+    assert np.array_equal(log.idx.cpu().numpy().view(np.uint32)[:cnt], io)
+    nw = (cnt + 31) // 32
+    assert np.array_equal(np.unpackbits(log.dir.cpu().numpy().view(np.uint8)[:4 * nw], bitorder="little")[:cnt],
+                          np.unpackbits(do.view(np.uint8)[:4 * nw], bitorder="little")[:cnt])
+    # one call per sequence gives the same bits
+    for o in range(Bo):
+        c32o = torch.empty(H * T * T, dtype=torch.float32, device="cuda")
+        c64o = torch.empty(H * T * T, dtype=torch.float64, device="cuda")
+        logo = vt.alloc_log(H * T * T)
+        vt.vt_gemm_f64_round_log(False, True, T, T, DH, 0.125, qd[o * T * 3 * D:], 3 * D, DH, qd[o * T * 3 * D + D:], 3 * D,
+                                 DH, None, H, c32o, T, T * T, c64o, variant, tau, logo, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(c64o.view(torch.int64), C64[o * H * T * T:(o + 1) * H * T * T].view(torch.int64))
+        assert torch.equal(c32o.view(torch.int32), C32[o * H * T * T:(o + 1) * H * T * T].view(torch.int32))

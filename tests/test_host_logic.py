@@ -289,3 +289,25 @@ def test_hash_entry_points_validate_on_the_host(hiplib):
     assert 32 * (n // chunk) <= need <= 32 * (n // chunk) * 1.02 + 1024
     assert L.vt_workspace_bytes(6, 1, 100, 4096, 1) == 256
     assert L.vt_workspace_bytes(7, 1, 1001, 0, 1) >= 2 * 32 * 501
+
+
+def test_nested_batch_validation_on_the_host(hiplib):
+    L = hiplib
+    vp, i64, dbl, cint = C.c_void_p, C.c_int64, C.c_double, C.c_int
+    from paper_2403_09603_amd.binding import _VtLog
+    L.vt_gemm_f64_round_log_nested.restype = cint
+    L.vt_gemm_f64_round_log_nested.argtypes = [cint, cint, i64, i64, i64, dbl, vp, i64, i64, i64, vp, i64, i64, i64, vp,
+                                               i64, i64, vp, i64, i64, vp, cint, dbl, C.POINTER(_VtLog), vp,
+                                               C.c_size_t, vp]
+    fake = 0x10000
+    log = _VtLog(fake, fake, 1 << 20, fake, None, 32)
+
+    def call(inner=4, outer=3, sAo=1000, sBo=1000, M=16, N=16, K=8):
+        return L.vt_gemm_f64_round_log_nested(0, 0, M, N, K, 1.0, fake, K, 64, sAo, fake, N, 64, sBo, None, inner, outer,
+                                              fake, N, M * N, None, 0, 0.1, C.byref(log), None, 0, None)
+    assert call(inner=-1) == 1
+    assert call(outer=-1) == 1
+    assert call(sAo=-5) == 1
+    assert call(sBo=-5) == 1
+    assert call(inner=1 << 20, outer=1 << 20) == 1          # more than 2^32 matrices
+    assert call() == 2                                       # valid arguments reach the workspace check
