@@ -108,6 +108,32 @@ __device__ __forceinline__ FastDecision decide_fast(double x)
     return o;
 }
 
+// The same decision with the threshold test folded into one subtraction and one unsigned compare,
+// and the direction taken by value: D(x) < thr  <=>  (r - c0) <u c1 with c0 = 2^28 - thr + 1 and
+// c1 = 2 thr - 1 (thr = 0: c1 = 0, never true), since |r - 2^28| < thr means r lies in
+// [2^28 - thr + 1, 2^28 + thr - 1]; and rnd(x) > x is asked of the converted value itself (exact:
+// every float is a double).  Four vector instructions fewer per output than decide_fast + compares,
+// which is what the GEMM epilogue is made of.
+struct FastLogged {
+    float y;
+    bool logged, up, slow;
+};
+
+static __host__ __device__ __forceinline__ uint32_t thr_window_base(uint32_t thr) { return kHalf - thr + 1u; }
+static __host__ __device__ __forceinline__ uint32_t thr_window_size(uint32_t thr) { return thr ? 2u * thr - 1u : 0u; }
+
+__device__ __forceinline__ FastLogged decide_fast_window(double x, uint32_t c0, uint32_t c1)
+{
+    const uint64_t bits = (uint64_t)__double_as_longlong(x);
+    const uint32_t hi = (uint32_t)(bits >> 32), lo = (uint32_t)bits;
+    FastLogged o;
+    o.slow = ((hi & 0x7FFFFFFFu) - (897u << 20)) >= ((1151u - 897u) << 20);
+    o.logged = ((lo & kMask29) - c0) < c1;
+    o.y = (float)x;
+    o.up = (double)o.y > x;
+    return o;
+}
+
 // Replay of one logged element (primitive "rev"): the FP32 neighbour of x on the logged side,
 // i.e. x rounded toward +inf (dir = 1) or toward -inf (dir = 0).
 static __host__ __device__ __forceinline__ uint32_t directed_slow(uint64_t bits, uint32_t dir)

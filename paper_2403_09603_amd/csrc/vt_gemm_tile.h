@@ -371,6 +371,7 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
     if (bm + BM <= p.M && bn + BN <= p.N && p.ldc < (1 << 26) && p.N < (1 << 25)) {
         auto full = [&](auto has64_tag) {
             constexpr bool HAS64 = decltype(has64_tag)::value;
+            const uint32_t win0 = thr_window_base(p.thr), win1 = thr_window_size(p.thr);
             char *c32_row = (char *)(p.C32 + (int64_t)b * p.strideC + row0 * p.ldc + col0);      // uniform, row 4 r of block i
             char *c64_row = HAS64 ? (char *)(p.C64 + ((int64_t)b * p.M + row0) * p.N + col0) : nullptr;
             const uint32_t step32 = (uint32_t)p.ldc * 16u, step64 = (uint32_t)p.N * 32u;         // four rows further
@@ -393,10 +394,10 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         c[j] = p.alpha * acc[i][j][r] + bias_f[j];
-                        const FastDecision f = decide_fast(c[j]);
+                        const FastLogged f = decide_fast_window(c[j], win0, win1);
                         yb[j] = __float_as_uint(f.y);
-                        lg[j] = __ballot(f.D < p.thr);
-                        dr[j] = __ballot(f.grow != f.neg) & lg[j];
+                        lg[j] = __ballot(f.logged);
+                        dr[j] = __ballot(f.up) & lg[j];
                         slow[j] = __ballot(f.slow);
                         any_slow |= slow[j];
                     }

@@ -61,3 +61,10 @@ extern "C" void h_sha256(const uint8_t *data, uint64_t len, uint8_t *digest)
         __builtin_memcpy(digest + 4 * i, &v, 4);
     }
 }
+
+// the GEMM epilogue's form of the threshold test: (r - c0) <u c1 on the 29 dropped bits
+extern "C" void h_window_test(const uint32_t *r, uint64_t n, uint32_t thr, uint8_t *logged)
+{
+    const uint32_t c0 = vt::thr_window_base(thr), c1 = vt::thr_window_size(thr);
+    for (uint64_t i = 0; i < n; ++i) logged[i] = (uint8_t)(((r[i] & vt::kMask29) - c0) < c1);
+}

@@ -311,3 +311,18 @@ def test_nested_batch_validation_on_the_host(hiplib):
     assert call(sBo=-5) == 1
     assert call(inner=1 << 20, outer=1 << 20) == 1          # more than 2^32 matrices
     assert call() == 2                                       # valid arguments reach the workspace check
+
+
+def test_threshold_window_form_equals_the_distance_test(harith):
+    """The fused epilogue tests D(x) < thr as one subtraction and one unsigned compare on the dropped bits;
+    against |r - 2^28| < thr for every threshold size class and every r near the edges of the window."""
+    half = 1 << 28
+    rng = np.random.default_rng(12)
+    for thr in [0, 1, 2, 3, 31, 32, 33, 1 << 20, (1 << 28) - 1, 1 << 28]:
+        near = np.array([half + s * (thr + d) for s in (-1, 1) for d in range(-3, 4)] + [0, 1, half - 1, half, half + 1,
+                        (1 << 29) - 1], dtype=np.int64)
+        r = np.concatenate([near[(near >= 0) & (near < (1 << 29))], rng.integers(0, 1 << 29, 20000)]).astype(np.uint32)
+        out = np.zeros(r.size, np.uint8)
+        harith.h_window_test(_u32p(r), C.c_uint64(r.size), C.c_uint32(thr), out.ctypes.data_as(C.POINTER(C.c_uint8)))
+        expect = np.abs(r.astype(np.int64) - half) < thr
+        assert np.array_equal(out.astype(bool), expect), thr
