@@ -365,6 +365,12 @@ int vt_conv2d_f64_round_log(int mode, const vt_conv2d *d, int64_t Cout, const do
     g.A = X; g.lda = 0; g.strideA = 0; g.B = B; g.ldb = Cout; g.strideB = 0;
     g.bias = bias; g.batch = 1; g.C32 = C32; g.ldc = Cout; g.strideC = 0;
     g.C64 = C64_debug; g.variant = variant; g.thr = thr;
+    if (c.KH == 1 && c.KW == 1 && c.stride_h == 1 && c.stride_w == 1 && c.pad_h == 0 && c.pad_w == 0) {
+        // a 1 x 1 filter at every position: the im2col matrix is the image itself, rows (n, h, w) by
+        // channels, so the plain operand loader (no address arithmetic in the loop) reads it as it lies
+        g.conv = nullptr;
+        g.lda = c.C;
+    }
     return run_gemm(g, log, ws, ws_bytes, s);
 }
 

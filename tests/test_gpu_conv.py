@@ -105,6 +105,8 @@ SMALL = [  # (N, H, W, C, KH, KW, Cout, stride, pad, dil)
     (1, 10, 13, 3, 3, 2, 2, (2, 1), (1, 0), (1, 2)),
     (1, 9, 9, 2, 3, 3, 2, 1, 2, 2),
     (1, 4, 4, 1, 5, 5, 1, 1, 2, 1),
+    (2, 9, 7, 5, 1, 1, 6, 1, 0, 1),          # 1 x 1 at every position, odd channel count: the plain-matrix route
+    (3, 20, 17, 64, 1, 1, 70, 1, 0, 3),      # the same with whole tiles, a ragged edge, and a dilation that cannot matter
 ]
 
 
