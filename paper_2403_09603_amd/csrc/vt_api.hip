@@ -76,11 +76,12 @@ int round_log_flat(const double *x, uint64_t n, uint32_t thr, float *y, const vt
 // planes already hold the decisions: count per segment (unless the producer did), scan, compact
 int finish_log(const vt::Planes &pl, uint64_t rows, const vt_log *log, bool counted, hipStream_t s)
 {
+    if (log->dense) return hip_status(vt::launch_planes_to_dense(pl, rows, log->dense, log->count, s));   // also writes *count
     const vt::LogOut lo{log->idx, log->dir, log->cap, log->count};
     hipError_t e = hipSuccess;
     if (!counted) e = vt::launch_seg_count(pl, s);
     if (e == hipSuccess) e = vt::launch_seg_scan(pl, lo, s);                 // also writes *count
-    if (e == hipSuccess) e = log->dense ? vt::launch_planes_to_dense(pl, rows, log->dense, s) : vt::launch_compact(pl, lo, s);
+    if (e == hipSuccess) e = vt::launch_compact(pl, lo, s);
     return hip_status(e);
 }
 
@@ -101,13 +102,24 @@ int run_gemm(vt::GemmArgs &g, const vt_log *log, void *ws, size_t ws_bytes, hipS
     if (plan.splits > 1 || two_pass) {
         // slabs -> fixed-order sum (alpha, bias) -> standalone round/log over the flat result
         double *partial = (double *)((char *)ws + planes);
-        double *reduced = partial + (uint64_t)plan.splits * total;
+        // A few slabs are summed inside the round/log pass (when its 16-byte accesses are legal); many
+        // slabs of a small output go through a kernel of their own first, which has a thread per
+        // output and more loads in flight (measured on the ResNet-50 weight gradients: summing 64 to
+        // 256 slabs in the pass made those calls up to twice as long).
+        const bool sum_in_pass = plan.splits <= 8 && (total % 2 == 0) && aligned(g.C32, 8) && (!g.C64 || aligned(g.C64, 16));
+        double *reduced = sum_in_pass ? nullptr : partial + (uint64_t)plan.splits * total;
         void *ws_rl = (char *)partial + vt::gemm_split_bytes(M, N, batch, plan.splits);
         mark_begin(s);
         const hipError_t e2 = vt::launch_gemm_round_planes(g, plan, pl, partial, reduced, s);
         mark_end(s);
         if (e2 != hipSuccess) return VT_ERR_HIP;
-        return round_log_flat(reduced, total, g.thr, g.C32, log, ws_rl, s, /*mark=*/false);
+        if (!sum_in_pass) return round_log_flat(reduced, total, g.thr, g.C32, log, ws_rl, s, /*mark=*/false);
+        const vt::SplitKArgs a{partial, total, plan.splits, g.variant, g.alpha, g.bias, (uint32_t)N, g.C64};
+        const uint32_t k = k_of(log->b_r);
+        if (log->dense)
+            return hip_status(vt::launch_splitk_log_dense(a, total, g.thr, k, g.C32, log->dense, log->count, (uint64_t *)ws_rl, s));
+        return hip_status(vt::launch_splitk_log_onepass(a, total, g.thr, k, g.C32, ws_rl,
+                                                        vt::LogOut{log->idx, log->dir, log->cap, log->count}, s));
     }
     mark_begin(s);
     hipError_t e = vt::launch_gemm_round_planes(g, plan, pl, nullptr, nullptr, s);

@@ -148,7 +148,7 @@ hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, con
     case 1: e = launch_gemm_64x128(p, am, kcb, s); break;
     default: e = launch_gemm_64x64(p, am, kcb, s); break;
     }
-    if (e != hipSuccess || (plan.splits <= 1 && !g.raw)) return e;
+    if (e != hipSuccess || (plan.splits <= 1 && !g.raw) || !reduced) return e;     // no `reduced`: the caller sums the slabs itself
     const uint64_t slab = (uint64_t)g.M * g.N * g.batch;
     splitk_reduce_kernel<<<(uint32_t)((slab + 255) / 256), 256, 0, s>>>(partial, slab, plan.splits, g.variant, g.alpha,
                                                                       g.bias, (uint32_t)g.N, reduced, g.C64);

@@ -59,7 +59,7 @@ size_t dense_count_bytes();   // scratch for the logged-output count of the call
 hipError_t launch_round_log_dense(const double *x, uint64_t n, uint32_t thr, uint32_t k, float *y, uint8_t *tlog,
                                   uint64_t *n_logged, uint64_t *slots, hipStream_t s);
 hipError_t launch_replay_dense(const double *x, uint64_t n, const uint8_t *tlog, uint32_t k, float *y, hipStream_t s);
-hipError_t launch_planes_to_dense(const Planes &pl, uint64_t rows, uint8_t *tlog, hipStream_t s);
+hipError_t launch_planes_to_dense(const Planes &pl, uint64_t rows, uint8_t *tlog, uint64_t *count, hipStream_t s);
 
 // ---- element-wise and row-wise layers fused with the trainer hook -----------------------------
 // Layer selectors (the public VT_LAYER_* values).
@@ -98,6 +98,17 @@ hipError_t launch_sha256_tree(const uint8_t *data, uint64_t nbytes, uint64_t chu
 size_t merkle_root_bytes(uint64_t n_leaves);
 hipError_t launch_merkle_root(const uint32_t *leaves, uint64_t n_leaves, uint32_t *root, void *ws, hipStream_t s);
 
+// the trainer hook over the result of a split-K GEMM, summed from its slabs on the fly (slab even,
+// y 8-byte aligned, y64 null or 16-byte aligned); same outputs as the two calls above on the sum
+struct SplitKArgs {
+    const double *partial; uint64_t slab; int splits, variant; double alpha; const double *bias; uint32_t ncols;
+    double *y64;
+};
+hipError_t launch_splitk_log_onepass(const SplitKArgs &a, uint64_t n, uint32_t thr, uint32_t k, float *y, void *ws,
+                                     const LogOut &log, hipStream_t s);
+hipError_t launch_splitk_log_dense(const SplitKArgs &a, uint64_t n, uint32_t thr, uint32_t k, float *y, uint8_t *tlog,
+                                   uint64_t *n_logged, uint64_t *slots, hipStream_t s);
+
 hipError_t launch_stats(const double *y1, const double *y2, uint64_t n, uint32_t k, uint64_t *out, hipStream_t s);
 
 // Geometry of a channels-last convolution whose image the GEMM kernel reads through an implicit
@@ -134,7 +145,8 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_sp
 size_t gemm_split_bytes(int64_t M, int64_t N, int64_t batch, int splits);
 // splits == 1 and not g.raw: C32 / C64 / planes written by the epilogue.  Otherwise `partial`
 // receives the slabs, `reduced` (and g.C64 if set) the FP64 result alpha * sum + bias; nothing
-// else is written.
+// else is written.  With `reduced` null only the slabs are written (the caller sums them where it
+// consumes them).
 hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, const Planes &pl, double *partial,
                                     double *reduced, hipStream_t s);
 

@@ -217,14 +217,18 @@ __global__ __launch_bounds__(256) void replay_dense_kernel(const double *__restr
 
 // Decision bit-planes of a dense (rows x ncols) output -> packed ternary log.  One thread per four
 // bytes (twenty outputs, one 32-bit store); the plane words of the current 64 columns stay in
-// registers and are reloaded only when the walk leaves them.
+// registers and are reloaded only when the walk leaves them.  The workgroup's number of logged
+// outputs goes to partial[blockIdx.x] (summed by count_partials_kernel: integer, any order).
 __global__ __launch_bounds__(256) void planes_to_dense_kernel(const uint64_t *__restrict__ logged,
                                                               const uint64_t *__restrict__ dir, uint32_t wpr,
-                                                              uint32_t ncols, uint64_t total, uint8_t *__restrict__ tlog)
+                                                              uint32_t ncols, uint64_t total, uint8_t *__restrict__ tlog,
+                                                              uint32_t *__restrict__ partial)
 {
+    __shared__ uint32_t wave_cnt[4];
     const uint64_t q = (uint64_t)blockIdx.x * 256u + threadIdx.x;       // 32-bit word of the log
     const uint64_t e0 = q * 20u;
-    if (e0 >= total) return;
+    uint32_t n_logged = 0;
+    if (e0 < total) {
     uint32_t row = (uint32_t)(e0 / ncols), col = (uint32_t)(e0 % ncols);
     uint64_t wl = 0, wd = 0;
     bool have = false;
@@ -244,6 +248,7 @@ __global__ __launch_bounds__(256) void planes_to_dense_kernel(const uint64_t *__
                 }
                 const uint32_t lg = (uint32_t)(wl >> (col & 63u)) & 1u, up = (uint32_t)(wd >> (col & 63u)) & 1u;
                 code = lg ? 2u * up : 1u;
+                n_logged += lg;
                 ++col;
                 if ((col & 63u) == 0) have = false;
                 if (col == ncols) { col = 0; ++row; have = false; }
@@ -258,6 +263,28 @@ __global__ __launch_bounds__(256) void planes_to_dense_kernel(const uint64_t *__
         *(uint32_t *)(tlog + 4 * q) = word;
     } else {                                          // the log ends inside this word
         for (uint64_t i = 4 * q; i < nbytes; ++i) tlog[i] = (uint8_t)(word >> (8 * (i - 4 * q)));
+    }
+    }
+    n_logged = wave_sum(n_logged);
+    if ((threadIdx.x & 63u) == 0) wave_cnt[threadIdx.x >> 6] = n_logged;
+    __syncthreads();
+    if (threadIdx.x == 0) partial[blockIdx.x] = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+}
+
+__global__ __launch_bounds__(1024) void count_partials_kernel(const uint32_t *__restrict__ partial, uint32_t n,
+                                                              uint64_t *__restrict__ count)
+{
+    __shared__ uint64_t part[16];
+    uint64_t sum = 0;
+    for (uint32_t i = threadIdx.x; i < n; i += 1024u) sum += partial[i];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sum += (uint64_t)__shfl_xor((unsigned long long)sum, o, 64);
+    if ((threadIdx.x & 63u) == 0) part[threadIdx.x >> 6] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint64_t total = 0;
+        for (int i = 0; i < 16; ++i) total += part[i];
+        *count = total;
     }
 }
 
@@ -310,6 +337,14 @@ hipError_t launch_round_log_dense(const double *x, uint64_t n, uint32_t thr, uin
     return launch_dense_from(PlainSource{x}, vec, n, thr, k, y, tlog, n_logged, slots, s);
 }
 
+hipError_t launch_splitk_log_dense(const SplitKArgs &a, uint64_t n, uint32_t thr, uint32_t k, float *y, uint8_t *tlog,
+                                   uint64_t *n_logged, uint64_t *slots, hipStream_t s)
+{
+    const SplitKSource src{a.partial, a.slab, a.splits, a.variant, a.alpha, a.bias, a.ncols ? a.ncols : 1u,
+                           1.0 / (double)(a.ncols ? a.ncols : 1u), a.y64};
+    return launch_dense_from(src, true, n, thr, k, y, tlog, n_logged, slots, s);
+}
+
 // the same stream with a layer evaluated on the fly as its source (inputs 16-byte aligned)
 hipError_t launch_layer_log_dense(const LayerArgs &g, uint64_t n, uint32_t thr, uint32_t k, float *y, uint8_t *tlog,
                                   uint64_t *n_logged, uint64_t *slots, hipStream_t s)
@@ -340,13 +375,18 @@ hipError_t launch_replay_dense(const double *x, uint64_t n, const uint8_t *tlog,
     return hipGetLastError();
 }
 
-hipError_t launch_planes_to_dense(const Planes &pl, uint64_t rows, uint8_t *tlog, hipStream_t s)
+// also writes *count; uses pl.seg_cnt as scratch (one entry per workgroup of 5120 outputs: never
+// more than the plane has segments of 4096)
+hipError_t launch_planes_to_dense(const Planes &pl, uint64_t rows, uint8_t *tlog, uint64_t *count, hipStream_t s)
 {
     const uint64_t total = rows * (uint64_t)pl.ncols;
-    if (total == 0) return hipSuccess;
     const uint64_t words = (total + 19) / 20;
-    planes_to_dense_kernel<<<(uint32_t)((words + 255) / 256), 256, 0, s>>>(pl.logged, pl.dir, pl.wpr, pl.ncols, total,
-                                                                         tlog);
+    const uint32_t blocks = (uint32_t)((words + 255) / 256);
+    if (blocks)
+        planes_to_dense_kernel<<<blocks, 256, 0, s>>>(pl.logged, pl.dir, pl.wpr, pl.ncols, total, tlog, pl.seg_cnt);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    count_partials_kernel<<<1, 1024, 0, s>>>(pl.seg_cnt, blocks, count);
     return hipGetLastError();
 }
 

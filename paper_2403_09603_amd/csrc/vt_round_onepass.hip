@@ -335,6 +335,14 @@ hipError_t launch_round_log_onepass(const double *x, uint64_t n, uint32_t thr, u
 }
 
 // the same pass with a layer evaluated on the fly as its source (inputs 16-byte, y 8-byte aligned)
+hipError_t launch_splitk_log_onepass(const SplitKArgs &a, uint64_t n, uint32_t thr, uint32_t k, float *y, void *ws,
+                                     const LogOut &log, hipStream_t s)
+{
+    const SplitKSource src{a.partial, a.slab, a.splits, a.variant, a.alpha, a.bias, a.ncols ? a.ncols : 1u,
+                           1.0 / (double)(a.ncols ? a.ncols : 1u), a.y64};
+    return launch_onepass_from(src, n, thr, k, y, ws, log, s);
+}
+
 hipError_t launch_layer_log_onepass(const LayerArgs &g, uint64_t n, uint32_t thr, uint32_t k, float *y, void *ws,
                                     const LogOut &log, hipStream_t s)
 {

@@ -31,6 +31,68 @@ struct PlainSource {
     __device__ __forceinline__ void keep(uint64_t, uint64_t, src_d2) const {}
 };
 
+// The result of a split-K GEMM before its single rounding: the K slices' partial sums (slabs of
+// `slab` doubles, slab even, 16-byte aligned) added in ascending (variant 0) or descending slice
+// order, scaled and biased -- alpha * (P0 + P1 + ...) + bias[column] -- evaluated where the
+// trainer hook consumes it, so the sum never goes to memory (unless y64 asks for a copy).
+struct SplitKSource {
+    const double *P;
+    uint64_t slab;
+    int splits, variant;
+    double alpha;
+    const double *bias;       // per output column, or null
+    uint32_t ncols;
+    double inv_ncols;
+    double *y64;
+    template <bool FULL, bool VEC>
+    __device__ __forceinline__ src_d2 pair(uint64_t e, uint64_t n) const
+    {
+        const bool has0 = FULL || e < n, has1 = FULL || e + 1 < n;
+        src_d2 acc = {0.0, 0.0};
+        if (has0) {
+            auto slice = [&](int k) {
+                const double *p = P + (uint64_t)(variant ? splits - 1 - k : k) * slab + e;
+                src_d2 v;
+                if (has1) v = *(const src_d2 *)p;
+                else { v.x = p[0]; v.y = 0.0; }
+                return v;
+            };
+            int k = 0;
+            for (; k + 4 <= splits; k += 4) {                 // four loads in flight, additions still in order
+                const src_d2 v0 = slice(k), v1 = slice(k + 1), v2 = slice(k + 2), v3 = slice(k + 3);
+                acc.x = acc.x + v0.x; acc.y = acc.y + v0.y;
+                acc.x = acc.x + v1.x; acc.y = acc.y + v1.y;
+                acc.x = acc.x + v2.x; acc.y = acc.y + v2.y;
+                acc.x = acc.x + v3.x; acc.y = acc.y + v3.y;
+            }
+            for (; k < splits; ++k) {
+                const src_d2 v = slice(k);
+                acc.x = acc.x + v.x; acc.y = acc.y + v.y;
+            }
+        }
+        src_d2 c;
+        c.x = alpha * acc.x;
+        c.y = alpha * acc.y;
+        if (bias && has0) {
+            uint32_t r, c0;
+            divmod_u32((uint32_t)e, ncols, inv_ncols, r, c0);
+            const uint32_t c1 = c0 + 1u == ncols ? 0u : c0 + 1u;
+            c.x = c.x + bias[c0];
+            if (has1) c.y = c.y + bias[c1];
+        }
+        if (!has0) c.x = 1.0;
+        if (!has1) c.y = 1.0;
+        return c;
+    }
+    template <bool FULL, bool VEC>
+    __device__ __forceinline__ void keep(uint64_t e, uint64_t n, src_d2 v) const
+    {
+        if (!y64) return;
+        if (FULL || e + 1 < n) *(src_d2 *)(y64 + e) = v;
+        else if (e < n) y64[e] = v.x;
+    }
+};
+
 // One output of a layer from its input value(s); e is the output's linear index (< n).
 template <int OP>
 __device__ __forceinline__ double layer_value(const LayerArgs &g, uint32_t e, double xa, double xb)
