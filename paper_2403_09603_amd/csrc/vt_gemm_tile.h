@@ -138,11 +138,16 @@ __device__ __forceinline__ void tile_offsets(int64_t ld, uint32_t (&off)[R / 32]
 
 template <bool KC, int R>
 __device__ __forceinline__ void load_tile_fast(const char *__restrict__ base, int64_t ld, int64_t k0,
-                                               const uint32_t (&off)[R / 32], d2 (&regs)[R / 32])
+                                               uint32_t (&off)[R / 32], d2 (&regs)[R / 32])
 {
     const char *p = base + (KC ? k0 : k0 * ld) * 8;      // uniform
 #pragma unroll
-    for (int j = 0; j < R / 32; ++j) regs[j] = *(const d2 *)(p + off[j]);
+    for (int j = 0; j < R / 32; ++j) {
+        // the offset is made opaque here so that its zero-extension stays next to the load: the load
+        // then takes the scalar base and the 32-bit lane offset as they are, with no vector add
+        asm volatile("" : "+v"(off[j]));
+        regs[j] = *(const d2 *)(p + off[j]);
+    }
 }
 
 template <bool KC, int R>
