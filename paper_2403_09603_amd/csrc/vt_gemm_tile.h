@@ -306,14 +306,28 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
             const bool more = FAST || it + 1 < nkt;
             const double *As = ldsA + cur * SA + wm * (16 * TM) + (lane & 15);
             const double *Bs = ldsB + cur * SB + wn * 64 + (lane & 15);
-            double a[TM], bb[4];
-#pragma unroll
-            for (int kk = 0; kk < BK / 4; ++kk) {
+            // The narrow tiles have registers to spare: the fragments of group kk + 1 are requested
+            // before the MFMAs of group kk are issued, so an LDS round trip hides behind a whole
+            // group instead of behind its last instruction.  (The large tile has none to spare; there
+            // the compiler interleaves the reads as fragment registers fall free.)
+            constexpr bool PIPE = TM <= 2;
+            double a[PIPE ? 2 : 1][TM], bb[PIPE ? 2 : 1][4];
+            auto frags = [&](int kk, double (&fa)[TM], double (&fb)[4]) {
                 const int krow = kk * 4 + (lane >> 4);
 #pragma unroll
-                for (int i = 0; i < TM; ++i) a[i] = As[krow * PA + i * 16];
+                for (int i = 0; i < TM; ++i) fa[i] = As[krow * PA + i * 16];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) bb[j] = Bs[krow * PB + j * 16];
+                for (int j = 0; j < 4; ++j) fb[j] = Bs[krow * PB + j * 16];
+            };
+            if (PIPE) frags(0, a[0], bb[0]);
+#pragma unroll
+            for (int kk = 0; kk < BK / 4; ++kk) {
+                const int cb = PIPE ? (kk & 1) : 0;
+                if (!PIPE) frags(kk, a[0], bb[0]);
+                else if (kk + 1 < BK / 4) {
+                    frags(kk + 1, a[cb ^ 1], bb[cb ^ 1]);
+                    __builtin_amdgcn_sched_barrier(0);         // keep the reads ahead of this group's MFMAs
+                }
                 if (kk == BK / 4 - 1) {
                     // (the last group's fragments are already requested: LDS completes in order,
                     // so the wave's MFMA stream has no gap before the barrier)
@@ -328,7 +342,7 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], bb[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[cb][i], bb[cb][j], acc[i][j], 0, 0, 0);
             }
             __syncthreads();
         };
