@@ -105,7 +105,8 @@ def test_every_tile_shape_and_split_factor_is_exercised(G):
              (260, 250, 20, 1, False, False),
              (64, 147, 5003, 1, True, False),       # weight-gradient shape: tiny output, long K
              (130, 200, 2600, 1, True, False),
-             (96, 64, 1100, 3, False, True)]
+             (96, 64, 1100, 3, False, True),
+             (2560, 1280, 256, 1, True, False)]      # lands on the 64x128 tile
     for M, N, K, batch, tA, tB in cases:
         plan = vt.vt_gemm_plan(M, N, K, batch, transA=tA)
         seen.add(plan[:2])
