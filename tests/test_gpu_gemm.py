@@ -252,3 +252,43 @@ def test_nested_batch_attention_scores(T, variant):
         torch.cuda.synchronize()
         assert torch.equal(c64o.view(torch.int64), C64[o * H * T * T:(o + 1) * H * T * T].view(torch.int64))
         assert torch.equal(c32o.view(torch.int32), C32[o * H * T * T:(o + 1) * H * T * T].view(torch.int32))
+
+
+def test_split_k_sum_inside_the_pass_equals_the_separate_reduction():
+    """A split-K result of a few slabs is summed inside the round/log pass when the output is 8-byte aligned,
+    and by a kernel of its own otherwise: same additions in the same order, so every bit must agree."""
+    import torch
+    import paper_2403_09603_amd as vt
+    M, N, K, batch = 96, 64, 1100, 3
+    tm, tn, splits = vt.vt_gemm_plan(M, N, K, batch)
+    assert 1 < splits <= 8
+    g = si.rng(si.seed_for(1, 23))
+    A = torch.from_numpy(g.standard_normal((batch, M, K))).cuda()
+    B = torch.from_numpy(g.standard_normal((batch, K, N)) * 0.1).cuda()
+    bias = torch.from_numpy(g.standard_normal(N)).cuda()
+    total = M * N * batch
+    ws = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG, M, N, K, batch))
+    res = []
+    for shift in (0, 1):                                    # 1: C32 on a 4-byte boundary only
+        for dense in (False, True):
+            buf = torch.full((total + 2,), float("nan"), dtype=torch.float32, device="cuda")
+            C32 = buf[shift:shift + total]
+            assert C32.data_ptr() % 8 == 4 * shift
+            C64 = torch.empty(total, dtype=torch.float64, device="cuda")
+            log = vt.alloc_dense_log(total) if dense else vt.alloc_log(total)
+            vt.vt_gemm_f64_round_log(False, False, M, N, K, 0.75, A, K, M * K, B, N, K * N, bias, batch, C32, N, M * N,
+                                     C64, 1, 2.0 ** -4, log, ws)
+            torch.cuda.synchronize()
+            cnt = int(log.count.item())
+            res.append((C32.clone(), C64, cnt, log.dense.clone() if dense else log.idx[:cnt].clone()))
+    for r in res[1:]:
+        assert torch.equal(r[0].view(torch.int32), res[0][0].view(torch.int32))
+        assert torch.equal(r[1].view(torch.int64), res[0][1].view(torch.int64))
+        assert r[2] == res[0][2] > 0
+    assert torch.equal(res[0][3], res[2][3]) and torch.equal(res[1][3], res[3][3])
+    c64 = res[0][1].cpu().numpy().reshape(batch, M, N)
+    truth = np.stack([vo.gemm_f64(A[b].cpu().numpy(), B[b].cpu().numpy(), alpha=0.75, bias=bias.cpu().numpy(), order=2) for b in range(batch)])
+    assert np.allclose(c64, truth, rtol=0, atol=1e-11)
+    yo, io, do, co = vo.round_log(c64.ravel(), 2.0 ** -4)
+    assert co == res[0][2] and np.array_equal(res[0][0].cpu().numpy().view(np.uint32), yo.view(np.uint32))
+    assert np.array_equal(res[0][3].cpu().numpy().view(np.uint32), io)
