@@ -365,6 +365,40 @@ int vto_conv2d_wgrad_f64(const vto_conv2d *d, int64_t Cout, const double *X, con
     return VTO_OK;
 }
 
+/* Gradient of the forward map with respect to its input (the backward pass of a convolution
+ * layer, which the method also computes in FP64 and rounds): dX[n,h,w,ci] is the sum over all
+ * (kh, kw, co) of dY[n,ho,wo,co] * W[kh,kw,ci,co] for the output positions whose tap (kh, kw)
+ * reads X[n,h,w,.], that is ho * stride - pad + kh * dil = h (likewise in w).  Terms are added in
+ * ascending (order 0) or descending (order 1) (kh, kw, co); order 2 accumulates in long double. */
+int vto_conv2d_dgrad_f64(const vto_conv2d *d, int64_t Cout, const double *dY, const double *Wt,
+                         double *dX, int order)
+{
+    int64_t Ho, Wo;
+    if (vto_conv2d_out_size(d, &Ho, &Wo) != VTO_OK || Cout < 0 || order < 0 || order > 2) return VTO_ERR_INVALID_ARG;
+    const int64_t terms = d->KH * d->KW * Cout;
+    for (int64_t n = 0; n < d->N; ++n)
+        for (int64_t h = 0; h < d->H; ++h)
+            for (int64_t w = 0; w < d->W; ++w)
+                for (int64_t ci = 0; ci < d->C; ++ci) {
+                    double acc = 0.0;
+                    long double accl = 0.0L;
+                    for (int64_t s = 0; s < terms; ++s) {
+                        int64_t t = order == 1 ? terms - 1 - s : s;
+                        int64_t co = t % Cout, kw = (t / Cout) % d->KW, kh = t / (Cout * d->KW);
+                        int64_t hs = h + d->pad_h - kh * d->dil_h, ws = w + d->pad_w - kw * d->dil_w;
+                        double g = 0.0;
+                        if (hs >= 0 && ws >= 0 && hs % d->stride_h == 0 && ws % d->stride_w == 0 &&
+                            hs / d->stride_h < Ho && ws / d->stride_w < Wo)
+                            g = dY[((n * Ho + hs / d->stride_h) * Wo + ws / d->stride_w) * Cout + co];
+                        double wv = Wt[((kh * d->KW + kw) * d->C + ci) * Cout + co];
+                        if (order == 2) accl += (long double)g * (long double)wv;
+                        else { double p = g * wv; acc = acc + p; }
+                    }
+                    dX[((n * d->H + h) * d->W + w) * d->C + ci] = order == 2 ? (double)accl : acc;
+                }
+    return VTO_OK;
+}
+
 int vto_elementwise_f64(int op, const double *a, const double *b, uint64_t n, double *y, int exact)
 {
     if (op < VTO_EW_ADD || op > VTO_EW_GELU_ERF || (n && (!a || !y)) || (op == VTO_EW_ADD && n && !b))

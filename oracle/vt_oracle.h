@@ -116,6 +116,14 @@ int vto_conv2d_fwd_f64(const vto_conv2d *d, int64_t Cout, const double *X, const
 int vto_conv2d_wgrad_f64(const vto_conv2d *d, int64_t Cout, const double *X, const double *dY,
                          double *dW, int order);
 
+/* Gradient of sum(Y * dY) with respect to the input:
+ * dX[n,h,w,ci] = sum_{kh,kw,co} dY[n,ho,wo,co] Wt[kh,kw,ci,co] over the (ho, wo) with
+ * ho s - p + kh dil = h and wo s - p + kw dil = w (none when the difference is not a multiple of
+ * the stride or falls outside the output).
+ * order 0: terms in ascending (kh,kw,co); 1: descending; 2: long double. */
+int vto_conv2d_dgrad_f64(const vto_conv2d *d, int64_t Cout, const double *dY, const double *Wt,
+                         double *dX, int order);
+
 /* The same primitives with a rounding amount b_r < 32 (Method, primitives rnd_{b_r}, log, rev;
  * caption of the floating-point figure: the nearest 32-bit float with zeros in the last 32 - b_r
  * mantissa bits).  The grid spacing is 2^(32 - b_r) ulp32(x); tau_ulp and thr are measured in

@@ -101,6 +101,8 @@ def lib():
         L.vto_conv2d_fwd_f64.argtypes = [C.POINTER(Conv2d), C.c_int64, dp, dp, dp, dp, C.c_int]
         L.vto_conv2d_wgrad_f64.restype = C.c_int
         L.vto_conv2d_wgrad_f64.argtypes = [C.POINTER(Conv2d), C.c_int64, dp, dp, dp, C.c_int]
+        L.vto_conv2d_dgrad_f64.restype = C.c_int
+        L.vto_conv2d_dgrad_f64.argtypes = [C.POINTER(Conv2d), C.c_int64, dp, dp, dp, C.c_int]
         L.vto_threshold_stats.restype = C.c_int
         L.vto_threshold_stats.argtypes = [dp, dp, C.c_uint64, u64p]
         _lib = L
@@ -270,6 +272,19 @@ def conv2d_wgrad(X, dY, KH, KW, *, stride=1, pad=0, dil=1, order=0):
     if rc != 0:
         raise ValueError(f"vto_conv2d_wgrad_f64: error {rc}")
     return dW
+
+
+def conv2d_dgrad(dY, Wt, xshape, *, stride=1, pad=0, dil=1, order=0):
+    """dY (N,Ho,Wo,Cout), Wt (KH,KW,C,Cout), input shape (N,H,W,C) -> dX (N,H,W,C)."""
+    dY, Wt = _f64(dY), _f64(Wt)
+    d, Ho, Wo = conv2d_geometry(xshape, Wt.shape[0], Wt.shape[1], stride, pad, dil)
+    assert Wt.shape[2] == xshape[3] and dY.shape == (xshape[0], Ho, Wo, Wt.shape[3])
+    dX = np.empty(tuple(int(v) for v in xshape), np.float64)
+    rc = lib().vto_conv2d_dgrad_f64(C.byref(d), Wt.shape[3], _p(dY, C.c_double), _p(Wt, C.c_double),
+                                    _p(dX, C.c_double), int(order))
+    if rc != 0:
+        raise ValueError(f"vto_conv2d_dgrad_f64: error {rc}")
+    return dX
 
 
 EW_ADD, EW_RELU, EW_GELU_TANH, EW_GELU_ERF = 0, 1, 2, 3

@@ -1,10 +1,11 @@
-"""Pins for the oracle's convolution layer (forward and weight gradient).
+"""Pins for the oracle's convolution layer (forward, weight gradient and input gradient).
 
 The oracle writes the definition out as nested loops over channels-last arrays.  It is pinned
 here against things that are not itself: library routines (scipy's 2-D correlation, PyTorch's
 CPU convolution and its autograd), exact integer brute force in pure Python, the reduction of a
 1x1 convolution to a matrix product, the adjoint identity between the forward map and the weight
-gradient, the closed-form output sizes of the ResNet-50 geometry, and the stated summation order
+gradient and between the forward map and the input gradient (a scatter over output positions
+where the oracle gathers over input positions), the closed-form output sizes of the ResNet-50 geometry, and the stated summation order
 (re-accumulated for sampled outputs with Python floats).
 """
 import itertools
@@ -160,6 +161,89 @@ def test_summation_order_is_the_stated_one():
                 x = float(X[n, h, w, ci]) if 0 <= h < H and 0 <= w < W else 0.0
                 acc = acc + x * float(dY[n, ho, wo, co])
             assert acc == dW[kh, kw, ci, co]
+
+
+def _brute_dgrad(dY, Wt, xshape, stride, pad, dil):
+    """Exact integer input gradient by scattering every (output position, tap) product, pure Python."""
+    (sh, sw), (ph, pw), (dh, dw) = _pair(stride), _pair(pad), _pair(dil)
+    N, H, W, Cin = xshape
+    KH, KW, _, Cout = Wt.shape
+    _, Ho, Wo, _ = dY.shape
+    dX = np.zeros(xshape, dtype=object)
+    for n, ho, wo, co, kh, kw, ci in itertools.product(range(N), range(Ho), range(Wo), range(Cout), range(KH),
+                                                       range(KW), range(Cin)):
+        h, w = ho * sh - ph + kh * dh, wo * sw - pw + kw * dw
+        if 0 <= h < H and 0 <= w < W:
+            dX[n, h, w, ci] += int(dY[n, ho, wo, co]) * int(Wt[kh, kw, ci, co])
+    return dX
+
+
+@pytest.mark.parametrize("geom", GEOMS)
+def test_input_gradient_against_pytorch(geom):
+    torch = pytest.importorskip("torch")
+    N, H, W, Cin, KH, KW, Cout, stride, pad, dil = geom
+    X, Wt = _rand((N, H, W, Cin), 61), _rand((KH, KW, Cin, Cout), 62)
+    xt = torch.from_numpy(X).permute(0, 3, 1, 2).clone().requires_grad_(True)
+    wt = torch.from_numpy(Wt).permute(3, 2, 0, 1).clone()
+    yt = torch.nn.functional.conv2d(xt, wt, None, stride=_pair(stride), padding=_pair(pad), dilation=_pair(dil))
+    dY = _rand(tuple(yt.permute(0, 2, 3, 1).shape), 63)
+    (yt * torch.from_numpy(dY).permute(0, 3, 1, 2)).sum().backward()
+    want = xt.grad.permute(0, 2, 3, 1).numpy()
+    for order in (0, 1, 2):
+        got = vo.conv2d_dgrad(dY, Wt, X.shape, stride=stride, pad=pad, dil=dil, order=order)
+        np.testing.assert_allclose(got, want, rtol=0, atol=1e-12 * KH * KW * Cout)
+
+
+@pytest.mark.parametrize("geom", GEOMS)
+def test_input_gradient_on_integers_is_exact(geom):
+    N, H, W, Cin, KH, KW, Cout, stride, pad, dil = geom
+    g = si.rng(71)
+    X = g.integers(-9, 10, (N, H, W, Cin)).astype(np.float64)
+    Wt = g.integers(-9, 10, (KH, KW, Cin, Cout)).astype(np.float64)
+    Y = _brute(X, Wt, stride, pad, dil)
+    dY = g.integers(-9, 10, Y.shape).astype(np.float64)
+    want = _brute_dgrad(dY, Wt, X.shape, stride, pad, dil)
+    lhs = int(sum(int(a) * int(b) for a, b in zip(Y.ravel(), dY.ravel())))
+    for order in (0, 1, 2):
+        got = vo.conv2d_dgrad(dY, Wt, X.shape, stride=stride, pad=pad, dil=dil, order=order)
+        assert np.array_equal(got, want.astype(np.float64))
+        # adjoint identity, exact on integers: <conv(X, W), dY> = <X, dgrad(dY, W)>
+        assert int(sum(int(a) * int(b) for a, b in zip(got.ravel(), X.ravel()))) == lhs
+
+
+def test_input_gradient_of_a_1x1_convolution_is_a_matrix_product():
+    Wt = _rand((1, 1, 5, 7), 81)
+    dY = _rand((2, 4, 3, 7), 82)
+    for order in (0, 1):
+        got = vo.conv2d_dgrad(dY, Wt, (2, 8, 6, 5), stride=2, order=order)
+        want = vo.gemm_f64(dY.reshape(-1, 7), Wt.reshape(5, 7), transB=True, order=order)
+        assert np.array_equal(got[:, ::2, ::2, :].reshape(-1, 5), want)     # same terms in the same order
+        mask = np.ones((8, 6), bool)
+        mask[::2, ::2] = False
+        assert not got[:, mask, :].any()                                    # positions no output reads
+    got = vo.conv2d_dgrad(dY, Wt, (2, 4, 3, 5), order=0)                    # stride 1: every position
+    assert np.array_equal(got.reshape(-1, 5), vo.gemm_f64(dY.reshape(-1, 7), Wt.reshape(5, 7), transB=True, order=0))
+
+
+def test_input_gradient_summation_order_is_the_stated_one():
+    """order 0 adds the terms in ascending (kh, kw, co), order 1 in descending order."""
+    N, H, W, Cin, KH, KW, Cout, s, p = 1, 7, 6, 2, 3, 3, 3, 2, 1
+    Wt = _rand((KH, KW, Cin, Cout), 91)
+    _, Ho, Wo = vo.conv2d_geometry((N, H, W, Cin), KH, KW, s, p, 1)
+    dY = _rand((N, Ho, Wo, Cout), 92)
+    D0 = vo.conv2d_dgrad(dY, Wt, (N, H, W, Cin), stride=s, pad=p, order=0)
+    D1 = vo.conv2d_dgrad(dY, Wt, (N, H, W, Cin), stride=s, pad=p, order=1)
+    assert (D0 != D1).any()
+    terms = list(itertools.product(range(KH), range(KW), range(Cout)))
+    for (h, w, ci) in [(0, 0, 0), (H - 1, W - 1, 1), (3, 2, 0), (2, 3, 1)]:
+        for order, seq in ((0, terms), (1, terms[::-1])):
+            acc = 0.0
+            for kh, kw, co in seq:
+                hs, ws = h + p - kh, w + p - kw
+                ok = hs >= 0 and ws >= 0 and hs % s == 0 and ws % s == 0 and hs // s < Ho and ws // s < Wo
+                g = float(dY[0, hs // s, ws // s, co]) if ok else 0.0
+                acc = acc + g * float(Wt[kh, kw, ci, co])
+            assert acc == (D0, D1)[order][0, h, w, ci]
 
 
 def test_invalid_geometry_is_rejected():
