@@ -80,6 +80,8 @@ extern "C" {
 #define VT_OP_LAYER_ROUND_LOG 5  /* vt_layer_f64_round_log: M = rows, N = cols */
 #define VT_OP_SHA256_TREE 6      /* vt_sha256_tree: N = bytes, K = chunk (M, batch ignored) */
 #define VT_OP_MERKLE_ROOT 7      /* vt_merkle_root: N = leaves (M, K, batch ignored) */
+#define VT_OP_CONV_DGRAD_ROUND_LOG 8     /* vt_conv2d_f64_round_log, VT_CONV_DATA_GRAD: (M, N, K) of its GEMM */
+#define VT_OP_CONV_DGRAD_ROUND_LOG_BR 9  /* the same with log->b_r below 32 */
 
 /* Caller-owned log buffers (all four pointers are device pointers). */
 typedef struct vt_log {
@@ -199,6 +201,12 @@ int vt_gemm_f64_round_log_nested(int transA, int transB, int64_t M, int64_t N, i
  *                        B = Wt [KH][KW][C][Cout];  C32 = Y [N][Ho][Wo][Cout]
  *   VT_CONV_WEIGHT_GRAD  dW[kh,kw,ci,co] = sum_{n,ho,wo} X[n, ho s - p + kh d, wo s - p + kw d, ci] dY[n,ho,wo,co]
  *                        B = dY [N][Ho][Wo][Cout];  C32 = dW [KH][KW][C][Cout];  bias must be NULL
+ *   VT_CONV_DATA_GRAD    dX[n,h,w,ci]    = sum_{kh,kw,co} dY[n,ho,wo,co] Wt[kh,kw,ci,co] over the output positions
+ *                        with ho s - p + kh d = h and wo s - p + kw d = w (the gradient with respect to the
+ *                        layer's input).  The argument X is dY [N][Ho][Wo][Cout] (read through the matching
+ *                        implicit view, zeros where no output position reads the input position);
+ *                        B = Wt [KH][KW][C][Cout];  C32 = dX [N][H][W][C];  bias must be NULL.  The geometry
+ *                        `d` is the forward layer's (N, H, W, C describe the layer's input).
  *   Ho = floor((H + 2 pad_h - dil_h (KH - 1) - 1) / stride_h) + 1, Wo alike.
  *
  *   X            device, the image batch [N][H][W][C], dense, 8-byte aligned (16-byte alignment and
@@ -207,9 +215,12 @@ int vt_gemm_f64_round_log_nested(int transA, int transB, int64_t M, int64_t N, i
  *                log index of an output is its linear index in C32.  variant 0 accumulates taps
  *                (forward) or output positions (weight gradient) in ascending order, 1 descending.
  *   ws           at least vt_workspace_bytes(VT_OP_GEMM_ROUND_LOG, M, N, K, 1) bytes for the
- *                (M, N, K) that vt_conv2d_gemm_shape reports.
+ *                (M, N, K) that vt_conv2d_gemm_shape reports; for VT_CONV_DATA_GRAD
+ *                vt_workspace_bytes(VT_OP_CONV_DGRAD_ROUND_LOG, M, N, K, 1) (it also holds the filter
+ *                re-laid as the (KH KW Cout) x C operand of that GEMM; ..._BR with log->b_r below 32).
  *   Limits: every field of the geometry below 2^24; N H W C, N Ho Wo and KH KW C below 2^31;
- *   outputs below 2^32.
+ *   outputs below 2^32; for VT_CONV_DATA_GRAD also N Ho Wo Cout, N H W and KH KW Cout below 2^31
+ *   and KH KW below 2^16.
  */
 typedef struct vt_conv2d {
     int64_t N, H, W, C;                       /* image batch, channels last */
@@ -219,13 +230,14 @@ typedef struct vt_conv2d {
 
 #define VT_CONV_FORWARD 0
 #define VT_CONV_WEIGHT_GRAD 1
+#define VT_CONV_DATA_GRAD 2
 
 int vt_conv2d_f64_round_log(int mode, const vt_conv2d *d, int64_t Cout, const double *X, const double *B,
                             const double *bias, float *C32, double *C64_debug, int variant,
                             double tau_ulp, const vt_log *log, void *ws, size_t ws_bytes, void *hip_stream);
 
 /* The GEMM the convolution runs as: forward M = N Ho Wo, N = Cout, K = KH KW C; weight gradient
- * M = KH KW C, N = Cout, K = N Ho Wo.  Host only. */
+ * M = KH KW C, N = Cout, K = N Ho Wo; input gradient M = N H W, N = C, K = KH KW Cout.  Host only. */
 int vt_conv2d_gemm_shape(const vt_conv2d *d, int64_t Cout, int mode, int64_t *M, int64_t *N, int64_t *K);
 
 /*

@@ -6,10 +6,11 @@ There is no CPU fallback: calling any entry point without the built library rais
 """
 from .binding import (  # noqa: F401
     VT_OP_GEMM_ROUND_LOG, VT_OP_GEMM_ROUND_LOG_BR, VT_OP_ROUND_LOG, VT_OP_ROUND_REPLAY, VT_OP_THRESHOLD_STATS,
-    VT_CONV_FORWARD, VT_CONV_WEIGHT_GRAD, Conv2d, VT_OP_LAYER_ROUND_LOG, VT_LAYER_ADD, VT_LAYER_RELU,
+    VT_CONV_FORWARD, VT_CONV_WEIGHT_GRAD, VT_CONV_DATA_GRAD, Conv2d, VT_OP_LAYER_ROUND_LOG, VT_LAYER_ADD, VT_LAYER_RELU,
     VT_LAYER_GELU_TANH, VT_LAYER_GELU_ERF, VT_LAYER_NORM, VT_LAYER_SOFTMAX, VT_LAYER_BATCHNORM,
     VT_LAYER_BATCHNORM_RELU, vt_layer_f64_round_log, vt_conv2d_f64_round_log, vt_conv2d_gemm_shape,
     VtError, Log, alloc_log, alloc_dense_log, vt_round_replay_dense, alloc_workspace, library_path, load_library,
     vt_gemm_f64_round_log, vt_gemm_f64_round_log_nested, vt_gemm_plan, vt_round_log, vt_round_replay, vt_set_kernel_events, vt_strerror, vt_thr_from_tau,
-    vt_threshold_stats, vt_workspace_bytes, vt_sha256_tree, vt_merkle_root, VT_OP_SHA256_TREE, VT_OP_MERKLE_ROOT,
+    vt_threshold_stats, vt_workspace_bytes, vt_sha256_tree, vt_merkle_root, VT_OP_SHA256_TREE, VT_OP_MERKLE_ROOT, VT_OP_CONV_DGRAD_ROUND_LOG,
+    VT_OP_CONV_DGRAD_ROUND_LOG_BR,
 )

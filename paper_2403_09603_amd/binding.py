@@ -16,11 +16,12 @@ _LIB_PATH = os.path.join(_HERE, "libvt_hip.so")
 _lib = None
 
 VT_OP_ROUND_LOG, VT_OP_ROUND_REPLAY, VT_OP_GEMM_ROUND_LOG, VT_OP_THRESHOLD_STATS, VT_OP_GEMM_ROUND_LOG_BR = 0, 1, 2, 3, 4
-VT_CONV_FORWARD, VT_CONV_WEIGHT_GRAD = 0, 1
+VT_CONV_FORWARD, VT_CONV_WEIGHT_GRAD, VT_CONV_DATA_GRAD = 0, 1, 2
 VT_OP_LAYER_ROUND_LOG = 5
 VT_LAYER_ADD, VT_LAYER_RELU, VT_LAYER_GELU_TANH, VT_LAYER_GELU_ERF, VT_LAYER_NORM, VT_LAYER_SOFTMAX = 0, 1, 2, 3, 4, 5
 VT_LAYER_BATCHNORM, VT_LAYER_BATCHNORM_RELU = 6, 7
 VT_OP_SHA256_TREE, VT_OP_MERKLE_ROOT = 6, 7
+VT_OP_CONV_DGRAD_ROUND_LOG, VT_OP_CONV_DGRAD_ROUND_LOG_BR = 8, 9
 
 
 class VtError(RuntimeError):
@@ -294,7 +295,11 @@ def vt_conv2d_f64_round_log(mode: int, d: Conv2d, Cout: int, X: torch.Tensor, B:
                             C32: torch.Tensor, C64_debug, variant: int, tau_ulp: float, log: Log,
                             ws: torch.Tensor, stream=None):
     M, N, K = vt_conv2d_gemm_shape(d, Cout, mode)
-    if X.numel() < d.N * d.H * d.W * d.C:
+    if mode == VT_CONV_DATA_GRAD:
+        Mf, _, _ = vt_conv2d_gemm_shape(d, Cout, VT_CONV_FORWARD)
+        if X.numel() < Mf * Cout:
+            raise VtError("dY is smaller than N*Ho*Wo*Cout")
+    elif X.numel() < d.N * d.H * d.W * d.C:
         raise VtError("X is smaller than N*H*W*C")
     if B.numel() < K * N:
         raise VtError("B is smaller than the geometry implies")

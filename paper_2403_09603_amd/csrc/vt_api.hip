@@ -132,7 +132,7 @@ int run_gemm(vt::GemmArgs &g, const vt_log *log, void *ws, size_t ws_bytes, hipS
 // Limits keep every index the kernel forms inside 32 bits.
 bool conv_desc(const vt_conv2d *d, int64_t Cout, int mode, vt::ConvDesc *c)
 {
-    if (!d || Cout < 0 || (mode != VT_CONV_FORWARD && mode != VT_CONV_WEIGHT_GRAD)) return false;
+    if (!d || Cout < 0 || (mode != VT_CONV_FORWARD && mode != VT_CONV_WEIGHT_GRAD && mode != VT_CONV_DATA_GRAD)) return false;
     const int64_t lim = (int64_t)1 << 24;
     if (d->N < 0 || d->H < 0 || d->W < 0 || d->C < 0 || d->KH < 1 || d->KW < 1 || d->stride_h < 1 || d->stride_w < 1 ||
         d->pad_h < 0 || d->pad_w < 0 || d->dil_h < 1 || d->dil_w < 1)
@@ -152,7 +152,52 @@ bool conv_desc(const vt_conv2d *d, int64_t Cout, int mode, vt::ConvDesc *c)
     if ((unsigned __int128)d->N * d->H * d->W * d->C >= two31) return false;          // image elements
     if ((unsigned __int128)d->N * c->Ho * c->Wo >= two31) return false;               // im2col rows
     if ((unsigned __int128)d->KH * d->KW * d->C >= two31) return false;               // taps
+    if (mode == VT_CONV_DATA_GRAD) {                  // the gathered image is dY, the rows are input positions
+        if ((unsigned __int128)d->N * c->Ho * c->Wo * Cout >= two31) return false;
+        if ((unsigned __int128)d->N * d->H * d->W >= two31) return false;
+        if ((unsigned __int128)d->KH * d->KW * Cout >= two31) return false;
+        if (d->KH * d->KW > 65535) return false;      // one grid plane per filter position in the weight re-layout
+    }
     return true;
+}
+
+// Input gradient of a convolution: dX (N H W x C) = view(dY) (N H W x KH KW Cout) times the filter
+// re-laid as (KH KW Cout) x C.  The geometry is validated by the caller.
+int conv_dgrad_entry(const vt::ConvDesc &c, int64_t Cout, const double *dY, const double *Wt, const double *bias,
+                     float *C32, double *C64_debug, int variant, uint32_t thr, const vt_log *log, void *ws,
+                     size_t ws_bytes, hipStream_t s)
+{
+    if (bias) return VT_ERR_INVALID_ARG;
+    // (no output positions: dY is empty, nothing is read and the gradient is zero)
+    const int64_t M = c.N * c.H * c.W, N = c.C, K = c.N * c.Ho * c.Wo == 0 ? 0 : c.KH * c.KW * Cout;
+    if ((unsigned __int128)M * (unsigned __int128)N >= ((unsigned __int128)1 << 32)) return VT_ERR_INVALID_ARG;
+    if (M * N == 0) {
+        const vt::Planes pl = vt::planes_carve(ws, 0, 0);
+        const vt::LogOut lo{log->idx, log->dir, log->cap, log->count};
+        return hip_status(vt::launch_seg_scan(pl, lo, s));
+    }
+    if (!C32 || !aligned(C32, 4) || (C64_debug && !aligned(C64_debug, 8))) return VT_ERR_INVALID_ARG;
+    if (K > 0 && (!dY || !Wt || !aligned(dY, 8) || !aligned(Wt, 8))) return VT_ERR_INVALID_ARG;
+    vt::GemmArgs g;
+    g.transA = 0; g.M = M; g.N = N; g.K = K; g.alpha = 1.0;
+    g.A = dY; g.strideA = 0; g.strideB = 0;
+    g.bias = nullptr; g.batch = 1; g.C32 = C32; g.ldc = N; g.strideC = 0;
+    g.C64 = C64_debug; g.variant = variant; g.thr = thr;
+    if (c.KH == 1 && c.KW == 1 && c.stride_h == 1 && c.stride_w == 1 && c.pad_h == 0 && c.pad_w == 0) {
+        // a 1 x 1 filter at every position: dX = dY (rows x Cout) times the transposed filter (C x Cout
+        // as it lies), a plain GEMM
+        g.lda = Cout; g.B = Wt; g.transB = 1; g.ldb = Cout;
+        return run_gemm(g, log, ws, ws_bytes, s);
+    }
+    const bool two_pass = k_of(log->b_r) != 0;
+    const size_t gemm = vt_workspace_bytes(two_pass ? VT_OP_GEMM_ROUND_LOG_BR : VT_OP_GEMM_ROUND_LOG, M, N, K, 1);
+    const size_t at = (gemm + 255) / 256 * 256;
+    if (!ws || !aligned(ws, 256) || ws_bytes < at + (size_t)K * (size_t)N * 8) return VT_ERR_WORKSPACE;
+    double *Wp = (double *)((char *)ws + at);
+    if (K > 0 && vt::launch_dgrad_weights(Wt, c.KH * c.KW, c.C, Cout, Wp, s) != hipSuccess) return VT_ERR_HIP;
+    g.conv = &c; g.conv_dgrad_cout = Cout;
+    g.lda = 0; g.B = Wp; g.transB = 0; g.ldb = N;
+    return run_gemm(g, log, ws, at, s);
 }
 
 }  // namespace
@@ -195,6 +240,13 @@ size_t vt_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int64_t batch
         if (splits > 1)
             bytes += vt::gemm_split_bytes(M, N, batch, splits) + round_log_bytes((uint64_t)M * (uint64_t)N * (uint64_t)batch);
         return bytes;
+    }
+    case VT_OP_CONV_DGRAD_ROUND_LOG:
+    case VT_OP_CONV_DGRAD_ROUND_LOG_BR: {
+        // the GEMM's workspace, then the filter in the layout the GEMM multiplies by (K x N doubles)
+        if (K < 0) return 0;
+        const size_t gemm = vt_workspace_bytes(op == VT_OP_CONV_DGRAD_ROUND_LOG ? VT_OP_GEMM_ROUND_LOG : VT_OP_GEMM_ROUND_LOG_BR, M, N, K, batch);
+        return (gemm + 255) / 256 * 256 + (size_t)K * (size_t)N * 8;
     }
     case VT_OP_SHA256_TREE:
         if (K < 0 || (K % 64) != 0) return 0;
@@ -345,6 +397,12 @@ int vt_conv2d_gemm_shape(const vt_conv2d *d, int64_t Cout, int mode, int64_t *M,
     vt::ConvDesc c;
     if (!M || !N || !K || !conv_desc(d, Cout, mode, &c)) return VT_ERR_INVALID_ARG;
     const int64_t rows = c.N * c.Ho * c.Wo, taps = c.KH * c.KW * c.C;
+    if (mode == VT_CONV_DATA_GRAD) {
+        *M = c.N * c.H * c.W;
+        *N = c.C;
+        *K = c.KH * c.KW * Cout;
+        return VT_OK;
+    }
     *M = mode == VT_CONV_FORWARD ? rows : taps;
     *N = Cout;
     *K = mode == VT_CONV_FORWARD ? taps : rows;
@@ -361,6 +419,8 @@ int vt_conv2d_f64_round_log(int mode, const vt_conv2d *d, int64_t Cout, const do
     if (!conv_desc(d, Cout, mode, &c)) return VT_ERR_INVALID_ARG;
     if (mode == VT_CONV_WEIGHT_GRAD && bias) return VT_ERR_INVALID_ARG;
     const int64_t rows = c.N * c.Ho * c.Wo, taps = c.KH * c.KW * c.C;
+    if (mode == VT_CONV_DATA_GRAD)
+        return conv_dgrad_entry(c, Cout, X, B, bias, C32, C64_debug, variant, thr, log, ws, ws_bytes, (hipStream_t)hip_stream);
     const int64_t M = mode == VT_CONV_FORWARD ? rows : taps, K = mode == VT_CONV_FORWARD ? taps : rows;
     if ((unsigned __int128)M * (unsigned __int128)Cout >= ((unsigned __int128)1 << 32)) return VT_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)hip_stream;

@@ -335,7 +335,7 @@ struct ConvGeom {
     int32_t sh, sw, ph, pw, dh, dw;
     int32_t vec;                     // taps (kc, kc + 1), kc even, are one aligned 16-byte load (C even)
     uint32_t rows, taps;             // N Ho Wo and KH KW C
-    double inv_HoWo, inv_Wo, inv_KWC, inv_C;
+    double inv_HoWo, inv_Wo, inv_KWC, inv_C, inv_sh, inv_sw;
 };
 
 constexpr int32_t kNowhere = -(1 << 30);        // row / tap coordinate that fails every bounds test
@@ -350,8 +350,9 @@ static __host__ __device__ __forceinline__ void divmod_u32(uint32_t x, uint32_t 
     r = (uint32_t)rem;
 }
 
-struct RowPos { int32_t base, h0, w0; };        // element offset of X[n, h0, w0, 0]; top-left tap position
-struct TapPos { int32_t off, hh, ww; };         // (hh W + ww) C + ci with hh = kh dil_h, ww = kw dil_w
+struct RowPos { int32_t base, h0, w0, rem; };   // element offset of X[n, h0, w0, 0]; top-left tap position
+struct TapPos { int32_t off, hh, ww, rem; };    // (hh W + ww) C + ci with hh = kh dil_h, ww = kw dil_w
+// (rem: stride remainders, used by the input-gradient view below only)
 
 static __host__ __device__ __forceinline__ RowPos conv_row(const ConvGeom &c, uint32_t m)
 {
@@ -362,6 +363,7 @@ static __host__ __device__ __forceinline__ RowPos conv_row(const ConvGeom &c, ui
     r.h0 = (int32_t)ho * c.sh - c.ph;
     r.w0 = (int32_t)wo * c.sw - c.pw;
     r.base = (int32_t)(((n * (uint32_t)c.H + (uint32_t)r.h0) * (uint32_t)c.W + (uint32_t)r.w0) * (uint32_t)c.C);
+    r.rem = 0;
     if (m >= c.rows) r.h0 = kNowhere;
     return r;
 }
@@ -375,6 +377,47 @@ static __host__ __device__ __forceinline__ TapPos conv_tap(const ConvGeom &c, ui
     t.hh = (int32_t)kh * c.dh;
     t.ww = (int32_t)kw * c.dw;
     t.off = (int32_t)(((uint32_t)t.hh * (uint32_t)c.W + (uint32_t)t.ww) * (uint32_t)c.C + ci);
+    t.rem = 0;
+    if (kc >= c.taps) t.hh = kNowhere;
+    return t;
+}
+
+// Input gradient (A operand mode 4).  The gathered image is dY[N][Ho][Wo][Cout]; matrix row
+// m = (n, h, w) is a position of the layer's input, column kc = (kh, kw, co), and the element is
+// dY[n, ho, wo, co] for the output position with ho s - p + kh d = h (likewise in w): zero when
+// h + p - kh d is not a multiple of the stride or ho falls outside the output.  With
+// h + p = s qh + rh and kh d = s qk + rk (remainders in [0, s)), the difference is a multiple of s
+// exactly when rh = rk, and then ho = qh - qk: the address splits into a row part and a tap part
+// as in the forward view.  The geometry reuses ConvGeom with the roles exchanged: (H, W, C) are
+// dY's (Ho, Wo, Cout); (Wo, HoWo) the input's (W, H W); KWC = KW Cout; rows = N H W; taps = KH KW Cout.
+static __host__ __device__ __forceinline__ RowPos dgrad_row(const ConvGeom &c, uint32_t m)
+{
+    uint32_t n, rem, h, w;
+    divmod_u32(m, (uint32_t)c.HoWo, c.inv_HoWo, n, rem);
+    divmod_u32(rem, (uint32_t)c.Wo, c.inv_Wo, h, w);
+    const uint32_t hp = h + (uint32_t)c.ph, wp = w + (uint32_t)c.pw;
+    const uint32_t qh = hp / (uint32_t)c.sh, qw = wp / (uint32_t)c.sw;           // once per row and thread
+    RowPos r;
+    r.h0 = (int32_t)qh;
+    r.w0 = (int32_t)qw;
+    r.rem = (int32_t)((hp - qh * (uint32_t)c.sh) | ((wp - qw * (uint32_t)c.sw) << 16));
+    r.base = (int32_t)(((n * (uint32_t)c.H + qh) * (uint32_t)c.W + qw) * (uint32_t)c.C);
+    if (m >= c.rows) r.h0 = kNowhere;
+    return r;
+}
+
+static __host__ __device__ __forceinline__ TapPos dgrad_tap(const ConvGeom &c, uint32_t kc)
+{
+    uint32_t kh, rem, kw, co, qk, rk, qkw, rkw;
+    divmod_u32(kc, (uint32_t)c.KWC, c.inv_KWC, kh, rem);
+    divmod_u32(rem, (uint32_t)c.C, c.inv_C, kw, co);
+    divmod_u32(kh * (uint32_t)c.dh, (uint32_t)c.sh, c.inv_sh, qk, rk);
+    divmod_u32(kw * (uint32_t)c.dw, (uint32_t)c.sw, c.inv_sw, qkw, rkw);
+    TapPos t;
+    t.hh = -(int32_t)qk;
+    t.ww = -(int32_t)qkw;
+    t.rem = (int32_t)(rk | (rkw << 16));
+    t.off = (int32_t)(co - (qk * (uint32_t)c.W + qkw) * (uint32_t)c.C);
     if (kc >= c.taps) t.hh = kNowhere;
     return t;
 }
@@ -392,6 +435,25 @@ static inline ConvGeom conv_geom(int64_t N, int64_t H, int64_t W, int64_t C, int
     c.rows = (uint32_t)(N * Ho * Wo); c.taps = (uint32_t)(KH * KW * C);
     c.inv_HoWo = 1.0 / (double)(c.HoWo > 0 ? c.HoWo : 1); c.inv_Wo = 1.0 / (double)(c.Wo > 0 ? c.Wo : 1);
     c.inv_KWC = 1.0 / (double)(c.KWC > 0 ? c.KWC : 1); c.inv_C = 1.0 / (double)(c.C > 0 ? c.C : 1);
+    c.inv_sh = 1.0 / (double)c.sh; c.inv_sw = 1.0 / (double)c.sw;
+    return c;
+}
+
+// The same structure for the input-gradient view of a layer with input (N, H, W, C), output
+// (N, Ho, Wo, Cout): see dgrad_row.
+static inline ConvGeom dgrad_geom(int64_t N, int64_t H, int64_t W, int64_t Cout, int64_t KH, int64_t KW, int64_t sh,
+                                  int64_t sw, int64_t ph, int64_t pw, int64_t dh, int64_t dw, int64_t Ho, int64_t Wo,
+                                  bool vec)
+{
+    ConvGeom c;
+    c.H = (int32_t)Ho; c.W = (int32_t)Wo; c.C = (int32_t)Cout; c.Wo = (int32_t)W;
+    c.HoWo = (int32_t)(H * W); c.KWC = (int32_t)(KW * Cout);
+    c.sh = (int32_t)sh; c.sw = (int32_t)sw; c.ph = (int32_t)ph; c.pw = (int32_t)pw; c.dh = (int32_t)dh; c.dw = (int32_t)dw;
+    c.vec = vec ? 1 : 0;
+    c.rows = (uint32_t)(N * H * W); c.taps = (uint32_t)(KH * KW * Cout);
+    c.inv_HoWo = 1.0 / (double)(c.HoWo > 0 ? c.HoWo : 1); c.inv_Wo = 1.0 / (double)(c.Wo > 0 ? c.Wo : 1);
+    c.inv_KWC = 1.0 / (double)(c.KWC > 0 ? c.KWC : 1); c.inv_C = 1.0 / (double)(c.C > 0 ? c.C : 1);
+    c.inv_sh = 1.0 / (double)c.sh; c.inv_sw = 1.0 / (double)c.sw;
     return c;
 }
 
@@ -402,6 +464,15 @@ static __host__ __device__ __forceinline__ int64_t conv_element(const ConvGeom &
     const RowPos r = conv_row(c, m);
     const TapPos t = conv_tap(c, kc);
     const bool ok = (uint32_t)(r.h0 + t.hh) < (uint32_t)c.H && (uint32_t)(r.w0 + t.ww) < (uint32_t)c.W;
+    return ok ? (int64_t)(r.base + t.off) : -1;
+}
+
+// The same for the input-gradient view: offset into dY of matrix entry (row m, column kc), or -1.
+static __host__ __device__ __forceinline__ int64_t dgrad_element(const ConvGeom &c, uint32_t m, uint32_t kc)
+{
+    const RowPos r = dgrad_row(c, m);
+    const TapPos t = dgrad_tap(c, kc);
+    const bool ok = (uint32_t)(r.h0 + t.hh) < (uint32_t)c.H && (uint32_t)(r.w0 + t.ww) < (uint32_t)c.W && r.rem == t.rem;
     return ok ? (int64_t)(r.base + t.off) : -1;
 }
 

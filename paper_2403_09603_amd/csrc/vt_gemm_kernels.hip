@@ -107,6 +107,40 @@ size_t gemm_split_bytes(int64_t M, int64_t N, int64_t batch, int splits)
     return (size_t)((slab + 255) / 256 * 256 * (uint64_t)(splits + 1));   // slabs + the reduced tensor
 }
 
+namespace {
+
+// one 32 x 32 block of one filter position, transposed through LDS (reads and writes coalesced)
+__global__ __launch_bounds__(256) void dgrad_weights_kernel(const double *__restrict__ Wt, uint32_t C, uint32_t Cout,
+                                                            double *__restrict__ Wp)
+{
+    __shared__ double tile[32][33];
+    const uint32_t tx = threadIdx.x & 31u, ty = threadIdx.x >> 5;            // 32 x 8 threads
+    const uint64_t tap = blockIdx.z, plane = (uint64_t)C * Cout;
+    const uint32_t co0 = blockIdx.x * 32u, c0 = blockIdx.y * 32u;
+#pragma unroll
+    for (uint32_t i = 0; i < 32; i += 8) {
+        const uint32_t c = c0 + ty + i, co = co0 + tx;
+        if (c < C && co < Cout) tile[ty + i][tx] = Wt[tap * plane + (uint64_t)c * Cout + co];
+    }
+    __syncthreads();
+#pragma unroll
+    for (uint32_t i = 0; i < 32; i += 8) {
+        const uint32_t co = co0 + ty + i, c = c0 + tx;
+        if (c < C && co < Cout) Wp[tap * plane + (uint64_t)co * C + c] = tile[tx][ty + i];
+    }
+}
+
+}  // namespace
+
+hipError_t launch_dgrad_weights(const double *Wt, int64_t taps_hw, int64_t C, int64_t Cout, double *Wp, hipStream_t s)
+{
+    if (taps_hw <= 0 || C <= 0 || Cout <= 0) return hipSuccess;
+    const uint64_t gx = (uint64_t)(Cout + 31) / 32, gy = (uint64_t)(C + 31) / 32;
+    if (gx > 0x7FFFFFFFull || gy > 65535ull || (uint64_t)taps_hw > 65535ull) return hipErrorInvalidValue;
+    dgrad_weights_kernel<<<dim3((uint32_t)gx, (uint32_t)gy, (uint32_t)taps_hw), 256, 0, s>>>(Wt, (uint32_t)C, (uint32_t)Cout, Wp);
+    return hipGetLastError();
+}
+
 hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, const Planes &pl, double *partial,
                                     double *reduced, hipStream_t s)
 {
@@ -140,6 +174,11 @@ hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, con
         p.conv = conv_geom(d.N, d.H, d.W, d.C, d.KH, d.KW, d.stride_h, d.stride_w, d.pad_h, d.pad_w, d.dil_h, d.dil_w,
                            d.Ho, d.Wo, (d.C % 2 == 0) && ((uintptr_t)g.A % 16 == 0));
         am = g.conv_wgrad ? 3 : 2;
+        if (g.conv_dgrad_cout > 0) {
+            p.conv = dgrad_geom(d.N, d.H, d.W, g.conv_dgrad_cout, d.KH, d.KW, d.stride_h, d.stride_w, d.pad_h, d.pad_w,
+                                d.dil_h, d.dil_w, d.Ho, d.Wo, (g.conv_dgrad_cout % 2 == 0) && ((uintptr_t)g.A % 16 == 0));
+            am = 4;
+        }
         p.vecA = p.conv.vec;
     }
     hipError_t e;

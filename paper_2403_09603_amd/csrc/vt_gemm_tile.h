@@ -71,18 +71,21 @@ constexpr int kPad = 18;
 // Two neighbouring taps of one row.  The load is unconditional (from X[0] when the element lies
 // in the padding or outside the matrix) and the value is selected afterwards, so the loop body
 // stays free of branches.
-template <bool VEC>
+template <bool VEC, bool UP = false>
 __device__ __forceinline__ d2 conv_gather(const double *__restrict__ X, const ConvGeom &c, const RowPos &r,
                                           const TapPos &t0, const TapPos &t1)
 {
-    const bool ok0 = (uint32_t)(r.h0 + t0.hh) < (uint32_t)c.H && (uint32_t)(r.w0 + t0.ww) < (uint32_t)c.W;
+    // UP (input gradient): the row's and the tap's stride remainders must agree as well
+    const bool ok0 = (uint32_t)(r.h0 + t0.hh) < (uint32_t)c.H && (uint32_t)(r.w0 + t0.ww) < (uint32_t)c.W &&
+                     (!UP || r.rem == t0.rem);
     d2 v;
     if (VEC) {
         const d2 x = *(const d2 *)(X + (ok0 ? r.base + t0.off : 0));
         v.x = ok0 ? x.x : 0.0;
         v.y = ok0 ? x.y : 0.0;
     } else {
-        const bool ok1 = (uint32_t)(r.h0 + t1.hh) < (uint32_t)c.H && (uint32_t)(r.w0 + t1.ww) < (uint32_t)c.W;
+        const bool ok1 = (uint32_t)(r.h0 + t1.hh) < (uint32_t)c.H && (uint32_t)(r.w0 + t1.ww) < (uint32_t)c.W &&
+                         (!UP || r.rem == t1.rem);
         const double a = X[ok0 ? r.base + t0.off : 0], b = X[ok1 ? r.base + t1.off : 0];
         v.x = ok0 ? a : 0.0;
         v.y = ok1 ? b : 0.0;
@@ -184,11 +187,12 @@ __device__ __forceinline__ int write_lane(uint32_t s, int ln, int v)
 
 // AM, the A operand: 0 = stored transposed (contiguous along m), 1 = row-major (contiguous along
 // k), 2 = implicit im2col of an image, rows x taps (convolution forward), 3 = its transpose,
-// taps x rows (convolution weight gradient).  KCB: B is stored transposed (contiguous along k).
+// taps x rows (convolution weight gradient), 4 = the input-gradient view of the output gradient,
+// input positions x (filter position, output channel).  KCB: B is stored transposed (contiguous along k).
 template <int AM, bool KCB, int WM, int TM>
 __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmParams p)
 {
-    constexpr bool KCA = AM == 1 || AM == 2;
+    constexpr bool KCA = AM == 1 || AM == 2 || AM == 4;
     constexpr bool GA = AM >= 2;
     constexpr int WN = 4 / WM;
     constexpr int BM = WM * 16 * TM, BN = WN * 64;
@@ -252,11 +256,15 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
     d2 ra0[BM / 32], rb0[BN / 32], ra1[BM / 32], rb1[BN / 32];
     // Implicit im2col: the part of the address that belongs to this thread for the whole loop --
     // its rows of the image matrix (forward) or its pair of taps (weight gradient).
-    RowPos rowp[AM == 2 ? BM / 32 : 1];
-    TapPos tap0{0, 0, 0}, tap1{0, 0, 0};
+    RowPos rowp[AM == 2 || AM == 4 ? BM / 32 : 1];
+    TapPos tap0{0, 0, 0, 0}, tap1{0, 0, 0, 0};
     if constexpr (AM == 2) {
 #pragma unroll
         for (int j = 0; j < BM / 32; ++j) rowp[j] = conv_row(p.conv, (uint32_t)bm + (t >> 3) + 32 * j);
+    }
+    if constexpr (AM == 4) {
+#pragma unroll
+        for (int j = 0; j < BM / 32; ++j) rowp[j] = dgrad_row(p.conv, (uint32_t)bm + (t >> 3) + 32 * j);
     }
     if constexpr (AM == 3) {
         const uint32_t kc = (uint32_t)bm + (t % (BM / 2)) * 2;
@@ -277,6 +285,12 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
                 const RowPos r = conv_row(p.conv, (uint32_t)k0 + t / (BM / 2) + (512 / BM) * j);
                 ra[j] = conv_gather<VEC>(p.A, p.conv, r, tap0, tap1);
             }
+        } else if constexpr (AM == 4) {
+            const uint32_t kc = (uint32_t)k0 + (t & 7) * 2;
+            const TapPos t0 = dgrad_tap(p.conv, kc);
+            const TapPos t1 = VEC ? t0 : dgrad_tap(p.conv, kc + 1);
+#pragma unroll
+            for (int j = 0; j < BM / 32; ++j) ra[j] = conv_gather<VEC, true>(p.A, p.conv, rowp[j], t0, t1);
         }
     };
     auto main_loop = [&](auto fast_tag) {
@@ -516,6 +530,7 @@ hipError_t launch_shape(const GemmParams &p, int am, bool kcb, hipStream_t s)
     const dim3 grid(p.total_blocks), block(256);
     if (am == 2 && !kcb) gemm_round_planes_kernel<2, false, WM, TM><<<grid, block, 0, s>>>(p);
     else if (am == 3 && !kcb) gemm_round_planes_kernel<3, false, WM, TM><<<grid, block, 0, s>>>(p);
+    else if (am == 4 && !kcb) gemm_round_planes_kernel<4, false, WM, TM><<<grid, block, 0, s>>>(p);
     else if (am == 1 && kcb) gemm_round_planes_kernel<1, true, WM, TM><<<grid, block, 0, s>>>(p);
     else if (am == 1 && !kcb) gemm_round_planes_kernel<1, false, WM, TM><<<grid, block, 0, s>>>(p);
     else if (am == 0 && kcb) gemm_round_planes_kernel<0, true, WM, TM><<<grid, block, 0, s>>>(p);

@@ -120,6 +120,8 @@ struct ConvDesc {
 struct GemmArgs {
     const ConvDesc *conv = nullptr;   // non-null: A is an image X[N][H][W][C]; M, K describe its im2col matrix
     bool conv_wgrad = false;          // the matrix is used transposed (taps x rows): weight gradient
+    int64_t conv_dgrad_cout = 0;      // > 0: A is the output gradient dY[N][Ho][Wo][Cout] read through the
+                                      // input-gradient view (rows = input positions, K = KH KW Cout)
     int transA, transB;
     int64_t M, N, K;
     double alpha;
@@ -149,5 +151,8 @@ size_t gemm_split_bytes(int64_t M, int64_t N, int64_t batch, int splits);
 // consumes them).
 hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, const Planes &pl, double *partial,
                                     double *reduced, hipStream_t s);
+// Filter Wt[taps_hw][C][Cout] -> Wp[taps_hw][Cout][C]: the B operand (K x C, row-major) of the
+// input-gradient GEMM.  A copy, so exact.
+hipError_t launch_dgrad_weights(const double *Wt, int64_t taps_hw, int64_t C, int64_t Cout, double *Wp, hipStream_t s);
 
 }  // namespace vt

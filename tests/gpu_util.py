@@ -100,14 +100,16 @@ def gpu_gemm(A, B, *, transA=False, transB=False, alpha=1.0, bias=None, tau=0.0,
             "idx": u32(log.idx)[:k].copy(), "dir": u32(log.dir)[:(k + 31) // 32].copy(), "count": count}
 
 
-def gpu_conv(mode, X, B, KH, KW, *, stride=1, pad=0, dil=1, bias=None, tau=0.0, variant=0, misalign=False, b_r=32):
+def gpu_conv(mode, X, B, KH, KW, *, stride=1, pad=0, dil=1, bias=None, tau=0.0, variant=0, misalign=False, b_r=32,
+             xshape=None):
     """mode 0: forward, B = weights (KH,KW,C,Cout); mode 1: weight gradient, B = dY (N,Ho,Wo,Cout).
-    X is (N,H,W,C).  misalign=True puts X on an 8-byte (not 16-byte) boundary."""
+    X is (N,H,W,C).  mode 2: input gradient, X = dY (N,Ho,Wo,Cout), B = weights, xshape = (N,H,W,C).
+    misalign=True puts X on an 8-byte (not 16-byte) boundary."""
     pair = lambda v: (int(v), int(v)) if np.isscalar(v) else (int(v[0]), int(v[1]))
     (sh, sw), (ph, pw), (dh, dw) = pair(stride), pair(pad), pair(dil)
     X = np.ascontiguousarray(X, np.float64)
     B = np.ascontiguousarray(B, np.float64)
-    N, H, W, Cin = X.shape
+    N, H, W, Cin = X.shape if mode != 2 else xshape
     Cout = B.shape[-1]
     d = vt.Conv2d(N, H, W, Cin, KH, KW, sh, sw, ph, pw, dh, dw)
     M, Nn, K = vt.vt_conv2d_gemm_shape(d, Cout, mode)
@@ -123,8 +125,11 @@ def gpu_conv(mode, X, B, KH, KW, *, stride=1, pad=0, dil=1, bias=None, tau=0.0, 
     C64 = torch.empty(max(M * Nn, 1), dtype=torch.float64, device=DEV)
     log = vt.alloc_log(M * Nn)
     log.b_r = b_r
-    ws = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG if b_r == 32 else vt.VT_OP_GEMM_ROUND_LOG_BR,
-                                                  M, Nn, K, 1))
+    if mode == 2:
+        op = vt.VT_OP_CONV_DGRAD_ROUND_LOG if b_r == 32 else vt.VT_OP_CONV_DGRAD_ROUND_LOG_BR
+    else:
+        op = vt.VT_OP_GEMM_ROUND_LOG if b_r == 32 else vt.VT_OP_GEMM_ROUND_LOG_BR
+    ws = vt.alloc_workspace(vt.vt_workspace_bytes(op, M, Nn, K, 1))
     bias_d = dev(np.ascontiguousarray(bias, np.float64)) if bias is not None else None
     vt.vt_conv2d_f64_round_log(mode, d, Cout, Xd, Bd, bias_d, C32, C64, variant, tau, log, ws)
     torch.cuda.synchronize()

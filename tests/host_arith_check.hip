@@ -35,6 +35,16 @@ extern "C" void h_im2col_offsets(const int64_t *g /* N H W C KH KW sh sw ph pw d
         for (uint32_t k = 0; k < taps_to_do; ++k) offsets[(uint64_t)m * taps_to_do + k] = vt::conv_element(c, row0 + m, tap0 + k);
 }
 
+// the input-gradient view of the same loader: offsets[m * cols + kc] = element of dY or -1
+extern "C" void h_dgrad_offsets(const int64_t *g /* N H W Cout KH KW sh sw ph pw dh dw Ho Wo */, uint32_t row0, uint32_t rows_to_do,
+                                uint32_t col0, uint32_t cols_to_do, int64_t *offsets)
+{
+    const vt::ConvGeom c = vt::dgrad_geom(g[0], g[1], g[2], g[3], g[4], g[5], g[6], g[7], g[8], g[9], g[10], g[11], g[12],
+                                          g[13], false);
+    for (uint32_t m = 0; m < rows_to_do; ++m)
+        for (uint32_t k = 0; k < cols_to_do; ++k) offsets[(uint64_t)m * cols_to_do + k] = vt::dgrad_element(c, row0 + m, col0 + k);
+}
+
 // SHA-256 of one byte range with the library's per-lane routines (csrc/vt_sha256.h), stepping
 // through the blocks the way the chunk kernel does: whole blocks, then the ragged end or the
 // constant padding block.

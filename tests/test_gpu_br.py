@@ -96,6 +96,12 @@ def test_gemm_and_conv_with_a_rounding_amount(G, b):
     assert r["count"] == co and np.array_equal(_bits(r["C32"].ravel()), _bits(yo)) and np.array_equal(r["idx"], io)
     truth = vo.conv2d_fwd(X, Wt, pad=1, order=2).reshape(-1, 16)
     assert np.max(np.abs(r["C64"] - truth)) < 1e-12 * 9 * 8 * 4
+    dY = g.standard_normal((2, 6, 6, 16))
+    r = G.gpu_conv(2, dY, Wt, 3, 3, stride=2, pad=1, tau=tau, b_r=b, xshape=(2, 12, 11, 8))      # input gradient
+    yo, io, do, co = vo.round_log(r["C64"].ravel(), tau, b_r=b)
+    assert r["count"] == co and np.array_equal(_bits(r["C32"].ravel()), _bits(yo)) and np.array_equal(r["idx"], io)
+    truth = vo.conv2d_dgrad(dY, Wt, (2, 12, 11, 8), stride=2, pad=1, order=2).reshape(-1, 8)
+    assert np.max(np.abs(r["C64"] - truth)) < 1e-12 * 9 * 16 * 4
 
 
 def test_padded_output_with_a_rounding_amount_is_refused(G):

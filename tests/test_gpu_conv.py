@@ -1,4 +1,4 @@
-"""GPU parity: convolution layers (forward and weight gradient) through the implicit-im2col GEMM.
+"""GPU parity: convolution layers (forward, weight gradient, input gradient) through the implicit-im2col GEMM.
 
 FP64 values within 1e-12 * ||patch|| ||filter column|| (+ |bias|) of the oracle's extended-precision
 convolution (the definition written out as loops); FP32 outputs, index list, direction bits and
@@ -14,7 +14,7 @@ from oracle import vt_oracle as vo
 
 pytestmark = pytest.mark.gpu
 
-FWD, WGRAD = 0, 1
+FWD, WGRAD, DGRAD = 0, 1, 2
 
 
 @pytest.fixture(scope="module")
@@ -95,6 +95,34 @@ def _check_layer(G, geom, *, tau=2.0 ** -5, misalign=False, seed=0, relu_input=T
         e = G.gpu_gemm(col, dY, transA=True, tau=tau, variant=variant)
         assert np.array_equal(e["C64"][0], r["C64"])
         out[("wgrad", variant)] = r
+    # ---- input gradient
+    dYn = dY.reshape(N, Ho, Wo, Cout) * 1e3
+    truth = vo.conv2d_dgrad(dYn, Wt, X.shape, order=2, **kw).reshape(-1, Cin)
+    # the gathered matrix of the output gradient, built test-side by scattering (n, ho, wo, kh, kw) -> input position
+    (sh, sw), (ph, pw), (dh, dw) = _pair(stride), _pair(pad), _pair(dil)
+    view = np.zeros((N, H, W, KH, KW, Cout))
+    for kh in range(KH):
+        for kw_ in range(KW):
+            for ho in range(Ho):
+                h = ho * sh - ph + kh * dh
+                if not 0 <= h < H:
+                    continue
+                for wo in range(Wo):
+                    w = wo * sw - pw + kw_ * dw
+                    if 0 <= w < W:
+                        view[:, h, w, kh, kw_, :] = dYn[:, ho, wo, :]
+    view = view.reshape(N * H * W, KH * KW * Cout)
+    Wp = np.ascontiguousarray(Wt.transpose(0, 1, 3, 2)).reshape(KH * KW * Cout, Cin)
+    bound = 1e-12 * np.linalg.norm(view, axis=1)[:, None] * np.linalg.norm(Wp, axis=0)[None, :] + 1e-300
+    for variant in (0, 1):
+        r = G.gpu_conv(DGRAD, dYn, Wt, KH, KW, tau=tau, variant=variant, misalign=misalign, xshape=X.shape, **kw)
+        assert r["shape"] == (N * H * W, Cin, KH * KW * Cout)
+        assert np.all(np.abs(r["C64"] - truth) <= bound), float(np.max(np.abs(r["C64"] - truth) / bound))
+        _check_log(r, tau)
+        if not (KH == 1 and KW == 1 and _pair(stride) == (1, 1) and _pair(pad) == (0, 0)):
+            e = G.gpu_gemm(view, Wp, tau=tau, variant=variant)
+            assert np.array_equal(e["C64"][0], r["C64"])         # materialised view: same bits
+        out[("dgrad", variant)] = r
     return out
 
 
@@ -150,3 +178,7 @@ def test_empty_and_degenerate_layers(G):
     assert r["count"] == 0 and r["shape"][0] == 0
     r = G.gpu_conv(WGRAD, X, np.zeros((1, 0, 7, 4)), 3, 3, tau=0.25)       # no positions: gradient is zero
     assert r["shape"] == (27, 4, 0) and np.array_equal(r["C64"], np.zeros((27, 4))) and r["count"] == 0
+    r = G.gpu_conv(DGRAD, np.zeros((1, 0, 7, 4)), g.standard_normal((3, 3, 3, 4)), 3, 3, tau=0.25, xshape=(1, 2, 9, 3))
+    assert r["shape"] == (18, 3, 36) and np.array_equal(r["C64"], np.zeros((18, 3))) and r["count"] == 0   # no outputs: zero gradient
+    r = G.gpu_conv(DGRAD, np.zeros((2, 3, 3, 0)), np.zeros((3, 3, 5, 0)), 3, 3, pad=1, xshape=(2, 3, 3, 5))  # no output channels
+    assert r["shape"] == (18, 5, 0) and np.array_equal(r["C64"], np.zeros((18, 5))) and r["count"] == 0

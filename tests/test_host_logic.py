@@ -144,11 +144,21 @@ def test_conv_geometry_and_validation_on_the_host(hiplib):
         _, Ho, Wo = vo.conv2d_geometry((64, H, H, Cin), K, K, s, p, 1)
         assert b.vt_conv2d_gemm_shape(d, Cout, b.VT_CONV_FORWARD) == (64 * Ho * Wo, Cout, K * K * Cin)
         assert b.vt_conv2d_gemm_shape(d, Cout, b.VT_CONV_WEIGHT_GRAD) == (K * K * Cin, Cout, 64 * Ho * Wo)
+        Md, Nd, Kd = b.vt_conv2d_gemm_shape(d, Cout, b.VT_CONV_DATA_GRAD)
+        assert (Md, Nd, Kd) == (64 * H * H, Cin, K * K * Cout)
+        plain = hiplib.vt_workspace_bytes(b.VT_OP_GEMM_ROUND_LOG, Md, Nd, Kd, 1)
+        assert hiplib.vt_workspace_bytes(b.VT_OP_CONV_DGRAD_ROUND_LOG, Md, Nd, Kd, 1) >= plain + 8 * Kd * Nd
+        assert hiplib.vt_workspace_bytes(b.VT_OP_CONV_DGRAD_ROUND_LOG_BR, Md, Nd, Kd, 1) >= \
+            hiplib.vt_workspace_bytes(b.VT_OP_GEMM_ROUND_LOG_BR, Md, Nd, Kd, 1) + 8 * Kd * Nd
     f = hiplib.vt_conv2d_f64_round_log
     good = b.Conv2d(2, 8, 8, 4, 3, 3, 1, 1, 1, 1, 1, 1)
     def call(d=good, mode=0, Cout=8, X=fake, bias=None, variant=0, tau=0.1, ws=fake, wsb=1 << 20):
         return f(mode, C.byref(d), Cout, X, fake, bias, fake, None, variant, tau, C.byref(log), ws, wsb, None)
-    assert call(mode=2) == INVALID and call(variant=3) == INVALID and call(tau=0.6) == INVALID
+    assert call(mode=3) == INVALID and call(variant=3) == INVALID and call(tau=0.6) == INVALID
+    assert call(mode=2, bias=fake) == INVALID and call(mode=2, X=None) == INVALID and call(mode=2, Cout=-1) == INVALID
+    assert call(mode=2, ws=None, wsb=0) == WORKSPACE and call(mode=2, wsb=16) == WORKSPACE
+    assert call(mode=2, d=b.Conv2d(1 << 10, 1 << 10, 1 << 11, 1, 3, 3, 1, 1, 1, 1, 1, 1), Cout=1) == INVALID   # N H W >= 2^31
+    assert call(mode=2, d=b.Conv2d(2, 600, 600, 4, 300, 300, 1, 1, 1, 1, 1, 1)) == INVALID          # KH KW >= 2^16
     assert call(X=None) == INVALID and call(mode=1, bias=fake) == INVALID and call(Cout=-1) == INVALID
     for field, val in (("KH", 0), ("stride_w", 0), ("dil_h", 0), ("pad_w", -1), ("N", -1), ("H", 1 << 24)):
         bad = b.Conv2d(2, 8, 8, 4, 3, 3, 1, 1, 1, 1, 1, 1)
@@ -200,6 +210,32 @@ def test_im2col_index_arithmetic_on_host(harith):
             ok = (m < rows) & (k < taps) & (h >= 0) & (h < H) & (w >= 0) & (w < W)
             want = np.where(ok, ((n_ * H + h) * W + w) * Cin + ci, -1)
             assert np.array_equal(out, want), (geo, row0, tap0)
+
+
+def test_input_gradient_index_arithmetic_on_host(harith):
+    """The loader's view of dY for the input gradient (stride remainders of row and tap must agree)
+    against plain integer arithmetic, past the ends of the matrix too."""
+    geoms = [(2, 9, 11, 3, 3, 3, 1, 1, 1, 1, 1, 1), (1, 12, 10, 2, 7, 7, 2, 2, 3, 3, 1, 1), (3, 8, 7, 4, 1, 1, 2, 2, 0, 0, 1, 1),
+             (1, 10, 13, 3, 3, 2, 2, 1, 1, 0, 1, 2), (1, 9, 9, 2, 3, 3, 1, 1, 2, 2, 2, 2), (1, 23, 17, 5, 5, 3, 3, 2, 2, 1, 2, 3),
+             (64, 56, 56, 128, 3, 3, 2, 2, 1, 1, 1, 1), (3, 1 << 11, 1 << 11, 25, 3, 3, 2, 2, 1, 1, 1, 1)]
+    for geo in geoms:
+        N, H, W, Cout, KH, KW, sh, sw, ph, pw, dh, dw = geo
+        Ho = (H + 2 * ph - dh * (KH - 1) - 1) // sh + 1
+        Wo = (W + 2 * pw - dw * (KW - 1) - 1) // sw + 1
+        rows, cols = N * H * W, KH * KW * Cout
+        arr = np.array(list(geo) + [Ho, Wo], np.int64)
+        for row0, col0 in ((0, 0), (max(rows - 300, 0), max(cols - 150, 0)), (rows // 2, cols // 3)):
+            nr, nt = min(rows - row0 + 40, 400), min(cols - col0 + 20, 200)
+            out = np.empty((nr, nt), np.int64)
+            harith.h_dgrad_offsets(arr.ctypes.data_as(C.POINTER(C.c_int64)), C.c_uint32(row0), C.c_uint32(nr),
+                                   C.c_uint32(col0), C.c_uint32(nt), out.ctypes.data_as(C.POINTER(C.c_int64)))
+            m, k = np.meshgrid(row0 + np.arange(nr), col0 + np.arange(nt), indexing="ij")
+            n_, h, w = m // (H * W), (m // W) % H, m % W
+            kh, kw, co = k // (KW * Cout), (k // Cout) % KW, k % Cout
+            hs, ws = h + ph - kh * dh, w + pw - kw * dw
+            ok = (m < rows) & (k < cols) & (hs >= 0) & (ws >= 0) & (hs % sh == 0) & (ws % sw == 0) & (hs // sh < Ho) & (ws // sw < Wo)
+            want = np.where(ok, ((n_ * Ho + hs // sh) * Wo + ws // sw) * Cout + co, -1)
+            assert np.array_equal(out, want), (geo, row0, col0)
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
