@@ -90,7 +90,7 @@ def resnet50_conv_layers():
 def workload_streams(vt, torch, dev):
     """The other two workloads the method is quoted on, as streams of fused calls on one GPU: every GEMM of
     the GPT-2 117M layer stream (12 layers, batch 8 x 1024 tokens) and every ResNet-50 convolution at
-    batch 64 (forward and weight gradient).  tau_ulp = 1/4 (the paper's default band: half of all outputs
+    batch 64 (forward, weight gradient and input gradient).  tau_ulp = 1/4 (the paper's default band: half of all outputs
     logged), decisions in the packed ternary log.  Operands are seeded synthetic tensors of the layers'
     shapes drawn on the GPU; parity at these shapes is the tests' business, this leg only measures."""
     gen = torch.Generator(device=dev)
@@ -184,23 +184,31 @@ def workload_streams(vt, torch, dev):
     xbuf = f32grid(torch.randn(max_x, generator=gen, device=dev, dtype=torch.float64).clamp_(min=0.0))
     dybuf = torch.randn(max_y, generator=gen, device=dev, dtype=torch.float64) * 1e-3
     wbuf = f32grid(torch.randn(max_w, generator=gen, device=dev, dtype=torch.float64) * 0.05)
-    y32 = torch.empty(max(max_y, max_w), dtype=torch.float32, device=dev)
-    dlog = vt.alloc_dense_log(max(max_y, max_w))
+    y32 = torch.empty(max(max_y, max_w, max_x), dtype=torch.float32, device=dev)
+    dlog = vt.alloc_dense_log(max(max_y, max_w, max_x))
     need = 0
     for _, d, cin, kf, cout, rows in geo:
         for mode in (vt.VT_CONV_FORWARD, vt.VT_CONV_WEIGHT_GRAD):
             m, n, k = vt.vt_conv2d_gemm_shape(d, cout, mode)
             need = max(need, vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG, m, n, k, 1))
+        m, n, k = vt.vt_conv2d_gemm_shape(d, cout, vt.VT_CONV_DATA_GRAD)
+        need = max(need, vt.vt_workspace_bytes(vt.VT_OP_CONV_DGRAD_ROUND_LOG, m, n, k, 1))
     ws = vt.alloc_workspace(need)
-    fwd, wgr = [], []
-    for kind, d, cin, kf, cout, rows in geo:
+    fwd, wgr, dgr = [], [], []
+    for li, (kind, d, cin, kf, cout, rows) in enumerate(geo):
         fl = 2.0 * rows * cout * kf * kf * cin
+        if li > 0:      # the network's input needs no gradient
+            dgr.append((kind, fl, lambda d=d, cout=cout: vt.vt_conv2d_f64_round_log(
+                vt.VT_CONV_DATA_GRAD, d, cout, dybuf, wbuf, None, y32, None, 0, tau, dlog, ws)))
         fwd.append((kind, fl, lambda d=d, cout=cout: vt.vt_conv2d_f64_round_log(
             vt.VT_CONV_FORWARD, d, cout, xbuf, wbuf, None, y32, None, 0, tau, dlog, ws)))
         wgr.append((kind, fl, lambda d=d, cout=cout: vt.vt_conv2d_f64_round_log(
             vt.VT_CONV_WEIGHT_GRAD, d, cout, xbuf, dybuf, None, y32, None, 0, tau, dlog, ws)))
     out["resnet50_conv_forward"] = run_stream(fwd)
     out["resnet50_conv_weight_grad"] = run_stream(wgr)
+    out["resnet50_conv_input_grad"] = run_stream(dgr)
+    out["resnet50_conv_input_grad"]["workload"] = ("input gradients of the 52 layers after the first; flops counted as the "
+                                                   "forward layer's (a strided layer multiplies the zeros of its view too)")
     out["resnet50_conv_forward"]["workload"] = "all 53 convolutions of ResNet-50, batch 64, 224 x 224 x 3 input, implicit im2col"
     out["resnet50_conv_weight_grad"]["workload"] = "weight gradients of the same 53 layers (deterministic split-K where the plan asks for it)"
     return out

@@ -1,5 +1,6 @@
 // vt_api.hip -- the C ABI declared in include/vt.h: argument checks and kernel sequencing.
 #include "../../include/vt.h"
+#include "vt_conv_phases.h"
 #include "vt_kernels.h"
 
 #include <cmath>
@@ -44,6 +45,19 @@ inline int max_splits(int64_t M, int64_t N, int64_t K, int64_t batch)
 inline bool split_allowed(int64_t M, int64_t N, int64_t batch, int64_t ldc, int64_t strideC)
 {
     return ldc == N && (batch <= 1 || strideC == M * N);    // the round/log pass sees one flat tensor
+}
+
+inline size_t up256(size_t v) { return (v + 255) / 256 * 256; }
+
+// Input gradient of a convolution: offset of the re-laid filter in the workspace.  Below it lies
+// either the GEMM's own workspace (one GEMM over the whole view) or, for a strided layer computed
+// phase by phase, the round/log scratch and the phases' FP64 results.
+inline size_t dgrad_filter_offset(int64_t M, int64_t N, int64_t K, bool two_pass)
+{
+    const size_t gemm = vt_workspace_bytes(two_pass ? VT_OP_GEMM_ROUND_LOG_BR : VT_OP_GEMM_ROUND_LOG, M, N, K, 1);
+    const uint64_t total = (uint64_t)M * (uint64_t)N;
+    const size_t phased = up256(round_log_bytes(total)) + up256((size_t)total * 8);
+    return up256(gemm > phased ? gemm : phased);
 }
 
 // round + log of a flat FP64 tensor that already lives in device memory (trainer hook)
@@ -190,11 +204,52 @@ int conv_dgrad_entry(const vt::ConvDesc &c, int64_t Cout, const double *dY, cons
         return run_gemm(g, log, ws, ws_bytes, s);
     }
     const bool two_pass = k_of(log->b_r) != 0;
-    const size_t gemm = vt_workspace_bytes(two_pass ? VT_OP_GEMM_ROUND_LOG_BR : VT_OP_GEMM_ROUND_LOG, M, N, K, 1);
-    const size_t at = (gemm + 255) / 256 * 256;
+    const size_t at = dgrad_filter_offset(M, N, K, two_pass);
     if (!ws || !aligned(ws, 256) || ws_bytes < at + (size_t)K * (size_t)N * 8) return VT_ERR_WORKSPACE;
     double *Wp = (double *)((char *)ws + at);
-    if (K > 0 && vt::launch_dgrad_weights(Wt, c.KH * c.KW, c.C, Cout, Wp, s) != hipSuccess) return VT_ERR_HIP;
+    const uint64_t total = (uint64_t)M * (uint64_t)N;
+    const bool phased = K > 0 && (c.stride_h > 1 || c.stride_w > 1) && c.stride_h <= 2 && c.stride_w <= 2 && N % 2 == 0 &&
+                        aligned(C32, 8) && (!C64_debug || aligned(C64_debug, 16));
+    if (phased) {
+        // One GEMM per stride phase (no structural zeros multiplied), FP64 results side by side in
+        // the workspace, then one round/log pass that looks every output up in its phase.
+        double *slabs = (double *)((char *)ws + up256(round_log_bytes(total)));
+        vt::PhaseArgs pa{};
+        pa.P = slabs; pa.H = (uint32_t)c.H; pa.W = (uint32_t)c.W; pa.C = (uint32_t)c.C;
+        pa.ph = (uint32_t)c.pad_h; pa.pw = (uint32_t)c.pad_w; pa.sh = (uint32_t)c.stride_h; pa.sw = (uint32_t)c.stride_w;
+        pa.y64 = C64_debug;
+        uint64_t slab_off = 0, w_off = 0;
+        mark_begin(s);
+        for (int64_t a = 0; a < c.stride_h; ++a)
+            for (int64_t b = 0; b < c.stride_w; ++b) {
+                const vt::PhaseAxis ax = vt::phase_axis(c.H, c.KH, c.stride_h, c.pad_h, c.dil_h, a);
+                const vt::PhaseAxis bx = vt::phase_axis(c.W, c.KW, c.stride_w, c.pad_w, c.dil_w, b);
+                const int idx = (int)(2 * a + b);
+                pa.q0h[a] = (uint32_t)ax.q0; pa.Ha[a] = (uint32_t)ax.count;
+                pa.q0w[b] = (uint32_t)bx.q0; pa.Wb[b] = (uint32_t)bx.count;
+                pa.off[idx] = (uint32_t)slab_off;
+                const int64_t rows = c.N * ax.count * bx.count, taps = ax.taps * bx.taps;
+                if (rows == 0 || taps == 0) continue;            // no positions, or no filter tap reaches them: zeros
+                pa.has |= 1u << idx;
+                if (vt::launch_dgrad_weights(Wt, c.KW, c.C, Cout, ax.k0, ax.kstep, ax.taps, bx.k0, bx.kstep, bx.taps,
+                                             Wp + w_off, s) != hipSuccess)
+                    return VT_ERR_HIP;
+                const vt::ConvDesc sub{c.N, ax.count, bx.count, c.C, ax.taps, bx.taps, 1, 1, ax.pad, bx.pad, ax.dil, bx.dil, c.Ho, c.Wo};
+                vt::GemmArgs q = g;
+                q.conv = &sub; q.conv_dgrad_cout = Cout;
+                q.M = rows; q.K = taps * Cout; q.lda = 0; q.B = Wp + w_off; q.transB = 0; q.ldb = N; q.raw = true;
+                const vt::GemmPlan plan = vt::plan_gemm(q.M, q.N, q.K, 1, /*allow_split=*/false, /*transA=*/false);
+                if (vt::launch_gemm_round_planes(q, plan, vt::Planes{}, slabs + slab_off, nullptr, s) != hipSuccess) return VT_ERR_HIP;
+                slab_off += (uint64_t)rows * (uint64_t)N;
+                w_off += (uint64_t)taps * (uint64_t)Cout * (uint64_t)N;
+            }
+        mark_end(s);
+        const uint32_t k = k_of(log->b_r);
+        if (log->dense)
+            return hip_status(vt::launch_phase_log_dense(pa, total, thr, k, C32, log->dense, log->count, (uint64_t *)ws, s));
+        return hip_status(vt::launch_phase_log_onepass(pa, total, thr, k, C32, ws, vt::LogOut{log->idx, log->dir, log->cap, log->count}, s));
+    }
+    if (K > 0 && vt::launch_dgrad_weights(Wt, c.KW, c.C, Cout, 0, 1, c.KH, 0, 1, c.KW, Wp, s) != hipSuccess) return VT_ERR_HIP;
     g.conv = &c; g.conv_dgrad_cout = Cout;
     g.lda = 0; g.B = Wp; g.transB = 0; g.ldb = N;
     return run_gemm(g, log, ws, at, s);
@@ -244,9 +299,8 @@ size_t vt_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int64_t batch
     case VT_OP_CONV_DGRAD_ROUND_LOG:
     case VT_OP_CONV_DGRAD_ROUND_LOG_BR: {
         // the GEMM's workspace, then the filter in the layout the GEMM multiplies by (K x N doubles)
-        if (K < 0) return 0;
-        const size_t gemm = vt_workspace_bytes(op == VT_OP_CONV_DGRAD_ROUND_LOG ? VT_OP_GEMM_ROUND_LOG : VT_OP_GEMM_ROUND_LOG_BR, M, N, K, batch);
-        return (gemm + 255) / 256 * 256 + (size_t)K * (size_t)N * 8;
+        if (K < 0 || batch != 1) return 0;
+        return dgrad_filter_offset(M, N, K, op == VT_OP_CONV_DGRAD_ROUND_LOG_BR) + (size_t)K * (size_t)N * 8;
     }
     case VT_OP_SHA256_TREE:
         if (K < 0 || (K % 64) != 0) return 0;

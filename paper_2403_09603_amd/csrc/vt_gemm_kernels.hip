@@ -110,34 +110,39 @@ size_t gemm_split_bytes(int64_t M, int64_t N, int64_t batch, int splits)
 namespace {
 
 // one 32 x 32 block of one filter position, transposed through LDS (reads and writes coalesced)
-__global__ __launch_bounds__(256) void dgrad_weights_kernel(const double *__restrict__ Wt, uint32_t C, uint32_t Cout,
+__global__ __launch_bounds__(256) void dgrad_weights_kernel(const double *__restrict__ Wt, uint32_t KW, uint32_t C, uint32_t Cout,
+                                                            uint32_t kh0, uint32_t sth, uint32_t kw0, uint32_t stw, uint32_t nkw,
                                                             double *__restrict__ Wp)
 {
     __shared__ double tile[32][33];
     const uint32_t tx = threadIdx.x & 31u, ty = threadIdx.x >> 5;            // 32 x 8 threads
-    const uint64_t tap = blockIdx.z, plane = (uint64_t)C * Cout;
+    const uint32_t ih = blockIdx.z / nkw, iw = blockIdx.z % nkw;
+    const uint64_t plane = (uint64_t)C * Cout;
+    const uint64_t src = (uint64_t)((kh0 + sth * ih) * KW + kw0 + stw * iw) * plane, dst = (uint64_t)blockIdx.z * plane;
     const uint32_t co0 = blockIdx.x * 32u, c0 = blockIdx.y * 32u;
 #pragma unroll
     for (uint32_t i = 0; i < 32; i += 8) {
         const uint32_t c = c0 + ty + i, co = co0 + tx;
-        if (c < C && co < Cout) tile[ty + i][tx] = Wt[tap * plane + (uint64_t)c * Cout + co];
+        if (c < C && co < Cout) tile[ty + i][tx] = Wt[src + (uint64_t)c * Cout + co];
     }
     __syncthreads();
 #pragma unroll
     for (uint32_t i = 0; i < 32; i += 8) {
         const uint32_t co = co0 + ty + i, c = c0 + tx;
-        if (c < C && co < Cout) Wp[tap * plane + (uint64_t)co * C + c] = tile[tx][ty + i];
+        if (c < C && co < Cout) Wp[dst + (uint64_t)co * C + c] = tile[tx][ty + i];
     }
 }
 
 }  // namespace
 
-hipError_t launch_dgrad_weights(const double *Wt, int64_t taps_hw, int64_t C, int64_t Cout, double *Wp, hipStream_t s)
+hipError_t launch_dgrad_weights(const double *Wt, int64_t KW, int64_t C, int64_t Cout, int64_t kh0, int64_t sth, int64_t nkh,
+                                int64_t kw0, int64_t stw, int64_t nkw, double *Wp, hipStream_t s)
 {
-    if (taps_hw <= 0 || C <= 0 || Cout <= 0) return hipSuccess;
-    const uint64_t gx = (uint64_t)(Cout + 31) / 32, gy = (uint64_t)(C + 31) / 32;
-    if (gx > 0x7FFFFFFFull || gy > 65535ull || (uint64_t)taps_hw > 65535ull) return hipErrorInvalidValue;
-    dgrad_weights_kernel<<<dim3((uint32_t)gx, (uint32_t)gy, (uint32_t)taps_hw), 256, 0, s>>>(Wt, (uint32_t)C, (uint32_t)Cout, Wp);
+    if (nkh <= 0 || nkw <= 0 || C <= 0 || Cout <= 0) return hipSuccess;
+    const uint64_t gx = (uint64_t)(Cout + 31) / 32, gy = (uint64_t)(C + 31) / 32, gz = (uint64_t)nkh * (uint64_t)nkw;
+    if (gx > 0x7FFFFFFFull || gy > 65535ull || gz > 65535ull) return hipErrorInvalidValue;
+    dgrad_weights_kernel<<<dim3((uint32_t)gx, (uint32_t)gy, (uint32_t)gz), 256, 0, s>>>(
+        Wt, (uint32_t)KW, (uint32_t)C, (uint32_t)Cout, (uint32_t)kh0, (uint32_t)sth, (uint32_t)kw0, (uint32_t)stw, (uint32_t)nkw, Wp);
     return hipGetLastError();
 }
 

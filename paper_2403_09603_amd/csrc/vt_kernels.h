@@ -109,6 +109,19 @@ hipError_t launch_splitk_log_onepass(const SplitKArgs &a, uint64_t n, uint32_t t
 hipError_t launch_splitk_log_dense(const SplitKArgs &a, uint64_t n, uint32_t thr, uint32_t k, float *y, uint8_t *tlog,
                                    uint64_t *n_logged, uint64_t *slots, hipStream_t s);
 
+// the trainer hook over an input gradient computed phase by phase (see PhaseSource in vt_source.h;
+// C even, slabs 16-byte aligned, y 8-byte aligned, y64 null or 16-byte aligned)
+struct PhaseArgs {
+    const double *P;
+    uint32_t H, W, C, ph, pw, sh, sw;       // sh, sw: 1 or 2
+    uint32_t q0h[2], Ha[2], q0w[2], Wb[2], off[4], has;
+    double *y64;
+};
+hipError_t launch_phase_log_onepass(const PhaseArgs &a, uint64_t n, uint32_t thr, uint32_t k, float *y, void *ws,
+                                    const LogOut &log, hipStream_t s);
+hipError_t launch_phase_log_dense(const PhaseArgs &a, uint64_t n, uint32_t thr, uint32_t k, float *y, uint8_t *tlog,
+                                  uint64_t *n_logged, uint64_t *slots, hipStream_t s);
+
 hipError_t launch_stats(const double *y1, const double *y2, uint64_t n, uint32_t k, uint64_t *out, hipStream_t s);
 
 // Geometry of a channels-last convolution whose image the GEMM kernel reads through an implicit
@@ -151,8 +164,11 @@ size_t gemm_split_bytes(int64_t M, int64_t N, int64_t batch, int splits);
 // consumes them).
 hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, const Planes &pl, double *partial,
                                     double *reduced, hipStream_t s);
-// Filter Wt[taps_hw][C][Cout] -> Wp[taps_hw][Cout][C]: the B operand (K x C, row-major) of the
+// Filter Wt[KH][KW][C][Cout] -> Wp[filter position][Cout][C]: the B operand (K x C, row-major) of the
 // input-gradient GEMM.  A copy, so exact.
-hipError_t launch_dgrad_weights(const double *Wt, int64_t taps_hw, int64_t C, int64_t Cout, double *Wp, hipStream_t s);
+// Only the filter positions (kh0 + sth i, kw0 + stw j), i < nkh, j < nkw, are taken (a stride phase's
+// sub-filter); the whole filter is (0, 1, KH, 0, 1, KW).
+hipError_t launch_dgrad_weights(const double *Wt, int64_t KW, int64_t C, int64_t Cout, int64_t kh0, int64_t sth, int64_t nkh,
+                                int64_t kw0, int64_t stw, int64_t nkw, double *Wp, hipStream_t s);
 
 }  // namespace vt

@@ -345,6 +345,20 @@ hipError_t launch_splitk_log_dense(const SplitKArgs &a, uint64_t n, uint32_t thr
     return launch_dense_from(src, true, n, thr, k, y, tlog, n_logged, slots, s);
 }
 
+hipError_t launch_phase_log_dense(const PhaseArgs &a, uint64_t n, uint32_t thr, uint32_t k, float *y, uint8_t *tlog,
+                                  uint64_t *n_logged, uint64_t *slots, hipStream_t s)
+{
+    if (a.sh < 1 || a.sh > 2 || a.sw < 1 || a.sw > 2 || a.C == 0 || a.C % 2 || a.H == 0 || a.W == 0) return hipErrorInvalidValue;
+    PhaseSource src;
+    src.P = a.P; src.C = a.C; src.W = a.W; src.HW = a.H * a.W;
+    src.inv_C = 1.0 / (double)a.C; src.inv_W = 1.0 / (double)a.W; src.inv_HW = 1.0 / (double)(a.H * a.W);
+    src.ph = a.ph; src.pw = a.pw; src.shift_h = a.sh - 1u; src.shift_w = a.sw - 1u;
+    for (int i = 0; i < 2; ++i) { src.q0h[i] = a.q0h[i]; src.Ha[i] = a.Ha[i]; src.q0w[i] = a.q0w[i]; src.Wb[i] = a.Wb[i]; }
+    for (int i = 0; i < 4; ++i) src.off[i] = a.off[i];
+    src.has = a.has; src.y64 = a.y64;
+    return launch_dense_from(src, true, n, thr, k, y, tlog, n_logged, slots, s);
+}
+
 // the same stream with a layer evaluated on the fly as its source (inputs 16-byte aligned)
 hipError_t launch_layer_log_dense(const LayerArgs &g, uint64_t n, uint32_t thr, uint32_t k, float *y, uint8_t *tlog,
                                   uint64_t *n_logged, uint64_t *slots, hipStream_t s)

@@ -93,6 +93,67 @@ struct SplitKSource {
     }
 };
 
+// The input gradient of a strided convolution computed phase by phase (strides 1 or 2 per axis):
+// the positions (n, h, w) of the layer's input with ((h + p_h) mod s_h, (w + p_w) mod s_w) = (a, b)
+// form a dense sub-grid whose FP64 results lie in slab (a, b), rows (n, i, j) by C channels.
+// Element e of the gradient [N][H][W][C] is looked up in its slab; a phase that no filter tap
+// reaches has no slab and reads as zero.  C is even, so a pair (e, e + 1) shares its position.
+struct PhaseSource {
+    const double *P;
+    uint32_t C, W, HW;
+    double inv_C, inv_W, inv_HW;
+    uint32_t ph, pw, shift_h, shift_w;     // shift = stride - 1 (0 or 1): phase = low bit, q = the rest
+    uint32_t q0h[2], Ha[2], q0w[2], Wb[2];
+    uint32_t off[4];                       // first element of slab (a, b) at off[2 a + b]
+    uint32_t has;                          // bit 2 a + b: the phase has a slab
+    double *y64;
+    template <bool FULL, bool VEC>
+    __device__ __forceinline__ src_d2 pair(uint64_t e, uint64_t n) const
+    {
+        src_d2 v = {1.0, 1.0};
+        if (!(FULL || e + 1 < n)) {
+            if (e < n) v.x = one((uint32_t)e);
+            return v;
+        }
+        uint32_t pos, c, img, rem, h, w;
+        divmod_u32((uint32_t)e, C, inv_C, pos, c);
+        divmod_u32(pos, HW, inv_HW, img, rem);
+        divmod_u32(rem, W, inv_W, h, w);
+        const uint32_t hp = h + ph, wp = w + pw;
+        const uint32_t a = hp & shift_h, b = wp & shift_w;
+        const uint32_t i = (hp >> shift_h) - (a ? q0h[1] : q0h[0]), j = (wp >> shift_w) - (b ? q0w[1] : q0w[0]);
+        const uint32_t rows_h = a ? Ha[1] : Ha[0], rows_w = b ? Wb[1] : Wb[0];
+        const uint32_t o = a ? (b ? off[3] : off[2]) : (b ? off[1] : off[0]);
+        const bool live = (has >> (2u * a + b)) & 1u;
+        const uint32_t at = live ? o + ((img * rows_h + i) * rows_w + j) * C + c : 0u;
+        const src_d2 x = *(const src_d2 *)(P + at);
+        v.x = live ? x.x : 0.0;
+        v.y = live ? x.y : 0.0;
+        return v;
+    }
+    __device__ __forceinline__ double one(uint32_t e) const      // a single element (odd tail; not reached for even C)
+    {
+        uint32_t pos, c, img, rem, h, w;
+        divmod_u32(e, C, inv_C, pos, c);
+        divmod_u32(pos, HW, inv_HW, img, rem);
+        divmod_u32(rem, W, inv_W, h, w);
+        const uint32_t hp = h + ph, wp = w + pw;
+        const uint32_t a = hp & shift_h, b = wp & shift_w;
+        const uint32_t i = (hp >> shift_h) - (a ? q0h[1] : q0h[0]), j = (wp >> shift_w) - (b ? q0w[1] : q0w[0]);
+        const uint32_t rows_h = a ? Ha[1] : Ha[0], rows_w = b ? Wb[1] : Wb[0];
+        const uint32_t o = a ? (b ? off[3] : off[2]) : (b ? off[1] : off[0]);
+        const bool live = (has >> (2u * a + b)) & 1u;
+        return live ? P[o + ((img * rows_h + i) * rows_w + j) * C + c] : 0.0;
+    }
+    template <bool FULL, bool VEC>
+    __device__ __forceinline__ void keep(uint64_t e, uint64_t n, src_d2 v) const
+    {
+        if (!y64) return;
+        if (FULL || e + 1 < n) *(src_d2 *)(y64 + e) = v;
+        else if (e < n) y64[e] = v.x;
+    }
+};
+
 // One output of a layer from its input value(s); e is the output's linear index (< n).
 template <int OP>
 __device__ __forceinline__ double layer_value(const LayerArgs &g, uint32_t e, double xa, double xb)

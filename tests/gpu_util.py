@@ -101,10 +101,10 @@ def gpu_gemm(A, B, *, transA=False, transB=False, alpha=1.0, bias=None, tau=0.0,
 
 
 def gpu_conv(mode, X, B, KH, KW, *, stride=1, pad=0, dil=1, bias=None, tau=0.0, variant=0, misalign=False, b_r=32,
-             xshape=None):
+             xshape=None, dense=False):
     """mode 0: forward, B = weights (KH,KW,C,Cout); mode 1: weight gradient, B = dY (N,Ho,Wo,Cout).
     X is (N,H,W,C).  mode 2: input gradient, X = dY (N,Ho,Wo,Cout), B = weights, xshape = (N,H,W,C).
-    misalign=True puts X on an 8-byte (not 16-byte) boundary."""
+    misalign=True puts X on an 8-byte (not 16-byte) boundary.  dense=True asks for the packed ternary log."""
     pair = lambda v: (int(v), int(v)) if np.isscalar(v) else (int(v[0]), int(v[1]))
     (sh, sw), (ph, pw), (dh, dw) = pair(stride), pair(pad), pair(dil)
     X = np.ascontiguousarray(X, np.float64)
@@ -123,8 +123,10 @@ def gpu_conv(mode, X, B, KH, KW, *, stride=1, pad=0, dil=1, bias=None, tau=0.0, 
     Bd = dev(B.ravel())
     C32 = torch.full((max(M * Nn, 1),), float("nan"), dtype=torch.float32, device=DEV)
     C64 = torch.empty(max(M * Nn, 1), dtype=torch.float64, device=DEV)
-    log = vt.alloc_log(M * Nn)
+    log = vt.alloc_dense_log(M * Nn) if dense else vt.alloc_log(M * Nn)
     log.b_r = b_r
+    if dense:
+        log.dense.fill_(0xEE)
     if mode == 2:
         op = vt.VT_OP_CONV_DGRAD_ROUND_LOG if b_r == 32 else vt.VT_OP_CONV_DGRAD_ROUND_LOG_BR
     else:
@@ -134,6 +136,11 @@ def gpu_conv(mode, X, B, KH, KW, *, stride=1, pad=0, dil=1, bias=None, tau=0.0, 
     vt.vt_conv2d_f64_round_log(mode, d, Cout, Xd, Bd, bias_d, C32, C64, variant, tau, log, ws)
     torch.cuda.synchronize()
     count = int(log.count.item())
+    if dense:
+        full = log.dense.cpu().numpy()
+        assert (full[(M * Nn + 4) // 5:] == 0xEE).all()
+        return {"C32": C32.cpu().numpy()[:M * Nn].reshape(M, Nn), "C64": C64.cpu().numpy()[:M * Nn].reshape(M, Nn),
+                "tlog": full[:(M * Nn + 4) // 5].copy(), "count": count, "shape": (M, Nn, K)}
     return {"C32": C32.cpu().numpy()[:M * Nn].reshape(M, Nn), "C64": C64.cpu().numpy()[:M * Nn].reshape(M, Nn),
             "idx": u32(log.idx)[:count].copy(), "dir": u32(log.dir)[:(count + 31) // 32].copy(), "count": count,
             "shape": (M, Nn, K)}

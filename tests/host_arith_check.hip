@@ -1,6 +1,7 @@
 // Test helper: runs the library's per-element integer arithmetic (csrc/vt_device.h) on the HOST
 // CPU, so its rounding / distance / direction logic can be compared with the oracle without a GPU.
 #include "../paper_2403_09603_amd/csrc/vt_device.h"
+#include "../paper_2403_09603_amd/csrc/vt_conv_phases.h"
 extern "C" void h_decide(const uint64_t *bits, uint64_t n, uint32_t *y, uint32_t *D, uint32_t *dir)
 {
     for (uint64_t i = 0; i < n; ++i) {
@@ -41,6 +42,27 @@ extern "C" void h_dgrad_offsets(const int64_t *g /* N H W Cout KH KW sh sw ph pw
 {
     const vt::ConvGeom c = vt::dgrad_geom(g[0], g[1], g[2], g[3], g[4], g[5], g[6], g[7], g[8], g[9], g[10], g[11], g[12],
                                           g[13], false);
+    for (uint32_t m = 0; m < rows_to_do; ++m)
+        for (uint32_t k = 0; k < cols_to_do; ++k) offsets[(uint64_t)m * cols_to_do + k] = vt::dgrad_element(c, row0 + m, col0 + k);
+}
+
+// One stride phase of the input gradient, planned and indexed as the library does it: the phase's
+// axes go to info[0..13] (q0, count, k0, kstep, taps, pad, dil for h, then for w) and
+// offsets[m * cols + kc] = element of dY that the phase's GEMM reads at (row m, column kc), or -1.
+extern "C" void h_dgrad_phase_offsets(const int64_t *g /* N H W Cout KH KW sh sw ph pw dh dw Ho Wo */, int64_t a, int64_t b,
+                                      uint32_t row0, uint32_t rows_to_do, uint32_t col0, uint32_t cols_to_do,
+                                      int64_t *info, int64_t *offsets)
+{
+    const vt::PhaseAxis ax = vt::phase_axis(g[1], g[4], g[6], g[8], g[10], a);
+    const vt::PhaseAxis bx = vt::phase_axis(g[2], g[5], g[7], g[9], g[11], b);
+    const vt::PhaseAxis *axes[2] = {&ax, &bx};
+    for (int i = 0; i < 2; ++i) {
+        int64_t *o = info + 7 * i;
+        o[0] = axes[i]->q0; o[1] = axes[i]->count; o[2] = axes[i]->k0; o[3] = axes[i]->kstep; o[4] = axes[i]->taps;
+        o[5] = axes[i]->pad; o[6] = axes[i]->dil;
+    }
+    const vt::ConvGeom c = vt::dgrad_geom(g[0], ax.count, bx.count, g[3], ax.taps, bx.taps, 1, 1, ax.pad, bx.pad, ax.dil, bx.dil,
+                                          g[12], g[13], false);
     for (uint32_t m = 0; m < rows_to_do; ++m)
         for (uint32_t k = 0; k < cols_to_do; ++k) offsets[(uint64_t)m * cols_to_do + k] = vt::dgrad_element(c, row0 + m, col0 + k);
 }

@@ -119,7 +119,9 @@ def _check_layer(G, geom, *, tau=2.0 ** -5, misalign=False, seed=0, relu_input=T
         assert r["shape"] == (N * H * W, Cin, KH * KW * Cout)
         assert np.all(np.abs(r["C64"] - truth) <= bound), float(np.max(np.abs(r["C64"] - truth) / bound))
         _check_log(r, tau)
-        if not (KH == 1 and KW == 1 and _pair(stride) == (1, 1) and _pair(pad) == (0, 0)):
+        one_gemm_over_the_view = not (KH == 1 and KW == 1 and _pair(stride) == (1, 1) and _pair(pad) == (0, 0)) and \
+            (_pair(stride) == (1, 1) or max(_pair(stride)) > 2 or Cin % 2 == 1)
+        if one_gemm_over_the_view:      # (strided layers with even C run one GEMM per stride phase instead)
             e = G.gpu_gemm(view, Wp, tau=tau, variant=variant)
             assert np.array_equal(e["C64"][0], r["C64"])         # materialised view: same bits
         out[("dgrad", variant)] = r
@@ -135,6 +137,9 @@ SMALL = [  # (N, H, W, C, KH, KW, Cout, stride, pad, dil)
     (1, 4, 4, 1, 5, 5, 1, 1, 2, 1),
     (2, 9, 7, 5, 1, 1, 6, 1, 0, 1),          # 1 x 1 at every position, odd channel count: the plain-matrix route
     (3, 20, 17, 64, 1, 1, 70, 1, 0, 3),      # the same with whole tiles, a ragged edge, and a dilation that cannot matter
+    (1, 11, 10, 4, 3, 3, 6, 3, 1, 1),        # stride 3: the input gradient as one GEMM over the strided view
+    (2, 10, 13, 4, 3, 2, 2, (2, 1), (1, 0), (1, 2)),   # stride phases along one axis only, dilation along the other
+    (1, 9, 12, 6, 4, 3, 4, 2, (0, 2), (2, 1)),         # dilation equal to the stride: one phase gets every filter row
 ]
 
 
@@ -169,6 +174,30 @@ def test_weight_gradient_with_split_k_is_deterministic(G):
     for key in a:
         assert np.array_equal(a[key]["C64"], b[key]["C64"]) and np.array_equal(a[key]["idx"], b[key]["idx"])
     assert (a[("wgrad", 0)]["C64"] != a[("wgrad", 1)]["C64"]).mean() > 0.3
+
+
+@pytest.mark.parametrize("geom", [(2, 13, 12, 8, 3, 3, 16, 2, 1, 1), (2, 12, 12, 6, 3, 3, 10, 1, 1, 1)])
+def test_packed_log_from_every_mode(G, geom):
+    """Forward, weight gradient and input gradient (per stride phase and as one GEMM) writing the
+    packed ternary log: bytes, FP32 outputs and count against the oracle on the kernel's FP64 values;
+    the input gradient's values must not depend on the log format."""
+    N, H, W, Cin, KH, KW, Cout, stride, pad, dil = geom
+    g = si.rng(si.seed_for(4, 30))
+    X = np.maximum(g.standard_normal((N, H, W, Cin)), 0.0)
+    Wt = g.standard_normal((KH, KW, Cin, Cout)) * 0.2
+    _, Ho, Wo = vo.conv2d_geometry(X.shape, KH, KW, stride, pad, dil)
+    dY = g.standard_normal((N, Ho, Wo, Cout))
+    kw = dict(stride=stride, pad=pad, dil=dil)
+    tau = 0.25
+    for mode, a, b, extra in ((FWD, X, Wt, {}), (WGRAD, X, dY, {}), (DGRAD, dY, Wt, {"xshape": X.shape})):
+        for variant in (0, 1):
+            r = G.gpu_conv(mode, a, b, KH, KW, tau=tau, variant=variant, dense=True, **kw, **extra)
+            yo, to, co = vo.round_log_dense(r["C64"].ravel(), tau)
+            assert r["count"] == co and co > r["C64"].size // 3
+            assert np.array_equal(_bits(r["C32"].ravel()), _bits(yo)) and np.array_equal(r["tlog"], to)
+            if mode == DGRAD:
+                sparse = G.gpu_conv(mode, a, b, KH, KW, tau=tau, variant=variant, **kw, **extra)
+                assert np.array_equal(sparse["C64"], r["C64"])
 
 
 def test_empty_and_degenerate_layers(G):

@@ -238,6 +238,63 @@ def test_input_gradient_index_arithmetic_on_host(harith):
             assert np.array_equal(out, want), (geo, row0, col0)
 
 
+def test_input_gradient_stride_phases_on_host(harith):
+    """The split of a strided layer's input gradient into one stride-1 problem per phase: the phases
+    partition the input positions and the filter taps, and every (row, column) of a phase's GEMM reads
+    the element of dY that the definition names (or nothing)."""
+    geoms = [(2, 9, 11, 4, 3, 3, 2, 2, 1, 1, 1, 1), (1, 12, 10, 2, 7, 7, 2, 2, 3, 3, 1, 1), (3, 8, 7, 4, 1, 1, 2, 2, 0, 0, 1, 1),
+             (1, 10, 13, 2, 3, 2, 2, 1, 1, 0, 1, 2), (1, 9, 9, 2, 3, 3, 2, 2, 2, 2, 2, 2), (1, 23, 17, 6, 5, 3, 3, 2, 2, 1, 2, 3),
+             (2, 7, 8, 2, 4, 5, 4, 3, 0, 5, 3, 2), (1, 5, 6, 2, 2, 2, 2, 2, 3, 3, 1, 1), (4, 56, 56, 8, 3, 3, 2, 2, 1, 1, 1, 1)]
+    for geo in geoms:
+        N, H, W, Cout, KH, KW, sh, sw, ph, pw, dh, dw = geo
+        Ho = (H + 2 * ph - dh * (KH - 1) - 1) // sh + 1
+        Wo = (W + 2 * pw - dw * (KW - 1) - 1) // sw + 1
+        arr = np.array(list(geo) + [Ho, Wo], np.int64)
+        seen_pos, seen_taps = np.zeros((H, W), int), np.zeros((KH, KW), int)
+        for a in range(sh):
+            for b in range(sw):
+                info = np.zeros(14, np.int64)
+                probe = np.empty((1, 1), np.int64)
+                harith.h_dgrad_phase_offsets(arr.ctypes.data_as(C.POINTER(C.c_int64)), C.c_int64(a), C.c_int64(b), C.c_uint32(0),
+                                             C.c_uint32(1), C.c_uint32(0), C.c_uint32(1), info.ctypes.data_as(C.POINTER(C.c_int64)),
+                                             probe.ctypes.data_as(C.POINTER(C.c_int64)))
+                q0h, Ha, kh0, sth, nkh, _, _, q0w, Wb, kw0, stw, nkw, _, _ = (int(v) for v in info)
+                hs = [sh * (q0h + i) + a - ph for i in range(Ha)]
+                ws_ = [sw * (q0w + j) + b - pw for j in range(Wb)]
+                khs = [kh0 + sth * t for t in range(nkh)]
+                kws = [kw0 + stw * t for t in range(nkw)]
+                assert hs == [h for h in range(H) if (h + ph) % sh == a] and ws_ == [w for w in range(W) if (w + pw) % sw == b]
+                assert khs == [k for k in range(KH) if (k * dh) % sh == a] and kws == [k for k in range(KW) if (k * dw) % sw == b]
+                for h in hs:
+                    for w in ws_:
+                        seen_pos[h, w] += 1
+                for kh in khs:
+                    for kw in kws:
+                        seen_taps[kh, kw] += 1
+                rows, cols = N * Ha * Wb, nkh * nkw * Cout
+                if rows == 0 or cols == 0:
+                    continue
+                for row0, col0 in ((0, 0), (max(rows - 200, 0), max(cols - 100, 0))):
+                    nr, nt = min(rows - row0 + 20, 260), min(cols - col0 + 10, 130)
+                    out = np.empty((nr, nt), np.int64)
+                    harith.h_dgrad_phase_offsets(arr.ctypes.data_as(C.POINTER(C.c_int64)), C.c_int64(a), C.c_int64(b),
+                                                 C.c_uint32(row0), C.c_uint32(nr), C.c_uint32(col0), C.c_uint32(nt),
+                                                 info.ctypes.data_as(C.POINTER(C.c_int64)), out.ctypes.data_as(C.POINTER(C.c_int64)))
+                    m, k = np.meshgrid(row0 + np.arange(nr), col0 + np.arange(nt), indexing="ij")
+                    inside = (m < rows) & (k < cols)
+                    mm, kk = np.minimum(m, rows - 1), np.minimum(k, cols - 1)
+                    n_, i, j = mm // (Ha * Wb), (mm // Wb) % Ha, mm % Wb
+                    th, tw, co = kk // (nkw * Cout), (kk // Cout) % nkw, kk % Cout
+                    h, w = np.array(hs)[i], np.array(ws_)[j]
+                    kh, kw = np.array(khs)[th], np.array(kws)[tw]
+                    hsrc, wsrc = h + ph - kh * dh, w + pw - kw * dw
+                    assert ((hsrc % sh == 0) & (wsrc % sw == 0)).all()          # inside a phase nothing is a structural zero
+                    ok = inside & (hsrc >= 0) & (wsrc >= 0) & (hsrc // sh < Ho) & (wsrc // sw < Wo)
+                    want = np.where(ok, ((n_ * Ho + hsrc // sh) * Wo + wsrc // sw) * Cout + co, -1)
+                    assert np.array_equal(out, want), (geo, a, b, row0, col0)
+        assert (seen_pos == 1).all() and (seen_taps == 1).all()
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     import paper_2403_09603_amd.binding as b
     monkeypatch.setattr(b, "_lib", None)
