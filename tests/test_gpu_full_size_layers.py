@@ -156,3 +156,49 @@ def test_resnet_convolutions_full_size(name, geom):
         truth = vo.gemm_f64(np.ascontiguousarray(col), dY, order=2)[0]      # the oracle's dot products over all positions
         assert np.all(np.abs(g64[kh, kw, ci] - truth) <= 1e-12 * np.linalg.norm(col) * np.linalg.norm(dY, axis=0) + 1e-300), name
     _hook_parity(G32.cpu().numpy(), g64, log, int(log.count.item()), tau)
+
+
+@pytest.mark.parametrize("name,geom", [
+    ("3x3 bottleneck", (64, 56, 56, 64, 3, 3, 64, 1, 1)),
+    ("3x3/2 (one GEMM per stride phase)", (64, 56, 56, 128, 3, 3, 128, 2, 1)),
+    ("1x1/2 downsample (one phase has taps)", (64, 56, 56, 256, 1, 1, 512, 2, 0)),
+])
+def test_resnet_input_gradients_full_size(name, geom):
+    """The gradient with respect to the layer's input at batch 64: two whole images against the oracle's
+    extended-precision loops, every output's FP32 value and the whole log against the oracle's hook."""
+    import torch
+    import paper_2403_09603_amd as vt
+    N, H, W, Cin, KH, KW, Cout, stride, pad = geom
+    g = si.rng(si.seed_for(4, 60) + Cin + KH)
+    Wt = _f32grid(g.standard_normal((KH, KW, Cin, Cout)) * np.sqrt(2.0 / (KH * KW * Cin)))
+    _, Ho, Wo = vo.conv2d_geometry((N, H, W, Cin), KH, KW, stride, pad, 1)
+    dY = g.standard_normal((N, Ho, Wo, Cout))
+    tau = 2.0 ** -5
+    d = vt.Conv2d(N, H, W, Cin, KH, KW, stride, stride, pad, pad, 1, 1)
+    M, Nn, K = vt.vt_conv2d_gemm_shape(d, Cout, vt.VT_CONV_DATA_GRAD)
+    assert (M, Nn, K) == (N * H * W, Cin, KH * KW * Cout)
+    dYd, Wd = torch.from_numpy(dY).cuda().reshape(-1), torch.from_numpy(Wt).cuda().reshape(-1)
+    X32 = torch.empty(M * Nn, dtype=torch.float32, device="cuda")
+    X64 = torch.empty(M * Nn, dtype=torch.float64, device="cuda")
+    log = vt.alloc_log(M * Nn)
+    ws = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_CONV_DGRAD_ROUND_LOG, M, Nn, K, 1))
+    vt.vt_conv2d_f64_round_log(vt.VT_CONV_DATA_GRAD, d, Cout, dYd, Wd, None, X32, X64, 0, tau, log, ws)
+    torch.cuda.synchronize()
+    x64 = X64.cpu().numpy().reshape(N, H, W, Cin)
+    wnorm = np.sqrt((Wt ** 2).sum(axis=(0, 1, 3)))                          # per input channel, over (kh, kw, co)
+    for n in (0, N - 1):
+        truth = vo.conv2d_dgrad(dY[n:n + 1], Wt, (1, H, W, Cin), stride=stride, pad=pad, order=2)[0]
+        # squared norm of each input position's row of the gathered view: the dY positions that read it
+        S = (dY[n] ** 2).sum(axis=2)
+        rn2 = np.zeros((H, W))
+        for kh in range(KH):
+            for kw in range(KW):
+                for ho in range(Ho):
+                    h = ho * stride - pad + kh
+                    if 0 <= h < H:
+                        w = np.arange(Wo) * stride - pad + kw
+                        ok = (w >= 0) & (w < W)
+                        rn2[h, w[ok]] += S[ho, ok]
+        bound = 1e-12 * np.sqrt(rn2)[:, :, None] * wnorm[None, None, :] + 1e-300
+        assert np.all(np.abs(x64[n] - truth) <= bound), name
+    _hook_parity(X32.cpu().numpy(), x64, log, int(log.count.item()), tau)
