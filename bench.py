@@ -168,6 +168,32 @@ def workload_streams(vt, torch, dev):
     out["gpt2_117m_layer_stream"] = run_stream(calls)
     out["gpt2_117m_layer_stream"]["workload"] = ("12 layers x (QKV 768->2304, scores Q K^T / 8 per head as strided slices, "
                                                  "attention output 768->768, MLP 768->3072->768), batch 8 x 1024 tokens")
+    # ---- the backward GEMMs of the same linear layers: dX = dY W^T (B transposed) and dW = X^T dY (A transposed,
+    # K = 8192 tokens: deterministic split-K), each output rounded and logged like the forward ones
+    gy = {n: torch.randn(R, w.shape[1], generator=gen, device=dev, dtype=torch.float64) * 1e-3 for n, w in wts.items()}
+    xin = {"qkv": act, "attn_out": act, "mlp_up": act, "mlp_down": act4}
+    ws_b = vt.alloc_workspace(max(max(vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG, R, w.shape[0], w.shape[1], 1),
+                                      vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG, w.shape[0], w.shape[1], R, 1))
+                                  for w in wts.values()))
+
+    def backward(name):
+        w = wts[name]
+        k, n = w.shape
+        return [(name + " dX", 2.0 * R * n * k,
+                 lambda: vt.vt_gemm_f64_round_log(False, True, R, k, n, 1.0, gy[name], n, 0, w, n, 0, None, 1, c32, k, 0,
+                                                  None, 0, tau, dlog, ws_b)),
+                (name + " dW", 2.0 * R * n * k,
+                 lambda: vt.vt_gemm_f64_round_log(True, False, k, n, R, 1.0, xin[name], k, 0, gy[name], n, 0, None, 1, c32, n, 0,
+                                                  None, 0, tau, dlog, ws_b))]
+
+    calls = []
+    for _ in range(12):
+        for name in ("mlp_down", "mlp_up", "attn_out", "qkv"):
+            calls += backward(name)
+    out["gpt2_117m_linear_backward"] = run_stream(calls)
+    out["gpt2_117m_linear_backward"]["workload"] = ("input and weight gradients of the four linear layers of each of the "
+                                                    "12 blocks, batch 8 x 1024 tokens")
+    del gy, xin, ws_b
     del act, act4, qkv, qkv_flat, wts, c32, dlog, ws, calls
 
     # ---- ResNet-50 at batch 64: 53 forward convolutions and 53 weight gradients
