@@ -215,55 +215,100 @@ __global__ __launch_bounds__(256) void replay_dense_kernel(const double *__restr
     else replay_dense_chunk<false, VEC, K0>(x, n, tlog, y, base, lane, codes[wv], k);
 }
 
+// `nbits` (1..20) plane bits of one row from column `col` on, from at most two words per plane
+// (col + nbits <= ncols, so a second word lies in the same row).
+__device__ __forceinline__ void plane_field(const uint64_t *__restrict__ logged, const uint64_t *__restrict__ dir,
+                                            uint64_t row, uint32_t wpr, uint32_t col, uint32_t nbits, uint32_t &lg, uint32_t &up)
+{
+    const uint64_t w = row * wpr + (col >> 6);
+    const uint32_t sh = col & 63u;
+    uint64_t wl = logged[w] >> sh, wd = dir[w] >> sh;
+    if (sh + nbits > 64u) {
+        wl |= logged[w + 1] << (64u - sh);
+        wd |= dir[w + 1] << (64u - sh);
+    }
+    lg = (uint32_t)wl & ((1u << nbits) - 1u);
+    up = (uint32_t)wd & lg;
+}
+
 // Decision bit-planes of a dense (rows x ncols) output -> packed ternary log.  One thread per four
-// bytes (twenty outputs, one 32-bit store); the plane words of the current 64 columns stay in
-// registers and are reloaded only when the walk leaves them.  The workgroup's number of logged
-// outputs goes to partial[blockIdx.x] (summed by count_partials_kernel: integer, any order).
+// bytes (twenty outputs, one 32-bit store).  The twenty plane bits are cut out as fields (two when
+// the window runs over a row end: every wave has such a thread unless 20 divides ncols, so that
+// case must not take a slow path), and a byte is 121 + 2 T[up bits] - T[logged bits] with
+// T[b] = sum of 3^j over the set bits of b (32 entries in LDS): code 1 everywhere, minus 3^j where
+// logged (code 0), plus 2 * 3^j where logged and up.  Rows shorter than twenty outputs and the end
+// of the log walk bit by bit.  total < 2^32.  The workgroup's number of logged outputs goes to
+// partial[blockIdx.x] (summed by count_partials_kernel: integer, any order).
 __global__ __launch_bounds__(256) void planes_to_dense_kernel(const uint64_t *__restrict__ logged,
                                                               const uint64_t *__restrict__ dir, uint32_t wpr,
-                                                              uint32_t ncols, uint64_t total, uint8_t *__restrict__ tlog,
-                                                              uint32_t *__restrict__ partial)
+                                                              uint32_t ncols, double inv_ncols, uint64_t total,
+                                                              uint8_t *__restrict__ tlog, uint32_t *__restrict__ partial)
 {
     __shared__ uint32_t wave_cnt[4];
+    __shared__ uint8_t T[32];
+    if (threadIdx.x < 32) {
+        const uint32_t b = threadIdx.x;
+        T[b] = (uint8_t)((b & 1u) + 3u * ((b >> 1) & 1u) + 9u * ((b >> 2) & 1u) + 27u * ((b >> 3) & 1u) + 81u * ((b >> 4) & 1u));
+    }
+    __syncthreads();
     const uint64_t q = (uint64_t)blockIdx.x * 256u + threadIdx.x;       // 32-bit word of the log
     const uint64_t e0 = q * 20u;
     uint32_t n_logged = 0;
     if (e0 < total) {
-    uint32_t row = (uint32_t)(e0 / ncols), col = (uint32_t)(e0 % ncols);
-    uint64_t wl = 0, wd = 0;
-    bool have = false;
-    uint32_t word = 0;
-#pragma unroll
-    for (int by = 0; by < 4; ++by) {
-        uint32_t byte = 0, weight = 1;
-#pragma unroll
-        for (int j = 0; j < 5; ++j) {
-            uint32_t code = 1;
-            if (e0 + (uint64_t)(5 * by + j) < total) {
-                if (!have) {
-                    const uint64_t w = (uint64_t)row * wpr + (col >> 6);
-                    wl = logged[w];
-                    wd = dir[w];
-                    have = true;
-                }
-                const uint32_t lg = (uint32_t)(wl >> (col & 63u)) & 1u, up = (uint32_t)(wd >> (col & 63u)) & 1u;
-                code = lg ? 2u * up : 1u;
-                n_logged += lg;
-                ++col;
-                if ((col & 63u) == 0) have = false;
-                if (col == ncols) { col = 0; ++row; have = false; }
+        uint32_t row, col;
+        divmod_u32((uint32_t)e0, ncols, inv_ncols, row, col);
+        uint32_t word = 0;
+        if (e0 + 20u <= total && ncols >= 20u) {
+            const uint32_t n1 = ncols - col < 20u ? ncols - col : 20u;
+            uint32_t lg, up;
+            plane_field(logged, dir, row, wpr, col, n1, lg, up);
+            if (n1 < 20u) {                                   // the rest starts the next row
+                uint32_t lg2, up2;
+                plane_field(logged, dir, (uint64_t)row + 1u, wpr, 0u, 20u - n1, lg2, up2);
+                lg |= lg2 << n1;
+                up |= up2 << n1;
             }
-            byte += code * weight;
-            weight *= 3u;
+            n_logged = (uint32_t)__popc(lg);
+#pragma unroll
+            for (int by = 0; by < 4; ++by) {
+                const uint32_t byte = 121u + 2u * T[(up >> (5 * by)) & 31u] - T[(lg >> (5 * by)) & 31u];
+                word |= byte << (8 * by);
+            }
+        } else {
+            uint64_t wl = 0, wd = 0;
+            bool have = false;
+#pragma unroll 1
+            for (int by = 0; by < 4; ++by) {
+                uint32_t byte = 0, weight = 1;
+#pragma unroll 1
+                for (int j = 0; j < 5; ++j) {
+                    uint32_t code = 1;
+                    if (e0 + (uint64_t)(5 * by + j) < total) {
+                        if (!have) {
+                            const uint64_t w = (uint64_t)row * wpr + (col >> 6);
+                            wl = logged[w];
+                            wd = dir[w];
+                            have = true;
+                        }
+                        const uint32_t lg = (uint32_t)(wl >> (col & 63u)) & 1u, up = (uint32_t)(wd >> (col & 63u)) & 1u;
+                        code = lg ? 2u * up : 1u;
+                        n_logged += lg;
+                        ++col;
+                        if ((col & 63u) == 0) have = false;
+                        if (col == ncols) { col = 0; ++row; have = false; }
+                    }
+                    byte += code * weight;
+                    weight *= 3u;
+                }
+                word |= byte << (8 * by);
+            }
         }
-        word |= byte << (8 * by);
-    }
-    const uint64_t nbytes = (total + 4) / 5;
-    if (4 * q + 4 <= nbytes) {
-        *(uint32_t *)(tlog + 4 * q) = word;
-    } else {                                          // the log ends inside this word
-        for (uint64_t i = 4 * q; i < nbytes; ++i) tlog[i] = (uint8_t)(word >> (8 * (i - 4 * q)));
-    }
+        const uint64_t nbytes = (total + 4) / 5;
+        if (4 * q + 4 <= nbytes) {
+            *(uint32_t *)(tlog + 4 * q) = word;
+        } else {                                          // the log ends inside this word
+            for (uint64_t i = 4 * q; i < nbytes; ++i) tlog[i] = (uint8_t)(word >> (8 * (i - 4 * q)));
+        }
     }
     n_logged = wave_sum(n_logged);
     if ((threadIdx.x & 63u) == 0) wave_cnt[threadIdx.x >> 6] = n_logged;
@@ -397,7 +442,8 @@ hipError_t launch_planes_to_dense(const Planes &pl, uint64_t rows, uint8_t *tlog
     const uint64_t words = (total + 19) / 20;
     const uint32_t blocks = (uint32_t)((words + 255) / 256);
     if (blocks)
-        planes_to_dense_kernel<<<blocks, 256, 0, s>>>(pl.logged, pl.dir, pl.wpr, pl.ncols, total, tlog, pl.seg_cnt);
+        planes_to_dense_kernel<<<blocks, 256, 0, s>>>(pl.logged, pl.dir, pl.wpr, pl.ncols, 1.0 / (double)(pl.ncols ? pl.ncols : 1u),
+                                                      total, tlog, pl.seg_cnt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     count_partials_kernel<<<1, 1024, 0, s>>>(pl.seg_cnt, blocks, count);
