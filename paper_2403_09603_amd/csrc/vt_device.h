@@ -85,7 +85,8 @@ static __host__ __device__ __forceinline__ Decision decide(uint64_t bits)
 // overflows to infinity from the top binade), so the hardware conversion under the default
 // round-to-nearest-even mode gives rnd_32(x) without touching denormal handling; the dropped
 // bits still decide D and the direction: the magnitude grows iff r + (kept LSB) > 2^28.
-// Lanes with slow == true must be redone with decide() (NaN, Inf, zero, tiny, |x| >= 2^128).
+// Lanes with slow == true must be redone with decide() (NaN, Inf, tiny, |x| >= 2^128); for +-0,
+// which also comes back slow, y and D = 2^28 (never logged) are already right.
 struct FastDecision {
     float y;
     uint32_t D;
@@ -270,9 +271,13 @@ __device__ __forceinline__ Rounded round_decide(double x, uint32_t thr, uint32_t
         o.ybits = __float_as_uint(f.y);
         o.logged = f.D < thr;
         o.up = f.grow != f.neg;
+        // (for +-0 the conversion and D = 2^28 above are already the answer: tensors that are half
+        // zeros, as after a ReLU, must not send every wave through the integer path)
         if (__builtin_expect(f.slow, 0)) {
-            const Decision d = decide(bits);
-            o.ybits = d.ybits; o.logged = d.D < thr; o.up = d.dir != 0;
+            if (x != 0.0) {
+                const Decision d = decide(bits);
+                o.ybits = d.ybits; o.logged = d.D < thr; o.up = d.dir != 0;
+            }
         }
     } else {
         const Decision d = decide_k(bits, k);

@@ -190,8 +190,8 @@ __device__ __forceinline__ void replay_dense_chunk(const double *__restrict__ x,
             const FastDecision fa = decide_fast(v[u].x), fb = decide_fast(v[u].y);
             ya = __float_as_uint(fa.y);
             yb = __float_as_uint(fb.y);
-            if (__builtin_expect(fa.slow, 0)) ya = decide(ba).ybits;
-            if (__builtin_expect(fb.slow, 0)) yb = decide(bb).ybits;
+            if (__builtin_expect(fa.slow, 0)) { if (v[u].x != 0.0) ya = decide(ba).ybits; }   // (+-0: the conversion stands)
+            if (__builtin_expect(fb.slow, 0)) { if (v[u].y != 0.0) yb = decide(bb).ybits; }
             if (ca != 1u) ya = directed(ba, ca >> 1);
             if (cb != 1u) yb = directed(bb, cb >> 1);
         } else {

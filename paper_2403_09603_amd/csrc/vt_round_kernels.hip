@@ -245,9 +245,9 @@ __device__ __forceinline__ void replay_store(const d2 (&v)[kReplayRows], const u
             if (__builtin_expect(ballot(a.slow || b.slow || f != 0) != 0, 0)) {
                 const uint64_t xa = (uint64_t)__double_as_longlong(v[u].x), xb = (uint64_t)__double_as_longlong(v[u].y);
                 if (f & 1u) ya = directed(xa, (f >> 1) & 1u);
-                else if (a.slow) ya = decide(xa).ybits;
+                else if (a.slow && v[u].x != 0.0) ya = decide(xa).ybits;      // (+-0: the conversion stands)
                 if (f & 0x100u) yb = directed(xb, (f >> 9) & 1u);
-                else if (b.slow) yb = decide(xb).ybits;
+                else if (b.slow && v[u].y != 0.0) yb = decide(xb).ybits;
             }
         } else {                                                     // rounding amount below 32
             const uint64_t xa = (uint64_t)__double_as_longlong(v[u].x), xb = (uint64_t)__double_as_longlong(v[u].y);

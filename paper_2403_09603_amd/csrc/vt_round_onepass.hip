@@ -174,11 +174,11 @@ __device__ __forceinline__ uint32_t round_rows(const Src &x, uint64_t n, uint32_
             la = a.D < thr; lb = b.D < thr;
             da = a.grow != a.neg; db = b.grow != b.neg;
             if (__builtin_expect(ballot(a.slow || b.slow) != 0, 0)) {      // rare values: redo those lanes
-                if (a.slow) {
+                if (a.slow && v[u].x != 0.0) {                            // (+-0: the fast result stands)
                     const Decision d = decide((uint64_t)__double_as_longlong(v[u].x));
                     ya = d.ybits; la = d.D < thr; da = d.dir != 0;
                 }
-                if (b.slow) {
+                if (b.slow && v[u].y != 0.0) {
                     const Decision d = decide((uint64_t)__double_as_longlong(v[u].y));
                     yb = d.ybits; lb = d.D < thr; db = d.dir != 0;
                 }
