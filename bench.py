@@ -369,6 +369,29 @@ def main():
                      "traffic": measured_traffic()},
     }
 
+    # ------------------------------------------------ the same trainer call at three fixed thresholds
+    # (sparse, medium and the paper's default band), with both log formats: call time and log size
+    sweep = []
+    dlog_T = vt.alloc_dense_log(total)
+    for name, tau_b in (("2^-24", 2.0 ** -24), ("2^-8", 2.0 ** -8), ("1/4", 0.25)):
+        row = {"tau_ulp": name}
+        for fmt, lg in (("sparse", log_T), ("packed", dlog_T)):
+            gemm(0, tau_b, C32_T, None, lg)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(5):
+                gemm(0, tau_b, C32_T, None, lg)
+            b.record()
+            torch.cuda.synchronize()
+            cnt_b = int(lg.count.item())
+            row["logged"] = cnt_b
+            row[fmt + "_call_ms"] = round(a.elapsed_time(b) / 5, 4)
+            row[fmt + "_log_bytes"] = cnt_b * 4 + (cnt_b + 7) // 8 if fmt == "sparse" else (total + 4) // 5
+        sweep.append(row)
+    out["tau_sweep"] = sweep
+    del dlog_T
+
     # ------------------------------------------------ standalone HBM-bound sweep (2^28 elements)
     if not args.no_stream:
         del C64_T, C32_A, y_S
