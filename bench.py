@@ -119,9 +119,23 @@ def workload_streams(vt, torch, dev):
             k = kinds.setdefault(kind, [0, 0.0, 0.0])
             k[0] += 1; k[1] += fl; k[2] += evs[i].elapsed_time(evs[i + 1])
         flops = sum(fl for _, fl, _ in calls)
+        # the same stream recorded once into a HIP graph and replayed (the library allocates nothing and
+        # never synchronises, so its calls can be captured): what the launch gaps between kernels cost
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _, _, fn in calls:
+                fn()
+        graph.replay()
+        torch.cuda.synchronize()
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g0.record(); graph.replay(); g1.record()
+        torch.cuda.synchronize()
+        graph_ms = g0.elapsed_time(g1)
+        del graph
         return {"calls": len(calls), "TFLOP": round(flops / 1e12, 4), "ms": round(total_ms, 3),
                 "TFLOPs": round(flops / total_ms / 1e9, 2),
                 "frac_mfma_peak": round(flops / total_ms / 1e9 / FP64_MFMA_PEAK_TFLOPS, 4),
+                "graph_replay_ms": round(graph_ms, 3), "graph_replay_TFLOPs": round(flops / graph_ms / 1e9, 2),
                 "by_kind": {k: {"calls": v[0], "ms": round(v[2], 3), "TFLOPs": round(v[1] / v[2] / 1e9, 2)}
                             for k, v in kinds.items()}}
 
