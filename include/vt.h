@@ -18,6 +18,9 @@
  *     detected before anything is enqueued.  vt_strerror() names a code.
  *   - Same inputs (and same `variant`) give bit-identical outputs on every run: no kernel uses
  *     floating-point atomics or a timing-dependent summation order.
+ *   - Calls may be recorded by stream capture into a HIP graph and replayed: they allocate nothing,
+ *     never synchronise, and clear their counters with kernels (no memset nodes).  Host-side
+ *     arguments (sizes, thresholds, a replay's entry count) are fixed at capture.
  *
  * Threshold
  *   `tau_ulp` is the logging threshold measured from the rounding boundary (the midpoint
