@@ -62,12 +62,12 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const double *__rest
 // cost of a tile's start and epilogue in k steps
 struct TileShape { int wm, tm, bm, bn; double eff; int conc; double overhead; };
 constexpr int kNumShapes = 3;
-constexpr TileShape kShapes[kNumShapes] = {{2, 4, 128, 128, 0.867, 2, 6.0}, {2, 2, 64, 128, 0.80, 2, 7.6},
-                                           {4, 1, 64, 64, 0.787, 3, 6.2}};
+constexpr TileShape kShapes[kNumShapes] = {{2, 4, 128, 128, 0.867, 2, 6.0}, {2, 2, 64, 128, 0.80, 2, 7.85},
+                                           {4, 1, 64, 64, 0.845, 4, 6.2}};
 // the same for an A operand stored transposed (its tiles are transposed on the way into LDS
 // from the other direction; the small square tile loses more there)
-constexpr TileShape kShapesT[kNumShapes] = {{2, 4, 128, 128, 0.869, 2, 9.4}, {2, 2, 64, 128, 0.726, 2, 9.8},
-                                            {4, 1, 64, 64, 0.62, 2, 6.1}};
+constexpr TileShape kShapesT[kNumShapes] = {{2, 4, 128, 128, 0.869, 2, 11.3}, {2, 2, 64, 128, 0.726, 2, 11.4},
+                                            {4, 1, 64, 64, 0.664, 3, 5.1}};
 
 }  // namespace
 
@@ -91,7 +91,9 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_sp
             const double rounds = std::ceil(blocks / 256.0);
             const double eff = t.eff * (rounds >= (double)t.conc ? 1.0 : 0.744);
             double cost = rounds * (double)t.bm * t.bn * ((double)((nkt + sp - 1) / sp) + t.overhead) / eff;
-            if (sp > 1) cost += 173000.0 + 0.0171 * (double)M * N * batch * (sp + 2);
+            // slabs: up to eight are summed inside the round/log pass, more go through a reduction kernel first
+            if (sp > 8) cost += 137000.0 + 0.0178 * (double)M * N * batch * (sp + 2);
+            else if (sp > 1) cost += 102700.0 + 0.0147 * (double)M * N * batch * (sp + 1);
             if (cost < best_cost) { best_cost = cost; best = GemmPlan{sh, sp, 0}; }
         }
     }

@@ -65,7 +65,10 @@ typedef double d2 __attribute__((ext_vector_type(2)));
 // doubles those land on 32 different bank pairs (a pitch of 16 mod 32 put all 8 k rows on one
 // pair: 8-way conflicts that kept the LDS pipe busy for about as long as the MFMAs).  Fragment
 // reads (2 k rows x 16 columns per pass) then overlap in 2 of 32 bank pairs only.
-constexpr int kPad = 18;
+// A pad of 14 has both properties as well (14 = 18 - 4: the same store pattern, reads overlapping
+// in bank pairs 14 and 15); the 64x64 tile takes it, which brings its two stages under 40 KB so
+// that four workgroups share a CU's LDS instead of three.
+constexpr int kPad = 18, kPadSmall = 14;
 
 
 // Two neighbouring taps of one row.  The load is unconditional (from X[0] when the element lies
@@ -153,11 +156,11 @@ __device__ __forceinline__ void load_tile_fast(const char *__restrict__ base, in
     }
 }
 
-template <bool KC, int R>
+template <bool KC, int R, int PAD>
 __device__ __forceinline__ void store_tile(double *__restrict__ S, const d2 (&regs)[R / 32])
 {
     const int t = threadIdx.x;
-    constexpr int pitch = R + kPad;
+    constexpr int pitch = R + PAD;
 #pragma unroll
     for (int j = 0; j < R / 32; ++j) {
         if (KC) {
@@ -196,7 +199,8 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
     constexpr bool GA = AM >= 2;
     constexpr int WN = 4 / WM;
     constexpr int BM = WM * 16 * TM, BN = WN * 64;
-    constexpr int PA = BM + kPad, PB = BN + kPad;          // LDS pitches
+    constexpr int PAD = TM == 1 ? kPadSmall : kPad;
+    constexpr int PA = BM + PAD, PB = BN + PAD;            // LDS pitches
     constexpr int SA = BK * PA, SB = BK * PB;              // doubles per stage
     __shared__ double lds[2 * SA + 2 * SB];                // A0 A1 B0 B1
     double *const ldsA = lds, *const ldsB = lds + 2 * SA;
@@ -347,8 +351,8 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
                     // so the wave's MFMA stream has no gap before the barrier)
                     __builtin_amdgcn_sched_barrier(0);
                     if (more) {
-                        store_tile<KCA, BM>(ldsA + (cur ^ 1) * SA, sa);
-                        store_tile<KCB, BN>(ldsB + (cur ^ 1) * SB, sb);
+                        store_tile<KCA, BM, PAD>(ldsA + (cur ^ 1) * SA, sa);
+                        store_tile<KCB, BN, PAD>(ldsB + (cur ^ 1) * SB, sb);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -362,8 +366,8 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
         };
         if (nkt > 0) {
             fetch(0, ra0, rb0);
-            store_tile<KCA, BM>(ldsA, ra0);
-            store_tile<KCB, BN>(ldsB, rb0);
+            store_tile<KCA, BM, PAD>(ldsA, ra0);
+            store_tile<KCB, BN, PAD>(ldsB, rb0);
             if (nkt > 1) fetch(1, ra0, rb0);
         }
         __syncthreads();
