@@ -349,12 +349,17 @@ uint32_t vt_thr_from_tau(double tau_ulp);
 
 /*
  * Introspection (host only, no counterpart in the paper): the workgroup tile and the split-K
- * factor vt_gemm_f64_round_log uses for a problem of this shape and A layout (the convolution weight
- * gradient counts as transA = 1).  The choice is a pure function
+ * factor vt_gemm_f64_round_log uses for a problem of this shape and A layout: transA is
+ * VT_A_ROW_MAJOR (also the forward and input-gradient views of a convolution), VT_A_TRANSPOSED (also
+ * the weight gradient of a 1 x 1 convolution at every position), or VT_A_IM2COL_T (the weight
+ * gradient of any other convolution).  The choice is a pure function
  * of these arguments, so a given call always accumulates in the same order.  splits > 1 (only
  * for dense outputs: ldc == N and strideC == M*N) means the K range is cut into that many
  * slices whose FP64 partial sums are added in a fixed order before the single rounding.
  */
+#define VT_A_ROW_MAJOR 0
+#define VT_A_TRANSPOSED 1
+#define VT_A_IM2COL_T 3
 int vt_gemm_plan(int transA, int64_t M, int64_t N, int64_t K, int64_t batch, int64_t ldc, int64_t strideC,
                  int *tile_m, int *tile_n, int *splits);
 

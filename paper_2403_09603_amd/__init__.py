@@ -12,5 +12,5 @@ from .binding import (  # noqa: F401
     VtError, Log, alloc_log, alloc_dense_log, vt_round_replay_dense, alloc_workspace, library_path, load_library,
     vt_gemm_f64_round_log, vt_gemm_f64_round_log_nested, vt_gemm_plan, vt_round_log, vt_round_replay, vt_set_kernel_events, vt_strerror, vt_thr_from_tau,
     vt_threshold_stats, vt_workspace_bytes, vt_sha256_tree, vt_merkle_root, VT_OP_SHA256_TREE, VT_OP_MERKLE_ROOT, VT_OP_CONV_DGRAD_ROUND_LOG,
-    VT_OP_CONV_DGRAD_ROUND_LOG_BR,
+    VT_OP_CONV_DGRAD_ROUND_LOG_BR, VT_A_ROW_MAJOR, VT_A_TRANSPOSED, VT_A_IM2COL_T,
 )

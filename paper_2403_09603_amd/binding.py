@@ -17,6 +17,7 @@ _lib = None
 
 VT_OP_ROUND_LOG, VT_OP_ROUND_REPLAY, VT_OP_GEMM_ROUND_LOG, VT_OP_THRESHOLD_STATS, VT_OP_GEMM_ROUND_LOG_BR = 0, 1, 2, 3, 4
 VT_CONV_FORWARD, VT_CONV_WEIGHT_GRAD, VT_CONV_DATA_GRAD = 0, 1, 2
+VT_A_ROW_MAJOR, VT_A_TRANSPOSED, VT_A_IM2COL_T = 0, 1, 3
 VT_OP_LAYER_ROUND_LOG = 5
 VT_LAYER_ADD, VT_LAYER_RELU, VT_LAYER_GELU_TANH, VT_LAYER_GELU_ERF, VT_LAYER_NORM, VT_LAYER_SOFTMAX = 0, 1, 2, 3, 4, 5
 VT_LAYER_BATCHNORM, VT_LAYER_BATCHNORM_RELU = 6, 7
@@ -342,10 +343,11 @@ def vt_layer_f64_round_log(op: int, a: torch.Tensor, b, gamma, beta, rows: int, 
 
 
 def vt_gemm_plan(M: int, N: int, K: int, batch: int = 1, ldc: int | None = None, strideC: int | None = None,
-                 transA: bool = False):
-    """(tile_m, tile_n, splits) the GEMM entry point uses for this shape."""
+                 transA=False):
+    """(tile_m, tile_n, splits) the GEMM entry point uses for this shape.  transA: False / True, or
+    VT_A_IM2COL_T for the weight gradient of a convolution that is not 1 x 1 at every position."""
     tm, tn, sp = C.c_int(), C.c_int(), C.c_int()
-    _check(load_library().vt_gemm_plan(int(bool(transA)), int(M), int(N), int(K), int(batch), int(N if ldc is None else ldc),
+    _check(load_library().vt_gemm_plan(int(transA), int(M), int(N), int(K), int(batch), int(N if ldc is None else ldc),
                                        int(M * N if strideC is None else strideC), C.byref(tm), C.byref(tn),
                                        C.byref(sp)), "vt_gemm_plan")
     return tm.value, tn.value, sp.value

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvt_hip.so")
-SOURCES = ["vt_gemm_shape_128x128.hip", "vt_gemm_shape_64x128.hip", "vt_gemm_shape_64x64.hip",
+SOURCES = ["vt_gemm_shape_128x128.hip", "vt_gemm_shape_64x64.hip",
            "vt_api.hip", "vt_round_kernels.hip", "vt_round_onepass.hip", "vt_round_dense.hip", "vt_layers.hip", "vt_hash.hip",
            "vt_gemm_kernels.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

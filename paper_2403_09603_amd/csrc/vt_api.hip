@@ -37,9 +37,12 @@ inline size_t round_log_bytes(uint64_t n)
 // the larger split factor of the two operand layouts (the workspace query does not know which)
 inline int max_splits(int64_t M, int64_t N, int64_t K, int64_t batch)
 {
-    const int a = vt::plan_gemm(M, N, K < 0 ? 0 : K, batch, true, false).splits;
-    const int b = vt::plan_gemm(M, N, K < 0 ? 0 : K, batch, true, true).splits;
-    return a > b ? a : b;
+    int most = 1;
+    for (int layout : {vt::kALayoutRowMajor, vt::kALayoutTransposed, vt::kALayoutIm2colT}) {
+        const int sp = vt::plan_gemm(M, N, K < 0 ? 0 : K, batch, true, layout).splits;
+        most = sp > most ? sp : most;
+    }
+    return most;
 }
 
 inline bool split_allowed(int64_t M, int64_t N, int64_t batch, int64_t ldc, int64_t strideC)
@@ -111,7 +114,8 @@ int run_gemm(vt::GemmArgs &g, const vt_log *log, void *ws, size_t ws_bytes, hipS
     if (!ws || ws_bytes < need || !aligned(ws, 256)) return VT_ERR_WORKSPACE;
     const vt::Planes pl = vt::planes_carve(ws, (uint64_t)M * (uint64_t)batch, (uint64_t)N);
     const size_t planes = vt::planes_bytes((uint64_t)M * (uint64_t)batch, (uint64_t)N);
-    const vt::GemmPlan plan = vt::plan_gemm(M, N, K, batch, split_allowed(M, N, batch, g.ldc, g.strideC), g.transA != 0);
+    const int a_layout = g.conv && g.conv_wgrad ? vt::kALayoutIm2colT : (g.transA ? vt::kALayoutTransposed : vt::kALayoutRowMajor);
+    const vt::GemmPlan plan = vt::plan_gemm(M, N, K, batch, split_allowed(M, N, batch, g.ldc, g.strideC), a_layout);
     g.raw = two_pass;
     if (plan.splits > 1 || two_pass) {
         // slabs -> fixed-order sum (alpha, bias) -> standalone round/log over the flat result
@@ -238,7 +242,7 @@ int conv_dgrad_entry(const vt::ConvDesc &c, int64_t Cout, const double *dY, cons
                 vt::GemmArgs q = g;
                 q.conv = &sub; q.conv_dgrad_cout = Cout;
                 q.M = rows; q.K = taps * Cout; q.lda = 0; q.B = Wp + w_off; q.transB = 0; q.ldb = N; q.raw = true;
-                const vt::GemmPlan plan = vt::plan_gemm(q.M, q.N, q.K, 1, /*allow_split=*/false, /*transA=*/false);
+                const vt::GemmPlan plan = vt::plan_gemm(q.M, q.N, q.K, 1, /*allow_split=*/false, vt::kALayoutRowMajor);
                 if (vt::launch_gemm_round_planes(q, plan, vt::Planes{}, slabs + slab_off, nullptr, s) != hipSuccess) return VT_ERR_HIP;
                 slab_off += (uint64_t)rows * (uint64_t)N;
                 w_off += (uint64_t)taps * (uint64_t)Cout * (uint64_t)N;
@@ -559,8 +563,9 @@ int vt_gemm_plan(int transA, int64_t M, int64_t N, int64_t K, int64_t batch, int
                  int *tile_m, int *tile_n, int *splits)
 {
     if (M < 0 || N < 0 || K < 0 || batch < 0 || !tile_m || !tile_n || !splits) return VT_ERR_INVALID_ARG;
-    const vt::GemmPlan plan = vt::plan_gemm(M, N, K, batch, split_allowed(M, N, batch, ldc, strideC), transA != 0);
-    static const int bm[3] = {128, 64, 64}, bn[3] = {128, 128, 64};
+    if (transA != VT_A_ROW_MAJOR && transA != VT_A_TRANSPOSED && transA != VT_A_IM2COL_T) return VT_ERR_INVALID_ARG;
+    const vt::GemmPlan plan = vt::plan_gemm(M, N, K, batch, split_allowed(M, N, batch, ldc, strideC), transA);
+    static const int bm[2] = {128, 64}, bn[2] = {128, 64};
     *tile_m = bm[plan.shape];
     *tile_n = bn[plan.shape];
     *splits = plan.splits;

@@ -61,13 +61,14 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const double *__rest
 // bm x bn, measured MFMA efficiency with a full CU, workgroups that fit on one CU (LDS-bound),
 // cost of a tile's start and epilogue in k steps
 struct TileShape { int wm, tm, bm, bn; double eff; int conc; double overhead; };
-constexpr int kNumShapes = 3;
-constexpr TileShape kShapes[kNumShapes] = {{2, 4, 128, 128, 0.867, 2, 6.0}, {2, 2, 64, 128, 0.80, 2, 7.85},
-                                           {4, 1, 64, 64, 0.845, 4, 6.2}};
-// the same for an A operand stored transposed (its tiles are transposed on the way into LDS
-// from the other direction; the small square tile loses more there)
-constexpr TileShape kShapesT[kNumShapes] = {{2, 4, 128, 128, 0.869, 2, 11.3}, {2, 2, 64, 128, 0.726, 2, 11.4},
-                                            {4, 1, 64, 64, 0.664, 3, 5.1}};
+constexpr int kNumShapes = 2;
+constexpr TileShape kShapes[kNumShapes] = {{2, 4, 128, 128, 0.928, 2, 6.0}, {4, 1, 64, 64, 0.891, 4, 5.6}};
+// the same for an A operand stored transposed (its tiles go into LDS as they lie, the other
+// operand's pattern) ...
+constexpr TileShape kShapesT[kNumShapes] = {{2, 4, 128, 128, 0.72, 2, 9.7}, {4, 1, 64, 64, 0.809, 4, 5.3}};
+// ... and for the transposed implicit-im2col view of a convolution's weight gradient, whose gather
+// costs the small tile more than the large one
+constexpr TileShape kShapesG[kNumShapes] = {{2, 4, 128, 128, 0.772, 2, 9.7}, {4, 1, 64, 64, 0.641, 4, 4.9}};
 
 }  // namespace
 
@@ -77,23 +78,24 @@ constexpr TileShape kShapesT[kNumShapes] = {{2, 4, 128, 128, 0.869, 2, 11.3}, {2
 // hidden), plus
 // for split-K the two extra kernels and the slab traffic.  Pure host arithmetic on the shape, so
 // the choice (and with it the accumulation order) is a function of the arguments alone.
-GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split, bool transA)
+GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split, int a_layout)
 {
     GemmPlan best{0, 1, 0};
     double best_cost = 1e300;
     const int64_t nkt = (K + BK - 1) / BK;
     for (int sh = 0; sh < kNumShapes; ++sh) {
-        const TileShape &t = transA ? kShapesT[sh] : kShapes[sh];
+        const TileShape &t = a_layout == kALayoutIm2colT ? kShapesG[sh] : (a_layout == kALayoutTransposed ? kShapesT[sh] : kShapes[sh]);
         const double tiles = (double)((M + t.bm - 1) / t.bm) * (double)((N + t.bn - 1) / t.bn) * (double)batch;
-        for (int sp = 1; sp <= 256; sp *= 2) {
+        // split factors: every count up to 16 (so that tiles x slices can fill whole rounds), then coarser
+        static const int kSplits[] = {1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 20, 24, 28, 32, 40, 48, 56, 64, 80, 96,
+                                      112, 128, 160, 192, 224, 256};
+        for (int sp : kSplits) {
             if (sp > 1 && (!allow_split || nkt / sp < 8)) break;        // keep >= 8 k steps per slice
             const double blocks = tiles * sp;
             const double rounds = std::ceil(blocks / 256.0);
-            const double eff = t.eff * (rounds >= (double)t.conc ? 1.0 : 0.744);
+            const double eff = t.eff * (rounds >= (double)t.conc ? 1.0 : 0.782);
             double cost = rounds * (double)t.bm * t.bn * ((double)((nkt + sp - 1) / sp) + t.overhead) / eff;
-            // slabs: up to eight are summed inside the round/log pass, more go through a reduction kernel first
-            if (sp > 8) cost += 137000.0 + 0.0178 * (double)M * N * batch * (sp + 2);
-            else if (sp > 1) cost += 102700.0 + 0.0147 * (double)M * N * batch * (sp + 1);
+            if (sp > 1) cost += 173000.0 + 0.0171 * (double)M * N * batch * (sp + 2);
             if (cost < best_cost) { best_cost = cost; best = GemmPlan{sh, sp, 0}; }
         }
     }
@@ -191,7 +193,6 @@ hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, con
     hipError_t e;
     switch (plan.shape) {
     case 0: e = launch_gemm_128x128(p, am, kcb, s); break;
-    case 1: e = launch_gemm_64x128(p, am, kcb, s); break;
     default: e = launch_gemm_64x64(p, am, kcb, s); break;
     }
     if (e != hipSuccess || (plan.splits <= 1 && !g.raw) || !reduced) return e;     // no `reduced`: the caller sums the slabs itself

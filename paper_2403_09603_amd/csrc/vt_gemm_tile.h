@@ -35,7 +35,6 @@ namespace vt {
 // one entry point per workgroup tile shape (defined in vt_gemm_shape_*.hip)
 struct GemmParams;
 hipError_t launch_gemm_128x128(const GemmParams &p, int am, bool kcb, hipStream_t s);
-hipError_t launch_gemm_64x128(const GemmParams &p, int am, bool kcb, hipStream_t s);
 hipError_t launch_gemm_64x64(const GemmParams &p, int am, bool kcb, hipStream_t s);
 
 constexpr int BK = 16;

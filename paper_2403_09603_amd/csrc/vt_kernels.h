@@ -152,11 +152,13 @@ struct GemmArgs {
 };
 // Tile shape (index into the kernel's shape table) and split-K factor chosen for a problem.
 struct GemmPlan {
-    int shape;          // 0: 128x128, 1: 64x128, 2: 64x64
+    int shape;          // 0: 128x128, 1: 64x64
     int splits;         // 1 = fused epilogue; > 1 = slabs + fixed-order reduction + round/log pass
     int kt_per_split;   // k steps of 16 per slice
 };
-GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split, bool transA);
+// a_layout: how the A operand reaches the kernel (the public VT_A_* values)
+enum { kALayoutRowMajor = 0, kALayoutTransposed = 1, kALayoutIm2colT = 3 };
+GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split, int a_layout);
 size_t gemm_split_bytes(int64_t M, int64_t N, int64_t batch, int splits);
 // splits == 1 and not g.raw: C32 / C64 / planes written by the epilogue.  Otherwise `partial`
 // receives the slabs, `reduced` (and g.C64 if set) the FP64 result alpha * sum + bias; nothing
