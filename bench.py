@@ -100,7 +100,7 @@ def workload_streams(vt, torch, dev):
     def f32grid(t):
         return t.float().double()
 
-    def run_stream(calls, reps=2):
+    def run_stream(calls, reps=4):
         """calls: list of (kind, flops, fn).  Runs the stream `reps` times, times the last pass as a whole
         and per call (events on the stream the library launches on)."""
         for _ in range(reps - 1):
@@ -257,8 +257,8 @@ def workload_streams(vt, torch, dev):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-stream", action="store_true", help="skip the 2^28-element standalone sweep")
     ap.add_argument("--no-workloads", action="store_true",
