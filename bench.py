@@ -422,8 +422,9 @@ def main():
         tau_s = thr_s * 2.0 ** -29
         e0, e1 = ev.create(), ev.create()
 
-        def timed(fn, reps=10):
-            fn(); fn()
+        def timed(fn, reps=20):
+            for _ in range(10):
+                fn()
             torch.cuda.synchronize()
             call_ms, kern_ms = [], []
             for _ in range(reps):
