@@ -358,6 +358,16 @@ __device__ __forceinline__ void stats_one(uint64_t a, uint64_t b, double xa, dou
         acc.thrmax = need > acc.thrmax ? need : acc.thrmax;
         return;
     }
+    if (!K0 && ordinary && ((a ^ b) >> 63) == 0) {
+        // Coarser grids: in the FP32-normal range the grid points are the patterns whose low 29 + k bits
+        // are zero, and rounding to nearest is rounding of the pattern; two values of one sign whose
+        // patterns round to the same point, neither of them a tie, cannot flip.  (Everything else,
+        // the rare pairs, goes through the full decision below.)
+        const uint32_t s = 29u + k;
+        const uint64_t half = 1ull << (s - 1u), low = (1ull << s) - 1ull;
+        const uint64_t ua = (a & 0x7FFFFFFFFFFFFFFFull) + half, ub = (b & 0x7FFFFFFFFFFFFFFFull) + half;
+        if ((ua >> s) == (ub >> s) && (ua & low) != 0 && (ub & low) != 0) return;
+    }
     const Decision da = decide_k(a, k), db = decide_k(b, k);
     if (da.ybits != db.ybits) {
         ++acc.flips;
