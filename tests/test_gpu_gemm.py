@@ -67,6 +67,23 @@ def test_config1_tiny_gemm_and_auditor_replay(G):
     assert np.array_equal(_bits(y_gpu_aud), _bits(r["C32"].ravel()))
 
 
+@pytest.mark.parametrize("M,N,K,tA,splits", [
+    (633, 765, 1100, True, 2), (313, 1085, 1100, False, 3), (121, 509, 700, False, 5), (377, 445, 1100, False, 6),
+    (377, 381, 1100, False, 7), (121, 509, 1100, False, 8), (249, 445, 1600, False, 9), (57, 1469, 2400, False, 11),
+    (57, 1213, 2400, False, 13), (121, 509, 2400, False, 15)])
+def test_split_factors_that_are_not_powers_of_two(G, M, N, K, tA, splits):
+    """The plan takes any slice count up to 16: up to eight slabs are summed inside the round/log pass,
+    more by the reduction kernel; the last slice is shorter than the others."""
+    import paper_2403_09603_amd as vt
+    assert vt.vt_gemm_plan(M, N, K, 1, transA=tA) == (64, 64, splits)
+    g = si.rng(si.seed_for(1, 30) + splits)
+    A = g.standard_normal((K, M) if tA else (M, K))
+    B = g.standard_normal((K, N)) * 0.1
+    bias = g.standard_normal(N)
+    for variant in (0, 1):
+        _check(G, A, B, transA=tA, alpha=1.25, bias=bias, tau=2.0 ** -4, variant=variant)
+
+
 def test_variants_differ_in_low_bits_and_are_deterministic(G):
     A, B = si.tiny_gemm()
     r0 = G.gpu_gemm(A, B, variant=0, tau=0.25)
