@@ -419,3 +419,29 @@ def test_threshold_window_form_equals_the_distance_test(harith):
         harith.h_window_test(_u32p(r), C.c_uint64(r.size), C.c_uint32(thr), out.ctypes.data_as(C.POINTER(C.c_uint8)))
         expect = np.abs(r.astype(np.int64) - half) < thr
         assert np.array_equal(out.astype(bool), expect), thr
+
+
+def test_gemm_plan_is_a_pure_host_function_of_the_shape(hiplib):
+    """The plan (tile, split factor) depends on the shape, the A layout and the density of C alone: same
+    answer every time, splits only for dense outputs and long K, at least eight k steps per slice, and a
+    workspace that covers the largest split factor of any layout."""
+    import paper_2403_09603_amd as vt
+    INVALID = 1
+    tm, tn, sp = (C.c_int(), C.c_int(), C.c_int())
+    f = hiplib.vt_gemm_plan
+    assert f(2, 64, 64, 64, 1, 64, 4096, C.byref(tm), C.byref(tn), C.byref(sp)) == INVALID          # no such layout
+    assert f(0, -1, 64, 64, 1, 64, 4096, C.byref(tm), C.byref(tn), C.byref(sp)) == INVALID
+    assert f(0, 64, 64, 64, 1, 64, 4096, None, C.byref(tn), C.byref(sp)) == INVALID
+    g = np.random.default_rng(7)
+    for _ in range(300):
+        M, N, K = (int(v) for v in (g.integers(1, 5000), g.integers(1, 3000), g.integers(1, 200000)))
+        batch = int(g.choice([1, 1, 3]))
+        for layout in (vt.VT_A_ROW_MAJOR, vt.VT_A_TRANSPOSED, vt.VT_A_IM2COL_T):
+            p = vt.vt_gemm_plan(M, N, K, batch, transA=layout)
+            assert p == vt.vt_gemm_plan(M, N, K, batch, transA=layout)
+            assert p[:2] in ((128, 128), (64, 64)) and 1 <= p[2] <= 256
+            if p[2] > 1:
+                assert ((K + 15) // 16) // p[2] >= 8
+                need = hiplib.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG, M, N, K, batch)
+                assert need >= 8 * M * N * batch * p[2]                          # room for every slab
+            assert vt.vt_gemm_plan(M, N, K, batch, ldc=N + 1, transA=layout)[2] == 1   # padded rows: never split
