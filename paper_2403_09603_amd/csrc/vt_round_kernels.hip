@@ -108,11 +108,20 @@ __global__ __launch_bounds__(kScanThreads) void seg_scan_kernel(const uint32_t *
 }
 
 // --------------------------------------------------------------------------------------------
-// compact: one wave per segment.  Phase 1 walks the 64 plane words (skipping empty ones) and
-// writes each logged output's position inside the segment (12 bits) and direction (bit 15) to
-// LDS at its rank.  Phase 2 emits entries 64 at a time, aligned to multiples of 64 in log
-// position, so index stores are contiguous and a ballot yields whole direction words.
+// compact: one wave per segment (64 plane words, 4096 outputs).  Phase 1: every lane owns one
+// plane word; an exclusive scan of the words' population counts gives the rank of its first
+// logged output, and the lane writes position (12 bits) and direction (bit 15) of each of its
+// set bits to LDS at rank, rank + 1, ...  Ranks of neighbouring lanes lie about as far apart as
+// a word has bits set, so the LDS array carries four entries of padding per 64 (ranks 64 l of a
+// full plane would otherwise all fall into one bank).  Phase 2 emits the entries 256 at a time,
+// aligned to multiples of 256 in log position: four consecutive entries per lane (one 16-byte
+// index store where the log is aligned), their direction bits gathered over eight lanes into
+// whole 32-bit words; only the words a segment shares with its neighbours are OR-ed.
 // --------------------------------------------------------------------------------------------
+constexpr uint32_t kEntSlots = kSegElems + 4u * (kSegElems / 64u);
+
+__device__ __forceinline__ uint32_t ent_slot(uint32_t rank) { return rank + 4u * (rank >> 6); }
+
 __global__ __launch_bounds__(256) void compact_kernel(const uint64_t *__restrict__ pl_logged,
                                                       const uint64_t *__restrict__ pl_dir, uint64_t words,
                                                       const uint32_t *__restrict__ seg_cnt,
@@ -121,7 +130,7 @@ __global__ __launch_bounds__(256) void compact_kernel(const uint64_t *__restrict
                                                       uint32_t *__restrict__ idx, uint32_t *__restrict__ dir,
                                                       uint64_t cap)
 {
-    __shared__ uint16_t ent[4][kSegElems];
+    __shared__ uint16_t ent[4][kEntSlots];
     __shared__ uint32_t wbase[4][kSegWords];
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wv = threadIdx.x >> 6;
@@ -132,36 +141,60 @@ __global__ __launch_bounds__(256) void compact_kernel(const uint64_t *__restrict
     const uint64_t off = seg_off[seg];
     if (off >= cap) return;
     const uint64_t w = (uint64_t)seg * kSegWords + lane;
-    const uint64_t word = w < words ? pl_logged[w] : 0;
+    uint64_t m = w < words ? pl_logged[w] : 0;
     const uint64_t dword = w < words ? pl_dir[w] : 0;
     {
         const uint64_t row = w / wpr;
         wbase[wv][lane] = (uint32_t)(row * ncols + (w - row * wpr) * 64u);
     }
-    uint32_t local = 0;
-    for (uint32_t i = 0; i < kSegWords; ++i) {
-        const uint64_t m = readlane64(word, i);
-        if (m == 0) continue;
-        const uint64_t d = readlane64(dword, i);
-        if ((m >> lane) & 1ull)
-            ent[wv][local + rank_below(m)] = (uint16_t)((i << 6) | lane | (((uint32_t)(d >> lane) & 1u) << 15));
-        local += popc64(m);
+    // exclusive scan of the population counts over the wave
+    const uint32_t c = popc64(m);
+    uint32_t incl = c;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t up = (uint32_t)__shfl_up((int)incl, o, 64);
+        if (lane >= (uint32_t)o) incl += up;
+    }
+    uint32_t rank = incl - c;
+    while (m) {                                             // lanes leave as their word runs out of bits
+        const uint32_t b = (uint32_t)__builtin_ctzll(m);
+        ent[wv][ent_slot(rank)] = (uint16_t)((lane << 6) | b | (((uint32_t)(dword >> b) & 1u) << 15));
+        m &= m - 1;
+        ++rank;
     }
     wave_lds_fence();
     const uint64_t end = off + cnt < cap ? off + cnt : cap;
-    for (uint64_t G = off & ~63ull; G < end; G += 64) {
-        const uint64_t p = G + lane;
-        const bool valid = p >= off && p < end;
-        const uint32_t e = valid ? ent[wv][p - off] : 0u;
-        if (valid) idx[p] = wbase[wv][(e & 0xFFFu) >> 6] + (e & 63u);
-        const uint64_t dm = ballot(valid && (e >> 15));
-        const uint64_t vm = ballot(valid);
-        if (lane < 2) {
-            const uint32_t vh = lane ? (uint32_t)(vm >> 32) : (uint32_t)vm;
-            const uint32_t dh = lane ? (uint32_t)(dm >> 32) : (uint32_t)dm;
-            uint32_t *wp = dir + (G >> 5) + lane;
-            if (vh == 0xFFFFFFFFu) *wp = dh;
-            else if (vh) atomicOr(wp, dh);
+    const bool wide = ((uintptr_t)idx & 15u) == 0;
+    for (uint64_t G = off & ~255ull; G < end; G += 256) {
+        const uint64_t p0 = G + 4u * lane;
+        uint32_t iv[4], nib_v = 0, nib_d = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint64_t p = p0 + j;
+            const bool valid = p >= off && p < end;
+            const uint32_t e = valid ? ent[wv][ent_slot((uint32_t)(p - off))] : 0u;
+            iv[j] = wbase[wv][(e & 0xFFFu) >> 6] + (e & 63u);
+            nib_v |= (uint32_t)valid << j;
+            nib_d |= (e >> 15) << j;                        // (e is 0 for invalid positions)
+        }
+        if (wide && nib_v == 0xFu) {
+            *(uint4 *)(idx + p0) = make_uint4(iv[0], iv[1], iv[2], iv[3]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if ((nib_v >> j) & 1u) idx[p0 + j] = iv[j];
+        }
+        // eight lanes' nibbles make one direction word (entries G + 32 g .. G + 32 g + 31)
+        uint32_t vv = nib_v << (4u * (lane & 7u)), dv = nib_d << (4u * (lane & 7u));
+#pragma unroll
+        for (int o = 1; o < 8; o <<= 1) {
+            vv |= (uint32_t)__shfl_xor((int)vv, o, 64);
+            dv |= (uint32_t)__shfl_xor((int)dv, o, 64);
+        }
+        if ((lane & 7u) == 0 && vv) {
+            uint32_t *wp = dir + (G >> 5) + (lane >> 3);
+            if (vv == 0xFFFFFFFFu) *wp = dv;
+            else atomicOr(wp, dv);
         }
     }
 }
