@@ -91,10 +91,15 @@ int round_log_flat(const double *x, uint64_t n, uint32_t thr, float *y, const vt
 }
 
 // planes already hold the decisions: count per segment (unless the producer did), scan, compact
-int finish_log(const vt::Planes &pl, uint64_t rows, const vt_log *log, bool counted, hipStream_t s)
+int finish_log(const vt::Planes &pl, uint64_t rows, const vt_log *log, bool counted, uint32_t thr, hipStream_t s)
 {
     if (log->dense) return hip_status(vt::launch_planes_to_dense(pl, rows, log->dense, log->count, s));   // also writes *count
     const vt::LogOut lo{log->idx, log->dir, log->cap, log->count};
+    if (thr == 0) {                         // a zero threshold logs nothing (the auditor's own layer): the count is 0
+        vt::Planes none = pl;
+        none.segs = 0;
+        return hip_status(vt::launch_seg_scan(none, lo, s));
+    }
     hipError_t e = hipSuccess;
     if (!counted) e = vt::launch_seg_count(pl, s);
     if (e == hipSuccess) e = vt::launch_seg_scan(pl, lo, s);                 // also writes *count
@@ -143,7 +148,7 @@ int run_gemm(vt::GemmArgs &g, const vt_log *log, void *ws, size_t ws_bytes, hipS
     hipError_t e = vt::launch_gemm_round_planes(g, plan, pl, nullptr, nullptr, s);
     mark_end(s);
     if (e != hipSuccess) return VT_ERR_HIP;
-    return finish_log(pl, (uint64_t)M * (uint64_t)batch, log, /*counted=*/false, s);
+    return finish_log(pl, (uint64_t)M * (uint64_t)batch, log, /*counted=*/false, g.thr, s);
 }
 
 // Validates a convolution geometry and fills the internal descriptor (with the output size).
