@@ -333,12 +333,24 @@ __global__ __launch_bounds__(256) void replay_kernel(const double *__restrict__ 
     const uint64_t lo = s_lo;
     // lo is at most 3 before the tile's first entry, and at most 4096 entries belong to the tile:
     // 64 rounds of 64 plus one for the ragged start
-    for (uint32_t r = wv; r <= kReplayTile / 64; r += 4) {
-        const uint64_t p = lo + (uint64_t)r * 64u + lane;
-        const uint64_t i = p < count ? (uint64_t)idx[p] : ~0ull;
-        if (i >= start && i < stop)
-            flags[i - start] = (uint8_t)(1u | (((dir[p >> 5] >> (p & 31u)) & 1u) << 1));
-        if (ballot(i < stop) == 0) break;                    // sorted list: nothing further belongs here
+    // (a wave takes rounds wv, wv + 4, ...; four of its rounds are requested together, so that a tile
+    // with many entries pays one memory round trip per 16 rounds instead of one per 4)
+    for (uint32_t r0 = wv; r0 <= kReplayTile / 64; r0 += 16) {
+        uint64_t pp[4], ii[4];
+        uint32_t dd[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t r = r0 + 4u * (uint32_t)q;
+            pp[q] = lo + (uint64_t)r * 64u + lane;
+            const bool in = r <= kReplayTile / 64 && pp[q] < count;
+            ii[q] = in ? (uint64_t)idx[pp[q]] : ~0ull;
+            dd[q] = in ? dir[pp[q] >> 5] : 0u;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (ii[q] >= start && ii[q] < stop)
+                flags[ii[q] - start] = (uint8_t)(1u | (((dd[q] >> (pp[q] & 31u)) & 1u) << 1));
+        if (ballot(ii[3] < stop) == 0) break;                // sorted list: nothing further belongs here
     }
     __syncthreads();
     if (full) replay_store<true, VEC, K0>(v, flags, wv, y, n, wbase, lane, k);
