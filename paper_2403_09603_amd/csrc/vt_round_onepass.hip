@@ -259,29 +259,48 @@ __global__ __launch_bounds__(kThreads) void round_log_onepass_kernel(const Src x
     }
     const uint64_t off = sv & kValMask;
     const uint64_t end = off + c < cap ? off + c : cap;
-    // entries leave in groups of 64 aligned in log position: contiguous index stores, and one
-    // ballot gives two whole direction words
-    for (uint64_t G = off & ~63ull; G < end; G += 64) {
-        const uint64_t p = G + lane;
-        const bool valid = p >= off && p < end;
-        uint32_t e = 0;
-        if (valid) {
-            const uint32_t q = (uint32_t)(p - off);
-            uint32_t chunk = 0, start = 0;
+    // entries leave 256 at a time, aligned in log position: four consecutive entries per lane (one
+    // 16-byte index store where the log is aligned), their direction bits gathered over eight lanes
+    // into whole 32-bit words (the words were cleared beforehand, so partial ones are OR-ed)
+    const bool wide = ((uintptr_t)idx & 15u) == 0;
+    for (uint64_t G = off & ~255ull; G < end; G += 256) {
+        const uint64_t p0 = G + 4u * lane;
+        uint32_t iv[4] = {0, 0, 0, 0}, nib_v = 0, nib_d = 0;
 #pragma unroll
-            for (int w = 1; w < kWaves; ++w)
-                if (q >= pre[w]) { chunk = w; start = pre[w]; }
-            e = ent[chunk][q - start];
-            __builtin_nontemporal_store((uint32_t)((uint64_t)tile * kTile + chunk * kWaveChunk + (e & 0x3FFu)), idx + p);
+        for (int j = 0; j < 4; ++j) {
+            const uint64_t p = p0 + j;
+            if (p >= off && p < end) {
+                const uint32_t q = (uint32_t)(p - off);
+                uint32_t chunk = 0, start = 0;
+#pragma unroll
+                for (int w = 1; w < kWaves; ++w)
+                    if (q >= pre[w]) { chunk = w; start = pre[w]; }
+                const uint32_t e = ent[chunk][q - start];
+                iv[j] = (uint32_t)((uint64_t)tile * kTile + chunk * kWaveChunk + (e & 0x3FFu));
+                nib_v |= 1u << j;
+                nib_d |= (e >> 15) << j;
+            }
         }
-        const uint64_t dm = ballot(valid && (e >> 15));
-        const uint64_t vm = ballot(valid);
-        if (lane < 2) {
-            const uint32_t vh = lane ? (uint32_t)(vm >> 32) : (uint32_t)vm;
-            const uint32_t dh = lane ? (uint32_t)(dm >> 32) : (uint32_t)dm;
-            uint32_t *wp = dir + (G >> 5) + lane;
-            if (vh == 0xFFFFFFFFu) *wp = dh;
-            else if (vh && dh) atomicOr(wp, dh);
+        if (wide && nib_v == 0xFu) {
+            typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+            u4 o;
+            o.x = iv[0]; o.y = iv[1]; o.z = iv[2]; o.w = iv[3];
+            __builtin_nontemporal_store(o, (u4 *)(idx + p0));
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if ((nib_v >> j) & 1u) __builtin_nontemporal_store(iv[j], idx + p0 + j);
+        }
+        uint32_t vv = nib_v << (4u * (lane & 7u)), dv = nib_d << (4u * (lane & 7u));
+#pragma unroll
+        for (int o = 1; o < 8; o <<= 1) {
+            vv |= (uint32_t)__shfl_xor((int)vv, o, 64);
+            dv |= (uint32_t)__shfl_xor((int)dv, o, 64);
+        }
+        if ((lane & 7u) == 0 && vv) {
+            uint32_t *wp = dir + (G >> 5) + (lane >> 3);
+            if (vv == 0xFFFFFFFFu) *wp = dv;
+            else if (dv) atomicOr(wp, dv);
         }
     }
 }
