@@ -49,6 +49,13 @@ __global__ __launch_bounds__(256) void sum_slots_kernel(const uint64_t *__restri
 
 __global__ void zero_u64_kernel(uint64_t *p) { *p = 0; }
 
+// Consecutive workgroup ids run on different XCDs; every XCD takes one contiguous eighth of the tiles.
+__device__ __forceinline__ uint32_t xcd_contiguous_tile()
+{
+    const uint32_t i = blockIdx.x, q = gridDim.x / 8u, r = gridDim.x % 8u, xcd = i % 8u;
+    return xcd * q + (xcd < r ? xcd : r) + i / 8u;
+}
+
 // ternary code and FP32 bits of one value
 template <bool K0>
 __device__ __forceinline__ uint32_t code_of(double x, uint32_t thr, uint32_t k, uint32_t &ybits)
@@ -134,13 +141,13 @@ __device__ __forceinline__ void round_log_dense_chunk(const Src &x, uint64_t n, 
 }
 
 template <bool VEC, bool K0, class Src>
-__global__ __launch_bounds__(256) void round_log_dense_kernel(const Src x, uint64_t n, uint32_t thr,
+__global__ __launch_bounds__(kWaves * 64) void round_log_dense_kernel(const Src x, uint64_t n, uint32_t thr,
                                                               uint32_t k, float *__restrict__ y,
                                                               uint8_t *__restrict__ tlog, uint64_t *__restrict__ slots)
 {
     __shared__ __attribute__((aligned(16))) uint8_t codes[kWaves][kChunk];
     const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
-    const uint64_t base = (uint64_t)blockIdx.x * kTile + (uint64_t)wv * kChunk;
+    const uint64_t base = (uint64_t)xcd_contiguous_tile() * kTile + (uint64_t)wv * kChunk;
     if (base >= n) return;
     if (base + kChunk <= n) round_log_dense_chunk<true, VEC, K0>(x, n, thr, k, y, tlog, base, lane, codes[wv], slots);
     else round_log_dense_chunk<false, VEC, K0>(x, n, thr, k, y, tlog, base, lane, codes[wv], slots);
@@ -203,13 +210,13 @@ __device__ __forceinline__ void replay_dense_chunk(const double *__restrict__ x,
 }
 
 template <bool VEC, bool K0>
-__global__ __launch_bounds__(256) void replay_dense_kernel(const double *__restrict__ x, uint64_t n,
+__global__ __launch_bounds__(kWaves * 64) void replay_dense_kernel(const double *__restrict__ x, uint64_t n,
                                                            const uint8_t *__restrict__ tlog, float *__restrict__ y,
                                                            uint32_t k)
 {
     __shared__ __attribute__((aligned(16))) uint8_t codes[kWaves][kChunk];
     const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
-    const uint64_t base = (uint64_t)blockIdx.x * kTile + (uint64_t)wv * kChunk;
+    const uint64_t base = (uint64_t)xcd_contiguous_tile() * kTile + (uint64_t)wv * kChunk;
     if (base >= n) return;
     if (base + kChunk <= n) replay_dense_chunk<true, VEC, K0>(x, n, tlog, y, base, lane, codes[wv], k);
     else replay_dense_chunk<false, VEC, K0>(x, n, tlog, y, base, lane, codes[wv], k);
@@ -358,7 +365,7 @@ hipError_t launch_dense_from(const Src &src, bool vec, uint64_t n, uint32_t thr,
         if (e != hipSuccess) return e;
     }
     const uint64_t blocks = (n + kTile - 1) / kTile;
-    const dim3 grid((uint32_t)blocks), block(256);
+    const dim3 grid((uint32_t)blocks), block(kWaves * 64);
     if (vec && k == 0) round_log_dense_kernel<true, true, Src><<<grid, block, 0, s>>>(src, n, thr, k, y, tlog, slots);
     else if (vec) round_log_dense_kernel<true, false, Src><<<grid, block, 0, s>>>(src, n, thr, k, y, tlog, slots);
     else if constexpr (std::is_same<Src, PlainSource>::value) {     // misaligned tensors: scalar accesses
@@ -426,7 +433,7 @@ hipError_t launch_replay_dense(const double *x, uint64_t n, const uint8_t *tlog,
     if (n == 0) return hipSuccess;
     const uint64_t blocks = (n + kTile - 1) / kTile;
     const bool vec = ((uintptr_t)x % 16 == 0) && ((uintptr_t)y % 8 == 0);
-    const dim3 grid((uint32_t)blocks), block(256);
+    const dim3 grid((uint32_t)blocks), block(kWaves * 64);
     if (vec && k == 0) replay_dense_kernel<true, true><<<grid, block, 0, s>>>(x, n, tlog, y, k);
     else if (vec) replay_dense_kernel<true, false><<<grid, block, 0, s>>>(x, n, tlog, y, k);
     else if (k == 0) replay_dense_kernel<false, true><<<grid, block, 0, s>>>(x, n, tlog, y, k);
