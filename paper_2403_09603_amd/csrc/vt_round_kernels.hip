@@ -73,23 +73,28 @@ __global__ __launch_bounds__(kScanThreads) void seg_scan_kernel(const uint32_t *
                                                                 uint32_t *__restrict__ dir, uint64_t cap,
                                                                 uint64_t *__restrict__ count)
 {
-    __shared__ uint64_t part[kScanThreads];
-    const uint32_t t = threadIdx.x;
+    __shared__ uint64_t wave_total[kScanThreads / 64];
+    const uint32_t t = threadIdx.x, lane = t & 63u, wv = t >> 6;
     const uint32_t chunk = (segs + kScanThreads - 1) / kScanThreads;
     const uint64_t lo = (uint64_t)t * chunk;
     const uint64_t hi = lo + chunk < segs ? lo + chunk : segs;
     uint64_t sum = 0;
     for (uint64_t s = lo; s < hi; ++s) sum += seg_cnt[s];
-    part[t] = sum;
-    __syncthreads();
-    for (int o = 1; o < kScanThreads; o <<= 1) {           // inclusive Hillis-Steele scan
-        const uint64_t add = t >= (uint32_t)o ? part[t - o] : 0;
-        __syncthreads();
-        part[t] += add;
-        __syncthreads();
+    uint64_t incl = sum;                                    // inclusive scan inside the wave, then over the waves
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint64_t up = (uint64_t)__shfl_up((unsigned long long)incl, o, 64);
+        if (lane >= (uint32_t)o) incl += up;
     }
-    const uint64_t total = part[kScanThreads - 1];
-    uint64_t run = part[t] - sum;
+    if (lane == 63) wave_total[wv] = incl;
+    __syncthreads();
+    uint64_t before = 0, total = 0;
+#pragma unroll
+    for (uint32_t w = 0; w < kScanThreads / 64; ++w) {
+        if (w < wv) before += wave_total[w];
+        total += wave_total[w];
+    }
+    uint64_t run = before + incl - sum;
     const uint64_t cap_words = (cap + 31) >> 5;
     for (uint64_t s = lo; s < hi; ++s) {
         const uint32_t c = seg_cnt[s];
