@@ -410,7 +410,9 @@ static int gemm_entry(int transA, int transB, int64_t M, int64_t N, int64_t K, d
         const vt::LogOut lo{log->idx, log->dir, log->cap, log->count};
         return hip_status(vt::launch_seg_scan(pl, lo, s));
     }
-    if (!C32 || !aligned(C32, 4) || ldc < N || (batch > 1 && strideC < 0)) return VT_ERR_INVALID_ARG;
+    if (!C32 || !aligned(C32, 4) || ldc < N) return VT_ERR_INVALID_ARG;
+    if (batch > 1 && (strideC < 0 || (unsigned __int128)strideC < (unsigned __int128)(M - 1) * (unsigned __int128)ldc + (unsigned __int128)N))
+        return VT_ERR_INVALID_ARG;          // the outputs of two matrices would overlap (also a negative stride)
     if (K > 0) {
         if (!A || !B || !aligned(A, 8) || !aligned(B, 8)) return VT_ERR_INVALID_ARG;
         if (lda < (transA ? M : K) || ldb < (transB ? K : N) || strideA < 0 || strideB < 0) return VT_ERR_INVALID_ARG;
