@@ -153,7 +153,8 @@ int vt_round_replay_dense_br(const double *x, uint64_t n, const uint8_t *tlog, i
  *                  (strideA or strideB may be 0 to share an operand)
  *   bias           device, N FP64 values added after the alpha scaling, or NULL
  *   C32            device, FP32 output, row pitch ldc >= N; with batch > 1 the matrices must not
- *                  overlap: strideC >= (M - 1) * ldc + N
+ *                  overlap: one after the other (strideC >= (M - 1) * ldc + N) or side by side in
+ *                  the columns of one wide matrix (strideC >= N, (batch - 1) * strideC + N <= ldc)
  *   C64_debug      device or NULL: when given, receives the FP64 values before rounding
  *                  (dense, pitch N, batch stride M*N) -- for tests and threshold statistics
  *   variant        accumulation order: 0 = k steps (and split-K slices) in ascending order;

@@ -411,8 +411,12 @@ static int gemm_entry(int transA, int transB, int64_t M, int64_t N, int64_t K, d
         return hip_status(vt::launch_seg_scan(pl, lo, s));
     }
     if (!C32 || !aligned(C32, 4) || ldc < N) return VT_ERR_INVALID_ARG;
-    if (batch > 1 && (strideC < 0 || (unsigned __int128)strideC < (unsigned __int128)(M - 1) * (unsigned __int128)ldc + (unsigned __int128)N))
-        return VT_ERR_INVALID_ARG;          // the outputs of two matrices would overlap (also a negative stride)
+    if (batch > 1) {                        // the matrices' outputs must not overlap: one after the other, or side by side
+        const unsigned __int128 sc = strideC < 0 ? 0 : (unsigned __int128)strideC;
+        const bool blocks = sc >= (unsigned __int128)(M - 1) * (unsigned __int128)ldc + (unsigned __int128)N;
+        const bool columns = sc >= (unsigned __int128)N && (unsigned __int128)(batch - 1) * sc + (unsigned __int128)N <= (unsigned __int128)ldc;
+        if (strideC < 0 || !(blocks || columns)) return VT_ERR_INVALID_ARG;
+    }
     if (K > 0) {
         if (!A || !B || !aligned(A, 8) || !aligned(B, 8)) return VT_ERR_INVALID_ARG;
         if (lda < (transA ? M : K) || ldb < (transB ? K : N) || strideA < 0 || strideB < 0) return VT_ERR_INVALID_ARG;

@@ -93,7 +93,7 @@ def test_argument_validation_happens_on_the_host(hiplib):
     assert call(ldc=127) == INVALID and call(variant=2) == INVALID and call(tau=-0.1) == INVALID
     assert call(tA=2) == INVALID and call(M=1 << 20, N=1 << 12, lda=64, ldc=1 << 12) == INVALID
     assert call(ws=None, wsb=0) == WORKSPACE and call(wsb=16) == WORKSPACE
-    for strideC, want in ((128 * 128 - 1, INVALID), (0, INVALID), (-5, INVALID)):          # batched outputs may not overlap
+    for strideC, want in ((128 * 128 - 1, INVALID), (0, INVALID), (-5, INVALID), (64, INVALID), (200, INVALID)):   # batched outputs may not overlap
         assert g(0, 0, 128, 128, 64, 1.0, fake, 64, 0, fake, 128, 0, None, 2, fake, 128, strideC, None, 0, 0.1, C.byref(log),
                  fake, 1 << 24, None) == want
     log26 = b._VtLog(None, None, 0, C.addressof(cnt), None, 26)                  # b_r < 32 needs a dense C
