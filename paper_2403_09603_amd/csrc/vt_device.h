@@ -341,7 +341,13 @@ struct ConvGeom {
     int32_t vec;                     // taps (kc, kc + 1), kc even, are one aligned 16-byte load (C even)
     uint32_t rows, taps;             // N Ho Wo and KH KW C
     double inv_HoWo, inv_Wo, inv_KWC, inv_C, inv_sh, inv_sw;
+    uint32_t mKWC, mC, msh, msw;     // multipliers of divmod_magic for KWC, C and the strides
+    int32_t uni;                     // the 16 taps of a k step share (kh, kw): C is a multiple of 16
+    int32_t Ho, nimg;                // output rows per image, images
+    int32_t st_n, st_ho, st_wo;      // kRowStep = st_n HoWo + st_ho Wo + st_wo: one k step of the weight gradient
 };
+
+constexpr int kRowStep = 16;         // rows of the image matrix per k step of the transposed view
 
 constexpr int32_t kNowhere = -(1 << 30);        // row / tap coordinate that fails every bounds test
 
@@ -353,6 +359,22 @@ static __host__ __device__ __forceinline__ void divmod_u32(uint32_t x, uint32_t 
     if (rem < 0) { --q; rem += (int32_t)d; }
     else if ((uint32_t)rem >= d) { ++q; rem -= (int32_t)d; }
     r = (uint32_t)rem;
+}
+
+// The same split in integer operations only: with m = min(floor(2^32 / d), 2^32 - 1) the high half of
+// x m is the quotient or one below it (x / d - x m / 2^32 = x (2^32 - m d) / (d 2^32) < x / 2^32 < 1).
+// A wave-uniform x then stays in scalar registers, where the double product above would not.
+static __host__ __device__ __forceinline__ void divmod_magic(uint32_t x, uint32_t d, uint32_t m, uint32_t &q, uint32_t &r)
+{
+    q = (uint32_t)(((uint64_t)x * m) >> 32);
+    r = x - q * d;
+    if (r >= d) { ++q; r -= d; }
+}
+
+static inline uint32_t magic_of(uint32_t d)
+{
+    const uint64_t m = (1ull << 32) / (d > 0 ? d : 1);
+    return m > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)m;
 }
 
 struct RowPos { int32_t base, h0, w0, rem; };   // element offset of X[n, h0, w0, 0]; top-left tap position
@@ -373,11 +395,62 @@ static __host__ __device__ __forceinline__ RowPos conv_row(const ConvGeom &c, ui
     return r;
 }
 
+// A row of the image matrix kept as (n, ho, wo) and moved kRowStep rows at a time (the weight
+// gradient walks the rows along k): digit-wise addition with one carry per digit instead of two
+// index splits per step.  Walking down adds the complement (Wo - st_wo, Ho - 1 - st_ho, -st_n - 1),
+// which lowers the row by kRowStep through the same carries.  Rows before the first or past the
+// last image have n outside [0, nimg) and read as padding.
+struct RowIter { int32_t n, ho, wo; };
+
+static __host__ __device__ __forceinline__ RowIter row_iter(const ConvGeom &c, uint32_t m)
+{
+    uint32_t n, rem, ho, wo;
+    divmod_u32(m, (uint32_t)c.HoWo, c.inv_HoWo, n, rem);
+    divmod_u32(rem, (uint32_t)c.Wo, c.inv_Wo, ho, wo);
+    return RowIter{(int32_t)n, (int32_t)ho, (int32_t)wo};
+}
+
+static __host__ __device__ __forceinline__ void row_step_digits(const ConvGeom &c, bool down, int32_t &an, int32_t &ah, int32_t &aw)
+{
+    an = down ? -c.st_n - 1 : c.st_n;
+    ah = down ? c.Ho - 1 - c.st_ho : c.st_ho;
+    aw = down ? c.Wo - c.st_wo : c.st_wo;
+}
+
+static __host__ __device__ __forceinline__ void row_advance(const ConvGeom &c, RowIter &s, int32_t an, int32_t ah, int32_t aw)
+{
+    s.wo += aw;
+    const int32_t cw = s.wo >= c.Wo ? 1 : 0;
+    s.wo -= cw ? c.Wo : 0;
+    s.ho += ah + cw;
+    const int32_t ch = s.ho >= c.Ho ? 1 : 0;
+    s.ho -= ch ? c.Ho : 0;
+    s.n += an + ch;
+}
+
+static __host__ __device__ __forceinline__ RowPos row_pos(const ConvGeom &c, const RowIter &s)
+{
+    RowPos r;
+    const int32_t h0 = s.ho * c.sh - c.ph;
+    r.w0 = s.wo * c.sw - c.pw;
+    r.base = (int32_t)((((uint32_t)s.n * (uint32_t)c.H + (uint32_t)h0) * (uint32_t)c.W + (uint32_t)r.w0) * (uint32_t)c.C);
+    r.h0 = (uint32_t)s.n < (uint32_t)c.nimg ? h0 : kNowhere;
+    r.rem = 0;
+    return r;
+}
+
+// INT: integer-only index split (for a wave-uniform kc: the whole tap is computed in scalar registers)
+template <bool INT = false>
 static __host__ __device__ __forceinline__ TapPos conv_tap(const ConvGeom &c, uint32_t kc)
 {
     uint32_t kh, rem, kw, ci;
-    divmod_u32(kc, (uint32_t)c.KWC, c.inv_KWC, kh, rem);
-    divmod_u32(rem, (uint32_t)c.C, c.inv_C, kw, ci);
+    if (INT) {
+        divmod_magic(kc, (uint32_t)c.KWC, c.mKWC, kh, rem);
+        divmod_magic(rem, (uint32_t)c.C, c.mC, kw, ci);
+    } else {
+        divmod_u32(kc, (uint32_t)c.KWC, c.inv_KWC, kh, rem);
+        divmod_u32(rem, (uint32_t)c.C, c.inv_C, kw, ci);
+    }
     TapPos t;
     t.hh = (int32_t)kh * c.dh;
     t.ww = (int32_t)kw * c.dw;
@@ -411,13 +484,21 @@ static __host__ __device__ __forceinline__ RowPos dgrad_row(const ConvGeom &c, u
     return r;
 }
 
+template <bool INT = false>
 static __host__ __device__ __forceinline__ TapPos dgrad_tap(const ConvGeom &c, uint32_t kc)
 {
     uint32_t kh, rem, kw, co, qk, rk, qkw, rkw;
-    divmod_u32(kc, (uint32_t)c.KWC, c.inv_KWC, kh, rem);
-    divmod_u32(rem, (uint32_t)c.C, c.inv_C, kw, co);
-    divmod_u32(kh * (uint32_t)c.dh, (uint32_t)c.sh, c.inv_sh, qk, rk);
-    divmod_u32(kw * (uint32_t)c.dw, (uint32_t)c.sw, c.inv_sw, qkw, rkw);
+    if (INT) {
+        divmod_magic(kc, (uint32_t)c.KWC, c.mKWC, kh, rem);
+        divmod_magic(rem, (uint32_t)c.C, c.mC, kw, co);
+        divmod_magic(kh * (uint32_t)c.dh, (uint32_t)c.sh, c.msh, qk, rk);
+        divmod_magic(kw * (uint32_t)c.dw, (uint32_t)c.sw, c.msw, qkw, rkw);
+    } else {
+        divmod_u32(kc, (uint32_t)c.KWC, c.inv_KWC, kh, rem);
+        divmod_u32(rem, (uint32_t)c.C, c.inv_C, kw, co);
+        divmod_u32(kh * (uint32_t)c.dh, (uint32_t)c.sh, c.inv_sh, qk, rk);
+        divmod_u32(kw * (uint32_t)c.dw, (uint32_t)c.sw, c.inv_sw, qkw, rkw);
+    }
     TapPos t;
     t.hh = -(int32_t)qk;
     t.ww = -(int32_t)qkw;
@@ -438,9 +519,17 @@ static inline ConvGeom conv_geom(int64_t N, int64_t H, int64_t W, int64_t C, int
     c.sh = (int32_t)sh; c.sw = (int32_t)sw; c.ph = (int32_t)ph; c.pw = (int32_t)pw; c.dh = (int32_t)dh; c.dw = (int32_t)dw;
     c.vec = vec ? 1 : 0;
     c.rows = (uint32_t)(N * Ho * Wo); c.taps = (uint32_t)(KH * KW * C);
+    c.Ho = (int32_t)Ho; c.nimg = (int32_t)N;
+    {
+        const int64_t hw = Ho * Wo > 0 ? Ho * Wo : 1, wq = Wo > 0 ? Wo : 1;
+        c.st_n = (int32_t)(kRowStep / hw); c.st_ho = (int32_t)(kRowStep % hw / wq); c.st_wo = (int32_t)(kRowStep % hw % wq);
+    }
     c.inv_HoWo = 1.0 / (double)(c.HoWo > 0 ? c.HoWo : 1); c.inv_Wo = 1.0 / (double)(c.Wo > 0 ? c.Wo : 1);
     c.inv_KWC = 1.0 / (double)(c.KWC > 0 ? c.KWC : 1); c.inv_C = 1.0 / (double)(c.C > 0 ? c.C : 1);
     c.inv_sh = 1.0 / (double)c.sh; c.inv_sw = 1.0 / (double)c.sw;
+    c.mKWC = magic_of((uint32_t)c.KWC); c.mC = magic_of((uint32_t)c.C);
+    c.msh = magic_of((uint32_t)c.sh); c.msw = magic_of((uint32_t)c.sw);
+    c.uni = vec && c.C > 0 && c.C % 16 == 0 ? 1 : 0;
     return c;
 }
 
@@ -456,27 +545,33 @@ static inline ConvGeom dgrad_geom(int64_t N, int64_t H, int64_t W, int64_t Cout,
     c.sh = (int32_t)sh; c.sw = (int32_t)sw; c.ph = (int32_t)ph; c.pw = (int32_t)pw; c.dh = (int32_t)dh; c.dw = (int32_t)dw;
     c.vec = vec ? 1 : 0;
     c.rows = (uint32_t)(N * H * W); c.taps = (uint32_t)(KH * KW * Cout);
+    c.Ho = (int32_t)H; c.nimg = (int32_t)N; c.st_n = c.st_ho = c.st_wo = 0;      // (rows are not walked along k in this view)
     c.inv_HoWo = 1.0 / (double)(c.HoWo > 0 ? c.HoWo : 1); c.inv_Wo = 1.0 / (double)(c.Wo > 0 ? c.Wo : 1);
     c.inv_KWC = 1.0 / (double)(c.KWC > 0 ? c.KWC : 1); c.inv_C = 1.0 / (double)(c.C > 0 ? c.C : 1);
     c.inv_sh = 1.0 / (double)c.sh; c.inv_sw = 1.0 / (double)c.sw;
+    c.mKWC = magic_of((uint32_t)c.KWC); c.mC = magic_of((uint32_t)c.C);
+    c.msh = magic_of((uint32_t)c.sh); c.msw = magic_of((uint32_t)c.sw);
+    c.uni = vec && c.C > 0 && c.C % 16 == 0 ? 1 : 0;
     return c;
 }
 
 // Element offset of the im2col matrix entry (row m, tap kc) in the image, or -1 when it is a
 // padding zero or lies outside the matrix: what conv_gather loads, as one function.
+template <bool INT = false>
 static __host__ __device__ __forceinline__ int64_t conv_element(const ConvGeom &c, uint32_t m, uint32_t kc)
 {
     const RowPos r = conv_row(c, m);
-    const TapPos t = conv_tap(c, kc);
+    const TapPos t = conv_tap<INT>(c, kc);
     const bool ok = (uint32_t)(r.h0 + t.hh) < (uint32_t)c.H && (uint32_t)(r.w0 + t.ww) < (uint32_t)c.W;
     return ok ? (int64_t)(r.base + t.off) : -1;
 }
 
 // The same for the input-gradient view: offset into dY of matrix entry (row m, column kc), or -1.
+template <bool INT = false>
 static __host__ __device__ __forceinline__ int64_t dgrad_element(const ConvGeom &c, uint32_t m, uint32_t kc)
 {
     const RowPos r = dgrad_row(c, m);
-    const TapPos t = dgrad_tap(c, kc);
+    const TapPos t = dgrad_tap<INT>(c, kc);
     const bool ok = (uint32_t)(r.h0 + t.hh) < (uint32_t)c.H && (uint32_t)(r.w0 + t.ww) < (uint32_t)c.W && r.rem == t.rem;
     return ok ? (int64_t)(r.base + t.off) : -1;
 }

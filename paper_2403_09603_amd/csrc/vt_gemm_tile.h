@@ -70,9 +70,12 @@ typedef double d2 __attribute__((ext_vector_type(2)));
 constexpr int kPad = 18, kPadSmall = 14;
 
 
-// Two neighbouring taps of one row.  The load is unconditional (from X[0] when the element lies
-// in the padding or outside the matrix) and the value is selected afterwards, so the loop body
-// stays free of branches.
+// Two neighbouring taps of one row.  An element in the padding, outside the matrix or (input
+// gradient) between the stride's positions is loaded from a pair of zeros instead: the choice is
+// made on the address, so nothing has to wait for the loaded value before it goes to LDS two
+// steps later, and the loop body stays free of branches.
+static __device__ __attribute__((aligned(16))) double kZeroPair[2] = {0.0, 0.0};     // never written (not const: a global-memory address keeps the loads off the LDS counter)
+
 template <bool VEC, bool UP = false>
 __device__ __forceinline__ d2 conv_gather(const double *__restrict__ X, const ConvGeom &c, const RowPos &r,
                                           const TapPos &t0, const TapPos &t1)
@@ -80,18 +83,14 @@ __device__ __forceinline__ d2 conv_gather(const double *__restrict__ X, const Co
     // UP (input gradient): the row's and the tap's stride remainders must agree as well
     const bool ok0 = (uint32_t)(r.h0 + t0.hh) < (uint32_t)c.H && (uint32_t)(r.w0 + t0.ww) < (uint32_t)c.W &&
                      (!UP || r.rem == t0.rem);
+    const double *p0 = X + (r.base + t0.off);
+    if (VEC) return *(const d2 *)(ok0 ? p0 : kZeroPair);
+    const bool ok1 = (uint32_t)(r.h0 + t1.hh) < (uint32_t)c.H && (uint32_t)(r.w0 + t1.ww) < (uint32_t)c.W &&
+                     (!UP || r.rem == t1.rem);
+    const double *p1 = X + (r.base + t1.off);
     d2 v;
-    if (VEC) {
-        const d2 x = *(const d2 *)(X + (ok0 ? r.base + t0.off : 0));
-        v.x = ok0 ? x.x : 0.0;
-        v.y = ok0 ? x.y : 0.0;
-    } else {
-        const bool ok1 = (uint32_t)(r.h0 + t1.hh) < (uint32_t)c.H && (uint32_t)(r.w0 + t1.ww) < (uint32_t)c.W &&
-                         (!UP || r.rem == t1.rem);
-        const double a = X[ok0 ? r.base + t0.off : 0], b = X[ok1 ? r.base + t1.off : 0];
-        v.x = ok0 ? a : 0.0;
-        v.y = ok1 ? b : 0.0;
-    }
+    v.x = *(ok0 ? p0 : kZeroPair);
+    v.y = *(ok1 ? p1 : kZeroPair);
     return v;
 }
 
@@ -269,14 +268,34 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
 #pragma unroll
         for (int j = 0; j < BM / 32; ++j) rowp[j] = dgrad_row(p.conv, (uint32_t)bm + (t >> 3) + 32 * j);
     }
+    // (weight gradient: the rows run along k; each thread walks its BM / 32 rows a k step at a time,
+    // from the first tile it fetches, in the variant's direction)
+    // (the large tile has no registers left for the walk: it splits its row indices at every step)
+    constexpr bool WALK = AM == 3 && BM == 64;
+    RowIter rit[WALK ? BM / 32 : 1];
+    int32_t row_an = 0, row_ah = 0, row_aw = 0;
     if constexpr (AM == 3) {
         const uint32_t kc = (uint32_t)bm + (t % (BM / 2)) * 2;
         tap0 = conv_tap(p.conv, kc);
         tap1 = conv_tap(p.conv, kc + 1);
     }
-    auto gather_tile = [&](auto vec_tag, int64_t k0, d2 (&ra)[BM / 32]) {
-        constexpr bool VEC = decltype(vec_tag)::value;
-        if constexpr (AM == 2) {
+    if constexpr (WALK) {
+        static_assert(BK == kRowStep, "the row walk advances one k step at a time");
+        const uint32_t kfirst = (uint32_t)(p.variant ? kt1 - 1 : kt0) * BK;
+#pragma unroll
+        for (int j = 0; j < BM / 32; ++j) rit[j] = row_iter(p.conv, kfirst + t / (BM / 2) + (512 / BM) * j);
+        row_step_digits(p.conv, p.variant != 0, row_an, row_ah, row_aw);
+    }
+    // UNI: the channel count is a multiple of 16, so the 16 taps of a k step are 16 channels of one
+    // filter position: (kh, kw) and the tap's offset are the same for the whole wave and are found
+    // with scalar integer operations; the lane's channel pair is already part of its rows' offsets.
+    auto gather_tile = [&](auto vec_tag, auto uni_tag, int64_t k0, d2 (&ra)[BM / 32]) {
+        constexpr bool VEC = decltype(vec_tag)::value, UNI = decltype(uni_tag)::value;
+        if constexpr (UNI && (AM == 2 || AM == 4)) {
+            const TapPos t0 = AM == 2 ? conv_tap<true>(p.conv, (uint32_t)k0) : dgrad_tap<true>(p.conv, (uint32_t)k0);
+#pragma unroll
+            for (int j = 0; j < BM / 32; ++j) ra[j] = conv_gather<true, AM == 4>(p.A, p.conv, rowp[j], t0, t0);
+        } else if constexpr (AM == 2) {
             const uint32_t kc = (uint32_t)k0 + (t & 7) * 2;
             const TapPos t0 = conv_tap(p.conv, kc);
             const TapPos t1 = VEC ? t0 : conv_tap(p.conv, kc + 1);
@@ -285,8 +304,15 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
         } else if constexpr (AM == 3) {
 #pragma unroll
             for (int j = 0; j < BM / 32; ++j) {
-                const RowPos r = conv_row(p.conv, (uint32_t)k0 + t / (BM / 2) + (512 / BM) * j);
-                ra[j] = conv_gather<VEC>(p.A, p.conv, r, tap0, tap1);
+                if constexpr (WALK) {
+                    // the tiles are fetched in order, one per call (a fetch repeated past the last
+                    // tile moves on to rows nobody multiplies): k0 is implied
+                    ra[j] = conv_gather<VEC>(p.A, p.conv, row_pos(p.conv, rit[j]), tap0, tap1);
+                    row_advance(p.conv, rit[j], row_an, row_ah, row_aw);
+                } else {
+                    const RowPos r = conv_row(p.conv, (uint32_t)k0 + t / (BM / 2) + (512 / BM) * j);
+                    ra[j] = conv_gather<VEC>(p.A, p.conv, r, tap0, tap1);
+                }
             }
         } else if constexpr (AM == 4) {
             const uint32_t kc = (uint32_t)k0 + (t & 7) * 2;
@@ -296,14 +322,14 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
             for (int j = 0; j < BM / 32; ++j) ra[j] = conv_gather<VEC, true>(p.A, p.conv, rowp[j], t0, t1);
         }
     };
-    auto main_loop = [&](auto fast_tag) {
+    auto main_loop = [&](auto fast_tag, auto uni_tag) {
         constexpr bool FAST = decltype(fast_tag)::value;
         auto fetch = [&](int it, d2 (&ra)[BM / 32], d2 (&rb)[BN / 32]) {   // `it`-th step in this variant's order
             const int64_t k0 = (int64_t)(p.variant ? kt1 - 1 - it : kt0 + it) * BK;
             if constexpr (GA) {
-                if constexpr (FAST) gather_tile(std::true_type{}, k0, ra);
-                else if (p.conv.vec) gather_tile(std::true_type{}, k0, ra);
-                else gather_tile(std::false_type{}, k0, ra);
+                if constexpr (FAST) gather_tile(std::true_type{}, uni_tag, k0, ra);
+                else if (p.conv.vec) gather_tile(std::true_type{}, std::false_type{}, k0, ra);
+                else gather_tile(std::false_type{}, std::false_type{}, k0, ra);
             } else if constexpr (FAST) {
                 load_tile_fast<KCA, BM>(baseA, p.lda, k0, offA, ra);
             } else {
@@ -370,13 +396,26 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
             if (nkt > 1) fetch(1, ra0, rb0);
         }
         __syncthreads();
-        for (int it = 0; it < nkt; it += 2) {
+        // (the odd last step stands after the loop: an exit from the middle of the body would reach
+        // the loop's head with the first step's loads pending, and every wait in the body is placed
+        // for the worst of the paths into it)
+        int it = 0;
+        for (; it + 1 < nkt; it += 2) {
             step(it, 0, ra1, rb1, ra0, rb0);                // tile it+1 sits in set 0, it+2 goes to set 1
-            if (it + 1 < nkt) step(it + 1, 1, ra0, rb0, ra1, rb1);
+            step(it + 1, 1, ra0, rb0, ra1, rb1);
         }
+        if (it < nkt) step(it, 0, ra1, rb1, ra0, rb0);
     };
-    if (fastA && fastB && (int64_t)kt1 * BK <= p.K) main_loop(std::true_type{});
-    else main_loop(std::false_type{});
+    const bool fast = fastA && fastB && (int64_t)kt1 * BK <= p.K;
+    if ((AM == 2 || AM == 4) && fast && p.conv.uni) {
+#pragma unroll
+        for (int j = 0; j < BM / 32; ++j) rowp[j].base += (t & 7) * 2;
+        main_loop(std::true_type{}, std::true_type{});
+    } else if (fast) {
+        main_loop(std::true_type{}, std::false_type{});
+    } else {
+        main_loop(std::false_type{}, std::false_type{});
+    }
 
     const int g = lane >> 4, c16 = lane & 15;
     const int64_t row0 = bm + wm * (16 * TM), col0 = bn + wn * 64;

@@ -46,6 +46,52 @@ extern "C" void h_dgrad_offsets(const int64_t *g /* N H W Cout KH KW sh sw ph pw
         for (uint32_t k = 0; k < cols_to_do; ++k) offsets[(uint64_t)m * cols_to_do + k] = vt::dgrad_element(c, row0 + m, col0 + k);
 }
 
+// The integer-only index split (used where the tap is wave-uniform): quotient and remainder for given
+// (x, d), and the number of (row, tap) pairs on which the two forms of the loader's arithmetic disagree.
+extern "C" void h_divmod_magic(const uint32_t *x, const uint32_t *d, uint64_t n, uint32_t *q, uint32_t *r)
+{
+    for (uint64_t i = 0; i < n; ++i) vt::divmod_magic(x[i], d[i], vt::magic_of(d[i]), q[i], r[i]);
+}
+
+extern "C" uint64_t h_tap_split_mismatches(const int64_t *g /* N H W C|Cout KH KW sh sw ph pw dh dw Ho Wo */, int dgrad,
+                                           uint32_t row0, uint32_t rows_to_do)
+{
+    const vt::ConvGeom c = dgrad ? vt::dgrad_geom(g[0], g[1], g[2], g[3], g[4], g[5], g[6], g[7], g[8], g[9], g[10], g[11],
+                                                  g[12], g[13], false)
+                                 : vt::conv_geom(g[0], g[1], g[2], g[3], g[4], g[5], g[6], g[7], g[8], g[9], g[10], g[11],
+                                                 g[12], g[13], false);
+    uint64_t bad = 0;
+    for (uint32_t m = row0; m < row0 + rows_to_do; ++m)
+        for (uint32_t k = 0; k < c.taps + 40; ++k)
+            bad += dgrad ? vt::dgrad_element<true>(c, m, k) != vt::dgrad_element<false>(c, m, k)
+                         : vt::conv_element<true>(c, m, k) != vt::conv_element<false>(c, m, k);
+    return bad;
+}
+
+// The weight gradient's row walk: from row m0, `steps` moves of kRowStep rows up or down; the number
+// of positions at which the walked row differs from the directly split one (rows outside the matrix
+// must read as padding, whatever their digits are).
+extern "C" uint64_t h_row_walk_mismatches(const int64_t *g /* N H W C KH KW sh sw ph pw dh dw Ho Wo */, uint32_t m0, uint32_t steps, int down)
+{
+    const vt::ConvGeom c = vt::conv_geom(g[0], g[1], g[2], g[3], g[4], g[5], g[6], g[7], g[8], g[9], g[10], g[11], g[12],
+                                         g[13], false);
+    vt::RowIter it = vt::row_iter(c, m0);
+    int32_t an, ah, aw;
+    vt::row_step_digits(c, down != 0, an, ah, aw);
+    uint64_t bad = 0;
+    for (uint32_t i = 0; i <= steps; ++i) {
+        const int64_t m = (int64_t)m0 + (down ? -1 : 1) * (int64_t)vt::kRowStep * i;
+        const vt::RowPos got = vt::row_pos(c, it);
+        if (m < 0 || m >= (int64_t)c.rows) bad += got.h0 != vt::kNowhere;
+        else {
+            const vt::RowPos want = vt::conv_row(c, (uint32_t)m);
+            bad += got.h0 != want.h0 || got.w0 != want.w0 || got.base != want.base || got.rem != want.rem;
+        }
+        vt::row_advance(c, it, an, ah, aw);
+    }
+    return bad;
+}
+
 // One stride phase of the input gradient, planned and indexed as the library does it: the phase's
 // axes go to info[0..13] (q0, count, k0, kstep, taps, pad, dil for h, then for w) and
 // offsets[m * cols + kc] = element of dY that the phase's GEMM reads at (row m, column kc), or -1.

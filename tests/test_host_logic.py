@@ -241,6 +241,65 @@ def test_input_gradient_index_arithmetic_on_host(harith):
             assert np.array_equal(out, want), (geo, row0, col0)
 
 
+def test_integer_only_index_split_on_host(harith):
+    """The multiply-high form of x / d (used where a whole wave shares the filter position): exact
+    against numpy for random and extreme (x, d), and the loader's offsets are the same with either
+    form for every tap of forward and input-gradient geometries (channel counts that are multiples
+    of 16 among them: the only ones the kernels use it for)."""
+    g = np.random.default_rng(20240309)
+    x = np.concatenate([g.integers(0, 1 << 32, 200000, dtype=np.uint64), [0, 1, (1 << 32) - 1, (1 << 32) - 2, 1 << 31]]).astype(np.uint32)
+    d = np.concatenate([g.integers(1, 1 << 32, 100000, dtype=np.uint64), g.integers(1, 5000, 100000, dtype=np.uint64),
+                        [1, 1, (1 << 32) - 1, 1, 3]]).astype(np.uint32)
+    q, r = np.empty_like(x), np.empty_like(x)
+    u32 = C.POINTER(C.c_uint32)
+    harith.h_divmod_magic(x.ctypes.data_as(u32), d.ctypes.data_as(u32), C.c_uint64(x.size), q.ctypes.data_as(u32), r.ctypes.data_as(u32))
+    assert np.array_equal(q, x // d) and np.array_equal(r, x % d)
+    for dv in (1, 2, 3, 7, 16, 48, 147, 65535, 65536, (1 << 31) + 1):                 # every x near multiples of d
+        k = np.arange(0, ((1 << 32) - 1) // dv + 1, max(1, (1 << 32) // dv // 50000), dtype=np.uint64) * dv
+        xs = np.unique(np.clip(np.concatenate([k, k + dv - 1, k[k > 0] - 1]), 0, (1 << 32) - 1)).astype(np.uint32)
+        ds = np.full_like(xs, dv)
+        q, r = np.empty_like(xs), np.empty_like(xs)
+        harith.h_divmod_magic(xs.ctypes.data_as(u32), ds.ctypes.data_as(u32), C.c_uint64(xs.size), q.ctypes.data_as(u32), r.ctypes.data_as(u32))
+        assert np.array_equal(q, xs // ds) and np.array_equal(r, xs % ds), dv
+    harith.h_tap_split_mismatches.restype = C.c_uint64
+    geoms = [(2, 9, 11, 16, 3, 3, 1, 1, 1, 1, 1, 1), (1, 12, 10, 32, 7, 7, 2, 2, 3, 3, 1, 1), (3, 8, 7, 48, 1, 1, 2, 2, 0, 0, 1, 1),
+             (1, 10, 13, 3, 3, 2, 2, 1, 1, 0, 1, 2), (1, 9, 9, 64, 3, 3, 1, 1, 2, 2, 2, 2), (1, 23, 17, 80, 5, 3, 3, 2, 2, 1, 2, 3),
+             (64, 56, 56, 128, 3, 3, 2, 2, 1, 1, 1, 1), (64, 14, 14, 256, 3, 3, 1, 1, 1, 1, 1, 1), (64, 7, 7, 512, 3, 3, 1, 1, 1, 1, 1, 1)]
+    for geo in geoms:
+        N, H, W, Cc, KH, KW, sh, sw, ph, pw, dh, dw = geo
+        Ho = (H + 2 * ph - dh * (KH - 1) - 1) // sh + 1
+        Wo = (W + 2 * pw - dw * (KW - 1) - 1) // sw + 1
+        arr = np.array(list(geo) + [Ho, Wo], np.int64)
+        for dgrad in (0, 1):
+            rows = N * H * W if dgrad else N * Ho * Wo
+            for row0 in (0, max(rows - 20, 0)):
+                bad = harith.h_tap_split_mismatches(arr.ctypes.data_as(C.POINTER(C.c_int64)), C.c_int(dgrad), C.c_uint32(row0), C.c_uint32(24))
+                assert bad == 0, (geo, dgrad, row0)
+
+
+def test_weight_gradient_row_walk_on_host(harith):
+    """Rows of the image matrix walked 16 at a time, up and down, against the direct split of the row
+    index: outputs narrower and shorter than the step (several carries' worth in one digit), one
+    output position per image, walks that run off either end of the matrix."""
+    harith.h_row_walk_mismatches.restype = C.c_uint64
+    geoms = [(2, 9, 11, 3, 3, 3, 1, 1, 1, 1, 1, 1), (40, 12, 10, 2, 7, 7, 2, 2, 3, 3, 1, 1), (70, 8, 7, 4, 1, 1, 2, 2, 0, 0, 1, 1),
+             (9, 10, 13, 3, 3, 2, 2, 1, 1, 0, 1, 2), (300, 3, 3, 2, 3, 3, 1, 1, 0, 0, 1, 1), (50, 1, 40, 2, 1, 3, 1, 1, 0, 1, 1, 1),
+             (50, 40, 1, 2, 3, 1, 1, 1, 1, 0, 1, 1), (64, 56, 56, 128, 3, 3, 2, 2, 1, 1, 1, 1), (64, 7, 7, 512, 3, 3, 1, 1, 1, 1, 1, 1),
+             (64, 224, 224, 3, 7, 7, 2, 2, 3, 3, 1, 1), (4, 16, 16, 2, 1, 1, 1, 1, 0, 0, 1, 1), (3, 17, 15, 2, 2, 2, 1, 1, 0, 0, 1, 1)]
+    for geo in geoms:
+        N, H, W, Cc, KH, KW, sh, sw, ph, pw, dh, dw = geo
+        Ho = (H + 2 * ph - dh * (KH - 1) - 1) // sh + 1
+        Wo = (W + 2 * pw - dw * (KW - 1) - 1) // sw + 1
+        rows = N * Ho * Wo
+        arr = np.array(list(geo) + [Ho, Wo], np.int64)
+        ptr = arr.ctypes.data_as(C.POINTER(C.c_int64))
+        steps = min(rows // 16 + 6, 3000)
+        for m0 in (0, 5, 15, Wo, Ho * Wo - 1):
+            assert harith.h_row_walk_mismatches(ptr, C.c_uint32(m0), C.c_uint32(steps), C.c_int(0)) == 0, (geo, m0, "up")
+        for m0 in (rows - 1, rows - 16, rows + 13, max(rows - Wo - 3, 0), min(rows - 1, 16 * 2000 + 7)):
+            assert harith.h_row_walk_mismatches(ptr, C.c_uint32(m0), C.c_uint32(steps), C.c_int(1)) == 0, (geo, m0, "down")
+
+
 def test_input_gradient_stride_phases_on_host(harith):
     """The split of a strided layer's input gradient into one stride-1 problem per phase: the phases
     partition the input positions and the filter taps, and every (row, column) of a phase's GEMM reads
