@@ -434,7 +434,7 @@ int vto_elementwise_f64(int op, const double *a, const double *b, uint64_t n, do
 int vto_layernorm_f64(const double *x, int64_t rows, int64_t cols, const double *gamma, const double *beta,
                       double eps, double *y, int order)
 {
-    if (rows < 0 || cols < 0 || order < 0 || order > 2 || (rows * cols && (!x || !y))) return VTO_ERR_INVALID_ARG;
+    if (rows < 0 || cols < 0 || order < 0 || order > 2 || (rows > 0 && cols > 0 && (!x || !y))) return VTO_ERR_INVALID_ARG;
     for (int64_t r = 0; r < rows; ++r) {
         const double *xr = x + r * cols;
         double *yr = y + r * cols;
@@ -470,7 +470,7 @@ int vto_layernorm_f64(const double *x, int64_t rows, int64_t cols, const double 
 int vto_batchnorm_f64(const double *x, int64_t rows, int64_t cols, const double *gamma, const double *beta,
                       double eps, int relu, double *y, int order)
 {
-    if (rows < 0 || cols < 0 || order < 0 || order > 2 || (rows * cols && (!x || !y))) return VTO_ERR_INVALID_ARG;
+    if (rows < 0 || cols < 0 || order < 0 || order > 2 || (rows > 0 && cols > 0 && (!x || !y))) return VTO_ERR_INVALID_ARG;
     for (int64_t c = 0; c < cols; ++c) {
         long double meanl = 0.0L, rstdl = 0.0L;
         double mean = 0.0, rstd = 0.0;
@@ -509,7 +509,7 @@ int vto_batchnorm_f64(const double *x, int64_t rows, int64_t cols, const double 
 int vto_softmax_f64(const double *x, int64_t rows, int64_t cols, double scale, int64_t causal_period,
                     double *y, int order)
 {
-    if (rows < 0 || cols < 0 || causal_period < 0 || order < 0 || order > 2 || (rows * cols && (!x || !y)))
+    if (rows < 0 || cols < 0 || causal_period < 0 || order < 0 || order > 2 || (rows > 0 && cols > 0 && (!x || !y)))
         return VTO_ERR_INVALID_ARG;
     for (int64_t r = 0; r < rows; ++r) {
         const double *xr = x + r * cols;
