@@ -171,6 +171,10 @@ hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, con
     if (total > 0x7FFFFFFFull) return hipErrorInvalidValue;
     p.tiles_per_split = (uint32_t)per_split;
     p.total_blocks = (uint32_t)total;
+    p.m_tiles_per_split = magic_of(p.tiles_per_split);
+    p.m_per_batch = magic_of(p.tilesM * p.tilesN);
+    p.m_width = magic_of(8u * p.tilesN);
+    p.m_batch_inner = magic_of(p.batch_inner);
     p.vecA = ((uintptr_t)g.A % 16 == 0) && (g.lda % 2 == 0) && (g.strideA % 2 == 0) && (g.strideA2 % 2 == 0);
     p.vecB = ((uintptr_t)g.B % 16 == 0) && (g.ldb % 2 == 0) && (g.strideB % 2 == 0) && (g.strideB2 % 2 == 0);
     const bool kcb = g.transB != 0;

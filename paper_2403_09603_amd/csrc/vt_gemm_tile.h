@@ -51,6 +51,7 @@ struct GemmParams {
     uint32_t batch_inner;                       // matrix b uses group b / batch_inner, member b % batch_inner
     double alpha;
     uint32_t thr, wpr, tilesM, tilesN, tiles_per_split, total_blocks;
+    uint32_t m_tiles_per_split, m_per_batch, m_width, m_batch_inner;   // divmod_magic multipliers of the tile mapping's divisors
     int variant, vecA, vecB, splits, kt_per_split, raw;
 };
 
@@ -214,19 +215,22 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
         const uint32_t i = blockIdx.x, q = p.total_blocks / 8u, r = p.total_blocks % 8u, xcd = i % 8u;
         pid = xcd * q + (xcd < r ? xcd : r) + i / 8u;
     }
-    const uint32_t split = pid / p.tiles_per_split;
-    pid -= split * p.tiles_per_split;
+    // (the divisors are run-time values: multiply-high by reciprocals from the host keeps these
+    // splits on the scalar unit; the compiler's own division sequence runs on the vector unit)
+    uint32_t split, b, pin, band, inband, b_out, b_in;
+    divmod_magic(pid, p.tiles_per_split, p.m_tiles_per_split, split, pid);
     const uint32_t per_batch = p.tilesM * p.tilesN;
-    const uint32_t b = pid / per_batch;
-    const uint32_t pin = pid - b * per_batch;
+    divmod_magic(pid, per_batch, p.m_per_batch, b, pin);
     const uint32_t GM = 8, width = GM * p.tilesN;
-    const uint32_t first_m = (pin / width) * GM;
+    divmod_magic(pin, width, p.m_width, band, inband);
+    const uint32_t first_m = band * GM;
     const uint32_t gsz = p.tilesM - first_m < GM ? p.tilesM - first_m : GM;
-    const uint32_t tm_ = first_m + (pin % width) % gsz;
-    const uint32_t tn_ = (pin % width) / gsz;
+    uint32_t tm_, tn_;
+    if (gsz == GM) { tm_ = first_m + (inband & (GM - 1)); tn_ = inband / GM; }
+    else { tm_ = first_m + inband % gsz; tn_ = inband / gsz; }       // the last, shorter band
     const int64_t bm = (int64_t)tm_ * BM, bn = (int64_t)tn_ * BN;
 
-    const uint32_t b_out = b / p.batch_inner, b_in = b - b_out * p.batch_inner;
+    divmod_magic(b, p.batch_inner, p.m_batch_inner, b_out, b_in);
     const double *A = p.A + (int64_t)b_out * p.strideA2 + (int64_t)b_in * p.strideA;
     const double *B = p.B + (int64_t)b_out * p.strideB2 + (int64_t)b_in * p.strideB;
 
