@@ -475,7 +475,8 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
                         c[j] = p.alpha * acc[i][j][r] + bias_f[j];
                         const FastLogged f = decide_fast_window(c[j], win0, win1);
                         yb[j] = __float_as_uint(f.y);
-                        lg[j] = __ballot(f.logged);
+                        // (the compare's lane mask itself: a ballot of the stored flag goes through a register)
+                        lg[j] = __builtin_amdgcn_uicmp(((uint32_t)__double_as_longlong(c[j]) & kMask29) - win0, win1, 36 /* unsigned < */);
                         dr[j] = __ballot(f.up) & lg[j];
                         slow[j] = __ballot(f.slow);
                         any_slow |= slow[j];
