@@ -448,8 +448,10 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
     // a row group are transposed into plane words with scalar pack operations, and the rare
     // values that need the integer rounding path are handled once per group of four.
     if (bm + BM <= p.M && bn + BN <= p.N && p.ldc < (1 << 26) && p.N < (1 << 25)) {
-        auto full = [&](auto has64_tag) {
-            constexpr bool HAS64 = decltype(has64_tag)::value;
+        // PLAIN: alpha = 1 and no bias (every convolution): the product and the sum would return the
+        // accumulator bit for bit, and each vector instruction here is paid in MFMA time
+        auto full = [&](auto has64_tag, auto plain_tag) {
+            constexpr bool HAS64 = decltype(has64_tag)::value, PLAIN = decltype(plain_tag)::value;
             const uint32_t win0 = thr_window_base(p.thr), win1 = thr_window_size(p.thr);
             char *c32_row = (char *)(p.C32 + (int64_t)b * p.strideC + row0 * p.ldc + col0);      // uniform, row 4 r of block i
             char *c64_row = HAS64 ? (char *)(p.C64 + ((int64_t)b * p.M + row0) * p.N + col0) : nullptr;
@@ -472,7 +474,7 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
                     uint64_t lg[4], dr[4], slow[4], any_slow = 0;
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        c[j] = p.alpha * acc[i][j][r] + bias_f[j];
+                        c[j] = PLAIN ? acc[i][j][r] : p.alpha * acc[i][j][r] + bias_f[j];
                         const FastLogged f = decide_fast_window(c[j], win0, win1);
                         yb[j] = __float_as_uint(f.y);
                         // (the compare's lane mask itself: a ballot of the stored flag goes through a register)
@@ -518,8 +520,9 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
                 wd_blk += (uint64_t)p.wpr * 128u;
             }
         };
-        if (p.C64) full(std::true_type{});
-        else full(std::false_type{});
+        const bool plain = p.alpha == 1.0 && !p.bias;
+        if (p.C64) { if (plain) full(std::true_type{}, std::true_type{}); else full(std::true_type{}, std::false_type{}); }
+        else { if (plain) full(std::false_type{}, std::true_type{}); else full(std::false_type{}, std::false_type{}); }
         return;
     }
     // edge tiles: every access guarded
