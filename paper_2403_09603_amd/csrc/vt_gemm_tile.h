@@ -480,7 +480,11 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
                         // (the compare's lane mask itself: a ballot of the stored flag goes through a register)
                         lg[j] = __builtin_amdgcn_uicmp(((uint32_t)__double_as_longlong(c[j]) & kMask29) - win0, win1, 36 /* unsigned < */);
                         dr[j] = __ballot(f.up) & lg[j];
-                        slow[j] = __ballot(f.slow);
+                        // outside the FP32-normal range (exponent field below 897 or from 1151 up, NaN):
+                        // two compares on |c| whose lane masks are the result
+                        const double ac = __builtin_fabs(c[j]);
+                        slow[j] = __builtin_amdgcn_fcmp(ac, 0x1p-126, 12 /* < or unordered */) |
+                                  __builtin_amdgcn_fcmp(ac, 0x1p128, 11 /* >= or unordered */);
                         any_slow |= slow[j];
                     }
                     if (__builtin_expect(any_slow != 0, 0)) {          // NaN, Inf, zero, tiny or huge values
