@@ -122,6 +122,10 @@ struct FastLogged {
 
 static __host__ __device__ __forceinline__ uint32_t thr_window_base(uint32_t thr) { return kHalf - thr + 1u; }
 static __host__ __device__ __forceinline__ uint32_t thr_window_size(uint32_t thr) { return thr ? 2u * thr - 1u : 0u; }
+// The same test in one add-and-shift and one compare on the whole low word `lo` of the value:
+// window_key(lo, 0 - base) < size << 3.  The shift by 3 drops the same top bits as the 29-bit mask,
+// and dropped bits below the window wrap to 2^29 - base + r, which is >= size for every thr <= 2^28.
+static __host__ __device__ __forceinline__ uint32_t window_key(uint32_t lo, uint32_t neg_base) { return (lo + neg_base) << 3; }
 
 __device__ __forceinline__ FastLogged decide_fast_window(double x, uint32_t c0, uint32_t c1)
 {

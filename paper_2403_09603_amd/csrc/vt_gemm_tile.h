@@ -453,6 +453,7 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
         auto full = [&](auto has64_tag, auto plain_tag) {
             constexpr bool HAS64 = decltype(has64_tag)::value, PLAIN = decltype(plain_tag)::value;
             const uint32_t win0 = thr_window_base(p.thr), win1 = thr_window_size(p.thr);
+            const uint32_t nwin0 = 0u - win0, win1s = win1 << 3;
             char *c32_row = (char *)(p.C32 + (int64_t)b * p.strideC + row0 * p.ldc + col0);      // uniform, row 4 r of block i
             char *c64_row = HAS64 ? (char *)(p.C64 + ((int64_t)b * p.M + row0) * p.N + col0) : nullptr;
             const uint32_t step32 = (uint32_t)p.ldc * 16u, step64 = (uint32_t)p.N * 32u;         // four rows further
@@ -478,7 +479,7 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
                         const FastLogged f = decide_fast_window(c[j], win0, win1);
                         yb[j] = __float_as_uint(f.y);
                         // (the compare's lane mask itself: a ballot of the stored flag goes through a register)
-                        lg[j] = __builtin_amdgcn_uicmp(((uint32_t)__double_as_longlong(c[j]) & kMask29) - win0, win1, 36 /* unsigned < */);
+                        lg[j] = __builtin_amdgcn_uicmp(window_key((uint32_t)__double_as_longlong(c[j]), nwin0), win1s, 36 /* unsigned < */);
                         dr[j] = __ballot(f.up) & lg[j];
                         // outside the FP32-normal range (exponent field below 897 or from 1151 up, NaN):
                         // two compares on |c| whose lane masks are the result

@@ -146,3 +146,10 @@ extern "C" void h_window_test(const uint32_t *r, uint64_t n, uint32_t thr, uint8
     const uint32_t c0 = vt::thr_window_base(thr), c1 = vt::thr_window_size(thr);
     for (uint64_t i = 0; i < n; ++i) logged[i] = (uint8_t)(((r[i] & vt::kMask29) - c0) < c1);
 }
+
+// and its shifted form on whole low words (any upper three bits)
+extern "C" void h_window_key_test(const uint32_t *lo, uint64_t n, uint32_t thr, uint8_t *logged)
+{
+    const uint32_t nbase = 0u - vt::thr_window_base(thr), size_s = vt::thr_window_size(thr) << 3;
+    for (uint64_t i = 0; i < n; ++i) logged[i] = (uint8_t)(vt::window_key(lo[i], nbase) < size_s);
+}

@@ -481,6 +481,11 @@ def test_threshold_window_form_equals_the_distance_test(harith):
         harith.h_window_test(_u32p(r), C.c_uint64(r.size), C.c_uint32(thr), out.ctypes.data_as(C.POINTER(C.c_uint8)))
         expect = np.abs(r.astype(np.int64) - half) < thr
         assert np.array_equal(out.astype(bool), expect), thr
+        # the shifted form takes whole low words: the same dropped bits under every pattern of the upper three
+        for top in (0, 1, 5, 7):
+            lo = (r | np.uint32(top << 29)).astype(np.uint32)
+            harith.h_window_key_test(_u32p(lo), C.c_uint64(lo.size), C.c_uint32(thr), out.ctypes.data_as(C.POINTER(C.c_uint8)))
+            assert np.array_equal(out.astype(bool), expect), (thr, top)
 
 
 def test_gemm_plan_is_a_pure_host_function_of_the_shape(hiplib):
