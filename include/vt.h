@@ -73,6 +73,7 @@ extern "C" {
 #define VT_ERR_WORKSPACE 2     /* ws is NULL or smaller than vt_workspace_bytes() */
 #define VT_ERR_HIP 3           /* a HIP call or kernel launch failed */
 #define VT_ERR_UNSUPPORTED 4   /* valid request this build has no kernel for */
+#define VT_ERR_STATIC_LIMIT 5  /* vt_round_log_static: n beyond VT_ROUND_LOG_STATIC_MAX_N */
 
 /* Operation selector for vt_workspace_bytes(). */
 #define VT_OP_ROUND_LOG 0      /* element count n = M * N * batch, K ignored */
@@ -111,6 +112,27 @@ typedef struct vt_log {
  */
 int vt_round_log(const double *x, uint64_t n, double tau_ulp, float *y, const vt_log *log,
                  void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * vt_round_log for callers that cannot allocate device memory and have no workspace to pass: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * outputs and errors as vt_round_log, minus `ws`: the kernels' scratch (the status words of the
+ * single-pass kernel, or the counters of the packed-log kernel) lives in a device array inside the
+ * library, 1 MiB + 16 KiB per GPU, held until the process ends.  The call allocates and frees nothing.
+ *   n        at most VT_ROUND_LOG_STATIC_MAX_N (VT_ERR_STATIC_LIMIT above it; nothing is enqueued)
+ *   x, y     with the index-list log (log->dense NULL) x must be 16-byte and y 8-byte aligned
+ *            (VT_ERR_UNSUPPORTED otherwise: the fallback for other alignments needs n / 4 bytes of
+ *            scratch); the packed ternary log takes any 8-byte / 4-byte aligned pair
+ *   The GPU that is current at the call must be the one `hip_stream` and the buffers belong to; the
+ *   first call on a GPU looks the array's address up once (make that call outside stream capture).
+ *   Every call on one GPU shares that GPU's array: calls that may overlap in time there (two streams,
+ *   two host threads) race on it and give unspecified logs -- serialise them, or use vt_round_log
+ *   with workspaces of the caller's own.  The kernels clear what they use, so calls made one after
+ *   the other need nothing in between.
+ */
+#define VT_ROUND_LOG_STATIC_MAX_N (1ull << 30)
+int vt_round_log_static(const double *x, uint64_t n, double tau_ulp, float *y, const vt_log *log,
+                        void *hip_stream);
 
 /*
  * Auditor side (primitive "rev"; Algorithm "audit": c <- read(F); output_i <- rev(output_i, b_r, c)).

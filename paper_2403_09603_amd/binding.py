@@ -23,6 +23,7 @@ VT_LAYER_ADD, VT_LAYER_RELU, VT_LAYER_GELU_TANH, VT_LAYER_GELU_ERF, VT_LAYER_NOR
 VT_LAYER_BATCHNORM, VT_LAYER_BATCHNORM_RELU = 6, 7
 VT_OP_SHA256_TREE, VT_OP_MERKLE_ROOT = 6, 7
 VT_OP_CONV_DGRAD_ROUND_LOG, VT_OP_CONV_DGRAD_ROUND_LOG_BR = 8, 9
+VT_ROUND_LOG_STATIC_MAX_N = 1 << 30
 
 
 class VtError(RuntimeError):
@@ -63,6 +64,8 @@ def load_library():
     vp, i64, u64, dbl, cint = C.c_void_p, C.c_int64, C.c_uint64, C.c_double, C.c_int
     L.vt_round_log.restype = cint
     L.vt_round_log.argtypes = [vp, u64, dbl, vp, C.POINTER(_VtLog), vp, C.c_size_t, vp]
+    L.vt_round_log_static.restype = cint
+    L.vt_round_log_static.argtypes = [vp, u64, dbl, vp, C.POINTER(_VtLog), vp]
     L.vt_round_replay.restype = cint
     L.vt_round_replay.argtypes = [vp, u64, vp, vp, u64, vp, vp, C.c_size_t, vp]
     L.vt_round_replay_dense.restype = cint
@@ -188,6 +191,18 @@ def vt_round_log(x: torch.Tensor, tau_ulp: float, y: torch.Tensor, log: Log, ws:
     _check(load_library().vt_round_log(_ptr(x, torch.float64), n, float(tau_ulp), _ptr(y, torch.float32),
                                        C.byref(clog), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)),
            "vt_round_log")
+
+
+def vt_round_log_static(x: torch.Tensor, tau_ulp: float, y: torch.Tensor, log: Log, stream=None):
+    """vt_round_log with the library's own static scratch instead of a workspace (allocates nothing)."""
+    n = x.numel()
+    if y.numel() != n:
+        raise VtError("y must have as many elements as x")
+    if log.dense is not None and log.dense.numel() < (n + 4) // 5:
+        raise VtError("dense log is smaller than ceil(n/5) bytes")
+    clog = log._c()
+    _check(load_library().vt_round_log_static(_ptr(x, torch.float64), n, float(tau_ulp), _ptr(y, torch.float32),
+                                              C.byref(clog), _stream(stream)), "vt_round_log_static")
 
 
 def vt_round_replay(x: torch.Tensor, idx: torch.Tensor, dir: torch.Tensor, count: int, y: torch.Tensor,

@@ -3,9 +3,34 @@
 #include "vt_conv_phases.h"
 #include "vt_kernels.h"
 
+#include <atomic>
 #include <cmath>
 
+// Scratch of vt_round_log_static: the status words of the one-pass kernel (8 bytes per tile of 8192
+// outputs, then its error words) or the 256 spread counters of the packed-log kernel.  One copy per
+// GPU, held until the process ends; in host code the name is only a handle for hipGetSymbolAddress.
+#define VT_STATIC_SCRATCH_BYTES ((VT_ROUND_LOG_STATIC_MAX_N / 8192) * 8 + 16384)
+static __device__ __align__(256) unsigned char scratch[VT_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+// device address of `scratch` on each GPU (every GPU holds its own copy at its own address),
+// resolved on the first call made with that GPU current
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+int static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return VT_ERR_HIP;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return VT_ERR_HIP;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);     // (a racing first call resolves the same address)
+    }
+    *out = p;
+    return VT_OK;
+}
 
 // Optional instrumentation (vt_set_kernel_events): events recorded around the main kernel.
 hipEvent_t g_ev_begin = nullptr, g_ev_end = nullptr;
@@ -282,6 +307,7 @@ const char *vt_strerror(int code)
     case VT_ERR_WORKSPACE: return "workspace missing or too small";
     case VT_ERR_HIP: return "HIP call or kernel launch failed";
     case VT_ERR_UNSUPPORTED: return "unsupported request";
+    case VT_ERR_STATIC_LIMIT: return "size beyond the limit of the library's static scratch";
     default: return "unknown status";
     }
 }
@@ -349,6 +375,23 @@ int vt_round_log(const double *x, uint64_t n, double tau_ulp, float *y, const vt
     if (n && (!x || !y || !aligned(x, 8) || !aligned(y, 4))) return VT_ERR_INVALID_ARG;
     const size_t need = round_log_bytes(n);
     if (!ws || ws_bytes < need || !aligned(ws, 256)) return VT_ERR_WORKSPACE;
+    return round_log_flat(x, n, thr, y, log, ws, (hipStream_t)hip_stream, /*mark=*/true);
+}
+
+int vt_round_log_static(const double *x, uint64_t n, double tau_ulp, float *y, const vt_log *log, void *hip_stream)
+{
+    const uint32_t thr = vt_thr_from_tau(tau_ulp);
+    if (thr == 0xFFFFFFFFu || !log_ok(log)) return VT_ERR_INVALID_ARG;
+    if (n > VT_ROUND_LOG_STATIC_MAX_N) return VT_ERR_STATIC_LIMIT;
+    if (n && (!x || !y || !aligned(x, 8) || !aligned(y, 4))) return VT_ERR_INVALID_ARG;
+    // the sparse log's fallback for misaligned tensors needs bit-planes (n / 4 bytes): not held statically
+    if (!log->dense && !vt::onepass_usable(x, y)) return VT_ERR_UNSUPPORTED;
+    const size_t need = log->dense ? vt::dense_count_bytes() : vt::onepass_bytes(n);
+    if (need > (size_t)VT_STATIC_SCRATCH_BYTES) return VT_ERR_STATIC_LIMIT;
+    void *ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != VT_OK) return rc;
+    // (the kernels clear the words they use themselves, so the last call's contents do not matter)
     return round_log_flat(x, n, thr, y, log, ws, (hipStream_t)hip_stream, /*mark=*/true);
 }
 

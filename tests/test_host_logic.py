@@ -104,6 +104,25 @@ def test_argument_validation_happens_on_the_host(hiplib):
     assert hiplib.vt_strerror(INVALID).decode() == "invalid argument"
 
 
+def test_static_scratch_entry_point_validates_on_the_host(hiplib):
+    """vt_round_log_static refuses sizes beyond its static scratch, and bad arguments, before any GPU call."""
+    import paper_2403_09603_amd.binding as b
+    cnt = (C.c_uint64 * 1)()
+    log = b._VtLog(None, None, 0, C.addressof(cnt), None, 0)
+    fake = C.c_void_p(0x1000)
+    f = hiplib.vt_round_log_static
+    LIMIT = 5
+    assert f(fake, (1 << 30) + 1, 0.1, fake, C.byref(log), None) == LIMIT
+    assert f(fake, (1 << 32) - 1, 0.1, fake, C.byref(log), None) == LIMIT
+    assert f(fake, 16, 0.75, fake, C.byref(log), None) == 1                     # tau
+    assert f(None, 16, 0.1, fake, C.byref(log), None) == 1
+    assert f(fake, 16, 0.1, fake, None, None) == 1
+    assert f(C.c_void_p(0x1008), 16, 0.1, fake, C.byref(log), None) == 4        # index-list log needs 16-byte x
+    assert f(fake, 16, 0.1, C.c_void_p(0x1004), C.byref(log), None) == 4        # ... and 8-byte y
+    assert b.VT_ROUND_LOG_STATIC_MAX_N == 1 << 30
+    assert "static scratch" in hiplib.vt_strerror(LIMIT).decode()
+
+
 @pytest.mark.parametrize("b", [32, 31, 29, 26, 16, 10])
 def test_kernel_arithmetic_for_other_rounding_amounts_on_host(harith, b):
     """decide_k / directed_k (rounding amounts below 32) against the oracle, on the host."""
