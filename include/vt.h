@@ -40,6 +40,13 @@
  *   count    number of logged outputs.  If it exceeds `cap`, only the first `cap` entries (in
  *            canonical order) are stored; all other outputs of the call are still complete,
  *            and the caller may re-run with a larger log.
+ *            One value is not a count: VT_COUNT_ABANDONED (all ones).  The single-pass kernel behind
+ *            vt_round_log, vt_layer_f64_round_log and the split-K / strided input-gradient routes
+ *            orders its tiles' entries through bounded waits inside one launch; if a wait runs out
+ *            (tens of seconds without progress: not seen in practice, it would take the GPU
+ *            withholding part of the launch that long) the kernel drains instead of hanging and
+ *            reports this value.  The FP32 outputs are then complete and correct, idx / dir are not
+ *            a valid log, and a larger `cap` does not help: run the call again.
  *   Unlogged outputs are the paper's code 1 ("ignore").
  *
  * The same decisions in the paper's own storage format (Method, "Reducing storage cost"): when
@@ -75,6 +82,9 @@ extern "C" {
 #define VT_ERR_UNSUPPORTED 4   /* valid request this build has no kernel for */
 #define VT_ERR_STATIC_LIMIT 5  /* vt_round_log_static: n beyond VT_ROUND_LOG_STATIC_MAX_N */
 
+/* *count after a call whose ordered-log pass gave up a bounded wait (see "The log" above). */
+#define VT_COUNT_ABANDONED UINT64_MAX
+
 /* Operation selector for vt_workspace_bytes(). */
 #define VT_OP_ROUND_LOG 0      /* element count n = M * N * batch, K ignored */
 #define VT_OP_ROUND_REPLAY 1   /* needs no workspace (returns 0) */
@@ -98,8 +108,8 @@ typedef struct vt_log {
 } vt_log;
 
 /*
- * Trainer side on a flat FP64 array (Algorithm "train", forward and backward loops:
- * log(output, b_r, tau, F) followed by output <- rnd_{b_r}(output), with b_r = 32;
+ * Trainer side on a flat FP64 array (Algorithm "train", forward and backward loops: the log
+ * step followed by the rounding step on each layer's output, here with b_r = 32;
  * Algorithm "log" for the decision).
  *   x        device, n FP64 values (8-byte aligned)
  *   y        device, n FP32 values: y[i] = rnd_32(x[i]), IEEE round-to-nearest-even; NaN inputs
@@ -135,7 +145,7 @@ int vt_round_log_static(const double *x, uint64_t n, double tau_ulp, float *y, c
                         void *hip_stream);
 
 /*
- * Auditor side (primitive "rev"; Algorithm "audit": c <- read(F); output_i <- rev(output_i, b_r, c)).
+ * Auditor side (primitive "rev"; Algorithm "audit", the read-and-reverse step after each layer).
  *   x            device, the auditor's own n FP64 results
  *   idx, dir     device, the trainer's log segment for this tensor (count entries, idx ascending)
  *   count        host value: entries in the segment
@@ -162,7 +172,7 @@ int vt_round_replay_br(const double *x, uint64_t n, const uint32_t *idx, const u
 int vt_round_replay_dense_br(const double *x, uint64_t n, const uint8_t *tlog, int b_r, float *y, void *hip_stream);
 
 /*
- * The layer itself, fused with the trainer hook (Algorithm "train": output <- l(input) in
+ * The layer itself, fused with the trainer hook (Algorithm "train": the layer evaluated in
  * b_tr = 64, then log and rnd; the Nondeterminism Challenge section names the tiling of
  * GEMMs as the source of divergence this controls).
  *
@@ -219,7 +229,7 @@ int vt_gemm_f64_round_log_nested(int transA, int transB, int64_t M, int64_t N, i
 
 /*
  * A convolution layer fused with the trainer hook (the paper's other example of an
- * "intermediate computation": Method, rounding after e.g. a convolution; Experiments, ResNet-50;
+ * intermediate computation: Method; Experiments, ResNet-50;
  * Algorithm "train" rounds and logs forward outputs and gradients alike).  The layer is the GEMM
  * above over the im2col matrix of the image, which is never materialised: the kernel forms the
  * addresses while it loads.  Cross-correlation with zero padding, channels last:
@@ -268,8 +278,8 @@ int vt_conv2d_f64_round_log(int mode, const vt_conv2d *d, int64_t Cout, const do
 int vt_conv2d_gemm_shape(const vt_conv2d *d, int64_t Cout, int mode, int64_t *M, int64_t *N, int64_t *K);
 
 /*
- * The element-wise and row-wise layers of a network, fused with the trainer hook (Method: rounding
- * "after every intermediate computation"; Table "thresholds" lists layer norm and batch norm beside
+ * The element-wise and row-wise layers of a network, fused with the trainer hook (Method: every intermediate
+ * computation is rounded; Table "thresholds" lists layer norm and batch norm beside
  * convolution and linear layers).  The layer is evaluated in FP64 from its FP64 inputs and every
  * output is rounded and logged in the same pass; the FP64 output is never stored (unless asked for).
  *

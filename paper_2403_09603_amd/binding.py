@@ -24,6 +24,7 @@ VT_LAYER_BATCHNORM, VT_LAYER_BATCHNORM_RELU = 6, 7
 VT_OP_SHA256_TREE, VT_OP_MERKLE_ROOT = 6, 7
 VT_OP_CONV_DGRAD_ROUND_LOG, VT_OP_CONV_DGRAD_ROUND_LOG_BR = 8, 9
 VT_ROUND_LOG_STATIC_MAX_N = 1 << 30
+VT_COUNT_ABANDONED = (1 << 64) - 1
 
 
 class VtError(RuntimeError):
@@ -146,12 +147,33 @@ class Log:
     dense: torch.Tensor | None = None   # uint8 [ceil(total/5)]: packed ternary log (then cap is 0)
     b_r: int = 32          # rounding amount the trainer call uses (10 .. 32)
 
+    def read_count(self, check_cap: bool = True) -> int:
+        """Synchronising read of the count word (see check_count)."""
+        return check_count(self.count.item(), self.cap if check_cap and self.dense is None else None)
+
     def _c(self) -> _VtLog:
         if self.dense is not None and (not self.dense.is_cuda or self.dense.dtype != torch.uint8):
             raise VtError("dense log must be a uint8 tensor on the GPU")
         return _VtLog(self.idx.data_ptr() if self.cap else None, self.dir.data_ptr() if self.cap else None,
                       self.cap, self.count.data_ptr(), self.dense.data_ptr() if self.dense is not None else None,
                       int(self.b_r))
+
+
+class VtLogAbandoned(VtError):
+    """*count == VT_COUNT_ABANDONED: the ordered-log pass gave up a bounded wait; outputs valid, log not."""
+
+
+def check_count(raw: int, cap: int | None = None) -> int:
+    """The value read from a log's count word as a number of entries.  Raises VtLogAbandoned for the
+    VT_COUNT_ABANDONED sentinel (run the call again) and VtError when the log overflowed `cap`
+    (run it again with a larger log)."""
+    raw = int(raw) & ((1 << 64) - 1)
+    if raw == VT_COUNT_ABANDONED:
+        raise VtLogAbandoned("ordered-log pass abandoned (count == VT_COUNT_ABANDONED): FP32 outputs are valid, "
+                             "idx/dir are not; repeat the call")
+    if cap is not None and raw > int(cap):
+        raise VtError(f"log overflow: {raw} entries for a capacity of {int(cap)}; repeat the call with a larger log")
+    return raw
 
 
 def alloc_log(cap: int, device="cuda") -> Log:

@@ -1,7 +1,14 @@
 // vt_device.h -- per-element device arithmetic of the round/log/replay path (gfx950).
 //
-// Everything here works on the binary64 bit pattern with integer instructions only, so the
-// result does not depend on the wave's rounding or denormal MODE bits.
+// The definitions (decide, decide_slow, decide_k, directed_*) work on the binary64 bit pattern with
+// integer instructions only.  The fast forms the kernels use for FP32-normal results (decide_fast,
+// decide_fast_window) take the FP32 value from the hardware conversion v_cvt_f32_f64 instead, which
+// equals rnd_32 only under round-to-nearest-even: they rely on the wave's MODE register holding the
+// default FP64 rounding mode.  HIP launches every kernel in that mode and no kernel of this library
+// changes it (no s_setreg, no directed-rounding intrinsics), which is what keeps the invariant; the
+// conversion is restricted to 2^-126 <= |x| < 2^128 so that the denormal MODE bits cannot matter, and
+// the distance and the direction always come from the dropped bits.  Both forms are held to each other
+// and to the CPU oracle bit for bit by the host and GPU tests.
 //
 // For a finite x with |x| >= 2^-126 the FP32 result keeps the top 23 mantissa bits; the 29
 // dropped bits r decide the rounding (Method, primitive rnd with b_r = 32):

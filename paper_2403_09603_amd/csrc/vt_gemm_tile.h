@@ -8,8 +8,9 @@
 // Tiling: a workgroup is 256 threads = 4 waves arranged WM x WN (2 x 2 or 4 x 1); a wave owns
 // TM x 4 MFMA tiles of 16 x 16, i.e. 16 TM rows by 64 columns, so that one wave always produces
 // whole 64-bit words of the decision planes.  Workgroup tiles: 128 x 128 (2x2, TM 4: the large
-// shape, 128 accumulator registers per lane), 64 x 128 (2x2, TM 2) and 64 x 64 (4x1, TM 1) for
-// narrow outputs, short K and problems with too few tiles to fill 256 CUs.
+// shape, 128 accumulator registers per lane, two workgroups per CU) and 64 x 64 (4x1, TM 1: four
+// workgroups per CU) for narrow outputs, short K and problems with too few large tiles to fill
+// 256 CUs; the host plan picks one per problem.
 // K step 16; operands are staged through LDS in k-major order ([k][m], [k][n]), double-buffered
 // against the global loads, and the next tile is written to LDS in the shadow of the last MFMA
 // group of the current one.
@@ -60,7 +61,7 @@ namespace {
 typedef double d4 __attribute__((ext_vector_type(4)));
 typedef double d2 __attribute__((ext_vector_type(2)));
 
-// LDS row pitch = tile width + 18 doubles.  A k-contiguous operand is transposed on its way into
+// LDS row pitch = tile width + 18 doubles (128 x 128 tile) or + 14 (64 x 64 tile).  A k-contiguous operand is transposed on its way into
 // LDS: the 32 lanes of a write pass hold 8 k rows x 4 columns, and with a pitch of 18 mod 32
 // doubles those land on 32 different bank pairs (a pitch of 16 mod 32 put all 8 k rows on one
 // pair: 8-way conflicts that kept the LDS pipe busy for about as long as the MFMAs).  Fragment

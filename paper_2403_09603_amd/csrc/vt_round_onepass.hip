@@ -21,7 +21,8 @@
 // their counts, which no tile waits for anything to do; tiles depend only on the scanner.
 // Every wait is bounded all the same: after kSpinLimit polls without progress (seconds) a
 // waiter sets the error word, which releases every other waiter too, so the grid always
-// drains; the host-visible result is then *count = UINT64_MAX.
+// drains; a tile that gives up writes no entries, and the host-visible result is then
+// *count = UINT64_MAX (VT_COUNT_ABANDONED: y complete, idx / dir invalid).
 #include "vt_device.h"
 #include "vt_kernels.h"
 #include "vt_source.h"
@@ -39,7 +40,10 @@ constexpr int kWaveChunk = 1024;     // contiguous outputs per wave: 8 rows of 1
 constexpr int kRows = 8;
 constexpr int kTile = kWaves * kWaveChunk;   // outputs per workgroup
 constexpr int kScanThreads = 256, kScanPer = 4;      // scanner: 1024 status words per round
-constexpr uint32_t kSpinLimit = 1u << 21;   // polls (each a few microseconds) before a waiter gives up
+constexpr uint32_t kSpinLimit = 1u << 21;   // polls (each a few microseconds) before a tile gives up waiting
+// The scanner waits for tiles to be dispatched at all, which other work on the GPU can delay: its
+// limit is longer (some tens of seconds of idle polling).
+constexpr uint32_t kScanIdleLimit = 1u << 24;
 
 constexpr uint64_t kCountFlag = 1ull << 62, kOffsetFlag = 2ull << 62, kValMask = (1ull << 62) - 1;
 
@@ -99,7 +103,7 @@ __device__ __forceinline__ void scanner(uint64_t *__restrict__ st, uint32_t tile
         if (R == 0) {                                      // nothing new yet
             ++idle_rounds;
             __syncthreads();
-            if (++idle > kSpinLimit) {                     // never expected: stop waiting, drain
+            if (++idle > kScanIdleLimit) {                 // never expected: stop waiting, drain
                 if (tid == 0) atomicOr(err, 1u);
                 force = true;
             }
@@ -251,10 +255,9 @@ __global__ __launch_bounds__(kThreads) void round_log_onepass_kernel(const Src x
         sv = st_load(st + tile);
         if ((sv >> 62) == 2) break;
         const bool failed = __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
-        if (failed || spins > kSpinLimit) {       // never expected: give up, do not hang
+        if (failed || spins > kSpinLimit) {       // never expected: give up, do not hang, write no entries
             if (lane == 0) atomicOr(err, 1u);
-            sv = 0;
-            break;
+            return;
         }
     }
     const uint64_t off = sv & kValMask;

@@ -104,6 +104,21 @@ def test_argument_validation_happens_on_the_host(hiplib):
     assert hiplib.vt_strerror(INVALID).decode() == "invalid argument"
 
 
+def test_abandoned_count_is_a_distinct_status():
+    """The all-ones count is reported as "pass abandoned", not as a log overflow (host logic only)."""
+    import paper_2403_09603_amd as vt
+    assert vt.check_count(0) == 0 and vt.check_count(17, cap=17) == 17
+    assert vt.check_count(-1 & ((1 << 64) - 1) - 1) == (1 << 64) - 2          # any other value is a count
+    with pytest.raises(vt.VtLogAbandoned):
+        vt.check_count(-1)                                                     # int64 view of the sentinel
+    with pytest.raises(vt.VtLogAbandoned):
+        vt.check_count(vt.VT_COUNT_ABANDONED, cap=5)
+    with pytest.raises(vt.VtError, match="overflow"):
+        vt.check_count(18, cap=17)
+    hdr = open(os.path.join(ROOT, "include", "vt.h")).read()
+    assert "VT_COUNT_ABANDONED UINT64_MAX" in hdr
+
+
 def test_static_scratch_entry_point_validates_on_the_host(hiplib):
     """vt_round_log_static refuses sizes beyond its static scratch, and bad arguments, before any GPU call."""
     import paper_2403_09603_amd.binding as b
