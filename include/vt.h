@@ -128,7 +128,7 @@ int vt_round_log(const double *x, uint64_t n, double tau_ulp, float *y, const vt
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
  * outputs and errors as vt_round_log, minus `ws`: the kernels' scratch (the status words of the
  * single-pass kernel, or the counters of the packed-log kernel) lives in a device array inside the
- * library, 1 MiB + 16 KiB per GPU, held until the process ends.  The call allocates and frees nothing.
+ * library, 2 MiB + 16 KiB per GPU, held until the process ends.  The call allocates and frees nothing.
  *   n        at most VT_ROUND_LOG_STATIC_MAX_N (VT_ERR_STATIC_LIMIT above it; nothing is enqueued)
  *   x, y     with the index-list log (log->dense NULL) x must be 16-byte and y 8-byte aligned
  *            (VT_ERR_UNSUPPORTED otherwise: the fallback for other alignments needs n / 4 bytes of

@@ -6,10 +6,10 @@
 #include <atomic>
 #include <cmath>
 
-// Scratch of vt_round_log_static: the status words of the one-pass kernel (8 bytes per tile of 8192
+// Scratch of vt_round_log_static: the status words of the one-pass kernel (8 bytes per tile of 4096
 // outputs, then its error words) or the 256 spread counters of the packed-log kernel.  One copy per
 // GPU, held until the process ends; in host code the name is only a handle for hipGetSymbolAddress.
-#define VT_STATIC_SCRATCH_BYTES ((VT_ROUND_LOG_STATIC_MAX_N / 8192) * 8 + 16384)
+#define VT_STATIC_SCRATCH_BYTES ((VT_ROUND_LOG_STATIC_MAX_N / 4096) * 8 + 16384)
 static __device__ __align__(256) unsigned char scratch[VT_STATIC_SCRATCH_BYTES];
 
 namespace {
@@ -100,6 +100,12 @@ int round_log_flat(const double *x, uint64_t n, uint32_t thr, float *y, const vt
         return hip_status(e0);
     }
     const vt::LogOut lo{log->idx, log->dir, log->cap, log->count};
+    if (thr == 0 && n > 0 && vt::onepass_usable(x, y)) {      // nothing can be logged: round only, count 0
+        if (mark) mark_begin(s);
+        const hipError_t e0 = vt::launch_round_only(x, n, k, y, log->count, s);
+        if (mark) mark_end(s);
+        return hip_status(e0);
+    }
     if (vt::onepass_usable(x, y)) {         // one streaming pass; otherwise bit-planes + compaction
         if (mark) mark_begin(s);
         const hipError_t e1 = vt::launch_round_log_onepass(x, n, thr, k, y, ws, lo, s);

@@ -188,37 +188,22 @@ __device__ __forceinline__ int write_lane(uint32_t s, int ln, int v)
     return v;
 }
 
-// AM, the A operand: 0 = stored transposed (contiguous along m), 1 = row-major (contiguous along
-// k), 2 = implicit im2col of an image, rows x taps (convolution forward), 3 = its transpose,
-// taps x rows (convolution weight gradient), 4 = the input-gradient view of the output gradient,
-// input positions x (filter position, output channel).  KCB: B is stored transposed (contiguous along k).
-template <int AM, bool KCB, int WM, int TM>
-__global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmParams p)
+// Work item id (a workgroup id, or a position in a persistent workgroup's list) -> (split, batch
+// element, tile origin, operand bases).  Consecutive ids land on different XCDs (8 of them, each with
+// its own L2), so ids are first regrouped per XCD, then walked in bands of 8 row tiles so that
+// neighbours in time share A and B panels in that L2.  All wave-uniform: the divisors are run-time
+// values, and multiply-high by reciprocals from the host keeps these splits on the scalar unit (the
+// compiler's own division sequence runs on the vector unit).
+template <int BM, int BN>
+__device__ __forceinline__ void tile_of(const GemmParams &p, uint32_t id, uint32_t &split, uint32_t &b, int64_t &bm,
+                                        int64_t &bn, const double *&A, const double *&B)
 {
-    constexpr bool KCA = AM == 1 || AM == 2 || AM == 4;
-    constexpr bool GA = AM >= 2;
-    constexpr int WN = 4 / WM;
-    constexpr int BM = WM * 16 * TM, BN = WN * 64;
-    constexpr int PAD = TM == 1 ? kPadSmall : kPad;
-    constexpr int PA = BM + PAD, PB = BN + PAD;            // LDS pitches
-    constexpr int SA = BK * PA, SB = BK * PB;              // doubles per stage
-    __shared__ double lds[2 * SA + 2 * SB];                // A0 A1 B0 B1
-    double *const ldsA = lds, *const ldsB = lds + 2 * SA;
-    const int t = threadIdx.x, lane = t & 63;
-    const int wv = __builtin_amdgcn_readfirstlane(t >> 6);      // wave-uniform: keeps tile addresses in scalar registers
-    const int wm = wv / WN, wn = wv % WN;
-
-    // Workgroup -> (split, tile).  Consecutive workgroup ids land on different XCDs (8 of them,
-    // each with its own L2), so ids are first regrouped per XCD, then walked in bands of 8 row
-    // tiles so that neighbours in time share A and B panels in that L2.
     uint32_t pid;
     {
-        const uint32_t i = blockIdx.x, q = p.total_blocks / 8u, r = p.total_blocks % 8u, xcd = i % 8u;
-        pid = xcd * q + (xcd < r ? xcd : r) + i / 8u;
+        const uint32_t q = p.total_blocks / 8u, r = p.total_blocks % 8u, xcd = id % 8u;
+        pid = xcd * q + (xcd < r ? xcd : r) + id / 8u;
     }
-    // (the divisors are run-time values: multiply-high by reciprocals from the host keeps these
-    // splits on the scalar unit; the compiler's own division sequence runs on the vector unit)
-    uint32_t split, b, pin, band, inband, b_out, b_in;
+    uint32_t pin, band, inband, b_out, b_in;
     divmod_magic(pid, p.tiles_per_split, p.m_tiles_per_split, split, pid);
     const uint32_t per_batch = p.tilesM * p.tilesN;
     divmod_magic(pid, per_batch, p.m_per_batch, b, pin);
@@ -229,219 +214,21 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
     uint32_t tm_, tn_;
     if (gsz == GM) { tm_ = first_m + (inband & (GM - 1)); tn_ = inband / GM; }
     else { tm_ = first_m + inband % gsz; tn_ = inband / gsz; }       // the last, shorter band
-    const int64_t bm = (int64_t)tm_ * BM, bn = (int64_t)tn_ * BN;
-
+    bm = (int64_t)tm_ * BM;
+    bn = (int64_t)tn_ * BN;
     divmod_magic(b, p.batch_inner, p.m_batch_inner, b_out, b_in);
-    const double *A = p.A + (int64_t)b_out * p.strideA2 + (int64_t)b_in * p.strideA;
-    const double *B = p.B + (int64_t)b_out * p.strideB2 + (int64_t)b_in * p.strideB;
+    A = p.A + (int64_t)b_out * p.strideA2 + (int64_t)b_in * p.strideA;
+    B = p.B + (int64_t)b_out * p.strideB2 + (int64_t)b_in * p.strideB;
+}
 
-    d4 acc[TM][4];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = (d4){0.0, 0.0, 0.0, 0.0};
-
-    // this workgroup's k tiles: [kt0, kt1)
-    const int nkt_all = (int)((p.K + BK - 1) / BK);
-    const int kt0 = (int)split * p.kt_per_split;
-    const int kt1 = kt0 + p.kt_per_split < nkt_all ? kt0 + p.kt_per_split : nkt_all;
-    const int nkt = kt1 > kt0 ? kt1 - kt0 : 0;
-    // whole-tile operands take the unguarded loader (a uniform choice per k step)
-    // (the per-thread offsets of the unguarded loader are 32-bit: pitches up to 2^31 / 8 / 128)
-    const bool fastA = GA ? p.conv.vec != 0 : p.vecA && bm + BM <= p.M && p.lda < (1 << 21);
-    const bool fastB = p.vecB && bn + BN <= p.N && p.ldb < (1 << 21);
-    const char *baseA = (const char *)(A + (KCA ? bm * p.lda : bm));
-    const char *baseB = (const char *)(B + (KCB ? bn * p.ldb : bn));
-    uint32_t offA[BM / 32], offB[BN / 32];
-    tile_offsets<KCA, BM>(p.lda, offA);
-    tile_offsets<KCB, BN>(p.ldb, offB);
-    // Two register sets: tile it+2 is in flight from memory while tile it+1 (fetched one step
-    // earlier) goes to LDS and tile it is multiplied, so a fetch has two full steps to land.
-    // The loop exists twice: with unguarded loads only (every tile of this workgroup lies inside
-    // the operands; straight-line code, so the load counter waits are exact and the newest
-    // fetch stays in flight across the LDS stores), and with the guarded loader for edges.
-    d2 ra0[BM / 32], rb0[BN / 32], ra1[BM / 32], rb1[BN / 32];
-    // Implicit im2col: the part of the address that belongs to this thread for the whole loop --
-    // its rows of the image matrix (forward) or its pair of taps (weight gradient).
-    RowPos rowp[AM == 2 || AM == 4 ? BM / 32 : 1];
-    TapPos tap0{0, 0, 0, 0}, tap1{0, 0, 0, 0};
-    if constexpr (AM == 2) {
-#pragma unroll
-        for (int j = 0; j < BM / 32; ++j) rowp[j] = conv_row(p.conv, (uint32_t)bm + (t >> 3) + 32 * j);
-    }
-    if constexpr (AM == 4) {
-#pragma unroll
-        for (int j = 0; j < BM / 32; ++j) rowp[j] = dgrad_row(p.conv, (uint32_t)bm + (t >> 3) + 32 * j);
-    }
-    // (weight gradient: the rows run along k; each thread walks its BM / 32 rows a k step at a time,
-    // from the first tile it fetches, in the variant's direction)
-    // (the large tile has no registers left for the walk: it splits its row indices at every step)
-    constexpr bool WALK = AM == 3 && BM == 64;
-    RowIter rit[WALK ? BM / 32 : 1];
-    int32_t row_an = 0, row_ah = 0, row_aw = 0;
-    if constexpr (AM == 3) {
-        const uint32_t kc = (uint32_t)bm + (t % (BM / 2)) * 2;
-        tap0 = conv_tap(p.conv, kc);
-        tap1 = conv_tap(p.conv, kc + 1);
-    }
-    if constexpr (WALK) {
-        static_assert(BK == kRowStep, "the row walk advances one k step at a time");
-        const uint32_t kfirst = (uint32_t)(p.variant ? kt1 - 1 : kt0) * BK;
-#pragma unroll
-        for (int j = 0; j < BM / 32; ++j) rit[j] = row_iter(p.conv, kfirst + t / (BM / 2) + (512 / BM) * j);
-        row_step_digits(p.conv, p.variant != 0, row_an, row_ah, row_aw);
-    }
-    // UNI: the channel count is a multiple of 16, so the 16 taps of a k step are 16 channels of one
-    // filter position: (kh, kw) and the tap's offset are the same for the whole wave and are found
-    // with scalar integer operations; the lane's channel pair is already part of its rows' offsets.
-    auto gather_tile = [&](auto vec_tag, auto uni_tag, int64_t k0, d2 (&ra)[BM / 32]) {
-        constexpr bool VEC = decltype(vec_tag)::value, UNI = decltype(uni_tag)::value;
-        if constexpr (UNI && (AM == 2 || AM == 4)) {
-            const TapPos t0 = AM == 2 ? conv_tap<true>(p.conv, (uint32_t)k0) : dgrad_tap<true>(p.conv, (uint32_t)k0);
-#pragma unroll
-            for (int j = 0; j < BM / 32; ++j) ra[j] = conv_gather<true, AM == 4>(p.A, p.conv, rowp[j], t0, t0);
-        } else if constexpr (AM == 2) {
-            const uint32_t kc = (uint32_t)k0 + (t & 7) * 2;
-            const TapPos t0 = conv_tap(p.conv, kc);
-            const TapPos t1 = VEC ? t0 : conv_tap(p.conv, kc + 1);
-#pragma unroll
-            for (int j = 0; j < BM / 32; ++j) ra[j] = conv_gather<VEC>(p.A, p.conv, rowp[j], t0, t1);
-        } else if constexpr (AM == 3) {
-#pragma unroll
-            for (int j = 0; j < BM / 32; ++j) {
-                if constexpr (WALK) {
-                    // the tiles are fetched in order, one per call (a fetch repeated past the last
-                    // tile moves on to rows nobody multiplies): k0 is implied
-                    ra[j] = conv_gather<VEC>(p.A, p.conv, row_pos(p.conv, rit[j]), tap0, tap1);
-                    row_advance(p.conv, rit[j], row_an, row_ah, row_aw);
-                } else {
-                    const RowPos r = conv_row(p.conv, (uint32_t)k0 + t / (BM / 2) + (512 / BM) * j);
-                    ra[j] = conv_gather<VEC>(p.A, p.conv, r, tap0, tap1);
-                }
-            }
-        } else if constexpr (AM == 4) {
-            const uint32_t kc = (uint32_t)k0 + (t & 7) * 2;
-            const TapPos t0 = dgrad_tap(p.conv, kc);
-            const TapPos t1 = VEC ? t0 : dgrad_tap(p.conv, kc + 1);
-#pragma unroll
-            for (int j = 0; j < BM / 32; ++j) ra[j] = conv_gather<VEC, true>(p.A, p.conv, rowp[j], t0, t1);
-        }
-    };
-    auto main_loop = [&](auto fast_tag, auto uni_tag) {
-        constexpr bool FAST = decltype(fast_tag)::value;
-        auto fetch = [&](int it, d2 (&ra)[BM / 32], d2 (&rb)[BN / 32]) {   // `it`-th step in this variant's order
-            const int64_t k0 = (int64_t)(p.variant ? kt1 - 1 - it : kt0 + it) * BK;
-            if constexpr (GA) {
-                if constexpr (FAST) gather_tile(std::true_type{}, uni_tag, k0, ra);
-                else if (p.conv.vec) gather_tile(std::true_type{}, std::false_type{}, k0, ra);
-                else gather_tile(std::false_type{}, std::false_type{}, k0, ra);
-            } else if constexpr (FAST) {
-                load_tile_fast<KCA, BM>(baseA, p.lda, k0, offA, ra);
-            } else {
-                load_tile<KCA, BM>(A, p.lda, bm, k0, p.M, p.K, p.vecA, ra);
-            }
-            if constexpr (FAST) load_tile_fast<KCB, BN>(baseB, p.ldb, k0, offB, rb);
-            else load_tile<KCB, BN>(B, p.ldb, bn, k0, p.N, p.K, p.vecB, rb);
-        };
-        // one k step: multiply the tile in LDS stage `cur`; start the fetch of tile it+2 into (la, lb);
-        // move tile it+1 from (sa, sb) to the other stage in the shadow of the last MFMA group
-        auto step = [&](int it, int cur, d2 (&la)[BM / 32], d2 (&lb)[BN / 32], d2 (&sa)[BM / 32], d2 (&sb)[BN / 32]) {
-            // In the unguarded loop the fetch and the LDS store are unconditional (past the end
-            // they repeat the last tile and fill a stage nobody reads): with no branch around
-            // them the compiler's load-counter waits are exact.
-            if (FAST) fetch(it + 2 < nkt ? it + 2 : nkt - 1, la, lb);
-            else if (it + 2 < nkt) fetch(it + 2, la, lb);
-            const bool more = FAST || it + 1 < nkt;
-            const double *As = ldsA + cur * SA + wm * (16 * TM) + (lane & 15);
-            const double *Bs = ldsB + cur * SB + wn * 64 + (lane & 15);
-            // The narrow tiles have registers to spare: the fragments of group kk + 1 are requested
-            // before the MFMAs of group kk are issued, so an LDS round trip hides behind a whole
-            // group instead of behind its last instruction.  (The large tile has none to spare; there
-            // the compiler interleaves the reads as fragment registers fall free.)
-            constexpr bool PIPE = TM <= 2;
-            double a[PIPE ? 2 : 1][TM], bb[PIPE ? 2 : 1][4];
-            auto frags = [&](int kk, double (&fa)[TM], double (&fb)[4]) {
-                const int krow = kk * 4 + (lane >> 4);
-#pragma unroll
-                for (int i = 0; i < TM; ++i) fa[i] = As[krow * PA + i * 16];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) fb[j] = Bs[krow * PB + j * 16];
-            };
-            if (PIPE) frags(0, a[0], bb[0]);
-#pragma unroll
-            for (int kk = 0; kk < BK / 4; ++kk) {
-                const int cb = PIPE ? (kk & 1) : 0;
-                if (!PIPE) frags(kk, a[0], bb[0]);
-                else if (kk + 1 < BK / 4) {
-                    frags(kk + 1, a[cb ^ 1], bb[cb ^ 1]);
-                    __builtin_amdgcn_sched_barrier(0);         // keep the reads ahead of this group's MFMAs
-                }
-                if (kk == BK / 4 - 1) {
-                    // (the last group's fragments are already requested: LDS completes in order,
-                    // so the wave's MFMA stream has no gap before the barrier)
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (more) {
-                        store_tile<KCA, BM, PAD>(ldsA + (cur ^ 1) * SA, sa);
-                        store_tile<KCB, BN, PAD>(ldsB + (cur ^ 1) * SB, sb);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[cb][i], bb[cb][j], acc[i][j], 0, 0, 0);
-            }
-            __syncthreads();
-        };
-        if (nkt > 0) {
-            fetch(0, ra0, rb0);
-            store_tile<KCA, BM, PAD>(ldsA, ra0);
-            store_tile<KCB, BN, PAD>(ldsB, rb0);
-            if (nkt > 1) fetch(1, ra0, rb0);
-        }
-        __syncthreads();
-        // (the odd last step stands after the loop: an exit from the middle of the body would reach
-        // the loop's head with the first step's loads pending, and every wait in the body is placed
-        // for the worst of the paths into it)
-        int it = 0;
-        for (; it + 1 < nkt; it += 2) {
-            step(it, 0, ra1, rb1, ra0, rb0);                // tile it+1 sits in set 0, it+2 goes to set 1
-            step(it + 1, 1, ra0, rb0, ra1, rb1);
-        }
-        if (it < nkt) step(it, 0, ra1, rb1, ra0, rb0);
-    };
-    const bool fast = fastA && fastB && (int64_t)kt1 * BK <= p.K;
-    if ((AM == 2 || AM == 4) && fast && p.conv.uni) {
-#pragma unroll
-        for (int j = 0; j < BM / 32; ++j) rowp[j].base += (t & 7) * 2;
-        main_loop(std::true_type{}, std::true_type{});
-    } else if (fast) {
-        main_loop(std::true_type{}, std::false_type{});
-    } else {
-        main_loop(std::false_type{}, std::false_type{});
-    }
-
+// The fused trainer hook on one wave's accumulators (16 TM rows x 64 columns at (row0, col0) of batch
+// element b): alpha, bias, round to FP32, decide, store C32 (and the FP64 copy), decision bits to the
+// two bit-planes.
+template <int TM, int BM, int BN>
+__device__ __forceinline__ void tile_epilogue(const GemmParams &p, const d4 (&acc)[TM][4], uint32_t b, int64_t bm, int64_t bn,
+                                              int64_t row0, int64_t col0, int lane)
+{
     const int g = lane >> 4, c16 = lane & 15;
-    const int64_t row0 = bm + wm * (16 * TM), col0 = bn + wn * 64;
-
-    if (p.splits > 1 || p.raw) {
-        // ---- split-K (or a caller that rounds in a later pass): raw accumulators to this slice's slab; alpha, bias, rounding come later
-        double *P = p.partial + ((int64_t)split * p.batch + (int64_t)b) * p.M * p.N;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int64_t row = row0 + i * 16 + 4 * r + g;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int64_t col = col0 + j * 16 + c16;
-                    if (row < p.M && col < p.N) P[row * p.N + col] = acc[i][j][r];
-                }
-            }
-        return;
-    }
-
     // ---- epilogue: alpha, bias, round, decide, store, bit-planes -------------------------
     const uint64_t colword = (uint64_t)col0 >> 6;
     // Whole tile inside the matrix (and pitches that fit 32-bit lane offsets): no guards, every
@@ -580,6 +367,245 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
     }
 }
 
+// AM, the A operand: 0 = stored transposed (contiguous along m), 1 = row-major (contiguous along
+// k), 2 = implicit im2col of an image, rows x taps (convolution forward), 3 = its transpose,
+// taps x rows (convolution weight gradient), 4 = the input-gradient view of the output gradient,
+// input positions x (filter position, output channel).  KCB: B is stored transposed (contiguous along k).
+template <int AM, bool KCB, int WM, int TM>
+__global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmParams p)
+{
+    constexpr bool KCA = AM == 1 || AM == 2 || AM == 4;
+    constexpr bool GA = AM >= 2;
+    constexpr int WN = 4 / WM;
+    constexpr int BM = WM * 16 * TM, BN = WN * 64;
+    constexpr int PAD = TM == 1 ? kPadSmall : kPad;
+    constexpr int PA = BM + PAD, PB = BN + PAD;            // LDS pitches
+    constexpr int SA = BK * PA, SB = BK * PB;              // doubles per stage
+    __shared__ double lds[2 * SA + 2 * SB];                // A0 A1 B0 B1
+    double *const ldsA = lds, *const ldsB = lds + 2 * SA;
+    const int t = threadIdx.x, lane = t & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(t >> 6);      // wave-uniform: keeps tile addresses in scalar registers
+    const int wm = wv / WN, wn = wv % WN;
+
+    uint32_t split, b;
+    int64_t bm, bn;
+    const double *A, *B;
+    tile_of<BM, BN>(p, blockIdx.x, split, b, bm, bn, A, B);
+
+    d4 acc[TM][4];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = (d4){0.0, 0.0, 0.0, 0.0};
+
+    // this workgroup's k tiles: [kt0, kt1)
+    const int nkt_all = (int)((p.K + BK - 1) / BK);
+    const int kt0 = (int)split * p.kt_per_split;
+    const int kt1 = kt0 + p.kt_per_split < nkt_all ? kt0 + p.kt_per_split : nkt_all;
+    const int nkt = kt1 > kt0 ? kt1 - kt0 : 0;
+    // whole-tile operands take the unguarded loader (a uniform choice per k step)
+    // (the per-thread offsets of the unguarded loader are 32-bit: pitches up to 2^31 / 8 / 128)
+    const bool fastA = GA ? p.conv.vec != 0 : p.vecA && bm + BM <= p.M && p.lda < (1 << 21);
+    const bool fastB = p.vecB && bn + BN <= p.N && p.ldb < (1 << 21);
+    const char *baseA = (const char *)(A + (KCA ? bm * p.lda : bm));
+    const char *baseB = (const char *)(B + (KCB ? bn * p.ldb : bn));
+    uint32_t offA[BM / 32], offB[BN / 32];
+    tile_offsets<KCA, BM>(p.lda, offA);
+    tile_offsets<KCB, BN>(p.ldb, offB);
+    // Two register sets: tile it+2 is in flight from memory while tile it+1 (fetched one step
+    // earlier) goes to LDS and tile it is multiplied, so a fetch has two full steps to land.
+    // The loop exists twice: with unguarded loads only (every tile of this workgroup lies inside
+    // the operands; straight-line code, so the load counter waits are exact and the newest
+    // fetch stays in flight across the LDS stores), and with the guarded loader for edges.
+    d2 ra0[BM / 32], rb0[BN / 32], ra1[BM / 32], rb1[BN / 32];
+    // Implicit im2col: the part of the address that belongs to this thread for the whole loop --
+    // its rows of the image matrix (forward) or its pair of taps (weight gradient).
+    RowPos rowp[AM == 2 || AM == 4 ? BM / 32 : 1];
+    TapPos tap0{0, 0, 0, 0}, tap1{0, 0, 0, 0};
+    if constexpr (AM == 2) {
+#pragma unroll
+        for (int j = 0; j < BM / 32; ++j) rowp[j] = conv_row(p.conv, (uint32_t)bm + (t >> 3) + 32 * j);
+    }
+    if constexpr (AM == 4) {
+#pragma unroll
+        for (int j = 0; j < BM / 32; ++j) rowp[j] = dgrad_row(p.conv, (uint32_t)bm + (t >> 3) + 32 * j);
+    }
+    // (weight gradient: the rows run along k; each thread walks its BM / 32 rows a k step at a time,
+    // from the first tile it fetches, in the variant's direction)
+    // (the large tile has no registers left for the walk: it splits its row indices at every step)
+    constexpr bool WALK = AM == 3 && BM == 64;
+    RowIter rit[WALK ? BM / 32 : 1];
+    int32_t row_an = 0, row_ah = 0, row_aw = 0;
+    if constexpr (AM == 3) {
+        const uint32_t kc = (uint32_t)bm + (t % (BM / 2)) * 2;
+        tap0 = conv_tap(p.conv, kc);
+        tap1 = conv_tap(p.conv, kc + 1);
+    }
+    if constexpr (WALK) {
+        static_assert(BK == kRowStep, "the row walk advances one k step at a time");
+        const uint32_t kfirst = (uint32_t)(p.variant ? kt1 - 1 : kt0) * BK;
+#pragma unroll
+        for (int j = 0; j < BM / 32; ++j) rit[j] = row_iter(p.conv, kfirst + t / (BM / 2) + (512 / BM) * j);
+        row_step_digits(p.conv, p.variant != 0, row_an, row_ah, row_aw);
+    }
+    // UNI: the channel count is a multiple of 16, so the 16 taps of a k step are 16 channels of one
+    // filter position: (kh, kw) and the tap's offset are the same for the whole wave and are found
+    // with scalar integer operations; the lane's channel pair is already part of its rows' offsets.
+    auto gather_tile = [&](auto vec_tag, auto uni_tag, int64_t k0, d2 (&ra)[BM / 32]) {
+        constexpr bool VEC = decltype(vec_tag)::value, UNI = decltype(uni_tag)::value;
+        if constexpr (UNI && (AM == 2 || AM == 4)) {
+            const TapPos t0 = AM == 2 ? conv_tap<true>(p.conv, (uint32_t)k0) : dgrad_tap<true>(p.conv, (uint32_t)k0);
+#pragma unroll
+            for (int j = 0; j < BM / 32; ++j) ra[j] = conv_gather<true, AM == 4>(p.A, p.conv, rowp[j], t0, t0);
+        } else if constexpr (AM == 2) {
+            const uint32_t kc = (uint32_t)k0 + (t & 7) * 2;
+            const TapPos t0 = conv_tap(p.conv, kc);
+            const TapPos t1 = VEC ? t0 : conv_tap(p.conv, kc + 1);
+#pragma unroll
+            for (int j = 0; j < BM / 32; ++j) ra[j] = conv_gather<VEC>(p.A, p.conv, rowp[j], t0, t1);
+        } else if constexpr (AM == 3) {
+#pragma unroll
+            for (int j = 0; j < BM / 32; ++j) {
+                if constexpr (WALK) {
+                    // the tiles are fetched in order, one per call (a fetch repeated past the last
+                    // tile moves on to rows nobody multiplies): k0 is implied
+                    ra[j] = conv_gather<VEC>(p.A, p.conv, row_pos(p.conv, rit[j]), tap0, tap1);
+                    row_advance(p.conv, rit[j], row_an, row_ah, row_aw);
+                } else {
+                    const RowPos r = conv_row(p.conv, (uint32_t)k0 + t / (BM / 2) + (512 / BM) * j);
+                    ra[j] = conv_gather<VEC>(p.A, p.conv, r, tap0, tap1);
+                }
+            }
+        } else if constexpr (AM == 4) {
+            const uint32_t kc = (uint32_t)k0 + (t & 7) * 2;
+            const TapPos t0 = dgrad_tap(p.conv, kc);
+            const TapPos t1 = VEC ? t0 : dgrad_tap(p.conv, kc + 1);
+#pragma unroll
+            for (int j = 0; j < BM / 32; ++j) ra[j] = conv_gather<VEC, true>(p.A, p.conv, rowp[j], t0, t1);
+        }
+    };
+    auto main_loop = [&](auto fast_tag, auto uni_tag) {
+        constexpr bool FAST = decltype(fast_tag)::value;
+        auto fetch = [&](int it, d2 (&ra)[BM / 32], d2 (&rb)[BN / 32]) {   // `it`-th step in this variant's order
+            const int64_t k0 = (int64_t)(p.variant ? kt1 - 1 - it : kt0 + it) * BK;
+            if constexpr (GA) {
+                if constexpr (FAST) gather_tile(std::true_type{}, uni_tag, k0, ra);
+                else if (p.conv.vec) gather_tile(std::true_type{}, std::false_type{}, k0, ra);
+                else gather_tile(std::false_type{}, std::false_type{}, k0, ra);
+            } else if constexpr (FAST) {
+                load_tile_fast<KCA, BM>(baseA, p.lda, k0, offA, ra);
+            } else {
+                load_tile<KCA, BM>(A, p.lda, bm, k0, p.M, p.K, p.vecA, ra);
+            }
+            if constexpr (FAST) load_tile_fast<KCB, BN>(baseB, p.ldb, k0, offB, rb);
+            else load_tile<KCB, BN>(B, p.ldb, bn, k0, p.N, p.K, p.vecB, rb);
+        };
+        // multiply the tile in LDS stage `cur`; with `more`, move the next tile from (sa, sb) to the other
+        // stage in the shadow of the last MFMA group
+        auto compute = [&](int cur, bool more, d2 (&sa)[BM / 32], d2 (&sb)[BN / 32]) {
+            const double *As = ldsA + cur * SA + wm * (16 * TM) + (lane & 15);
+            const double *Bs = ldsB + cur * SB + wn * 64 + (lane & 15);
+            // The narrow tiles have registers to spare: the fragments of group kk + 1 are requested
+            // before the MFMAs of group kk are issued, so an LDS round trip hides behind a whole
+            // group instead of behind its last instruction.  (The large tile has none to spare; there
+            // the compiler interleaves the reads as fragment registers fall free.)
+            constexpr bool PIPE = TM <= 2;
+            double a[PIPE ? 2 : 1][TM], bb[PIPE ? 2 : 1][4];
+            auto frags = [&](int kk, double (&fa)[TM], double (&fb)[4]) {
+                const int krow = kk * 4 + (lane >> 4);
+#pragma unroll
+                for (int i = 0; i < TM; ++i) fa[i] = As[krow * PA + i * 16];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) fb[j] = Bs[krow * PB + j * 16];
+            };
+            if (PIPE) frags(0, a[0], bb[0]);
+#pragma unroll
+            for (int kk = 0; kk < BK / 4; ++kk) {
+                const int cb = PIPE ? (kk & 1) : 0;
+                if (!PIPE) frags(kk, a[0], bb[0]);
+                else if (kk + 1 < BK / 4) {
+                    frags(kk + 1, a[cb ^ 1], bb[cb ^ 1]);
+                    __builtin_amdgcn_sched_barrier(0);         // keep the reads ahead of this group's MFMAs
+                }
+                if (kk == BK / 4 - 1) {
+                    // (the last group's fragments are already requested: LDS completes in order,
+                    // so the wave's MFMA stream has no gap before the barrier)
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (more) {
+                        store_tile<KCA, BM, PAD>(ldsA + (cur ^ 1) * SA, sa);
+                        store_tile<KCB, BN, PAD>(ldsB + (cur ^ 1) * SB, sb);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[cb][i], bb[cb][j], acc[i][j], 0, 0, 0);
+            }
+            __syncthreads();
+        };
+        // one k step: start the fetch of tile it+2 into (la, lb); multiply tile it; tile it+1 goes from
+        // (sa, sb) to LDS
+        auto step = [&](int it, int cur, d2 (&la)[BM / 32], d2 (&lb)[BN / 32], d2 (&sa)[BM / 32], d2 (&sb)[BN / 32]) {
+            // In the unguarded loop the fetch and the LDS store are unconditional (past the end
+            // they repeat the last tile and fill a stage nobody reads): with no branch around
+            // them the compiler's load-counter waits are exact.
+            if (FAST) fetch(it + 2 < nkt ? it + 2 : nkt - 1, la, lb);
+            else if (it + 2 < nkt) fetch(it + 2, la, lb);
+            compute(cur, FAST || it + 1 < nkt, sa, sb);
+        };
+        if (nkt > 0) {
+            fetch(0, ra0, rb0);
+            store_tile<KCA, BM, PAD>(ldsA, ra0);
+            store_tile<KCB, BN, PAD>(ldsB, rb0);
+            if (nkt > 1) fetch(1, ra0, rb0);
+        }
+        __syncthreads();
+        // (the odd last step stands after the loop: an exit from the middle of the body would reach
+        // the loop's head with the first step's loads pending, and every wait in the body is placed
+        // for the worst of the paths into it)
+        int it = 0;
+        for (; it + 1 < nkt; it += 2) {
+            step(it, 0, ra1, rb1, ra0, rb0);                // tile it+1 sits in set 0, it+2 goes to set 1
+            step(it + 1, 1, ra0, rb0, ra1, rb1);
+        }
+        if (it < nkt) step(it, 0, ra1, rb1, ra0, rb0);
+    };
+    const bool fast = fastA && fastB && (int64_t)kt1 * BK <= p.K;
+    if ((AM == 2 || AM == 4) && fast && p.conv.uni) {
+#pragma unroll
+        for (int j = 0; j < BM / 32; ++j) rowp[j].base += (t & 7) * 2;
+        main_loop(std::true_type{}, std::true_type{});
+    } else if (fast) {
+        main_loop(std::true_type{}, std::false_type{});
+    } else {
+        main_loop(std::false_type{}, std::false_type{});
+    }
+
+    const int g = lane >> 4, c16 = lane & 15;
+    const int64_t row0 = bm + wm * (16 * TM), col0 = bn + wn * 64;
+
+    if (p.splits > 1 || p.raw) {
+        // ---- split-K (or a caller that rounds in a later pass): raw accumulators to this slice's slab; alpha, bias, rounding come later
+        double *P = p.partial + ((int64_t)split * p.batch + (int64_t)b) * p.M * p.N;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int64_t row = row0 + i * 16 + 4 * r + g;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int64_t col = col0 + j * 16 + c16;
+                    if (row < p.M && col < p.N) P[row * p.N + col] = acc[i][j][r];
+                }
+            }
+        return;
+    }
+
+    tile_epilogue<TM, BM, BN>(p, acc, b, bm, bn, row0, col0, lane);
+}
+
 template <int WM, int TM>
 hipError_t launch_shape(const GemmParams &p, int am, bool kcb, hipStream_t s)
 {
@@ -594,7 +620,6 @@ hipError_t launch_shape(const GemmParams &p, int am, bool kcb, hipStream_t s)
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
-
 
 }  // namespace
 

@@ -51,6 +51,9 @@ bool onepass_usable(const double *x, const float *y);
 hipError_t launch_round_log_onepass(const double *x, uint64_t n, uint32_t thr, uint32_t k, float *y, void *ws,
                                     const LogOut &log, hipStream_t s);
 
+// threshold 0 (nothing is logged): y = rnd(x), *count = 0, as one plain stream; same alignment as the single-pass kernel
+hipError_t launch_round_only(const double *x, uint64_t n, uint32_t k, float *y, uint64_t *count, hipStream_t s);
+
 hipError_t launch_replay(const double *x, uint64_t n, const uint32_t *idx, const uint32_t *dir,
                          uint64_t count, uint32_t k, float *y, hipStream_t s);
 

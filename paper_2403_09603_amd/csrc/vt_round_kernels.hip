@@ -314,12 +314,15 @@ __global__ __launch_bounds__(256) void replay_kernel(const double *__restrict__ 
     __shared__ uint64_t s_lo;
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wv = tid >> 6;
     // Consecutive workgroup ids run on different XCDs (8, each with its own L2).  Every XCD takes
-    // one contiguous eighth of the tiles, so the index-list lines that the searches of
-    // neighbouring tiles share are fetched into one L2 instead of eight.
-    uint32_t tile;
+    // runs of 64 consecutive tiles, so the index-list lines that the searches of neighbouring tiles
+    // share are fetched into one L2 instead of eight, while the eight XCDs together still sweep one
+    // window of 512 tiles at a time (an eighth of the array per XCD, eight streams far apart, measured
+    // 4 % slower for a plain copy).  The last, incomplete window is walked in id order.
+    uint32_t tile = blockIdx.x;
     {
-        const uint32_t i = blockIdx.x, q = gridDim.x / 8u, r = gridDim.x % 8u, xcd = i % 8u;
-        tile = xcd * q + (xcd < r ? xcd : r) + i / 8u;
+        constexpr uint32_t kRun = 64;
+        const uint32_t i = blockIdx.x, window = i / (8u * kRun);
+        if ((window + 1u) * (8u * kRun) <= gridDim.x) tile = window * (8u * kRun) + (i % 8u) * kRun + (i / 8u) % kRun;
     }
     const uint64_t start = (uint64_t)tile * kReplayTile;
     const uint64_t stop = start + kReplayTile < n ? start + kReplayTile : n;

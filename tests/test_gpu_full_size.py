@@ -77,12 +77,15 @@ def test_config2_full_size():
     assert np.array_equal(_bits(vo.round_replay(aud_rows, idx[:k], dirw[:(k + 31) // 32], count=k)), _bits(c32_T[:16 * N]))
 
 
-def test_config5_full_size():
+@pytest.mark.parametrize("thr,tau", [(32, 2.0 ** -24), (1, 2.0 ** -40), (1, 2.0 ** -32)])
+def test_config5_full_size(thr, tau):
+    """thr = 32 is tau = 2^-24 ulp; tau = 2^-40 and 2^-32 are below FP64 resolution and both quantise to thr = 1:
+    exactly the planted ties are logged, the near misses one and two steps away are not."""
     import torch
     import paper_2403_09603_amd as vt
     dev = "cuda"
-    n, thr = 1 << 28, 32
-    tau = thr * 2.0 ** -29
+    n = 1 << 28
+    assert vt.vt_thr_from_tau(tau) == thr
     x, kind = si.planted_vector(n, si.seed_for(5, 0), thr=thr)
     xa = si.perturb_steps(x, si.seed_for(5, 1), thr)
     xd = torch.from_numpy(x).to(dev)
@@ -124,14 +127,20 @@ def test_config5_full_size():
     sub_dir = np.packbits(_dir_bits(dirw, cnt)[a:b], bitorder="little")
     sub_dir = np.frombuffer(sub_dir.tobytes().ljust(4 * ((b - a + 31) // 32), b"\0"), np.uint32)
     assert np.array_equal(_bits(y2h[lo:hi]), _bits(vo.round_replay(xa[lo:hi], idx[a:b] - lo, sub_dir, count=b - a)))
+    st = torch.zeros(68, dtype=torch.int64, device=dev)
+    vt.vt_threshold_stats(xd, xad, st)
+    torch.cuda.synchronize()
+    s = st.cpu().numpy().view(np.uint64)
+    if thr == 1:
+        # only exact ties are logged: the count is the number of planted values, every one a tie broken to even
+        assert cnt == int((kind == 1).sum())
+        assert np.array_equal(xa.view(np.uint64), x.view(np.uint64))       # no room to move inside (-1, 1) steps
+        assert int(s[0]) == 0 and int(s[1]) == 0 and int(s[2]) == 0 and int(s[3]) == n
+        return
     # without the log the auditor does diverge
     empty = vt.alloc_log(0)
     vt.vt_round_replay(xad, empty.idx, empty.dir, 0, y2)
     torch.cuda.synchronize()
     assert int((y2.view(torch.int32) != y.view(torch.int32)).sum().item()) > 1000
     # statistics of the pair at full size: every flip is inside the band, so thr_flip <= thr
-    st = torch.zeros(68, dtype=torch.int64, device=dev)
-    vt.vt_threshold_stats(xd, xad, st)
-    torch.cuda.synchronize()
-    s = st.cpu().numpy().view(np.uint64)
     assert int(s[0]) > 1000 and 0 < int(s[1]) <= thr and int(s[2]) < thr and int(s[3:].sum()) == n

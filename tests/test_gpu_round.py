@@ -54,8 +54,8 @@ def test_round_log_ragged_sizes(G, n, misalign):
 
 
 def test_round_log_paths_agree_on_many_tiles(G):
-    """600 tiles of 8192 (more than two buckets of 256 tiles) with very uneven density: a dense
-    planted stretch, a long run that logs nothing, then dense again."""
+    """1200 tiles of the single-pass kernel (more than one round of its scanner) with very uneven density:
+    a dense planted stretch, a long run that logs nothing, then dense again."""
     n = 600 * 8192 + 77
     x, _ = si.planted_vector(n, si.seed_for(1, 6), thr=64, planted_frac=0.9)
     x[40 * 8192:430 * 8192] = 1.5                      # FP32 values: never logged
@@ -64,6 +64,19 @@ def test_round_log_paths_agree_on_many_tiles(G):
     for misalign in (False, True):
         for _ in range(2):
             _same_log(G.gpu_round_log(x, tau, misalign=misalign), o)
+
+
+@pytest.mark.parametrize("n", [1, 1023, 1024, 1025, 512 * 1024, 700 * 1024 + 77, 1500 * 1024 - 1])
+def test_round_only_at_threshold_zero(G, n):
+    """tau = 0 logs nothing and takes the plain rounding stream (workgroups of 1024 values, walked in windows
+    of 512 workgroups): every FP32 value against the oracle, count 0, for both rounding amounts."""
+    x, _ = si.planted_vector(n, si.seed_for(1, 7) + n, thr=32, planted_frac=0.2)
+    x[: min(n, 400)] = si.edge_values()[: min(n, 400)]
+    for b_r in (32, 26):
+        y, idx, dirw, cnt = G.gpu_round_log(x, 0.0, b_r=b_r)
+        yo, io, do, co = vo.round_log(x, 0.0, b_r=b_r)
+        assert cnt == co == 0 and len(idx) == 0
+        assert np.array_equal(_bits(y), _bits(yo))
 
 
 @pytest.mark.parametrize("tau", [2.0 ** -30, 2.0 ** -4, 0.25])
