@@ -338,14 +338,14 @@ def leg_config2(b: Bench, args, si):
     for name, tau_b in (("2^-24", 2.0 ** -24), ("2^-8", 2.0 ** -8), ("1/4", 0.25)):
         row = {"tau_ulp": name, "thr": vt.vt_thr_from_tau(tau_b)}
         for fmt, lg in (("sparse", log_T), ("packed", dlog_T)):
-            t = b.per_call(lambda: gemm(0, tau_b, C32_T, None, lg), warm=5, reps=20)
+            t = b.per_call(lambda: gemm(0, tau_b, C32_T, None, lg), warm=40, reps=20)
             cnt_b = lg.read_count()
             row["logged"] = cnt_b
             row[fmt + "_call_ms"] = r4(t["median_ms"])
             row[fmt + "_call_ms_min"] = r4(t["min_ms"])
             row[fmt + "_log_bytes"] = cnt_b * 4 + (cnt_b + 7) // 8 if fmt == "sparse" else (total + 4) // 5
         sweep.append(row)
-    out["tau_sweep"] = {"timing": "5 warm-up + 20 timed calls each, HIP events around every call: median and minimum",
+    out["tau_sweep"] = {"timing": "40 warm-up + 20 timed calls each, HIP events around every call: median and minimum",
                         "rows": sweep}
     return out, tau, (X, W, bias)
 

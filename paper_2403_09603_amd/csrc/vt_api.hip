@@ -121,8 +121,9 @@ int round_log_flat(const double *x, uint64_t n, uint32_t thr, float *y, const vt
     return hip_status(e);
 }
 
-// planes already hold the decisions: count per segment (unless the producer did), scan, compact
-int finish_log(const vt::Planes &pl, uint64_t rows, const vt_log *log, bool counted, uint32_t thr, hipStream_t s)
+// planes already hold the decisions: compaction to the ordered log.  `cleared`: the kernel that wrote the
+// planes also zeroed what the single-launch compaction needs (see prepare_compaction)
+int finish_log(const vt::Planes &pl, uint64_t rows, const vt_log *log, bool cleared, uint32_t thr, hipStream_t s)
 {
     if (log->dense) return hip_status(vt::launch_planes_to_dense(pl, rows, log->dense, log->count, s));   // also writes *count
     const vt::LogOut lo{log->idx, log->dir, log->cap, log->count};
@@ -131,11 +132,23 @@ int finish_log(const vt::Planes &pl, uint64_t rows, const vt_log *log, bool coun
         none.segs = 0;
         return hip_status(vt::launch_seg_scan(none, lo, s));
     }
-    hipError_t e = hipSuccess;
-    if (!counted) e = vt::launch_seg_count(pl, s);
+    if (cleared) return hip_status(vt::launch_compact_onepass(pl, lo, s));   // also writes *count
+    hipError_t e = vt::launch_seg_count(pl, s);
     if (e == hipSuccess) e = vt::launch_seg_scan(pl, lo, s);                 // also writes *count
     if (e == hipSuccess) e = vt::launch_compact(pl, lo, s);
     return hip_status(e);
+}
+
+// Tells the GEMM kernel what to zero for the single-launch compaction of an index-list log: the scanner's
+// scratch and the direction words the entries will be OR-ed into.  False when that route is not taken.
+bool prepare_compaction(vt::GemmArgs &g, const vt::Planes &pl, const vt_log *log, uint64_t total)
+{
+    if (log->dense || g.thr == 0 || pl.segs == 0) return false;
+    vt::compact_onepass_scratch(pl, &g.zero_b, &g.zero_b_words);
+    const uint64_t stored = log->cap < total ? log->cap : total;
+    g.zero_a = log->dir;
+    g.zero_a_words = (uint32_t)((stored + 31) / 32);
+    return true;
 }
 
 // workspace check, plan, launch and log compaction shared by the GEMM and convolution entry points
@@ -175,11 +188,12 @@ int run_gemm(vt::GemmArgs &g, const vt_log *log, void *ws, size_t ws_bytes, hipS
         return hip_status(vt::launch_splitk_log_onepass(a, total, g.thr, k, g.C32, ws_rl,
                                                         vt::LogOut{log->idx, log->dir, log->cap, log->count}, s));
     }
+    const bool cleared = prepare_compaction(g, pl, log, total);
     mark_begin(s);
     hipError_t e = vt::launch_gemm_round_planes(g, plan, pl, nullptr, nullptr, s);
     mark_end(s);
     if (e != hipSuccess) return VT_ERR_HIP;
-    return finish_log(pl, (uint64_t)M * (uint64_t)batch, log, /*counted=*/false, g.thr, s);
+    return finish_log(pl, (uint64_t)M * (uint64_t)batch, log, cleared, g.thr, s);
 }
 
 // Validates a convolution geometry and fills the internal descriptor (with the output size).

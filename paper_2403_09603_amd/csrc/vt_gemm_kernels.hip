@@ -176,6 +176,7 @@ hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, con
     p.m_per_batch = magic_of(p.tilesM * p.tilesN);
     p.m_width = magic_of(8u * p.tilesN);
     p.m_batch_inner = magic_of(p.batch_inner);
+    p.zero_a = g.zero_a; p.zero_a_words = g.zero_a_words; p.zero_b = g.zero_b; p.zero_b_words = g.zero_b_words;
     p.vecA = ((uintptr_t)g.A % 16 == 0) && (g.lda % 2 == 0) && (g.strideA % 2 == 0) && (g.strideA2 % 2 == 0);
     p.vecB = ((uintptr_t)g.B % 16 == 0) && (g.ldb % 2 == 0) && (g.strideB % 2 == 0) && (g.strideB2 % 2 == 0);
     const bool kcb = g.transB != 0;

@@ -54,6 +54,8 @@ struct GemmParams {
     uint32_t thr, wpr, tilesM, tilesN, tiles_per_split, total_blocks;
     uint32_t m_tiles_per_split, m_per_batch, m_width, m_batch_inner;   // divmod_magic multipliers of the tile mapping's divisors
     int variant, vecA, vecB, splits, kt_per_split, raw;
+    uint32_t *zero_a, *zero_b;                  // words cleared by the kernel for the log compaction that follows
+    uint32_t zero_a_words, zero_b_words;
 };
 
 namespace {
@@ -386,6 +388,11 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
     const int t = threadIdx.x, lane = t & 63;
     const int wv = __builtin_amdgcn_readfirstlane(t >> 6);      // wave-uniform: keeps tile addresses in scalar registers
     const int wm = wv / WN, wn = wv % WN;
+
+    // what the single-launch log compaction after this kernel needs zeroed: its status words and the
+    // direction words of the log (a few words per workgroup)
+    for (uint32_t i = blockIdx.x * 256u + t; i < p.zero_a_words; i += gridDim.x * 256u) p.zero_a[i] = 0u;
+    for (uint32_t i = blockIdx.x * 256u + t; i < p.zero_b_words; i += gridDim.x * 256u) p.zero_b[i] = 0u;
 
     uint32_t split, b;
     int64_t bm, bn;

@@ -45,6 +45,12 @@ hipError_t launch_seg_scan(const Planes &pl, const LogOut &log, hipStream_t s);
 // ordered stream compaction: planes -> ascending idx[] + packed direction bits
 hipError_t launch_compact(const Planes &pl, const LogOut &log, hipStream_t s);
 
+// The three kernels above as one launch (a scanner workgroup hands the tiles their offsets).  Needs zeroed
+// beforehand, by the kernel that wrote the planes: the scratch that compact_onepass_scratch names (inside
+// the planes' bookkeeping arrays) and the first ceil(min(cap, outputs) / 32) direction words of the log.
+void compact_onepass_scratch(const Planes &pl, uint32_t **zero, uint32_t *zero_words);
+hipError_t launch_compact_onepass(const Planes &pl, const LogOut &log, hipStream_t s);
+
 // single-pass standalone trainer hook (chained scan); needs x 16-byte and y 8-byte aligned
 size_t onepass_bytes(uint64_t n);
 bool onepass_usable(const double *x, const float *y);
@@ -152,6 +158,9 @@ struct GemmArgs {
     int variant;
     uint32_t thr;
     bool raw = false;     // leave alpha, bias and the rounding to a later pass even without split-K
+    // two arrays of 32-bit words the kernel clears on its way (what the log compaction that follows needs zeroed)
+    uint32_t *zero_a = nullptr, *zero_b = nullptr;
+    uint32_t zero_a_words = 0, zero_b_words = 0;
 };
 // Tile shape (index into the kernel's shape table) and split-K factor chosen for a problem.
 struct GemmPlan {

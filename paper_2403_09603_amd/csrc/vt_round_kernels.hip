@@ -5,6 +5,7 @@
 //   stats        : threshold statistics over two results (Algorithm "threshold", collection)
 #include "vt_device.h"
 #include "vt_kernels.h"
+#include "vt_scan.h"
 
 namespace vt {
 
@@ -200,6 +201,113 @@ __global__ __launch_bounds__(256) void compact_kernel(const uint64_t *__restrict
             uint32_t *wp = dir + (G >> 5) + (lane >> 3);
             if (vv == 0xFFFFFFFFu) *wp = dv;
             else atomicOr(wp, dv);
+        }
+    }
+}
+
+// --------------------------------------------------------------------------------------------
+// compact, single launch: the same compaction without the count and scan kernels before it (the
+// three launches cost more in the gaps between them than in themselves: about 8 us per kernel
+// boundary behind a 0.6 ms GEMM).  A tile is the four segments of a workgroup; it counts its own
+// entries, trades the count for its offset with the scanner workgroup (vt_scan.h) while it already
+// sorts its entries into LDS, and then emits them as compact_kernel does.  The status words, the
+// error words and the direction words of the log must be zero at launch (the producer of the planes
+// clears them); the scanner writes *count.
+// --------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void compact_onepass_kernel(const uint64_t *__restrict__ pl_logged,
+                                                              const uint64_t *__restrict__ pl_dir, uint64_t words,
+                                                              uint32_t segs, uint32_t wpr, uint32_t ncols,
+                                                              uint64_t *__restrict__ st, uint32_t tiles,
+                                                              uint32_t *__restrict__ err,
+                                                              uint32_t *__restrict__ idx, uint32_t *__restrict__ dir,
+                                                              uint64_t cap, uint64_t *__restrict__ count)
+{
+    __shared__ uint16_t ent[4][kEntSlots];
+    __shared__ uint32_t wbase[4][kSegWords];
+    __shared__ uint32_t s_cnt[4], s_scan[8];
+    __shared__ uint64_t s_off;
+    __shared__ uint32_t s_ok;
+    if (blockIdx.x == 0) {
+        scanner(st, tiles, err, count, s_scan);
+        return;
+    }
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wv = threadIdx.x >> 6;
+    const uint32_t tile = blockIdx.x - 1u;
+    const uint32_t seg = tile * 4u + wv;
+    const uint64_t w = (uint64_t)seg * kSegWords + lane;
+    const bool have = seg < segs && w < words;
+    uint64_t m = have ? pl_logged[w] : 0;
+    const uint64_t dword = have ? pl_dir[w] : 0;
+    {
+        const uint64_t row = w / wpr;
+        wbase[wv][lane] = (uint32_t)(row * ncols + (w - row * wpr) * 64u);
+    }
+    // exclusive scan of the population counts over the wave
+    const uint32_t c = popc64(m);
+    uint32_t incl = c;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t up = (uint32_t)__shfl_up((int)incl, o, 64);
+        if (lane >= (uint32_t)o) incl += up;
+    }
+    const uint32_t cnt = (uint32_t)__shfl((int)incl, 63, 64);      // this segment's entries
+    if (lane == 0) s_cnt[wv] = cnt;
+    __syncthreads();
+    const uint32_t tile_cnt = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+    if (wv == 0) {
+        // publish the tile's count and wait for its place in the log while the other waves sort
+        uint64_t off;
+        const bool ok = tile_offset(st, tile, tile_cnt, err, lane, off);
+        if (lane == 0) { s_off = off; s_ok = ok ? 1u : 0u; }
+    }
+    uint32_t rank = incl - c;
+    while (m) {                                             // lanes leave as their word runs out of bits
+        const uint32_t b = (uint32_t)__builtin_ctzll(m);
+        ent[wv][ent_slot(rank)] = (uint16_t)((lane << 6) | b | (((uint32_t)(dword >> b) & 1u) << 15));
+        m &= m - 1;
+        ++rank;
+    }
+    __syncthreads();
+    if (!s_ok || cnt == 0) return;
+    uint64_t off = s_off;
+#pragma unroll
+    for (uint32_t v = 0; v < 3; ++v)
+        if (v < wv) off += s_cnt[v];
+    if (off >= cap) return;
+    const uint64_t end = off + cnt < cap ? off + cnt : cap;
+    const bool wide = ((uintptr_t)idx & 15u) == 0;
+    for (uint64_t G = off & ~255ull; G < end; G += 256) {
+        const uint64_t p0 = G + 4u * lane;
+        uint32_t iv[4], nib_v = 0, nib_d = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint64_t p = p0 + j;
+            const bool valid = p >= off && p < end;
+            const uint32_t e = valid ? ent[wv][ent_slot((uint32_t)(p - off))] : 0u;
+            iv[j] = wbase[wv][(e & 0xFFFu) >> 6] + (e & 63u);
+            nib_v |= (uint32_t)valid << j;
+            nib_d |= (e >> 15) << j;                        // (e is 0 for invalid positions)
+        }
+        if (wide && nib_v == 0xFu) {
+            *(uint4 *)(idx + p0) = make_uint4(iv[0], iv[1], iv[2], iv[3]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if ((nib_v >> j) & 1u) idx[p0 + j] = iv[j];
+        }
+        // eight lanes' nibbles make one direction word (entries G + 32 g .. G + 32 g + 31); the words
+        // were cleared before the launch, so partial ones are OR-ed
+        uint32_t vv = nib_v << (4u * (lane & 7u)), dv = nib_d << (4u * (lane & 7u));
+#pragma unroll
+        for (int o = 1; o < 8; o <<= 1) {
+            vv |= (uint32_t)__shfl_xor((int)vv, o, 64);
+            dv |= (uint32_t)__shfl_xor((int)dv, o, 64);
+        }
+        if ((lane & 7u) == 0 && vv) {
+            uint32_t *wp = dir + (G >> 5) + (lane >> 3);
+            if (vv == 0xFFFFFFFFu) *wp = dv;
+            else if (dv) atomicOr(wp, dv);
         }
     }
 }
@@ -532,6 +640,24 @@ hipError_t launch_seg_count(const Planes &pl, hipStream_t s)
 hipError_t launch_seg_scan(const Planes &pl, const LogOut &log, hipStream_t s)
 {
     seg_scan_kernel<<<1, kScanThreads, 0, s>>>(pl.seg_cnt, pl.seg_off, pl.segs, log.dir, log.cap, log.count);
+    return hipGetLastError();
+}
+
+void compact_onepass_scratch(const Planes &pl, uint32_t **zero, uint32_t *zero_words)
+{
+    const uint32_t tiles = (pl.segs + 3u) / 4u;
+    *zero = pl.seg_cnt;                                     // status words (8 bytes per tile), then the error words
+    *zero_words = 2u * tiles + 4u;
+}
+
+hipError_t launch_compact_onepass(const Planes &pl, const LogOut &log, hipStream_t s)
+{
+    if (pl.segs == 0) return hipErrorInvalidValue;
+    const uint32_t tiles = (pl.segs + 3u) / 4u;
+    uint64_t *st = (uint64_t *)pl.seg_cnt;
+    uint32_t *err = (uint32_t *)(st + tiles);
+    compact_onepass_kernel<<<tiles + 1u, 256, 0, s>>>(pl.logged, pl.dir, pl.words, pl.segs, pl.wpr, pl.ncols, st, tiles, err,
+                                                      log.idx, log.dir, log.cap, log.count);
     return hipGetLastError();
 }
 

@@ -8,25 +8,14 @@
 // the algorithmic bytes: 8 B + 4 B per element plus 4.125 B per logged entry.
 //
 // Position in the globally ordered log, without a second pass over the data: workgroup 0 is a
-// scanner.  A tile publishes its count in its status word and waits (one wave only; the other
-// three retire at once) until the scanner has replaced it by the tile's offset.  The scanner
-// polls up to 1024 consecutive status words per round, takes the prefix of them that is
-// already published, scans it in LDS and writes the offsets back, so the log position of a
-// tile costs two memory round trips however many tiles are in flight, each status line has
-// one polling reader, and the scan advances by up to 1024 tiles per round trip.  (Measured
-// alternatives on 2^28 values, which stream in 0.50 ms: tile-to-tile decoupled look-back
-// 0.71 ms -- its frontier moves slower than HBM retires tiles; per-bucket atomic totals read
-// by every tile 2.7 ms -- polling of shared lines serialises at the memory side.)
-// Integer sums in a fixed order: the result does not depend on timing.
-//
-// Progress: the scanner is workgroup 0, dispatched first, and depends only on tiles publishing
-// their counts, which no tile waits for anything to do; tiles depend only on the scanner.
-// Every wait is bounded all the same: after kSpinLimit polls without progress (seconds) a
-// waiter sets the error word, which releases every other waiter too, so the grid always
-// drains; a tile that gives up writes no entries, and the host-visible result is then
-// *count = UINT64_MAX (VT_COUNT_ABANDONED: y complete, idx / dir invalid).
+// scanner and every tile trades its count for its offset (vt_scan.h).  Only one wave of a tile
+// waits; the other three retire at once.  (Measured alternatives on 2^28 values, which stream in
+// 0.50 ms: tile-to-tile decoupled look-back 0.71 ms -- its frontier moves slower than HBM retires
+// tiles; per-bucket atomic totals read by every tile 2.7 ms -- polling of shared lines serialises
+// at the memory side.)
 #include "vt_device.h"
 #include "vt_kernels.h"
+#include "vt_scan.h"
 #include "vt_source.h"
 
 namespace vt {
@@ -41,22 +30,6 @@ constexpr int kWaves = kThreads / 64;
 constexpr int kWaveChunk = 1024;     // contiguous outputs per wave: 8 rows of 128
 constexpr int kRows = 8;
 constexpr int kTile = kWaves * kWaveChunk;   // outputs per workgroup
-constexpr int kScanThreads = 256, kScanPer = 4;      // scanner: 1024 status words per round
-constexpr uint32_t kSpinLimit = 1u << 21;   // polls (each a few microseconds) before a tile gives up waiting
-// The scanner waits for tiles to be dispatched at all, which other work on the GPU can delay: its
-// limit is longer (some tens of seconds of idle polling).
-constexpr uint32_t kScanIdleLimit = 1u << 24;
-
-constexpr uint64_t kCountFlag = 1ull << 62, kOffsetFlag = 2ull << 62, kValMask = (1ull << 62) - 1;
-
-__device__ __forceinline__ uint64_t st_load(const uint64_t *p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void st_store(uint64_t *p, uint64_t v)
-{
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 
 __global__ __launch_bounds__(256) void onepass_init_kernel(uint64_t *__restrict__ st, uint32_t tiles,
                                                            uint32_t *__restrict__ err, uint32_t *__restrict__ dir,
@@ -67,89 +40,6 @@ __global__ __launch_bounds__(256) void onepass_init_kernel(uint64_t *__restrict_
     for (uint64_t k = i; k < tiles; k += stride) st[k] = 0;
     for (uint64_t k = i; k < dir_words; k += stride) dir[k] = 0;
     if (i == 0) { *err = 0; if (tiles == 0) *count = 0; }
-}
-
-// Workgroup 0: turns published counts into offsets, in tile order.
-__device__ __forceinline__ void scanner(uint64_t *__restrict__ st, uint32_t tiles, uint32_t *__restrict__ err,
-                                        uint64_t *__restrict__ count, uint32_t *s_u32)
-{
-    const uint32_t tid = threadIdx.x, lane = tid & 63u, wv = tid >> 6;
-    uint32_t *s_min = s_u32;          // [4] first unpublished position per wave
-    uint32_t *s_sum = s_u32 + 4;      // [4] count total per wave
-    uint64_t run = 0;
-    uint32_t base = 0, idle = 0, rounds = 0, idle_rounds = 0;
-    bool force = false;
-    while (base < tiles) {
-        uint64_t v[kScanPer];
-        uint32_t first = kScanPer;                        // first unpublished among my four
-#pragma unroll
-        for (int j = kScanPer - 1; j >= 0; --j) {
-            const uint64_t t = (uint64_t)base + tid * kScanPer + j;
-            v[j] = t < tiles ? st_load(st + t) : kCountFlag;   // past the end: published, count 0
-            if (force && (v[j] >> 62) == 0) v[j] = kCountFlag;
-            if ((v[j] >> 62) == 0) first = j;
-        }
-        uint32_t pos = first < kScanPer ? tid * kScanPer + first : kScanThreads * kScanPer;
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            const uint32_t other = __shfl_xor(pos, o, 64);
-            pos = other < pos ? other : pos;
-        }
-        if (lane == 0) s_min[wv] = pos;
-        __syncthreads();
-        uint32_t R = s_min[0];
-#pragma unroll
-        for (int w = 1; w < kScanThreads / 64; ++w) R = s_min[w] < R ? s_min[w] : R;
-        if (R > tiles - base) R = tiles - base;
-        ++rounds;
-        if (R == 0) {                                      // nothing new yet
-            ++idle_rounds;
-            __syncthreads();
-            if (++idle > kScanIdleLimit) {                 // never expected: stop waiting, drain
-                if (tid == 0) atomicOr(err, 1u);
-                force = true;
-            }
-            __builtin_amdgcn_s_sleep(2);
-            continue;
-        }
-        idle = 0;
-        // exclusive scan of the counts of tiles base .. base + R - 1
-        uint32_t c[kScanPer], mine = 0;
-#pragma unroll
-        for (int j = 0; j < kScanPer; ++j) {
-            c[j] = tid * kScanPer + j < R ? (uint32_t)(v[j] & kValMask) : 0u;
-            mine += c[j];
-        }
-        uint32_t incl = mine;                              // inclusive scan across the wave
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const uint32_t up = __shfl_up(incl, o, 64);
-            if (lane >= (uint32_t)o) incl += up;
-        }
-        if (lane == 63) s_sum[wv] = incl;
-        __syncthreads();
-        uint32_t before = 0, total = 0;
-#pragma unroll
-        for (int w = 0; w < kScanThreads / 64; ++w) {
-            if ((uint32_t)w < wv) before += s_sum[w];
-            total += s_sum[w];
-        }
-        uint64_t off = run + before + (incl - mine);
-#pragma unroll
-        for (int j = 0; j < kScanPer; ++j) {
-            const uint32_t q = tid * kScanPer + j;
-            if (q < R) st_store(st + base + q, kOffsetFlag | off);
-            off += c[j];
-        }
-        run += total;
-        base += R;
-        __syncthreads();                                   // s_min / s_sum are reused next round
-    }
-    if (tid == 0) {
-        *count = __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ? ~0ull : run;
-        err[1] = rounds;                                   // diagnostics: scan rounds, of which idle
-        err[2] = idle_rounds;
-    }
 }
 
 // One wave's share of a tile: 1024 contiguous values as 8 rows of 128 (two per lane).  FULL:
@@ -226,10 +116,10 @@ __global__ __launch_bounds__(kThreads) void round_log_onepass_kernel(const Src x
                                                                 uint64_t cap, uint64_t *__restrict__ count)
 {
     __shared__ uint16_t ent[kWaves][kWaveChunk];  // per wave: position in its chunk | direction << 15
-    __shared__ uint32_t s_wc[kWaves];             // logged outputs per wave (scanner: scratch)
+    __shared__ uint32_t s_wc[kWaves < 8 ? 8 : kWaves];   // logged outputs per wave (scanner: its 8 words of scratch)
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wv = tid >> 6;
     if (blockIdx.x == 0) {
-        if (tid < kScanThreads) scanner(st, tiles, err, count, s_wc);
+        if (tid < kScannerThreads) scanner(st, tiles, err, count, s_wc);
         return;
     }
     const uint32_t tile = blockIdx.x - 1;
@@ -247,22 +137,8 @@ __global__ __launch_bounds__(kThreads) void round_log_onepass_kernel(const Src x
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) pre[w + 1] = pre[w] + s_wc[w];
     const uint32_t c = pre[kWaves];
-    if (lane == 0) st_store(st + tile, kCountFlag | c);
-    if (c == 0) return;                           // nothing to place: no need to wait
-    uint64_t sv = 0;
-    for (uint32_t spins = 0;; ++spins) {
-        // polls are round trips to memory and compete with the stream: a scan round takes a
-        // few microseconds, so poll about that often (s_sleep 127 = 8128 cycles)
-        __builtin_amdgcn_s_sleep(127);
-        sv = st_load(st + tile);
-        if ((sv >> 62) == 2) break;
-        const bool failed = __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
-        if (failed || spins > kSpinLimit) {       // never expected: give up, do not hang, write no entries
-            if (lane == 0) atomicOr(err, 1u);
-            return;
-        }
-    }
-    const uint64_t off = sv & kValMask;
+    uint64_t off;
+    if (!tile_offset(st, tile, c, err, lane, off) || c == 0) return;
     const uint64_t end = off + c < cap ? off + c : cap;
     // entries leave 256 at a time, aligned in log position: four consecutive entries per lane (one
     // 16-byte index store where the log is aligned), their direction bits gathered over eight lanes
