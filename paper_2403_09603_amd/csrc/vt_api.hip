@@ -611,7 +611,10 @@ int vt_layer_f64_round_log(const vt_layer *L, float *y, double *y64_debug, int v
     g.scale = L->scale;
     g.period = L->op == VT_LAYER_SOFTMAX ? (uint32_t)L->causal_period : 0u;
     g.inv_period = g.period ? 1.0 / (double)g.period : 0.0;
-    hipError_t e = vt::launch_layer_stats(g, (uint64_t)L->rows, L->eps, variant, s);
+    g.eps = L->eps;
+    g.variant = variant;
+    g.tile_stats = vt::layer_tile_stats(L->op, (uint64_t)L->cols);
+    hipError_t e = vt::launch_layer_stats(g, (uint64_t)L->rows, s);
     if (e != hipSuccess) return VT_ERR_HIP;
     const uint32_t k = k_of(log->b_r);
     mark_begin(s);

@@ -87,13 +87,29 @@ struct LayerArgs {
     double scale;                 // softmax: logits are scale * a
     uint32_t period;              // softmax: causal mask period, 0 = none
     double inv_period;
+    double eps;                   // layer norm, batch norm
+    int variant;                  // summation order of the statistics
+    bool tile_stats;              // layer norm: the fused kernel computes the statistics of the rows of its own
+                                  // tile (layer_tile_stats()); `stat` is then not read
 };
+
+// Layer norm over rows of 64 to 2048 columns: a tile of the fused kernels (4096 or 5120 outputs) meets
+// at most kTileStatRows rows and reads little more than its own outputs to get their statistics, so
+// the separate statistics pass (a second read of the whole input from memory) is dropped: 2^28
+// values in rows of 1024, 0.99 -> 0.78 ms.  (Softmax is bound by its two exponentials per value, not
+// by memory: the same scheme measured slower there, 1.26 -> 1.50 ms, also with the exponentials
+// kept in LDS between the two phases, 1.98 ms.)
+constexpr uint32_t kTileStatMinCols = 64, kTileStatMaxCols = 2048, kTileStatRows = 84;
+inline bool layer_tile_stats(int op, uint64_t cols)
+{
+    return op == kLayerNorm && cols >= kTileStatMinCols && cols <= kTileStatMaxCols;
+}
 
 size_t layer_stat_bytes(uint64_t rows, uint64_t cols);
 // per-row statistics of layer norm / softmax, per-column statistics of batch norm into g.stat
-// (no-op for the element-wise layers; batch norm also uses the scratch that follows g.stat);
-// variant selects the summation order
-hipError_t launch_layer_stats(const LayerArgs &g, uint64_t rows, double eps, int variant, hipStream_t s);
+// (no-op for the element-wise layers and when g.tile_stats is set; batch norm also uses the scratch
+// that follows g.stat); g.variant selects the summation order
+hipError_t launch_layer_stats(const LayerArgs &g, uint64_t rows, hipStream_t s);
 hipError_t launch_layer_log_onepass(const LayerArgs &g, uint64_t n, uint32_t thr, uint32_t k, float *y, void *ws,
                                     const LogOut &log, hipStream_t s);
 hipError_t launch_layer_log_dense(const LayerArgs &g, uint64_t n, uint32_t thr, uint32_t k, float *y, uint8_t *tlog,

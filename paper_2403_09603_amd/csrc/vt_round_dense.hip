@@ -146,11 +146,15 @@ __global__ __launch_bounds__(kWaves * 64) void round_log_dense_kernel(const Src 
                                                               uint8_t *__restrict__ tlog, uint64_t *__restrict__ slots)
 {
     __shared__ __attribute__((aligned(16))) uint8_t codes[kWaves][kChunk];
+    __shared__ __attribute__((aligned(16))) double tile_stat[Src::template tile_lds_doubles<kTile>() ? Src::template tile_lds_doubles<kTile>() : 1];
     const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
-    const uint64_t base = (uint64_t)xcd_contiguous_tile() * kTile + (uint64_t)wv * kChunk;
+    const uint64_t tile0 = (uint64_t)xcd_contiguous_tile() * kTile;
+    Src src = x;
+    src.template begin_tile<kTile>(tile0, n, tile_stat);
+    const uint64_t base = tile0 + (uint64_t)wv * kChunk;
     if (base >= n) return;
-    if (base + kChunk <= n) round_log_dense_chunk<true, VEC, K0>(x, n, thr, k, y, tlog, base, lane, codes[wv], slots);
-    else round_log_dense_chunk<false, VEC, K0>(x, n, thr, k, y, tlog, base, lane, codes[wv], slots);
+    if (base + kChunk <= n) round_log_dense_chunk<true, VEC, K0>(src, n, thr, k, y, tlog, base, lane, codes[wv], slots);
+    else round_log_dense_chunk<false, VEC, K0>(src, n, thr, k, y, tlog, base, lane, codes[wv], slots);
 }
 
 // Auditor: entry i of the packed log applied to x[i].
@@ -420,8 +424,11 @@ hipError_t launch_layer_log_dense(const LayerArgs &g, uint64_t n, uint32_t thr, 
     case kLayerRelu: return launch_dense_from(LayerSource<kLayerRelu>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
     case kLayerGeluTanh: return launch_dense_from(LayerSource<kLayerGeluTanh>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
     case kLayerGeluErf: return launch_dense_from(LayerSource<kLayerGeluErf>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
-    case kLayerNorm: return launch_dense_from(LayerSource<kLayerNorm>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
-    case kLayerSoftmax: return launch_dense_from(LayerSource<kLayerSoftmax>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
+    case kLayerNorm:
+        if (g.tile_stats) return launch_dense_from(LayerSource<kLayerNorm, true>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
+        return launch_dense_from(LayerSource<kLayerNorm>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
+    case kLayerSoftmax:
+        return launch_dense_from(LayerSource<kLayerSoftmax>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
     case kLayerBatchNorm: return launch_dense_from(LayerSource<kLayerBatchNorm>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
     case kLayerBatchNormRelu: return launch_dense_from(LayerSource<kLayerBatchNormRelu>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
     default: return hipErrorInvalidValue;

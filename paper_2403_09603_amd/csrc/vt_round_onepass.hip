@@ -117,16 +117,19 @@ __global__ __launch_bounds__(kThreads) void round_log_onepass_kernel(const Src x
 {
     __shared__ uint16_t ent[kWaves][kWaveChunk];  // per wave: position in its chunk | direction << 15
     __shared__ uint32_t s_wc[kWaves < 8 ? 8 : kWaves];   // logged outputs per wave (scanner: its 8 words of scratch)
+    __shared__ __attribute__((aligned(16))) double tile_stat[Src::template tile_lds_doubles<kTile>() ? Src::template tile_lds_doubles<kTile>() : 1];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wv = tid >> 6;
     if (blockIdx.x == 0) {
         if (tid < kScannerThreads) scanner(st, tiles, err, count, s_wc);
         return;
     }
     const uint32_t tile = blockIdx.x - 1;
+    Src src = x;
+    src.template begin_tile<kTile>((uint64_t)tile * kTile, n, tile_stat);
     const uint64_t wbase = (uint64_t)tile * kTile + (uint64_t)wv * kWaveChunk;
     const uint32_t wcount = ((uint64_t)(tile + 1) * kTile <= n)
-                                ? round_rows<true, K0>(x, n, thr, k, y, wbase, lane, ent[wv])
-                                : round_rows<false, K0>(x, n, thr, k, y, wbase, lane, ent[wv]);
+                                ? round_rows<true, K0>(src, n, thr, k, y, wbase, lane, ent[wv])
+                                : round_rows<false, K0>(src, n, thr, k, y, wbase, lane, ent[wv]);
     if (lane == 0) s_wc[wv] = wcount;
     __syncthreads();
     // Only wave 0 goes on: it alone waits for the tile's place in the log, so the other three
@@ -308,8 +311,11 @@ hipError_t launch_layer_log_onepass(const LayerArgs &g, uint64_t n, uint32_t thr
     case kLayerRelu: return launch_onepass_from(LayerSource<kLayerRelu>{g}, n, thr, k, y, ws, log, s);
     case kLayerGeluTanh: return launch_onepass_from(LayerSource<kLayerGeluTanh>{g}, n, thr, k, y, ws, log, s);
     case kLayerGeluErf: return launch_onepass_from(LayerSource<kLayerGeluErf>{g}, n, thr, k, y, ws, log, s);
-    case kLayerNorm: return launch_onepass_from(LayerSource<kLayerNorm>{g}, n, thr, k, y, ws, log, s);
-    case kLayerSoftmax: return launch_onepass_from(LayerSource<kLayerSoftmax>{g}, n, thr, k, y, ws, log, s);
+    case kLayerNorm:
+        if (g.tile_stats) return launch_onepass_from(LayerSource<kLayerNorm, true>{g}, n, thr, k, y, ws, log, s);
+        return launch_onepass_from(LayerSource<kLayerNorm>{g}, n, thr, k, y, ws, log, s);
+    case kLayerSoftmax:
+        return launch_onepass_from(LayerSource<kLayerSoftmax>{g}, n, thr, k, y, ws, log, s);
     case kLayerBatchNorm: return launch_onepass_from(LayerSource<kLayerBatchNorm>{g}, n, thr, k, y, ws, log, s);
     case kLayerBatchNormRelu: return launch_onepass_from(LayerSource<kLayerBatchNormRelu>{g}, n, thr, k, y, ws, log, s);
     default: return hipErrorInvalidValue;

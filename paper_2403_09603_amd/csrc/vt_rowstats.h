@@ -1,0 +1,105 @@
+// vt_rowstats.h -- statistics of one row of a row-wise layer (layer norm, softmax) by one wavefront:
+// two sweeps over the row (the second one hits the cache), eight loads in flight per lane, FP64
+// throughout.  Shared by the stand-alone statistics kernels and by the fused layer-norm kernels
+// that compute the statistics of the rows of their own tile.
+//
+// Summation order: the row is cut into chunks of 512 columns; lane l owns columns l, l + 64, ...,
+// l + 448 of each chunk and adds them to its partial sum chunk by chunk (variant 0: ascending
+// columns, variant 1: descending), then the 64 partial sums are combined by a fixed butterfly
+// (variant 0: strides 32, 16, ..., 1; variant 1: strides 1, 2, ..., 32).  Both orders are fixed, so
+// a given variant always returns the same bits; the two variants differ in their low bits the
+// way two GPU types do.
+#pragma once
+#include "vt_device.h"
+
+#include <math.h>
+
+namespace vt {
+
+typedef double stat_d2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ double wave_add(double v, int variant)
+{
+    if (variant == 0) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v = v + __shfl_xor(v, o, 64);
+    } else {
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) v = v + __shfl_xor(v, o, 64);
+    }
+    return v;
+}
+
+__device__ __forceinline__ double wave_max(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const double w = __shfl_xor(v, o, 64);
+        v = w > v ? w : v;
+    }
+    return v;
+}
+
+constexpr uint32_t kRowInFlight = 8, kRowChunkCols = 64 * kRowInFlight;
+
+// Calls fold(column, value) for every column c < lim of the row that belongs to this lane, in the
+// variant's order; `load` maps a column to the value to accumulate.
+template <class Load, class Fold>
+__device__ __forceinline__ void row_sweep(uint32_t lim, uint32_t lane, int variant, Load load, Fold fold)
+{
+    const uint32_t chunks = (lim + kRowChunkCols - 1) / kRowChunkCols;
+    for (uint32_t i = 0; i < chunks; ++i) {
+        const uint32_t c0 = (variant ? chunks - 1 - i : i) * kRowChunkCols + lane;
+        double v[kRowInFlight];
+        bool in[kRowInFlight];
+#pragma unroll
+        for (uint32_t u = 0; u < kRowInFlight; ++u) {
+            const uint32_t c = c0 + 64u * (variant ? kRowInFlight - 1 - u : u);
+            in[u] = c < lim;
+            v[u] = in[u] ? load(c) : 0.0;
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < kRowInFlight; ++u)
+            if (in[u]) fold(c0 + 64u * (variant ? kRowInFlight - 1 - u : u), v[u]);
+    }
+}
+
+// (mean, 1 / sqrt(variance + eps)) of xr[0 .. cols): the same pair in every lane
+__device__ __forceinline__ stat_d2 norm_row_stats(const double *__restrict__ xr, uint32_t cols, double eps, int variant,
+                                                  uint32_t lane)
+{
+    double s = 0.0;
+    row_sweep(cols, lane, variant, [&](uint32_t c) { return xr[c]; }, [&](uint32_t, double v) { s = s + v; });
+    const double mean = wave_add(s, variant) / (double)cols;
+    double q = 0.0;
+    row_sweep(cols, lane, variant, [&](uint32_t c) { return xr[c]; }, [&](uint32_t, double v) { const double d = v - mean; q = q + d * d; });
+    stat_d2 st;
+    st.x = mean;
+    st.y = 1.0 / sqrt(wave_add(q, variant) / (double)cols + eps);
+    return st;
+}
+
+// (max, 1 / sum of exp(scale x - max)) over the visible columns 0 .. seen - 1: the same pair in every lane
+__device__ __forceinline__ stat_d2 softmax_row_stats(const double *__restrict__ xr, uint32_t seen, double scale, int variant,
+                                                     uint32_t lane)
+{
+    double m = -INFINITY;
+    row_sweep(seen, lane, 0, [&](uint32_t c) { return scale * xr[c]; }, [&](uint32_t, double z) { m = z > m ? z : m; });
+    m = wave_max(m);
+    double s = 0.0;
+    row_sweep(seen, lane, variant, [&](uint32_t c) { return xr[c]; }, [&](uint32_t, double v) { s = s + exp(scale * v - m); });
+    stat_d2 st;
+    st.x = m;
+    st.y = 1.0 / wave_add(s, variant);
+    return st;
+}
+
+// columns of row r that a softmax with causal period `period` sees (0 = all)
+__device__ __forceinline__ uint32_t softmax_seen(uint32_t r, uint32_t cols, uint32_t period)
+{
+    if (!period) return cols;
+    const uint32_t rem = r % period;
+    return rem + 1u < cols ? rem + 1u : cols;
+}
+
+}  // namespace vt

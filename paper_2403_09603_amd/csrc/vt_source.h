@@ -2,9 +2,16 @@
 // memory, or an element-wise / row-wise layer evaluated on the fly so that its FP64 output never
 // goes to memory (residual add, ReLU, GELU, layer norm, softmax: the non-GEMM layers of a
 // transformer block, each an "intermediate computation" whose output the method rounds).
+//
+// A source has pair(e, n) (two neighbouring values), keep(e, n, v) (an optional FP64 copy) and
+// begin_tile<TILE>(e0, n, lds): called by every thread of a tile workgroup before the first pair()
+// of the TILE outputs from e0 on, with tile_lds_doubles<TILE>() doubles of LDS.  Only the row-wise
+// layers use it: a layer-norm workgroup computes the statistics of the rows its tile meets, one
+// wavefront per row.
 #pragma once
 #include "vt_device.h"
 #include "vt_kernels.h"
+#include "vt_rowstats.h"
 
 #include <math.h>
 
@@ -16,6 +23,10 @@ typedef double src_d2 __attribute__((ext_vector_type(2)));
 // a value that is never logged.
 struct PlainSource {
     const double *x;
+    template <uint32_t TILE>
+    static constexpr uint32_t tile_lds_doubles() { return 0; }
+    template <uint32_t TILE>
+    __device__ __forceinline__ void begin_tile(uint64_t, uint64_t, double *) {}
     template <bool FULL, bool VEC>
     __device__ __forceinline__ src_d2 pair(uint64_t e, uint64_t n) const
     {
@@ -44,6 +55,10 @@ struct SplitKSource {
     uint32_t ncols;
     double inv_ncols;
     double *y64;
+    template <uint32_t TILE>
+    static constexpr uint32_t tile_lds_doubles() { return 0; }
+    template <uint32_t TILE>
+    __device__ __forceinline__ void begin_tile(uint64_t, uint64_t, double *) {}
     template <bool FULL, bool VEC>
     __device__ __forceinline__ src_d2 pair(uint64_t e, uint64_t n) const
     {
@@ -107,6 +122,10 @@ struct PhaseSource {
     uint32_t off[4];                       // first element of slab (a, b) at off[2 a + b]
     uint32_t has;                          // bit 2 a + b: the phase has a slab
     double *y64;
+    template <uint32_t TILE>
+    static constexpr uint32_t tile_lds_doubles() { return 0; }
+    template <uint32_t TILE>
+    __device__ __forceinline__ void begin_tile(uint64_t, uint64_t, double *) {}
     template <bool FULL, bool VEC>
     __device__ __forceinline__ src_d2 pair(uint64_t e, uint64_t n) const
     {
@@ -154,9 +173,9 @@ struct PhaseSource {
     }
 };
 
-// One output of a layer from its input value(s); e is the output's linear index (< n).
+// One output of an element-wise layer from its input value(s).
 template <int OP>
-__device__ __forceinline__ double layer_value(const LayerArgs &g, uint32_t e, double xa, double xb)
+__device__ __forceinline__ double layer_value(double xa, double xb)
 {
     switch (OP) {                                                     // compile-time
     case kLayerAdd: return xa + xb;
@@ -168,25 +187,7 @@ __device__ __forceinline__ double layer_value(const LayerArgs &g, uint32_t e, do
         const double u = 0.7978845608028654 * (xa + 0.044715 * x3);   // sqrt(2 / pi)
         return xa / (1.0 + exp(-2.0 * u));
     }
-    case kLayerGeluErf: return 0.5 * xa * (1.0 + erf(xa * 0.7071067811865476));
-    case kLayerNorm: {
-        uint32_t r, c;
-        divmod_u32(e, g.cols, g.inv_cols, r, c);
-        double v = (xa - g.stat[2 * (uint64_t)r]) * g.stat[2 * (uint64_t)r + 1];
-        if (g.gamma) v = v * g.gamma[c];
-        if (g.beta) v = v + g.beta[c];
-        return v;
-    }
-    default: {                                                        // softmax
-        uint32_t r, c, seen = g.cols;
-        divmod_u32(e, g.cols, g.inv_cols, r, c);
-        if (g.period) {
-            uint32_t q, rem;
-            divmod_u32(r, g.period, g.inv_period, q, rem);
-            seen = rem + 1u < g.cols ? rem + 1u : g.cols;
-        }
-        return c < seen ? exp(g.scale * xa - g.stat[2 * (uint64_t)r]) * g.stat[2 * (uint64_t)r + 1] : 0.0;
-    }
+    default: return 0.5 * xa * (1.0 + erf(xa * 0.7071067811865476));   // kLayerGeluErf
     }
 }
 
@@ -220,9 +221,53 @@ __device__ __forceinline__ double col_value(const LayerArgs &g, uint32_t c, doub
     return v;
 }
 
-template <int OP>
+template <int OP, bool TILE_STATS = false>
 struct LayerSource {
+    typedef __attribute__((address_space(3))) double lds_double;
     LayerArgs g;
+    lds_double *tile_stat = nullptr;       // TILE_STATS: statistics of rows tile_row0, tile_row0 + 1, ... of this tile
+    uint32_t tile_row0 = 0;
+    static_assert(!TILE_STATS || OP == kLayerNorm, "tile statistics are built for layer norm");
+    template <uint32_t TILE>
+    static constexpr uint32_t tile_lds_doubles() { return TILE_STATS ? 2 * kTileStatRows : 0; }
+
+    template <uint32_t TILE>
+    __device__ __forceinline__ void begin_tile(uint64_t e0, uint64_t n, double *lds)
+    {
+        if (!TILE_STATS) return;
+        static_assert(TILE / kTileStatMinCols + 2 <= kTileStatRows, "more rows per tile than the LDS array holds");
+        tile_stat = (lds_double *)lds;
+        if (e0 < n) {                                                // the same for the whole workgroup
+            const uint32_t e1 = (uint32_t)(e0 + TILE < n ? e0 + TILE : n);
+            uint32_t r_first, r_last, c;
+            divmod_u32((uint32_t)e0, g.cols, g.inv_cols, r_first, c);
+            divmod_u32(e1 - 1u, g.cols, g.inv_cols, r_last, c);
+            tile_row0 = r_first;
+            // row j of the tile goes to wave (j + rot) mod waves; rot differs between the tiles that share a
+            // compute unit, so that the wave with one row more is not always the one on the same SIMD
+            const uint32_t lane = threadIdx.x & 63u, waves = blockDim.x >> 6, t = (uint32_t)(e0 / TILE);
+            const uint32_t rot = (t + (t >> 5) + (t >> 8)) % waves;
+            for (uint32_t r = r_first + ((threadIdx.x >> 6) + waves - rot) % waves; r <= r_last; r += waves) {
+                const stat_d2 st = norm_row_stats(g.a + (uint64_t)r * g.cols, g.cols, g.eps, g.variant, lane);
+                if (lane == 0) {
+                    tile_stat[2 * (r - r_first)] = st.x;
+                    tile_stat[2 * (r - r_first) + 1] = st.y;
+                }
+            }
+        }
+        __syncthreads();
+    }
+    __device__ __forceinline__ src_d2 row_stat(uint32_t r) const
+    {
+        src_d2 st;
+        if (TILE_STATS) {
+            st.x = tile_stat[2 * (r - tile_row0)];
+            st.y = tile_stat[2 * (r - tile_row0) + 1];
+        } else {
+            st = *(const src_d2 *)(g.stat + 2 * (uint64_t)r);
+        }
+        return st;
+    }
     template <bool FULL, bool VEC>
     __device__ __forceinline__ src_d2 pair(uint64_t e, uint64_t n) const
     {
@@ -241,28 +286,32 @@ struct LayerSource {
             }
             return v;
         }
-        if (FULL && (OP == kLayerNorm || OP == kLayerSoftmax)) {
-            // both outputs exist: split the index once, one 16-byte load of the row statistics
-            // (a second one only when the pair straddles two rows)
+        if (OP == kLayerNorm || OP == kLayerSoftmax) {
+            // split the index once, one 16-byte load of the row statistics (a second one only when
+            // the pair straddles two rows); indices past the end are clamped to the last output so
+            // that the statistics they select exist, and their values replaced below
             uint32_t r0, c0;
-            divmod_u32((uint32_t)e, g.cols, g.inv_cols, r0, c0);
-            const bool wrap = c0 + 1u == g.cols;
-            const uint32_t r1 = wrap ? r0 + 1u : r0, c1 = wrap ? 0u : c0 + 1u;
-            const src_d2 s0 = *(const src_d2 *)(g.stat + 2 * (uint64_t)r0);
+            divmod_u32((uint32_t)(FULL || e < n ? e : n - 1), g.cols, g.inv_cols, r0, c0);
+            const bool has1 = FULL || e + 1 < n;
+            const bool wrap = has1 && c0 + 1u == g.cols;
+            const uint32_t r1 = wrap ? r0 + 1u : r0, c1 = has1 ? (wrap ? 0u : c0 + 1u) : c0;
+            const src_d2 s0 = row_stat(r0);
             src_d2 s1 = s0;
-            if (wrap) s1 = *(const src_d2 *)(g.stat + 2 * (uint64_t)r1);
+            if (wrap) s1 = row_stat(r1);
             src_d2 v;
             v.x = row_value<OP>(g, r0, c0, xa.x, s0);
             v.y = row_value<OP>(g, r1, c1, xa.y, s1);
+            if (!FULL) {
+                if (e >= n) v.x = 1.0;
+                if (e + 1 >= n) v.y = 1.0;
+            }
             return v;
         }
         src_d2 xb = {0.0, 0.0};
         if (OP == kLayerAdd) xb = PlainSource{g.b}.template pair<FULL, VEC>(e, n);
-        // indices past the end are clamped so that the row statistics they select exist
-        const uint32_t e0 = (uint32_t)(FULL || e < n ? e : n - 1), e1 = (uint32_t)(FULL || e + 1 < n ? e + 1 : n - 1);
         src_d2 v;
-        v.x = layer_value<OP>(g, e0, xa.x, xb.x);
-        v.y = layer_value<OP>(g, e1, xa.y, xb.y);
+        v.x = layer_value<OP>(xa.x, xb.x);
+        v.y = layer_value<OP>(xa.y, xb.y);
         if (!FULL) {
             if (e >= n) v.x = 1.0;
             if (e + 1 >= n) v.y = 1.0;

@@ -16,6 +16,9 @@ pytestmark = pytest.mark.gpu
 
 ADD, RELU, GELU_TANH, GELU_ERF, NORM, SOFTMAX = range(6)
 SHAPES = [(1, 1), (7, 333), (3, 8197), (200, 768), (37, 1280)]
+# layer norm takes its row statistics inside the fused kernel for rows of 64 to 2048 columns and in a pass of its
+# own otherwise: both sides of both limits, rows that straddle tiles, a ragged last tile
+NORM_SHAPES = SHAPES + [(301, 64), (100, 63), (41, 2048), (9, 2049), (5, 1024), (13, 1025)]
 
 
 @pytest.fixture(scope="module")
@@ -70,7 +73,7 @@ def test_elementwise_layers(G, shape, dense):
 
 
 @pytest.mark.parametrize("dense", [False, True])
-@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("shape", NORM_SHAPES)
 def test_layernorm(G, shape, dense):
     a, _, g = _inputs(shape, 50 + shape[1])
     a = a + 0.25
