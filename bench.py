@@ -76,15 +76,13 @@ def committed_traffic():
     return None
 
 
-def next_pow2(v: int) -> int:
-    return 1 << max(int(v) - 1, 0).bit_length()
-
-
 def thr_layer_from(stats_u64) -> tuple[int, int, int, int]:
-    """(thr_layer, n_flip, thr_flip, max_ulp64_diff) from the 68 integers of vt_threshold_stats: the smallest
-    power-of-two threshold, capped at 1/4 ulp, that covers every observed divergence of the pair."""
+    """(thr_layer, n_flip, thr_flip, max_ulp64_diff) from the 68 integers of vt_threshold_stats: the library's
+    rule (vt_thr_layer_from_stats), the smallest power-of-two threshold, capped at 1/4 ulp, that covers every
+    observed divergence of the pair."""
+    from paper_2403_09603_amd import vt_thr_layer_from_stats
     n_flip, thr_flip, max_diff = int(stats_u64[0]), int(stats_u64[1]), int(stats_u64[2])
-    return min(1 << 27, next_pow2(max(thr_flip, max_diff + 1, 1))), n_flip, thr_flip, max_diff
+    return vt_thr_layer_from_stats(thr_flip, max_diff), n_flip, thr_flip, max_diff
 
 
 def resnet50_conv_layers():
@@ -646,7 +644,7 @@ def leg_gpt2(b: Bench, si):
         for k in o:
             o[k].append(row[k])
     res["adaptive_threshold"] = {
-        "rule": "per op and layer: vt_threshold_stats over variants 0 and 1, thr_layer = min(2^27, next_pow2(max(thr_flip, "
+        "rule": "per op and layer: vt_threshold_stats over variants 0 and 1, thr_layer = vt_thr_layer_from_stats = min(2^27, next_pow2(max(thr_flip, "
                 "max_ulp64_diff + 1))) (guarantees replay on the observed pair); thr_flip is the paper's rule (flips only)",
         "by_op": {k: {"thr_layer_min": min(v["thr_layer"]), "thr_layer_max": max(v["thr_layer"]),
                       "thr_flip_max": max(v["thr_flip"]),

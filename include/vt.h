@@ -382,6 +382,19 @@ size_t vt_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int64_t batch
 uint32_t vt_thr_from_tau(double tau_ulp);
 
 /*
+ * Threshold for a layer from the statistics of its two variants (out[1] = thr_flip and out[2] =
+ * max_ulp64_diff of vt_threshold_stats), in the unit of vt_thr_from_tau (tau_ulp = thr * 2^-29):
+ * the smallest power of two that is at least thr_flip -- every output the two variants round
+ * differently is then logged, the aim of Algorithm "threshold" -- and larger than max_ulp64_diff,
+ * so that a value one party logs lies within the other party's band as well; never more than
+ * VT_THR_LAYER_MAX = 2^27 (1/4 ulp, the largest threshold of Method, "Reducing storage cost"), never
+ * less than 1.  Below the cap, the log written with this threshold replays without a mismatch on the
+ * observed pair.  A convention of this library, not the paper's search; host arithmetic only.
+ */
+#define VT_THR_LAYER_MAX (1u << 27)
+uint32_t vt_thr_layer_from_stats(uint64_t thr_flip, uint64_t max_ulp64_diff);
+
+/*
  * Introspection (host only, no counterpart in the paper): the workgroup tile and the split-K
  * factor vt_gemm_f64_round_log uses for a problem of this shape and A layout: transA is
  * VT_A_ROW_MAJOR (also the forward and input-gradient views of a convolution), VT_A_TRANSPOSED (also

@@ -101,6 +101,8 @@ def load_library():
     L.vt_workspace_bytes.argtypes = [cint, i64, i64, i64, i64]
     L.vt_thr_from_tau.restype = C.c_uint32
     L.vt_thr_from_tau.argtypes = [dbl]
+    L.vt_thr_layer_from_stats.restype = C.c_uint32
+    L.vt_thr_layer_from_stats.argtypes = [C.c_uint64, C.c_uint64]
     L.vt_gemm_plan.restype = cint
     L.vt_gemm_plan.argtypes = [cint, i64, i64, i64, i64, i64, i64, C.POINTER(cint), C.POINTER(cint), C.POINTER(cint)]
     L.vt_set_kernel_events.restype = cint
@@ -407,6 +409,13 @@ def vt_threshold_stats(y1: torch.Tensor, y2: torch.Tensor, out: torch.Tensor, st
     else:
         _check(load_library().vt_threshold_stats_br(_ptr(y1, torch.float64), _ptr(y2, torch.float64), y1.numel(),
                                                     int(b_r), _ptr(out), _stream(stream)), "vt_threshold_stats_br")
+
+
+VT_THR_LAYER_MAX = 1 << 27
+
+
+def vt_thr_layer_from_stats(thr_flip: int, max_ulp64_diff: int) -> int:
+    return int(load_library().vt_thr_layer_from_stats(int(thr_flip), int(max_ulp64_diff)))
 
 
 def vt_sha256_tree(data: torch.Tensor, chunk: int, digest: torch.Tensor, ws: torch.Tensor, stream=None):

@@ -319,6 +319,16 @@ uint32_t vt_thr_from_tau(double tau_ulp)
     return (uint32_t)std::ceil(std::ldexp(tau_ulp, 29));
 }
 
+uint32_t vt_thr_layer_from_stats(uint64_t thr_flip, uint64_t max_ulp64_diff)
+{
+    uint64_t need = thr_flip;
+    if (max_ulp64_diff >= need) need = max_ulp64_diff == UINT64_MAX ? UINT64_MAX : max_ulp64_diff + 1;
+    if (need >= VT_THR_LAYER_MAX) return VT_THR_LAYER_MAX;
+    uint32_t thr = 1;
+    while (thr < need) thr <<= 1;
+    return thr;
+}
+
 const char *vt_strerror(int code)
 {
     switch (code) {

@@ -7,6 +7,7 @@ count -- must be bit-exact against the oracle's round/log applied to the kernel'
 import numpy as np
 import pytest
 
+import paper_2403_09603_amd as vtlib
 import synth_inputs as si
 from oracle import vt_oracle as vo
 
@@ -57,9 +58,8 @@ def test_config1_tiny_gemm_and_auditor_replay(G):
     st = G.gpu_stats(r0["C64"], aud)
     so = vo.threshold_stats(r0["C64"], aud)
     assert st["n_flip"] == so["n_flip"] and st["thr_flip"] == so["thr_flip"] and np.array_equal(st["hist"], so["hist"])
-    need = max(st["thr_flip"], st["max_ulp64_diff"] + 1, 1)
-    thr = 1 << int(np.ceil(np.log2(need)))
-    assert thr <= 1 << 27
+    thr = vtlib.vt_thr_layer_from_stats(st["thr_flip"], st["max_ulp64_diff"])      # the library's rule
+    assert max(st["thr_flip"], st["max_ulp64_diff"] + 1) <= thr                # not capped at 1/4 ulp
     r = _check(G, A, B, tau=thr * 2.0 ** -29)
     y_aud = vo.round_replay(aud.ravel(), r["idx"], r["dir"])
     assert np.array_equal(_bits(y_aud), _bits(r["C32"].ravel()))
@@ -198,9 +198,8 @@ def test_planted_midpoint_gemm_flips_and_replay(G):
     aud = vo.gemm_f64(A, B, order=1)
     st = G.gpu_stats(r["C64"], aud)
     assert st["n_flip"] > 1000                               # the test is not vacuous
-    need = max(st["thr_flip"], st["max_ulp64_diff"] + 1)
-    thr = 1 << int(np.ceil(np.log2(need)))
-    assert thr <= 1 << 27
+    thr = vtlib.vt_thr_layer_from_stats(st["thr_flip"], st["max_ulp64_diff"])      # the library's rule
+    assert max(st["thr_flip"], st["max_ulp64_diff"] + 1) <= thr                # not capped at 1/4 ulp
     r = _check(G, A, B, tau=thr * 2.0 ** -29)
     plain = vo.round_replay(aud.ravel(), r["idx"][:0], np.zeros(1, np.uint32), count=0)
     assert (_bits(plain) != _bits(r["C32"].ravel())).sum() == st["n_flip"]

@@ -15,6 +15,7 @@ the trainer's log) must end with the trainer's FP32 bits.
 import numpy as np
 import pytest
 
+import paper_2403_09603_amd as vtlib
 import synth_inputs as si
 from oracle import vt_oracle as vo
 
@@ -106,9 +107,8 @@ def _audited_gemm(P, name, A, lda, sA, B, ldb, sB, bias, M, N, K, batch, ldc, sC
     so = vo.threshold_stats(t64.ravel(), a64.ravel())
     assert st["n_flip"] == so["n_flip"] and st["thr_flip"] == so["thr_flip"], name
     assert st["max_ulp64_diff"] == so["max_ulp64_diff"] and np.array_equal(st["hist"], so["hist"]), name
-    need = max(st["thr_flip"], st["max_ulp64_diff"] + 1, 1)
-    thr = 1 << int(np.ceil(np.log2(need)))
-    assert thr <= 1 << 27, (name, need)
+    thr = vtlib.vt_thr_layer_from_stats(st["thr_flip"], st["max_ulp64_diff"])      # the library's rule
+    assert max(st["thr_flip"], st["max_ulp64_diff"] + 1) <= thr, name                # not capped at 1/4 ulp
     tau = thr * 2.0 ** -29
     c32_t, c64_t2, log, cnt = P.gemm(A, lda, sA, B, ldb, sB, bias, M, N, K, batch, ldc, sC, out_elems, variant=0,
                                      tau=tau, **kw)
@@ -174,9 +174,8 @@ def _audited_layer(P, name, op, a, b, gamma, beta, rows, cols, **kw):
     for v64 in (t64, a64):
         assert np.all(np.abs(v64.cpu().numpy().reshape(rows, cols) - truth) <= tol), name
     st = P.stats(t64, a64)
-    need = max(st["thr_flip"], st["max_ulp64_diff"] + 1, 1)
-    thr = 1 << int(np.ceil(np.log2(need)))
-    assert thr <= 1 << 27, (name, need)
+    thr = vtlib.vt_thr_layer_from_stats(st["thr_flip"], st["max_ulp64_diff"])      # the library's rule
+    assert max(st["thr_flip"], st["max_ulp64_diff"] + 1) <= thr, name                # not capped at 1/4 ulp
     tau = thr * 2.0 ** -29
     y, t64b, log, cnt = run(0, tau)
     assert torch.equal(t64b, t64), name

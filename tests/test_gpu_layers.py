@@ -9,6 +9,7 @@ other order's values reproduces the trainer's FP32 outputs."""
 import numpy as np
 import pytest
 
+import paper_2403_09603_amd as vtlib
 import synth_inputs as si
 from oracle import vt_oracle as vo
 
@@ -150,9 +151,8 @@ def test_two_summation_orders_and_replay(G):
         st = G.gpu_stats(r0["y64"], r1["y64"])
         so = vo.threshold_stats(r0["y64"], r1["y64"])
         assert st["n_flip"] == so["n_flip"] and st["thr_flip"] == so["thr_flip"]
-        need = max(st["thr_flip"], st["max_ulp64_diff"] + 1, 1)
-        thr = 1 << int(np.ceil(np.log2(need)))
-        assert thr <= 1 << 27
+        thr = vtlib.vt_thr_layer_from_stats(st["thr_flip"], st["max_ulp64_diff"])      # the library's rule
+        assert max(st["thr_flip"], st["max_ulp64_diff"] + 1) <= thr                # not capped at 1/4 ulp
         tau = thr * 2.0 ** -29
         for dense in (False, True):
             t = G.gpu_layer(op, a, tau=tau, variant=0, dense=dense, **kw)
