@@ -158,8 +158,8 @@ def cpu_baseline(pool, workers, tau, M, N, K, rows_single):
     t0 = time.perf_counter()
     mism1 = _cpu_step_rows((0, rows_single, tau))
     dt1 = time.perf_counter() - t0
-    # all workers: one block of `rows_single` rows each (bounded sample: at most the whole batch)
-    M = min(M, workers * rows_single)
+    # all workers: one block of 2 * `rows_single` rows each (bounded sample: at most the whole batch)
+    M = min(M, workers * 2 * rows_single)
     edges = [M * i // workers for i in range(workers + 1)]
     t0 = time.perf_counter()
     mism = sum(pool.map(_cpu_step_rows, [(edges[i], edges[i + 1], tau) for i in range(workers)], chunksize=1))
@@ -322,7 +322,7 @@ def leg_config2(b: Bench, args, si):
         "roofline": {"bound": "mfma", "kernel": "gemm_round_planes_kernel (trainer, variant 0), the dominant kernel of the call",
                      "achieved": round(achieved, 3), "peak": FP64_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": r4(achieved / FP64_MFMA_PEAK_TFLOPS), "kernel_ms": r4(gemm_mean),
-                     "call": {"kernels": "gemm_round_planes_kernel + seg_count_kernel + seg_scan_kernel + compact_kernel",
+                     "call": {"kernels": "gemm_round_planes_kernel + compact_onepass_kernel",
                               "ms": r4(call_mean), "achieved": round(value, 3), "frac": r4(value / FP64_MFMA_PEAK_TFLOPS)},
                      "algorithmic_bytes": 8 * (M * K + K * N + N) + 4 * M * N + 2 * (M * ((N + 63) // 64) * 8),
                      "traffic": committed_traffic(),
