@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvt_hip.so")
 SOURCES = ["vt_gemm_shape_128x128.hip", "vt_gemm_shape_64x64.hip",
-           "vt_api.hip", "vt_round_kernels.hip", "vt_round_onepass.hip", "vt_round_dense.hip", "vt_layers.hip", "vt_hash.hip",
+           "vt_api.hip", "vt_round_kernels.hip", "vt_round_onepass.hip", "vt_round_dense.hip", "vt_round_rowwise.hip", "vt_layers.hip", "vt_hash.hip",
            "vt_gemm_kernels.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-ffp-contract=off",

@@ -623,10 +623,18 @@ int vt_layer_f64_round_log(const vt_layer *L, float *y, double *y64_debug, int v
     g.inv_period = g.period ? 1.0 / (double)g.period : 0.0;
     g.eps = L->eps;
     g.variant = variant;
-    g.tile_stats = vt::layer_tile_stats(L->op, (uint64_t)L->cols);
-    hipError_t e = vt::launch_layer_stats(g, (uint64_t)L->rows, s);
+    const bool rowwise = n && vt::rowwise_usable(L->op, (uint64_t)L->cols, log->dense != nullptr) &&
+                         vt::rowwise_bytes((uint64_t)L->rows) <= rl;
+    hipError_t e = rowwise ? hipSuccess : vt::launch_layer_stats(g, (uint64_t)L->rows, s);
     if (e != hipSuccess) return VT_ERR_HIP;
     const uint32_t k = k_of(log->b_r);
+    if (rowwise) {                          // a row at a time in registers: no statistics pass before it
+        mark_begin(s);
+        if (log->dense) e = vt::launch_rowwise_dense(g, (uint64_t)L->rows, thr, k, y, log->dense, log->count, (uint64_t *)ws, s);
+        else e = vt::launch_rowwise_onepass(g, (uint64_t)L->rows, thr, k, y, ws, vt::LogOut{log->idx, log->dir, log->cap, log->count}, s);
+        mark_end(s);
+        return hip_status(e);
+    }
     mark_begin(s);
     if (log->dense) e = vt::launch_layer_log_dense(g, n, thr, k, y, log->dense, log->count, (uint64_t *)ws, s);
     else e = vt::launch_layer_log_onepass(g, n, thr, k, y, ws, vt::LogOut{log->idx, log->dir, log->cap, log->count}, s);

@@ -89,27 +89,30 @@ struct LayerArgs {
     double inv_period;
     double eps;                   // layer norm, batch norm
     int variant;                  // summation order of the statistics
-    bool tile_stats;              // layer norm: the fused kernel computes the statistics of the rows of its own
-                                  // tile (layer_tile_stats()); `stat` is then not read
 };
-
-// Layer norm over rows of 64 to 2048 columns: a tile of the fused kernels (4096 or 5120 outputs) meets
-// at most kTileStatRows rows and reads little more than its own outputs to get their statistics, so
-// the separate statistics pass (a second read of the whole input from memory) is dropped: 2^28
-// values in rows of 1024, 0.99 -> 0.78 ms.  (Softmax is bound by its two exponentials per value, not
-// by memory: the same scheme measured slower there, 1.26 -> 1.50 ms, also with the exponentials
-// kept in LDS between the two phases, 1.98 ms.)
-constexpr uint32_t kTileStatMinCols = 64, kTileStatMaxCols = 2048, kTileStatRows = 84;
-inline bool layer_tile_stats(int op, uint64_t cols)
-{
-    return op == kLayerNorm && cols >= kTileStatMinCols && cols <= kTileStatMaxCols;
-}
 
 size_t layer_stat_bytes(uint64_t rows, uint64_t cols);
 // per-row statistics of layer norm / softmax, per-column statistics of batch norm into g.stat
-// (no-op for the element-wise layers and when g.tile_stats is set; batch norm also uses the scratch
-// that follows g.stat); g.variant selects the summation order
+// (no-op for the element-wise layers; batch norm also uses the scratch that follows g.stat);
+// g.variant selects the summation order
 hipError_t launch_layer_stats(const LayerArgs &g, uint64_t rows, hipStream_t s);
+// Layer norm and softmax a row at a time in registers (vt_round_rowwise.hip): one read of the input,
+// softmax with one exponential per value.  Rows of kRowwiseMinCols columns up to 2048 (packed log) or
+// 1024 (index-list log, whose entries wait in LDS); other row lengths take the statistics kernel and
+// the element-wise pass.  Same bits either way.
+constexpr uint32_t kRowwiseMinCols = 64, kRowwiseMaxColsDense = 2048, kRowwiseMaxColsSparse = 1024;
+bool rowwise_usable(int op, uint64_t cols, bool dense);
+size_t rowwise_bytes(uint64_t rows);      // scratch of launch_rowwise_onepass
+hipError_t launch_rowwise_dense(const LayerArgs &g, uint64_t rows, uint32_t thr, uint32_t k, float *y, uint8_t *tlog,
+                                uint64_t *n_logged, uint64_t *slots, hipStream_t s);
+hipError_t launch_rowwise_onepass(const LayerArgs &g, uint64_t rows, uint32_t thr, uint32_t k, float *y, void *ws,
+                                  const LogOut &log, hipStream_t s);
+// shared by the kernels that write the packed log: clear the spread counters (or *n_logged when
+// slots is null and n_logged is not) before the pass, fold them into *n_logged after it
+hipError_t launch_count_begin(uint64_t *slots, uint64_t *n_logged, hipStream_t s);
+hipError_t launch_count_end(const uint64_t *slots, uint64_t *n_logged, hipStream_t s);
+// shared by the single-pass index-list kernels: status words, error words, direction words, count
+hipError_t launch_onepass_init(uint64_t *st, uint32_t tiles, uint32_t *err, const LogOut &log, uint64_t n, hipStream_t s);
 hipError_t launch_layer_log_onepass(const LayerArgs &g, uint64_t n, uint32_t thr, uint32_t k, float *y, void *ws,
                                     const LogOut &log, hipStream_t s);
 hipError_t launch_layer_log_dense(const LayerArgs &g, uint64_t n, uint32_t thr, uint32_t k, float *y, uint8_t *tlog,

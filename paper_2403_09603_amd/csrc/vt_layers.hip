@@ -1,6 +1,6 @@
-// vt_layers.hip -- statistics that the fused layer + trainer-hook kernels read: per row for softmax,
-// and for layer norm when the rows are too long or too short for the fused kernel to compute them
-// tile by tile (one wavefront per row, vt_rowstats.h), per column for batch norm.
+// vt_layers.hip -- statistics that the element-wise fused layer + trainer-hook kernels read: per row
+// for layer norm and softmax over rows too long or too short for the row-at-a-time kernels of
+// vt_round_rowwise.hip (one wavefront per row, vt_rowstats.h), per column for batch norm.
 #include "vt_device.h"
 #include "vt_kernels.h"
 #include "vt_rowstats.h"
@@ -155,7 +155,7 @@ size_t layer_stat_bytes(uint64_t rows, uint64_t cols)
 
 hipError_t launch_layer_stats(const LayerArgs &g, uint64_t rows, hipStream_t s)
 {
-    if (rows == 0 || g.cols == 0 || g.tile_stats) return hipSuccess;
+    if (rows == 0 || g.cols == 0) return hipSuccess;
     const double eps = g.eps;
     const int variant = g.variant;
     if (g.op == kLayerBatchNorm || g.op == kLayerBatchNormRelu) {

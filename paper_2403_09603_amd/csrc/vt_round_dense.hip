@@ -146,15 +146,11 @@ __global__ __launch_bounds__(kWaves * 64) void round_log_dense_kernel(const Src 
                                                               uint8_t *__restrict__ tlog, uint64_t *__restrict__ slots)
 {
     __shared__ __attribute__((aligned(16))) uint8_t codes[kWaves][kChunk];
-    __shared__ __attribute__((aligned(16))) double tile_stat[Src::template tile_lds_doubles<kTile>() ? Src::template tile_lds_doubles<kTile>() : 1];
     const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
-    const uint64_t tile0 = (uint64_t)xcd_contiguous_tile() * kTile;
-    Src src = x;
-    src.template begin_tile<kTile>(tile0, n, tile_stat);
-    const uint64_t base = tile0 + (uint64_t)wv * kChunk;
+    const uint64_t base = (uint64_t)xcd_contiguous_tile() * kTile + (uint64_t)wv * kChunk;
     if (base >= n) return;
-    if (base + kChunk <= n) round_log_dense_chunk<true, VEC, K0>(src, n, thr, k, y, tlog, base, lane, codes[wv], slots);
-    else round_log_dense_chunk<false, VEC, K0>(src, n, thr, k, y, tlog, base, lane, codes[wv], slots);
+    if (base + kChunk <= n) round_log_dense_chunk<true, VEC, K0>(x, n, thr, k, y, tlog, base, lane, codes[wv], slots);
+    else round_log_dense_chunk<false, VEC, K0>(x, n, thr, k, y, tlog, base, lane, codes[wv], slots);
 }
 
 // Auditor: entry i of the packed log applied to x[i].
@@ -348,6 +344,19 @@ __global__ __launch_bounds__(1024) void count_partials_kernel(const uint32_t *__
 
 size_t dense_count_bytes() { return (size_t)kSlots * kSlotStride * 8; }
 
+hipError_t launch_count_begin(uint64_t *slots, uint64_t *n_logged, hipStream_t s)
+{
+    if (slots) zero_slots_kernel<<<1, kSlots, 0, s>>>(slots);
+    else if (n_logged) zero_u64_kernel<<<1, 1, 0, s>>>(n_logged);
+    return hipGetLastError();
+}
+
+hipError_t launch_count_end(const uint64_t *slots, uint64_t *n_logged, hipStream_t s)
+{
+    sum_slots_kernel<<<1, kSlots, 0, s>>>(slots, n_logged);
+    return hipGetLastError();
+}
+
 namespace {
 
 // `slots`: dense_count_bytes() of scratch, needed when n_logged is wanted
@@ -355,19 +364,9 @@ template <class Src>
 hipError_t launch_dense_from(const Src &src, bool vec, uint64_t n, uint32_t thr, uint32_t k, float *y, uint8_t *tlog,
                              uint64_t *n_logged, uint64_t *slots, hipStream_t s)
 {
-    if (n == 0 || !n_logged || !slots) {
-        if (n_logged) {
-            zero_u64_kernel<<<1, 1, 0, s>>>(n_logged);
-            const hipError_t e = hipGetLastError();
-            if (e != hipSuccess) return e;
-        }
-        if (n == 0) return hipSuccess;
-        slots = nullptr;
-    } else {
-        zero_slots_kernel<<<1, kSlots, 0, s>>>(slots);
-        const hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
+    if (n == 0 || !n_logged) slots = nullptr;              // nothing to count, or nobody asks
+    const hipError_t e0 = launch_count_begin(slots, n_logged, s);
+    if (e0 != hipSuccess || n == 0) return e0;
     const uint64_t blocks = (n + kTile - 1) / kTile;
     const dim3 grid((uint32_t)blocks), block(kWaves * 64);
     if (vec && k == 0) round_log_dense_kernel<true, true, Src><<<grid, block, 0, s>>>(src, n, thr, k, y, tlog, slots);
@@ -377,10 +376,7 @@ hipError_t launch_dense_from(const Src &src, bool vec, uint64_t n, uint32_t thr,
         else round_log_dense_kernel<false, false, Src><<<grid, block, 0, s>>>(src, n, thr, k, y, tlog, slots);
     } else return hipErrorInvalidValue;
     hipError_t e = hipGetLastError();
-    if (e == hipSuccess && slots) {
-        sum_slots_kernel<<<1, kSlots, 0, s>>>(slots, n_logged);
-        e = hipGetLastError();
-    }
+    if (e == hipSuccess && slots) e = launch_count_end(slots, n_logged, s);
     return e;
 }
 
@@ -424,11 +420,8 @@ hipError_t launch_layer_log_dense(const LayerArgs &g, uint64_t n, uint32_t thr, 
     case kLayerRelu: return launch_dense_from(LayerSource<kLayerRelu>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
     case kLayerGeluTanh: return launch_dense_from(LayerSource<kLayerGeluTanh>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
     case kLayerGeluErf: return launch_dense_from(LayerSource<kLayerGeluErf>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
-    case kLayerNorm:
-        if (g.tile_stats) return launch_dense_from(LayerSource<kLayerNorm, true>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
-        return launch_dense_from(LayerSource<kLayerNorm>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
-    case kLayerSoftmax:
-        return launch_dense_from(LayerSource<kLayerSoftmax>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
+    case kLayerNorm: return launch_dense_from(LayerSource<kLayerNorm>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
+    case kLayerSoftmax: return launch_dense_from(LayerSource<kLayerSoftmax>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
     case kLayerBatchNorm: return launch_dense_from(LayerSource<kLayerBatchNorm>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
     case kLayerBatchNormRelu: return launch_dense_from(LayerSource<kLayerBatchNormRelu>{g}, true, n, thr, k, y, tlog, n_logged, slots, s);
     default: return hipErrorInvalidValue;

@@ -117,19 +117,16 @@ __global__ __launch_bounds__(kThreads) void round_log_onepass_kernel(const Src x
 {
     __shared__ uint16_t ent[kWaves][kWaveChunk];  // per wave: position in its chunk | direction << 15
     __shared__ uint32_t s_wc[kWaves < 8 ? 8 : kWaves];   // logged outputs per wave (scanner: its 8 words of scratch)
-    __shared__ __attribute__((aligned(16))) double tile_stat[Src::template tile_lds_doubles<kTile>() ? Src::template tile_lds_doubles<kTile>() : 1];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wv = tid >> 6;
     if (blockIdx.x == 0) {
         if (tid < kScannerThreads) scanner(st, tiles, err, count, s_wc);
         return;
     }
     const uint32_t tile = blockIdx.x - 1;
-    Src src = x;
-    src.template begin_tile<kTile>((uint64_t)tile * kTile, n, tile_stat);
     const uint64_t wbase = (uint64_t)tile * kTile + (uint64_t)wv * kWaveChunk;
     const uint32_t wcount = ((uint64_t)(tile + 1) * kTile <= n)
-                                ? round_rows<true, K0>(src, n, thr, k, y, wbase, lane, ent[wv])
-                                : round_rows<false, K0>(src, n, thr, k, y, wbase, lane, ent[wv]);
+                                ? round_rows<true, K0>(x, n, thr, k, y, wbase, lane, ent[wv])
+                                : round_rows<false, K0>(x, n, thr, k, y, wbase, lane, ent[wv]);
     if (lane == 0) s_wc[wv] = wcount;
     __syncthreads();
     // Only wave 0 goes on: it alone waits for the tile's place in the log, so the other three
@@ -142,51 +139,7 @@ __global__ __launch_bounds__(kThreads) void round_log_onepass_kernel(const Src x
     const uint32_t c = pre[kWaves];
     uint64_t off;
     if (!tile_offset(st, tile, c, err, lane, off) || c == 0) return;
-    const uint64_t end = off + c < cap ? off + c : cap;
-    // entries leave 256 at a time, aligned in log position: four consecutive entries per lane (one
-    // 16-byte index store where the log is aligned), their direction bits gathered over eight lanes
-    // into whole 32-bit words (the words were cleared beforehand, so partial ones are OR-ed)
-    const bool wide = ((uintptr_t)idx & 15u) == 0;
-    for (uint64_t G = off & ~255ull; G < end; G += 256) {
-        const uint64_t p0 = G + 4u * lane;
-        uint32_t iv[4] = {0, 0, 0, 0}, nib_v = 0, nib_d = 0;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint64_t p = p0 + j;
-            if (p >= off && p < end) {
-                const uint32_t q = (uint32_t)(p - off);
-                uint32_t chunk = 0, start = 0;
-#pragma unroll
-                for (int w = 1; w < kWaves; ++w)
-                    if (q >= pre[w]) { chunk = w; start = pre[w]; }
-                const uint32_t e = ent[chunk][q - start];
-                iv[j] = (uint32_t)((uint64_t)tile * kTile + chunk * kWaveChunk + (e & 0x3FFu));
-                nib_v |= 1u << j;
-                nib_d |= (e >> 15) << j;
-            }
-        }
-        if (wide && nib_v == 0xFu) {
-            typedef uint32_t u4 __attribute__((ext_vector_type(4)));
-            u4 o;
-            o.x = iv[0]; o.y = iv[1]; o.z = iv[2]; o.w = iv[3];
-            __builtin_nontemporal_store(o, (u4 *)(idx + p0));
-        } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if ((nib_v >> j) & 1u) __builtin_nontemporal_store(iv[j], idx + p0 + j);
-        }
-        uint32_t vv = nib_v << (4u * (lane & 7u)), dv = nib_d << (4u * (lane & 7u));
-#pragma unroll
-        for (int o = 1; o < 8; o <<= 1) {
-            vv |= (uint32_t)__shfl_xor((int)vv, o, 64);
-            dv |= (uint32_t)__shfl_xor((int)dv, o, 64);
-        }
-        if ((lane & 7u) == 0 && vv) {
-            uint32_t *wp = dir + (G >> 5) + (lane >> 3);
-            if (vv == 0xFFFFFFFFu) *wp = dv;
-            else if (dv) atomicOr(wp, dv);
-        }
-    }
+    emit_tile_entries<kWaves>(&ent[0][0], kWaveChunk, 0x3FFu, pre, (uint64_t)tile * kTile, kWaveChunk, off, cap, idx, dir, lane);
 }
 
 // Round only (threshold 0: nothing can be logged, the count is 0).  No scan, no status words: the
@@ -245,6 +198,20 @@ bool onepass_usable(const double *x, const float *y)
     return ((uintptr_t)x % 16 == 0) && ((uintptr_t)y % 8 == 0);
 }
 
+// zeroes the status words of `tiles` tiles, the error words, the direction words that n outputs can
+// fill, and (when there are no tiles) the count
+hipError_t launch_onepass_init(uint64_t *st, uint32_t tiles, uint32_t *err, const LogOut &log, uint64_t n, hipStream_t s)
+{
+    const uint64_t stored = log.cap < n ? log.cap : n;
+    const uint64_t dir_words = (stored + 31) / 32;
+    const uint64_t work = tiles > dir_words ? tiles : dir_words;
+    uint32_t blocks = (uint32_t)((work + 1023) / 1024);
+    if (blocks < 1) blocks = 1;
+    if (blocks > 4096) blocks = 4096;
+    onepass_init_kernel<<<blocks, 256, 0, s>>>(st, tiles, err, log.dir, dir_words, log.count);
+    return hipGetLastError();
+}
+
 namespace {
 
 template <class Src>
@@ -254,14 +221,7 @@ hipError_t launch_onepass_from(const Src &src, uint64_t n, uint32_t thr, uint32_
     const uint32_t tiles = (uint32_t)((n + kTile - 1) / kTile);
     uint64_t *st = (uint64_t *)ws;
     uint32_t *err = (uint32_t *)((char *)ws + ((uint64_t)tiles * 8 + 255) / 256 * 256);
-    const uint64_t stored = log.cap < n ? log.cap : n;
-    const uint64_t dir_words = (stored + 31) / 32;
-    const uint64_t work = tiles > dir_words ? tiles : dir_words;
-    uint32_t blocks = (uint32_t)((work + 1023) / 1024);
-    if (blocks < 1) blocks = 1;
-    if (blocks > 4096) blocks = 4096;
-    onepass_init_kernel<<<blocks, 256, 0, s>>>(st, tiles, err, log.dir, dir_words, log.count);
-    hipError_t e = hipGetLastError();
+    hipError_t e = launch_onepass_init(st, tiles, err, log, n, s);
     if (e != hipSuccess || tiles == 0) return e;
     if (k == 0)
         round_log_onepass_kernel<true, Src><<<tiles + 1, kThreads, 0, s>>>(src, n, thr, k, y, st, tiles, err, log.idx,
@@ -311,11 +271,8 @@ hipError_t launch_layer_log_onepass(const LayerArgs &g, uint64_t n, uint32_t thr
     case kLayerRelu: return launch_onepass_from(LayerSource<kLayerRelu>{g}, n, thr, k, y, ws, log, s);
     case kLayerGeluTanh: return launch_onepass_from(LayerSource<kLayerGeluTanh>{g}, n, thr, k, y, ws, log, s);
     case kLayerGeluErf: return launch_onepass_from(LayerSource<kLayerGeluErf>{g}, n, thr, k, y, ws, log, s);
-    case kLayerNorm:
-        if (g.tile_stats) return launch_onepass_from(LayerSource<kLayerNorm, true>{g}, n, thr, k, y, ws, log, s);
-        return launch_onepass_from(LayerSource<kLayerNorm>{g}, n, thr, k, y, ws, log, s);
-    case kLayerSoftmax:
-        return launch_onepass_from(LayerSource<kLayerSoftmax>{g}, n, thr, k, y, ws, log, s);
+    case kLayerNorm: return launch_onepass_from(LayerSource<kLayerNorm>{g}, n, thr, k, y, ws, log, s);
+    case kLayerSoftmax: return launch_onepass_from(LayerSource<kLayerSoftmax>{g}, n, thr, k, y, ws, log, s);
     case kLayerBatchNorm: return launch_onepass_from(LayerSource<kLayerBatchNorm>{g}, n, thr, k, y, ws, log, s);
     case kLayerBatchNormRelu: return launch_onepass_from(LayerSource<kLayerBatchNormRelu>{g}, n, thr, k, y, ws, log, s);
     default: return hipErrorInvalidValue;

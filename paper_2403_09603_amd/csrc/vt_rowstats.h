@@ -1,12 +1,12 @@
 // vt_rowstats.h -- statistics of one row of a row-wise layer (layer norm, softmax) by one wavefront:
 // two sweeps over the row (the second one hits the cache), eight loads in flight per lane, FP64
-// throughout.  Shared by the stand-alone statistics kernels and by the fused layer-norm kernels
-// that compute the statistics of the rows of their own tile.
+// throughout.  The row-at-a-time kernels (vt_round_rowwise.hip) add up in the same order from
+// registers, so a row's statistics have the same bits whichever kernel takes it.
 //
-// Summation order: the row is cut into chunks of 512 columns; lane l owns columns l, l + 64, ...,
-// l + 448 of each chunk and adds them to its partial sum chunk by chunk (variant 0: ascending
-// columns, variant 1: descending), then the 64 partial sums are combined by a fixed butterfly
-// (variant 0: strides 32, 16, ..., 1; variant 1: strides 1, 2, ..., 32).  Both orders are fixed, so
+// Summation order: lane l owns the column pairs (2l, 2l + 1), (128 + 2l, 128 + 2l + 1), ... of the
+// row and adds them to its partial sum one after the other (variant 0: ascending columns, variant 1:
+// descending), then the 64 partial sums are combined by a fixed butterfly (variant 0: strides 32,
+// 16, ..., 1; variant 1: strides 1, 2, ..., 32).  Both orders are fixed, so
 // a given variant always returns the same bits; the two variants differ in their low bits the
 // way two GPU types do.
 #pragma once
@@ -40,27 +40,38 @@ __device__ __forceinline__ double wave_max(double v)
     return v;
 }
 
-constexpr uint32_t kRowInFlight = 8, kRowChunkCols = 64 * kRowInFlight;
+constexpr uint32_t kRowInFlight = 8, kRowChunkCols = 128 * kRowInFlight;
 
 // Calls fold(column, value) for every column c < lim of the row that belongs to this lane, in the
-// variant's order; `load` maps a column to the value to accumulate.
-template <class Load, class Fold>
-__device__ __forceinline__ void row_sweep(uint32_t lim, uint32_t lane, int variant, Load load, Fold fold)
+// variant's order.  Rows that start on a 16-byte boundary are read two values per load.
+template <class Fold>
+__device__ __forceinline__ void row_sweep(const double *__restrict__ xr, uint32_t lim, uint32_t lane, int variant, Fold fold)
 {
+    const bool aligned = ((uintptr_t)xr & 15u) == 0;                 // the same for the whole wave
     const uint32_t chunks = (lim + kRowChunkCols - 1) / kRowChunkCols;
     for (uint32_t i = 0; i < chunks; ++i) {
-        const uint32_t c0 = (variant ? chunks - 1 - i : i) * kRowChunkCols + lane;
-        double v[kRowInFlight];
-        bool in[kRowInFlight];
+        const uint32_t c0 = (variant ? chunks - 1 - i : i) * kRowChunkCols + 2u * lane;
+        stat_d2 v[kRowInFlight];
 #pragma unroll
         for (uint32_t u = 0; u < kRowInFlight; ++u) {
-            const uint32_t c = c0 + 64u * (variant ? kRowInFlight - 1 - u : u);
-            in[u] = c < lim;
-            v[u] = in[u] ? load(c) : 0.0;
+            const uint32_t c = c0 + 128u * (variant ? kRowInFlight - 1 - u : u);
+            if (aligned && c + 1 < lim) v[u] = *(const stat_d2 *)(xr + c);
+            else {
+                v[u].x = c < lim ? xr[c] : 0.0;
+                v[u].y = c + 1 < lim ? xr[c + 1] : 0.0;
+            }
         }
 #pragma unroll
-        for (uint32_t u = 0; u < kRowInFlight; ++u)
-            if (in[u]) fold(c0 + 64u * (variant ? kRowInFlight - 1 - u : u), v[u]);
+        for (uint32_t u = 0; u < kRowInFlight; ++u) {
+            const uint32_t c = c0 + 128u * (variant ? kRowInFlight - 1 - u : u);
+            if (variant == 0) {
+                if (c < lim) fold(c, v[u].x);
+                if (c + 1 < lim) fold(c + 1, v[u].y);
+            } else {
+                if (c + 1 < lim) fold(c + 1, v[u].y);
+                if (c < lim) fold(c, v[u].x);
+            }
+        }
     }
 }
 
@@ -69,10 +80,10 @@ __device__ __forceinline__ stat_d2 norm_row_stats(const double *__restrict__ xr,
                                                   uint32_t lane)
 {
     double s = 0.0;
-    row_sweep(cols, lane, variant, [&](uint32_t c) { return xr[c]; }, [&](uint32_t, double v) { s = s + v; });
+    row_sweep(xr, cols, lane, variant, [&](uint32_t, double v) { s = s + v; });
     const double mean = wave_add(s, variant) / (double)cols;
     double q = 0.0;
-    row_sweep(cols, lane, variant, [&](uint32_t c) { return xr[c]; }, [&](uint32_t, double v) { const double d = v - mean; q = q + d * d; });
+    row_sweep(xr, cols, lane, variant, [&](uint32_t, double v) { const double d = v - mean; q = q + d * d; });
     stat_d2 st;
     st.x = mean;
     st.y = 1.0 / sqrt(wave_add(q, variant) / (double)cols + eps);
@@ -84,10 +95,10 @@ __device__ __forceinline__ stat_d2 softmax_row_stats(const double *__restrict__ 
                                                      uint32_t lane)
 {
     double m = -INFINITY;
-    row_sweep(seen, lane, 0, [&](uint32_t c) { return scale * xr[c]; }, [&](uint32_t, double z) { m = z > m ? z : m; });
+    row_sweep(xr, seen, lane, 0, [&](uint32_t, double v) { const double z = scale * v; m = z > m ? z : m; });
     m = wave_max(m);
     double s = 0.0;
-    row_sweep(seen, lane, variant, [&](uint32_t c) { return xr[c]; }, [&](uint32_t, double v) { s = s + exp(scale * v - m); });
+    row_sweep(xr, seen, lane, variant, [&](uint32_t, double v) { s = s + exp(scale * v - m); });
     stat_d2 st;
     st.x = m;
     st.y = 1.0 / wave_add(s, variant);

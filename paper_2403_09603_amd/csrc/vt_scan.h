@@ -143,6 +143,64 @@ __device__ __forceinline__ bool tile_offset(uint64_t *__restrict__ st, uint32_t 
     }
 }
 
+// Emission of a tile's entries by one wave.  The tile is WAVES chunks of `chunk_elems` consecutive
+// outputs starting at output `first`; chunk w holds pre[w + 1] - pre[w] entries at ent + w * pitch, in
+// output order, each the output's position in its chunk (bits 0 .. 14, under pos_mask) and its
+// direction (bit 15).  The entries go to log positions off .. off + pre[WAVES] - 1 (those below `cap`),
+// 256 at a time, aligned in log position: four consecutive entries per lane (one 16-byte index store
+// where the log is aligned), their direction bits gathered over eight lanes into whole 32-bit words
+// (the words were cleared beforehand, so partial ones are OR-ed).
+template <int WAVES>
+__device__ __forceinline__ void emit_tile_entries(const uint16_t *__restrict__ ent, uint32_t pitch, uint32_t pos_mask,
+                                                  const uint32_t (&pre)[WAVES + 1], uint64_t first, uint32_t chunk_elems,
+                                                  uint64_t off, uint64_t cap, uint32_t *__restrict__ idx,
+                                                  uint32_t *__restrict__ dir, uint32_t lane)
+{
+    const uint32_t c = pre[WAVES];
+    const uint64_t end = off + c < cap ? off + c : cap;
+    const bool wide = ((uintptr_t)idx & 15u) == 0;
+    for (uint64_t G = off & ~255ull; G < end; G += 256) {
+        const uint64_t p0 = G + 4u * lane;
+        uint32_t iv[4] = {0, 0, 0, 0}, nib_v = 0, nib_d = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint64_t p = p0 + j;
+            if (p >= off && p < end) {
+                const uint32_t q = (uint32_t)(p - off);
+                uint32_t chunk = 0, start = 0;
+#pragma unroll
+                for (int w = 1; w < WAVES; ++w)
+                    if (q >= pre[w]) { chunk = w; start = pre[w]; }
+                const uint32_t e = ent[chunk * pitch + (q - start)];
+                iv[j] = (uint32_t)(first + (uint64_t)chunk * chunk_elems + (e & pos_mask));
+                nib_v |= 1u << j;
+                nib_d |= (e >> 15) << j;
+            }
+        }
+        if (wide && nib_v == 0xFu) {
+            typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+            u4 o;
+            o.x = iv[0]; o.y = iv[1]; o.z = iv[2]; o.w = iv[3];
+            __builtin_nontemporal_store(o, (u4 *)(idx + p0));
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if ((nib_v >> j) & 1u) __builtin_nontemporal_store(iv[j], idx + p0 + j);
+        }
+        uint32_t vv = nib_v << (4u * (lane & 7u)), dv = nib_d << (4u * (lane & 7u));
+#pragma unroll
+        for (int o = 1; o < 8; o <<= 1) {
+            vv |= (uint32_t)__shfl_xor((int)vv, o, 64);
+            dv |= (uint32_t)__shfl_xor((int)dv, o, 64);
+        }
+        if ((lane & 7u) == 0 && vv) {
+            uint32_t *wp = dir + (G >> 5) + (lane >> 3);
+            if (vv == 0xFFFFFFFFu) *wp = dv;
+            else if (dv) atomicOr(wp, dv);
+        }
+    }
+}
+
 }  // namespace
 
 }  // namespace vt

@@ -2,16 +2,9 @@
 // memory, or an element-wise / row-wise layer evaluated on the fly so that its FP64 output never
 // goes to memory (residual add, ReLU, GELU, layer norm, softmax: the non-GEMM layers of a
 // transformer block, each an "intermediate computation" whose output the method rounds).
-//
-// A source has pair(e, n) (two neighbouring values), keep(e, n, v) (an optional FP64 copy) and
-// begin_tile<TILE>(e0, n, lds): called by every thread of a tile workgroup before the first pair()
-// of the TILE outputs from e0 on, with tile_lds_doubles<TILE>() doubles of LDS.  Only the row-wise
-// layers use it: a layer-norm workgroup computes the statistics of the rows its tile meets, one
-// wavefront per row.
 #pragma once
 #include "vt_device.h"
 #include "vt_kernels.h"
-#include "vt_rowstats.h"
 
 #include <math.h>
 
@@ -23,10 +16,6 @@ typedef double src_d2 __attribute__((ext_vector_type(2)));
 // a value that is never logged.
 struct PlainSource {
     const double *x;
-    template <uint32_t TILE>
-    static constexpr uint32_t tile_lds_doubles() { return 0; }
-    template <uint32_t TILE>
-    __device__ __forceinline__ void begin_tile(uint64_t, uint64_t, double *) {}
     template <bool FULL, bool VEC>
     __device__ __forceinline__ src_d2 pair(uint64_t e, uint64_t n) const
     {
@@ -55,10 +44,6 @@ struct SplitKSource {
     uint32_t ncols;
     double inv_ncols;
     double *y64;
-    template <uint32_t TILE>
-    static constexpr uint32_t tile_lds_doubles() { return 0; }
-    template <uint32_t TILE>
-    __device__ __forceinline__ void begin_tile(uint64_t, uint64_t, double *) {}
     template <bool FULL, bool VEC>
     __device__ __forceinline__ src_d2 pair(uint64_t e, uint64_t n) const
     {
@@ -122,10 +107,6 @@ struct PhaseSource {
     uint32_t off[4];                       // first element of slab (a, b) at off[2 a + b]
     uint32_t has;                          // bit 2 a + b: the phase has a slab
     double *y64;
-    template <uint32_t TILE>
-    static constexpr uint32_t tile_lds_doubles() { return 0; }
-    template <uint32_t TILE>
-    __device__ __forceinline__ void begin_tile(uint64_t, uint64_t, double *) {}
     template <bool FULL, bool VEC>
     __device__ __forceinline__ src_d2 pair(uint64_t e, uint64_t n) const
     {
@@ -221,53 +202,9 @@ __device__ __forceinline__ double col_value(const LayerArgs &g, uint32_t c, doub
     return v;
 }
 
-template <int OP, bool TILE_STATS = false>
+template <int OP>
 struct LayerSource {
-    typedef __attribute__((address_space(3))) double lds_double;
     LayerArgs g;
-    lds_double *tile_stat = nullptr;       // TILE_STATS: statistics of rows tile_row0, tile_row0 + 1, ... of this tile
-    uint32_t tile_row0 = 0;
-    static_assert(!TILE_STATS || OP == kLayerNorm, "tile statistics are built for layer norm");
-    template <uint32_t TILE>
-    static constexpr uint32_t tile_lds_doubles() { return TILE_STATS ? 2 * kTileStatRows : 0; }
-
-    template <uint32_t TILE>
-    __device__ __forceinline__ void begin_tile(uint64_t e0, uint64_t n, double *lds)
-    {
-        if (!TILE_STATS) return;
-        static_assert(TILE / kTileStatMinCols + 2 <= kTileStatRows, "more rows per tile than the LDS array holds");
-        tile_stat = (lds_double *)lds;
-        if (e0 < n) {                                                // the same for the whole workgroup
-            const uint32_t e1 = (uint32_t)(e0 + TILE < n ? e0 + TILE : n);
-            uint32_t r_first, r_last, c;
-            divmod_u32((uint32_t)e0, g.cols, g.inv_cols, r_first, c);
-            divmod_u32(e1 - 1u, g.cols, g.inv_cols, r_last, c);
-            tile_row0 = r_first;
-            // row j of the tile goes to wave (j + rot) mod waves; rot differs between the tiles that share a
-            // compute unit, so that the wave with one row more is not always the one on the same SIMD
-            const uint32_t lane = threadIdx.x & 63u, waves = blockDim.x >> 6, t = (uint32_t)(e0 / TILE);
-            const uint32_t rot = (t + (t >> 5) + (t >> 8)) % waves;
-            for (uint32_t r = r_first + ((threadIdx.x >> 6) + waves - rot) % waves; r <= r_last; r += waves) {
-                const stat_d2 st = norm_row_stats(g.a + (uint64_t)r * g.cols, g.cols, g.eps, g.variant, lane);
-                if (lane == 0) {
-                    tile_stat[2 * (r - r_first)] = st.x;
-                    tile_stat[2 * (r - r_first) + 1] = st.y;
-                }
-            }
-        }
-        __syncthreads();
-    }
-    __device__ __forceinline__ src_d2 row_stat(uint32_t r) const
-    {
-        src_d2 st;
-        if (TILE_STATS) {
-            st.x = tile_stat[2 * (r - tile_row0)];
-            st.y = tile_stat[2 * (r - tile_row0) + 1];
-        } else {
-            st = *(const src_d2 *)(g.stat + 2 * (uint64_t)r);
-        }
-        return st;
-    }
     template <bool FULL, bool VEC>
     __device__ __forceinline__ src_d2 pair(uint64_t e, uint64_t n) const
     {
@@ -295,9 +232,9 @@ struct LayerSource {
             const bool has1 = FULL || e + 1 < n;
             const bool wrap = has1 && c0 + 1u == g.cols;
             const uint32_t r1 = wrap ? r0 + 1u : r0, c1 = has1 ? (wrap ? 0u : c0 + 1u) : c0;
-            const src_d2 s0 = row_stat(r0);
+            const src_d2 s0 = *(const src_d2 *)(g.stat + 2 * (uint64_t)r0);
             src_d2 s1 = s0;
-            if (wrap) s1 = row_stat(r1);
+            if (wrap) s1 = *(const src_d2 *)(g.stat + 2 * (uint64_t)r1);
             src_d2 v;
             v.x = row_value<OP>(g, r0, c0, xa.x, s0);
             v.y = row_value<OP>(g, r1, c1, xa.y, s1);

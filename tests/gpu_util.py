@@ -217,8 +217,10 @@ def gpu_gemm_dense(A, B, *, transA=False, transB=False, alpha=1.0, bias=None, ta
 
 
 def gpu_layer(op, a, b=None, gamma=None, beta=None, *, eps=1e-5, scale=1.0, causal_period=0, tau=0.0, variant=0,
-              dense=False, b_r=32):
-    """Fused layer + trainer hook.  a (and b): 2-D numpy arrays.  Returns y32, y64 and the log."""
+              dense=False, b_r=32, want_y64=True, cap=None):
+    """Fused layer + trainer hook.  a (and b): 2-D numpy arrays.  Returns y32, y64 (unless want_y64 is
+    False: the call then gets no FP64 debug buffer, as in the benchmarks) and the log (index list of
+    capacity `cap`, default one entry per output)."""
     a = np.ascontiguousarray(a, np.float64)
     rows, cols = a.shape
     n = rows * cols
@@ -228,17 +230,20 @@ def gpu_layer(op, a, b=None, gamma=None, beta=None, *, eps=1e-5, scale=1.0, caus
     be = dev(np.ascontiguousarray(beta, np.float64)) if beta is not None else None
     y = torch.full((max(n, 1),), float("nan"), dtype=torch.float32, device=DEV)
     y64 = torch.full((max(n, 1),), float("nan"), dtype=torch.float64, device=DEV)
-    log = vt.alloc_dense_log(n) if dense else vt.alloc_log(n)
+    log = vt.alloc_dense_log(n) if dense else vt.alloc_log(n if cap is None else cap)
     log.b_r = b_r
     ws = vt.alloc_workspace(vt.vt_workspace_bytes(vt.VT_OP_LAYER_ROUND_LOG, rows, cols))
-    vt.vt_layer_f64_round_log(op, ad, bd, gd, be, rows, cols, y, y64, variant, tau, log, ws, eps=eps, scale=scale,
-                              causal_period=causal_period)
+    vt.vt_layer_f64_round_log(op, ad, bd, gd, be, rows, cols, y, y64 if want_y64 else None, variant, tau, log, ws, eps=eps,
+                              scale=scale, causal_period=causal_period)
     torch.cuda.synchronize()
     cnt = int(log.count.item())
-    out = {"y32": y.cpu().numpy()[:n].reshape(rows, cols), "y64": y64.cpu().numpy()[:n].reshape(rows, cols), "count": cnt}
+    out = {"y32": y.cpu().numpy()[:n].reshape(rows, cols), "count": cnt}
+    if want_y64:
+        out["y64"] = y64.cpu().numpy()[:n].reshape(rows, cols)
     if dense:
         out["tlog"] = log.dense.cpu().numpy()[:(n + 4) // 5].copy()
     else:
-        out["idx"] = u32(log.idx)[:cnt].copy()
-        out["dir"] = u32(log.dir)[:(cnt + 31) // 32].copy()
+        stored = cnt if cap is None else min(cnt, cap)
+        out["idx"] = u32(log.idx)[:stored].copy()
+        out["dir"] = u32(log.dir)[:(stored + 31) // 32].copy()
     return out

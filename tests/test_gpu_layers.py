@@ -17,9 +17,12 @@ pytestmark = pytest.mark.gpu
 
 ADD, RELU, GELU_TANH, GELU_ERF, NORM, SOFTMAX = range(6)
 SHAPES = [(1, 1), (7, 333), (3, 8197), (200, 768), (37, 1280)]
-# layer norm takes its row statistics inside the fused kernel for rows of 64 to 2048 columns and in a pass of its
-# own otherwise: both sides of both limits, rows that straddle tiles, a ragged last tile
-NORM_SHAPES = SHAPES + [(301, 64), (100, 63), (41, 2048), (9, 2049), (5, 1024), (13, 1025)]
+# layer norm and softmax over rows of 64 to 2048 columns (1024 with the index-list log) are computed a row at a
+# time in registers, five rows per wave, other row lengths by a statistics pass and the element-wise pass: both
+# sides of every limit, row counts that leave a wave or a workgroup partly empty, odd row lengths (rows that
+# start off a 16-byte boundary)
+ROW_SHAPES = [(301, 64), (100, 63), (41, 2048), (9, 2049), (5, 1024), (13, 1025), (23, 512), (11, 513), (7, 127), (6, 129)]
+NORM_SHAPES = SHAPES + ROW_SHAPES
 
 
 @pytest.fixture(scope="module")
@@ -101,7 +104,8 @@ def test_layernorm(G, shape, dense):
 
 @pytest.mark.parametrize("dense", [False, True])
 @pytest.mark.parametrize("shape,period", [((1, 1), 0), ((7, 333), 0), ((24, 200), 8), ((300, 100), 100), ((64, 1024), 0),
-                                          ((3, 8197), 0)])
+                                          ((3, 8197), 0), ((7, 127), 4), ((23, 513), 16), ((41, 2048), 0), ((44, 1024), 11)]
+                         + [(sh, 0) for sh in ROW_SHAPES])
 def test_softmax(G, shape, period, dense):
     a, _, _ = _inputs(shape, 70 + shape[1])
     a = np.clip(a, -50, 50)
@@ -137,6 +141,42 @@ def test_batchnorm(G, shape, dense):
         _hook(rr, tau)
     again = G.gpu_layer(6, a, gamma=gamma, beta=beta, eps=1e-5, tau=tau, variant=1, dense=dense)
     assert np.array_equal(again["y64"], r["y64"])                                # deterministic
+
+
+@pytest.mark.parametrize("dense", [False, True])
+@pytest.mark.parametrize("op,shape,kw", [(GELU_TANH, (37, 1280), {}), (NORM, (43, 1000), dict(eps=1e-5)), (NORM, (9, 2049), dict(eps=1e-5)),
+                                         (SOFTMAX, (43, 1000), dict(scale=0.125, causal_period=7)),
+                                         (SOFTMAX, (3, 8197), dict(scale=0.125)), (6, (1300, 513), dict(eps=1e-5))])
+def test_without_the_fp64_debug_copy(G, op, shape, kw, dense):
+    """The call as the benchmarks make it (no FP64 copy of the layer's output) writes the same FP32 values and the
+    same log, bit for bit, as the call with the copy, whose FP64 values the tests above hold to the oracle."""
+    a, _, g = _inputs(shape, 400 + shape[1])
+    a = np.clip(a, -50, 50)
+    tau = 2.0 ** -5
+    for b_r in (32, 26):
+        full = G.gpu_layer(op, a, tau=tau, dense=dense, b_r=b_r, **kw)
+        bare = G.gpu_layer(op, a, tau=tau, dense=dense, b_r=b_r, want_y64=False, **kw)
+        _hook(full, tau, b_r)
+        assert bare["count"] == full["count"] and np.array_equal(_bits(bare["y32"]), _bits(full["y32"]))
+        for key in ("tlog", "idx", "dir"):
+            if key in full:
+                assert np.array_equal(bare[key], full[key]), key
+
+
+@pytest.mark.parametrize("op,kw", [(NORM, dict(eps=1e-5)), (SOFTMAX, dict(scale=0.25))])
+def test_rowwise_index_list_capacity(G, op, kw):
+    """A log smaller than the number of entries keeps the first `cap` entries in output order and still
+    counts them all (rows held in registers: the entries of a tile leave through the scanner protocol)."""
+    a, _, _ = _inputs((83, 1000), 500)
+    tau = 0.25
+    full = G.gpu_layer(op, a, tau=tau, **kw)
+    assert full["count"] > 1000
+    for cap in (0, 1, 255, 256, 257, full["count"] // 2, full["count"] - 1, full["count"]):
+        part = G.gpu_layer(op, a, tau=tau, cap=cap, **kw)
+        stored = min(cap, full["count"])
+        assert part["count"] == full["count"] and np.array_equal(_bits(part["y32"]), _bits(full["y32"]))
+        assert np.array_equal(part["idx"], full["idx"][:stored])
+        assert np.array_equal(_dir_bits(part["dir"], stored), _dir_bits(full["dir"], stored))
 
 
 def test_two_summation_orders_and_replay(G):
