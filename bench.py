@@ -689,6 +689,89 @@ def leg_gpt2(b: Bench, si):
     return out
 
 
+def leg_gpt2_block(b: Bench, si):
+    """One whole GPT-2 117M block forward at batch 8 x 1024 tokens, every intermediate rounded and logged (tau = 1/4 ulp,
+    packed log): the five GEMMs of config 3 plus what stands between them -- layer norms, causal softmax, the
+    probabilities-times-values product per head, GELU, residual additions.  Every op has seeded operands of its own on
+    the FP32 grid (a real block would feed each op the FP32 output of the one before)."""
+    vt, torch = b.vt, b.torch
+    dev = b.dev
+    T, D, H, DH, B = 1024, 768, 12, 64, 8
+    R = B * T
+    tau = 0.25
+    f32grid = lambda a: a.astype(np.float32).astype(np.float64)
+    seed = lambda i: si.seed_for(3, 900 + i)
+    x = b.up(f32grid(si.normal((R, D), seed(0))))
+    x2 = b.up(f32grid(si.normal((R, D), seed(1))))
+    h4 = b.up(f32grid(si.normal((R, 4 * D), seed(2))))
+    qkv = b.up(f32grid(si.normal((R, 3 * D), seed(3)))).view(-1)
+    logits = b.up(f32grid(si.normal(B * H * T * T, seed(4), 2.0)))                      # pre-softmax scores, already scaled
+    probs = b.up(f32grid(np.abs(si.normal(B * H * T * T, seed(5))) * (2.0 / T)))     # rows of about unit mass
+    gamma = b.up(f32grid(1.0 + 0.1 * si.normal(D, seed(6))))
+    beta = b.up(f32grid(0.1 * si.normal(D, seed(7))))
+    shapes = {"qkv": (D, 3 * D), "attn_out": (D, D), "mlp_up": (D, 4 * D), "mlp_down": (4 * D, D)}
+    wts = {nm: b.up(si.normal(sh, seed(8 + i), 0.02)) for i, (nm, sh) in enumerate(shapes.items())}
+    bias = {nm: torch.zeros(sh[1], dtype=torch.float64, device=dev) for nm, sh in shapes.items()}
+    big = B * H * T * T
+    y32 = torch.empty(big, dtype=torch.float32, device=dev)
+    dlog = vt.alloc_dense_log(big)
+    ws = vt.alloc_workspace(max(vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG, R, 4 * D, D, 1),
+                                vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG, R, D, 4 * D, 1),
+                                vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG, T, T, DH, B * H),
+                                vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG, T, DH, T, B * H),
+                                vt.vt_workspace_bytes(vt.VT_OP_LAYER_ROUND_LOG, B * H * T, T),
+                                vt.vt_workspace_bytes(vt.VT_OP_LAYER_ROUND_LOG, R, 4 * D)))
+
+    def linear(nm, a):
+        w = wts[nm]
+        k, n = w.shape
+        return (nm, 2.0 * R * n * k, 8.0 * (R * k + k * n) + 4.2 * R * n,
+                lambda: vt.vt_gemm_f64_round_log(False, False, R, n, k, 1.0, a, k, 0, w, n, 0, bias[nm], 1, y32, n, 0, None, 0,
+                                                 tau, dlog, ws))
+
+    def layer(nm, op, a, rows, cols, reads=1, second=None, **kw):
+        g, be = (gamma, beta) if op == vt.VT_LAYER_NORM else (None, None)
+        return (nm, 0.0, rows * cols * (8.0 * reads + 4.2),
+                lambda: vt.vt_layer_f64_round_log(op, a, second, g, be, rows, cols, y32, None, 0, tau, dlog, ws, **kw))
+
+    ops = [
+        layer("layer_norm_1", vt.VT_LAYER_NORM, x, R, D, eps=1e-5),
+        linear("qkv", x),
+        ("scores", 2.0 * B * H * T * T * DH, 8.0 * 2 * R * D + 4.2 * B * H * T * T,
+         lambda: vt.vt_gemm_f64_round_log_nested(False, True, T, T, DH, 0.125, qkv, 3 * D, DH, T * 3 * D, qkv[D:], 3 * D, DH,
+                                                 T * 3 * D, None, H, B, y32, T, T * T, None, 0, tau, dlog, ws)),
+        layer("softmax_causal", vt.VT_LAYER_SOFTMAX, logits, B * H * T, T, scale=1.0, causal_period=T),
+        ("probs_times_values", 2.0 * B * H * T * T * DH, 8.0 * (B * H * T * T + R * D) + 4.2 * R * D,
+         lambda: vt.vt_gemm_f64_round_log_nested(False, False, T, DH, T, 1.0, probs, T, T * T, H * T * T, qkv[2 * D:], 3 * D, DH,
+                                                 T * 3 * D, None, H, B, y32, DH, T * DH, None, 0, tau, dlog, ws)),
+        linear("attn_out", x),
+        layer("residual_add_1", vt.VT_LAYER_ADD, x, R, D, reads=2, second=x2),
+        layer("layer_norm_2", vt.VT_LAYER_NORM, x2, R, D, eps=1e-5),
+        linear("mlp_up", x),
+        layer("gelu_tanh", vt.VT_LAYER_GELU_TANH, h4, R, 4 * D),
+        linear("mlp_down", h4),
+        layer("residual_add_2", vt.VT_LAYER_ADD, x2, R, D, reads=2, second=x),
+    ]
+    res, per_call = run_stream(b, [(nm, fl, fn) for nm, fl, _, fn in ops])
+    res.pop("by_kind")
+    rows = []
+    for (nm, fl, nbytes, _), ms in zip(ops, per_call):
+        row = {"op": nm, "ms": r4(ms)}
+        if fl:
+            row["TFLOPs"] = round(fl / ms / 1e9, 2)
+            row["frac_mfma_peak"] = r4(fl / ms / 1e9 / FP64_MFMA_PEAK_TFLOPS)
+        row["GBs_algorithmic"] = round(nbytes / ms / 1e6, 1)
+        rows.append(row)
+    res["per_op"] = rows
+    res["gemm_ms"] = round(sum(ms for (_, fl, _, _), ms in zip(ops, per_call) if fl), 3)
+    res["other_ms"] = round(sum(ms for (_, fl, _, _), ms in zip(ops, per_call) if not fl), 3)
+    res["workload"] = ("one GPT-2 117M block forward, batch 8 x 1024 tokens, 12 hooked ops: layer norm, QKV, scores (96 x 1024 x 1024 x 64), "
+                       "causal softmax over 98304 rows of 1024, probabilities x values (96 x 1024 x 64 x 1024), attention output, residual "
+                       "add, layer norm, MLP up, GELU, MLP down, residual add; tau = 1/4 ulp, packed log; operand seeds "
+                       "0x240309603000 + 16*3 + 900 + i")
+    return {"gpt2_117m_block_forward": res}
+
+
 def leg_resnet(b: Bench, si):
     """Config 4: the 53 convolutions of ResNet-50 at batch 64, forward, weight gradient and input gradient, tau = 1/4 ulp,
     packed log; per distinct layer shape the roof min(MFMA peak, arithmetic intensity x HBM peak)."""
@@ -829,6 +912,8 @@ def main():
         torch.cuda.empty_cache()
     if not args.no_workloads:
         out["workloads"] = {**leg_gpt2(b, si)}
+        torch.cuda.empty_cache()
+        out["workloads"].update(leg_gpt2_block(b, si))
         torch.cuda.empty_cache()
         out["workloads"].update(leg_resnet(b, si))
     if pool is not None:
