@@ -45,11 +45,13 @@ def test_captured_stream_of_calls_replays_bit_identically():
     f32 = lambda n: torch.empty(n, dtype=torch.float32, device=dev)
     o = {"gemm": f32(M * N), "wgrad": f32(Mw * Nw), "rl": f32(x.numel()), "rld": f32(x.numel()), "rp": f32(x.numel()),
          "rpd": f32(x.numel()), "conv": f32(Mc * Nc), "dgrad": f32(Md * Nd), "softmax": f32(rows * cols),
+         "lnorm": f32(rows * cols), "bnorm": f32(rows * cols),
          "stats": torch.empty(68, dtype=torch.int64, device=dev), "digest": torch.empty(32, dtype=torch.uint8, device=dev),
          "root": torch.empty(32, dtype=torch.uint8, device=dev)}
     logs = {"gemm": vt.alloc_log(M * N), "wgrad": vt.alloc_dense_log(Mw * Nw), "rl": vt.alloc_log(x.numel()),
             "rld": vt.alloc_dense_log(x.numel()), "conv": vt.alloc_dense_log(Mc * Nc), "dgrad": vt.alloc_log(Md * Nd),
-            "softmax": vt.alloc_dense_log(rows * cols)}
+            "softmax": vt.alloc_dense_log(rows * cols), "lnorm": vt.alloc_log(rows * cols),
+            "bnorm": vt.alloc_dense_log(rows * cols)}
     wsb = max(vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG, M, N, K, 1), vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG, Mw, Nw, Kw, 1),
               vt.vt_workspace_bytes(vt.VT_OP_ROUND_LOG, 1, x.numel()), vt.vt_workspace_bytes(vt.VT_OP_GEMM_ROUND_LOG, Mc, Nc, Kc, 1),
               vt.vt_workspace_bytes(vt.VT_OP_CONV_DGRAD_ROUND_LOG, Md, Nd, Kd, 1),
@@ -72,6 +74,10 @@ def test_captured_stream_of_calls_replays_bit_identically():
         vt.vt_conv2d_f64_round_log(vt.VT_CONV_DATA_GRAD, geo, Cout, dY, Wt.view(-1), None, o["dgrad"], None, 0, tau, logs["dgrad"], ws)
         vt.vt_layer_f64_round_log(vt.VT_LAYER_SOFTMAX, La, None, None, None, rows, cols, o["softmax"], None, 0, tau, logs["softmax"], ws,
                                   scale=0.125, causal_period=cols)
+        # (rows held in registers, index-list log: a scanner workgroup inside the captured launch; column statistics)
+        vt.vt_layer_f64_round_log(vt.VT_LAYER_NORM, La, None, None, None, rows, cols, o["lnorm"], None, 1, tau, logs["lnorm"], ws, eps=1e-5)
+        vt.vt_layer_f64_round_log(vt.VT_LAYER_BATCHNORM_RELU, La, None, None, None, rows, cols, o["bnorm"], None, 0, tau, logs["bnorm"], ws,
+                                  eps=1e-5)
         vt.vt_sha256_tree(x, 1024, o["digest"], ws)
         vt.vt_merkle_root(leaves, o["root"], ws)
 
