@@ -353,6 +353,7 @@ struct ConvGeom {
     uint32_t rows, taps;             // N Ho Wo and KH KW C
     double inv_HoWo, inv_Wo, inv_KWC, inv_C, inv_sh, inv_sw;
     uint32_t mKWC, mC, msh, msw;     // multipliers of divmod_magic for KWC, C and the strides
+    uint32_t mHoWo, mWo;             // and for HoWo and Wo (rows split in scalar registers)
     int32_t uni;                     // the 16 taps of a k step share (kh, kw): C is a multiple of 16
     int32_t Ho, nimg;                // output rows per image, images
     int32_t st_n, st_ho, st_wo;      // kRowStep = st_n HoWo + st_ho Wo + st_wo: one k step of the weight gradient
@@ -392,11 +393,18 @@ struct RowPos { int32_t base, h0, w0, rem; };   // element offset of X[n, h0, w0
 struct TapPos { int32_t off, hh, ww, rem; };    // (hh W + ww) C + ci with hh = kh dil_h, ww = kw dil_w
 // (rem: stride remainders, used by the input-gradient view below only)
 
+// INT: integer-only index split (for a wave-uniform m: the whole row is computed in scalar registers)
+template <bool INT = false>
 static __host__ __device__ __forceinline__ RowPos conv_row(const ConvGeom &c, uint32_t m)
 {
     uint32_t n, rem, ho, wo;
-    divmod_u32(m, (uint32_t)c.HoWo, c.inv_HoWo, n, rem);
-    divmod_u32(rem, (uint32_t)c.Wo, c.inv_Wo, ho, wo);
+    if (INT) {
+        divmod_magic(m, (uint32_t)c.HoWo, c.mHoWo, n, rem);
+        divmod_magic(rem, (uint32_t)c.Wo, c.mWo, ho, wo);
+    } else {
+        divmod_u32(m, (uint32_t)c.HoWo, c.inv_HoWo, n, rem);
+        divmod_u32(rem, (uint32_t)c.Wo, c.inv_Wo, ho, wo);
+    }
     RowPos r;
     r.h0 = (int32_t)ho * c.sh - c.ph;
     r.w0 = (int32_t)wo * c.sw - c.pw;
@@ -540,6 +548,7 @@ static inline ConvGeom conv_geom(int64_t N, int64_t H, int64_t W, int64_t C, int
     c.inv_sh = 1.0 / (double)c.sh; c.inv_sw = 1.0 / (double)c.sw;
     c.mKWC = magic_of((uint32_t)c.KWC); c.mC = magic_of((uint32_t)c.C);
     c.msh = magic_of((uint32_t)c.sh); c.msw = magic_of((uint32_t)c.sw);
+    c.mHoWo = magic_of((uint32_t)c.HoWo); c.mWo = magic_of((uint32_t)c.Wo);
     c.uni = vec && c.C > 0 && c.C % 16 == 0 ? 1 : 0;
     return c;
 }
@@ -562,6 +571,7 @@ static inline ConvGeom dgrad_geom(int64_t N, int64_t H, int64_t W, int64_t Cout,
     c.inv_sh = 1.0 / (double)c.sh; c.inv_sw = 1.0 / (double)c.sw;
     c.mKWC = magic_of((uint32_t)c.KWC); c.mC = magic_of((uint32_t)c.C);
     c.msh = magic_of((uint32_t)c.sh); c.msw = magic_of((uint32_t)c.sw);
+    c.mHoWo = magic_of((uint32_t)c.HoWo); c.mWo = magic_of((uint32_t)c.Wo);
     c.uni = vec && c.C > 0 && c.C % 16 == 0 ? 1 : 0;
     return c;
 }

@@ -69,7 +69,7 @@ constexpr TileShape kShapes[kNumShapes] = {{2, 4, 128, 128, 0.928, 2, 6.0}, {4, 
 constexpr TileShape kShapesT[kNumShapes] = {{2, 4, 128, 128, 0.72, 2, 9.7}, {4, 1, 64, 64, 0.809, 4, 5.3}};
 // ... and for the transposed implicit-im2col view of a convolution's weight gradient, whose gather
 // costs the small tile more than the large one
-constexpr TileShape kShapesG[kNumShapes] = {{2, 4, 128, 128, 0.772, 2, 9.7}, {4, 1, 64, 64, 0.641, 4, 4.9}};
+constexpr TileShape kShapesG[kNumShapes] = {{2, 4, 128, 128, 0.82, 2, 9.7}, {4, 1, 64, 64, 0.641, 4, 4.9}};
 
 }  // namespace
 
