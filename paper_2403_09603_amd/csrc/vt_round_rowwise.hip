@@ -8,12 +8,13 @@
 // ternary log (five outputs per byte) whatever the row length, so a wave's part of either log format
 // is its own.  Lane l holds the column pairs (2 l, 2 l + 1), (128 + 2 l, ...), ... of the current row
 // (up to 128 U columns, 16-byte loads and 8-byte stores; the next row is already on its way when
-// U <= 8).  The sums run over a lane's columns upwards (variant 0) or downwards (variant 1) and across the lanes by the butterfly of vt_rowstats.h: the summation order,
-// and with it every bit, is that of the stand-alone statistics kernel followed by the element-wise
-// pass.  Packed log: codes go to LDS by output position and every lane packs four bytes (twenty
-// outputs) at a time.  Index-list log: the entries are compacted per wave in LDS by ballots (lane by
-// lane and pair by pair a group of 128 columns is in output order), a workgroup of four waves is one tile of the scanner
-// protocol (vt_scan.h).
+// U <= 8).  The sums run over a lane's columns upwards (variant 0) or downwards (variant 1) and
+// across the lanes by the butterfly of vt_rowstats.h: the summation order, and with it every bit, is
+// that of the stand-alone statistics kernel followed by the element-wise pass.  Packed log: codes go
+// to LDS by output position and every lane packs four bytes (twenty outputs) at a time.  Index-list
+// log: the entries are compacted per wave in LDS by ballots (lane by lane and pair by pair a group of
+// 128 columns is in output order), and a workgroup of four waves is one tile of the scanner protocol
+// (vt_scan.h).
 #include "vt_device.h"
 #include "vt_kernels.h"
 #include "vt_rowstats.h"
