@@ -623,7 +623,7 @@ int vt_layer_f64_round_log(const vt_layer *L, float *y, double *y64_debug, int v
     g.inv_period = g.period ? 1.0 / (double)g.period : 0.0;
     g.eps = L->eps;
     g.variant = variant;
-    const bool rowwise = n && vt::rowwise_usable(L->op, (uint64_t)L->cols, log->dense != nullptr) &&
+    const bool rowwise = n && vt::rowwise_usable(L->op, (uint64_t)L->cols) &&
                          vt::rowwise_bytes((uint64_t)L->rows) <= rl;
     hipError_t e = rowwise ? hipSuccess : vt::launch_layer_stats(g, (uint64_t)L->rows, s);
     if (e != hipSuccess) return VT_ERR_HIP;

@@ -7,8 +7,7 @@
 // A wavefront owns five consecutive rows: five rows are a whole number of bytes of the packed
 // ternary log (five outputs per byte) whatever the row length, so a wave's part of either log format
 // is its own.  Lane l holds the column pairs (2 l, 2 l + 1), (128 + 2 l, ...), ... of the current row
-// (up to 128 U columns, 16-byte loads and 8-byte stores; the next row is already on its way when
-// U <= 8).  The sums run over a lane's columns upwards (variant 0) or downwards (variant 1) and
+// (up to 128 U columns, 16-byte loads and 8-byte stores; the next row is already on its way).  The sums run over a lane's columns upwards (variant 0) or downwards (variant 1) and
 // across the lanes by the butterfly of vt_rowstats.h: the summation order, and with it every bit, is
 // that of the stand-alone statistics kernel followed by the element-wise pass.  Packed log: codes go
 // to LDS by output position and every lane packs four bytes (twenty outputs) at a time.  Index-list
@@ -133,7 +132,7 @@ __global__ __launch_bounds__(256) void rowwise_kernel(const LayerArgs g, uint32_
                                                       uint64_t *__restrict__ count)
 {
     constexpr uint32_t kWaveOut = kRwRows * 128u * U;       // most outputs of one wave
-    constexpr bool PREFETCH = U <= 8;
+    constexpr bool PREFETCH = true;
     static_assert(kWaveOut <= 0x8000u, "an entry holds a 15-bit position");
     __shared__ __attribute__((aligned(16))) uint8_t smem[kRwWaves * kWaveOut * (DENSE ? 1 : 2)];
     __shared__ uint32_t s_wc[8];                            // entries per wave (scanner: its 8 words of scratch)
@@ -263,16 +262,29 @@ __global__ __launch_bounds__(256) void rowwise_kernel(const LayerArgs g, uint32_
 
     if (lane == 0) s_wc[wv] = wcount;
     __syncthreads();
-    if (wv != 0) return;                                    // one wave waits for the tile's place in the log
     uint32_t pre[kRwWaves + 1];
     pre[0] = 0;
 #pragma unroll
     for (int w = 0; w < kRwWaves; ++w) pre[w + 1] = pre[w] + s_wc[w];
     const uint32_t c = pre[kRwWaves];
-    uint64_t off;
-    if (!tile_offset(st, tile, c, err, lane, off) || c == 0) return;
+    if (c == 0) {                                           // nothing to place: publish the count and go
+        if (tid == 0) st_store(st + tile, kCountFlag);
+        return;
+    }
+    // One wave trades the count for the tile's place in the log; all four then write entries (a tile
+    // of twenty rows can hold thousands, and the workgroup's LDS is held until the last one has left
+    // anyway, so the other waves lose nothing by waiting here).
+    __shared__ uint64_t s_off;
+    __shared__ uint32_t s_ok;
+    if (wv == 0) {
+        uint64_t off;
+        const bool ok = tile_offset(st, tile, c, err, lane, off);
+        if (lane == 0) { s_off = off; s_ok = ok ? 1u : 0u; }
+    }
+    __syncthreads();
+    if (!s_ok) return;
     emit_tile_entries<kRwWaves>((const uint16_t *)smem, kWaveOut, 0x7FFFu, pre, (uint64_t)tile * kRwWaves * kRwRows * cols,
-                                kRwRows * cols, off, cap, idx, dir, lane);
+                                kRwRows * cols, s_off, cap, idx, dir, lane, wv, kRwWaves);
 }
 
 template <int OP, int U, bool DENSE>
@@ -295,16 +307,14 @@ hipError_t launch_op(const LayerArgs &g, uint32_t rows, uint32_t thr, uint32_t k
 {
     if (g.cols <= 512) return launch_u<OP, 4, DENSE>(g, rows, thr, k, y, tlog, slots, st, tiles, err, log, s);
     if (g.cols <= 1024) return launch_u<OP, 8, DENSE>(g, rows, thr, k, y, tlog, slots, st, tiles, err, log, s);
-    if constexpr (DENSE) return launch_u<OP, 16, true>(g, rows, thr, k, y, tlog, slots, st, tiles, err, log, s);
     return hipErrorInvalidValue;
 }
 
 }  // namespace
 
-bool rowwise_usable(int op, uint64_t cols, bool dense)
+bool rowwise_usable(int op, uint64_t cols)
 {
-    return (op == kLayerNorm || op == kLayerSoftmax) && cols >= kRowwiseMinCols &&
-           cols <= (dense ? kRowwiseMaxColsDense : kRowwiseMaxColsSparse);
+    return (op == kLayerNorm || op == kLayerSoftmax) && cols >= kRowwiseMinCols && cols <= kRowwiseMaxCols;
 }
 
 size_t rowwise_bytes(uint64_t rows)

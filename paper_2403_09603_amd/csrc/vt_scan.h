@@ -149,17 +149,19 @@ __device__ __forceinline__ bool tile_offset(uint64_t *__restrict__ st, uint32_t 
 // direction (bit 15).  The entries go to log positions off .. off + pre[WAVES] - 1 (those below `cap`),
 // 256 at a time, aligned in log position: four consecutive entries per lane (one 16-byte index store
 // where the log is aligned), their direction bits gathered over eight lanes into whole 32-bit words
-// (the words were cleared beforehand, so partial ones are OR-ed).
+// (the words were cleared beforehand, so partial ones are OR-ed).  Several waves may share the work:
+// the calling wave takes every `parts`-th group of 256 from group `part` on.
 template <int WAVES>
 __device__ __forceinline__ void emit_tile_entries(const uint16_t *__restrict__ ent, uint32_t pitch, uint32_t pos_mask,
                                                   const uint32_t (&pre)[WAVES + 1], uint64_t first, uint32_t chunk_elems,
                                                   uint64_t off, uint64_t cap, uint32_t *__restrict__ idx,
-                                                  uint32_t *__restrict__ dir, uint32_t lane)
+                                                  uint32_t *__restrict__ dir, uint32_t lane, uint32_t part = 0,
+                                                  uint32_t parts = 1)
 {
     const uint32_t c = pre[WAVES];
     const uint64_t end = off + c < cap ? off + c : cap;
     const bool wide = ((uintptr_t)idx & 15u) == 0;
-    for (uint64_t G = off & ~255ull; G < end; G += 256) {
+    for (uint64_t G = (off & ~255ull) + 256ull * part; G < end; G += 256ull * parts) {
         const uint64_t p0 = G + 4u * lane;
         uint32_t iv[4] = {0, 0, 0, 0}, nib_v = 0, nib_d = 0;
 #pragma unroll
