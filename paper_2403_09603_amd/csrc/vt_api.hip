@@ -273,6 +273,11 @@ int conv_dgrad_entry(const vt::ConvDesc &c, int64_t Cout, const double *dY, cons
         pa.ph = (uint32_t)c.pad_h; pa.pw = (uint32_t)c.pad_w; pa.sh = (uint32_t)c.stride_h; pa.sw = (uint32_t)c.stride_w;
         pa.y64 = C64_debug;
         uint64_t slab_off = 0, w_off = 0;
+        // the phases' GEMMs (different depths, each too small to fill the part) go out as one launch
+        vt::GemmArgs group[4];
+        vt::ConvDesc subs[4];
+        double *outs[4];
+        int count = 0;
         mark_begin(s);
         for (int64_t a = 0; a < c.stride_h; ++a)
             for (int64_t b = 0; b < c.stride_w; ++b) {
@@ -288,15 +293,23 @@ int conv_dgrad_entry(const vt::ConvDesc &c, int64_t Cout, const double *dY, cons
                 if (vt::launch_dgrad_weights(Wt, c.KW, c.C, Cout, ax.k0, ax.kstep, ax.taps, bx.k0, bx.kstep, bx.taps,
                                              Wp + w_off, s) != hipSuccess)
                     return VT_ERR_HIP;
-                const vt::ConvDesc sub{c.N, ax.count, bx.count, c.C, ax.taps, bx.taps, 1, 1, ax.pad, bx.pad, ax.dil, bx.dil, c.Ho, c.Wo};
-                vt::GemmArgs q = g;
-                q.conv = &sub; q.conv_dgrad_cout = Cout;
+                subs[count] = vt::ConvDesc{c.N, ax.count, bx.count, c.C, ax.taps, bx.taps, 1, 1, ax.pad, bx.pad, ax.dil, bx.dil, c.Ho, c.Wo};
+                vt::GemmArgs &q = group[count];
+                q = g;
+                q.conv = &subs[count]; q.conv_dgrad_cout = Cout;
                 q.M = rows; q.K = taps * Cout; q.lda = 0; q.B = Wp + w_off; q.transB = 0; q.ldb = N; q.raw = true;
-                const vt::GemmPlan plan = vt::plan_gemm(q.M, q.N, q.K, 1, /*allow_split=*/false, vt::kALayoutRowMajor);
-                if (vt::launch_gemm_round_planes(q, plan, vt::Planes{}, slabs + slab_off, nullptr, s) != hipSuccess) return VT_ERR_HIP;
+                outs[count] = slabs + slab_off;
+                ++count;
                 slab_off += (uint64_t)rows * (uint64_t)N;
                 w_off += (uint64_t)taps * (uint64_t)Cout * (uint64_t)N;
             }
+        if (count) {
+            // one tile shape for all: the one the plan takes for the phases together
+            int64_t rows_all = 0, k_most = 0;
+            for (int i = 0; i < count; ++i) { rows_all += group[i].M; k_most = group[i].K > k_most ? group[i].K : k_most; }
+            const vt::GemmPlan plan = vt::plan_gemm(rows_all, N, k_most, 1, /*allow_split=*/false, vt::kALayoutRowMajor);
+            if (vt::launch_gemm_group(group, outs, count, plan.shape, s) != hipSuccess) return VT_ERR_HIP;
+        }
         mark_end(s);
         const uint32_t k = k_of(log->b_r);
         if (log->dense)

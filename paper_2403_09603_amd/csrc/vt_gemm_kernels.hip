@@ -151,11 +151,13 @@ hipError_t launch_dgrad_weights(const double *Wt, int64_t KW, int64_t C, int64_t
     return hipGetLastError();
 }
 
-hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, const Planes &pl, double *partial,
-                                    double *reduced, hipStream_t s)
+namespace {
+
+// Kernel parameters of one problem (am, kcb: the kernel's operand modes).  total_blocks = 0: nothing to launch.
+hipError_t build_params(const GemmArgs &g, const GemmPlan &plan, const Planes &pl, double *partial, GemmParams &p, int &am,
+                        bool &kcb)
 {
     const TileShape &t = kShapes[plan.shape];
-    GemmParams p;
     p.A = g.A; p.B = g.B; p.bias = g.bias; p.C32 = g.C32; p.C64 = g.C64; p.partial = partial;
     p.pl_logged = pl.logged; p.pl_dir = pl.dir;
     p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc;
@@ -168,7 +170,6 @@ hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, con
     p.tilesN = (uint32_t)((g.N + t.bn - 1) / t.bn);
     const uint64_t per_split = (uint64_t)p.tilesM * p.tilesN * (uint64_t)g.batch;
     const uint64_t total = per_split * (uint64_t)plan.splits;
-    if (total == 0) return hipSuccess;
     if (total > 0x7FFFFFFFull) return hipErrorInvalidValue;
     p.tiles_per_split = (uint32_t)per_split;
     p.total_blocks = (uint32_t)total;
@@ -179,8 +180,8 @@ hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, con
     p.zero_a = g.zero_a; p.zero_a_words = g.zero_a_words; p.zero_b = g.zero_b; p.zero_b_words = g.zero_b_words;
     p.vecA = ((uintptr_t)g.A % 16 == 0) && (g.lda % 2 == 0) && (g.strideA % 2 == 0) && (g.strideA2 % 2 == 0);
     p.vecB = ((uintptr_t)g.B % 16 == 0) && (g.ldb % 2 == 0) && (g.strideB % 2 == 0) && (g.strideB2 % 2 == 0);
-    const bool kcb = g.transB != 0;
-    int am = g.transA ? 0 : 1;
+    kcb = g.transB != 0;
+    am = g.transA ? 0 : 1;
     p.conv = ConvGeom{};
     if (g.conv) {
         // A is the image; the matrix the kernel multiplies is its im2col view (transposed for the
@@ -196,7 +197,19 @@ hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, con
         }
         p.vecA = p.conv.vec;
     }
-    hipError_t e;
+    return hipSuccess;
+}
+
+}  // namespace
+
+hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, const Planes &pl, double *partial,
+                                    double *reduced, hipStream_t s)
+{
+    GemmParams p;
+    int am;
+    bool kcb;
+    hipError_t e = build_params(g, plan, pl, partial, p, am, kcb);
+    if (e != hipSuccess || p.total_blocks == 0) return e;
     switch (plan.shape) {
     case 0: e = launch_gemm_128x128(p, am, kcb, s); break;
     default: e = launch_gemm_64x64(p, am, kcb, s); break;
@@ -206,6 +219,34 @@ hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, con
     splitk_reduce_kernel<<<(uint32_t)((slab + 255) / 256), 256, 0, s>>>(partial, slab, plan.splits, g.variant, g.alpha,
                                                                       g.bias, (uint32_t)g.N, reduced, g.C64);
     return hipGetLastError();
+}
+
+// Up to kGroupMax problems (raw accumulators to partial[i], no planes) of one tile shape in one launch.
+hipError_t launch_gemm_group(const GemmArgs *g, double *const *partial, int count, int shape, hipStream_t s)
+{
+    if (count < 1 || count > kGroupMax) return hipErrorInvalidValue;
+    GemmGroup gp{};
+    GemmPlan plan{shape, 1, 0};
+    int am0 = -1;
+    bool kcb0 = false;
+    uint32_t at = 0;
+    for (int i = 0; i < kGroupMax; ++i) {
+        gp.first[i] = at;
+        if (i >= count) { gp.p[i] = gp.p[0]; continue; }
+        plan.kt_per_split = (int)((g[i].K + BK - 1) / BK);
+        if (plan.kt_per_split < 1) plan.kt_per_split = 1;
+        int am;
+        bool kcb;
+        const hipError_t e = build_params(g[i], plan, Planes{}, partial[i], gp.p[i], am, kcb);
+        if (e != hipSuccess) return e;
+        if (i == 0) { am0 = am; kcb0 = kcb; }
+        else if (am != am0 || kcb != kcb0) return hipErrorInvalidValue;
+        if ((uint64_t)at + gp.p[i].total_blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+        at += gp.p[i].total_blocks;
+    }
+    gp.first[kGroupMax] = at;
+    if (at == 0) return hipSuccess;
+    return shape == 0 ? launch_gemm_grouped_128x128(gp, am0, kcb0, s) : launch_gemm_grouped_64x64(gp, am0, kcb0, s);
 }
 
 }  // namespace vt

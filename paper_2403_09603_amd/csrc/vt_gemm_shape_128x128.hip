@@ -8,4 +8,9 @@ hipError_t launch_gemm_128x128(const GemmParams &p, int am, bool kcb, hipStream_
     return launch_shape<2, 4>(p, am, kcb, s);
 }
 
+hipError_t launch_gemm_grouped_128x128(const GemmGroup &gp, int am, bool kcb, hipStream_t s)
+{
+    return launch_shape_grouped<2, 4>(gp, am, kcb, s);
+}
+
 }  // namespace vt

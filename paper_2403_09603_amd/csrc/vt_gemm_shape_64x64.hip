@@ -8,4 +8,9 @@ hipError_t launch_gemm_64x64(const GemmParams &p, int am, bool kcb, hipStream_t 
     return launch_shape<4, 1>(p, am, kcb, s);
 }
 
+hipError_t launch_gemm_grouped_64x64(const GemmGroup &gp, int am, bool kcb, hipStream_t s)
+{
+    return launch_shape_grouped<4, 1>(gp, am, kcb, s);
+}
+
 }  // namespace vt

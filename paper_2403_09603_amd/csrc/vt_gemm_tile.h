@@ -58,6 +58,14 @@ struct GemmParams {
     uint32_t zero_a_words, zero_b_words;
 };
 
+constexpr int kGroupMax = 4;
+struct GemmGroup {
+    GemmParams p[kGroupMax];
+    uint32_t first[kGroupMax + 1];
+};
+hipError_t launch_gemm_grouped_128x128(const GemmGroup &gp, int am, bool kcb, hipStream_t s);
+hipError_t launch_gemm_grouped_64x64(const GemmGroup &gp, int am, bool kcb, hipStream_t s);
+
 namespace {
 
 typedef double d4 __attribute__((ext_vector_type(4)));
@@ -373,8 +381,9 @@ __device__ __forceinline__ void tile_epilogue(const GemmParams &p, const d4 (&ac
 // k), 2 = implicit im2col of an image, rows x taps (convolution forward), 3 = its transpose,
 // taps x rows (convolution weight gradient), 4 = the input-gradient view of the output gradient,
 // input positions x (filter position, output channel).  KCB: B is stored transposed (contiguous along k).
+// `bid` of `nblk`: the workgroup's number among those of this problem (the launch may hold several problems)
 template <int AM, bool KCB, int WM, int TM>
-__global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmParams p)
+__device__ __forceinline__ void gemm_tile_body(const GemmParams &p, const uint32_t bid, const uint32_t nblk)
 {
     constexpr bool KCA = AM == 1 || AM == 2 || AM == 4;
     constexpr bool GA = AM >= 2;
@@ -391,13 +400,13 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
 
     // what the single-launch log compaction after this kernel needs zeroed: its status words and the
     // direction words of the log (a few words per workgroup)
-    for (uint32_t i = blockIdx.x * 256u + t; i < p.zero_a_words; i += gridDim.x * 256u) p.zero_a[i] = 0u;
-    for (uint32_t i = blockIdx.x * 256u + t; i < p.zero_b_words; i += gridDim.x * 256u) p.zero_b[i] = 0u;
+    for (uint32_t i = bid * 256u + t; i < p.zero_a_words; i += nblk * 256u) p.zero_a[i] = 0u;
+    for (uint32_t i = bid * 256u + t; i < p.zero_b_words; i += nblk * 256u) p.zero_b[i] = 0u;
 
     uint32_t split, b;
     int64_t bm, bn;
     const double *A, *B;
-    tile_of<BM, BN>(p, blockIdx.x, split, b, bm, bn, A, B);
+    tile_of<BM, BN>(p, bid, split, b, bm, bn, A, B);
 
     d4 acc[TM][4];
 #pragma unroll
@@ -614,6 +623,34 @@ __global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmPar
     }
 
     tile_epilogue<TM, BM, BN>(p, acc, b, bm, bn, row0, col0, lane);
+}
+
+template <int AM, bool KCB, int WM, int TM>
+__global__ __launch_bounds__(256, 2) void gemm_round_planes_kernel(const GemmParams p)
+{
+    gemm_tile_body<AM, KCB, WM, TM>(p, blockIdx.x, gridDim.x);
+}
+
+// Several problems of one tile shape and operand mode in one launch: workgroups first[g] .. first[g + 1] - 1
+// belong to problem g (an empty problem has first[g] = first[g + 1]).  The stride phases of an input
+// gradient are four small GEMMs of different depth; apart, each leaves most of the part idle.
+template <int AM, bool KCB, int WM, int TM>
+__global__ __launch_bounds__(256, 2) void gemm_grouped_kernel(const GemmGroup gp)
+{
+    uint32_t g = 0;
+#pragma unroll
+    for (int i = 1; i < kGroupMax; ++i)
+        if (blockIdx.x >= gp.first[i]) g = i;
+    gemm_tile_body<AM, KCB, WM, TM>(gp.p[g], blockIdx.x - gp.first[g], gp.first[g + 1] - gp.first[g]);
+}
+
+template <int WM, int TM>
+hipError_t launch_shape_grouped(const GemmGroup &gp, int am, bool kcb, hipStream_t s)
+{
+    const dim3 grid(gp.first[kGroupMax]), block(256);
+    if (am == 4 && !kcb) gemm_grouped_kernel<4, false, WM, TM><<<grid, block, 0, s>>>(gp);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
 }
 
 template <int WM, int TM>

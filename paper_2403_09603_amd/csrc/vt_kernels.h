@@ -197,6 +197,8 @@ size_t gemm_split_bytes(int64_t M, int64_t N, int64_t batch, int splits);
 // consumes them).
 hipError_t launch_gemm_round_planes(const GemmArgs &g, const GemmPlan &plan, const Planes &pl, double *partial,
                                     double *reduced, hipStream_t s);
+// up to four problems (raw accumulators to partial[i]; no split-K, no planes) of tile shape `shape` in one launch
+hipError_t launch_gemm_group(const GemmArgs *g, double *const *partial, int count, int shape, hipStream_t s);
 // Filter Wt[KH][KW][C][Cout] -> Wp[filter position][Cout][C]: the B operand (K x C, row-major) of the
 // input-gradient GEMM.  A copy, so exact.
 // Only the filter positions (kh0 + sth i, kw0 + stw j), i < nkh, j < nkw, are taken (a stride phase's
