@@ -411,6 +411,17 @@ int vt_gemm_plan(int transA, int64_t M, int64_t N, int64_t K, int64_t batch, int
                  int *tile_m, int *tile_n, int *splits);
 
 /*
+ * Introspection (host only): when the fused path (splits = 1) launches a number of tiles a little
+ * over a multiple of the 256 compute units, its last *tail_tiles tiles are each multiplied by *slices
+ * workgroups (4 slices of the K range, added in slice order -- ascending for variant 0,
+ * descending for variant 1 -- before the epilogue), so that the launch does not run a whole extra tile
+ * time for them.  *tail_tiles = 0, *slices = 1 when it does not.  Same arguments as vt_gemm_plan; like
+ * the plan, a function of the shape alone, so the accumulation order stays a function of the arguments.
+ */
+int vt_gemm_tail_plan(int transA, int64_t M, int64_t N, int64_t K, int64_t batch, int64_t ldc, int64_t strideC,
+                      int *tail_tiles, int *slices);
+
+/*
  * Optional instrumentation for benchmarks (no counterpart in the paper).  While two hipEvent_t
  * handles are registered, vt_gemm_f64_round_log, vt_round_log and vt_round_replay record
  * ev_begin immediately before and ev_end immediately after their MAIN kernel (the GEMM, the

@@ -105,6 +105,8 @@ def load_library():
     L.vt_thr_layer_from_stats.argtypes = [C.c_uint64, C.c_uint64]
     L.vt_gemm_plan.restype = cint
     L.vt_gemm_plan.argtypes = [cint, i64, i64, i64, i64, i64, i64, C.POINTER(cint), C.POINTER(cint), C.POINTER(cint)]
+    L.vt_gemm_tail_plan.restype = cint
+    L.vt_gemm_tail_plan.argtypes = [cint, i64, i64, i64, i64, i64, i64, C.POINTER(cint), C.POINTER(cint)]
     L.vt_set_kernel_events.restype = cint
     L.vt_set_kernel_events.argtypes = [vp, vp]
     L.vt_strerror.restype = C.c_char_p
@@ -390,6 +392,17 @@ def vt_gemm_plan(M: int, N: int, K: int, batch: int = 1, ldc: int | None = None,
                                        int(M * N if strideC is None else strideC), C.byref(tm), C.byref(tn),
                                        C.byref(sp)), "vt_gemm_plan")
     return tm.value, tn.value, sp.value
+
+
+def vt_gemm_tail_plan(M: int, N: int, K: int, batch: int = 1, ldc: int | None = None, strideC: int | None = None,
+                      transA=False):
+    """(tail_tiles, slices): see vt_gemm_tail_plan in include/vt.h."""
+    tiles, slices = C.c_int(0), C.c_int(0)
+    ldc = N if ldc is None else ldc
+    strideC = M * N if strideC is None else strideC
+    _check(load_library().vt_gemm_tail_plan(int(transA), M, N, K, batch, ldc, strideC, C.byref(tiles), C.byref(slices)),
+           "vt_gemm_tail_plan")
+    return tiles.value, slices.value
 
 
 def vt_set_kernel_events(ev_begin, ev_end):

@@ -189,6 +189,7 @@ int run_gemm(vt::GemmArgs &g, const vt_log *log, void *ws, size_t ws_bytes, hipS
                                                         vt::LogOut{log->idx, log->dir, log->cap, log->count}, s));
     }
     const bool cleared = prepare_compaction(g, pl, log, total);
+    g.tail_ws = (double *)((char *)ws + up256(planes));            // (the split-K slabs' place: free on this path)
     mark_begin(s);
     hipError_t e = vt::launch_gemm_round_planes(g, plan, pl, nullptr, nullptr, s);
     mark_end(s);
@@ -368,11 +369,15 @@ size_t vt_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int64_t batch
                round_log_bytes((uint64_t)M * (uint64_t)N * (uint64_t)batch);
     case VT_OP_GEMM_ROUND_LOG: {
         // sized for the split-K path too (taken for dense outputs when few tiles meet a long K)
-        size_t bytes = vt::planes_bytes((uint64_t)M * (uint64_t)batch, (uint64_t)N);
+        // ... and for the slices of tail tiles (the fused path)
+        size_t bytes = up256(vt::planes_bytes((uint64_t)M * (uint64_t)batch, (uint64_t)N));
         const int splits = max_splits(M, N, K, batch);
-        if (splits > 1)
-            bytes += vt::gemm_split_bytes(M, N, batch, splits) + round_log_bytes((uint64_t)M * (uint64_t)N * (uint64_t)batch);
-        return bytes;
+        size_t extra = vt::gemm_tail_bytes();
+        if (splits > 1) {
+            const size_t sk = vt::gemm_split_bytes(M, N, batch, splits) + round_log_bytes((uint64_t)M * (uint64_t)N * (uint64_t)batch);
+            extra = sk > extra ? sk : extra;
+        }
+        return bytes + extra;
     }
     case VT_OP_CONV_DGRAD_ROUND_LOG:
     case VT_OP_CONV_DGRAD_ROUND_LOG_BR: {
@@ -677,6 +682,24 @@ int vt_gemm_plan(int transA, int64_t M, int64_t N, int64_t K, int64_t batch, int
     *tile_m = bm[plan.shape];
     *tile_n = bn[plan.shape];
     *splits = plan.splits;
+    return VT_OK;
+}
+
+int vt_gemm_tail_plan(int transA, int64_t M, int64_t N, int64_t K, int64_t batch, int64_t ldc, int64_t strideC,
+                      int *tail_tiles, int *slices)
+{
+    int tm, tn, splits;
+    if (!tail_tiles || !slices) return VT_ERR_INVALID_ARG;
+    const int rc = vt_gemm_plan(transA, M, N, K, batch, ldc, strideC, &tm, &tn, &splits);
+    if (rc != VT_OK) return rc;
+    *tail_tiles = 0;
+    *slices = 1;
+    if (splits != 1 || M == 0 || N == 0 || batch == 0) return VT_OK;
+    const uint64_t tiles = (uint64_t)((M + tm - 1) / tm) * (uint64_t)((N + tn - 1) / tn) * (uint64_t)batch;
+    if (vt::gemm_tail_cut(tm == 128 ? 0 : 1, tiles, (K + 15) / 16)) {
+        *tail_tiles = (int)(tiles % 256u);
+        *slices = 4;
+    }
     return VT_OK;
 }
 

@@ -71,7 +71,24 @@ constexpr TileShape kShapesT[kNumShapes] = {{2, 4, 128, 128, 0.72, 2, 9.7}, {4, 
 // costs the small tile more than the large one
 constexpr TileShape kShapesG[kNumShapes] = {{2, 4, 128, 128, 0.82, 2, 9.7}, {4, 1, 64, 64, 0.641, 4, 4.9}};
 
+constexpr uint32_t kTailTilesMax = 64;
+
 }  // namespace
+
+// Tail tiles.  All tiles of a launch take equally long and the compute units take them in turn, so
+// a launch of 256 f + r tiles runs as long as one of 256 (f + 1).  When r <= 64, the last r tiles are
+// cut along k into four slices each -- at most 256 short workgroups, a quarter tile time -- and a
+// small kernel adds the slices in a fixed order and applies the epilogue.  (Larger r, where the
+// slices take two or three quarters, measured no gain.)  True when the tail is cut: when the time
+// saved (from measured per-step costs of the two tiles) clearly exceeds the small kernel's.  A pure
+// function of the shape, like the plan.
+bool gemm_tail_cut(int shape, uint64_t tiles, int64_t nkt)
+{
+    const uint64_t full = tiles / 256u, rem = tiles % 256u;
+    if (full < 1 || full > 16 || rem < 1 || rem > kTailTilesMax || nkt < 32) return false;
+    const double tile_us = shape == 0 ? ((double)nkt + 6.0) * 1.9 : ((double)nkt + 5.6) * 0.47;
+    return tile_us * 0.75 >= 20.0;
+}
 
 // Tile shape and split count for a problem, from a small cost model calibrated on the box (unit:
 // a quarter MFMA-pipe cycle per CU): rounds of 256 workgroups x work per workgroup / efficiency
@@ -93,9 +110,13 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_sp
         for (int sp : kSplits) {
             if (sp > 1 && (!allow_split || nkt / sp < 8)) break;        // keep >= 8 k steps per slice
             const double blocks = tiles * sp;
-            const double rounds = std::ceil(blocks / 256.0);
+            double rounds = std::ceil(blocks / 256.0);
             const double eff = t.eff * (rounds >= (double)t.conc ? 1.0 : 0.782);
+            // (the fused path shares its last few tiles among several workgroups: a fraction of a round, and a small kernel)
+            const bool tail = sp == 1 && gemm_tail_cut(sh, (uint64_t)tiles, nkt);
+            if (tail) rounds = std::floor(blocks / 256.0) + 0.25;
             double cost = rounds * (double)t.bm * t.bn * ((double)((nkt + sp - 1) / sp) + t.overhead) / eff;
+            if (tail) cost += 40000.0;
             if (sp > 1) cost += 173000.0 + 0.0171 * (double)M * N * batch * (sp + 2);
             if (cost < best_cost) { best_cost = cost; best = GemmPlan{sh, sp, 0}; }
         }
@@ -104,6 +125,8 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_sp
     if (best.kt_per_split < 1) best.kt_per_split = 1;
     return best;
 }
+
+size_t gemm_tail_bytes() { return (size_t)kTailTilesMax * 4 * 128 * 128 * 8; }   // tiles x slices x the larger tile, in doubles
 
 size_t gemm_split_bytes(int64_t M, int64_t N, int64_t batch, int splits)
 {
@@ -173,6 +196,19 @@ hipError_t build_params(const GemmArgs &g, const GemmPlan &plan, const Planes &p
     if (total > 0x7FFFFFFFull) return hipErrorInvalidValue;
     p.tiles_per_split = (uint32_t)per_split;
     p.total_blocks = (uint32_t)total;
+    p.tiles_total = (uint32_t)total;
+    p.tail_first = p.tiles_total; p.tail_shift = 0; p.tail_kt = 0; p.tail_partial = nullptr;
+    if (g.tail_ws && plan.splits == 1 && !g.raw) {      // tail tiles (gemm_tail_quarters)
+        const int64_t nkt = (g.K + BK - 1) / BK;
+        if (gemm_tail_cut(plan.shape, p.tiles_total, nkt)) {
+            const uint32_t rem = p.tiles_total % 256u, shift = 2;
+            p.tail_first = p.tiles_total - rem;
+            p.tail_shift = shift;
+            p.tail_kt = (uint32_t)((nkt + (1 << shift) - 1) >> shift);
+            p.tail_partial = g.tail_ws;
+            p.total_blocks = p.tail_first + (rem << shift);
+        }
+    }
     p.m_tiles_per_split = magic_of(p.tiles_per_split);
     p.m_per_batch = magic_of(p.tilesM * p.tilesN);
     p.m_width = magic_of(8u * p.tilesN);

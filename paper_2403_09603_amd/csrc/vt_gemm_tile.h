@@ -56,6 +56,13 @@ struct GemmParams {
     int variant, vecA, vecB, splits, kt_per_split, raw;
     uint32_t *zero_a, *zero_b;                  // words cleared by the kernel for the log compaction that follows
     uint32_t zero_a_words, zero_b_words;
+    // Tail tiles: the tiles from number tail_first on are multiplied by 2^tail_shift workgroups each, every one a
+    // slice of tail_kt k steps whose raw accumulators go to tail_partial (tile-sized slabs); gemm_tail_fixup_kernel
+    // adds the slices in a fixed order and runs the epilogue.  Workgroup tail_first + (j << tail_shift) + s of the
+    // launch is slice s of tail tile j.  tail_first = tiles_total: no tail.
+    uint32_t tiles_total;                       // tiles x split-K slices: what the tile mapping counts
+    uint32_t tail_first, tail_shift, tail_kt;
+    double *tail_partial;
 };
 
 constexpr int kGroupMax = 4;
@@ -210,7 +217,7 @@ __device__ __forceinline__ void tile_of(const GemmParams &p, uint32_t id, uint32
 {
     uint32_t pid;
     {
-        const uint32_t q = p.total_blocks / 8u, r = p.total_blocks % 8u, xcd = id % 8u;
+        const uint32_t q = p.tiles_total / 8u, r = p.tiles_total % 8u, xcd = id % 8u;
         pid = xcd * q + (xcd < r ? xcd : r) + id / 8u;
     }
     uint32_t pin, band, inband, b_out, b_in;
@@ -403,10 +410,18 @@ __device__ __forceinline__ void gemm_tile_body(const GemmParams &p, const uint32
     for (uint32_t i = bid * 256u + t; i < p.zero_a_words; i += nblk * 256u) p.zero_a[i] = 0u;
     for (uint32_t i = bid * 256u + t; i < p.zero_b_words; i += nblk * 256u) p.zero_b[i] = 0u;
 
+    // a tail tile is shared by several workgroups, each a slice of its k range (uniform over the workgroup)
+    const bool tail = bid >= p.tail_first;
+    uint32_t tile_id = bid, tail_slice = 0;
+    if (tail) {
+        const uint32_t j = bid - p.tail_first;
+        tile_id = p.tail_first + (j >> p.tail_shift);
+        tail_slice = j & ((1u << p.tail_shift) - 1u);
+    }
     uint32_t split, b;
     int64_t bm, bn;
     const double *A, *B;
-    tile_of<BM, BN>(p, bid, split, b, bm, bn, A, B);
+    tile_of<BM, BN>(p, tile_id, split, b, bm, bn, A, B);
 
     d4 acc[TM][4];
 #pragma unroll
@@ -416,8 +431,9 @@ __device__ __forceinline__ void gemm_tile_body(const GemmParams &p, const uint32
 
     // this workgroup's k tiles: [kt0, kt1)
     const int nkt_all = (int)((p.K + BK - 1) / BK);
-    const int kt0 = (int)split * p.kt_per_split;
-    const int kt1 = kt0 + p.kt_per_split < nkt_all ? kt0 + p.kt_per_split : nkt_all;
+    const int kt_len = tail ? (int)p.tail_kt : p.kt_per_split;
+    const int kt0 = (int)(tail ? tail_slice : split) * kt_len;
+    const int kt1 = kt0 + kt_len < nkt_all ? kt0 + kt_len : nkt_all;
     const int nkt = kt1 > kt0 ? kt1 - kt0 : 0;
     // whole-tile operands take the unguarded loader (a uniform choice per k step)
     // (the per-thread offsets of the unguarded loader are 32-bit: pitches up to 2^31 / 8 / 128)
@@ -605,6 +621,17 @@ __device__ __forceinline__ void gemm_tile_body(const GemmParams &p, const uint32
     const int g = lane >> 4, c16 = lane & 15;
     const int64_t row0 = bm + wm * (16 * TM), col0 = bn + wn * 64;
 
+    if (tail) {
+        // ---- a slice of a tail tile: raw accumulators to this workgroup's slab, rows and columns of the tile
+        double *P = p.tail_partial + (uint64_t)(bid - p.tail_first) * (uint64_t)(BM * BN) + (wm * (16 * TM) + g) * BN + wn * 64 + c16;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) P[(i * 16 + 4 * r) * BN + j * 16] = acc[i][j][r];
+        return;
+    }
     if (p.splits > 1 || p.raw) {
         // ---- split-K (or a caller that rounds in a later pass): raw accumulators to this slice's slab; alpha, bias, rounding come later
         double *P = p.partial + ((int64_t)split * p.batch + (int64_t)b) * p.M * p.N;
@@ -653,6 +680,37 @@ hipError_t launch_shape_grouped(const GemmGroup &gp, int am, bool kcb, hipStream
     return hipGetLastError();
 }
 
+// The tail tiles' slices added in ascending (variant 0) or descending slice order, then the fused epilogue: one
+// workgroup per tail tile, every wave the rows and columns it would own in the GEMM kernel.
+template <int WM, int TM>
+__global__ __launch_bounds__(256) void gemm_tail_fixup_kernel(const GemmParams p)
+{
+    constexpr int WN = 4 / WM;
+    constexpr int BM = WM * 16 * TM, BN = WN * 64;
+    const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
+    const int wm = wv / WN, wn = wv % WN, g = lane >> 4, c16 = lane & 15;
+    uint32_t split, b;
+    int64_t bm, bn;
+    const double *A, *B;
+    tile_of<BM, BN>(p, p.tail_first + blockIdx.x, split, b, bm, bn, A, B);
+    const uint32_t S = 1u << p.tail_shift;
+    d4 acc[TM][4];
+    for (uint32_t q = 0; q < S; ++q) {
+        const uint32_t sl = p.variant ? S - 1u - q : q;
+        const double *P = p.tail_partial + ((uint64_t)blockIdx.x * S + sl) * (uint64_t)(BM * BN) + (wm * (16 * TM) + g) * BN + wn * 64 + c16;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const double v = P[(i * 16 + 4 * r) * BN + j * 16];
+                    acc[i][j][r] = q == 0 ? v : acc[i][j][r] + v;
+                }
+    }
+    tile_epilogue<TM, BM, BN>(p, acc, b, bm, bn, bm + wm * (16 * TM), bn + wn * 64, lane);
+}
+
 template <int WM, int TM>
 hipError_t launch_shape(const GemmParams &p, int am, bool kcb, hipStream_t s)
 {
@@ -665,7 +723,12 @@ hipError_t launch_shape(const GemmParams &p, int am, bool kcb, hipStream_t s)
     else if (am == 0 && kcb) gemm_round_planes_kernel<0, true, WM, TM><<<grid, block, 0, s>>>(p);
     else if (am == 0 && !kcb) gemm_round_planes_kernel<0, false, WM, TM><<<grid, block, 0, s>>>(p);
     else return hipErrorInvalidValue;
-    return hipGetLastError();
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && p.tail_first < p.tiles_total) {
+        gemm_tail_fixup_kernel<WM, TM><<<p.tiles_total - p.tail_first, 256, 0, s>>>(p);
+        e = hipGetLastError();
+    }
+    return e;
 }
 
 }  // namespace

@@ -309,3 +309,37 @@ def test_split_k_sum_inside_the_pass_equals_the_separate_reduction():
     yo, io, do, co = vo.round_log(c64.ravel(), 2.0 ** -4)
     assert co == res[0][2] and np.array_equal(res[0][0].cpu().numpy().view(np.uint32), yo.view(np.uint32))
     assert np.array_equal(res[0][3].cpu().numpy().view(np.uint32), io)
+
+
+@pytest.mark.parametrize("M,N,K,tile,tail", [(2112, 512, 1024, 64, (8, 4)), (2100, 500, 1042, 64, (8, 4)),
+                                             (4700, 1000, 1024, 128, (40, 4))])
+def test_tail_tiles_shared_among_workgroups(G, M, N, K, tile, tail):
+    """A launch of a few tiles more than a multiple of 256: the last tiles are multiplied in slices of K by
+    several workgroups and finished by the fix-up kernel.  FP64 values of sampled rows (every row tile,
+    every column) against the oracle, every FP32 value and the whole log against the oracle's hook; both
+    accumulation orders; ragged edges.  (ldc > N keeps the plan off split-K.)"""
+    assert vtlib.vt_gemm_plan(M, N, K, 1, ldc=N + 8) == (tile, tile, 1)
+    assert vtlib.vt_gemm_tail_plan(M, N, K, 1, ldc=N + 8) == tail
+    g = si.rng(si.seed_for(1, 40) + M)
+    A = g.standard_normal((M, K))
+    B = g.standard_normal((K, N)) * 0.05
+    bias = g.standard_normal(N)
+    tau = 2.0 ** -6
+    rows = np.arange(0, M, 29)
+    truth = vo.gemm_f64(np.ascontiguousarray(A[rows]), B, alpha=0.5, bias=bias, order=2)
+    bound = 1e-12 * (0.5 * np.linalg.norm(A[rows], axis=1)[:, None] * np.linalg.norm(B, axis=0)[None, :] + np.abs(bias)[None, :])
+    res = {}
+    for variant in (0, 1):
+        r = G.gpu_gemm(A, B, alpha=0.5, bias=bias, tau=tau, variant=variant, ldc=N + 8)
+        assert np.all(np.abs(r["C64"][0][rows] - truth) <= bound), float(np.max(np.abs(r["C64"][0][rows] - truth) / bound))
+        yo, io, do, co = vo.round_log(r["C64"].ravel(), tau)
+        assert r["count"] == co and np.array_equal(_bits(r["C32"].ravel()), _bits(yo))
+        assert np.array_equal(r["idx"], io) and np.array_equal(_dir_bits(r["dir"], co), _dir_bits(do, co))
+        assert np.isnan(r["C32_full"][:, :, N:]).all()                          # the padding of the pitch is untouched
+        res[variant] = r["C64"]
+    assert (res[0] != res[1]).mean() > 0.05                                      # two orders, different low bits
+    again = G.gpu_gemm(A, B, alpha=0.5, bias=bias, tau=tau, variant=1, ldc=N + 8)
+    assert np.array_equal(again["C64"], res[1])                                   # deterministic
+    bare = G.gpu_gemm(A, B, alpha=0.5, bias=bias, tau=tau, variant=1, ldc=N + 8, want_c64=False)
+    assert bare["count"] == again["count"] and np.array_equal(_bits(bare["C32"]), _bits(again["C32"]))
+    assert np.array_equal(bare["idx"], again["idx"]) and np.array_equal(bare["dir"], again["dir"])
