@@ -70,6 +70,25 @@ inline int max_splits(int64_t M, int64_t N, int64_t K, int64_t batch)
     return most;
 }
 
+// scratch for the slices of tail tiles (gemm_tail_cut) under any plan this shape can get: the workspace query
+// knows neither the operand layout nor whether the output is dense
+inline size_t tail_bytes_for(int64_t M, int64_t N, int64_t K, int64_t batch)
+{
+    size_t most = 0;
+    if (M <= 0 || N <= 0 || K <= 0 || batch <= 0) return 0;
+    for (int layout : {vt::kALayoutRowMajor, vt::kALayoutTransposed, vt::kALayoutIm2colT})
+        for (bool allow : {false, true}) {
+            const vt::GemmPlan plan = vt::plan_gemm(M, N, K, batch, allow, layout);
+            if (plan.splits != 1) continue;
+            const int64_t t = plan.shape == 0 ? 128 : 64;
+            const uint64_t tiles = (uint64_t)((M + t - 1) / t) * (uint64_t)((N + t - 1) / t) * (uint64_t)batch;
+            if (!vt::gemm_tail_cut(plan.shape, tiles, (K + 15) / 16)) continue;
+            const size_t bytes = (size_t)(tiles % 256u) * 4u * (size_t)(t * t * 8);
+            most = bytes > most ? bytes : most;
+        }
+    return most;
+}
+
 inline bool split_allowed(int64_t M, int64_t N, int64_t batch, int64_t ldc, int64_t strideC)
 {
     return ldc == N && (batch <= 1 || strideC == M * N);    // the round/log pass sees one flat tensor
@@ -372,7 +391,7 @@ size_t vt_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int64_t batch
         // ... and for the slices of tail tiles (the fused path)
         size_t bytes = up256(vt::planes_bytes((uint64_t)M * (uint64_t)batch, (uint64_t)N));
         const int splits = max_splits(M, N, K, batch);
-        size_t extra = vt::gemm_tail_bytes();
+        size_t extra = tail_bytes_for(M, N, K, batch);
         if (splits > 1) {
             const size_t sk = vt::gemm_split_bytes(M, N, batch, splits) + round_log_bytes((uint64_t)M * (uint64_t)N * (uint64_t)batch);
             extra = sk > extra ? sk : extra;

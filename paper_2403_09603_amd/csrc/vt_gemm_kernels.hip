@@ -126,8 +126,6 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_sp
     return best;
 }
 
-size_t gemm_tail_bytes() { return (size_t)kTailTilesMax * 4 * 128 * 128 * 8; }   // tiles x slices x the larger tile, in doubles
-
 size_t gemm_split_bytes(int64_t M, int64_t N, int64_t batch, int splits)
 {
     if (splits < 1) return 0;

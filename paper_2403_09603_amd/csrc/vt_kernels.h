@@ -180,11 +180,11 @@ struct GemmArgs {
     // two arrays of 32-bit words the kernel clears on its way (what the log compaction that follows needs zeroed)
     uint32_t *zero_a = nullptr, *zero_b = nullptr;
     uint32_t zero_a_words = 0, zero_b_words = 0;
-    // gemm_tail_bytes() of scratch (256-byte aligned), or null: lets the launcher share the last few tiles of a
-    // launch whose tile count is a little over a multiple of the compute units among several workgroups
+    // scratch for the slices of tail tiles (tiles % 256 x 4 slices x tile area, in doubles; 256-byte aligned), or
+    // null: lets the launcher share the last few tiles of a launch whose tile count is a little over a multiple
+    // of the compute units among several workgroups (gemm_tail_cut)
     double *tail_ws = nullptr;
 };
-size_t gemm_tail_bytes();
 bool gemm_tail_cut(int shape, uint64_t tiles, int64_t nkt);   // the last tiles % 256 tiles are cut into four slices of K
 // Tile shape (index into the kernel's shape table) and split-K factor chosen for a problem.
 struct GemmPlan {

@@ -53,6 +53,19 @@ def test_workspace_bytes_monotone_and_aligned(hiplib):
     assert hiplib.vt_workspace_bytes(3, 1, 1 << 20, 0, 1) == 0
 
 
+def test_workspace_covers_the_slices_of_tail_tiles(hiplib):
+    """A launch whose last tiles are cut into slices needs tile-sized slabs for them beside the decision planes."""
+    import paper_2403_09603_amd as vt
+    for M, N, K in ((12544, 256, 2304), (2112, 512, 1024), (4700, 1000, 1024), (50176, 256, 512)):
+        tile = vt.vt_gemm_plan(M, N, K, 1, ldc=N + 8)[0]
+        tail_tiles, slices = vt.vt_gemm_tail_plan(M, N, K, 1, ldc=N + 8)
+        assert tail_tiles > 0 and slices == 4
+        assert hiplib.vt_workspace_bytes(2, M, N, K, 1) >= M * N // 4 + tail_tiles * slices * tile * tile * 8
+    assert vt.vt_gemm_tail_plan(8192, 3072, 768, 1) == (0, 1)              # 1536 tiles: six whole rounds
+    assert vt.vt_gemm_tail_plan(128, 128, 64, 1) == (0, 1)
+    assert hiplib.vt_workspace_bytes(2, 128, 128, 64, 1) < 1 << 20
+
+
 def test_argument_validation_happens_on_the_host(hiplib):
     """None of these calls may reach a kernel launch: they run here without a GPU."""
     import paper_2403_09603_amd.binding as b
