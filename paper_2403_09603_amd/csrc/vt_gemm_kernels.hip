@@ -80,14 +80,16 @@ constexpr uint32_t kTailTilesMax = 64;
 // cut along k into four slices each -- at most 256 short workgroups, a quarter tile time -- and a
 // small kernel adds the slices in a fixed order and applies the epilogue.  (Larger r, where the
 // slices take two or three quarters, measured no gain.)  True when the tail is cut: when the time
-// saved (from measured per-step costs of the two tiles) clearly exceeds the small kernel's.  A pure
-// function of the shape, like the plan.
+// saved (from measured per-step costs of the two tiles) exceeds the small kernel's 6 us twice over --
+// thresholds of 20 / 12 / 7 us gave 9.85 / 9.64 / 9.73 ms on the ResNet-50 forward stream; slices
+// shorter than eight k steps (K < 512) are mostly prologue and lost.  A pure function of the shape,
+// like the plan.
 bool gemm_tail_cut(int shape, uint64_t tiles, int64_t nkt)
 {
     const uint64_t full = tiles / 256u, rem = tiles % 256u;
     if (full < 1 || full > 16 || rem < 1 || rem > kTailTilesMax || nkt < 32) return false;
     const double tile_us = shape == 0 ? ((double)nkt + 6.0) * 1.9 : ((double)nkt + 5.6) * 0.47;
-    return tile_us * 0.75 >= 20.0;
+    return tile_us * 0.75 >= 12.0;
 }
 
 // Tile shape and split count for a problem, from a small cost model calibrated on the box (unit:
